@@ -1,0 +1,74 @@
+/*
+ * Seeded synthetic input generator (weights, activations, token ids).
+ *
+ * Holds none of the decoder's arithmetic: it only draws random numbers and
+ * stores them.  Both the CPU oracle's tests and the GPU path's tests/bench take
+ * their inputs from here, so the two sides see identical bytes.
+ *
+ * Counter based and order free: element i of tensor t under seed s is a pure
+ * function of (s, t, i), so threads may fill any range in any order.
+ *
+ *   key    = s XOR (t * 2^40 + i)
+ *   h      = splitmix64 finaliser of key        (Steele/Lea/Flood mixing constants)
+ *   u1, u2 = ((high 32 bits of h) + 0.5) / 2^32, ((low 32 bits of h) + 0.5) / 2^32
+ *   normal = sqrt(-2 ln u1) * cos(2 pi u2)      (Box-Muller, fp64)
+ *
+ * The workload these stand in for is the Qwen3 checkpoints and prompts of the
+ * paper's evaluation (Section 5, experimental setup), which are not available
+ * here; shapes follow the public Qwen3 sizes.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+static inline uint64_t mix64(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+static inline uint64_t draw(uint64_t seed, uint64_t tensor, uint64_t i) {
+  return mix64(seed ^ ((tensor << 40) + i));
+}
+
+static inline double std_normal(uint64_t h) {
+  const double u1 = ((double)(uint32_t)(h >> 32) + 0.5) * (1.0 / 4294967296.0);
+  const double u2 = ((double)(uint32_t)(h & 0xffffffffu) + 0.5) * (1.0 / 4294967296.0);
+  return sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925286766559 * u2);
+}
+
+/* fp32 -> bf16 storage format, round to nearest, ties to even. Inputs here are
+ * finite normals, so no NaN handling is needed. */
+static inline uint16_t store_bf16(float f) {
+  uint32_t b;
+  memcpy(&b, &f, 4);
+  b += 0x7fffu + ((b >> 16) & 1u);
+  return (uint16_t)(b >> 16);
+}
+
+void synth_normal_f32(uint64_t seed, uint64_t tensor, uint64_t first, uint64_t n,
+                      double scale, float *out) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < (int64_t)n; ++i)
+    out[i] = (float)(scale * std_normal(draw(seed, tensor, first + (uint64_t)i)));
+}
+
+void synth_normal_bf16(uint64_t seed, uint64_t tensor, uint64_t first, uint64_t n,
+                       double scale, uint16_t *out) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < (int64_t)n; ++i)
+    out[i] = store_bf16((float)(scale * std_normal(draw(seed, tensor, first + (uint64_t)i))));
+}
+
+/* Uniform integers in [0, bound): floor(u * bound) with u the high 32 bits / 2^32. */
+void synth_uniform_i32(uint64_t seed, uint64_t tensor, uint64_t first, uint64_t n,
+                       uint32_t bound, int32_t *out) {
+  for (uint64_t i = 0; i < n; ++i) {
+    const uint64_t hi = draw(seed, tensor, first + i) >> 32;
+    out[i] = (int32_t)((hi * (uint64_t)bound) >> 32);
+  }
+}
+
+uint64_t synth_raw(uint64_t seed, uint64_t tensor, uint64_t i) { return draw(seed, tensor, i); }
