@@ -1,0 +1,190 @@
+/*
+ * nnc.h - C ABI of the MI355X (gfx950) Qwen3-style decoder forward pass.
+ *
+ * The workload is the one the nncase paper compiles and times: the decode stage
+ * (and the prompt pass before it) of Qwen3-0.6B / 1.7B at batch 1, tokens/s over
+ * the decoding stage (Section 5, experimental setup; Sections 5.1 and 5.2), with
+ * weights laid out once, ahead of time, in the layout the matmul micro-kernel
+ * wants (Section 3.1.2 "Auto Vectorize": packed / blocked layouts; Section 3.3.1:
+ * constants are pre-split and pinned; Section 3.3.2: MatMul micro-kernels over
+ * packed operands).  Here the packed layout is the CDNA4 matrix-core fragment
+ * order and the micro-kernels are hand-written HIP.
+ *
+ * Conventions for every entry point
+ *   - returns nnc_status; never throws, never aborts; on error the out-params and
+ *     the model state are left untouched and nnc_last_error() describes the cause;
+ *   - "host" pointers are ordinary CPU memory read during the call only;
+ *     "device" pointers are GPU memory owned by the caller, read or written by
+ *     work enqueued on the model's stream; calls do not synchronise the stream;
+ *   - a model is bound to the GPU that was current at nnc_model_create and to one
+ *     stream; calls on one model must not overlap (not thread-safe);
+ *   - positions are implicit: each KV slot remembers its length, nnc_prefill and
+ *     nnc_decode_step append at that length.
+ *
+ * Canonical weight blob (host memory, little endian, tensors contiguous,
+ * matrices row-major [out, in] in blob_dtype, gains always fp32), in order:
+ *   embed [V,H]                                   if has_embed_and_head
+ *   per layer: g_in [H], Wq [Dq,H], Wk [Dkv,H], Wv [Dkv,H], g_q [d], g_k [d],
+ *              Wo [H,Dq], g_post [H], Wgate [F,H], Wup [F,H], Wdown [H,F]
+ *   g_final [H]                                   if has_embed_and_head
+ *   lm_head [V,H]                                 if has_embed_and_head && !tied_lm_head
+ * with Dq = n_q_heads*head_dim, Dkv = n_kv_heads*head_dim.
+ */
+#ifndef NNC_H_
+#define NNC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct nnc_model nnc_model; /* opaque; owned by the library */
+
+typedef enum {
+  NNC_OK = 0,
+  NNC_E_ARG = 1,     /* null pointer, slot/batch/token out of range, duplicate slots */
+  NNC_E_CONFIG = 2,  /* unsupported or inconsistent nnc_config */
+  NNC_E_BLOB = 3,    /* blob_bytes does not match the config */
+  NNC_E_NOMEM = 4,   /* device allocation failed */
+  NNC_E_KV_FULL = 5, /* a slot would exceed max_seq */
+  NNC_E_DEVICE = 6,  /* HIP error, or no gfx950 device */
+  NNC_E_STATE = 7    /* call not valid for this model (e.g. token API on a hidden-state model) */
+} nnc_status;
+
+typedef enum { NNC_F32 = 0, NNC_BF16 = 1 } nnc_dtype;
+
+typedef struct {
+  uint32_t struct_bytes; /* = sizeof(nnc_config) */
+  uint32_t hidden, n_layers, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  float rms_eps, rope_theta;
+  uint32_t has_embed_and_head; /* 0: hidden state in, hidden state out (one-layer fp32 config) */
+  uint32_t tied_lm_head;       /* 1: LM head is the embedding matrix, blob holds no lm_head */
+  uint32_t blob_dtype;         /* nnc_dtype of the matrices in the blob */
+  uint32_t compute_dtype;      /* NNC_F32: fp32 weights, fp32 KV cache, fp32 matrix-core math;
+                                  NNC_BF16: bf16 weights and KV cache, fp32 accumulation.
+                                  Must equal blob_dtype, or be NNC_BF16 with an NNC_F32 blob
+                                  (weights are then rounded to nearest even once, at create). */
+  uint32_t max_batch;          /* number of KV slots */
+  uint32_t max_seq;            /* positions per slot */
+} nnc_config;
+
+/* Device memory and stream come from the caller (e.g. PyTorch's allocator and
+ * current stream).  alloc returns device memory aligned to >= 256 bytes or NULL;
+ * both callbacks are invoked only inside nnc_model_create / nnc_model_destroy.
+ * A NULL nnc_device, or NULL alloc/free, selects hipMalloc/hipFree and the
+ * default stream. */
+typedef struct {
+  void *(*alloc)(size_t bytes, void *ctx);
+  void (*free)(void *p, void *ctx);
+  void *ctx;
+  void *stream; /* hipStream_t; NULL = default stream */
+} nnc_device;
+
+/*
+ * Build a model: validate the config, check blob_bytes, allocate weights / KV
+ * cache / workspace, upload and repack every matrix once into the matrix-core
+ * tile layout (the on-GPU counterpart of the paper's packed constant layouts,
+ * Sections 3.1.2 and 3.3.1): Wq|Wk|Wv fused row-wise, Wgate/Wup interleaved in
+ * 16-row tiles, bf16 rounding if requested.  blob is host memory borrowed for
+ * the duration of the call.  Synchronises the stream before returning.
+ */
+nnc_status nnc_model_create(const nnc_config *cfg, const void *blob, size_t blob_bytes,
+                            const nnc_device *dev, nnc_model **out);
+
+/* Release everything obtained through nnc_device.alloc.  NULL is allowed.
+ * Synchronises the stream first. */
+void nnc_model_destroy(nnc_model *m);
+
+/*
+ * Prompt pass (the paper's pre-decode stage, Section 5 setup): run n tokens
+ * (host int32, each in [0, vocab)) through the model for one KV slot, appending
+ * K/V at positions len..len+n-1.  logits_out: device, vocab floats, logits of the
+ * LAST position; may be NULL.  next_out: device int32, greedy arg-max of those
+ * logits (lowest index wins ties); may be NULL.  Chunked prefill = repeated calls.
+ * NNC_E_KV_FULL if len + n > max_seq.
+ */
+nnc_status nnc_prefill(nnc_model *m, uint32_t slot, const int32_t *tokens, uint32_t n,
+                       float *logits_out, int32_t *next_out);
+
+/*
+ * One decode step (the stage the paper's tokens/s metric covers): one token for
+ * each of `batch` distinct slots (host arrays slots[batch], tokens[batch]).
+ * logits_out: device [batch, vocab] floats or NULL.  next_out: device [batch]
+ * int32 greedy tokens or NULL.
+ */
+nnc_status nnc_decode_step(nnc_model *m, const uint32_t *slots, const int32_t *tokens,
+                           uint32_t batch, float *logits_out, int32_t *next_out);
+
+/*
+ * Greedy decode loop with the token fed back on the device: n_steps decode steps
+ * for `batch` distinct slots starting from first_tokens (host), no host
+ * synchronisation between steps.  tokens_out: device [n_steps, batch] int32, the
+ * token produced by each step.  logits_out: device [n_steps, batch, vocab] floats
+ * or NULL.  NNC_E_KV_FULL if any slot would exceed max_seq during the run.
+ */
+nnc_status nnc_decode_greedy(nnc_model *m, const uint32_t *slots, const int32_t *first_tokens,
+                             uint32_t batch, uint32_t n_steps, int32_t *tokens_out,
+                             float *logits_out);
+
+/* Forget the contents of one slot (slot >= 0) or of all slots (slot = -1). */
+nnc_status nnc_kv_reset(nnc_model *m, int32_t slot);
+
+/* Current length of a slot (host out-param). */
+nnc_status nnc_slot_len(const nnc_model *m, uint32_t slot, uint32_t *len_out);
+
+/*
+ * Hidden-state variants for models created with has_embed_and_head = 0.
+ * x: device [n, hidden] floats in; y: device [n, hidden] floats out (the residual
+ * stream after the last layer).  nnc_prefill_hidden treats the n rows as
+ * consecutive positions of one slot; nnc_decode_step_hidden treats row i as the
+ * next position of slots[i].
+ */
+nnc_status nnc_prefill_hidden(nnc_model *m, uint32_t slot, const float *x, uint32_t n, float *y);
+nnc_status nnc_decode_step_hidden(nnc_model *m, const uint32_t *slots, const float *x,
+                                  uint32_t batch, float *y);
+
+/*
+ * Copy cached rows out for inspection: positions pos0..pos0+n-1 of one layer and
+ * slot, widened to fp32, as [n, Dkv] (kv head major inside a row) into device
+ * memory `out`.  which: 0 = K (after QK-norm and RoPE), 1 = V.
+ */
+nnc_status nnc_kv_read(nnc_model *m, uint32_t layer, uint32_t slot, uint32_t which, uint32_t pos0,
+                       uint32_t n, float *out);
+
+/* Runtime switches. */
+typedef enum {
+  NNC_OPT_GRAPH = 0,        /* 1 (default): replay decode steps as captured HIP graphs; 0: eager */
+  NNC_OPT_PREFILL_EXACT = 1 /* 1: prompt GEMMs keep fp32-grade activations (split-bf16
+                               operands); 0 (default for bf16 models): activations entering a
+                               prompt GEMM are rounded to bf16 once, as matrix-core operands */
+} nnc_option;
+nnc_status nnc_set_option(nnc_model *m, nnc_option opt, int32_t value);
+
+/*
+ * Per-kernel timing with HIP events on the model's stream.  After
+ * nnc_profile_begin, every launch of the forward pass runs eagerly and is
+ * bracketed by events; nnc_profile_end synchronises, stops profiling and fills up
+ * to `cap` records (host), returning the number written in *n_out.
+ */
+typedef struct {
+  char name[48];        /* kernel family, e.g. "gemm_skinny" */
+  uint64_t launches;
+  double total_ms;      /* sum of event-to-event times */
+  double bytes;         /* algorithmic bytes those launches had to move */
+  double flops;         /* algorithmic flops (2 per multiply-add) */
+} nnc_kernel_stat;
+nnc_status nnc_profile_begin(nnc_model *m);
+nnc_status nnc_profile_end(nnc_model *m, nnc_kernel_stat *out, uint32_t cap, uint32_t *n_out);
+
+/* Bytes of the canonical blob for a config (0 if the config is invalid). */
+uint64_t nnc_blob_bytes(const nnc_config *cfg);
+
+/* Message for the most recent failure on this thread (static storage). */
+const char *nnc_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NNC_H_ */

@@ -1,0 +1,791 @@
+// Host side of the C ABI declared in include/nnc.h: validation, one-time weight
+// upload + repack, the fixed per-layer kernel sequence of one forward pass, graph
+// capture of decode steps, per-kernel event timing.
+//
+// One "pass" pushes up to MAX_COLS activation columns through every layer.  A
+// decode step is a pass whose columns are different KV slots; a prompt chunk is a
+// pass whose columns are consecutive positions of one slot (the attention kernel
+// takes each column's own position from device memory, so causal masking needs no
+// special case).  The paper's run loop is the same: prompt first, then one token
+// at a time, timed over the decoding stage (Section 5, experimental setup).
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <string>
+#include <tuple>
+#include <vector>
+
+#include "../../include/nnc.h"
+#include "nnc_internal.h"
+
+using namespace nnc;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+nnc_status fail(nnc_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+struct LayerW {
+  float *g_in = nullptr, *g_q = nullptr, *g_k = nullptr, *g_post = nullptr;
+  void *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wd = nullptr;
+  void *kc = nullptr, *vc = nullptr;
+};
+
+struct ProfRec {
+  int fam;
+  double bytes, flops;
+  hipEvent_t e0, e1;
+};
+
+enum Family { FAM_GEMM = 0, FAM_NORM, FAM_QKROPE, FAM_ATTN, FAM_COMBINE, FAM_EMBED, FAM_ARGMAX, FAM_MISC, FAM_COUNT };
+const char* const kFamName[FAM_COUNT] = {"gemm_skinny", "rmsnorm_pack", "qknorm_rope_append", "attn_partial",
+                                         "attn_combine", "embed", "argmax", "misc"};
+
+}  // namespace
+
+struct nnc_model {
+  nnc_config c{};
+  bool f32 = false;
+  int device = 0;
+  hipStream_t stream = nullptr;
+  nnc_device hooks{};
+  bool use_hooks = false;
+  std::vector<void*> allocs;
+
+  void* embed = nullptr;
+  void* lm_head = nullptr;
+  float* g_final = nullptr;
+  std::vector<LayerW> L;
+  float2* rope = nullptr;
+
+  ColState* st = nullptr;
+  float* x = nullptr;        // [MAX_COLS][H] residual stream
+  float* qkv = nullptr;      // [MAX_COLS][Dq + 2 Dkv]
+  void* Xp = nullptr;        // packed operand, K = H
+  void* Ap = nullptr;        // packed operand, K = max(Dq, F)
+  float* partial = nullptr;  // attention partials
+  int max_chunks = 0;
+  float* logits = nullptr;   // [32][V] when the caller passes no logits buffer
+  float* am_val = nullptr;
+  int32_t* am_idx = nullptr;
+  int32_t* next = nullptr;   // [MAX_COLS]
+  int32_t* token_log = nullptr;
+  uint32_t token_log_steps = 0;
+
+  std::vector<uint32_t> len;
+
+  bool opt_graph = true;
+  bool opt_prefill_exact = false;
+  std::map<std::tuple<int, int, int>, hipGraphExec_t> graphs;
+
+  bool profiling = false;
+  std::vector<ProfRec> prof;
+
+  uint32_t H() const { return c.hidden; }
+  uint32_t Dq() const { return c.n_q_heads * c.head_dim; }
+  uint32_t Dkv() const { return c.n_kv_heads * c.head_dim; }
+  uint32_t F() const { return c.ffn; }
+  uint32_t V() const { return c.vocab; }
+  size_t esz() const { return f32 ? 4 : 2; }
+  int ktile() const { return f32 ? 16 : 32; }
+};
+
+namespace {
+
+constexpr uint32_t MAX_DECODE_BATCH = 32;
+
+nnc_status check_config(const nnc_config* c) {
+  if (!c) return fail(NNC_E_ARG, "config is NULL");
+  if (c->struct_bytes != sizeof(nnc_config))
+    return fail(NNC_E_CONFIG, "struct_bytes %u != sizeof(nnc_config) %zu", c->struct_bytes, sizeof(nnc_config));
+  if (!c->hidden || !c->n_q_heads || !c->n_kv_heads || !c->ffn || !c->max_batch || !c->max_seq)
+    return fail(NNC_E_CONFIG, "zero dimension in config");
+  if (c->head_dim != 128) return fail(NNC_E_CONFIG, "head_dim %u unsupported (kernels are written for 128)", c->head_dim);
+  if (c->n_q_heads % c->n_kv_heads) return fail(NNC_E_CONFIG, "n_q_heads %% n_kv_heads != 0");
+  if (c->hidden % 32 || c->ffn % 32) return fail(NNC_E_CONFIG, "hidden and ffn must be multiples of 32");
+  if (c->has_embed_and_head && (c->vocab == 0 || c->vocab % 16))
+    return fail(NNC_E_CONFIG, "vocab must be a positive multiple of 16");
+  if (c->blob_dtype > NNC_BF16 || c->compute_dtype > NNC_BF16)
+    return fail(NNC_E_CONFIG, "unknown dtype");
+  if (c->compute_dtype == NNC_F32 && c->blob_dtype != NNC_F32)
+    return fail(NNC_E_CONFIG, "fp32 compute needs an fp32 blob");
+  if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return fail(NNC_E_CONFIG, "bad rms_eps / rope_theta");
+  if (c->max_batch > 4096 || c->max_seq > (1u << 20)) return fail(NNC_E_CONFIG, "max_batch / max_seq too large");
+  if (c->n_layers > 1024) return fail(NNC_E_CONFIG, "too many layers");
+  return NNC_OK;
+}
+
+uint64_t blob_bytes_of(const nnc_config* c) {
+  const uint64_t H = c->hidden, d = c->head_dim, Dq = (uint64_t)c->n_q_heads * d,
+                 Dkv = (uint64_t)c->n_kv_heads * d, F = c->ffn, V = c->vocab;
+  const uint64_t w = c->blob_dtype == NNC_F32 ? 4 : 2;
+  uint64_t total = (uint64_t)c->n_layers * (w * (Dq * H + 2 * Dkv * H + H * Dq + 3 * F * H) + 4 * (2 * H + 2 * d));
+  if (c->has_embed_and_head) {
+    total += w * V * H + 4 * H;
+    if (!c->tied_lm_head) total += w * V * H;
+  }
+  return total;
+}
+
+nnc_status dev_fail(hipError_t e, const char* what) {
+  return fail(e == hipErrorOutOfMemory ? NNC_E_NOMEM : NNC_E_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(call)                                      \
+  do {                                                     \
+    hipError_t e_ = (call);                                \
+    if (e_ != hipSuccess) return dev_fail(e_, #call);      \
+  } while (0)
+
+void* dev_alloc(nnc_model* m, size_t bytes) {
+  void* p = nullptr;
+  if (bytes == 0) bytes = 256;
+  if (m->use_hooks) {
+    p = m->hooks.alloc(bytes, m->hooks.ctx);
+  } else if (hipMalloc(&p, bytes) != hipSuccess) {
+    p = nullptr;
+  }
+  if (p) m->allocs.push_back(p);
+  return p;
+}
+
+void release_all(nnc_model* m) {
+  for (auto& kv : m->graphs) (void)hipGraphExecDestroy(kv.second);
+  m->graphs.clear();
+  for (auto& r : m->prof) {
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  m->prof.clear();
+  for (void* p : m->allocs) {
+    if (m->use_hooks)
+      m->hooks.free(p, m->hooks.ctx);
+    else
+      (void)hipFree(p);
+  }
+  m->allocs.clear();
+}
+
+// ---- launch bookkeeping ------------------------------------------------------
+
+struct Launch {
+  nnc_model* m;
+  int fam;
+  double bytes, flops;
+  Launch(nnc_model* m_, int fam_, double bytes_, double flops_) : m(m_), fam(fam_), bytes(bytes_), flops(flops_) {
+    if (m->profiling) {
+      ProfRec r{fam, bytes, flops, nullptr, nullptr};
+      if (hipEventCreate(&r.e0) == hipSuccess && hipEventCreate(&r.e1) == hipSuccess) {
+        (void)hipEventRecord(r.e0, m->stream);
+        m->prof.push_back(r);
+      }
+    }
+  }
+  ~Launch() {
+    if (m->profiling && !m->prof.empty()) (void)hipEventRecord(m->prof.back().e1, m->stream);
+  }
+};
+
+#define RUN(fam, bytes, flops, call)                     \
+  do {                                                   \
+    hipError_t e_;                                       \
+    {                                                    \
+      Launch l_(m, fam, (double)(bytes), (double)(flops)); \
+      e_ = (call);                                       \
+    }                                                    \
+    if (e_ != hipSuccess) return dev_fail(e_, #call);    \
+  } while (0)
+
+// k-slices for the accumulate-into-residual GEMMs: enough workgroups to cover the
+// chip, but at least 8 k tiles (2 per wave) per workgroup.
+int pick_kts(int n_tiles, int KT) {
+  int ksplit = 512 / (n_tiles > 0 ? n_tiles : 1);
+  if (ksplit < 1) ksplit = 1;
+  int max_split = KT / 8;
+  if (max_split < 1) max_split = 1;
+  if (ksplit > max_split) ksplit = max_split;
+  return (KT + ksplit - 1) / ksplit;
+}
+
+struct Pass {
+  int ncols = 0;          // sequences (columns) in the pass
+  int nsplit = 1;         // bf16 pieces per activation
+  bool tokens = true;     // embed from ColState.tok; otherwise x already holds the input rows
+  int head_col0 = 0;      // first column whose logits are wanted
+  int head_ncols = 0;     // number of such columns (0: skip final norm + LM head)
+  float* logits = nullptr;
+  long logits_ld = 0;
+  const uint32_t* step_ptr = nullptr;
+  long step_stride = 0;
+  int32_t* next = nullptr;  // arg-max output (device) or NULL
+  int grid_chunks = 1;
+  double kv_rows = 0;       // sum over columns of (position + 1): cached rows attention must read
+};
+
+nnc_status run_pass(nnc_model* m, const Pass& p) {
+  const nnc_config& c = m->c;
+  hipStream_t s = m->stream;
+  const bool f32 = m->f32;
+  const int H = m->H(), Dq = m->Dq(), Dkv = m->Dkv(), F = m->F(), V = m->V();
+  const int nq = c.n_q_heads, nkv = c.n_kv_heads;
+  const int n = p.ncols, ns = p.nsplit, nc = n * ns;
+  const double w = (double)m->esz();
+  const int KTH = H / m->ktile(), KTQ = Dq / m->ktile(), KTF = F / m->ktile();
+  const int Nqkv = Dq + 2 * Dkv;
+
+  if (p.tokens) RUN(FAM_EMBED, n * H * w, 0, launch_embed(s, f32, m->embed, H, m->st, n, m->x));
+
+  for (uint32_t li = 0; li < c.n_layers; ++li) {
+    const LayerW& L = m->L[li];
+    RUN(FAM_NORM, n * H * 8.0, 0,
+        launch_rmsnorm_pack(s, f32, m->x, H, L.g_in, H, c.rms_eps, n, m->Xp, nc, ns));
+    {
+      GemmArgs a{};
+      a.Wp = L.wqkv; a.n_tiles = Nqkv / 16; a.KT = KTH; a.kts_per_split = KTH;
+      a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
+      a.out = m->qkv; a.ldo = Nqkv;
+      RUN(FAM_GEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * n, launch_gemm(s, f32, EPI_STORE, a));
+    }
+    RUN(FAM_QKROPE, n * Nqkv * 4.0, 0,
+        launch_qknorm_rope_append(s, f32, m->qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, m->st, n,
+                                  L.kc, L.vc, c.max_batch, c.max_seq));
+    RUN(FAM_ATTN, p.kv_rows * 2.0 * Dkv * w, p.kv_rows * 4.0 * Dq,
+        launch_attn_partial(s, f32, m->qkv, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, m->st, n,
+                            p.grid_chunks, m->partial, m->max_chunks));
+    RUN(FAM_COMBINE, 0, 0,
+        launch_attn_combine(s, f32, m->partial, m->max_chunks, nq, m->st, n, m->Ap, nc, ns));
+    {
+      GemmArgs a{};
+      a.Wp = L.wo; a.n_tiles = H / 16; a.KT = KTQ; a.kts_per_split = pick_kts(a.n_tiles, KTQ);
+      a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
+      a.out = m->x; a.ldo = H;
+      RUN(FAM_GEMM, (double)H * Dq * w, 2.0 * H * Dq * n, launch_gemm(s, f32, EPI_RESID, a));
+    }
+    RUN(FAM_NORM, n * H * 8.0, 0,
+        launch_rmsnorm_pack(s, f32, m->x, H, L.g_post, H, c.rms_eps, n, m->Xp, nc, ns));
+    {
+      GemmArgs a{};
+      a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = KTH; a.kts_per_split = KTH;
+      a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
+      a.packed_out = m->Ap; a.NC_out = nc; a.nsplit_out = ns;
+      RUN(FAM_GEMM, 2.0 * F * H * w, 4.0 * F * H * n, launch_gemm(s, f32, EPI_SWIGLU, a));
+    }
+    {
+      GemmArgs a{};
+      a.Wp = L.wd; a.n_tiles = H / 16; a.KT = KTF; a.kts_per_split = pick_kts(a.n_tiles, KTF);
+      a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
+      a.out = m->x; a.ldo = H;
+      RUN(FAM_GEMM, (double)H * F * w, 2.0 * H * F * n, launch_gemm(s, f32, EPI_RESID, a));
+    }
+  }
+
+  if (c.has_embed_and_head && p.head_ncols > 0) {
+    const int hn = p.head_ncols, hc = hn * ns;
+    RUN(FAM_NORM, hn * H * 8.0, 0,
+        launch_rmsnorm_pack(s, f32, m->x + (size_t)p.head_col0 * H, H, m->g_final, H, c.rms_eps, hn, m->Xp,
+                            hc, ns));
+    GemmArgs a{};
+    a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = KTH; a.kts_per_split = KTH;
+    a.Xp = m->Xp; a.NC = hc; a.ncols = hc; a.nsplit = ns; a.nseq = hn;
+    a.out = p.logits; a.ldo = p.logits_ld; a.step_ptr = p.step_ptr; a.step_stride = p.step_stride;
+    RUN(FAM_GEMM, (double)V * H * w, 2.0 * V * H * hn, launch_gemm(s, f32, EPI_STORE, a));
+    if (p.next)
+      RUN(FAM_ARGMAX, hn * V * 4.0, 0,
+          launch_argmax(s, p.logits, p.logits_ld, V, hn, p.step_ptr, p.step_stride, m->am_val, m->am_idx,
+                        p.next));
+  }
+  return NNC_OK;
+}
+
+// bf16 pieces per activation for a decode batch: exact (3) while the pieces of all
+// sequences fit one 16-column block, otherwise 2 (relative error <= 2^-17).
+int decode_nsplit(const nnc_model* m, uint32_t batch) {
+  if (m->f32) return 1;
+  return batch <= 5 ? 3 : 2;
+}
+
+int chunks_grid(uint32_t max_pos) {
+  const int need = (int)(max_pos / ATT_CHUNK) + 1;
+  int g = 1;
+  while (g < need) g <<= 1;
+  return g;
+}
+
+nnc_status check_slots(const nnc_model* m, const uint32_t* slots, uint32_t batch, uint32_t n_steps) {
+  if (!m) return fail(NNC_E_ARG, "model is NULL");
+  if (!slots) return fail(NNC_E_ARG, "slots is NULL");
+  if (batch == 0 || batch > m->c.max_batch || batch > MAX_DECODE_BATCH)
+    return fail(NNC_E_ARG, "batch %u out of range (max_batch %u, limit %u)", batch, m->c.max_batch, MAX_DECODE_BATCH);
+  for (uint32_t i = 0; i < batch; ++i) {
+    if (slots[i] >= m->c.max_batch) return fail(NNC_E_ARG, "slot %u out of range", slots[i]);
+    for (uint32_t j = 0; j < i; ++j)
+      if (slots[j] == slots[i]) return fail(NNC_E_ARG, "slot %u appears twice", slots[i]);
+    if ((uint64_t)m->len[slots[i]] + n_steps > m->c.max_seq)
+      return fail(NNC_E_KV_FULL, "slot %u: length %u + %u exceeds max_seq %u", slots[i], m->len[slots[i]], n_steps,
+                  m->c.max_seq);
+  }
+  return NNC_OK;
+}
+
+nnc_status set_decode_state(nnc_model* m, const uint32_t* slots, const int32_t* tokens, uint32_t batch,
+                            uint32_t* max_pos_out, double* kv_rows_out) {
+  uint32_t pos[MAX_COLS];
+  uint32_t mx = 0;
+  double rows = 0;
+  for (uint32_t i = 0; i < batch; ++i) {
+    pos[i] = m->len[slots[i]];
+    mx = pos[i] > mx ? pos[i] : mx;
+    rows += pos[i] + 1.0;
+  }
+  *max_pos_out = mx;
+  *kv_rows_out = rows;
+  HIP_TRY(launch_set_state(m->stream, m->st, (int)batch, tokens, slots, pos, 0));
+  return NNC_OK;
+}
+
+// One greedy decode step (pass + token feedback) as a graph, captured on first use
+// per (batch, pieces, attention grid).
+nnc_status greedy_step(nnc_model* m, uint32_t batch, int nsplit, int grid_chunks, bool allow_graph,
+                       double kv_rows) {
+  Pass p;
+  p.kv_rows = kv_rows;
+  p.ncols = (int)batch;
+  p.nsplit = nsplit;
+  p.head_ncols = (int)batch;
+  p.logits = m->logits;
+  p.logits_ld = m->V();
+  p.next = m->next;
+  p.grid_chunks = grid_chunks;
+  const bool graph = allow_graph && m->opt_graph && !m->profiling && m->stream != nullptr;
+  if (!graph) {
+    if (nnc_status st = run_pass(m, p)) return st;
+    HIP_TRY(launch_finish_step(m->stream, m->st, (int)batch, m->next, m->token_log));
+    return NNC_OK;
+  }
+  const auto key = std::make_tuple((int)batch, nsplit, grid_chunks);
+  auto it = m->graphs.find(key);
+  if (it == m->graphs.end()) {
+    hipGraph_t g = nullptr;
+    HIP_TRY(hipStreamBeginCapture(m->stream, hipStreamCaptureModeThreadLocal));
+    nnc_status st = run_pass(m, p);
+    hipError_t e1 = st == NNC_OK ? launch_finish_step(m->stream, m->st, (int)batch, m->next, m->token_log)
+                                 : hipSuccess;
+    hipError_t e2 = hipStreamEndCapture(m->stream, &g);
+    if (st != NNC_OK) {
+      if (g) (void)hipGraphDestroy(g);
+      return st;
+    }
+    if (e1 != hipSuccess) return dev_fail(e1, "capture finish_step");
+    if (e2 != hipSuccess) return dev_fail(e2, "hipStreamEndCapture");
+    hipGraphExec_t ge = nullptr;
+    hipError_t e3 = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(g);
+    if (e3 != hipSuccess) return dev_fail(e3, "hipGraphInstantiate");
+    it = m->graphs.emplace(key, ge).first;
+  }
+  HIP_TRY(hipGraphLaunch(it->second, m->stream));
+  return NNC_OK;
+}
+
+}  // namespace
+
+// =============================================================================
+// public ABI
+// =============================================================================
+extern "C" {
+
+const char* nnc_last_error(void) { return g_err; }
+
+uint64_t nnc_blob_bytes(const nnc_config* cfg) {
+  if (check_config(cfg) != NNC_OK) return 0;
+  return blob_bytes_of(cfg);
+}
+
+nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob_bytes, const nnc_device* dev,
+                            nnc_model** out) {
+  if (!out) return fail(NNC_E_ARG, "out is NULL");
+  if (nnc_status st = check_config(cfg)) return st;
+  if (!blob) return fail(NNC_E_ARG, "blob is NULL");
+  if ((uint64_t)blob_bytes != blob_bytes_of(cfg))
+    return fail(NNC_E_BLOB, "blob has %zu bytes, config needs %llu", blob_bytes,
+                (unsigned long long)blob_bytes_of(cfg));
+
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev == 0) return fail(NNC_E_DEVICE, "no HIP device");
+  int device = 0;
+  HIP_TRY(hipGetDevice(&device));
+  hipDeviceProp_t prop;
+  HIP_TRY(hipGetDeviceProperties(&prop, device));
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+    return fail(NNC_E_DEVICE, "device is %s; this library is built for gfx950 only", prop.gcnArchName);
+
+  nnc_model* m = new (std::nothrow) nnc_model;
+  if (!m) return fail(NNC_E_NOMEM, "host allocation failed");
+  m->c = *cfg;
+  m->f32 = cfg->compute_dtype == NNC_F32;
+  m->device = device;
+  if (dev) {
+    m->stream = static_cast<hipStream_t>(dev->stream);
+    if (dev->alloc && dev->free) {
+      m->hooks = *dev;
+      m->use_hooks = true;
+    }
+  }
+  m->opt_prefill_exact = true;
+  const nnc_config& c = m->c;
+  const size_t H = m->H(), Dq = m->Dq(), Dkv = m->Dkv(), F = m->F(), V = m->V(), d = c.head_dim;
+  const size_t w = m->esz(), bw = c.blob_dtype == NNC_F32 ? 4 : 2;
+  const bool src_f32 = c.blob_dtype == NNC_F32;
+  hipStream_t s = m->stream;
+
+  nnc_status st = NNC_OK;
+  auto bail = [&](nnc_status code) {
+    (void)hipStreamSynchronize(s);
+    release_all(m);
+    delete m;
+    return code;
+  };
+#define ALLOC(ptr, type, bytes)                                                              \
+  do {                                                                                       \
+    (ptr) = static_cast<type>(dev_alloc(m, (bytes)));                                        \
+    if (!(ptr)) return bail(fail(NNC_E_NOMEM, "device allocation of %zu bytes failed", (size_t)(bytes))); \
+  } while (0)
+#define TRY_OR_BAIL(call)                                  \
+  do {                                                     \
+    hipError_t e_ = (call);                                \
+    if (e_ != hipSuccess) return bail(dev_fail(e_, #call)); \
+  } while (0)
+
+  // staging buffer for one canonical matrix at a time
+  size_t stage_elems = std::max(std::max(Dq * H, 2 * 0 + F * H), c.has_embed_and_head ? V * H : 0);
+  void* stage = nullptr;
+  ALLOC(stage, void*, stage_elems * bw);
+
+  const char* bp = static_cast<const char*>(blob);
+  auto upload_gain = [&](float*& dst, size_t n) -> hipError_t {
+    dst = static_cast<float*>(dev_alloc(m, n * 4));
+    if (!dst) return hipErrorOutOfMemory;
+    hipError_t e = hipMemcpyAsync(dst, bp, n * 4, hipMemcpyHostToDevice, s);
+    bp += n * 4;
+    return e;
+  };
+  auto upload_matrix = [&](void* dst, size_t rows, size_t K, int tile_stride, int tile_offset) -> hipError_t {
+    hipError_t e = hipMemcpyAsync(stage, bp, rows * K * bw, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return e;
+    bp += rows * K * bw;
+    return launch_repack(s, src_f32, m->f32, stage, dst, (int)rows, (int)K, tile_stride, tile_offset);
+  };
+
+  if (c.has_embed_and_head) {
+    ALLOC(m->embed, void*, V * H * w);
+    TRY_OR_BAIL(upload_matrix(m->embed, V, H, 1, 0));
+  }
+  m->L.resize(c.n_layers);
+  for (auto& L : m->L) {
+    TRY_OR_BAIL(upload_gain(L.g_in, H));
+    ALLOC(L.wqkv, void*, (Dq + 2 * Dkv) * H * w);
+    TRY_OR_BAIL(upload_matrix(L.wqkv, Dq, H, 1, 0));
+    TRY_OR_BAIL(upload_matrix(L.wqkv, Dkv, H, 1, (int)(Dq / 16)));
+    TRY_OR_BAIL(upload_matrix(L.wqkv, Dkv, H, 1, (int)((Dq + Dkv) / 16)));
+    TRY_OR_BAIL(upload_gain(L.g_q, d));
+    TRY_OR_BAIL(upload_gain(L.g_k, d));
+    ALLOC(L.wo, void*, H * Dq * w);
+    TRY_OR_BAIL(upload_matrix(L.wo, H, Dq, 1, 0));
+    TRY_OR_BAIL(upload_gain(L.g_post, H));
+    ALLOC(L.wgu, void*, 2 * F * H * w);
+    TRY_OR_BAIL(upload_matrix(L.wgu, F, H, 2, 0));
+    TRY_OR_BAIL(upload_matrix(L.wgu, F, H, 2, 1));
+    ALLOC(L.wd, void*, H * F * w);
+    TRY_OR_BAIL(upload_matrix(L.wd, H, F, 1, 0));
+    const size_t kv_bytes = (size_t)c.max_batch * c.n_kv_heads * c.max_seq * d * w;
+    ALLOC(L.kc, void*, kv_bytes);
+    ALLOC(L.vc, void*, kv_bytes);
+  }
+  if (c.has_embed_and_head) {
+    TRY_OR_BAIL(upload_gain(m->g_final, H));
+    if (c.tied_lm_head) {
+      m->lm_head = m->embed;
+    } else {
+      ALLOC(m->lm_head, void*, V * H * w);
+      TRY_OR_BAIL(upload_matrix(m->lm_head, V, H, 1, 0));
+    }
+  }
+
+  // rotary table: cos/sin of pos * theta^(-2i/d), evaluated in fp64, stored as fp32
+  {
+    const size_t n = (size_t)c.max_seq * 64;
+    std::vector<float2> tab(n);
+    for (uint32_t p = 0; p < c.max_seq; ++p)
+      for (int i = 0; i < 64; ++i) {
+        const double phi = (double)p * std::pow((double)c.rope_theta, -2.0 * i / 128.0);
+        tab[(size_t)p * 64 + i] = make_float2((float)std::cos(phi), (float)std::sin(phi));
+      }
+    ALLOC(m->rope, float2*, n * sizeof(float2));
+    TRY_OR_BAIL(hipMemcpyAsync(m->rope, tab.data(), n * sizeof(float2), hipMemcpyHostToDevice, s));
+    TRY_OR_BAIL(hipStreamSynchronize(s));  // tab goes out of scope
+  }
+
+  m->max_chunks = chunks_grid(c.max_seq - 1);
+  ALLOC(m->st, ColState*, sizeof(ColState));
+  ALLOC(m->x, float*, (size_t)MAX_COLS * H * 4);
+  ALLOC(m->qkv, float*, (size_t)MAX_COLS * (Dq + 2 * Dkv) * 4);
+  ALLOC(m->Xp, void*, (size_t)MAX_COLS * H * w);
+  ALLOC(m->Ap, void*, (size_t)MAX_COLS * std::max(Dq, F) * w);
+  ALLOC(m->partial, float*, (size_t)MAX_COLS * c.n_q_heads * m->max_chunks * 132 * 4);
+  ALLOC(m->next, int32_t*, MAX_COLS * 4);
+  m->token_log_steps = c.max_seq;
+  ALLOC(m->token_log, int32_t*, (size_t)m->token_log_steps * MAX_DECODE_BATCH * 4);
+  if (c.has_embed_and_head) {
+    ALLOC(m->logits, float*, (size_t)MAX_DECODE_BATCH * V * 4);
+    ALLOC(m->am_val, float*, MAX_COLS * 64 * 4);
+    ALLOC(m->am_idx, int32_t*, MAX_COLS * 64 * 4);
+  }
+  m->len.assign(c.max_batch, 0);
+  TRY_OR_BAIL(hipStreamSynchronize(s));
+  (void)st;
+#undef ALLOC
+#undef TRY_OR_BAIL
+  *out = m;
+  return NNC_OK;
+}
+
+void nnc_model_destroy(nnc_model* m) {
+  if (!m) return;
+  (void)hipStreamSynchronize(m->stream);
+  release_all(m);
+  delete m;
+}
+
+nnc_status nnc_kv_reset(nnc_model* m, int32_t slot) {
+  if (!m) return fail(NNC_E_ARG, "model is NULL");
+  if (slot < -1 || (slot >= 0 && (uint32_t)slot >= m->c.max_batch)) return fail(NNC_E_ARG, "slot %d out of range", slot);
+  if (slot < 0)
+    for (auto& l : m->len) l = 0;
+  else
+    m->len[slot] = 0;
+  return NNC_OK;
+}
+
+nnc_status nnc_slot_len(const nnc_model* m, uint32_t slot, uint32_t* len_out) {
+  if (!m || !len_out) return fail(NNC_E_ARG, "NULL argument");
+  if (slot >= m->c.max_batch) return fail(NNC_E_ARG, "slot %u out of range", slot);
+  *len_out = m->len[slot];
+  return NNC_OK;
+}
+
+nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
+  if (!m) return fail(NNC_E_ARG, "model is NULL");
+  switch (opt) {
+    case NNC_OPT_GRAPH: m->opt_graph = value != 0; return NNC_OK;
+    case NNC_OPT_PREFILL_EXACT: m->opt_prefill_exact = value != 0; return NNC_OK;
+  }
+  return fail(NNC_E_ARG, "unknown option %d", (int)opt);
+}
+
+static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tokens, const float* x, uint32_t n,
+                                 float* logits_out, int32_t* next_out, float* y) {
+  if (slot >= m->c.max_batch) return fail(NNC_E_ARG, "slot %u out of range", slot);
+  if (n == 0) return fail(NNC_E_ARG, "n is 0");
+  if ((uint64_t)m->len[slot] + n > m->c.max_seq)
+    return fail(NNC_E_KV_FULL, "slot %u: length %u + %u exceeds max_seq %u", slot, m->len[slot], n, m->c.max_seq);
+  if (tokens)
+    for (uint32_t i = 0; i < n; ++i)
+      if (tokens[i] < 0 || (uint32_t)tokens[i] >= m->c.vocab) return fail(NNC_E_ARG, "token %d out of range", tokens[i]);
+  const int nsplit = m->f32 ? 1 : (m->opt_prefill_exact ? 2 : 1);
+  const uint32_t chunk = MAX_COLS / nsplit;
+  const size_t H = m->H();
+  const uint32_t len0 = m->len[slot];
+  for (uint32_t t0 = 0; t0 < n; t0 += chunk) {
+    const uint32_t nc = std::min(chunk, n - t0);
+    uint32_t slots[MAX_COLS], pos[MAX_COLS];
+    for (uint32_t i = 0; i < nc; ++i) {
+      slots[i] = slot;
+      pos[i] = len0 + t0 + i;
+    }
+    HIP_TRY(launch_set_state(m->stream, m->st, (int)nc, tokens ? tokens + t0 : nullptr, slots, pos, 0));
+    Pass p;
+    p.ncols = (int)nc;
+    p.nsplit = nsplit;
+    p.tokens = tokens != nullptr;
+    p.grid_chunks = chunks_grid(pos[nc - 1]);
+    for (uint32_t i = 0; i < nc; ++i) p.kv_rows += pos[i] + 1.0;
+    const bool last = t0 + nc == n;
+    if (!tokens)
+      HIP_TRY(launch_copy_rows(m->stream, x + (size_t)t0 * H, m->x, (size_t)nc * H));
+    if (last && tokens && (logits_out || next_out)) {
+      p.head_col0 = (int)nc - 1;
+      p.head_ncols = 1;
+      p.logits = logits_out ? logits_out : m->logits;
+      p.logits_ld = m->V();
+      p.next = next_out ? m->next : nullptr;
+    }
+    if (nnc_status st = run_pass(m, p)) return st;
+    if (!tokens) HIP_TRY(launch_copy_rows(m->stream, m->x, y + (size_t)t0 * H, (size_t)nc * H));
+    if (last && next_out && tokens)
+      HIP_TRY(hipMemcpyAsync(next_out, m->next, 4, hipMemcpyDeviceToDevice, m->stream));
+  }
+  m->len[slot] = len0 + n;
+  return NNC_OK;
+}
+
+nnc_status nnc_prefill(nnc_model* m, uint32_t slot, const int32_t* tokens, uint32_t n, float* logits_out,
+                       int32_t* next_out) {
+  if (!m || !tokens) return fail(NNC_E_ARG, "NULL argument");
+  if (!m->c.has_embed_and_head) return fail(NNC_E_STATE, "model has no embedding; use nnc_prefill_hidden");
+  return prefill_common(m, slot, tokens, nullptr, n, logits_out, next_out, nullptr);
+}
+
+nnc_status nnc_prefill_hidden(nnc_model* m, uint32_t slot, const float* x, uint32_t n, float* y) {
+  if (!m || !x || !y) return fail(NNC_E_ARG, "NULL argument");
+  if (m->c.has_embed_and_head) return fail(NNC_E_STATE, "model takes tokens; use nnc_prefill");
+  return prefill_common(m, slot, nullptr, x, n, nullptr, nullptr, y);
+}
+
+nnc_status nnc_decode_step(nnc_model* m, const uint32_t* slots, const int32_t* tokens, uint32_t batch,
+                           float* logits_out, int32_t* next_out) {
+  if (!m || !tokens) return fail(NNC_E_ARG, "NULL argument");
+  if (!m->c.has_embed_and_head) return fail(NNC_E_STATE, "model has no embedding; use nnc_decode_step_hidden");
+  if (nnc_status st = check_slots(m, slots, batch, 1)) return st;
+  for (uint32_t i = 0; i < batch; ++i)
+    if (tokens[i] < 0 || (uint32_t)tokens[i] >= m->c.vocab) return fail(NNC_E_ARG, "token %d out of range", tokens[i]);
+  uint32_t max_pos = 0;
+  double kv_rows = 0;
+  if (nnc_status st = set_decode_state(m, slots, tokens, batch, &max_pos, &kv_rows)) return st;
+  const int nsplit = decode_nsplit(m, batch);
+  if (logits_out) {
+    Pass p;
+    p.ncols = (int)batch;
+    p.nsplit = nsplit;
+    p.head_ncols = (int)batch;
+    p.logits = logits_out;
+    p.logits_ld = m->V();
+    p.next = next_out ? m->next : nullptr;
+    p.grid_chunks = chunks_grid(max_pos);
+    p.kv_rows = kv_rows;
+    if (nnc_status st = run_pass(m, p)) return st;
+  } else {
+    if (nnc_status st = greedy_step(m, batch, nsplit, chunks_grid(max_pos), true, kv_rows)) return st;
+  }
+  if (next_out) HIP_TRY(hipMemcpyAsync(next_out, m->next, batch * 4, hipMemcpyDeviceToDevice, m->stream));
+  for (uint32_t i = 0; i < batch; ++i) m->len[slots[i]] += 1;
+  return NNC_OK;
+}
+
+nnc_status nnc_decode_greedy(nnc_model* m, const uint32_t* slots, const int32_t* first_tokens, uint32_t batch,
+                             uint32_t n_steps, int32_t* tokens_out, float* logits_out) {
+  if (!m || !first_tokens || !tokens_out) return fail(NNC_E_ARG, "NULL argument");
+  if (!m->c.has_embed_and_head) return fail(NNC_E_STATE, "model has no embedding");
+  if (n_steps == 0) return fail(NNC_E_ARG, "n_steps is 0");
+  if (n_steps > m->token_log_steps) return fail(NNC_E_ARG, "n_steps %u exceeds %u", n_steps, m->token_log_steps);
+  if (nnc_status st = check_slots(m, slots, batch, n_steps)) return st;
+  for (uint32_t i = 0; i < batch; ++i)
+    if (first_tokens[i] < 0 || (uint32_t)first_tokens[i] >= m->c.vocab)
+      return fail(NNC_E_ARG, "token %d out of range", first_tokens[i]);
+  uint32_t max_pos = 0;
+  double kv_rows = 0;
+  if (nnc_status st = set_decode_state(m, slots, first_tokens, batch, &max_pos, &kv_rows)) return st;
+  const int nsplit = decode_nsplit(m, batch);
+  for (uint32_t step = 0; step < n_steps; ++step) {
+    const int gc = chunks_grid(max_pos + step);
+    if (logits_out) {
+      Pass p;
+      p.ncols = (int)batch;
+      p.nsplit = nsplit;
+      p.head_ncols = (int)batch;
+      p.logits = logits_out + (size_t)step * batch * m->V();
+      p.logits_ld = m->V();
+      p.next = m->next;
+      p.grid_chunks = gc;
+      p.kv_rows = kv_rows + (double)step * batch;
+      if (nnc_status st = run_pass(m, p)) return st;
+      HIP_TRY(launch_finish_step(m->stream, m->st, (int)batch, m->next, m->token_log));
+    } else {
+      if (nnc_status st = greedy_step(m, batch, nsplit, gc, true, kv_rows + (double)step * batch)) return st;
+    }
+  }
+  HIP_TRY(hipMemcpyAsync(tokens_out, m->token_log, (size_t)n_steps * batch * 4, hipMemcpyDeviceToDevice, m->stream));
+  for (uint32_t i = 0; i < batch; ++i) m->len[slots[i]] += n_steps;
+  return NNC_OK;
+}
+
+nnc_status nnc_decode_step_hidden(nnc_model* m, const uint32_t* slots, const float* x, uint32_t batch, float* y) {
+  if (!m || !x || !y) return fail(NNC_E_ARG, "NULL argument");
+  if (m->c.has_embed_and_head) return fail(NNC_E_STATE, "model takes tokens; use nnc_decode_step");
+  if (nnc_status st = check_slots(m, slots, batch, 1)) return st;
+  uint32_t max_pos = 0;
+  double kv_rows = 0;
+  if (nnc_status st = set_decode_state(m, slots, nullptr, batch, &max_pos, &kv_rows)) return st;
+  HIP_TRY(launch_copy_rows(m->stream, x, m->x, (size_t)batch * m->H()));
+  Pass p;
+  p.kv_rows = kv_rows;
+  p.ncols = (int)batch;
+  p.nsplit = decode_nsplit(m, batch);
+  p.tokens = false;
+  p.grid_chunks = chunks_grid(max_pos);
+  if (nnc_status st = run_pass(m, p)) return st;
+  HIP_TRY(launch_copy_rows(m->stream, m->x, y, (size_t)batch * m->H()));
+  for (uint32_t i = 0; i < batch; ++i) m->len[slots[i]] += 1;
+  return NNC_OK;
+}
+
+nnc_status nnc_kv_read(nnc_model* m, uint32_t layer, uint32_t slot, uint32_t which, uint32_t pos0, uint32_t n,
+                       float* out) {
+  if (!m || !out) return fail(NNC_E_ARG, "NULL argument");
+  if (layer >= m->c.n_layers || slot >= m->c.max_batch || which > 1 || n == 0 ||
+      (uint64_t)pos0 + n > m->len[slot])
+    return fail(NNC_E_ARG, "kv_read range out of bounds");
+  const size_t slot_elems = (size_t)m->c.n_kv_heads * m->c.max_seq * 128;
+  const char* base = static_cast<const char*>(which ? m->L[layer].vc : m->L[layer].kc) + slot * slot_elems * m->esz();
+  HIP_TRY(launch_kv_read(m->stream, m->f32, base, m->c.max_seq, (int)m->c.n_kv_heads, pos0, n, out));
+  return NNC_OK;
+}
+
+nnc_status nnc_profile_begin(nnc_model* m) {
+  if (!m) return fail(NNC_E_ARG, "model is NULL");
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  for (auto& r : m->prof) {
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  m->prof.clear();
+  m->profiling = true;
+  return NNC_OK;
+}
+
+nnc_status nnc_profile_end(nnc_model* m, nnc_kernel_stat* out, uint32_t cap, uint32_t* n_out) {
+  if (!m || !n_out) return fail(NNC_E_ARG, "NULL argument");
+  m->profiling = false;
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  nnc_kernel_stat acc[FAM_COUNT];
+  memset(acc, 0, sizeof acc);
+  for (int f = 0; f < FAM_COUNT; ++f) snprintf(acc[f].name, sizeof acc[f].name, "%s", kFamName[f]);
+  for (auto& r : m->prof) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.e0, r.e1) == hipSuccess) {
+      acc[r.fam].launches += 1;
+      acc[r.fam].total_ms += ms;
+      acc[r.fam].bytes += r.bytes;
+      acc[r.fam].flops += r.flops;
+    }
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  m->prof.clear();
+  uint32_t k = 0;
+  for (int f = 0; f < FAM_COUNT && k < cap; ++f)
+    if (acc[f].launches && out) out[k++] = acc[f];
+  *n_out = k;
+  return NNC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,99 @@
+// Internal interface between the host-side step scheduler (nnc_api.hip) and the
+// gfx950 kernels (nnc_kernels.hip).  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace nnc {
+
+// Activation columns one pass may carry: decode batch, or a prompt chunk.
+constexpr int MAX_COLS = 64;
+// Cached positions one attention workgroup covers.
+constexpr int ATT_CHUNK = 64;
+
+// Per-column bookkeeping, resident in device memory so that a captured graph
+// never bakes a position, slot or token into a kernel argument.
+struct ColState {
+  int32_t tok[MAX_COLS];    // token id of the column (token models)
+  uint32_t slot[MAX_COLS];  // KV slot the column belongs to
+  uint32_t pos[MAX_COLS];   // position the column occupies in its slot
+  uint32_t step;            // greedy-loop step counter
+  uint32_t pad[3];
+};
+
+enum Epilogue { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+
+// Skinny GEMM  Y[n, seq] = sum_k W[n, k] * X[k, seq]  over packed operands.
+//
+// Packed weight layout (both dtypes: 16 rows x KTILE columns per 1 KiB tile,
+// KTILE = 32 for bf16 and 16 for fp32, VEC = 8 or 4 elements per lane):
+//   Wp[((nt * KT + kt) * 64 + lane) * VEC + j] = W[nt*16 + lane%16][kt*KTILE + (lane/16)*VEC + j]
+// i.e. tile (nt, kt) is stored in the order a 64-lane wave feeds it to the
+// 16x16 matrix-core instruction as its A operand: every lane issues one
+// 16-byte load and a wave reads 1 KiB contiguously.
+//
+// Packed activation layout (the B operand; NC columns allocated, `ncols` used):
+//   Xp[((k / VEC) * NC + col) * VEC + k % VEC]
+// bf16 models carry each fp32 activation as `nsplit` bf16 pieces in adjacent
+// columns (col = seq * nsplit + piece, piece 0 = rounded value, piece 1 = rounded
+// remainder, ...); the pieces' products are summed in the epilogue, which keeps
+// activations at fp32 accuracy while the weights stream through the bf16 matrix
+// cores untouched.
+struct GemmArgs {
+  const void* Wp;
+  int n_tiles;        // output rows / 16
+  int KT;             // k tiles in the matrix
+  int kts_per_split;  // k tiles per blockIdx.y slice
+  const void* Xp;
+  int NC;     // allocated operand columns
+  int ncols;  // used operand columns = nseq * nsplit
+  int nsplit;
+  int nseq;
+  // EPI_STORE: out[seq * ldo + n] = y.  EPI_RESID: out[seq * ldo + n] += y.
+  float* out;
+  long ldo;
+  // offset added to `out`, in floats, = *step_ptr * step_stride (greedy loop logits log)
+  const uint32_t* step_ptr;
+  long step_stride;
+  // EPI_SWIGLU: rows come in 16-row pairs (gate tile, up tile); the activation
+  // silu(gate) * up for feature f is written as the packed operand of the next
+  // GEMM (K = number of features), split into nsplit_out pieces.
+  void* packed_out;
+  int NC_out;
+  int nsplit_out;
+};
+
+struct KernelCtx;  // profiling hook, defined in nnc_api.hip
+
+// All launchers enqueue on `s` and return the launch error code.
+hipError_t launch_repack(hipStream_t s, bool src_f32, bool dst_f32, const void* src, void* dst,
+                         int rows, int K, int tile_stride, int tile_offset);
+hipError_t launch_set_state(hipStream_t s, ColState* st, int ncols, const int32_t* tok,
+                            const uint32_t* slot, const uint32_t* pos, uint32_t step);
+hipError_t launch_embed(hipStream_t s, bool f32, const void* Ep, int H, const ColState* st,
+                        int ncols, float* x);
+hipError_t launch_rmsnorm_pack(hipStream_t s, bool f32, const float* x, long ldx, const float* gain,
+                               int H, float eps, int ncols, void* Xp, int NC, int nsplit);
+hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a);
+hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq, int nkv,
+                                     const float* gq, const float* gk, float eps,
+                                     const float2* rope, const ColState* st, int ncols, void* kc,
+                                     void* vc, uint32_t max_batch, uint32_t max_seq);
+hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, int nq, int nkv,
+                               const void* kc, const void* vc, uint32_t max_batch, uint32_t max_seq,
+                               const ColState* st, int ncols, int grid_chunks, float* partial,
+                               int max_chunks);
+hipError_t launch_attn_combine(hipStream_t s, bool f32, const float* partial, int max_chunks, int nq,
+                               const ColState* st, int ncols, void* Op, int NC, int nsplit);
+hipError_t launch_argmax(hipStream_t s, const float* logits, long ld, int V, int ncols,
+                         const uint32_t* step_ptr, long step_stride, float* scratch_val,
+                         int32_t* scratch_idx, int32_t* next);
+hipError_t launch_finish_step(hipStream_t s, ColState* st, int ncols, const int32_t* next,
+                              int32_t* token_log);
+hipError_t launch_kv_read(hipStream_t s, bool f32, const void* cache, uint32_t max_seq, int nkv,
+                          uint32_t pos0, uint32_t n, float* out);
+hipError_t launch_copy_rows(hipStream_t s, const float* src, float* dst, size_t n);
+
+}  // namespace nnc

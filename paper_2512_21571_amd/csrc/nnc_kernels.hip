@@ -1,0 +1,769 @@
+// gfx950 (CDNA4) kernels of the Qwen3-style decoder forward pass.
+//
+// The matmuls follow the paper's packed-layout idea (Section 3.1.2, Auto
+// Vectorize: keep operands in the hardware-intrinsic blocked layout end to end;
+// Section 3.3.2: MatMul micro-kernels over packed operands): weights are stored
+// once in matrix-core fragment order and every lane streams them with 16-byte
+// loads.  Everything else (norms, RoPE, SwiGLU, attention) is the public Qwen3
+// decoder arithmetic in fp32.
+#include "nnc_internal.h"
+
+namespace nnc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// small device helpers
+// ---------------------------------------------------------------------------
+
+// fp32 -> bf16 bit pattern, round to nearest, ties to even; NaN stays NaN.
+__device__ __forceinline__ uint32_t bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// Split v into up to three bf16 pieces whose sum is v to fp32 accuracy.
+__device__ __forceinline__ void split_bf16(float v, int nsplit, uint32_t* piece) {
+  float r = v;
+#pragma unroll
+  for (int s = 0; s < 3; ++s) {
+    if (s < nsplit) {
+      const uint32_t b = bf16_bits(r);
+      piece[s] = b;
+      r -= bf16_to_f32(b);
+    }
+  }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Sum over a 256-thread block; every thread gets the result.  `sm` holds 4 floats.
+__device__ __forceinline__ float block_sum_256(float v, float* sm) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (sm[0] + sm[1]) + (sm[2] + sm[3]);
+}
+
+// ---------------------------------------------------------------------------
+// weight repack: canonical row-major [rows, K] -> matrix-core tile order
+// ---------------------------------------------------------------------------
+// One thread per (tile row-block nt, k tile kt, lane).  The destination tile index is
+// nt * tile_stride + tile_offset, which expresses both "append below" (stride 1,
+// offset = first tile of the sub-matrix in a fused matrix) and "interleave with a
+// sibling matrix in 16-row tiles" (stride 2, offset 0 or 1).
+template <bool SRC_F32, bool DST_F32>
+__global__ __launch_bounds__(256) void k_repack(const void* __restrict__ src, void* __restrict__ dst,
+                                                int rows, int K, int tile_stride, int tile_offset) {
+  constexpr int VEC = DST_F32 ? 4 : 8;
+  constexpr int KTILE = VEC * 4;
+  const int KT = K / KTILE;
+  const size_t total = (size_t)(rows / 16) * KT * 64;
+  const size_t v = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (v >= total) return;
+  const int lane = (int)(v & 63);
+  const size_t t = v >> 6;
+  const int kt = (int)(t % KT);
+  const int nt = (int)(t / KT);
+  const size_t r = (size_t)nt * 16 + (lane & 15);
+  const size_t k0 = (size_t)kt * KTILE + (lane >> 4) * VEC;
+  const size_t dvec = ((size_t)(nt * tile_stride + tile_offset) * KT + kt) * 64 + lane;
+  if constexpr (DST_F32) {
+    static_assert(SRC_F32 || !DST_F32, "bf16 blobs are never widened");
+    const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(src) + r * K + k0);
+    reinterpret_cast<float4*>(dst)[dvec] = x;
+  } else if constexpr (SRC_F32) {
+    const float* p = static_cast<const float*>(src) + r * K + k0;
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    const float4 b = *reinterpret_cast<const float4*>(p + 4);
+    uint4 o;
+    o.x = bf16_bits(a.x) | (bf16_bits(a.y) << 16);
+    o.y = bf16_bits(a.z) | (bf16_bits(a.w) << 16);
+    o.z = bf16_bits(b.x) | (bf16_bits(b.y) << 16);
+    o.w = bf16_bits(b.z) | (bf16_bits(b.w) << 16);
+    reinterpret_cast<uint4*>(dst)[dvec] = o;
+  } else {
+    reinterpret_cast<uint4*>(dst)[dvec] =
+        *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(src) + r * K + k0);
+  }
+}
+
+hipError_t launch_repack(hipStream_t s, bool src_f32, bool dst_f32, const void* src, void* dst,
+                         int rows, int K, int tile_stride, int tile_offset) {
+  const int ktile = dst_f32 ? 16 : 32;
+  const size_t total = (size_t)(rows / 16) * (K / ktile) * 64;
+  const unsigned grid = (unsigned)((total + 255) / 256);
+  if (dst_f32)
+    k_repack<true, true><<<grid, 256, 0, s>>>(src, dst, rows, K, tile_stride, tile_offset);
+  else if (src_f32)
+    k_repack<true, false><<<grid, 256, 0, s>>>(src, dst, rows, K, tile_stride, tile_offset);
+  else
+    k_repack<false, false><<<grid, 256, 0, s>>>(src, dst, rows, K, tile_stride, tile_offset);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// column state
+// ---------------------------------------------------------------------------
+struct StateInit {
+  int32_t tok[MAX_COLS];
+  uint32_t slot[MAX_COLS];
+  uint32_t pos[MAX_COLS];
+};
+
+__global__ void k_set_state(ColState* st, StateInit init, int ncols, uint32_t step) {
+  const int i = threadIdx.x;
+  if (i < ncols) {
+    st->tok[i] = init.tok[i];
+    st->slot[i] = init.slot[i];
+    st->pos[i] = init.pos[i];
+  }
+  if (i == 0) st->step = step;
+}
+
+hipError_t launch_set_state(hipStream_t s, ColState* st, int ncols, const int32_t* tok,
+                            const uint32_t* slot, const uint32_t* pos, uint32_t step) {
+  StateInit init;
+  for (int i = 0; i < MAX_COLS; ++i) {
+    init.tok[i] = (i < ncols && tok) ? tok[i] : 0;
+    init.slot[i] = i < ncols ? slot[i] : 0;
+    init.pos[i] = i < ncols ? pos[i] : 0;
+  }
+  k_set_state<<<1, MAX_COLS, 0, s>>>(st, init, ncols, step);
+  return hipGetLastError();
+}
+
+// After a greedy step: feed the chosen token back, advance positions, log the token.
+__global__ void k_finish_step(ColState* st, int ncols, const int32_t* next, int32_t* token_log) {
+  const int i = threadIdx.x;
+  const uint32_t step = st->step;
+  __syncthreads();
+  if (i < ncols) {
+    const int32_t t = next[i];
+    st->tok[i] = t;
+    st->pos[i] += 1;
+    token_log[(size_t)step * ncols + i] = t;
+  }
+  if (i == 0) st->step = step + 1;
+}
+
+hipError_t launch_finish_step(hipStream_t s, ColState* st, int ncols, const int32_t* next,
+                              int32_t* token_log) {
+  k_finish_step<<<1, MAX_COLS, 0, s>>>(st, ncols, next, token_log);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// embedding gather from the packed matrix: x[col][k] = E[tok[col]][k]
+// ---------------------------------------------------------------------------
+template <bool F32>
+__global__ __launch_bounds__(256) void k_embed(const void* __restrict__ Ep, int H,
+                                               const ColState* __restrict__ st, float* __restrict__ x) {
+  constexpr int VEC = F32 ? 4 : 8;
+  constexpr int KTILE = VEC * 4;
+  const int col = blockIdx.x;
+  const int r = st->tok[col];
+  const int KT = H / KTILE;
+  const size_t nt = (size_t)(r >> 4);
+  for (int k = threadIdx.x; k < H; k += 256) {
+    const int kt = k / KTILE, kk = k % KTILE;
+    const int lane = (r & 15) + 16 * (kk / VEC);
+    const size_t e = ((nt * KT + kt) * 64 + lane) * VEC + (kk % VEC);
+    float v;
+    if constexpr (F32)
+      v = static_cast<const float*>(Ep)[e];
+    else
+      v = bf16_to_f32(static_cast<const uint16_t*>(Ep)[e]);
+    x[(size_t)col * H + k] = v;
+  }
+}
+
+hipError_t launch_embed(hipStream_t s, bool f32, const void* Ep, int H, const ColState* st,
+                        int ncols, float* x) {
+  if (f32)
+    k_embed<true><<<ncols, 256, 0, s>>>(Ep, H, st, x);
+  else
+    k_embed<false><<<ncols, 256, 0, s>>>(Ep, H, st, x);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// RMSNorm of one column, written as a packed (split) GEMM operand
+//   h_i = x_i / sqrt(mean_j x_j^2 + eps) * g_i
+// ---------------------------------------------------------------------------
+template <bool F32>
+__device__ __forceinline__ void store_packed(void* Xp, int NC, int nsplit, int seq, int k, float v) {
+  if constexpr (F32) {
+    static_cast<float*>(Xp)[((size_t)(k >> 2) * NC + seq) * 4 + (k & 3)] = v;
+  } else {
+    uint32_t piece[3];
+    split_bf16(v, nsplit, piece);
+    uint16_t* p = static_cast<uint16_t*>(Xp) + ((size_t)(k >> 3) * NC + seq * nsplit) * 8 + (k & 7);
+#pragma unroll
+    for (int s = 0; s < 3; ++s)
+      if (s < nsplit) p[s * 8] = (uint16_t)piece[s];
+  }
+}
+
+template <bool F32>
+__global__ __launch_bounds__(256) void k_rmsnorm_pack(const float* __restrict__ x, long ldx,
+                                                      const float* __restrict__ gain, int H, float eps,
+                                                      void* __restrict__ Xp, int NC, int nsplit) {
+  __shared__ float sm[4];
+  const int seq = blockIdx.x;
+  const float* xr = x + (size_t)seq * ldx;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < H; i += 256) {
+    const float v = xr[i];
+    ss += v * v;
+  }
+  ss = block_sum_256(ss, sm);
+  const float r = 1.0f / sqrtf(ss / (float)H + eps);
+  for (int i = threadIdx.x; i < H; i += 256) store_packed<F32>(Xp, NC, nsplit, seq, i, xr[i] * r * gain[i]);
+}
+
+hipError_t launch_rmsnorm_pack(hipStream_t s, bool f32, const float* x, long ldx, const float* gain,
+                               int H, float eps, int ncols, void* Xp, int NC, int nsplit) {
+  if (f32)
+    k_rmsnorm_pack<true><<<ncols, 256, 0, s>>>(x, ldx, gain, H, eps, Xp, NC, nsplit);
+  else
+    k_rmsnorm_pack<false><<<ncols, 256, 0, s>>>(x, ldx, gain, H, eps, Xp, NC, nsplit);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// skinny GEMM on the matrix cores (decode GEMV, batched decode, prompt chunks)
+// ---------------------------------------------------------------------------
+// Workgroup = 4 waves.  blockIdx.x picks RT adjacent 16-row tiles, blockIdx.y a
+// slice of the k tiles; the four waves take k tiles of the slice round-robin, so
+// the workgroup walks memory contiguously.  Per k tile a wave loads RT x 1 KiB of
+// weights (one 16-byte load per lane per tile) and NCB operand fragments, and
+// issues RT x NCB matrix-core instructions (x4 k-steps for fp32).  Partial
+// accumulators of the four waves meet in LDS; the epilogue adds the bf16 pieces
+// of each activation column and stores / accumulates / applies SwiGLU.
+template <bool F32, int NCB, int RT, int EPI, int U>
+__global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
+  __shared__ float red[4][RT][NCB][256];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int c16 = lane & 15, g = lane >> 4;
+  const int KT = a.KT;
+  const int kt_begin = blockIdx.y * a.kts_per_split;
+  const int kt_end = min(KT, kt_begin + a.kts_per_split);
+  const uint4* __restrict__ W = static_cast<const uint4*>(a.Wp);
+  const uint4* __restrict__ X = static_cast<const uint4*>(a.Xp);
+  const size_t tile0 = (size_t)blockIdx.x * RT;
+
+  f32x4 acc[RT][NCB];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) acc[rt][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  bool colok[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) colok[cb] = cb * 16 + c16 < a.ncols;
+
+  for (int kt0 = kt_begin + wave; kt0 < kt_end; kt0 += 4 * U) {
+    uint4 av[U][RT], bv[U][NCB];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kt = kt0 + 4 * u;
+      const bool ok = kt < kt_end;
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+        av[u][rt] = ok ? W[((tile0 + rt) * KT + kt) * 64 + lane] : uint4{0, 0, 0, 0};
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb)
+        bv[u][cb] = (ok && colok[cb]) ? X[((size_t)kt * 4 + g) * a.NC + cb * 16 + c16] : uint4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+          if constexpr (F32) {
+            const float4 af = __builtin_bit_cast(float4, av[u][rt]);
+            const float4 bf = __builtin_bit_cast(float4, bv[u][cb]);
+            acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, acc[rt][cb], 0, 0, 0);
+            acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, acc[rt][cb], 0, 0, 0);
+            acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, acc[rt][cb], 0, 0, 0);
+            acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, acc[rt][cb], 0, 0, 0);
+          } else {
+            acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8, av[u][rt]), __builtin_bit_cast(bf16x8, bv[u][cb]),
+                acc[rt][cb], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+
+  // accumulator element i of a lane is output row (lane/16)*4 + i, operand column lane%16
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) red[wave][rt][cb][i * 64 + lane] = acc[rt][cb][i];
+  __syncthreads();
+
+  const int nsplit = a.nsplit, nseq = a.nseq;
+  auto total = [&](int rt, int row, int seq) {
+    float v = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+      const int col = seq * nsplit + s;
+      const int idx = (row & 3) * 64 + (row >> 2) * 16 + (col & 15);
+      const int cb = col >> 4;
+      v += (red[0][rt][cb][idx] + red[1][rt][cb][idx]) + (red[2][rt][cb][idx] + red[3][rt][cb][idx]);
+    }
+    return v;
+  };
+
+  if constexpr (EPI == EPI_SWIGLU) {
+    static_assert(EPI != EPI_SWIGLU || RT == 2, "SwiGLU needs the (gate, up) tile pair");
+    for (int o = tid; o < 16 * nseq; o += 256) {
+      const int seq = o >> 4, row = o & 15;
+      const float gate = total(0, row, seq);
+      const float up = total(RT - 1, row, seq);
+      const float act = gate / (1.0f + expf(-gate)) * up;
+      const int f = blockIdx.x * 16 + row;
+      store_packed<F32>(a.packed_out, a.NC_out, a.nsplit_out, seq, f, act);
+    }
+  } else {
+    float* out = a.out;
+    if (a.step_ptr) out += (size_t)(*a.step_ptr) * a.step_stride;
+    for (int o = tid; o < RT * 16 * nseq; o += 256) {
+      const int rt = o / (16 * nseq);
+      const int rem = o - rt * 16 * nseq;
+      const int seq = rem >> 4, row = rem & 15;
+      const float v = total(rt, row, seq);
+      float* dst = out + (size_t)seq * a.ldo + (tile0 + rt) * 16 + row;
+      if constexpr (EPI == EPI_STORE) {
+        *dst = v;
+      } else {
+        if (gridDim.y == 1)
+          *dst += v;
+        else
+          unsafeAtomicAdd(dst, v);
+      }
+    }
+  }
+}
+
+template <bool F32, int NCB, int RT, int EPI>
+static hipError_t gemm_dispatch(hipStream_t s, const GemmArgs& a) {
+  const int ksplit = (a.KT + a.kts_per_split - 1) / a.kts_per_split;
+  dim3 grid(a.n_tiles / RT, ksplit);
+  constexpr int U = (RT * NCB <= 2) ? 4 : 2;
+  k_gemm_skinny<F32, NCB, RT, EPI, U><<<grid, 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+template <bool F32, int EPI, int RT>
+static hipError_t gemm_dispatch_ncb(hipStream_t s, const GemmArgs& a) {
+  const int ncb = (a.ncols + 15) / 16;
+  switch (ncb) {
+    case 1: return gemm_dispatch<F32, 1, RT, EPI>(s, a);
+    case 2: return gemm_dispatch<F32, 2, RT, EPI>(s, a);
+    case 3: return gemm_dispatch<F32, 3, RT, EPI>(s, a);
+    case 4: return gemm_dispatch<F32, 4, RT, EPI>(s, a);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+// RT (16-row tiles per workgroup) is 2 for SwiGLU and for matrices with many rows,
+// 1 for the narrow output projections, where more workgroups matter more.
+hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a) {
+  if (a.ncols <= 0 || a.ncols > MAX_COLS || a.ncols > a.NC || a.nseq * a.nsplit != a.ncols ||
+      a.kts_per_split <= 0 || a.n_tiles <= 0)
+    return hipErrorInvalidValue;
+  const bool wide = a.n_tiles >= 1024 && (a.n_tiles % 2 == 0);
+  if (epi == EPI_SWIGLU) {
+    if (a.n_tiles % 2 || a.kts_per_split < a.KT) return hipErrorInvalidValue;
+    return f32 ? gemm_dispatch_ncb<true, EPI_SWIGLU, 2>(s, a) : gemm_dispatch_ncb<false, EPI_SWIGLU, 2>(s, a);
+  }
+  if (epi == EPI_STORE) {
+    if (a.kts_per_split < a.KT) return hipErrorInvalidValue;
+    if (wide) return f32 ? gemm_dispatch_ncb<true, EPI_STORE, 2>(s, a) : gemm_dispatch_ncb<false, EPI_STORE, 2>(s, a);
+    return f32 ? gemm_dispatch_ncb<true, EPI_STORE, 1>(s, a) : gemm_dispatch_ncb<false, EPI_STORE, 1>(s, a);
+  }
+  return f32 ? gemm_dispatch_ncb<true, EPI_RESID, 1>(s, a) : gemm_dispatch_ncb<false, EPI_RESID, 1>(s, a);
+}
+
+// ---------------------------------------------------------------------------
+// per-head QK RMSNorm + rotary embedding + KV append (head_dim 128)
+// ---------------------------------------------------------------------------
+// One wave per (column, head).  Lane i holds elements i and i+64 of the head,
+// which is exactly one rotary pair (half-split pairing).  q heads are normed,
+// rotated and written back in place (fp32); k heads are normed, rotated and
+// stored in the cache; v heads are stored as they are.
+// Cache layout: [slot][kv head][position][128], one such array per layer.
+template <bool F32>
+__global__ __launch_bounds__(64) void k_qknorm_rope_append(
+    float* __restrict__ qkv, int nq, int nkv, const float* __restrict__ gq, const float* __restrict__ gk,
+    float eps, const float2* __restrict__ rope, const ColState* __restrict__ st, void* __restrict__ kc,
+    void* __restrict__ vc, uint32_t max_seq) {
+  const int col = blockIdx.y, hh = blockIdx.x, lane = threadIdx.x;
+  const int ld = (nq + 2 * nkv) * 128;
+  float* p = qkv + (size_t)col * ld + (size_t)hh * 128;
+  const uint32_t pos = st->pos[col], slot = st->slot[col];
+  float a = p[lane], b = p[lane + 64];
+  const bool is_v = hh >= nq + nkv;
+  if (!is_v) {
+    const float ss = wave_sum(a * a + b * b);
+    const float r = 1.0f / sqrtf(ss * (1.0f / 128.0f) + eps);
+    const float* gg = hh < nq ? gq : gk;
+    a = a * r * gg[lane];
+    b = b * r * gg[lane + 64];
+    const float2 cs = rope[(size_t)pos * 64 + lane];
+    const float ra = a * cs.x - b * cs.y;
+    const float rb = b * cs.x + a * cs.y;
+    a = ra;
+    b = rb;
+  }
+  if (hh < nq) {
+    p[lane] = a;
+    p[lane + 64] = b;
+    return;
+  }
+  const int kvh = is_v ? hh - nq - nkv : hh - nq;
+  const size_t row = (((size_t)slot * nkv + kvh) * max_seq + pos) * 128;
+  void* dst = is_v ? vc : kc;
+  if constexpr (F32) {
+    static_cast<float*>(dst)[row + lane] = a;
+    static_cast<float*>(dst)[row + lane + 64] = b;
+  } else {
+    static_cast<uint16_t*>(dst)[row + lane] = (uint16_t)bf16_bits(a);
+    static_cast<uint16_t*>(dst)[row + lane + 64] = (uint16_t)bf16_bits(b);
+  }
+}
+
+hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq, int nkv,
+                                     const float* gq, const float* gk, float eps,
+                                     const float2* rope, const ColState* st, int ncols, void* kc,
+                                     void* vc, uint32_t max_batch, uint32_t max_seq) {
+  (void)max_batch;
+  dim3 grid(nq + 2 * nkv, ncols);
+  if (f32)
+    k_qknorm_rope_append<true><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, st, kc, vc, max_seq);
+  else
+    k_qknorm_rope_append<false><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, st, kc, vc, max_seq);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// split-KV attention for one new token per column (decode, and prompt chunks
+// whose columns are consecutive positions of one slot)
+// ---------------------------------------------------------------------------
+// grid (chunk, kv head x head groups, column); 4 waves.  A workgroup covers
+// ATT_CHUNK cached positions of one kv head for GH query heads that share it, so
+// each cached byte is read once per group.  Scores go through LDS; the chunk's
+// own max / sum / weighted value sum (un-normalised) are written as a partial
+// that k_attn_combine merges with the other chunks (online-softmax rescaling).
+// 16 lanes cover one cached row (8 elements each), a wave covers 4 rows per step.
+template <bool F32>
+__device__ __forceinline__ void load_row8(const void* base, size_t elem, float* v) {
+  if constexpr (F32) {
+    const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem);
+    const float4 y = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem + 4);
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
+  } else {
+    const uint4 x = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(base) + elem);
+    v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xffff0000u);
+    v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
+    v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xffff0000u);
+    v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xffff0000u);
+  }
+}
+
+template <bool F32, int GH>
+__global__ __launch_bounds__(256) void k_attn_partial(
+    const float* __restrict__ qkv, int nq, int nkv, const void* __restrict__ kc,
+    const void* __restrict__ vc, uint32_t max_seq, const ColState* __restrict__ st,
+    float* __restrict__ partial, int max_chunks) {
+  __shared__ float sc[GH][ATT_CHUNK];      // scores, then softmax weights
+  __shared__ float red[4][GH][128];        // per-wave value sums
+  __shared__ float sm_m[GH], sm_l[GH];
+  const int chunk = blockIdx.x, col = blockIdx.z;
+  const int G = nq / nkv;
+  const int groups = G / GH;
+  const int kvh = blockIdx.y / groups, hg = blockIdx.y % groups;
+  const int head0 = kvh * G + hg * GH;
+  const uint32_t pos = st->pos[col], slot = st->slot[col];
+  const uint32_t j0 = (uint32_t)chunk * ATT_CHUNK;
+  if (j0 > pos) return;  // chunk lies entirely in the future (uniform for the workgroup)
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int c16 = lane & 15, jj = lane >> 4;
+  const int ld = (nq + 2 * nkv) * 128;
+  const size_t base = ((size_t)slot * nkv + kvh) * max_seq * 128;
+
+  // this lane's 8-element slice of each query head
+  float q[GH][8];
+#pragma unroll
+  for (int h = 0; h < GH; ++h) {
+    const float* qp = qkv + (size_t)col * ld + (size_t)(head0 + h) * 128 + c16 * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q[h][e] = qp[e];
+  }
+  const float scale = 0.08838834764831845f;  // 1 / sqrt(128)
+
+  // scores s[h][j] = <q_h, K_j> / sqrt(d); positions beyond `pos` get -inf
+  for (int it = 0; it < ATT_CHUNK / 16; ++it) {
+    const int jl = it * 16 + wave * 4 + jj;
+    const uint32_t j = j0 + jl;
+    const bool valid = j <= pos;
+    float kv[8];
+    if (valid) {
+      load_row8<F32>(kc, base + (size_t)j * 128 + c16 * 8, kv);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) kv[e] = 0.f;
+    }
+#pragma unroll
+    for (int h = 0; h < GH; ++h) {
+      float d = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d += q[h][e] * kv[e];
+      d += __shfl_xor(d, 1, 64);
+      d += __shfl_xor(d, 2, 64);
+      d += __shfl_xor(d, 4, 64);
+      d += __shfl_xor(d, 8, 64);
+      if (c16 == 0) sc[h][jl] = valid ? d * scale : -INFINITY;
+    }
+  }
+  __syncthreads();
+
+  // chunk max, weights exp(s - max), chunk sum: one wave per head
+  for (int h = wave; h < GH; h += 4) {
+    const float s = sc[h][lane];  // ATT_CHUNK == 64 == wave size
+    const float m = wave_max(s);
+    const float w = expf(s - m);  // exp(-inf) = 0 for masked positions; position j0 is always valid
+    sc[h][lane] = w;
+    const float l = wave_sum(w);
+    if (lane == 0) {
+      sm_m[h] = m;
+      sm_l[h] = l;
+    }
+  }
+  __syncthreads();
+
+  // weighted value sum
+  float acc[GH][8];
+#pragma unroll
+  for (int h = 0; h < GH; ++h)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
+  for (int it = 0; it < ATT_CHUNK / 16; ++it) {
+    const int jl = it * 16 + wave * 4 + jj;
+    const uint32_t j = j0 + jl;
+    if (j <= pos) {
+      float vv[8];
+      load_row8<F32>(vc, base + (size_t)j * 128 + c16 * 8, vv);
+#pragma unroll
+      for (int h = 0; h < GH; ++h) {
+        const float w = sc[h][jl];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] += w * vv[e];
+      }
+    }
+  }
+#pragma unroll
+  for (int h = 0; h < GH; ++h)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float v = acc[h][e];
+      v += __shfl_xor(v, 16, 64);
+      v += __shfl_xor(v, 32, 64);
+      if (jj == 0) red[wave][h][c16 * 8 + e] = v;
+    }
+  __syncthreads();
+  // partial record per (column, head, chunk): 128 value sums, then max, then sum
+  for (int o = tid; o < GH * 128; o += 256) {
+    const int h = o >> 7, i = o & 127;
+    const float v = (red[0][h][i] + red[1][h][i]) + (red[2][h][i] + red[3][h][i]);
+    float* rec = partial + (((size_t)col * nq + head0 + h) * max_chunks + chunk) * 132;
+    rec[i] = v;
+    if (i == 0) {
+      rec[128] = sm_m[h];
+      rec[129] = sm_l[h];
+    }
+  }
+}
+
+hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, int nq, int nkv,
+                               const void* kc, const void* vc, uint32_t max_batch, uint32_t max_seq,
+                               const ColState* st, int ncols, int grid_chunks, float* partial,
+                               int max_chunks) {
+  (void)max_batch;
+  const int G = nq / nkv;
+  const int GH = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
+  dim3 grid(grid_chunks, nkv * (G / GH), ncols);
+#define NNC_ATT(F, H) \
+  k_attn_partial<F, H><<<grid, 256, 0, s>>>(qkv, nq, nkv, kc, vc, max_seq, st, partial, max_chunks)
+  if (f32) {
+    if (GH == 4) NNC_ATT(true, 4); else if (GH == 2) NNC_ATT(true, 2); else NNC_ATT(true, 1);
+  } else {
+    if (GH == 4) NNC_ATT(false, 4); else if (GH == 2) NNC_ATT(false, 2); else NNC_ATT(false, 1);
+  }
+#undef NNC_ATT
+  return hipGetLastError();
+}
+
+// Merge the chunk partials of one (column, head) and write the attention output
+// as the packed operand of the output projection (k index = head * 128 + i).
+//   M = max_c m_c;  o = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} l_c
+template <bool F32>
+__global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ partial, int max_chunks,
+                                                      int nq, const ColState* __restrict__ st,
+                                                      void* __restrict__ Op, int NC, int nsplit) {
+  const int head = blockIdx.x, col = blockIdx.y, i = threadIdx.x;
+  const int nchunks = (int)(st->pos[col] / ATT_CHUNK) + 1;
+  const float* rec0 = partial + ((size_t)col * nq + head) * max_chunks * 132;
+  float M = -INFINITY;
+  for (int c = 0; c < nchunks; ++c) M = fmaxf(M, rec0[(size_t)c * 132 + 128]);
+  float num = 0.f, den = 0.f;
+  for (int c = 0; c < nchunks; ++c) {
+    const float* rec = rec0 + (size_t)c * 132;
+    const float f = expf(rec[128] - M);
+    num += f * rec[i];
+    den += f * rec[129];
+  }
+  store_packed<F32>(Op, NC, nsplit, col, head * 128 + i, num / den);
+}
+
+hipError_t launch_attn_combine(hipStream_t s, bool f32, const float* partial, int max_chunks, int nq,
+                               const ColState* st, int ncols, void* Op, int NC, int nsplit) {
+  dim3 grid(nq, ncols);
+  if (f32)
+    k_attn_combine<true><<<grid, 128, 0, s>>>(partial, max_chunks, nq, st, Op, NC, nsplit);
+  else
+    k_attn_combine<false><<<grid, 128, 0, s>>>(partial, max_chunks, nq, st, Op, NC, nsplit);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// greedy arg-max over the vocabulary (lowest index wins ties)
+// ---------------------------------------------------------------------------
+constexpr int ARGMAX_BLOCKS = 64;
+
+__device__ __forceinline__ void argmax_merge(float& v, int32_t& i, float ov, int32_t oi) {
+  if (ov > v || (ov == v && oi < i)) {
+    v = ov;
+    i = oi;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_argmax_part(const float* __restrict__ logits, long ld, int V,
+                                                     const uint32_t* step_ptr, long step_stride,
+                                                     float* __restrict__ pv, int32_t* __restrict__ pi) {
+  __shared__ float sv[4];
+  __shared__ int32_t si[4];
+  const int col = blockIdx.y;
+  const float* row = logits + (size_t)col * ld;
+  if (step_ptr) row += (size_t)(*step_ptr) * step_stride;
+  float best = -INFINITY;
+  int32_t bi = 0x7fffffff;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < V; i += ARGMAX_BLOCKS * 256) {
+    const float v = row[i];
+    if (v > best) {  // indices increase within a thread, so strict > keeps the lowest
+      best = v;
+      bi = i;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(best, o, 64);
+    const int32_t oi = __shfl_xor(bi, o, 64);
+    argmax_merge(best, bi, ov, oi);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    sv[threadIdx.x >> 6] = best;
+    si[threadIdx.x >> 6] = bi;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) argmax_merge(best, bi, sv[w], si[w]);
+    pv[col * ARGMAX_BLOCKS + blockIdx.x] = best;
+    pi[col * ARGMAX_BLOCKS + blockIdx.x] = bi;
+  }
+}
+
+__global__ __launch_bounds__(64) void k_argmax_final(const float* __restrict__ pv,
+                                                     const int32_t* __restrict__ pi,
+                                                     int32_t* __restrict__ next) {
+  const int col = blockIdx.x;
+  float best = pv[col * ARGMAX_BLOCKS + threadIdx.x];
+  int32_t bi = pi[col * ARGMAX_BLOCKS + threadIdx.x];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(best, o, 64);
+    const int32_t oi = __shfl_xor(bi, o, 64);
+    argmax_merge(best, bi, ov, oi);
+  }
+  if (threadIdx.x == 0) next[col] = bi == 0x7fffffff ? 0 : bi;
+}
+
+hipError_t launch_argmax(hipStream_t s, const float* logits, long ld, int V, int ncols,
+                         const uint32_t* step_ptr, long step_stride, float* scratch_val,
+                         int32_t* scratch_idx, int32_t* next) {
+  static_assert(ARGMAX_BLOCKS == 64, "final pass assumes one wave of partials");
+  k_argmax_part<<<dim3(ARGMAX_BLOCKS, ncols), 256, 0, s>>>(logits, ld, V, step_ptr, step_stride,
+                                                           scratch_val, scratch_idx);
+  k_argmax_final<<<ncols, 64, 0, s>>>(scratch_val, scratch_idx, next);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// inspection / plumbing
+// ---------------------------------------------------------------------------
+// cache [kv head][position][128] of one slot and layer -> out [n][nkv*128] fp32
+template <bool F32>
+__global__ __launch_bounds__(128) void k_kv_read(const void* __restrict__ cache, uint32_t max_seq, int nkv,
+                                                 uint32_t pos0, float* __restrict__ out) {
+  const int kvh = blockIdx.x, t = blockIdx.y, i = threadIdx.x;
+  const size_t e = ((size_t)kvh * max_seq + pos0 + t) * 128 + i;
+  float v;
+  if constexpr (F32)
+    v = static_cast<const float*>(cache)[e];
+  else
+    v = bf16_to_f32(static_cast<const uint16_t*>(cache)[e]);
+  out[((size_t)t * nkv + kvh) * 128 + i] = v;
+}
+
+hipError_t launch_kv_read(hipStream_t s, bool f32, const void* cache, uint32_t max_seq, int nkv,
+                          uint32_t pos0, uint32_t n, float* out) {
+  dim3 grid(nkv, n);
+  if (f32)
+    k_kv_read<true><<<grid, 128, 0, s>>>(cache, max_seq, nkv, pos0, out);
+  else
+    k_kv_read<false><<<grid, 128, 0, s>>>(cache, max_seq, nkv, pos0, out);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void k_copy(const float* __restrict__ src, float* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_copy_rows(hipStream_t s, const float* src, float* dst, size_t n) {
+  const unsigned grid = (unsigned)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+  k_copy<<<grid ? grid : 1, 256, 0, s>>>(src, dst, n);
+  return hipGetLastError();
+}
+
+}  // namespace nnc
