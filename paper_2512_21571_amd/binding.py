@@ -56,6 +56,10 @@ def lib():
     """Load libnnc.so (building it first only if no built library exists)."""
     global _lib
     if _lib is None:
+        # PyTorch ships its own HIP runtime (soname libamdhip64.so.7).  Import it first so
+        # that libnnc.so binds to that already-loaded runtime: two HIP runtimes in one
+        # process cannot both own the device.
+        import torch  # noqa: F401
         if not os.path.exists(_build.LIB_PATH):
             _build.build(True)
         L = ctypes.CDLL(_build.LIB_PATH)   # raises OSError if the library cannot be loaded
@@ -170,13 +174,25 @@ class Model:
     def synchronize(self):
         self.stream.synchronize()
 
+    def _before(self):
+        # inputs may have been produced on the caller's current stream
+        self.stream.wait_stream(self.torch.cuda.current_stream(self.device))
+
+    def _after(self):
+        # outputs are consumed on the caller's current stream
+        self.torch.cuda.current_stream(self.device).wait_stream(self.stream)
+
     # -- forward pass ---------------------------------------------------------------
     def prefill(self, slot: int, tokens, want_logits: bool = True):
         t = _i32(tokens)
         logits = self._empty((self.V,), self.torch.float32) if want_logits else None
         nxt = self._empty((1,), self.torch.int32)
-        _check(lib().nnc_prefill(self.h, slot, t.ctypes.data, t.size,
-                                 logits.data_ptr() if want_logits else None, nxt.data_ptr()))
+        self._before()
+        try:
+            _check(lib().nnc_prefill(self.h, slot, t.ctypes.data, t.size,
+                                     logits.data_ptr() if want_logits else None, nxt.data_ptr()))
+        finally:
+            self._after()
         return logits, nxt
 
     def decode_step(self, slots, tokens, want_logits: bool = True):
@@ -184,8 +200,12 @@ class Model:
         b = s.size
         logits = self._empty((b, self.V), self.torch.float32) if want_logits else None
         nxt = self._empty((b,), self.torch.int32)
-        _check(lib().nnc_decode_step(self.h, s.ctypes.data, t.ctypes.data, b,
-                                     logits.data_ptr() if want_logits else None, nxt.data_ptr()))
+        self._before()
+        try:
+            _check(lib().nnc_decode_step(self.h, s.ctypes.data, t.ctypes.data, b,
+                                         logits.data_ptr() if want_logits else None, nxt.data_ptr()))
+        finally:
+            self._after()
         return logits, nxt
 
     def decode_greedy(self, slots, first_tokens, n_steps: int, want_logits: bool = False):
@@ -193,22 +213,34 @@ class Model:
         b = s.size
         toks = self._empty((n_steps, b), self.torch.int32)
         logits = self._empty((n_steps, b, self.V), self.torch.float32) if want_logits else None
-        _check(lib().nnc_decode_greedy(self.h, s.ctypes.data, t.ctypes.data, b, n_steps, toks.data_ptr(),
-                                       logits.data_ptr() if want_logits else None))
+        self._before()
+        try:
+            _check(lib().nnc_decode_greedy(self.h, s.ctypes.data, t.ctypes.data, b, n_steps, toks.data_ptr(),
+                                           logits.data_ptr() if want_logits else None))
+        finally:
+            self._after()
         return toks, logits
 
     def prefill_hidden(self, slot: int, x):
         """x: [n, hidden] float32 torch tensor on the device (or array-like, copied)."""
         x = self._as_dev(x)
         y = self._empty(tuple(x.shape), self.torch.float32)
-        _check(lib().nnc_prefill_hidden(self.h, slot, x.data_ptr(), x.shape[0], y.data_ptr()))
+        self._before()
+        try:
+            _check(lib().nnc_prefill_hidden(self.h, slot, x.data_ptr(), x.shape[0], y.data_ptr()))
+        finally:
+            self._after()
         return y
 
     def decode_step_hidden(self, slots, x):
         s = _u32(slots)
         x = self._as_dev(x)
         y = self._empty(tuple(x.shape), self.torch.float32)
-        _check(lib().nnc_decode_step_hidden(self.h, s.ctypes.data, x.data_ptr(), s.size, y.data_ptr()))
+        self._before()
+        try:
+            _check(lib().nnc_decode_step_hidden(self.h, s.ctypes.data, x.data_ptr(), s.size, y.data_ptr()))
+        finally:
+            self._after()
         return y
 
     def _as_dev(self, x):
@@ -233,7 +265,11 @@ class Model:
     def kv_read(self, layer: int, slot: int, which: int, pos0: int, n: int):
         dkv = self.cfg.n_kv_heads * self.cfg.head_dim
         out = self._empty((n, dkv), self.torch.float32)
-        _check(lib().nnc_kv_read(self.h, layer, slot, which, pos0, n, out.data_ptr()))
+        self._before()
+        try:
+            _check(lib().nnc_kv_read(self.h, layer, slot, which, pos0, n, out.data_ptr()))
+        finally:
+            self._after()
         return out
 
     def set_option(self, opt: int, value: int):

@@ -73,6 +73,7 @@ struct nnc_model {
   float* qkv = nullptr;      // [MAX_COLS][Dq + 2 Dkv]
   void* Xp = nullptr;        // packed operand, K = H
   void* Ap = nullptr;        // packed operand, K = max(Dq, F)
+  float* rpart = nullptr;    // [MAX_KSPLIT][MAX_COLS][H] k-slice partials of the O / down projections
   float* partial = nullptr;  // attention partials
   int max_chunks = 0;
   float* logits = nullptr;   // [32][V] when the caller passes no logits buffer
@@ -102,7 +103,7 @@ struct nnc_model {
 
 namespace {
 
-constexpr uint32_t MAX_DECODE_BATCH = 32;
+constexpr uint32_t MAX_DECODE_BATCH = 21;  // 21 sequences x 3 pieces = 63 operand columns
 
 nnc_status check_config(const nnc_config* c) {
   if (!c) return fail(NNC_E_ARG, "config is NULL");
@@ -206,11 +207,13 @@ struct Launch {
     if (e_ != hipSuccess) return dev_fail(e_, #call);    \
   } while (0)
 
-// k-slices for the accumulate-into-residual GEMMs: enough workgroups to cover the
-// chip, but at least 8 k tiles (2 per wave) per workgroup.
+// k-slices for the narrow output projections: enough workgroups to cover the chip,
+// but at least 8 k tiles (2 per wave) per workgroup.
+constexpr int MAX_KSPLIT = 16;
 int pick_kts(int n_tiles, int KT) {
   int ksplit = 512 / (n_tiles > 0 ? n_tiles : 1);
   if (ksplit < 1) ksplit = 1;
+  if (ksplit > MAX_KSPLIT) ksplit = MAX_KSPLIT;
   int max_split = KT / 8;
   if (max_split < 1) max_split = 1;
   if (ksplit > max_split) ksplit = max_split;
@@ -245,10 +248,13 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
 
   if (p.tokens) RUN(FAM_EMBED, n * H * w, 0, launch_embed(s, f32, m->embed, H, m->st, n, m->x));
 
+  // k-slice partials of the previous projection still to be added to x
+  int pending = 0;
+  const long pstride = (long)n * H;
   for (uint32_t li = 0; li < c.n_layers; ++li) {
     const LayerW& L = m->L[li];
     RUN(FAM_NORM, n * H * 8.0, 0,
-        launch_rmsnorm_pack(s, f32, m->x, H, L.g_in, H, c.rms_eps, n, m->Xp, nc, ns));
+        launch_rmsnorm_pack(s, f32, m->x, H, m->rpart, pending, pstride, L.g_in, H, c.rms_eps, n, m->Xp, nc, ns));
     {
       GemmArgs a{};
       a.Wp = L.wqkv; a.n_tiles = Nqkv / 16; a.KT = KTH; a.kts_per_split = KTH;
@@ -268,11 +274,12 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       GemmArgs a{};
       a.Wp = L.wo; a.n_tiles = H / 16; a.KT = KTQ; a.kts_per_split = pick_kts(a.n_tiles, KTQ);
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
-      a.out = m->x; a.ldo = H;
-      RUN(FAM_GEMM, (double)H * Dq * w, 2.0 * H * Dq * n, launch_gemm(s, f32, EPI_RESID, a));
+      a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
+      pending = (KTQ + a.kts_per_split - 1) / a.kts_per_split;
+      RUN(FAM_GEMM, (double)H * Dq * w, 2.0 * H * Dq * n, launch_gemm(s, f32, EPI_STORE, a));
     }
     RUN(FAM_NORM, n * H * 8.0, 0,
-        launch_rmsnorm_pack(s, f32, m->x, H, L.g_post, H, c.rms_eps, n, m->Xp, nc, ns));
+        launch_rmsnorm_pack(s, f32, m->x, H, m->rpart, pending, pstride, L.g_post, H, c.rms_eps, n, m->Xp, nc, ns));
     {
       GemmArgs a{};
       a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = KTH; a.kts_per_split = KTH;
@@ -284,16 +291,17 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       GemmArgs a{};
       a.Wp = L.wd; a.n_tiles = H / 16; a.KT = KTF; a.kts_per_split = pick_kts(a.n_tiles, KTF);
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
-      a.out = m->x; a.ldo = H;
-      RUN(FAM_GEMM, (double)H * F * w, 2.0 * H * F * n, launch_gemm(s, f32, EPI_RESID, a));
+      a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
+      pending = (KTF + a.kts_per_split - 1) / a.kts_per_split;
+      RUN(FAM_GEMM, (double)H * F * w, 2.0 * H * F * n, launch_gemm(s, f32, EPI_STORE, a));
     }
   }
 
   if (c.has_embed_and_head && p.head_ncols > 0) {
     const int hn = p.head_ncols, hc = hn * ns;
     RUN(FAM_NORM, hn * H * 8.0, 0,
-        launch_rmsnorm_pack(s, f32, m->x + (size_t)p.head_col0 * H, H, m->g_final, H, c.rms_eps, hn, m->Xp,
-                            hc, ns));
+        launch_rmsnorm_pack(s, f32, m->x + (size_t)p.head_col0 * H, H, m->rpart + (size_t)p.head_col0 * H, pending,
+                            pstride, m->g_final, H, c.rms_eps, hn, m->Xp, hc, ns));
     GemmArgs a{};
     a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = KTH; a.kts_per_split = KTH;
     a.Xp = m->Xp; a.NC = hc; a.ncols = hc; a.nsplit = ns; a.nseq = hn;
@@ -303,15 +311,20 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       RUN(FAM_ARGMAX, hn * V * 4.0, 0,
           launch_argmax(s, p.logits, p.logits_ld, V, hn, p.step_ptr, p.step_stride, m->am_val, m->am_idx,
                         p.next));
+  } else if (!c.has_embed_and_head && pending > 0) {
+    // hidden-state models return x itself: add the last projection's partials now
+    RUN(FAM_MISC, 0, 0, launch_fold_residual(s, m->x, m->rpart, pending, pstride, (size_t)n * H));
   }
   return NNC_OK;
 }
 
-// bf16 pieces per activation for a decode batch: exact (3) while the pieces of all
-// sequences fit one 16-column block, otherwise 2 (relative error <= 2^-17).
+// bf16 pieces per activation in decode: three, whose sum is the fp32 value to within
+// 2^-25 relative, so a batch of B sequences computes what B batch-1 steps compute.
+// (Two pieces, 2^-17, were measurably noisier: a bf16 K/V element that rounds the
+// other way perturbs everything downstream by ~1e-4 relative.)
 int decode_nsplit(const nnc_model* m, uint32_t batch) {
-  if (m->f32) return 1;
-  return batch <= 5 ? 3 : 2;
+  (void)batch;
+  return m->f32 ? 1 : 3;
 }
 
 int chunks_grid(uint32_t max_pos) {
@@ -541,6 +554,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
   ALLOC(m->qkv, float*, (size_t)MAX_COLS * (Dq + 2 * Dkv) * 4);
   ALLOC(m->Xp, void*, (size_t)MAX_COLS * H * w);
   ALLOC(m->Ap, void*, (size_t)MAX_COLS * std::max(Dq, F) * w);
+  ALLOC(m->rpart, float*, (size_t)MAX_KSPLIT * MAX_COLS * H * 4);
   ALLOC(m->partial, float*, (size_t)MAX_COLS * c.n_q_heads * m->max_chunks * 132 * 4);
   ALLOC(m->next, int32_t*, MAX_COLS * 4);
   m->token_log_steps = c.max_seq;
@@ -601,7 +615,7 @@ static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tok
   if (tokens)
     for (uint32_t i = 0; i < n; ++i)
       if (tokens[i] < 0 || (uint32_t)tokens[i] >= m->c.vocab) return fail(NNC_E_ARG, "token %d out of range", tokens[i]);
-  const int nsplit = m->f32 ? 1 : (m->opt_prefill_exact ? 2 : 1);
+  const int nsplit = m->f32 ? 1 : (m->opt_prefill_exact ? 3 : 1);
   const uint32_t chunk = MAX_COLS / nsplit;
   const size_t H = m->H();
   const uint32_t len0 = m->len[slot];

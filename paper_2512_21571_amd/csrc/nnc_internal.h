@@ -23,7 +23,7 @@ struct ColState {
   uint32_t pad[3];
 };
 
-enum Epilogue { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+enum Epilogue { EPI_STORE = 0, EPI_SWIGLU = 2 };
 
 // Skinny GEMM  Y[n, seq] = sum_k W[n, k] * X[k, seq]  over packed operands.
 //
@@ -51,9 +51,11 @@ struct GemmArgs {
   int ncols;  // used operand columns = nseq * nsplit
   int nsplit;
   int nseq;
-  // EPI_STORE: out[seq * ldo + n] = y.  EPI_RESID: out[seq * ldo + n] += y.
+  // EPI_STORE: out[kslice * split_stride + seq * ldo + n] = partial y of that k slice
+  // (one slice, split_stride unused, for the GEMMs whose consumer wants the full sum).
   float* out;
   long ldo;
+  long split_stride;
   // offset added to `out`, in floats, = *step_ptr * step_stride (greedy loop logits log)
   const uint32_t* step_ptr;
   long step_stride;
@@ -74,8 +76,11 @@ hipError_t launch_set_state(hipStream_t s, ColState* st, int ncols, const int32_
                             const uint32_t* slot, const uint32_t* pos, uint32_t step);
 hipError_t launch_embed(hipStream_t s, bool f32, const void* Ep, int H, const ColState* st,
                         int ncols, float* x);
-hipError_t launch_rmsnorm_pack(hipStream_t s, bool f32, const float* x, long ldx, const float* gain,
-                               int H, float eps, int ncols, void* Xp, int NC, int nsplit);
+hipError_t launch_rmsnorm_pack(hipStream_t s, bool f32, float* x, long ldx, const float* part, int nparts,
+                               long part_stride, const float* gain, int H, float eps, int ncols, void* Xp,
+                               int NC, int nsplit);
+hipError_t launch_fold_residual(hipStream_t s, float* x, const float* part, int nparts, long part_stride,
+                                size_t n);
 hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a);
 hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq, int nkv,
                                      const float* gq, const float* gk, float eps,

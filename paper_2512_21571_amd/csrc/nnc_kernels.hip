@@ -219,29 +219,59 @@ __device__ __forceinline__ void store_packed(void* Xp, int NC, int nsplit, int s
   }
 }
 
+// Before the norm, the pending output of the previous projection is added to the
+// residual stream: x += part[0] + part[1] + ... (k slices of that GEMM, fixed order),
+// and the updated x is written back.  part_seq0 is the column of `part` that
+// corresponds to blockIdx.x == 0 (the LM head norms a sub-range of the columns).
 template <bool F32>
-__global__ __launch_bounds__(256) void k_rmsnorm_pack(const float* __restrict__ x, long ldx,
-                                                      const float* __restrict__ gain, int H, float eps,
-                                                      void* __restrict__ Xp, int NC, int nsplit) {
+__global__ __launch_bounds__(256) void k_rmsnorm_pack(float* __restrict__ x, long ldx,
+                                                      const float* __restrict__ part, int nparts,
+                                                      long part_stride, const float* __restrict__ gain,
+                                                      int H, float eps, void* __restrict__ Xp, int NC,
+                                                      int nsplit) {
   __shared__ float sm[4];
   const int seq = blockIdx.x;
-  const float* xr = x + (size_t)seq * ldx;
+  float* xr = x + (size_t)seq * ldx;
   float ss = 0.f;
   for (int i = threadIdx.x; i < H; i += 256) {
-    const float v = xr[i];
+    float v = xr[i];
+    if (nparts > 0) {
+      float add = part[(size_t)seq * H + i];
+      for (int p = 1; p < nparts; ++p) add += part[(size_t)p * part_stride + (size_t)seq * H + i];
+      v += add;
+      xr[i] = v;
+    }
     ss += v * v;
   }
-  ss = block_sum_256(ss, sm);
+  ss = block_sum_256(ss, sm);  // also orders the writes above before the reads below
   const float r = 1.0f / sqrtf(ss / (float)H + eps);
   for (int i = threadIdx.x; i < H; i += 256) store_packed<F32>(Xp, NC, nsplit, seq, i, xr[i] * r * gain[i]);
 }
 
-hipError_t launch_rmsnorm_pack(hipStream_t s, bool f32, const float* x, long ldx, const float* gain,
-                               int H, float eps, int ncols, void* Xp, int NC, int nsplit) {
+hipError_t launch_rmsnorm_pack(hipStream_t s, bool f32, float* x, long ldx, const float* part, int nparts,
+                               long part_stride, const float* gain, int H, float eps, int ncols, void* Xp,
+                               int NC, int nsplit) {
   if (f32)
-    k_rmsnorm_pack<true><<<ncols, 256, 0, s>>>(x, ldx, gain, H, eps, Xp, NC, nsplit);
+    k_rmsnorm_pack<true><<<ncols, 256, 0, s>>>(x, ldx, part, nparts, part_stride, gain, H, eps, Xp, NC, nsplit);
   else
-    k_rmsnorm_pack<false><<<ncols, 256, 0, s>>>(x, ldx, gain, H, eps, Xp, NC, nsplit);
+    k_rmsnorm_pack<false><<<ncols, 256, 0, s>>>(x, ldx, part, nparts, part_stride, gain, H, eps, Xp, NC, nsplit);
+  return hipGetLastError();
+}
+
+// x += part[0] + part[1] + ... for n contiguous floats (all columns), fixed order.
+__global__ __launch_bounds__(256) void k_fold_residual(float* __restrict__ x, const float* __restrict__ part,
+                                                       int nparts, long part_stride, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    float add = part[i];
+    for (int p = 1; p < nparts; ++p) add += part[(size_t)p * part_stride + i];
+    x[i] += add;
+  }
+}
+
+hipError_t launch_fold_residual(hipStream_t s, float* x, const float* part, int nparts, long part_stride,
+                                size_t n) {
+  const unsigned grid = (unsigned)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+  k_fold_residual<<<grid ? grid : 1, 256, 0, s>>>(x, part, nparts, part_stride, n);
   return hipGetLastError();
 }
 
@@ -351,16 +381,9 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
       const int rt = o / (16 * nseq);
       const int rem = o - rt * 16 * nseq;
       const int seq = rem >> 4, row = rem & 15;
-      const float v = total(rt, row, seq);
-      float* dst = out + (size_t)seq * a.ldo + (tile0 + rt) * 16 + row;
-      if constexpr (EPI == EPI_STORE) {
-        *dst = v;
-      } else {
-        if (gridDim.y == 1)
-          *dst += v;
-        else
-          unsafeAtomicAdd(dst, v);
-      }
+      // each k slice stores its own partial sums: slice s goes to out + s * split_stride
+      out[(size_t)blockIdx.y * a.split_stride + (size_t)seq * a.ldo + (tile0 + rt) * 16 + row] =
+          total(rt, row, seq);
     }
   }
 }
@@ -387,7 +410,10 @@ static hipError_t gemm_dispatch_ncb(hipStream_t s, const GemmArgs& a) {
 }
 
 // RT (16-row tiles per workgroup) is 2 for SwiGLU and for matrices with many rows,
-// 1 for the narrow output projections, where more workgroups matter more.
+// 1 for the narrow output projections, where more workgroups matter more.  Those
+// also split k across workgroups; each slice stores its own partial result and the
+// consumer (k_rmsnorm_pack / k_fold_residual) adds the slices in a fixed order, so
+// results do not depend on scheduling.
 hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a) {
   if (a.ncols <= 0 || a.ncols > MAX_COLS || a.ncols > a.NC || a.nseq * a.nsplit != a.ncols ||
       a.kts_per_split <= 0 || a.n_tiles <= 0)
@@ -397,12 +423,9 @@ hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a) {
     if (a.n_tiles % 2 || a.kts_per_split < a.KT) return hipErrorInvalidValue;
     return f32 ? gemm_dispatch_ncb<true, EPI_SWIGLU, 2>(s, a) : gemm_dispatch_ncb<false, EPI_SWIGLU, 2>(s, a);
   }
-  if (epi == EPI_STORE) {
-    if (a.kts_per_split < a.KT) return hipErrorInvalidValue;
-    if (wide) return f32 ? gemm_dispatch_ncb<true, EPI_STORE, 2>(s, a) : gemm_dispatch_ncb<false, EPI_STORE, 2>(s, a);
-    return f32 ? gemm_dispatch_ncb<true, EPI_STORE, 1>(s, a) : gemm_dispatch_ncb<false, EPI_STORE, 1>(s, a);
-  }
-  return f32 ? gemm_dispatch_ncb<true, EPI_RESID, 1>(s, a) : gemm_dispatch_ncb<false, EPI_RESID, 1>(s, a);
+  if (epi != EPI_STORE) return hipErrorInvalidValue;
+  if (wide) return f32 ? gemm_dispatch_ncb<true, EPI_STORE, 2>(s, a) : gemm_dispatch_ncb<false, EPI_STORE, 2>(s, a);
+  return f32 ? gemm_dispatch_ncb<true, EPI_STORE, 1>(s, a) : gemm_dispatch_ncb<false, EPI_STORE, 1>(s, a);
 }
 
 // ---------------------------------------------------------------------------
