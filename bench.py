@@ -1,0 +1,153 @@
+#!/usr/bin/env python3
+"""Benchmark of the decoder hot path on one MI355X.
+
+One "step" = one whole pass of the hot path over one synthetic request of the
+configuration the metric is quoted on (Qwen3-0.6B-shaped, bf16 weights and KV cache,
+fp32 accumulation, batch 1): reset the KV slot, run the 128-token prompt, then 128
+greedy decode steps with the token fed back on the device.  The paper's metric is
+tokens/s over the decoding stage (Section 5, experimental setup); `value` is that,
+summed over the K timed steps, with weights and prompt already resident in HBM.
+
+Prints ONE JSON line (see the design doc for the meaning of `roofline` and `cpu_baseline`).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
+WORKLOADS = {
+    # name: (shape key, prompt tokens, decode steps)
+    "qwen3-0.6b-bf16-b1-p128-d128": ("qwen3-0.6b", 128, 128),
+    "qwen3-1.7b-bf16-b1-p512-d256": ("qwen3-1.7b", 512, 256),
+}
+
+
+def algorithmic_bytes_per_decode_step(shape, ctx_mean: float) -> float:
+    """Every weight element once per step, every cached K/V element once per step."""
+    w = 2 if shape.dtype == 1 else 4
+    per_layer = (shape.dq + 2 * shape.dkv) * shape.hidden + shape.hidden * shape.dq + 3 * shape.ffn * shape.hidden
+    weights = w * (shape.n_layers * per_layer + shape.vocab * shape.hidden)
+    kv = shape.n_layers * 2 * shape.dkv * w * ctx_mean
+    return float(weights + kv)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="qwen3-0.6b-bf16-b1-p128-d128", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no cross-GPU sharding or collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import synth
+    from paper_2512_21571_amd import binding as nnc
+
+    shape_key, T, S = WORKLOADS[args.workload]
+    shape = synth.SHAPES[shape_key]
+    blob = synth.make_blob(shape)
+    model = nnc.Model(shape, blob, 1, T + S)
+    prompt = synth.tokens(T, shape.vocab)
+    stream = model.stream
+
+    def one_pass(events=None):
+        model.kv_reset(0)
+        if events:
+            events[0].record(stream)
+        _, nxt = model.prefill(0, prompt, want_logits=False)
+        if events:
+            events[1].record(stream)
+        first = int(nxt.item())                    # the one host round trip of a request
+        if events:
+            events[2].record(stream)
+        toks, _ = model.decode_greedy([0], [first], S)
+        if events:
+            events[3].record(stream)
+        return toks
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        toks = one_pass(evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prefill_ms = sum(e[0].elapsed_time(e[1]) for e in evs)
+    decode_ms = sum(e[2].elapsed_time(e[3]) for e in evs)
+    decode_tok_s = args.steps * S / (decode_ms * 1e-3)
+    prefill_tok_s = args.steps * T / (prefill_ms * 1e-3)
+    ctx_mean = T + (S - 1) / 2.0 + 1
+    step_bytes = algorithmic_bytes_per_decode_step(shape, ctx_mean)
+    decode_ms_per_token = decode_ms / (args.steps * S)
+
+    # per-kernel durations: the same pass again, eager, every launch bracketed by HIP
+    # events on the model's stream (inside the library)
+    model.kv_reset(0)
+    _, nxt = model.prefill(0, prompt, want_logits=False)
+    first = int(nxt.item())
+    model.profile_begin()
+    model.decode_greedy([0], [first], S)
+    stats = model.profile_end()
+    dom = max(stats, key=lambda r: r["total_ms"])
+    per_launch_bytes = dom["bytes"] / dom["launches"]
+    avg_ms = dom["total_ms"] / dom["launches"]
+    achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom["name"], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "launches": dom["launches"], "avg_launch_us": round(avg_ms * 1e3, 3),
+                "bytes_per_launch": round(per_launch_bytes)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        o = oracle.from_shape(shape, blob, 1, T + S)
+        ctx0 = 16                                    # short prompt so the sample is mostly decode
+        _, t = o.prefill(0, prompt[:ctx0], oracle.ROUND_KV)
+        n, c0 = 0, time.perf_counter()
+        while n < S and time.perf_counter() - c0 < args.cpu_seconds:
+            _, t = o.step_token(0, t, oracle.ROUND_KV)
+            n += 1
+        dt = time.perf_counter() - c0
+        cpu = {"value": round(n / dt, 3), "unit": "tokens/s", "cores": oracle.get_threads(), "kind": "oracle",
+               "sample": f"{n} greedy decode steps of the same model after a {ctx0}-token prompt, fp64, "
+                         f"{oracle.get_threads()} OpenMP threads"}
+
+    out = {
+        "metric": "decode tokens/s + achieved HBM GB/s fraction; prefill tokens/s + MFMA util",
+        "value": round(decode_tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / args.steps, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": 1, "prompt_tokens": T, "decode_steps": S,
+                   "weights": "N(0,0.02) seeded, bf16", "kv_cache": "bf16"},
+        "decode_ms_per_token": round(decode_ms_per_token, 5),
+        "decode_hbm_frac_step": round(step_bytes / (decode_ms_per_token * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
+        "decode_algorithmic_bytes_per_step": round(step_bytes),
+        "prefill_tokens_per_s": round(prefill_tok_s, 1),
+        "prefill_ms": round(prefill_ms / args.steps, 4),
+        "roofline": roofline,
+        "kernels": [{"name": r["name"], "launches": r["launches"], "total_ms": round(r["total_ms"], 4)} for r in stats],
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -156,9 +156,15 @@ nnc_status nnc_kv_read(nnc_model *m, uint32_t layer, uint32_t slot, uint32_t whi
 /* Runtime switches. */
 typedef enum {
   NNC_OPT_GRAPH = 0,        /* 1 (default): replay decode steps as captured HIP graphs; 0: eager */
-  NNC_OPT_PREFILL_EXACT = 1 /* 1: prompt GEMMs keep fp32-grade activations (split-bf16
-                               operands); 0 (default for bf16 models): activations entering a
-                               prompt GEMM are rounded to bf16 once, as matrix-core operands */
+  NNC_OPT_PREFILL_EXACT = 1, /* 1 (default): prompt GEMMs keep fp32-grade activations (split-bf16
+                               operands); 0: activations entering a prompt GEMM are rounded to
+                               bf16 once, as matrix-core operands */
+  NNC_OPT_PERSISTENT = 2,   /* 1 (default): decode steps of bf16 models with batch <= 5 run in
+                               one resident kernel per call (all steps of nnc_decode_greedy in a
+                               single launch); 0: one kernel per stage */
+  NNC_OPT_STAGE_TRACE = 3   /* s + 1: the resident kernel stamps the 100 MHz wall clock at every
+                               stage boundary of decode step s of each following launch (read them
+                               with nnc_stage_trace); 0 (default): off */
 } nnc_option;
 nnc_status nnc_set_option(nnc_model *m, nnc_option opt, int32_t value);
 
@@ -177,6 +183,17 @@ typedef struct {
 } nnc_kernel_stat;
 nnc_status nnc_profile_begin(nnc_model *m);
 nnc_status nnc_profile_end(nnc_model *m, nnc_kernel_stat *out, uint32_t cap, uint32_t *n_out);
+
+/*
+ * Stage stamps of the last traced resident-kernel launch (see NNC_OPT_STAGE_TRACE), for
+ * tuning: host buffer out[workgroups][points] of 64-bit wall-clock ticks (10 ns each).
+ * Per layer 12 points: layer start, after the input norm, before/after barriers 1, 2, 3,
+ * after the post-attention norm, before/after barrier 4, before barrier 5; then LM-head
+ * start, before and after its barrier.  Synchronises the stream.  NNC_E_ARG if cap (in
+ * 64-bit words) is too small; NNC_E_STATE if tracing is off.
+ */
+nnc_status nnc_stage_trace(nnc_model *m, uint64_t *out, uint32_t cap, uint32_t *workgroups,
+                           uint32_t *points);
 
 /* Bytes of the canonical blob for a config (0 if the config is invalid). */
 uint64_t nnc_blob_bytes(const nnc_config *cfg);

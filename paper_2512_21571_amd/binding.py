@@ -13,13 +13,14 @@ from . import _build
 
 OK, E_ARG, E_CONFIG, E_BLOB, E_NOMEM, E_KV_FULL, E_DEVICE, E_STATE = range(8)
 F32, BF16 = 0, 1
-OPT_GRAPH, OPT_PREFILL_EXACT = 0, 1
+OPT_GRAPH, OPT_PREFILL_EXACT, OPT_PERSISTENT, OPT_STAGE_TRACE = 0, 1, 2, 3
 
 # every symbol include/nnc.h declares
 EXPORTS = [
     "nnc_model_create", "nnc_model_destroy", "nnc_prefill", "nnc_decode_step", "nnc_decode_greedy",
     "nnc_kv_reset", "nnc_slot_len", "nnc_prefill_hidden", "nnc_decode_step_hidden", "nnc_kv_read",
-    "nnc_set_option", "nnc_profile_begin", "nnc_profile_end", "nnc_blob_bytes", "nnc_last_error",
+    "nnc_set_option", "nnc_profile_begin", "nnc_profile_end", "nnc_stage_trace", "nnc_blob_bytes",
+    "nnc_last_error",
 ]
 
 
@@ -79,6 +80,7 @@ def lib():
             "nnc_set_option": (i32, [vp, i32, i32]),
             "nnc_profile_begin": (i32, [vp]),
             "nnc_profile_end": (i32, [vp, P(NncKernelStat), u32, P(u32)]),
+            "nnc_stage_trace": (i32, [vp, vp, u32, P(u32), P(u32)]),
             "nnc_blob_bytes": (ctypes.c_uint64, [P(NncConfig)]),
             "nnc_last_error": (ctypes.c_char_p, []),
         }
@@ -274,6 +276,14 @@ class Model:
 
     def set_option(self, opt: int, value: int):
         _check(lib().nnc_set_option(self.h, opt, value))
+
+    def stage_trace(self):
+        """[workgroups, points] uint64 wall-clock ticks (10 ns) of the traced decode step."""
+        cap = 1024 * (12 * self.cfg.n_layers + 3)
+        buf = np.zeros(cap, dtype=np.uint64)
+        nwg, npts = ctypes.c_uint32(), ctypes.c_uint32()
+        _check(lib().nnc_stage_trace(self.h, buf.ctypes.data, cap, ctypes.byref(nwg), ctypes.byref(npts)))
+        return buf[: nwg.value * npts.value].reshape(nwg.value, npts.value)
 
     # -- per-kernel event timing ---------------------------------------------------------
     def profile_begin(self):

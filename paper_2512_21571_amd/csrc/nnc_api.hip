@@ -85,8 +85,20 @@ struct nnc_model {
 
   std::vector<uint32_t> len;
 
+  // persistent decode kernel
+  bool mk_ok = false;
+  int mk_nwg = 0, mk_ks_o = 1, mk_ks_d = 1;
+  void* mk_layers = nullptr;
+  unsigned* mk_flags = nullptr;
+  unsigned* mk_error = nullptr;
+  float *mk_X0 = nullptr, *mk_X1 = nullptr, *mk_act = nullptr, *mk_opart = nullptr, *mk_amv = nullptr;
+  int32_t* mk_ami = nullptr;
+  unsigned long long* mk_trace = nullptr;
+  int mk_trace_step = -1;
+
   bool opt_graph = true;
   bool opt_prefill_exact = false;
+  bool opt_persistent = true;
   std::map<std::tuple<int, int, int>, hipGraphExec_t> graphs;
 
   bool profiling = false;
@@ -410,6 +422,38 @@ nnc_status greedy_step(nnc_model* m, uint32_t batch, int nsplit, int grid_chunks
   return NNC_OK;
 }
 
+bool use_persistent(const nnc_model* m, uint32_t batch) {
+  if (!m->mk_ok || !m->opt_persistent || m->profiling || batch > (uint32_t)MK_MAX_SEQS) return false;
+  MkPlan plan{};
+  plan.H = (int)m->H(); plan.nq = (int)m->c.n_q_heads; plan.F = (int)m->F(); plan.nseq = (int)batch;
+  plan.ks_o = m->mk_ks_o; plan.ks_d = m->mk_ks_d;
+  return mk_opnd_bytes(plan) <= 96 * 1024;  // activation operand + ~37 KiB of static LDS per workgroup
+}
+
+// n_steps decode steps of `batch` sequences in one resident kernel.  Column state must
+// have been set.  Tokens land in token_log [n_steps][batch].
+nnc_status persistent_steps(nnc_model* m, uint32_t batch, uint32_t n_steps, float* logits_out) {
+  const nnc_config& c = m->c;
+  MkPlan p{};
+  p.nwg = m->mk_nwg;
+  p.n_layers = (int)c.n_layers; p.H = (int)m->H(); p.nq = (int)c.n_q_heads; p.nkv = (int)c.n_kv_heads;
+  p.F = (int)m->F(); p.V = (int)m->V();
+  p.eps = c.rms_eps; p.max_seq = c.max_seq; p.max_chunks = m->max_chunks;
+  p.nseq = (int)batch; p.n_steps = (int)n_steps;
+  p.ks_o = m->mk_ks_o; p.ks_d = m->mk_ks_d;
+  MkBuffers b{};
+  b.layers = m->mk_layers; b.embed = m->embed; b.lm_head = m->lm_head; b.g_final = m->g_final; b.rope = m->rope;
+  b.flags = m->mk_flags; b.error = m->mk_error; b.st = m->st;
+  b.X0 = m->mk_X0; b.X1 = m->mk_X1; b.qkv = m->qkv; b.att = m->partial; b.opart = m->mk_opart;
+  b.act = m->mk_act; b.dpart = m->rpart; b.am_val = m->mk_amv; b.am_idx = m->mk_ami;
+  b.logits = logits_out; b.token_log = m->token_log;
+  b.trace = m->mk_trace_step >= 0 ? m->mk_trace : nullptr;
+  b.trace_step = m->mk_trace_step;
+  b.trace_points = mk_trace_points((int)c.n_layers);
+  HIP_TRY(launch_decode_persistent(m->stream, p, b));
+  return NNC_OK;
+}
+
 }  // namespace
 
 // =============================================================================
@@ -564,6 +608,47 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     ALLOC(m->am_val, float*, MAX_COLS * 64 * 4);
     ALLOC(m->am_idx, int32_t*, MAX_COLS * 64 * 4);
   }
+  // persistent decode kernel: per-layer pointer table, flags, exchange buffers
+  if (!m->f32 && c.has_embed_and_head && c.n_layers > 0 && H <= 4096) {
+    m->mk_nwg = prop.multiProcessorCount;
+    auto slices = [&](int n_tiles, int KT) {
+      int ks = m->mk_nwg / (n_tiles > 0 ? n_tiles : 1);
+      if (ks < 1) ks = 1;
+      while (ks > 1 && KT / ks < 8) --ks;          // at least one k tile per wave
+      while ((KT + ks - 1) / ks * 32 > 4096) ++ks;  // operand slice must fit LDS
+      return ks > 4 ? 4 : ks;  // the resident kernel adds at most four slices per consumer
+    };
+    m->mk_ks_o = slices((int)H / 16, (int)Dq / 32);
+    m->mk_ks_d = slices((int)H / 16, (int)F / 32);
+    MkPlan plan{};
+    plan.H = (int)H; plan.nq = (int)c.n_q_heads; plan.F = (int)F; plan.nseq = 1;
+    plan.ks_o = m->mk_ks_o; plan.ks_d = m->mk_ks_d;
+    if (mk_opnd_bytes(plan) <= 96 * 1024 && (F / 32 + m->mk_ks_d - 1) / m->mk_ks_d * 32 <= 4096 &&
+        (Dq / 32 + m->mk_ks_o - 1) / m->mk_ks_o * 32 <= 4096) {
+      const size_t lb = mk_layer_bytes();
+      std::vector<char> table(lb * c.n_layers);
+      for (uint32_t i = 0; i < c.n_layers; ++i) {
+        const LayerW& L = m->L[i];
+        mk_fill_layer(table.data() + lb * i, L.wqkv, L.wo, L.wgu, L.wd, L.g_in, L.g_q, L.g_k, L.g_post, L.kc, L.vc);
+      }
+      ALLOC(m->mk_layers, void*, table.size());
+      TRY_OR_BAIL(hipMemcpyAsync(m->mk_layers, table.data(), table.size(), hipMemcpyHostToDevice, s));
+      ALLOC(m->mk_flags, unsigned*, (size_t)m->mk_nwg * 32 * 4);
+      ALLOC(m->mk_error, unsigned*, 256);
+      TRY_OR_BAIL(hipMemsetAsync(m->mk_flags, 0, (size_t)m->mk_nwg * 32 * 4, s));
+      TRY_OR_BAIL(hipMemsetAsync(m->mk_error, 0, 256, s));
+      ALLOC(m->mk_X0, float*, (size_t)MK_MAX_SEQS * H * 4);
+      ALLOC(m->mk_X1, float*, (size_t)MK_MAX_SEQS * H * 4);
+      ALLOC(m->mk_act, float*, (size_t)MK_MAX_SEQS * F * 4);
+      ALLOC(m->mk_opart, float*, (size_t)MAX_KSPLIT * MK_MAX_SEQS * H * 4);
+      ALLOC(m->mk_amv, float*, (size_t)m->mk_nwg * MK_MAX_SEQS * 4);
+      ALLOC(m->mk_ami, int32_t*, (size_t)m->mk_nwg * MK_MAX_SEQS * 4);
+      ALLOC(m->mk_trace, unsigned long long*, (size_t)m->mk_nwg * mk_trace_points((int)c.n_layers) * 8);
+      TRY_OR_BAIL(hipMemsetAsync(m->mk_trace, 0, (size_t)m->mk_nwg * mk_trace_points((int)c.n_layers) * 8, s));
+      TRY_OR_BAIL(hipStreamSynchronize(s));  // table goes out of scope
+      m->mk_ok = true;
+    }
+  }
   m->len.assign(c.max_batch, 0);
   TRY_OR_BAIL(hipStreamSynchronize(s));
   (void)st;
@@ -602,6 +687,11 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
   switch (opt) {
     case NNC_OPT_GRAPH: m->opt_graph = value != 0; return NNC_OK;
     case NNC_OPT_PREFILL_EXACT: m->opt_prefill_exact = value != 0; return NNC_OK;
+    case NNC_OPT_PERSISTENT: m->opt_persistent = value != 0; return NNC_OK;
+    case NNC_OPT_STAGE_TRACE:
+      if (!m->mk_ok) return fail(NNC_E_STATE, "the resident decode kernel is not available for this model");
+      m->mk_trace_step = value - 1;
+      return NNC_OK;
   }
   return fail(NNC_E_ARG, "unknown option %d", (int)opt);
 }
@@ -676,6 +766,12 @@ nnc_status nnc_decode_step(nnc_model* m, const uint32_t* slots, const int32_t* t
   double kv_rows = 0;
   if (nnc_status st = set_decode_state(m, slots, tokens, batch, &max_pos, &kv_rows)) return st;
   const int nsplit = decode_nsplit(m, batch);
+  if (use_persistent(m, batch)) {
+    if (nnc_status st = persistent_steps(m, batch, 1, logits_out)) return st;
+    if (next_out) HIP_TRY(hipMemcpyAsync(next_out, m->token_log, batch * 4, hipMemcpyDeviceToDevice, m->stream));
+    for (uint32_t i = 0; i < batch; ++i) m->len[slots[i]] += 1;
+    return NNC_OK;
+  }
   if (logits_out) {
     Pass p;
     p.ncols = (int)batch;
@@ -709,6 +805,12 @@ nnc_status nnc_decode_greedy(nnc_model* m, const uint32_t* slots, const int32_t*
   double kv_rows = 0;
   if (nnc_status st = set_decode_state(m, slots, first_tokens, batch, &max_pos, &kv_rows)) return st;
   const int nsplit = decode_nsplit(m, batch);
+  if (use_persistent(m, batch)) {
+    if (nnc_status st = persistent_steps(m, batch, n_steps, logits_out)) return st;
+    HIP_TRY(hipMemcpyAsync(tokens_out, m->token_log, (size_t)n_steps * batch * 4, hipMemcpyDeviceToDevice, m->stream));
+    for (uint32_t i = 0; i < batch; ++i) m->len[slots[i]] += n_steps;
+    return NNC_OK;
+  }
   for (uint32_t step = 0; step < n_steps; ++step) {
     const int gc = chunks_grid(max_pos + step);
     if (logits_out) {
@@ -761,6 +863,18 @@ nnc_status nnc_kv_read(nnc_model* m, uint32_t layer, uint32_t slot, uint32_t whi
   const size_t slot_elems = (size_t)m->c.n_kv_heads * m->c.max_seq * 128;
   const char* base = static_cast<const char*>(which ? m->L[layer].vc : m->L[layer].kc) + slot * slot_elems * m->esz();
   HIP_TRY(launch_kv_read(m->stream, m->f32, base, m->c.max_seq, (int)m->c.n_kv_heads, pos0, n, out));
+  return NNC_OK;
+}
+
+nnc_status nnc_stage_trace(nnc_model* m, uint64_t* out, uint32_t cap, uint32_t* workgroups, uint32_t* points) {
+  if (!m || !out || !workgroups || !points) return fail(NNC_E_ARG, "NULL argument");
+  if (!m->mk_ok || m->mk_trace_step < 0) return fail(NNC_E_STATE, "stage tracing is off");
+  const uint32_t np = (uint32_t)mk_trace_points((int)m->c.n_layers);
+  if ((uint64_t)cap < (uint64_t)m->mk_nwg * np) return fail(NNC_E_ARG, "trace buffer too small");
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  HIP_TRY(hipMemcpy(out, m->mk_trace, (size_t)m->mk_nwg * np * 8, hipMemcpyDeviceToHost));
+  *workgroups = (uint32_t)m->mk_nwg;
+  *points = np;
   return NNC_OK;
 }
 

@@ -145,21 +145,29 @@ def test_greedy_loop_graph_and_eager_agree_with_oracle(nnc):
         _, t = o.step_token(0, t, fl)
         want.append(t)
     outs = {}
-    for mode in (1, 0):
+    # (persistent kernel, graph replay) x on/off: resident kernel, per-stage kernels in a
+    # captured graph, per-stage kernels launched eagerly
+    for mode in ((1, 1), (0, 1), (0, 0)):
         g.kv_reset(0)
-        g.set_option(nnc.OPT_GRAPH, mode)
+        g.set_option(nnc.OPT_PERSISTENT, mode[0])
+        g.set_option(nnc.OPT_GRAPH, mode[1])
         g.prefill(0, toks, want_logits=False)
         got, _ = g.decode_greedy([0], [first], 120)
         outs[mode] = got.cpu().numpy()[:, 0]
         assert g.slot_len(0) == 140
-    assert np.array_equal(outs[1], outs[0])
-    assert np.array_equal(outs[1], np.array(want))
+        assert np.array_equal(outs[mode], np.array(want)), mode
     # replay through the captured graph a second time, with eager work in between
     g.kv_reset(0)
     g.set_option(nnc.OPT_GRAPH, 1)
     g.prefill(0, toks, want_logits=False)
     again, _ = g.decode_greedy([0], [first], 120)
-    assert np.array_equal(again.cpu().numpy()[:, 0], outs[1])
+    assert np.array_equal(again.cpu().numpy()[:, 0], outs[(0, 1)])
+    # and the resident kernel again after the per-stage path has run
+    g.kv_reset(0)
+    g.set_option(nnc.OPT_PERSISTENT, 1)
+    g.prefill(0, toks, want_logits=False)
+    again, _ = g.decode_greedy([0], [first], 120)
+    assert np.array_equal(again.cpu().numpy()[:, 0], outs[(1, 1)])
 
 
 def test_reset_replay_and_error_paths(nnc):
