@@ -159,8 +159,8 @@ typedef enum {
   NNC_OPT_PREFILL_EXACT = 1, /* 1 (default): prompt GEMMs keep fp32-grade activations (split-bf16
                                operands); 0: activations entering a prompt GEMM are rounded to
                                bf16 once, as matrix-core operands */
-  NNC_OPT_PERSISTENT = 2,   /* 1 (default): decode steps of bf16 models with batch <= 5 run in
-                               one resident kernel per call (all steps of nnc_decode_greedy in a
+  NNC_OPT_PERSISTENT = 2,   /* 1 (default): batch-1 decode steps of bf16 models run in one
+                               resident kernel per call (all steps of nnc_decode_greedy in a
                                single launch); 0: one kernel per stage */
   NNC_OPT_STAGE_TRACE = 3   /* s + 1: the resident kernel stamps the 100 MHz wall clock at every
                                stage boundary of decode step s of each following launch (read them
@@ -187,9 +187,10 @@ nnc_status nnc_profile_end(nnc_model *m, nnc_kernel_stat *out, uint32_t cap, uin
 /*
  * Stage stamps of the last traced resident-kernel launch (see NNC_OPT_STAGE_TRACE), for
  * tuning: host buffer out[workgroups][points] of 64-bit wall-clock ticks (10 ns each).
- * Per layer 12 points: layer start, after the input norm, before/after barriers 1, 2, 3,
- * after the post-attention norm, before/after barrier 4, before barrier 5; then LM-head
- * start, before and after its barrier.  Synchronises the stream.  NNC_E_ARG if cap (in
+ * Per layer 8 points: layer start, QKV operand ready, q|k|v published, attention partials
+ * published, attention block output published, gate/up operand ready, activations
+ * published, MLP output published; then LM-head operand ready, per-workgroup winners
+ * published, token known.  Synchronises the stream.  NNC_E_ARG if cap (in
  * 64-bit words) is too small; NNC_E_STATE if tracing is off.
  */
 nnc_status nnc_stage_trace(nnc_model *m, uint64_t *out, uint32_t cap, uint32_t *workgroups,

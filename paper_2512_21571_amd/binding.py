@@ -279,7 +279,7 @@ class Model:
 
     def stage_trace(self):
         """[workgroups, points] uint64 wall-clock ticks (10 ns) of the traced decode step."""
-        cap = 1024 * (12 * self.cfg.n_layers + 3)
+        cap = 1024 * (8 * self.cfg.n_layers + 3)
         buf = np.zeros(cap, dtype=np.uint64)
         nwg, npts = ctypes.c_uint32(), ctypes.c_uint32()
         _check(lib().nnc_stage_trace(self.h, buf.ctypes.data, cap, ctypes.byref(nwg), ctypes.byref(npts)))

@@ -85,14 +85,14 @@ struct nnc_model {
 
   std::vector<uint32_t> len;
 
-  // persistent decode kernel
+  // resident decode kernel
   bool mk_ok = false;
   int mk_nwg = 0, mk_ks_o = 1, mk_ks_d = 1;
+  unsigned mk_tag = 1;  // next unused exchange tag
   void* mk_layers = nullptr;
-  unsigned* mk_flags = nullptr;
   unsigned* mk_error = nullptr;
-  float *mk_X0 = nullptr, *mk_X1 = nullptr, *mk_act = nullptr, *mk_opart = nullptr, *mk_amv = nullptr;
-  int32_t* mk_ami = nullptr;
+  void *mk_xq = nullptr, *mk_xatt = nullptr, *mk_xop = nullptr, *mk_xact = nullptr, *mk_xdp = nullptr,
+       *mk_xamv = nullptr, *mk_xami = nullptr;
   unsigned long long* mk_trace = nullptr;
   int mk_trace_step = -1;
 
@@ -423,34 +423,47 @@ nnc_status greedy_step(nnc_model* m, uint32_t batch, int nsplit, int grid_chunks
 }
 
 bool use_persistent(const nnc_model* m, uint32_t batch) {
-  if (!m->mk_ok || !m->opt_persistent || m->profiling || batch > (uint32_t)MK_MAX_SEQS) return false;
-  MkPlan plan{};
-  plan.H = (int)m->H(); plan.nq = (int)m->c.n_q_heads; plan.F = (int)m->F(); plan.nseq = (int)batch;
-  plan.ks_o = m->mk_ks_o; plan.ks_d = m->mk_ks_d;
-  return mk_opnd_bytes(plan) <= 96 * 1024;  // activation operand + ~37 KiB of static LDS per workgroup
+  return m->mk_ok && m->opt_persistent && !m->profiling && batch == 1;
 }
 
-// n_steps decode steps of `batch` sequences in one resident kernel.  Column state must
-// have been set.  Tokens land in token_log [n_steps][batch].
-nnc_status persistent_steps(nnc_model* m, uint32_t batch, uint32_t n_steps, float* logits_out) {
+// n_steps greedy decode steps of one sequence in one resident kernel, starting from
+// `token` at the slot's current length.  Tokens land in token_log [n_steps].
+nnc_status persistent_steps(nnc_model* m, uint32_t slot, int32_t token, uint32_t n_steps, float* logits_out) {
   const nnc_config& c = m->c;
   MkPlan p{};
   p.nwg = m->mk_nwg;
   p.n_layers = (int)c.n_layers; p.H = (int)m->H(); p.nq = (int)c.n_q_heads; p.nkv = (int)c.n_kv_heads;
   p.F = (int)m->F(); p.V = (int)m->V();
   p.eps = c.rms_eps; p.max_seq = c.max_seq; p.max_chunks = m->max_chunks;
-  p.nseq = (int)batch; p.n_steps = (int)n_steps;
+  p.tok0 = token; p.pos0 = m->len[slot]; p.slot = slot;
+  p.n_steps = (int)n_steps;
+  p.tag_base = m->mk_tag;
   p.ks_o = m->mk_ks_o; p.ks_d = m->mk_ks_d;
+  {
+    // gate/up pairs start at workgroup 0; output-projection units end at the last workgroup,
+    // attention units sit before them, down-projection units before those
+    const int o_units = (int)(m->H() / 16) * p.ks_o, d_units = (int)(m->H() / 16) * p.ks_d;
+    const int att_units = (int)c.n_kv_heads * ((int)(m->len[slot] + n_steps - 1) / ATT_CHUNK + 1);
+    auto wrap = [&](int v) { return ((v % p.nwg) + p.nwg) % p.nwg; };
+    p.off_o = wrap(p.nwg - o_units);
+    p.off_att = wrap(p.nwg - o_units - att_units);
+    p.off_d = wrap(p.nwg - o_units - att_units - d_units);
+  }
+  const uint64_t tags = (uint64_t)n_steps * mk_tags_per_step((int)c.n_layers);
+  if ((uint64_t)m->mk_tag + tags >= 0xffffffffull)
+    return fail(NNC_E_STATE, "exchange tags exhausted (after ~2^32 / %u decode steps); recreate the model",
+                mk_tags_per_step((int)c.n_layers));
   MkBuffers b{};
   b.layers = m->mk_layers; b.embed = m->embed; b.lm_head = m->lm_head; b.g_final = m->g_final; b.rope = m->rope;
-  b.flags = m->mk_flags; b.error = m->mk_error; b.st = m->st;
-  b.X0 = m->mk_X0; b.X1 = m->mk_X1; b.qkv = m->qkv; b.att = m->partial; b.opart = m->mk_opart;
-  b.act = m->mk_act; b.dpart = m->rpart; b.am_val = m->mk_amv; b.am_idx = m->mk_ami;
+  b.error = m->mk_error;
+  b.xq = m->mk_xq; b.xatt = m->mk_xatt; b.xop = m->mk_xop; b.xact = m->mk_xact; b.xdp = m->mk_xdp;
+  b.xamv = m->mk_xamv; b.xami = m->mk_xami;
   b.logits = logits_out; b.token_log = m->token_log;
   b.trace = m->mk_trace_step >= 0 ? m->mk_trace : nullptr;
   b.trace_step = m->mk_trace_step;
   b.trace_points = mk_trace_points((int)c.n_layers);
-  HIP_TRY(launch_decode_persistent(m->stream, p, b));
+  HIP_TRY(launch_decode_resident(m->stream, p, b));
+  m->mk_tag += (unsigned)tags;
   return NNC_OK;
 }
 
@@ -608,23 +621,18 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     ALLOC(m->am_val, float*, MAX_COLS * 64 * 4);
     ALLOC(m->am_idx, int32_t*, MAX_COLS * 64 * 4);
   }
-  // persistent decode kernel: per-layer pointer table, flags, exchange buffers
-  if (!m->f32 && c.has_embed_and_head && c.n_layers > 0 && H <= 4096) {
-    m->mk_nwg = prop.multiProcessorCount;
-    auto slices = [&](int n_tiles, int KT) {
-      int ks = m->mk_nwg / (n_tiles > 0 ? n_tiles : 1);
-      if (ks < 1) ks = 1;
-      while (ks > 1 && KT / ks < 8) --ks;          // at least one k tile per wave
-      while ((KT + ks - 1) / ks * 32 > 4096) ++ks;  // operand slice must fit LDS
-      return ks > 4 ? 4 : ks;  // the resident kernel adds at most four slices per consumer
-    };
-    m->mk_ks_o = slices((int)H / 16, (int)Dq / 32);
-    m->mk_ks_d = slices((int)H / 16, (int)F / 32);
+  // resident decode kernel: per-layer pointer table, exchange buffers
+  if (!m->f32 && c.has_embed_and_head && c.n_layers > 0 && H <= 4096 && (c.n_q_heads / c.n_kv_heads) % 2 == 0) {
+    const int qkv_tiles = (int)((Dq + 2 * Dkv) / 16);
+    m->mk_nwg = prop.multiProcessorCount < qkv_tiles ? prop.multiProcessorCount : qkv_tiles;
+    // k slices of the narrow projections: 32 k tiles per slice (all of it prefetched, 8 loads
+    // per lane), at most 4 slices (a consumer adds at most four partial vectors)
+    m->mk_ks_o = (int)std::min<size_t>(4, (Dq / 32 + 31) / 32);
+    m->mk_ks_d = (int)std::min<size_t>(4, (F / 32 + 31) / 32);
     MkPlan plan{};
-    plan.H = (int)H; plan.nq = (int)c.n_q_heads; plan.F = (int)F; plan.nseq = 1;
+    plan.H = (int)H; plan.nq = (int)c.n_q_heads; plan.F = (int)F;
     plan.ks_o = m->mk_ks_o; plan.ks_d = m->mk_ks_d;
-    if (mk_opnd_bytes(plan) <= 96 * 1024 && (F / 32 + m->mk_ks_d - 1) / m->mk_ks_d * 32 <= 4096 &&
-        (Dq / 32 + m->mk_ks_o - 1) / m->mk_ks_o * 32 <= 4096) {
+    if (m->mk_ks_o <= 4 && m->mk_ks_d <= 4 && mk_opnd_bytes(plan) <= 96 * 1024) {
       const size_t lb = mk_layer_bytes();
       std::vector<char> table(lb * c.n_layers);
       for (uint32_t i = 0; i < c.n_layers; ++i) {
@@ -633,18 +641,24 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
       }
       ALLOC(m->mk_layers, void*, table.size());
       TRY_OR_BAIL(hipMemcpyAsync(m->mk_layers, table.data(), table.size(), hipMemcpyHostToDevice, s));
-      ALLOC(m->mk_flags, unsigned*, (size_t)m->mk_nwg * 32 * 4);
-      ALLOC(m->mk_error, unsigned*, 256);
-      TRY_OR_BAIL(hipMemsetAsync(m->mk_flags, 0, (size_t)m->mk_nwg * 32 * 4, s));
-      TRY_OR_BAIL(hipMemsetAsync(m->mk_error, 0, 256, s));
-      ALLOC(m->mk_X0, float*, (size_t)MK_MAX_SEQS * H * 4);
-      ALLOC(m->mk_X1, float*, (size_t)MK_MAX_SEQS * H * 4);
-      ALLOC(m->mk_act, float*, (size_t)MK_MAX_SEQS * F * 4);
-      ALLOC(m->mk_opart, float*, (size_t)MAX_KSPLIT * MK_MAX_SEQS * H * 4);
-      ALLOC(m->mk_amv, float*, (size_t)m->mk_nwg * MK_MAX_SEQS * 4);
-      ALLOC(m->mk_ami, int32_t*, (size_t)m->mk_nwg * MK_MAX_SEQS * 4);
-      ALLOC(m->mk_trace, unsigned long long*, (size_t)m->mk_nwg * mk_trace_points((int)c.n_layers) * 8);
-      TRY_OR_BAIL(hipMemsetAsync(m->mk_trace, 0, (size_t)m->mk_nwg * mk_trace_points((int)c.n_layers) * 8, s));
+      auto zeroed = [&](void*& ptr, size_t bytes) -> hipError_t {
+        ptr = dev_alloc(m, bytes);
+        if (!ptr) return hipErrorOutOfMemory;
+        return hipMemsetAsync(ptr, 0, bytes, s);
+      };
+      void* err = nullptr;
+      TRY_OR_BAIL(zeroed(err, 256));
+      m->mk_error = static_cast<unsigned*>(err);
+      TRY_OR_BAIL(zeroed(m->mk_xq, (Dq + 2 * Dkv) * 8));
+      TRY_OR_BAIL(zeroed(m->mk_xatt, (size_t)c.n_q_heads * m->max_chunks * 132 * 8));
+      TRY_OR_BAIL(zeroed(m->mk_xop, 4 * H * 8));
+      TRY_OR_BAIL(zeroed(m->mk_xact, F * 8));
+      TRY_OR_BAIL(zeroed(m->mk_xdp, 4 * H * 8));
+      TRY_OR_BAIL(zeroed(m->mk_xamv, (size_t)m->mk_nwg * 8));
+      TRY_OR_BAIL(zeroed(m->mk_xami, (size_t)m->mk_nwg * 8));
+      void* tr = nullptr;
+      TRY_OR_BAIL(zeroed(tr, (size_t)m->mk_nwg * mk_trace_points((int)c.n_layers) * 8));
+      m->mk_trace = static_cast<unsigned long long*>(tr);
       TRY_OR_BAIL(hipStreamSynchronize(s));  // table goes out of scope
       m->mk_ok = true;
     }
@@ -767,7 +781,7 @@ nnc_status nnc_decode_step(nnc_model* m, const uint32_t* slots, const int32_t* t
   if (nnc_status st = set_decode_state(m, slots, tokens, batch, &max_pos, &kv_rows)) return st;
   const int nsplit = decode_nsplit(m, batch);
   if (use_persistent(m, batch)) {
-    if (nnc_status st = persistent_steps(m, batch, 1, logits_out)) return st;
+    if (nnc_status st = persistent_steps(m, slots[0], tokens[0], 1, logits_out)) return st;
     if (next_out) HIP_TRY(hipMemcpyAsync(next_out, m->token_log, batch * 4, hipMemcpyDeviceToDevice, m->stream));
     for (uint32_t i = 0; i < batch; ++i) m->len[slots[i]] += 1;
     return NNC_OK;
@@ -806,7 +820,7 @@ nnc_status nnc_decode_greedy(nnc_model* m, const uint32_t* slots, const int32_t*
   if (nnc_status st = set_decode_state(m, slots, first_tokens, batch, &max_pos, &kv_rows)) return st;
   const int nsplit = decode_nsplit(m, batch);
   if (use_persistent(m, batch)) {
-    if (nnc_status st = persistent_steps(m, batch, n_steps, logits_out)) return st;
+    if (nnc_status st = persistent_steps(m, slots[0], first_tokens[0], n_steps, logits_out)) return st;
     HIP_TRY(hipMemcpyAsync(tokens_out, m->token_log, (size_t)n_steps * batch * 4, hipMemcpyDeviceToDevice, m->stream));
     for (uint32_t i = 0; i < batch; ++i) m->len[slots[i]] += n_steps;
     return NNC_OK;

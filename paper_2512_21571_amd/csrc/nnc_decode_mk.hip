@@ -1,23 +1,35 @@
-// Persistent whole-step decode kernel for small batches (bf16 models).
+// Resident whole-step decode kernel for batch 1 (bf16 models).
 //
 // Batch-1 decode of a 0.6B-shaped model moves ~1.2 GB per token: 150 us at HBM
 // speed, spread over ~140 dependent matmul / attention stages of about 1 us each.
-// Run as separate kernels, every stage costs a launch-drain-launch bubble of
-// several microseconds, which is where the time goes; the paper observes the same
-// thing on CPUs, where fork-join barriers of a threading runtime limit scaling and
-// a static partition with cheap synchronisation wins (Section 5.2, architectural
-// discussion).  Here one resident grid (one workgroup per compute unit) runs whole
-// decode steps: every stage is statically partitioned over the workgroups, the
-// stages are separated by a grid-wide barrier built from per-workgroup flags, and
-// the weights of the next stage are already in flight (prefetched into registers)
-// while a stage finishes and the barrier is crossed.
+// Run as separate kernels, every stage pays a launch-drain-launch bubble of several
+// microseconds, and that is where the time goes.  The paper observes the same on
+// CPUs: fork-join barriers of a threading runtime limit scaling, and a static
+// partition with cheap, deterministic communication wins (Section 5.2,
+// architectural discussion).  Here one resident grid (at most one workgroup per
+// compute unit) runs all the decode steps of a call:
 //
-// Coherence protocol (8 XCDs, one L2 each, no cross-L2 coherence for ordinary
-// accesses): everything one workgroup writes for another to read is written and
-// read with relaxed agent-scope atomic accesses, which go to the memory side.  A
-// barrier is: wait for this wave's stores to be acknowledged, workgroup barrier,
-// publish flag = epoch, poll everyone's flag.  No cache write-back / invalidate
-// is needed and none is issued (they cost ~10 us per barrier on this part).
+//   * every stage is statically partitioned over the workgroups;
+//   * there are no grid barriers.  Whatever one workgroup produces for others is
+//     written as 64-bit words (fp32 value, 32-bit tag) with relaxed agent-scope
+//     atomic stores, which go to the memory side past the per-XCD L2s; the tag
+//     names the (step, layer, stage) that produced it.  A consumer simply loads
+//     the words it needs (relaxed agent-scope atomic loads) and repeats until
+//     every tag is the one it expects.  Synchronisation and data transfer are
+//     one and the same memory round trip (~1.7 us for an all-to-all of a hidden
+//     vector among 256 workgroups, measured), and no cache write-back or
+//     invalidate is ever issued (those cost ~10 us each on this part);
+//   * the weights of a workgroup's next stage are loaded into registers while the
+//     current stage finishes and the exchange is in flight;
+//   * the residual stream never goes through memory: every workgroup keeps its own
+//     copy in registers and adds the exchanged projection outputs to it.
+//
+// Why a producer may overwrite an exchange buffer without asking: each buffer is
+// rewritten one layer later at the same stage, and before that can happen its
+// readers have produced something the writer (transitively) waited for.  This
+// needs every workgroup to own at least one QKV tile per layer, so the grid is
+// min(compute units, QKV tiles).
+//
 // Weights, gains, the rotary table and cached K/V rows older than the current
 // step are immutable during a launch and use ordinary loads.
 #include <cstring>
@@ -28,13 +40,17 @@ namespace nnc {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned long long u64;
 
 namespace {
 
-constexpr int MK_THREADS = 512;
+// One wave per SIMD: each wave may then use the whole 512-entry register file, which holds the
+// prefetched weights of the next stage (64 KiB per workgroup) without any spilling.
+constexpr int MK_THREADS = 256;
 constexpr int MK_WAVES = MK_THREADS / 64;
-constexpr unsigned MK_SPIN_MAX = 1u << 21;
-constexpr int MK_PF = 8;  // 16-byte weight loads per lane kept in flight across a barrier
+constexpr unsigned MK_SPIN_MAX = 1u << 20;
+constexpr int MK_PF = 8;      // prefetched 16-byte weight loads per lane and 16-row tile (32 KiB per workgroup)
+constexpr int MK_MAX_KS = 4;  // k slices of a narrow projection
 
 // ---- memory-side accesses ----------------------------------------------------
 __device__ __forceinline__ unsigned ld_u32(const unsigned* p) {
@@ -43,22 +59,30 @@ __device__ __forceinline__ unsigned ld_u32(const unsigned* p) {
 __device__ __forceinline__ void st_u32(unsigned* p, unsigned v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float ld_f(const float* p) {
-  return __uint_as_float(ld_u32(reinterpret_cast<const unsigned*>(p)));
+__device__ __forceinline__ u64 ld_t(const u64* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void st_f(float* p, float v) {
-  st_u32(reinterpret_cast<unsigned*>(p), __float_as_uint(v));
+__device__ __forceinline__ void st_t(u64* p, float v, unsigned tag) {
+  __hip_atomic_store(p, (u64)__float_as_uint(v) | ((u64)tag << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float2 ld_f2(const float* p) {
-  const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
-                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
+__device__ __forceinline__ float t_val(u64 w) { return __uint_as_float((unsigned)w); }
+__device__ __forceinline__ bool t_ok(u64 w, unsigned tag) { return (unsigned)(w >> 32) == tag; }
+
+// Returns v, but the compiler must assume it changed.  Used on lane / thread indices at the
+// top of each stage helper so that the dozens of per-load address offsets are recomputed
+// where they are used instead of being hoisted out of the layer loop, where they would
+// occupy (and spill) registers that the in-flight weight prefetch needs.
+__device__ __forceinline__ int opaque(int v) {
+  asm volatile("" : "+v"(v));
+  return v;
 }
-__device__ __forceinline__ void st_f2(float* p, float2 v) {
-  const unsigned long long u = (unsigned long long)__float_as_uint(v.x) |
-                               ((unsigned long long)__float_as_uint(v.y) << 32);
-  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), u, __ATOMIC_RELAXED,
-                     __HIP_MEMORY_SCOPE_AGENT);
+
+// Workgroup barrier that orders LDS traffic only: outstanding global loads (the
+// weight prefetch) stay in flight across it.
+__device__ __forceinline__ void wg_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 __device__ __forceinline__ uint32_t bf16_bits(float f) {
@@ -97,23 +121,27 @@ struct MkArgs {
   const float* g_final;
   const float2* rope;
   uint32_t max_seq;
-  unsigned* flags;  // one per workgroup, 128 bytes apart
   unsigned* error;
-  const ColState* st;
-  int nseq, n_steps;
+  int tok0;             // first token
+  uint32_t pos0, slot;  // position of the first step, KV slot
+  int n_steps;
+  unsigned tag_base;
   int ks_o, ks_d;  // k slices of the output / down projections
-  float* X0;       // residual stream, two buffers [nseq][H]
-  float* X1;
-  float* qkv;      // [nseq][Dq + 2 Dkv] raw projections
-  float* att;      // attention partials [nseq][nq][max_chunks][132]
+  // Unit u of a stage runs on workgroup (u + offset) % workgroups.  The offsets keep the
+  // few-unit stages (attention, output projection, down projection) on different
+  // workgroups, so that a workgroup's weight prefetch for its next role is issued early.
+  int off_att, off_o, off_d;
+  // exchange buffers of (value, tag) words
+  u64* xq;    // [Dq + 2 Dkv] raw q | k | v
+  u64* xatt;  // [nq][max_chunks][132] attention partials: 128 sums, max, sum
   int max_chunks;
-  float* opart;    // [ks_o][nseq][H]
-  float* act;      // [nseq][F]
-  float* dpart;    // [ks_d][nseq][H]
-  float* am_val;   // [workgroups][nseq]
-  int32_t* am_idx;
-  float* logits;   // [n_steps][nseq][V] or NULL
-  int32_t* token_log;  // [n_steps][nseq]
+  u64* xop;   // [ks_o][H]
+  u64* xact;  // [F]
+  u64* xdp;   // [ks_d][H]
+  u64* xamv;  // [workgroups] best logit
+  u64* xami;  // [workgroups] its index
+  float* logits;       // [n_steps][V] or NULL
+  int32_t* token_log;  // [n_steps]
   unsigned long long* trace;  // [workgroups][trace_points] wall-clock stamps of one step, or NULL
   int trace_step, trace_points;
 };
@@ -121,56 +149,48 @@ struct MkArgs {
 namespace {
 
 struct Smem {
-  float red[MK_WAVES][2][256];  // per-wave accumulator tiles
+  union {
+    float red[MK_WAVES][2][256];   // GEMM: per-wave accumulator tiles
+    float ared[MK_WAVES][4][128];  // attention: per-wave value sums
+  };
   float wsum[MK_WAVES];
   float sc[4][ATT_CHUNK];
   float qs[4][128];
   float knew[128], vnew[128];
   float att_m[4], att_l[4];
-  float ared[MK_WAVES][4][128];
-  float bestv[MK_WAVES][8];
-  int besti[MK_WAVES][8];
-  int tok[8];
+  float bestv[MK_WAVES];
+  int besti[MK_WAVES];
+  int tok;
+  int abort;
 };
 
-// Grid-wide barrier.  Returns false (for the whole workgroup) if it timed out or
-// another workgroup reported an error; the caller then leaves the kernel.
-__device__ __forceinline__ bool grid_barrier(const MkArgs& a, unsigned& epoch) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores are acknowledged
-  __syncthreads();
-  ++epoch;
-  const unsigned nwg = gridDim.x;
-  if (threadIdx.x == 0) st_u32(a.flags + blockIdx.x * 32, epoch);
-  bool ok = true;
-  for (unsigned w = threadIdx.x; w < nwg; w += MK_THREADS) {
-    unsigned spins = 0;
-    while ((int)(ld_u32(a.flags + w * 32) - epoch) < 0) {
-      if (++spins > MK_SPIN_MAX || ((spins & 1023u) == 0 && ld_u32(a.error))) {
-        st_u32(a.error, 1u);
-        ok = false;
-        break;
-      }
-    }
-  }
-  return __syncthreads_and(ok);
+// Called by a thread whose wait ran out (or that saw another workgroup give up).
+__device__ __forceinline__ void give_up(const MkArgs& a, Smem& sm) {
+  st_u32(a.error, 1u);
+  sm.abort = 1;
+}
+__device__ __forceinline__ bool spin_over(const MkArgs& a, unsigned& spins) {
+  ++spins;
+  return spins > MK_SPIN_MAX || ((spins & 255u) == 0 && ld_u32(a.error) != 0);
 }
 
 __device__ __forceinline__ float block_sum(float v, Smem& sm) {
   v = wave_sum(v);
-  __syncthreads();
+  wg_sync();
   if ((threadIdx.x & 63) == 0) sm.wsum[threadIdx.x >> 6] = v;
-  __syncthreads();
+  wg_sync();
   float t = 0.f;
 #pragma unroll
   for (int w = 0; w < MK_WAVES; ++w) t += sm.wsum[w];
   return t;
 }
 
-// Write the bf16 pieces of the pair (v.x, v.y) = activations k, k+1 (k even) of
-// sequence `seq` into the packed LDS operand (k is relative to the operand's start).
-__device__ __forceinline__ void put_pair(uint4* opnd, int NC, int seq, int k, float2 v) {
+// bf16 pieces of the pair (v.x, v.y) = activations k, k+1 (k even, relative to the
+// operand's first k) into the packed LDS operand: 4 columns of 16 bytes per 8 k
+// (three pieces and one unused column).
+__device__ __forceinline__ void put_pair(uint4* opnd, int k, float2 v) {
   float rx = v.x, ry = v.y;
-  uint32_t* base = reinterpret_cast<uint32_t*>(opnd + (size_t)(k >> 3) * NC + seq * 3) + ((k & 7) >> 1);
+  uint32_t* base = reinterpret_cast<uint32_t*>(opnd + (size_t)(k >> 3) * 4) + ((k & 7) >> 1);
 #pragma unroll
   for (int s = 0; s < 3; ++s) {
     const uint32_t bx = bf16_bits(rx), by = bf16_bits(ry);
@@ -180,132 +200,46 @@ __device__ __forceinline__ void put_pair(uint4* opnd, int NC, int seq, int k, fl
   }
 }
 
+// Prefetched weights of one GEMM unit: MK_PF loads per lane for each of its RT tiles.
+template <int RT>
 struct Pf {
-  uint4 v[MK_PF];
+  uint4 v[MK_PF * RT];
 };
 
-constexpr int MK_MAX_KS = 4;  // k slices of a narrow projection (partial vectors a consumer adds)
-
-// Pairs (k, k+1) owned by a thread: k = 2 * (tid + MK_THREADS * j), j < NP (H <= 1024 NP).
-// xv[j] = [X] + sum of `ksd` slices of d + sum of `kso` slices of o, every load issued
-// before the first use so that the memory-side round trips overlap.
-template <int NP>
-__device__ __forceinline__ void gather_resid(float2 (&xv)[NP], int H, const float* X, const float* d, int ksd,
-                                             const float* o, int kso, long pstride) {
-  float2 tx[NP], td[NP][MK_MAX_KS], to[NP][MK_MAX_KS];
-#pragma unroll
-  for (int j = 0; j < NP; ++j) {
-    const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
-    if (k < H) {
-      if (X) tx[j] = ld_f2(X + k);
-#pragma unroll
-      for (int p = 0; p < MK_MAX_KS; ++p)
-        if (p < ksd) td[j][p] = ld_f2(d + (size_t)p * pstride + k);
-#pragma unroll
-      for (int p = 0; p < MK_MAX_KS; ++p)
-        if (p < kso) to[j][p] = ld_f2(o + (size_t)p * pstride + k);
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < NP; ++j) {
-    const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
-    if (k < H) {
-      float2 v = X ? tx[j] : xv[j];
-      if (ksd > 0) {
-        float2 add = td[j][0];
-#pragma unroll
-        for (int p = 1; p < MK_MAX_KS; ++p)
-          if (p < ksd) {
-            add.x += td[j][p].x;
-            add.y += td[j][p].y;
-          }
-        v.x += add.x;
-        v.y += add.y;
-      }
-      if (kso > 0) {
-        float2 add = to[j][0];
-#pragma unroll
-        for (int p = 1; p < MK_MAX_KS; ++p)
-          if (p < kso) {
-            add.x += to[j][p].x;
-            add.y += to[j][p].y;
-          }
-        v.x += add.x;
-        v.y += add.y;
-      }
-      xv[j] = v;
-    }
-  }
-}
-
-// Row `r` of the packed embedding, pairs owned by this thread.
-template <int NP>
-__device__ __forceinline__ void gather_embed(float2 (&xv)[NP], int H, const uint4* embed, int r) {
-  const int KTH = H / 32;
-#pragma unroll
-  for (int j = 0; j < NP; ++j) {
-    const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
-    xv[j] = make_float2(0.f, 0.f);
-    if (k < H) {
-      const size_t e = (((size_t)(r >> 4) * KTH + (k >> 5)) * 64 + (r & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
-      const uint32_t two = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint16_t*>(embed) + e);
-      xv[j] = make_float2(bf16_to_f32(two & 0xffffu), bf16_to_f32(two >> 16));
-    }
-  }
-}
-
-// RMSNorm of the gathered row and packing as the GEMM operand of sequence b.
-template <int NP>
-__device__ __forceinline__ void norm_pack(Smem& sm, uint4* opnd, int NC, int b, int H, float eps,
-                                          const float2 (&xv)[NP], const float* gain) {
-  float ss = 0.f;
-#pragma unroll
-  for (int j = 0; j < NP; ++j) ss += xv[j].x * xv[j].x + xv[j].y * xv[j].y;  // unowned pairs are zero
-  ss = block_sum(ss, sm);
-  const float r = 1.0f / sqrtf(ss / (float)H + eps);
-#pragma unroll
-  for (int j = 0; j < NP; ++j) {
-    const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
-    if (k < H) {
-      const float2 gg = *reinterpret_cast<const float2*>(gain + k);
-      put_pair(opnd, NC, b, k, make_float2(xv[j].x * r * gg.x, xv[j].y * r * gg.y));
-    }
-  }
-}
-
-// Issue the first MK_PF weight loads of a GEMM unit (same order gemm_unit consumes them).
+// Issue the first MK_PF * RT weight loads of a GEMM unit (same order gemm_unit consumes them).
 template <int RT>
-__device__ __forceinline__ void pf_issue(Pf& pf, const uint4* __restrict__ W, size_t tile0, int KT, int kt_begin,
+__device__ __forceinline__ void pf_issue(Pf<RT>& pf, const uint4* __restrict__ W, size_t tile0, int KT, int kt_begin,
                                          int kt_end) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int tid = opaque(threadIdx.x);
+  const int wave = tid >> 6, lane = tid & 63;
 #pragma unroll
-  for (int j = 0; j < MK_PF; ++j) {
+  for (int j = 0; j < MK_PF * RT; ++j) {
     const int kt = kt_begin + wave + MK_WAVES * (j / RT);
     const int rt = j % RT;
     pf.v[j] = kt < kt_end ? W[((tile0 + rt) * KT + kt) * 64 + lane] : uint4{0, 0, 0, 0};
   }
 }
 
-// One GEMM unit: RT adjacent 16-row tiles x k tiles [kt_begin, kt_end), the eight
-// waves taking k tiles round-robin.  The operand in LDS starts at k tile `opnd_kt0`.
-// Result: red[wave][rt][256] holds every wave's partial tile; caller synchronises.
+// One GEMM unit: RT adjacent 16-row tiles x k tiles [kt_begin, kt_end), the
+// waves taking k tiles round-robin; the operand in LDS starts at k tile opnd_kt0.
+// Every wave leaves its partial tile in red[wave][rt]; the caller synchronises.
 template <int RT, bool USE_PF>
 __device__ __forceinline__ void gemm_unit(Smem& sm, const uint4* __restrict__ W, size_t tile0, int KT, int kt_begin,
-                                          int kt_end, const Pf& pf, const uint4* opnd, int opnd_kt0, int NC,
-                                          int ncols) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+                                          int kt_end, const Pf<RT>& pf, const uint4* opnd, int opnd_kt0) {
+  const int tid = opaque(threadIdx.x);
+  const int wave = tid >> 6, lane = tid & 63;
   const int c16 = lane & 15, g = lane >> 4;
-  const bool colok = c16 < ncols;
+  const bool colok = c16 < 3;
   f32x4 acc[RT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  constexpr int U = MK_PF / RT;  // k tiles per group
+  constexpr int U = MK_PF;  // k tiles per group
   auto consume = [&](int kt0, const uint4 (&av)[U][RT]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int kt = kt0 + MK_WAVES * u;
       uint4 bv = uint4{0, 0, 0, 0};
-      if (kt < kt_end && colok) bv = opnd[((size_t)(kt - opnd_kt0) * 4 + g) * NC + c16];
+      if (kt < kt_end && colok) bv = opnd[((size_t)(kt - opnd_kt0) * 4 + g) * 4 + c16];
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
         acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av[u][rt]),
@@ -314,7 +248,6 @@ __device__ __forceinline__ void gemm_unit(Smem& sm, const uint4* __restrict__ W,
   };
   int kt0 = kt_begin + wave;
   if constexpr (USE_PF) {
-    // the first group was loaded before the preceding barrier
     uint4 av[U][RT];
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -340,14 +273,14 @@ __device__ __forceinline__ void gemm_unit(Smem& sm, const uint4* __restrict__ W,
     for (int i = 0; i < 4; ++i) sm.red[wave][rt][i * 64 + lane] = acc[rt][i];
 }
 
-// Sum of the eight waves' partial tiles and of the three bf16 pieces for output
-// (rt, row, seq); call after __syncthreads().
-__device__ __forceinline__ float tile_total(const Smem& sm, int rt, int row, int seq) {
+// Sum of the waves' partial tiles and of the three bf16 pieces for output row
+// `row` of tile rt; call after wg_sync().  Accumulator element i of lane l is output
+// row (l / 16) * 4 + i, operand column l % 16.
+__device__ __forceinline__ float tile_total(const Smem& sm, int rt, int row) {
   float v = 0.f;
 #pragma unroll
   for (int s = 0; s < 3; ++s) {
-    const int col = seq * 3 + s;
-    const int idx = (row & 3) * 64 + (row >> 2) * 16 + col;
+    const int idx = (row & 3) * 64 + (row >> 2) * 16 + s;
     float t = 0.f;
 #pragma unroll
     for (int w = 0; w < MK_WAVES; ++w) t += sm.red[w][rt][idx];
@@ -356,538 +289,618 @@ __device__ __forceinline__ float tile_total(const Smem& sm, int rt, int row, int
   return v;
 }
 
+// x[j] += sum over `ks` slices of the exchanged vector `buf` ([ks][H] tagged words), for
+// the pairs k = 2 * (tid + MK_THREADS * j) this thread owns.  Loads are repeated until
+// every word carries `tag`.
+template <int NP>
+__device__ __forceinline__ void add_exchanged(const MkArgs& a, Smem& sm, float2 (&x)[NP], int H, const u64* buf, int ks,
+                                              unsigned tag) {
+  unsigned spins = 0;
+  const int tid = opaque(threadIdx.x);
+  for (;;) {
+    u64 w[NP][MK_MAX_KS][2];
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+      const int k = 2 * (tid + MK_THREADS * j);
+      if (k < H) {
+#pragma unroll
+        for (int p = 0; p < MK_MAX_KS; ++p)
+          if (p < ks) {
+            w[j][p][0] = ld_t(buf + (size_t)p * H + k);
+            w[j][p][1] = ld_t(buf + (size_t)p * H + k + 1);
+          }
+      }
+    }
+    bool ok = true;
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+      const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
+      if (k < H) {
+#pragma unroll
+        for (int p = 0; p < MK_MAX_KS; ++p)
+          if (p < ks) ok = ok && t_ok(w[j][p][0], tag) && t_ok(w[j][p][1], tag);
+      }
+    }
+    if (ok) {
+#pragma unroll
+      for (int j = 0; j < NP; ++j) {
+        const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
+        if (k < H) {
+          float2 add = make_float2(t_val(w[j][0][0]), t_val(w[j][0][1]));
+#pragma unroll
+          for (int p = 1; p < MK_MAX_KS; ++p)
+            if (p < ks) {
+              add.x += t_val(w[j][p][0]);
+              add.y += t_val(w[j][p][1]);
+            }
+          x[j].x += add.x;
+          x[j].y += add.y;
+        }
+      }
+      return;
+    }
+    if (spin_over(a, spins)) {
+      give_up(a, sm);
+      return;
+    }
+  }
+}
+
+// Row r of the packed embedding matrix, pairs owned by this thread.
+template <int NP>
+__device__ __forceinline__ void gather_embed(float2 (&x)[NP], int H, const uint4* embed, int r) {
+  const int KTH = H / 32;
+#pragma unroll
+  for (int j = 0; j < NP; ++j) {
+    const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
+    x[j] = make_float2(0.f, 0.f);
+    if (k < H) {
+      const size_t e = (((size_t)(r >> 4) * KTH + (k >> 5)) * 64 + (r & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
+      const uint32_t two = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint16_t*>(embed) + e);
+      x[j] = make_float2(bf16_to_f32(two & 0xffffu), bf16_to_f32(two >> 16));
+    }
+  }
+}
+
+// RMSNorm of the row held in x and packing as the GEMM operand (k = 0 .. H).
+template <int NP>
+__device__ __forceinline__ void norm_pack(Smem& sm, uint4* opnd, int H, float eps, const float2 (&x)[NP],
+                                          const float* gain) {
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < NP; ++j) ss += x[j].x * x[j].x + x[j].y * x[j].y;  // unowned pairs are zero
+  ss = block_sum(ss, sm);
+  const float r = 1.0f / sqrtf(ss / (float)H + eps);
+#pragma unroll
+  for (int j = 0; j < NP; ++j) {
+    const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
+    if (k < H) {
+      const float2 gg = *reinterpret_cast<const float2*>(gain + k);
+      put_pair(opnd, k, make_float2(x[j].x * r * gg.x, x[j].y * r * gg.y));
+    }
+  }
+}
+
 }  // namespace
 
-// GH = query heads sharing one kv head that a workgroup handles together (nq/nkv).
-// NP = (k, k+1) pairs of a hidden-state row per thread: hidden <= 1024 * NP.
+// GH = query heads sharing one kv head that a workgroup handles together (divides nq/nkv).
+// NP = (k, k+1) pairs of a hidden-state row per thread: hidden <= 2 * MK_THREADS * NP.
 template <int GH, int NP>
-__global__ __launch_bounds__(MK_THREADS, 1) void k_decode_persistent(MkArgs a) {
+__global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
   extern __shared__ uint4 opnd[];  // packed activation operand of the current GEMM stage
   __shared__ Smem sm;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nwg = gridDim.x, wg = blockIdx.x;
-  const int H = a.H, F = a.F, V = a.V, nq = a.nq, nkv = a.nkv, nseq = a.nseq;
+  const int H = a.H, F = a.F, V = a.V, nq = a.nq, nkv = a.nkv;
   const int Dq = nq * 128, Dkv = nkv * 128, Nqkv = Dq + 2 * Dkv;
   const int KTH = H / 32, KTQ = Dq / 32, KTF = F / 32;
-  const int NC = nseq == 1 ? 4 : 16, ncols = nseq * 3;
   const int G = nq / nkv;
 
   if (ld_u32(a.error)) return;
-  unsigned epoch = ld_u32(a.flags + wg * 32);  // all flags are equal between launches
+  if (tid == 0) sm.abort = 0;
+  wg_sync();
 
   // static partition of every stage
   const int qkv_tiles = Nqkv / 16, o_tiles = H / 16, gu_pairs = F / 16, v_tiles = V / 16;
   const int kts_o = (KTQ + a.ks_o - 1) / a.ks_o, kts_d = (KTF + a.ks_d - 1) / a.ks_d;
   const int o_units = o_tiles * a.ks_o, d_units = o_tiles * a.ks_d;
-  const long pstride = (long)nseq * H;
+  const int att_units = nkv * a.max_chunks;
+  const unsigned tags_per_step = 5u * (unsigned)a.n_layers + 1u;
 
-  // optional stage trace: thread 0 stamps the 100 MHz wall clock at every stage boundary
+  // optional stage trace: thread 0 stamps the 100 MHz wall clock at stage boundaries
   int tp = 0;
   auto stamp = [&](int step) {
     if (a.trace && tid == 0 && step == a.trace_step && tp < a.trace_points)
       a.trace[(size_t)wg * a.trace_points + tp++] = wall_clock64();
   };
 
-  // Cached K and V rows of one attention unit (64 positions of one kv head): two rows of
-  // each per lane, loaded as soon as the unit is known; only the step's own new row,
-  // which does not exist yet, is excluded (it comes from LDS later).
-  const int att_units = nseq * nkv * a.max_chunks;
-  auto kv_issue = [&](const MkLayer& L, int u, int step, uint4 (&kreg)[2], uint4 (&vreg)[2]) {
-    const int chunk = u % a.max_chunks;
-    const int kvh = (u / a.max_chunks) % nkv;
-    const int b = u / (a.max_chunks * nkv);
-    const uint32_t pos = a.st->pos[b] + step, slot = a.st->slot[b];
-    const size_t cbase = ((size_t)slot * nkv + kvh) * a.max_seq * 128;
-#pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const uint32_t j = (uint32_t)chunk * ATT_CHUNK + it * 32 + wave * 4 + (lane >> 4);
-      kreg[it] = vreg[it] = uint4{0, 0, 0, 0};
-      if (j < pos) {
-        kreg[it] = *reinterpret_cast<const uint4*>(L.kc + cbase + (size_t)j * 128 + (lane & 15) * 8);
-        vreg[it] = *reinterpret_cast<const uint4*>(L.vc + cbase + (size_t)j * 128 + (lane & 15) * 8);
-      }
-    }
-  };
-  uint4 kpf[2], vpf[2];
+  // this workgroup's first unit in the stages that are placed with an offset
+  const int wg_att = (wg + nwg - a.off_att) % nwg, wg_o = (wg + nwg - a.off_o) % nwg,
+            wg_d = (wg + nwg - a.off_d) % nwg;
 
-  Pf pf;
-  // prefetch for the very first stage (layer 0 QKV)
-  if (wg < qkv_tiles) pf_issue<1>(pf, a.layers[0].wqkv, (size_t)wg, KTH, 0, KTH);
+  // Prefetched weights of this workgroup's first unit in each GEMM stage.  They are issued
+  // right after a stage's input has arrived (the waits return in order behind them, so a
+  // prefetch must never be issued just before a wait): stages 3 and 4 after the stage-1
+  // wait, stage 5 and the next layer's stage 1 after the stage-4 wait.
+  Pf<1> pf1, pf3, pf5;
+  Pf<2> pf4;
+  if (wg < qkv_tiles) pf_issue<1>(pf1, a.layers[0].wqkv, (size_t)wg, KTH, 0, KTH);
+
+  float2 x[NP];  // this workgroup's copy of the residual stream (pairs owned by the thread)
+  int tok = a.tok0;
 
   for (int step = 0; step < a.n_steps; ++step) {
-    float* Xa = a.X0;
-    float* Xb = a.X1;
+    const uint32_t pos = a.pos0 + step;
+    const unsigned t_step = a.tag_base + (unsigned)step * tags_per_step;
     for (int li = 0; li < a.n_layers; ++li) {
       const MkLayer L = a.layers[li];
-      stamp(step);
+      const unsigned t_q = t_step + 5u * li, t_att = t_q + 1, t_op = t_q + 2, t_act = t_q + 3, t_dp = t_q + 4;
+      stamp(step);  // 0: layer start
 
-      // ================= stage 1: input norm + QKV projection =================
-      // x = (layer 0 ? embedding row : Xa + down-projection slices of the previous layer)
-      for (int b = 0; b < nseq; ++b) {
-        float2 xv[NP];
-        if (li == 0) {
-          gather_embed(xv, H, a.embed, step == 0 ? a.st->tok[b] : sm.tok[b]);
-        } else {
-#pragma unroll
-          for (int j = 0; j < NP; ++j) xv[j] = make_float2(0.f, 0.f);
-          gather_resid(xv, H, Xa + (size_t)b * H, a.dpart + (size_t)b * H, a.ks_d, nullptr, 0, pstride);
-        }
-        norm_pack(sm, opnd, NC, b, H, a.eps, xv, L.g_in);
+      // ============ stage 1: residual update + input norm + QKV projection ============
+      if (li == 0)
+        gather_embed<NP>(x, H, a.embed, tok);
+      else
+        add_exchanged<NP>(a, sm, x, H, a.xdp, a.ks_d, t_dp - 5u);
+      if (wg_o < o_units) {
+        const int to = wg_o / a.ks_o, so = wg_o % a.ks_o;
+        pf_issue<1>(pf3, L.wo, (size_t)to, KTQ, so * kts_o, min(KTQ, (so + 1) * kts_o));
       }
-      stamp(step);
-      __syncthreads();
+      if (wg < gu_pairs) pf_issue<2>(pf4, L.wgu, (size_t)wg * 2, KTH, 0, KTH);
+      norm_pack<NP>(sm, opnd, H, a.eps, x, L.g_in);
+      wg_sync();
+      if (sm.abort) return;
+      stamp(step);  // 1: operand ready
       for (int t = wg; t < qkv_tiles; t += nwg) {
         if (t == wg)
-          gemm_unit<1, true>(sm, L.wqkv, (size_t)t, KTH, 0, KTH, pf, opnd, 0, NC, ncols);
+          gemm_unit<1, true>(sm, L.wqkv, (size_t)t, KTH, 0, KTH, pf1, opnd, 0);
         else
-          gemm_unit<1, false>(sm, L.wqkv, (size_t)t, KTH, 0, KTH, pf, opnd, 0, NC, ncols);
-        __syncthreads();
-        if (tid < 16 * nseq) {
-          const int seq = tid >> 4, row = tid & 15;
-          st_f(a.qkv + (size_t)seq * Nqkv + t * 16 + row, tile_total(sm, 0, row, seq));
-        }
-        __syncthreads();
+          gemm_unit<1, false>(sm, L.wqkv, (size_t)t, KTH, 0, KTH, pf1, opnd, 0);
+        wg_sync();
+        if (tid < 16) st_t(a.xq + t * 16 + tid, tile_total(sm, 0, tid), t_q);
+        wg_sync();
       }
-      // next GEMM stage with weights: output projection (stage 3)
-      if (wg < o_units) {
-        const int t = wg / a.ks_o, s = wg % a.ks_o;
-        pf_issue<1>(pf, L.wo, (size_t)t, KTQ, s * kts_o, min(KTQ, (s + 1) * kts_o));
-      }
-      if (wg < att_units) kv_issue(L, wg, step, kpf, vpf);
-      stamp(step);
-      if (!grid_barrier(a, epoch)) return;
-      stamp(step);
+      stamp(step);  // 2: q | k | v published
 
-      // ================= stage 2: QK-norm + RoPE + KV append + attention partials ==========
-      {
-        const int units = att_units;
-        for (int u = wg; u < units; u += nwg) {
-          const int chunk = u % a.max_chunks;
-          const int kvh = (u / a.max_chunks) % nkv;
-          const int b = u / (a.max_chunks * nkv);
-          const uint32_t pos = a.st->pos[b] + step, slot = a.st->slot[b];
-          const uint32_t j0 = (uint32_t)chunk * ATT_CHUNK;
-          if (j0 > pos) continue;  // uniform per workgroup
-          uint4 kreg[2], vreg[2];
-          if (u == wg) {
+      // ============ stage 2: QK-norm + RoPE + KV append + attention partials ============
+      for (int u = wg_att; u < att_units; u += nwg) {
+        const int chunk = u % a.max_chunks, kvh = u / a.max_chunks;
+        const uint32_t j0 = (uint32_t)chunk * ATT_CHUNK;
+        if (j0 > pos) continue;  // uniform per workgroup
+        const bool owns_new = pos - j0 < ATT_CHUNK;
+        const size_t cbase = ((size_t)a.slot * nkv + kvh) * a.max_seq * 128;
+        const int c16 = lane & 15, jj = lane >> 4;
+        // cached rows of the chunk: ATT_IT K and V rows per lane group, loaded up front
+        constexpr int ATT_IT = ATT_CHUNK / (4 * MK_WAVES);
+        uint4 kreg[ATT_IT], vreg[ATT_IT];
 #pragma unroll
-            for (int it = 0; it < 2; ++it) {
-              kreg[it] = kpf[it];
-              vreg[it] = vpf[it];
-            }
-          } else {
-            kv_issue(L, u, step, kreg, vreg);
+        for (int it = 0; it < ATT_IT; ++it) {
+          const uint32_t j = j0 + it * (4 * MK_WAVES) + wave * 4 + jj;
+          kreg[it] = vreg[it] = uint4{0, 0, 0, 0};
+          if (j < pos) {
+            kreg[it] = *reinterpret_cast<const uint4*>(L.kc + cbase + (size_t)j * 128 + c16 * 8);
+            vreg[it] = *reinterpret_cast<const uint4*>(L.vc + cbase + (size_t)j * 128 + c16 * 8);
           }
-          const bool owns_new = pos - j0 < ATT_CHUNK;
-          const size_t cbase = ((size_t)slot * nkv + kvh) * a.max_seq * 128;
-          const float* qrow = a.qkv + (size_t)b * Nqkv;
-          for (int hg = 0; hg < G; hg += GH) {
-            const int head0 = kvh * G + hg;
-            __syncthreads();
-            // waves 0..GH-1: q heads; wave GH: new k row; wave GH+1: new v row
-            if (wave < GH + 2 && (wave < GH || (owns_new && hg == 0))) {
-              const float* src = wave < GH ? qrow + (size_t)(head0 + wave) * 128
-                                           : qrow + Dq + (size_t)(wave == GH ? 0 : Dkv) + (size_t)kvh * 128;
-              float x0 = ld_f(src + lane), x1 = ld_f(src + lane + 64);
-              if (wave <= GH) {
-                const float ss = wave_sum(x0 * x0 + x1 * x1);
-                const float r = 1.0f / sqrtf(ss * (1.0f / 128.0f) + a.eps);
-                const float* gg = wave < GH ? L.g_q : L.g_k;
-                x0 = x0 * r * gg[lane];
-                x1 = x1 * r * gg[lane + 64];
-                const float2 cs = a.rope[(size_t)pos * 64 + lane];
-                const float r0 = x0 * cs.x - x1 * cs.y, r1 = x1 * cs.x + x0 * cs.y;
-                x0 = r0;
-                x1 = r1;
-              }
-              if (wave < GH) {
-                sm.qs[wave][lane] = x0;
-                sm.qs[wave][lane + 64] = x1;
-              } else {
-                const uint32_t b0 = bf16_bits(x0), b1 = bf16_bits(x1);
-                uint16_t* dst = (wave == GH ? L.kc : L.vc) + cbase + (size_t)pos * 128;
-                // 16-bit stores cannot be atomic accesses; pair lanes into 32-bit memory-side stores
-                const uint32_t n0 = __shfl_down(b0, 1, 64), n1 = __shfl_down(b1, 1, 64);
-                if ((lane & 1) == 0) {
-                  st_u32(reinterpret_cast<unsigned*>(dst + lane), b0 | (n0 << 16));
-                  st_u32(reinterpret_cast<unsigned*>(dst + lane + 64), b1 | (n1 << 16));
-                }
-                float* keep = wave == GH ? sm.knew : sm.vnew;
-                keep[lane] = bf16_to_f32(b0);
-                keep[lane + 64] = bf16_to_f32(b1);
+        }
+        for (int hg = 0; hg < G; hg += GH) {
+          const int head0 = kvh * G + hg;
+          wg_sync();
+          // roles 0..GH-1: q heads; role GH: the step's k row; role GH+1: its v row
+          for (int role = wave; role < GH + 2; role += MK_WAVES) {
+            if (role >= GH && !(owns_new && hg == 0)) continue;
+            const u64* src = role < GH ? a.xq + (size_t)(head0 + role) * 128
+                                       : a.xq + Dq + (size_t)(role == GH ? 0 : Dkv) + (size_t)kvh * 128;
+            u64 w0, w1;
+            unsigned spins = 0;
+            for (;;) {
+              w0 = ld_t(src + lane);
+              w1 = ld_t(src + lane + 64);
+              if (t_ok(w0, t_q) && t_ok(w1, t_q)) break;
+              if (spin_over(a, spins)) {
+                give_up(a, sm);
+                break;
               }
             }
-            __syncthreads();
-            const int c16 = lane & 15, jj = lane >> 4;
-            float q[GH][8];
-#pragma unroll
-            for (int h = 0; h < GH; ++h)
-#pragma unroll
-              for (int e = 0; e < 8; ++e) q[h][e] = sm.qs[h][c16 * 8 + e];
-            // scores
-#pragma unroll
-            for (int it = 0; it < ATT_CHUNK / 32; ++it) {
-              const int jl = it * 32 + wave * 4 + jj;
-              const uint32_t j = j0 + jl;
-              float kv[8];
-#pragma unroll
-              for (int e = 0; e < 8; ++e) kv[e] = 0.f;
-              if (j < pos) {
-                const uint4 x = kreg[it];
-                kv[0] = __uint_as_float(x.x << 16); kv[1] = __uint_as_float(x.x & 0xffff0000u);
-                kv[2] = __uint_as_float(x.y << 16); kv[3] = __uint_as_float(x.y & 0xffff0000u);
-                kv[4] = __uint_as_float(x.z << 16); kv[5] = __uint_as_float(x.z & 0xffff0000u);
-                kv[6] = __uint_as_float(x.w << 16); kv[7] = __uint_as_float(x.w & 0xffff0000u);
-              } else if (j == pos) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) kv[e] = sm.knew[c16 * 8 + e];
+            float x0 = t_val(w0), x1 = t_val(w1);
+            if (role <= GH) {
+              const float ss = wave_sum(x0 * x0 + x1 * x1);
+              const float r = 1.0f / sqrtf(ss * (1.0f / 128.0f) + a.eps);
+              const float* gg = role < GH ? L.g_q : L.g_k;
+              x0 = x0 * r * gg[lane];
+              x1 = x1 * r * gg[lane + 64];
+              const float2 cs = a.rope[(size_t)pos * 64 + lane];
+              const float r0 = x0 * cs.x - x1 * cs.y, r1 = x1 * cs.x + x0 * cs.y;
+              x0 = r0;
+              x1 = r1;
+            }
+            if (role < GH) {
+              sm.qs[role][lane] = x0;
+              sm.qs[role][lane + 64] = x1;
+            } else {
+              const uint32_t b0 = bf16_bits(x0), b1 = bf16_bits(x1);
+              uint16_t* dst = (role == GH ? L.kc : L.vc) + cbase + (size_t)pos * 128;
+              // memory-side 32-bit stores (two bf16 each): other workgroups read this row next step
+              const uint32_t n0 = __shfl_down(b0, 1, 64), n1 = __shfl_down(b1, 1, 64);
+              if ((lane & 1) == 0) {
+                st_u32(reinterpret_cast<unsigned*>(dst + lane), b0 | (n0 << 16));
+                st_u32(reinterpret_cast<unsigned*>(dst + lane + 64), b1 | (n1 << 16));
               }
+              float* keep = role == GH ? sm.knew : sm.vnew;
+              keep[lane] = bf16_to_f32(b0);
+              keep[lane + 64] = bf16_to_f32(b1);
+            }
+          }
+          wg_sync();
+          if (sm.abort) return;
+          float q[GH][8];
+#pragma unroll
+          for (int h = 0; h < GH; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) q[h][e] = sm.qs[h][c16 * 8 + e];
+          // scores s[h][j] = <q_h, K_j> / sqrt(128)
+#pragma unroll
+          for (int it = 0; it < ATT_IT; ++it) {
+            const int jl = it * (4 * MK_WAVES) + wave * 4 + jj;
+            const uint32_t j = j0 + jl;
+            float kv[8];
+            const uint4 xk = kreg[it];
+            kv[0] = __uint_as_float(xk.x << 16); kv[1] = __uint_as_float(xk.x & 0xffff0000u);
+            kv[2] = __uint_as_float(xk.y << 16); kv[3] = __uint_as_float(xk.y & 0xffff0000u);
+            kv[4] = __uint_as_float(xk.z << 16); kv[5] = __uint_as_float(xk.z & 0xffff0000u);
+            kv[6] = __uint_as_float(xk.w << 16); kv[7] = __uint_as_float(xk.w & 0xffff0000u);
+            if (j == pos) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) kv[e] = sm.knew[c16 * 8 + e];
+            }
+#pragma unroll
+            for (int h = 0; h < GH; ++h) {
+              float d = 0.f;
+#pragma unroll
+              for (int e = 0; e < 8; ++e) d += q[h][e] * kv[e];
+              d += __shfl_xor(d, 1, 64);
+              d += __shfl_xor(d, 2, 64);
+              d += __shfl_xor(d, 4, 64);
+              d += __shfl_xor(d, 8, 64);
+              if (c16 == 0) sm.sc[h][jl] = j <= pos ? d * 0.08838834764831845f : -INFINITY;
+            }
+          }
+          wg_sync();
+          for (int h = wave; h < GH; h += MK_WAVES) {
+            const float s = sm.sc[h][lane];
+            const float m = wave_max(s);
+            const float w = expf(s - m);
+            sm.sc[h][lane] = w;
+            const float l = wave_sum(w);
+            if (lane == 0) {
+              sm.att_m[h] = m;
+              sm.att_l[h] = l;
+            }
+          }
+          wg_sync();
+          float acc[GH][8];
+#pragma unroll
+          for (int h = 0; h < GH; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
+#pragma unroll
+          for (int it = 0; it < ATT_IT; ++it) {
+            const int jl = it * (4 * MK_WAVES) + wave * 4 + jj;
+            const uint32_t j = j0 + jl;
+            float vv[8];
+            const uint4 xv = vreg[it];
+            vv[0] = __uint_as_float(xv.x << 16); vv[1] = __uint_as_float(xv.x & 0xffff0000u);
+            vv[2] = __uint_as_float(xv.y << 16); vv[3] = __uint_as_float(xv.y & 0xffff0000u);
+            vv[4] = __uint_as_float(xv.z << 16); vv[5] = __uint_as_float(xv.z & 0xffff0000u);
+            vv[6] = __uint_as_float(xv.w << 16); vv[7] = __uint_as_float(xv.w & 0xffff0000u);
+            if (j == pos) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) vv[e] = sm.vnew[c16 * 8 + e];
+            }
+            if (j <= pos) {
 #pragma unroll
               for (int h = 0; h < GH; ++h) {
-                float d = 0.f;
+                const float w = sm.sc[h][jl];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) d += q[h][e] * kv[e];
-                d += __shfl_xor(d, 1, 64);
-                d += __shfl_xor(d, 2, 64);
-                d += __shfl_xor(d, 4, 64);
-                d += __shfl_xor(d, 8, 64);
-                if (c16 == 0) sm.sc[h][jl] = j <= pos ? d * 0.08838834764831845f : -INFINITY;
+                for (int e = 0; e < 8; ++e) acc[h][e] += w * vv[e];
               }
             }
-            __syncthreads();
-            if (wave < GH) {
-              const float s = sm.sc[wave][lane];
-              const float m = wave_max(s);
-              const float w = expf(s - m);
-              sm.sc[wave][lane] = w;
-              const float l = wave_sum(w);
-              if (lane == 0) {
-                sm.att_m[wave] = m;
-                sm.att_l[wave] = l;
-              }
+          }
+#pragma unroll
+          for (int h = 0; h < GH; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              float v = acc[h][e];
+              v += __shfl_xor(v, 16, 64);
+              v += __shfl_xor(v, 32, 64);
+              if (jj == 0) sm.ared[wave][h][c16 * 8 + e] = v;
             }
-            __syncthreads();
-            float acc[GH][8];
+          wg_sync();
+          for (int o = tid; o < GH * 128; o += MK_THREADS) {
+            const int h = o >> 7, i = o & 127;
+            float v = 0.f;
 #pragma unroll
-            for (int h = 0; h < GH; ++h)
-#pragma unroll
-              for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
-#pragma unroll
-            for (int it = 0; it < ATT_CHUNK / 32; ++it) {
-              const int jl = it * 32 + wave * 4 + jj;
-              const uint32_t j = j0 + jl;
-              if (j <= pos) {
-                float vv[8];
-                if (j < pos) {
-                  const uint4 x = vreg[it];
-                  vv[0] = __uint_as_float(x.x << 16); vv[1] = __uint_as_float(x.x & 0xffff0000u);
-                  vv[2] = __uint_as_float(x.y << 16); vv[3] = __uint_as_float(x.y & 0xffff0000u);
-                  vv[4] = __uint_as_float(x.z << 16); vv[5] = __uint_as_float(x.z & 0xffff0000u);
-                  vv[6] = __uint_as_float(x.w << 16); vv[7] = __uint_as_float(x.w & 0xffff0000u);
-                } else {
-#pragma unroll
-                  for (int e = 0; e < 8; ++e) vv[e] = sm.vnew[c16 * 8 + e];
-                }
-#pragma unroll
-                for (int h = 0; h < GH; ++h) {
-                  const float w = sm.sc[h][jl];
-#pragma unroll
-                  for (int e = 0; e < 8; ++e) acc[h][e] += w * vv[e];
-                }
-              }
-            }
-#pragma unroll
-            for (int h = 0; h < GH; ++h)
-#pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                float v = acc[h][e];
-                v += __shfl_xor(v, 16, 64);
-                v += __shfl_xor(v, 32, 64);
-                if (jj == 0) sm.ared[wave][h][c16 * 8 + e] = v;
-              }
-            __syncthreads();
-            for (int o = tid; o < GH * 128; o += MK_THREADS) {
-              const int h = o >> 7, i = o & 127;
-              float v = 0.f;
-#pragma unroll
-              for (int w = 0; w < MK_WAVES; ++w) v += sm.ared[w][h][i];
-              float* rec = a.att + (((size_t)b * nq + head0 + h) * a.max_chunks + chunk) * 132;
-              st_f(rec + i, v);
-              if (i == 0) {
-                st_f(rec + 128, sm.att_m[h]);
-                st_f(rec + 129, sm.att_l[h]);
-              }
+            for (int w = 0; w < MK_WAVES; ++w) v += sm.ared[w][h][i];
+            u64* rec = a.xatt + ((size_t)(head0 + h) * a.max_chunks + chunk) * 132;
+            st_t(rec + i, v, t_att);
+            if (i == 0) {
+              st_t(rec + 128, sm.att_m[h], t_att);
+              st_t(rec + 129, sm.att_l[h], t_att);
             }
           }
         }
       }
-      stamp(step);
-      if (!grid_barrier(a, epoch)) return;
-      stamp(step);
+      stamp(step);  // 3: attention partials published
 
-      // ================= stage 3: merge attention chunks + output projection =================
-      for (int u = wg; u < o_units; u += nwg) {
+      // ============ stage 3: merge attention chunks + output projection ============
+      const int nch = (int)(pos / ATT_CHUNK) + 1;
+      for (int u = wg_o; u < o_units; u += nwg) {
         const int t = u / a.ks_o, s = u % a.ks_o;
         const int kt0 = s * kts_o, kt1 = min(KTQ, (s + 1) * kts_o);
-        __syncthreads();
-        for (int b = 0; b < nseq; ++b) {
-          const int nch = (int)((a.st->pos[b] + step) / ATT_CHUNK) + 1;
-          for (int k = kt0 * 32 + 2 * tid; k < kt1 * 32; k += 2 * MK_THREADS) {
-            const int head = k >> 7, i = k & 127;
-            const float* rec0 = a.att + ((size_t)b * nq + head) * a.max_chunks * 132;
-            // online merge, four chunks' records in flight at a time
-            float M = -INFINITY, n0 = 0.f, n1 = 0.f, den = 0.f;
-            for (int c0 = 0; c0 < nch; c0 += 4) {
-              float mm[4], ll[4];
-              float2 oo[4];
+        wg_sync();
+        // two (k, k+1) pairs per thread at a time, four chunk records each, all in flight together
+        for (int kb = kt0 * 32 + 2 * tid; kb < kt1 * 32; kb += 4 * MK_THREADS) {
+          float M[2], n0[2], n1[2], den[2];
 #pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                const float* rec = rec0 + (size_t)min(c0 + q, nch - 1) * 132;
-                mm[q] = ld_f(rec + 128);
-                ll[q] = ld_f(rec + 129);
-                oo[q] = ld_f2(rec + i);
-              }
-              float Mn = M;
+          for (int r = 0; r < 2; ++r) {
+            M[r] = -INFINITY;
+            n0[r] = n1[r] = den[r] = 0.f;
+          }
+          for (int c0 = 0; c0 < nch; c0 += 4) {
+            u64 wm[2][4], wl[2][4], wa[2][4], wb[2][4];
+            unsigned spins = 0;
+            for (;;) {
+              bool ok = true;
 #pragma unroll
-              for (int q = 0; q < 4; ++q)
-                if (c0 + q < nch) Mn = fmaxf(Mn, mm[q]);
-              const float sc = expf(M - Mn);  // 0 on the first group (M = -inf)
-              n0 *= sc;
-              n1 *= sc;
-              den *= sc;
+              for (int r = 0; r < 2; ++r) {
+                const int k = kb + 2 * MK_THREADS * r;
+                if (k < kt1 * 32) {
+                  const u64* rec0 = a.xatt + (size_t)(k >> 7) * a.max_chunks * 132;
 #pragma unroll
-              for (int q = 0; q < 4; ++q)
-                if (c0 + q < nch) {
-                  const float f = expf(mm[q] - Mn);
-                  n0 += f * oo[q].x;
-                  n1 += f * oo[q].y;
-                  den += f * ll[q];
+                  for (int q = 0; q < 4; ++q) {
+                    const u64* rec = rec0 + (size_t)min(c0 + q, nch - 1) * 132;
+                    wm[r][q] = ld_t(rec + 128);
+                    wl[r][q] = ld_t(rec + 129);
+                    wa[r][q] = ld_t(rec + (k & 127));
+                    wb[r][q] = ld_t(rec + (k & 127) + 1);
+                  }
                 }
-              M = Mn;
+              }
+#pragma unroll
+              for (int r = 0; r < 2; ++r)
+                if (kb + 2 * MK_THREADS * r < kt1 * 32) {
+#pragma unroll
+                  for (int q = 0; q < 4; ++q)
+                    ok = ok && t_ok(wm[r][q], t_att) && t_ok(wl[r][q], t_att) && t_ok(wa[r][q], t_att) &&
+                         t_ok(wb[r][q], t_att);
+                }
+              if (ok) break;
+              if (spin_over(a, spins)) {
+                give_up(a, sm);
+                break;
+              }
             }
-            put_pair(opnd, NC, b, k - kt0 * 32, make_float2(n0 / den, n1 / den));
+            // online merge of the chunk records
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+              if (kb + 2 * MK_THREADS * r < kt1 * 32) {
+                float Mn = M[r];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                  if (c0 + q < nch) Mn = fmaxf(Mn, t_val(wm[r][q]));
+                const float sc = expf(M[r] - Mn);  // 0 on the first group (M = -inf)
+                n0[r] *= sc;
+                n1[r] *= sc;
+                den[r] *= sc;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                  if (c0 + q < nch) {
+                    const float f = expf(t_val(wm[r][q]) - Mn);
+                    n0[r] += f * t_val(wa[r][q]);
+                    n1[r] += f * t_val(wb[r][q]);
+                    den[r] += f * t_val(wl[r][q]);
+                  }
+                M[r] = Mn;
+              }
+          }
+#pragma unroll
+          for (int r = 0; r < 2; ++r) {
+            const int k = kb + 2 * MK_THREADS * r;
+            if (k < kt1 * 32) put_pair(opnd, k - kt0 * 32, make_float2(n0[r] / den[r], n1[r] / den[r]));
           }
         }
-        __syncthreads();
-        if (u == wg)
-          gemm_unit<1, true>(sm, L.wo, (size_t)t, KTQ, kt0, kt1, pf, opnd, kt0, NC, ncols);
+        wg_sync();
+        if (sm.abort) return;
+        if (u == wg_o)
+          gemm_unit<1, true>(sm, L.wo, (size_t)t, KTQ, kt0, kt1, pf3, opnd, kt0);
         else
-          gemm_unit<1, false>(sm, L.wo, (size_t)t, KTQ, kt0, kt1, pf, opnd, kt0, NC, ncols);
-        __syncthreads();
-        if (tid < 16 * nseq) {
-          const int seq = tid >> 4, row = tid & 15;
-          st_f(a.opart + (size_t)s * pstride + (size_t)seq * H + t * 16 + row, tile_total(sm, 0, row, seq));
-        }
+          gemm_unit<1, false>(sm, L.wo, (size_t)t, KTQ, kt0, kt1, pf3, opnd, kt0);
+        wg_sync();
+        if (tid < 16) st_t(a.xop + (size_t)s * H + t * 16 + tid, tile_total(sm, 0, tid), t_op);
       }
-      // next: gate/up (stage 4)
-      if (wg < gu_pairs) pf_issue<2>(pf, L.wgu, (size_t)wg * 2, KTH, 0, KTH);
-      stamp(step);
-      if (!grid_barrier(a, epoch)) return;
-      stamp(step);
+      stamp(step);  // 4: attention block output published
 
-      // ================= stage 4: residual + post-attention norm + gate/up + SwiGLU ==========
-      for (int b = 0; b < nseq; ++b) {
-        float2 xv[NP];
-        if (li == 0) {
-          gather_embed(xv, H, a.embed, step == 0 ? a.st->tok[b] : sm.tok[b]);
-          gather_resid(xv, H, nullptr, nullptr, 0, a.opart + (size_t)b * H, a.ks_o, pstride);
-        } else {
-#pragma unroll
-          for (int j = 0; j < NP; ++j) xv[j] = make_float2(0.f, 0.f);
-          gather_resid(xv, H, Xa + (size_t)b * H, a.dpart + (size_t)b * H, a.ks_d, a.opart + (size_t)b * H, a.ks_o,
-                       pstride);
-        }
-        if (wg == 0) {
-#pragma unroll
-          for (int j = 0; j < NP; ++j) {
-            const int k = 2 * (tid + MK_THREADS * j);
-            if (k < H) st_f2(Xb + (size_t)b * H + k, xv[j]);
-          }
-        }
-        norm_pack(sm, opnd, NC, b, H, a.eps, xv, L.g_post);
+      // ============ stage 4: residual update + post-attention norm + gate/up + SwiGLU ============
+      add_exchanged<NP>(a, sm, x, H, a.xop, a.ks_o, t_op);
+      if (wg_d < d_units) {
+        const int td = wg_d / a.ks_d, sd = wg_d % a.ks_d;
+        pf_issue<1>(pf5, L.wd, (size_t)td, KTF, sd * kts_d, min(KTF, (sd + 1) * kts_d));
       }
-      __syncthreads();
-      stamp(step);
+      if (wg < qkv_tiles && (li + 1 < a.n_layers || step + 1 < a.n_steps))
+        pf_issue<1>(pf1, a.layers[li + 1 < a.n_layers ? li + 1 : 0].wqkv, (size_t)wg, KTH, 0, KTH);
+      norm_pack<NP>(sm, opnd, H, a.eps, x, L.g_post);
+      wg_sync();
+      if (sm.abort) return;
+      stamp(step);  // 5: operand ready
       for (int pr = wg; pr < gu_pairs; pr += nwg) {
         if (pr == wg)
-          gemm_unit<2, true>(sm, L.wgu, (size_t)pr * 2, KTH, 0, KTH, pf, opnd, 0, NC, ncols);
+          gemm_unit<2, true>(sm, L.wgu, (size_t)pr * 2, KTH, 0, KTH, pf4, opnd, 0);
         else
-          gemm_unit<2, false>(sm, L.wgu, (size_t)pr * 2, KTH, 0, KTH, pf, opnd, 0, NC, ncols);
-        __syncthreads();
-        if (tid < 16 * nseq) {
-          const int seq = tid >> 4, row = tid & 15;
-          const float gate = tile_total(sm, 0, row, seq), up = tile_total(sm, 1, row, seq);
-          st_f(a.act + (size_t)seq * F + pr * 16 + row, gate / (1.0f + expf(-gate)) * up);
+          gemm_unit<2, false>(sm, L.wgu, (size_t)pr * 2, KTH, 0, KTH, pf4, opnd, 0);
+        wg_sync();
+        if (tid < 16) {
+          const float gate = tile_total(sm, 0, tid), up = tile_total(sm, 1, tid);
+          st_t(a.xact + pr * 16 + tid, gate / (1.0f + expf(-gate)) * up, t_act);
         }
-        __syncthreads();
+        wg_sync();
       }
-      // next: down projection (stage 5)
-      if (wg < d_units) {
-        const int t = wg / a.ks_d, s = wg % a.ks_d;
-        pf_issue<1>(pf, L.wd, (size_t)t, KTF, s * kts_d, min(KTF, (s + 1) * kts_d));
-      }
-      stamp(step);
-      if (!grid_barrier(a, epoch)) return;
-      stamp(step);
+      stamp(step);  // 6: activations published
 
-      // ================= stage 5: down projection (k slices) =================
-      for (int u = wg; u < d_units; u += nwg) {
+      // ============ stage 5: down projection (k slices) ============
+      for (int u = wg_d; u < d_units; u += nwg) {
         const int t = u / a.ks_d, s = u % a.ks_d;
         const int kt0 = s * kts_d, kt1 = min(KTF, (s + 1) * kts_d);
-        __syncthreads();
-        for (int b = 0; b < nseq; ++b) {
-          float2 av[4];  // a slice is at most 4096 wide: four pairs per thread, loaded together
+        wg_sync();
+        // four (k, k+1) pairs per thread at a time, loaded together
+        for (int kb = kt0 * 32 + 2 * tid; kb < kt1 * 32; kb += 8 * MK_THREADS) {
+          unsigned spins = 0;
+          for (;;) {
+            u64 w[4][2];
+            bool ok = true;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int k = kt0 * 32 + 2 * (tid + MK_THREADS * j);
-            if (k < kt1 * 32) av[j] = ld_f2(a.act + (size_t)b * F + k);
-          }
+            for (int j = 0; j < 4; ++j) {
+              const int k = kb + 2 * MK_THREADS * j;
+              if (k < kt1 * 32) {
+                w[j][0] = ld_t(a.xact + k);
+                w[j][1] = ld_t(a.xact + k + 1);
+              }
+            }
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int k = kt0 * 32 + 2 * (tid + MK_THREADS * j);
-            if (k < kt1 * 32) put_pair(opnd, NC, b, k - kt0 * 32, av[j]);
+            for (int j = 0; j < 4; ++j) {
+              const int k = kb + 2 * MK_THREADS * j;
+              if (k < kt1 * 32) ok = ok && t_ok(w[j][0], t_act) && t_ok(w[j][1], t_act);
+            }
+            if (ok) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                const int k = kb + 2 * MK_THREADS * j;
+                if (k < kt1 * 32) put_pair(opnd, k - kt0 * 32, make_float2(t_val(w[j][0]), t_val(w[j][1])));
+              }
+              break;
+            }
+            if (spin_over(a, spins)) {
+              give_up(a, sm);
+              break;
+            }
           }
         }
-        __syncthreads();
-        if (u == wg)
-          gemm_unit<1, true>(sm, L.wd, (size_t)t, KTF, kt0, kt1, pf, opnd, kt0, NC, ncols);
+        wg_sync();
+        if (sm.abort) return;
+        if (u == wg_d)
+          gemm_unit<1, true>(sm, L.wd, (size_t)t, KTF, kt0, kt1, pf5, opnd, kt0);
         else
-          gemm_unit<1, false>(sm, L.wd, (size_t)t, KTF, kt0, kt1, pf, opnd, kt0, NC, ncols);
-        __syncthreads();
-        if (tid < 16 * nseq) {
-          const int seq = tid >> 4, row = tid & 15;
-          st_f(a.dpart + (size_t)s * pstride + (size_t)seq * H + t * 16 + row, tile_total(sm, 0, row, seq));
-        }
+          gemm_unit<1, false>(sm, L.wd, (size_t)t, KTF, kt0, kt1, pf5, opnd, kt0);
+        wg_sync();
+        if (tid < 16) st_t(a.xdp + (size_t)s * H + t * 16 + tid, tile_total(sm, 0, tid), t_dp);
       }
-      // next: QKV of the next layer (the LM head streams on its own)
-      if (li + 1 < a.n_layers && wg < qkv_tiles) pf_issue<1>(pf, a.layers[li + 1].wqkv, (size_t)wg, KTH, 0, KTH);
-      stamp(step);
-      if (!grid_barrier(a, epoch)) return;
-
-      // the residual stream written in stage 4 becomes the input of the next layer
-      float* tmp = Xa;
-      Xa = Xb;
-      Xb = tmp;
+      stamp(step);  // 7: MLP output published
     }
 
-    stamp(step);
-    // ================= final norm + LM head + arg-max =================
-    for (int b = 0; b < nseq; ++b) {
-      float2 xv[NP];
-#pragma unroll
-      for (int j = 0; j < NP; ++j) xv[j] = make_float2(0.f, 0.f);
-      gather_resid(xv, H, Xa + (size_t)b * H, a.dpart + (size_t)b * H, a.ks_d, nullptr, 0, pstride);
-      norm_pack(sm, opnd, NC, b, H, a.eps, xv, a.g_final);
-    }
-    __syncthreads();
+    // ============ final norm + LM head + arg-max ============
+    const unsigned t_am = t_step + tags_per_step - 1u;
+    add_exchanged<NP>(a, sm, x, H, a.xdp, a.ks_d, t_am - 1u);
+    norm_pack<NP>(sm, opnd, H, a.eps, x, a.g_final);
+    wg_sync();
+    if (sm.abort) return;
+    stamp(step);  // LM head operand ready
     {
       // every wave walks whole 16-row tiles of the vocabulary on its own (no k split,
       // no workgroup synchronisation): tile = global wave index, stride = all waves
       const int c16 = lane & 15, g = lane >> 4;
-      const bool colok = c16 < ncols;
-      float best[5];
-      int besti[5];
-#pragma unroll
-      for (int b = 0; b < 5; ++b) {
-        best[b] = -INFINITY;
-        besti[b] = 0x7fffffff;
-      }
-      float* lg = a.logits ? a.logits + (size_t)step * nseq * V : nullptr;
+      const bool colok = c16 < 3;
+      float best = -INFINITY;
+      int besti = 0x7fffffff;
+      float* lg = a.logits ? a.logits + (size_t)step * V : nullptr;
       for (int t = wg * MK_WAVES + wave; t < v_tiles; t += nwg * MK_WAVES) {
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
         const uint4* Wt = a.lm_head + (size_t)t * KTH * 64 + lane;
-        for (int kt0 = 0; kt0 < KTH; kt0 += 8) {
-          uint4 av[8];
+        for (int kt0 = 0; kt0 < KTH; kt0 += 16) {
+          uint4 av[16];
 #pragma unroll
-          for (int u = 0; u < 8; ++u) av[u] = kt0 + u < KTH ? Wt[(size_t)(kt0 + u) * 64] : uint4{0, 0, 0, 0};
+          for (int u = 0; u < 16; ++u) av[u] = kt0 + u < KTH ? Wt[(size_t)(kt0 + u) * 64] : uint4{0, 0, 0, 0};
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
+          for (int u = 0; u < 16; ++u) {
             uint4 bv = uint4{0, 0, 0, 0};
-            if (kt0 + u < KTH && colok) bv = opnd[((size_t)(kt0 + u) * 4 + g) * NC + c16];
+            if (kt0 + u < KTH && colok) bv = opnd[((size_t)(kt0 + u) * 4 + g) * 4 + c16];
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av[u]),
                                                           __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
           }
         }
-        // add the three pieces: columns 3b, 3b+1, 3b+2 sit in adjacent lanes
+        // add the three pieces: columns 0, 1, 2 sit in adjacent lanes
         f32x4 s;
 #pragma unroll
         for (int i = 0; i < 4; ++i) s[i] = acc[i] + __shfl_down(acc[i], 1, 64) + __shfl_down(acc[i], 2, 64);
-        const int seq = c16 / 3;
-        if (c16 % 3 == 0 && seq < nseq) {
+        if (c16 == 0) {
           const int row0 = t * 16 + g * 4;
-          if (lg) *reinterpret_cast<float4*>(lg + (size_t)seq * V + row0) = make_float4(s[0], s[1], s[2], s[3]);
+          if (lg) *reinterpret_cast<float4*>(lg + row0) = make_float4(s[0], s[1], s[2], s[3]);
 #pragma unroll
-          for (int b = 0; b < 5; ++b)
-            if (b == seq) {
-#pragma unroll
-              for (int i = 0; i < 4; ++i)
-                if (s[i] > best[b]) {  // rows increase, strict > keeps the lowest index
-                  best[b] = s[i];
-                  besti[b] = row0 + i;
-                }
+          for (int i = 0; i < 4; ++i)
+            if (s[i] > best) {  // rows increase, strict > keeps the lowest index
+              best = s[i];
+              besti = row0 + i;
             }
         }
       }
-      // lanes that own sequence b: c16 == 3b, four of them (g = 0..3) per wave
 #pragma unroll
-      for (int b = 0; b < 5; ++b) {
-        float v = best[b];
-        int i = besti[b];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-          const float ov = __shfl_xor(v, o, 64);
-          const int oi = __shfl_xor(i, o, 64);
-          if (ov > v || (ov == v && oi < i)) {
-            v = ov;
-            i = oi;
-          }
-        }
-        if (lane == 0 && b < nseq) {
-          sm.bestv[wave][b] = v;
-          sm.besti[wave][b] = i;
+      for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best, o, 64);
+        const int oi = __shfl_xor(besti, o, 64);
+        if (ov > best || (ov == best && oi < besti)) {
+          best = ov;
+          besti = oi;
         }
       }
-      __syncthreads();
-      if (tid < nseq) {
-        float v = sm.bestv[0][tid];
-        int i = sm.besti[0][tid];
-        for (int w = 1; w < MK_WAVES; ++w) {
-          const float ov = sm.bestv[w][tid];
-          const int oi = sm.besti[w][tid];
-          if (ov > v || (ov == v && oi < i)) {
-            v = ov;
-            i = oi;
+      if (lane == 0) {
+        sm.bestv[wave] = best;
+        sm.besti[wave] = besti;
+      }
+      wg_sync();
+      if (tid == 0) {
+        float v = sm.bestv[0];
+        int i = sm.besti[0];
+        for (int w = 1; w < MK_WAVES; ++w)
+          if (sm.bestv[w] > v || (sm.bestv[w] == v && sm.besti[w] < i)) {
+            v = sm.bestv[w];
+            i = sm.besti[w];
           }
-        }
-        st_f(a.am_val + (size_t)wg * nseq + tid, v);
-        st_u32(reinterpret_cast<unsigned*>(a.am_idx) + (size_t)wg * nseq + tid, (unsigned)i);
+        st_t(a.xamv + wg, v, t_am);
+        st_t(a.xami + wg, __int_as_float(i), t_am);
       }
     }
-    if (step + 1 < a.n_steps && wg < qkv_tiles) pf_issue<1>(pf, a.layers[0].wqkv, (size_t)wg, KTH, 0, KTH);
-    stamp(step);
-    if (!grid_barrier(a, epoch)) return;
-    stamp(step);
+    stamp(step);  // winners published
 
     // every workgroup reduces the per-workgroup winners itself: the next token needs no
     // further exchange
-    if (wave < nseq) {
+    if (wave == 0) {
       float v = -INFINITY;
       int i = 0x7fffffff;
       for (int w0 = lane; w0 < nwg; w0 += 256) {
-        float ov[4];
-        int oi[4];
+        u64 wv[4], wi[4];
+        unsigned spins = 0;
+        for (;;) {
+          bool ok = true;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int w = min(w0 + 64 * q, nwg - 1);
-          ov[q] = ld_f(a.am_val + (size_t)w * nseq + wave);
-          oi[q] = (int)ld_u32(reinterpret_cast<const unsigned*>(a.am_idx) + (size_t)w * nseq + wave);
+          for (int q = 0; q < 4; ++q) {
+            const int w = min(w0 + 64 * q, nwg - 1);
+            wv[q] = ld_t(a.xamv + w);
+            wi[q] = ld_t(a.xami + w);
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q) ok = ok && t_ok(wv[q], t_am) && t_ok(wi[q], t_am);
+          if (ok) break;
+          if (spin_over(a, spins)) {
+            give_up(a, sm);
+            break;
+          }
         }
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          if (w0 + 64 * q < nwg && (ov[q] > v || (ov[q] == v && oi[q] < i))) {
-            v = ov[q];
-            i = oi[q];
+        for (int q = 0; q < 4; ++q) {
+          const float ov = t_val(wv[q]);
+          const int oi = __float_as_int(t_val(wi[q]));
+          if (w0 + 64 * q < nwg && (ov > v || (ov == v && oi < i))) {
+            v = ov;
+            i = oi;
           }
+        }
       }
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) {
@@ -900,11 +913,14 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_persistent(MkArgs a) {
       }
       if (lane == 0) {
         const int t = i == 0x7fffffff ? 0 : i;
-        sm.tok[wave] = t;
-        if (wg == 0) a.token_log[(size_t)step * nseq + wave] = t;
+        sm.tok = t;
+        if (wg == 0) a.token_log[step] = t;
       }
     }
-    __syncthreads();
+    wg_sync();
+    if (sm.abort) return;
+    tok = sm.tok;
+    stamp(step);  // token known
   }
 }
 
@@ -929,17 +945,20 @@ void mk_fill_layer(void* dst, const void* wqkv, const void* wo, const void* wgu,
   memcpy(dst, &l, sizeof l);
 }
 
-// Operand bytes in LDS: the widest k range any stage holds at once.
+// Operand bytes in LDS: the widest k range any stage holds at once (4 columns of 16 bytes per 8 k).
 size_t mk_opnd_bytes(const MkPlan& p) {
-  const int NC = p.nseq == 1 ? 4 : 16;
   const int kts_o = (p.nq * 128 / 32 + p.ks_o - 1) / p.ks_o, kts_d = (p.F / 32 + p.ks_d - 1) / p.ks_d;
   int kt = p.H / 32;
   if (kts_o > kt) kt = kts_o;
   if (kts_d > kt) kt = kts_d;
-  return (size_t)kt * 4 * NC * 16;
+  return (size_t)kt * 4 * 4 * 16;
 }
 
-hipError_t launch_decode_persistent(hipStream_t s, const MkPlan& p, const MkBuffers& bf) {
+hipError_t launch_decode_resident(hipStream_t s, const MkPlan& p, const MkBuffers& bf) {
+  const int G = p.nq / p.nkv;
+  if (p.H > 4096 || p.ks_o > MK_MAX_KS || p.ks_d > MK_MAX_KS || p.ks_o < 1 || p.ks_d < 1 || (G % 2) != 0 ||
+      p.nwg < 1 || p.nwg > (p.nq + 2 * p.nkv) * 8)
+    return hipErrorInvalidValue;
   MkArgs a{};
   a.layers = static_cast<const MkLayer*>(bf.layers);
   a.n_layers = p.n_layers; a.H = p.H; a.nq = p.nq; a.nkv = p.nkv; a.F = p.F; a.V = p.V;
@@ -949,34 +968,34 @@ hipError_t launch_decode_persistent(hipStream_t s, const MkPlan& p, const MkBuff
   a.g_final = bf.g_final;
   a.rope = bf.rope;
   a.max_seq = p.max_seq;
-  a.flags = bf.flags; a.error = bf.error;
-  a.st = bf.st;
-  a.nseq = p.nseq; a.n_steps = p.n_steps;
+  a.error = bf.error;
+  a.tok0 = p.tok0; a.pos0 = p.pos0; a.slot = p.slot;
+  a.n_steps = p.n_steps;
+  a.tag_base = p.tag_base;
   a.ks_o = p.ks_o; a.ks_d = p.ks_d;
-  a.X0 = bf.X0; a.X1 = bf.X1; a.qkv = bf.qkv; a.att = bf.att; a.max_chunks = p.max_chunks;
-  a.opart = bf.opart; a.act = bf.act; a.dpart = bf.dpart; a.am_val = bf.am_val; a.am_idx = bf.am_idx;
+  a.off_att = p.off_att % p.nwg; a.off_o = p.off_o % p.nwg; a.off_d = p.off_d % p.nwg;
+  a.xq = static_cast<u64*>(bf.xq); a.xatt = static_cast<u64*>(bf.xatt); a.max_chunks = p.max_chunks;
+  a.xop = static_cast<u64*>(bf.xop); a.xact = static_cast<u64*>(bf.xact); a.xdp = static_cast<u64*>(bf.xdp);
+  a.xamv = static_cast<u64*>(bf.xamv); a.xami = static_cast<u64*>(bf.xami);
   a.logits = bf.logits; a.token_log = bf.token_log;
   a.trace = bf.trace; a.trace_step = bf.trace_step; a.trace_points = bf.trace_points;
   const size_t dyn = mk_opnd_bytes(p);
-  const int G = p.nq / p.nkv;
   hipError_t e;
-#define MK_LAUNCH(GH, NP)                                                                                        \
-  do {                                                                                                           \
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_persistent<GH, NP>),                         \
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);                               \
-    if (e != hipSuccess) return e;                                                                               \
-    k_decode_persistent<GH, NP><<<p.nwg, MK_THREADS, dyn, s>>>(a);                                               \
+#define MK_LAUNCH(GH, NP)                                                                                     \
+  do {                                                                                                        \
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_resident<GH, NP>),                        \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);                            \
+    if (e != hipSuccess) return e;                                                                            \
+    k_decode_resident<GH, NP><<<p.nwg, MK_THREADS, dyn, s>>>(a);                                              \
   } while (0)
-#define MK_LAUNCH_NP(GH)              \
-  do {                                \
-    if (p.H <= 1024) MK_LAUNCH(GH, 1); \
-    else if (p.H <= 2048) MK_LAUNCH(GH, 2); \
-    else MK_LAUNCH(GH, 4);            \
+#define MK_LAUNCH_NP(GH)                    \
+  do {                                      \
+    if (p.H <= 1024) MK_LAUNCH(GH, 2);      \
+    else if (p.H <= 2048) MK_LAUNCH(GH, 4); \
+    else MK_LAUNCH(GH, 8);                  \
   } while (0)
-  if (p.H > 4096 || p.ks_o > MK_MAX_KS || p.ks_d > MK_MAX_KS) return hipErrorInvalidValue;
   if (G % 4 == 0) MK_LAUNCH_NP(4);
-  else if (G % 2 == 0) MK_LAUNCH_NP(2);
-  else MK_LAUNCH_NP(1);
+  else MK_LAUNCH_NP(2);
 #undef MK_LAUNCH_NP
 #undef MK_LAUNCH
   return hipGetLastError();

@@ -101,17 +101,19 @@ hipError_t launch_kv_read(hipStream_t s, bool f32, const void* cache, uint32_t m
                           uint32_t pos0, uint32_t n, float* out);
 hipError_t launch_copy_rows(hipStream_t s, const float* src, float* dst, size_t n);
 
-// ---- persistent whole-step decode kernel (bf16 models, up to MK_MAX_SEQS sequences) ----
-constexpr int MK_MAX_SEQS = 5;  // 5 sequences x 3 bf16 pieces fit one 16-column operand block
-
+// ---- resident whole-step decode kernel (bf16 models, batch 1) ----
 struct MkPlan {
-  int nwg;  // resident workgroups (one per compute unit)
+  int nwg;  // resident workgroups: min(compute units, QKV tiles)
   int n_layers, H, nq, nkv, F, V;
   float eps;
   uint32_t max_seq;
   int max_chunks;
-  int nseq, n_steps;
-  int ks_o, ks_d;  // k slices of the output / down projections
+  int tok0;             // token fed to the first step
+  uint32_t pos0, slot;  // its position and KV slot
+  int n_steps;
+  unsigned tag_base;    // first exchange tag of this launch (tags must never repeat)
+  int ks_o, ks_d;       // k slices of the output / down projections
+  int off_att, off_o, off_d;  // first workgroup of the attention / output / down projection units
 };
 
 struct MkBuffers {
@@ -120,25 +122,26 @@ struct MkBuffers {
   const void* lm_head;
   const float* g_final;
   const float2* rope;
-  unsigned* flags;  // [nwg * 32], zero-initialised once
   unsigned* error;  // single word, zero-initialised once
-  const ColState* st;
-  float *X0, *X1, *qkv, *att, *opart, *act, *dpart, *am_val;
-  int32_t* am_idx;
-  float* logits;       // [n_steps][nseq][V] or NULL
-  int32_t* token_log;  // [n_steps][nseq]
+  // exchange buffers of 64-bit (value, tag) words, zero-initialised once
+  void *xq, *xatt, *xop, *xact, *xdp, *xamv, *xami;
+  float* logits;       // [n_steps][V] or NULL
+  int32_t* token_log;  // [n_steps]
   unsigned long long* trace;  // [nwg][trace_points] or NULL
   int trace_step, trace_points;
 };
-// Stamps per traced step, 12 per layer: layer start, after the stage-1 norm, before / after
-// barrier 1, before / after barrier 2, before / after barrier 3, after the stage-4 norm,
-// before / after barrier 4, before barrier 5; then LM-head start, before and after its barrier.
-inline int mk_trace_points(int n_layers) { return 12 * n_layers + 3; }
+// Stamps per traced step, 8 per layer: layer start, stage-1 operand ready, q|k|v published,
+// attention partials published, attention block output published, stage-4 operand ready,
+// activations published, MLP output published; then LM-head operand ready, winners
+// published, token known.
+inline int mk_trace_points(int n_layers) { return 8 * n_layers + 3; }
+// exchange tags one decode step consumes
+inline unsigned mk_tags_per_step(int n_layers) { return 5u * (unsigned)n_layers + 1u; }
 
 size_t mk_layer_bytes();
 void mk_fill_layer(void* dst, const void* wqkv, const void* wo, const void* wgu, const void* wd, const float* g_in,
                    const float* g_q, const float* g_k, const float* g_post, void* kc, void* vc);
 size_t mk_opnd_bytes(const MkPlan& p);
-hipError_t launch_decode_persistent(hipStream_t s, const MkPlan& p, const MkBuffers& b);
+hipError_t launch_decode_resident(hipStream_t s, const MkPlan& p, const MkBuffers& b);
 
 }  // namespace nnc
