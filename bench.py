@@ -38,6 +38,22 @@ def algorithmic_bytes_per_decode_step(shape, ctx_mean: float) -> float:
     return float(weights + kv)
 
 
+def counter_traffic(workload: str, decode_steps: int):
+    """HBM bytes per launch of the resident kernel as measured with rocprofv3 counters
+    (FETCH_SIZE + WRITE_SIZE, scaled by a known copy); read from the committed summary of
+    that measurement, which is valid for the same workload only.  None if there is none."""
+    path = os.path.join(ROOT, "profiles", "k_decode_resident__qwen3-0.6b-b1-p128-d128__hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch="):
+                kv = dict(f.split("=") for f in line.split())
+                if kv.get("workload") == workload and int(kv.get("decode_steps", -1)) == decode_steps:
+                    return int(kv["traffic_bytes_per_launch"])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,7 +122,8 @@ def main() -> int:
     launch_bytes = step_bytes * S
     achieved = launch_bytes / (launch_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "k_decode_resident", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": counter_traffic(args.workload, S),
                 "launches": args.steps, "avg_launch_us": round(launch_ms * 1e3, 1),
                 "bytes_per_launch": round(launch_bytes)}
 
@@ -116,6 +133,14 @@ def main() -> int:
     model.profile_begin()
     model.prefill(0, prompt, want_logits=False)
     stats = model.profile_end()
+
+    # one plain device-to-device copy of known size (1 GiB read + 1 GiB written), untimed: the
+    # reference a counter run (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) scales its readings by
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
 
     cpu = None
     if not args.no_cpu_baseline:
