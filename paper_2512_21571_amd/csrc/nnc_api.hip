@@ -440,14 +440,15 @@ nnc_status persistent_steps(nnc_model* m, uint32_t slot, int32_t token, uint32_t
   p.tag_base = m->mk_tag;
   p.ks_o = m->mk_ks_o; p.ks_d = m->mk_ks_d;
   {
-    // gate/up pairs start at workgroup 0; output-projection units end at the last workgroup,
-    // attention units sit before them, down-projection units before those
-    const int o_units = (int)(m->H() / 16) * p.ks_o, d_units = (int)(m->H() / 16) * p.ks_d;
+    // gate/up pairs and attention units start at workgroup 0 (attention workgroups then have
+    // nothing to prefetch before they wait for q); output-projection units end at the last
+    // workgroup; down-projection units start after the attention workgroups
+    const int o_units = (int)(m->H() / 16) * p.ks_o;
     const int att_units = (int)c.n_kv_heads * ((int)(m->len[slot] + n_steps - 1) / ATT_CHUNK + 1);
     auto wrap = [&](int v) { return ((v % p.nwg) + p.nwg) % p.nwg; };
+    p.off_att = 0;
     p.off_o = wrap(p.nwg - o_units);
-    p.off_att = wrap(p.nwg - o_units - att_units);
-    p.off_d = wrap(p.nwg - o_units - att_units - d_units);
+    p.off_d = wrap(att_units);
   }
   const uint64_t tags = (uint64_t)n_steps * mk_tags_per_step((int)c.n_layers);
   if ((uint64_t)m->mk_tag + tags >= 0xffffffffull)

@@ -174,17 +174,6 @@ __device__ __forceinline__ bool spin_over(const MkArgs& a, unsigned& spins) {
   return spins > MK_SPIN_MAX || ((spins & 255u) == 0 && ld_u32(a.error) != 0);
 }
 
-__device__ __forceinline__ float block_sum(float v, Smem& sm) {
-  v = wave_sum(v);
-  wg_sync();
-  if ((threadIdx.x & 63) == 0) sm.wsum[threadIdx.x >> 6] = v;
-  wg_sync();
-  float t = 0.f;
-#pragma unroll
-  for (int w = 0; w < MK_WAVES; ++w) t += sm.wsum[w];
-  return t;
-}
-
 // bf16 pieces of the pair (v.x, v.y) = activations k, k+1 (k even, relative to the
 // operand's first k) into the packed LDS operand: 4 columns of 16 bytes per 8 k
 // (three pieces and one unused column).
@@ -362,23 +351,42 @@ __device__ __forceinline__ void gather_embed(float2 (&x)[NP], int H, const uint4
   }
 }
 
-// RMSNorm of the row held in x and packing as the GEMM operand (k = 0 .. H).
+// RMSNorm in two halves, so that neither waits for the other: the operand packed here is
+// x * gain (not yet divided by the root mean square); each wave leaves its sum of squares in
+// sm.wsum, and the GEMM epilogues multiply their outputs by rms_scale(), which is exact
+// because the matmul is linear.  Caller synchronises before the GEMM as it must anyway.
+// Gains of the pairs this thread owns.  Loaded before the wait for the exchanged vector, so
+// that their latency (an L2 hit, ~0.7 us) overlaps with it instead of following it.
 template <int NP>
-__device__ __forceinline__ void norm_pack(Smem& sm, uint4* opnd, int H, float eps, const float2 (&x)[NP],
-                                          const float* gain) {
-  float ss = 0.f;
-#pragma unroll
-  for (int j = 0; j < NP; ++j) ss += x[j].x * x[j].x + x[j].y * x[j].y;  // unowned pairs are zero
-  ss = block_sum(ss, sm);
-  const float r = 1.0f / sqrtf(ss / (float)H + eps);
+__device__ __forceinline__ void load_gain(float2 (&gg)[NP], int H, const float* gain) {
 #pragma unroll
   for (int j = 0; j < NP; ++j) {
     const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
-    if (k < H) {
-      const float2 gg = *reinterpret_cast<const float2*>(gain + k);
-      put_pair(opnd, k, make_float2(x[j].x * r * gg.x, x[j].y * r * gg.y));
-    }
+    gg[j] = k < H ? *reinterpret_cast<const float2*>(gain + k) : make_float2(0.f, 0.f);
   }
+}
+
+template <int NP>
+__device__ __forceinline__ void norm_pack(Smem& sm, uint4* opnd, int H, const float2 (&x)[NP],
+                                          const float2 (&gg)[NP]) {
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < NP; ++j) ss += x[j].x * x[j].x + x[j].y * x[j].y;  // unowned pairs are zero
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) sm.wsum[threadIdx.x >> 6] = ss;
+#pragma unroll
+  for (int j = 0; j < NP; ++j) {
+    const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
+    if (k < H) put_pair(opnd, k, make_float2(x[j].x * gg[j].x, x[j].y * gg[j].y));
+  }
+}
+
+// 1 / sqrt(mean(x^2) + eps) of the row last passed to norm_pack (after the workgroup barrier).
+__device__ __forceinline__ float rms_scale(const Smem& sm, int H, float eps) {
+  float t = 0.f;
+#pragma unroll
+  for (int w = 0; w < MK_WAVES; ++w) t += sm.wsum[w];
+  return 1.0f / sqrtf(t / (float)H + eps);
 }
 
 }  // namespace
@@ -418,10 +426,11 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
   const int wg_att = (wg + nwg - a.off_att) % nwg, wg_o = (wg + nwg - a.off_o) % nwg,
             wg_d = (wg + nwg - a.off_d) % nwg;
 
-  // Prefetched weights of this workgroup's first unit in each GEMM stage.  They are issued
-  // right after a stage's input has arrived (the waits return in order behind them, so a
-  // prefetch must never be issued just before a wait): stages 3 and 4 after the stage-1
-  // wait, stage 5 and the next layer's stage 1 after the stage-4 wait.
+  // Prefetched weights of this workgroup's first unit in each GEMM stage, one register set
+  // per stage.  Issuing a set costs the wave ~0.3 us of address traffic, and loads return in
+  // order, so a wait issued after a prefetch cannot complete before the prefetch has landed
+  // (~2 us).  Both are free just before a wait that is long anyway, and that is where the
+  // three prefetch points sit; none follows a wait directly.
   Pf<1> pf1, pf3, pf5;
   Pf<2> pf4;
   if (wg < qkv_tiles) pf_issue<1>(pf1, a.layers[0].wqkv, (size_t)wg, KTH, 0, KTH);
@@ -438,16 +447,13 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
       stamp(step);  // 0: layer start
 
       // ============ stage 1: residual update + input norm + QKV projection ============
+      float2 gg[NP];
+      load_gain<NP>(gg, H, L.g_in);
       if (li == 0)
         gather_embed<NP>(x, H, a.embed, tok);
       else
         add_exchanged<NP>(a, sm, x, H, a.xdp, a.ks_d, t_dp - 5u);
-      if (wg_o < o_units) {
-        const int to = wg_o / a.ks_o, so = wg_o % a.ks_o;
-        pf_issue<1>(pf3, L.wo, (size_t)to, KTQ, so * kts_o, min(KTQ, (so + 1) * kts_o));
-      }
-      if (wg < gu_pairs) pf_issue<2>(pf4, L.wgu, (size_t)wg * 2, KTH, 0, KTH);
-      norm_pack<NP>(sm, opnd, H, a.eps, x, L.g_in);
+      norm_pack<NP>(sm, opnd, H, x, gg);
       wg_sync();
       if (sm.abort) return;
       stamp(step);  // 1: operand ready
@@ -457,8 +463,13 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
         else
           gemm_unit<1, false>(sm, L.wqkv, (size_t)t, KTH, 0, KTH, pf1, opnd, 0);
         wg_sync();
-        if (tid < 16) st_t(a.xq + t * 16 + tid, tile_total(sm, 0, tid), t_q);
+        if (tid < 16) st_t(a.xq + t * 16 + tid, tile_total(sm, 0, tid) * rms_scale(sm, H, a.eps), t_q);
         wg_sync();
+      }
+      // prefetch point A (a long wait follows: attention has to run first): output projection
+      if (wg_o < o_units) {
+        const int to = wg_o / a.ks_o, so = wg_o % a.ks_o;
+        pf_issue<1>(pf3, L.wo, (size_t)to, KTQ, so * kts_o, min(KTQ, (so + 1) * kts_o));
       }
       stamp(step);  // 2: q | k | v published
 
@@ -490,6 +501,10 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
             if (role >= GH && !(owns_new && hg == 0)) continue;
             const u64* src = role < GH ? a.xq + (size_t)(head0 + role) * 128
                                        : a.xq + Dq + (size_t)(role == GH ? 0 : Dkv) + (size_t)kvh * 128;
+            // rotary factors and norm gains first: their loads overlap with the wait for q
+            const float* gsrc = role < GH ? L.g_q : L.g_k;
+            const float g0 = gsrc[lane], g1 = gsrc[lane + 64];
+            const float2 cs = a.rope[(size_t)pos * 64 + lane];
             u64 w0, w1;
             unsigned spins = 0;
             for (;;) {
@@ -505,10 +520,8 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
             if (role <= GH) {
               const float ss = wave_sum(x0 * x0 + x1 * x1);
               const float r = 1.0f / sqrtf(ss * (1.0f / 128.0f) + a.eps);
-              const float* gg = role < GH ? L.g_q : L.g_k;
-              x0 = x0 * r * gg[lane];
-              x1 = x1 * r * gg[lane + 64];
-              const float2 cs = a.rope[(size_t)pos * 64 + lane];
+              x0 = x0 * r * g0;
+              x1 = x1 * r * g1;
               const float r0 = x0 * cs.x - x1 * cs.y, r1 = x1 * cs.x + x0 * cs.y;
               x0 = r0;
               x1 = r1;
@@ -631,6 +644,12 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
       }
       stamp(step);  // 3: attention partials published
 
+      // prefetch point B (the waits of stages 3 and 4 follow, both long): gate/up and down
+      if (wg < gu_pairs) pf_issue<2>(pf4, L.wgu, (size_t)wg * 2, KTH, 0, KTH);
+      if (wg_d < d_units) {
+        const int td = wg_d / a.ks_d, sd = wg_d % a.ks_d;
+        pf_issue<1>(pf5, L.wd, (size_t)td, KTF, sd * kts_d, min(KTF, (sd + 1) * kts_d));
+      }
       // ============ stage 3: merge attention chunks + output projection ============
       const int nch = (int)(pos / ATT_CHUNK) + 1;
       for (int u = wg_o; u < o_units; u += nwg) {
@@ -720,14 +739,9 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
       stamp(step);  // 4: attention block output published
 
       // ============ stage 4: residual update + post-attention norm + gate/up + SwiGLU ============
+      load_gain<NP>(gg, H, L.g_post);
       add_exchanged<NP>(a, sm, x, H, a.xop, a.ks_o, t_op);
-      if (wg_d < d_units) {
-        const int td = wg_d / a.ks_d, sd = wg_d % a.ks_d;
-        pf_issue<1>(pf5, L.wd, (size_t)td, KTF, sd * kts_d, min(KTF, (sd + 1) * kts_d));
-      }
-      if (wg < qkv_tiles && (li + 1 < a.n_layers || step + 1 < a.n_steps))
-        pf_issue<1>(pf1, a.layers[li + 1 < a.n_layers ? li + 1 : 0].wqkv, (size_t)wg, KTH, 0, KTH);
-      norm_pack<NP>(sm, opnd, H, a.eps, x, L.g_post);
+      norm_pack<NP>(sm, opnd, H, x, gg);
       wg_sync();
       if (sm.abort) return;
       stamp(step);  // 5: operand ready
@@ -738,13 +752,17 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
           gemm_unit<2, false>(sm, L.wgu, (size_t)pr * 2, KTH, 0, KTH, pf4, opnd, 0);
         wg_sync();
         if (tid < 16) {
-          const float gate = tile_total(sm, 0, tid), up = tile_total(sm, 1, tid);
+          const float r = rms_scale(sm, H, a.eps);
+          const float gate = tile_total(sm, 0, tid) * r, up = tile_total(sm, 1, tid) * r;
           st_t(a.xact + pr * 16 + tid, gate / (1.0f + expf(-gate)) * up, t_act);
         }
         wg_sync();
       }
       stamp(step);  // 6: activations published
 
+      // prefetch point C (the activation exchange follows): QKV of the next layer / next step
+      if (wg < qkv_tiles && (li + 1 < a.n_layers || step + 1 < a.n_steps))
+        pf_issue<1>(pf1, a.layers[li + 1 < a.n_layers ? li + 1 : 0].wqkv, (size_t)wg, KTH, 0, KTH);
       // ============ stage 5: down projection (k slices) ============
       for (int u = wg_d; u < d_units; u += nwg) {
         const int t = u / a.ks_d, s = u % a.ks_d;
@@ -797,8 +815,12 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
 
     // ============ final norm + LM head + arg-max ============
     const unsigned t_am = t_step + tags_per_step - 1u;
-    add_exchanged<NP>(a, sm, x, H, a.xdp, a.ks_d, t_am - 1u);
-    norm_pack<NP>(sm, opnd, H, a.eps, x, a.g_final);
+    {
+      float2 gg[NP];
+      load_gain<NP>(gg, H, a.g_final);
+      add_exchanged<NP>(a, sm, x, H, a.xdp, a.ks_d, t_am - 1u);
+      norm_pack<NP>(sm, opnd, H, x, gg);
+    }
     wg_sync();
     if (sm.abort) return;
     stamp(step);  // LM head operand ready
@@ -809,6 +831,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
       const bool colok = c16 < 3;
       float best = -INFINITY;
       int besti = 0x7fffffff;
+      const float rms = rms_scale(sm, H, a.eps);
       float* lg = a.logits ? a.logits + (size_t)step * V : nullptr;
       for (int t = wg * MK_WAVES + wave; t < v_tiles; t += nwg * MK_WAVES) {
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -828,7 +851,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
         // add the three pieces: columns 0, 1, 2 sit in adjacent lanes
         f32x4 s;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) s[i] = acc[i] + __shfl_down(acc[i], 1, 64) + __shfl_down(acc[i], 2, 64);
+        for (int i = 0; i < 4; ++i) s[i] = (acc[i] + __shfl_down(acc[i], 1, 64) + __shfl_down(acc[i], 2, 64)) * rms;
         if (c16 == 0) {
           const int row0 = t * 16 + g * 4;
           if (lg) *reinterpret_cast<float4*>(lg + row0) = make_float4(s[0], s[1], s[2], s[3]);
