@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libnnc.so")
-SOURCES = ["nnc_kernels.hip", "nnc_decode_mk.hip", "nnc_api.hip"]
+SOURCES = ["nnc_kernels.hip", "nnc_decode_mk.hip", "nnc_prefill.hip", "nnc_api.hip"]
 HEADERS = [os.path.join(CSRC, "nnc_internal.h"), os.path.join(HERE, "..", "include", "nnc.h")]
 
 HIPCC_FLAGS = [

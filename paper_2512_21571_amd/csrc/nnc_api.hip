@@ -47,9 +47,9 @@ struct ProfRec {
   hipEvent_t e0, e1;
 };
 
-enum Family { FAM_GEMM = 0, FAM_NORM, FAM_QKROPE, FAM_ATTN, FAM_COMBINE, FAM_EMBED, FAM_ARGMAX, FAM_MISC, FAM_COUNT };
+enum Family { FAM_GEMM = 0, FAM_NORM, FAM_QKROPE, FAM_ATTN, FAM_COMBINE, FAM_EMBED, FAM_ARGMAX, FAM_MISC, FAM_PGEMM, FAM_COUNT };
 const char* const kFamName[FAM_COUNT] = {"gemm_skinny", "rmsnorm_pack", "qknorm_rope_append", "attn_partial",
-                                         "attn_combine", "embed", "argmax", "misc"};
+                                         "attn_combine", "embed", "argmax", "misc", "gemm_prefill"};
 
 }  // namespace
 
@@ -84,6 +84,12 @@ struct nnc_model {
   uint32_t token_log_steps = 0;
 
   std::vector<uint32_t> len;
+
+  // prompt pass on large token blocks
+  uint32_t pb_max = 0;         // tokens per block (multiple of 128), 0 if unavailable
+  float *pb_x = nullptr, *pb_qkv = nullptr;
+  void *pb_fa = nullptr, *pb_fb = nullptr;  // fragment-order bf16 operands: K = H, K = max(Dq, F)
+  int32_t* pb_tok = nullptr;
 
   // resident decode kernel
   bool mk_ok = false;
@@ -260,6 +266,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
 
   if (p.tokens) RUN(FAM_EMBED, n * H * w, 0, launch_embed(s, f32, m->embed, H, m->st, n, m->x));
 
+  const ColMap cm{m->st, 0, 0, 0};
   // k-slice partials of the previous projection still to be added to x
   int pending = 0;
   const long pstride = (long)n * H;
@@ -275,13 +282,13 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       RUN(FAM_GEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * n, launch_gemm(s, f32, EPI_STORE, a));
     }
     RUN(FAM_QKROPE, n * Nqkv * 4.0, 0,
-        launch_qknorm_rope_append(s, f32, m->qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, m->st, n,
+        launch_qknorm_rope_append(s, f32, m->qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, n,
                                   L.kc, L.vc, c.max_batch, c.max_seq));
     RUN(FAM_ATTN, p.kv_rows * 2.0 * Dkv * w, p.kv_rows * 4.0 * Dq,
-        launch_attn_partial(s, f32, m->qkv, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, m->st, n,
+        launch_attn_partial(s, f32, m->qkv, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, cm, n,
                             p.grid_chunks, m->partial, m->max_chunks));
     RUN(FAM_COMBINE, 0, 0,
-        launch_attn_combine(s, f32, m->partial, m->max_chunks, nq, m->st, n, m->Ap, nc, ns));
+        launch_attn_combine(s, f32, m->partial, m->max_chunks, nq, cm, n, m->Ap, nc, ns, false));
     {
       GemmArgs a{};
       a.Wp = L.wo; a.n_tiles = H / 16; a.KT = KTQ; a.kts_per_split = pick_kts(a.n_tiles, KTQ);
@@ -512,7 +519,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
       m->use_hooks = true;
     }
   }
-  m->opt_prefill_exact = true;
+  m->opt_prefill_exact = false;
   const nnc_config& c = m->c;
   const size_t H = m->H(), Dq = m->Dq(), Dkv = m->Dkv(), F = m->F(), V = m->V(), d = c.head_dim;
   const size_t w = m->esz(), bw = c.blob_dtype == NNC_F32 ? 4 : 2;
@@ -622,6 +629,20 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     ALLOC(m->am_val, float*, MAX_COLS * 64 * 4);
     ALLOC(m->am_idx, int32_t*, MAX_COLS * 64 * 4);
   }
+  // prompt pass on large token blocks (bf16 token models)
+  if (!m->f32 && c.has_embed_and_head) {
+    uint32_t pb = (c.max_seq + 127) / 128 * 128;
+    if (pb > 2048) pb = 2048;
+    m->pb_max = pb;
+    ALLOC(m->pb_x, float*, (size_t)pb * H * 4);
+    ALLOC(m->pb_qkv, float*, (size_t)pb * (Dq + 2 * Dkv) * 4);
+    // prompts of <= 512 tokens carry two bf16 pieces per activation
+    const size_t frag_rows = std::max<size_t>(pb, 2 * std::min<size_t>(pb, 512));
+    ALLOC(m->pb_fa, void*, frag_rows * H * 2);
+    ALLOC(m->pb_fb, void*, frag_rows * std::max(Dq, F) * 2);
+    ALLOC(m->pb_tok, int32_t*, (size_t)pb * 4);
+  }
+
   // resident decode kernel: per-layer pointer table, exchange buffers
   if (!m->f32 && c.has_embed_and_head && c.n_layers > 0 && H <= 4096 && (c.n_q_heads / c.n_kv_heads) % 2 == 0) {
     const int qkv_tiles = (int)((Dq + 2 * Dkv) / 16);
@@ -711,6 +732,86 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
   return fail(NNC_E_ARG, "unknown option %d", (int)opt);
 }
 
+// Prompt pass over one block of up to pb_max tokens of one slot with the LDS-staged
+// matrix-core GEMMs.  Activations entering a GEMM are rounded to bf16 once.
+static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* tokens, uint32_t n, uint32_t pos0,
+                                bool want_head, float* logits_out, int32_t* next_dev) {
+  const nnc_config& c = m->c;
+  hipStream_t s = m->stream;
+  const int H = m->H(), Dq = m->Dq(), Dkv = m->Dkv(), F = m->F(), V = m->V();
+  const int nq = c.n_q_heads, nkv = c.n_kv_heads, Nqkv = Dq + 2 * Dkv;
+  const int tt = (int)((n + 15) / 16);  // token tiles; rows up to 16 * tt exist in every buffer
+  // Short prompts are bound by streaming the weights, not by the matrix cores: carry the
+  // activations as two bf16 pieces (fp32-grade) and use small row tiles for more workgroups.
+  // Long prompts are matrix-core bound: one bf16 per activation, 256-row tiles.
+  const int pieces = n <= 512 ? 2 : 1;
+  const bool small_tiles = n <= 256;
+  const int ct = tt * pieces;  // operand column tiles
+  const double w = 2.0, T = n;
+  HIP_TRY(hipMemcpyAsync(m->pb_tok, tokens, (size_t)n * 4, hipMemcpyHostToDevice, s));
+  RUN(FAM_EMBED, T * H * w, 0, launch_embed_rows(s, m->embed, H, m->pb_tok, (int)n, m->pb_x));
+  for (uint32_t li = 0; li < c.n_layers; ++li) {
+    const LayerW& L = m->L[li];
+    RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, m->pb_x, L.g_in, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
+    {
+      PrefillGemmArgs a{};
+      a.Wp = L.wqkv; a.n_tiles = Nqkv / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
+      a.out = m->pb_qkv; a.ldo = Nqkv;
+      RUN(FAM_PGEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * T, launch_gemm_prefill(s, EPI_STORE, a, pieces, small_tiles));
+    }
+    {
+      const ColMap cm{nullptr, slot, pos0, 0};
+      RUN(FAM_QKROPE, T * Nqkv * 4.0, 0,
+          launch_qknorm_rope_append(s, false, m->pb_qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, (int)n, L.kc,
+                                    L.vc, c.max_batch, c.max_seq));
+    }
+    for (uint32_t b0 = 0; b0 < n; b0 += MAX_COLS) {
+      const int nb = (int)std::min<uint32_t>(MAX_COLS, n - b0);
+      const ColMap cm{nullptr, slot, pos0 + b0, (int)b0};
+      double rows = 0;
+      for (int i = 0; i < nb; ++i) rows += pos0 + b0 + i + 1.0;
+      RUN(FAM_ATTN, rows * 2.0 * Dkv * w, rows * 4.0 * Dq,
+          launch_attn_partial(s, false, m->pb_qkv, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, cm, nb,
+                              chunks_grid(pos0 + b0 + nb - 1), m->partial, m->max_chunks));
+      RUN(FAM_COMBINE, 0, 0,
+          launch_attn_combine(s, false, m->partial, m->max_chunks, nq, cm, nb, m->pb_fb, 0, pieces, true));
+    }
+    {
+      PrefillGemmArgs a{};
+      a.Wp = L.wo; a.n_tiles = H / 16; a.KT = Dq / 32; a.Xf = m->pb_fb; a.t_tiles = ct;
+      a.out = m->pb_x; a.ldo = H;
+      RUN(FAM_PGEMM, (double)H * Dq * w, 2.0 * H * Dq * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, small_tiles));
+    }
+    RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, m->pb_x, L.g_post, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
+    {
+      PrefillGemmArgs a{};
+      a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
+      a.packed_out = m->pb_fb;
+      RUN(FAM_PGEMM, 2.0 * F * H * w, 4.0 * F * H * T, launch_gemm_prefill(s, EPI_SWIGLU, a, pieces, small_tiles));
+    }
+    {
+      PrefillGemmArgs a{};
+      a.Wp = L.wd; a.n_tiles = H / 16; a.KT = F / 32; a.Xf = m->pb_fb; a.t_tiles = ct;
+      a.out = m->pb_x; a.ldo = H;
+      RUN(FAM_PGEMM, (double)H * F * w, 2.0 * H * F * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, small_tiles));
+    }
+  }
+  if (want_head) {
+    // logits of the block's last token: fp32-grade (three-piece) GEMV over the LM head
+    RUN(FAM_NORM, H * 8.0, 0,
+        launch_rmsnorm_pack(s, false, m->pb_x + (size_t)(n - 1) * H, H, nullptr, 0, 0, m->g_final, H, c.rms_eps, 1,
+                            m->Xp, 3, 3));
+    GemmArgs a{};
+    a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = H / 32; a.kts_per_split = H / 32;
+    a.Xp = m->Xp; a.NC = 3; a.ncols = 3; a.nsplit = 3; a.nseq = 1;
+    a.out = logits_out ? logits_out : m->logits; a.ldo = V;
+    RUN(FAM_GEMM, (double)V * H * w, 2.0 * V * H, launch_gemm(s, false, EPI_STORE, a));
+    if (next_dev)
+      RUN(FAM_ARGMAX, V * 4.0, 0, launch_argmax(s, a.out, V, V, 1, nullptr, 0, m->am_val, m->am_idx, next_dev));
+  }
+  return NNC_OK;
+}
+
 static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tokens, const float* x, uint32_t n,
                                  float* logits_out, int32_t* next_out, float* y) {
   if (slot >= m->c.max_batch) return fail(NNC_E_ARG, "slot %u out of range", slot);
@@ -720,7 +821,20 @@ static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tok
   if (tokens)
     for (uint32_t i = 0; i < n; ++i)
       if (tokens[i] < 0 || (uint32_t)tokens[i] >= m->c.vocab) return fail(NNC_E_ARG, "token %d out of range", tokens[i]);
-  const int nsplit = m->f32 ? 1 : (m->opt_prefill_exact ? 3 : 1);
+  if (tokens && m->pb_max && !m->opt_prefill_exact) {
+    const uint32_t len0 = m->len[slot];
+    for (uint32_t t0 = 0; t0 < n; t0 += m->pb_max) {
+      const uint32_t nb = std::min(m->pb_max, n - t0);
+      const bool last = t0 + nb == n;
+      if (nnc_status st = prefill_block(m, slot, tokens + t0, nb, len0 + t0, last && (logits_out || next_out),
+                                        logits_out, next_out ? m->next : nullptr))
+        return st;
+    }
+    if (next_out) HIP_TRY(hipMemcpyAsync(next_out, m->next, 4, hipMemcpyDeviceToDevice, m->stream));
+    m->len[slot] = len0 + n;
+    return NNC_OK;
+  }
+  const int nsplit = m->f32 ? 1 : 3;
   const uint32_t chunk = MAX_COLS / nsplit;
   const size_t H = m->H();
   const uint32_t len0 = m->len[slot];

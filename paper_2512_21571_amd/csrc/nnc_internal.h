@@ -23,7 +23,16 @@ struct ColState {
   uint32_t pad[3];
 };
 
-enum Epilogue { EPI_STORE = 0, EPI_SWIGLU = 2 };
+enum Epilogue { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+
+// Column -> (slot, position, row of the q|k|v buffer).  st != NULL: decode pass, looked up
+// per column, row = column.  st == NULL: prompt block, column c is position pos0 + c of
+// `slot` and row row0 + c.
+struct ColMap {
+  const ColState* st;
+  uint32_t slot, pos0;
+  int row0;
+};
 
 // Skinny GEMM  Y[n, seq] = sum_k W[n, k] * X[k, seq]  over packed operands.
 //
@@ -84,14 +93,38 @@ hipError_t launch_fold_residual(hipStream_t s, float* x, const float* part, int 
 hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a);
 hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq, int nkv,
                                      const float* gq, const float* gk, float eps,
-                                     const float2* rope, const ColState* st, int ncols, void* kc,
+                                     const float2* rope, const ColMap& cm, int ncols, void* kc,
                                      void* vc, uint32_t max_batch, uint32_t max_seq);
 hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, int nq, int nkv,
                                const void* kc, const void* vc, uint32_t max_batch, uint32_t max_seq,
-                               const ColState* st, int ncols, int grid_chunks, float* partial,
+                               const ColMap& cm, int ncols, int grid_chunks, float* partial,
                                int max_chunks);
 hipError_t launch_attn_combine(hipStream_t s, bool f32, const float* partial, int max_chunks, int nq,
-                               const ColState* st, int ncols, void* Op, int NC, int nsplit);
+                               const ColMap& cm, int ncols, void* Op, int NC, int nsplit, bool frag);
+
+// ---- prompt pass on large token blocks (bf16 models): LDS-staged matrix-core GEMM ----
+// Y[t, n] = sum_k X[t, k] W[n, k].  W: packed weights (above).  X: bf16 activations in
+// fragment order [column tile][k / 32][64 lanes][8]; with `pieces` = 2 every activation is two
+// bf16 values (value, remainder) and token tile q occupies column tiles 2q, 2q+1 (the
+// epilogue adds their products).  t_tiles counts column tiles = token tiles x pieces.
+// epi EPI_STORE: out[t * ldo + n] = y (fp32).  EPI_RESID: out[t * ldo + n] += y.
+// EPI_SWIGLU: rows alternate gate / up in 16-row tiles; silu(gate) * up for feature f is
+// written as bf16 in fragment order (k = f, k tiles = n_tiles / 2 / 2) into packed_out.
+struct PrefillGemmArgs {
+  const void* Wp;
+  int n_tiles, KT;
+  const void* Xf;
+  int t_tiles;
+  float* out;
+  long ldo;
+  void* packed_out;
+};
+hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a, int pieces, bool small_tiles);
+// RMSNorm of rows 0..n_rows-1 of x ([rows, H] fp32), one bf16 per value, fragment order;
+// rows n_rows .. 16 * t_tiles - 1 of the operand are zero-filled.
+hipError_t launch_rmsnorm_frag(hipStream_t s, const float* x, const float* gain, int H, float eps, int n_rows,
+                               int token_tiles, int pieces, void* Xf);
+hipError_t launch_embed_rows(hipStream_t s, const void* Ep, int H, const int32_t* tokens_dev, int n, float* x);
 hipError_t launch_argmax(hipStream_t s, const float* logits, long ld, int V, int ncols,
                          const uint32_t* step_ptr, long step_stride, float* scratch_val,
                          int32_t* scratch_idx, int32_t* next);

@@ -428,6 +428,11 @@ hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a) {
   return f32 ? gemm_dispatch_ncb<true, EPI_STORE, 1>(s, a) : gemm_dispatch_ncb<false, EPI_STORE, 1>(s, a);
 }
 
+// Which sequence position a column of a pass stands for: decode passes look it up in the
+// device-resident column state; prompt blocks are `ncols` consecutive positions of one slot.
+__device__ __forceinline__ uint32_t col_pos(const ColMap& cm, int col) { return cm.st ? cm.st->pos[col] : cm.pos0 + col; }
+__device__ __forceinline__ uint32_t col_slot(const ColMap& cm, int col) { return cm.st ? cm.st->slot[col] : cm.slot; }
+
 // ---------------------------------------------------------------------------
 // per-head QK RMSNorm + rotary embedding + KV append (head_dim 128)
 // ---------------------------------------------------------------------------
@@ -439,12 +444,12 @@ hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a) {
 template <bool F32>
 __global__ __launch_bounds__(64) void k_qknorm_rope_append(
     float* __restrict__ qkv, int nq, int nkv, const float* __restrict__ gq, const float* __restrict__ gk,
-    float eps, const float2* __restrict__ rope, const ColState* __restrict__ st, void* __restrict__ kc,
+    float eps, const float2* __restrict__ rope, ColMap cm, void* __restrict__ kc,
     void* __restrict__ vc, uint32_t max_seq) {
   const int col = blockIdx.y, hh = blockIdx.x, lane = threadIdx.x;
   const int ld = (nq + 2 * nkv) * 128;
-  float* p = qkv + (size_t)col * ld + (size_t)hh * 128;
-  const uint32_t pos = st->pos[col], slot = st->slot[col];
+  float* p = qkv + (size_t)(cm.row0 + col) * ld + (size_t)hh * 128;
+  const uint32_t pos = col_pos(cm, col), slot = col_slot(cm, col);
   float a = p[lane], b = p[lane + 64];
   const bool is_v = hh >= nq + nkv;
   if (!is_v) {
@@ -478,14 +483,14 @@ __global__ __launch_bounds__(64) void k_qknorm_rope_append(
 
 hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq, int nkv,
                                      const float* gq, const float* gk, float eps,
-                                     const float2* rope, const ColState* st, int ncols, void* kc,
+                                     const float2* rope, const ColMap& cm, int ncols, void* kc,
                                      void* vc, uint32_t max_batch, uint32_t max_seq) {
   (void)max_batch;
   dim3 grid(nq + 2 * nkv, ncols);
   if (f32)
-    k_qknorm_rope_append<true><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, st, kc, vc, max_seq);
+    k_qknorm_rope_append<true><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq);
   else
-    k_qknorm_rope_append<false><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, st, kc, vc, max_seq);
+    k_qknorm_rope_append<false><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq);
   return hipGetLastError();
 }
 
@@ -518,7 +523,7 @@ __device__ __forceinline__ void load_row8(const void* base, size_t elem, float* 
 template <bool F32, int GH>
 __global__ __launch_bounds__(256) void k_attn_partial(
     const float* __restrict__ qkv, int nq, int nkv, const void* __restrict__ kc,
-    const void* __restrict__ vc, uint32_t max_seq, const ColState* __restrict__ st,
+    const void* __restrict__ vc, uint32_t max_seq, ColMap cm,
     float* __restrict__ partial, int max_chunks) {
   __shared__ float sc[GH][ATT_CHUNK];      // scores, then softmax weights
   __shared__ float red[4][GH][128];        // per-wave value sums
@@ -528,7 +533,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(
   const int groups = G / GH;
   const int kvh = blockIdx.y / groups, hg = blockIdx.y % groups;
   const int head0 = kvh * G + hg * GH;
-  const uint32_t pos = st->pos[col], slot = st->slot[col];
+  const uint32_t pos = col_pos(cm, col), slot = col_slot(cm, col);
   const uint32_t j0 = (uint32_t)chunk * ATT_CHUNK;
   if (j0 > pos) return;  // chunk lies entirely in the future (uniform for the workgroup)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -540,7 +545,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(
   float q[GH][8];
 #pragma unroll
   for (int h = 0; h < GH; ++h) {
-    const float* qp = qkv + (size_t)col * ld + (size_t)(head0 + h) * 128 + c16 * 8;
+    const float* qp = qkv + (size_t)(cm.row0 + col) * ld + (size_t)(head0 + h) * 128 + c16 * 8;
 #pragma unroll
     for (int e = 0; e < 8; ++e) q[h][e] = qp[e];
   }
@@ -631,14 +636,14 @@ __global__ __launch_bounds__(256) void k_attn_partial(
 
 hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, int nq, int nkv,
                                const void* kc, const void* vc, uint32_t max_batch, uint32_t max_seq,
-                               const ColState* st, int ncols, int grid_chunks, float* partial,
+                               const ColMap& cm, int ncols, int grid_chunks, float* partial,
                                int max_chunks) {
   (void)max_batch;
   const int G = nq / nkv;
   const int GH = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
   dim3 grid(grid_chunks, nkv * (G / GH), ncols);
 #define NNC_ATT(F, H) \
-  k_attn_partial<F, H><<<grid, 256, 0, s>>>(qkv, nq, nkv, kc, vc, max_seq, st, partial, max_chunks)
+  k_attn_partial<F, H><<<grid, 256, 0, s>>>(qkv, nq, nkv, kc, vc, max_seq, cm, partial, max_chunks)
   if (f32) {
     if (GH == 4) NNC_ATT(true, 4); else if (GH == 2) NNC_ATT(true, 2); else NNC_ATT(true, 1);
   } else {
@@ -651,12 +656,16 @@ hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, int nq
 // Merge the chunk partials of one (column, head) and write the attention output
 // as the packed operand of the output projection (k index = head * 128 + i).
 //   M = max_c m_c;  o = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} l_c
-template <bool F32>
+// FRAG = false: split-bf16 (or fp32) columns of the skinny GEMM operand.
+// FRAG = true : one bf16 per value, matrix-core fragment order of the prompt GEMM
+//               ([token / 16][k / 32][64 lanes][8], lane = token % 16 + 16 * ((k % 32) / 8)),
+//               as nsplit (1 or 2) bf16 pieces in adjacent column tiles.
+template <bool F32, bool FRAG>
 __global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ partial, int max_chunks,
-                                                      int nq, const ColState* __restrict__ st,
-                                                      void* __restrict__ Op, int NC, int nsplit) {
+                                                      int nq, ColMap cm, void* __restrict__ Op, int NC,
+                                                      int nsplit) {
   const int head = blockIdx.x, col = blockIdx.y, i = threadIdx.x;
-  const int nchunks = (int)(st->pos[col] / ATT_CHUNK) + 1;
+  const int nchunks = (int)(col_pos(cm, col) / ATT_CHUNK) + 1;
   const float* rec0 = partial + ((size_t)col * nq + head) * max_chunks * 132;
   float M = -INFINITY;
   for (int c = 0; c < nchunks; ++c) M = fmaxf(M, rec0[(size_t)c * 132 + 128]);
@@ -667,16 +676,34 @@ __global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ 
     num += f * rec[i];
     den += f * rec[129];
   }
-  store_packed<F32>(Op, NC, nsplit, col, head * 128 + i, num / den);
+  const int k = head * 128 + i;
+  if constexpr (FRAG) {
+    // nsplit bf16 pieces per value; token tile q occupies column tiles q * nsplit + piece
+    const int t = cm.row0 + col, KT = nq * 4;  // k tiles of the operand: nq * 128 / 32
+    float v = num / den;
+    for (int pc = 0; pc < nsplit; ++pc) {
+      const uint32_t h = bf16_bits(v);
+      v -= bf16_to_f32(h);
+      const size_t e =
+          (((size_t)((t >> 4) * nsplit + pc) * KT + (k >> 5)) * 64 + (t & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
+      static_cast<uint16_t*>(Op)[e] = (uint16_t)h;
+    }
+  } else {
+    store_packed<F32>(Op, NC, nsplit, col, k, num / den);
+  }
 }
 
 hipError_t launch_attn_combine(hipStream_t s, bool f32, const float* partial, int max_chunks, int nq,
-                               const ColState* st, int ncols, void* Op, int NC, int nsplit) {
+                               const ColMap& cm, int ncols, void* Op, int NC, int nsplit, bool frag) {
   dim3 grid(nq, ncols);
-  if (f32)
-    k_attn_combine<true><<<grid, 128, 0, s>>>(partial, max_chunks, nq, st, Op, NC, nsplit);
-  else
-    k_attn_combine<false><<<grid, 128, 0, s>>>(partial, max_chunks, nq, st, Op, NC, nsplit);
+  if (frag) {
+    if (f32) return hipErrorInvalidValue;
+    k_attn_combine<false, true><<<grid, 128, 0, s>>>(partial, max_chunks, nq, cm, Op, NC, nsplit);
+  } else if (f32) {
+    k_attn_combine<true, false><<<grid, 128, 0, s>>>(partial, max_chunks, nq, cm, Op, NC, nsplit);
+  } else {
+    k_attn_combine<false, false><<<grid, 128, 0, s>>>(partial, max_chunks, nq, cm, Op, NC, nsplit);
+  }
   return hipGetLastError();
 }
 

@@ -1,0 +1,291 @@
+// Prompt-pass kernels for large token blocks (bf16 models): an LDS-staged matrix-core GEMM
+// over the packed weights, and the row-wise passes that produce its operands.
+//
+// This is the compute-bound side of the path: with T tokens every weight byte is used T
+// times, so the matmuls run at matrix-core speed, not HBM speed.  As in the paper's packed
+// "pass-through" chain (Section 3.1.2, Eq. (1)) activations stay in the blocked layout of
+// the tensor unit between operators: norms, the SwiGLU epilogue and the attention merge
+// write bf16 values directly in the fragment order the next GEMM loads, and nothing is
+// unpacked in between.  Activations entering a GEMM are rounded to bf16 once (round to
+// nearest even): that is the precision contract of this path.
+#include "nnc_internal.h"
+
+namespace nnc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+__device__ __forceinline__ uint32_t bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// Workgroup barrier that orders LDS traffic only: the global loads of the register ring stay
+// in flight across it (a plain __syncthreads() would wait for all of them at every k step).
+__device__ __forceinline__ void lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Block tile: NT row tiles (16 rows each) x 8 column tiles (16 operand columns each), k step
+// 32.  4 waves in a 2 x 2 arrangement, each NT/2 x 4 accumulator tiles.  NT = 16 (256 rows)
+// for large token counts; NT = 4 (64 rows) gives four times as many workgroups when the
+// prompt is short and the launch would otherwise leave most of the chip idle.
+// PIECES = 1: one bf16 per activation, a column tile is 16 tokens.  PIECES = 2: every
+// activation is carried as two bf16 pieces (value, remainder) in adjacent column tiles, whose
+// products the epilogue adds: fp32-grade activations at twice the matrix-core work, which is
+// free while the GEMM is bound by streaming the weights (short prompts).
+constexpr int PG_TT = 8;  // column tiles per block
+
+}  // namespace
+
+// Both operands are already stored in fragment order in memory (1 KiB per 16 x 32 tile, one
+// 16-byte element per lane), so staging is a straight copy: global -> registers -> LDS, and
+// every LDS access is a conflict-free 16-byte access at lane * 16.  Double-buffered in LDS,
+// fed from a register ring several k steps deep; one workgroup barrier per k step.
+template <int EPI, int NT, int PIECES>
+__global__ __launch_bounds__(256) void k_gemm_prefill(PrefillGemmArgs a) {
+  constexpr int WI = NT / 2;   // row tiles per wave
+  constexpr int AL = NT / 4;   // 16-byte A loads per thread and k step
+  __shared__ uint4 As[2][NT][64];
+  __shared__ uint4 Bs[2][PG_TT][64];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wn = wave >> 1, wt = wave & 1;
+  const int KT = a.KT;
+  const int nt0 = blockIdx.x * NT, tt0 = blockIdx.y * PG_TT;
+  const uint4* __restrict__ W = static_cast<const uint4*>(a.Wp);
+  const uint4* __restrict__ X = static_cast<const uint4*>(a.Xf);
+
+  f32x4 acc[WI][4];
+#pragma unroll
+  for (int i = 0; i < WI; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // Register ring of D k steps: the loads of step kt + D are issued when step kt starts, so D
+  // steps of matrix-core work cover the memory latency even with one workgroup per CU.
+  constexpr int D = NT == 16 ? 4 : 8;
+  uint4 ra[D][AL], rb[D][2];
+  auto gload = [&](int st, int kt) {
+#pragma unroll
+    for (int j = 0; j < AL; ++j) {
+      const int idx = tid + 256 * j, tile = idx >> 6, ln = idx & 63;
+      ra[st][j] = nt0 + tile < a.n_tiles ? W[((size_t)(nt0 + tile) * KT + kt) * 64 + ln] : uint4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int idx = tid + 256 * j, tile = idx >> 6, ln = idx & 63;
+      rb[st][j] = tt0 + tile < a.t_tiles ? X[((size_t)(tt0 + tile) * KT + kt) * 64 + ln] : uint4{0, 0, 0, 0};
+    }
+  };
+  auto sstore = [&](int st, int buf) {
+#pragma unroll
+    for (int j = 0; j < AL; ++j) {
+      const int idx = tid + 256 * j;
+      As[buf][idx >> 6][idx & 63] = ra[st][j];
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int idx = tid + 256 * j;
+      Bs[buf][idx >> 6][idx & 63] = rb[st][j];
+    }
+  };
+
+#pragma unroll
+  for (int d = 0; d < D; ++d)
+    if (d < KT) gload(d, d);
+  sstore(0, 0);
+  lds_sync();
+  for (int kt0 = 0; kt0 < KT; kt0 += D) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      const int kt = kt0 + d;  // ring stage d held step kt (already in LDS); D is even: buffer d & 1
+      if (kt < KT) {
+        if (kt + D < KT) gload(d, kt + D);
+        uint4 af[WI], bf[4];
+#pragma unroll
+        for (int i = 0; i < WI; ++i) af[i] = As[d & 1][wn * WI + i][lane];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bf[j] = Bs[d & 1][wt * 4 + j][lane];
+#pragma unroll
+        for (int i = 0; i < WI; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8, af[i]), __builtin_bit_cast(bf16x8, bf[j]), acc[i][j], 0, 0, 0);
+        if (kt + 1 < KT) sstore((d + 1) % D, (d + 1) & 1);
+        lds_sync();
+      }
+    }
+  }
+
+  // accumulator element e of lane l in tile (i, j): row (l / 16) * 4 + e of row tile i,
+  // operand column l % 16 of column tile j.  With two pieces, column tiles 2q and 2q+1 are
+  // the two pieces of token tile q and their accumulators are added.
+  const int c16 = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int j = 0; j < 4; j += PIECES) {
+    const int ct = tt0 + wt * 4 + j;  // column tile
+    if (ct >= a.t_tiles) continue;
+    const int tt = ct / PIECES;        // token tile
+    const size_t t = (size_t)tt * 16 + c16;
+    f32x4 v[WI];
+#pragma unroll
+    for (int i = 0; i < WI; ++i) {
+      v[i] = acc[i][j];
+      if constexpr (PIECES == 2) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[i][e] += acc[i][j + 1][e];
+      }
+    }
+    if constexpr (EPI == EPI_SWIGLU) {
+      // row tiles come as (gate, up) pairs; feature tile = row tile / 2
+      const int FKT = a.n_tiles / 4;  // k tiles of the next GEMM: features / 32
+#pragma unroll
+      for (int i = 0; i < WI; i += 2) {
+        const int nt = nt0 + wn * WI + i;
+        if (nt >= a.n_tiles) continue;
+        const int f0 = (nt >> 1) * 16 + g * 4;
+        uint32_t h[PIECES][4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float gate = v[i][e], up = v[i + 1][e];
+          float act = gate / (1.0f + expf(-gate)) * up;
+#pragma unroll
+          for (int pc = 0; pc < PIECES; ++pc) {
+            h[pc][e] = bf16_bits(act);
+            act -= bf16_to_f32(h[pc][e]);
+          }
+        }
+        // features f0 .. f0+3 of token t: 8 bytes inside one 16-byte fragment element
+#pragma unroll
+        for (int pc = 0; pc < PIECES; ++pc) {
+          const size_t el =
+              (((size_t)(tt * PIECES + pc) * FKT + (f0 >> 5)) * 64 + c16 + 16 * ((f0 & 31) >> 3)) * 8 + (f0 & 7);
+          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.packed_out) + el) =
+              make_uint2(h[pc][0] | (h[pc][1] << 16), h[pc][2] | (h[pc][3] << 16));
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < WI; ++i) {
+        const int nt = nt0 + wn * WI + i;
+        if (nt >= a.n_tiles) continue;
+        float4* dst = reinterpret_cast<float4*>(a.out + t * a.ldo + (size_t)nt * 16 + g * 4);
+        float4 o = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
+        if constexpr (EPI == EPI_RESID) {
+          const float4 p = *dst;
+          o = make_float4(p.x + o.x, p.y + o.y, p.z + o.z, p.w + o.w);
+        }
+        *dst = o;
+      }
+    }
+  }
+}
+
+// a.t_tiles counts operand column tiles (token tiles x pieces).
+hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a, int pieces, bool small_tiles) {
+  if (a.n_tiles <= 0 || a.t_tiles <= 0 || a.KT <= 0 || (pieces != 1 && pieces != 2) || a.t_tiles % pieces)
+    return hipErrorInvalidValue;
+  if (epi == EPI_SWIGLU && a.n_tiles % 4) return hipErrorInvalidValue;
+  const int NT = small_tiles ? 4 : 16;
+  dim3 grid((a.n_tiles + NT - 1) / NT, (a.t_tiles + PG_TT - 1) / PG_TT);
+#define PG_LAUNCH(E)                                                              \
+  do {                                                                            \
+    if (small_tiles) {                                                            \
+      if (pieces == 2) k_gemm_prefill<E, 4, 2><<<grid, 256, 0, s>>>(a);           \
+      else k_gemm_prefill<E, 4, 1><<<grid, 256, 0, s>>>(a);                       \
+    } else {                                                                      \
+      if (pieces == 2) k_gemm_prefill<E, 16, 2><<<grid, 256, 0, s>>>(a);          \
+      else k_gemm_prefill<E, 16, 1><<<grid, 256, 0, s>>>(a);                      \
+    }                                                                             \
+  } while (0)
+  switch (epi) {
+    case EPI_STORE: PG_LAUNCH(EPI_STORE); break;
+    case EPI_RESID: PG_LAUNCH(EPI_RESID); break;
+    case EPI_SWIGLU: PG_LAUNCH(EPI_SWIGLU); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef PG_LAUNCH
+  return hipGetLastError();
+}
+
+// One workgroup per token row: h = x / sqrt(mean(x^2) + eps) * g as `pieces` bf16 values
+// (value, remainder), written in fragment order: token tile q occupies column tiles
+// q * pieces + piece.  Rows beyond n_rows are zero-filled so that padded tiles are defined.
+__global__ __launch_bounds__(256) void k_rmsnorm_frag(const float* __restrict__ x, const float* __restrict__ gain,
+                                                      int H, float eps, int n_rows, int pieces,
+                                                      void* __restrict__ Xf) {
+  __shared__ float sm[4];
+  const int t = blockIdx.x, KT = H / 32;
+  uint4* out = static_cast<uint4*>(Xf) + ((size_t)(t >> 4) * pieces * KT) * 64 + (t & 15);
+  const size_t piece_stride = (size_t)KT * 64;
+  if (t >= n_rows) {
+    for (int kg = threadIdx.x; kg < H / 8; kg += 256)
+      for (int pc = 0; pc < pieces; ++pc)
+        out[pc * piece_stride + (size_t)(kg >> 2) * 64 + 16 * (kg & 3)] = uint4{0, 0, 0, 0};
+    return;
+  }
+  const float* xr = x + (size_t)t * H;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < H; i += 256) ss += xr[i] * xr[i];
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float r = 1.0f / sqrtf(((sm[0] + sm[1]) + (sm[2] + sm[3])) / (float)H + eps);
+  for (int kg = threadIdx.x; kg < H / 8; kg += 256) {
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = xr[kg * 8 + e] * r * gain[kg * 8 + e];
+    for (int pc = 0; pc < pieces; ++pc) {
+      uint32_t h[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        h[e] = bf16_bits(v[e]);
+        v[e] -= bf16_to_f32(h[e]);
+      }
+      out[pc * piece_stride + (size_t)(kg >> 2) * 64 + 16 * (kg & 3)] =
+          uint4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+    }
+  }
+}
+
+hipError_t launch_rmsnorm_frag(hipStream_t s, const float* x, const float* gain, int H, float eps, int n_rows,
+                               int token_tiles, int pieces, void* Xf) {
+  k_rmsnorm_frag<<<token_tiles * 16, 256, 0, s>>>(x, gain, H, eps, n_rows, pieces, Xf);
+  return hipGetLastError();
+}
+
+// x[t][k] = E[tokens[t]][k] from the packed bf16 embedding matrix.
+__global__ __launch_bounds__(256) void k_embed_rows(const void* __restrict__ Ep, int H,
+                                                    const int32_t* __restrict__ tokens, float* __restrict__ x) {
+  const int t = blockIdx.x, r = tokens[t], KT = H / 32;
+  const uint4* row = static_cast<const uint4*>(Ep) + ((size_t)(r >> 4) * KT) * 64 + (r & 15);
+  for (int kg = threadIdx.x; kg < H / 8; kg += 256) {
+    const uint4 v = row[(size_t)(kg >> 2) * 64 + 16 * (kg & 3)];
+    float* dst = x + (size_t)t * H + kg * 8;
+    *reinterpret_cast<float4*>(dst) = make_float4(bf16_to_f32(v.x & 0xffffu), bf16_to_f32(v.x >> 16),
+                                                  bf16_to_f32(v.y & 0xffffu), bf16_to_f32(v.y >> 16));
+    *reinterpret_cast<float4*>(dst + 4) = make_float4(bf16_to_f32(v.z & 0xffffu), bf16_to_f32(v.z >> 16),
+                                                      bf16_to_f32(v.w & 0xffffu), bf16_to_f32(v.w >> 16));
+  }
+}
+
+hipError_t launch_embed_rows(hipStream_t s, const void* Ep, int H, const int32_t* tokens_dev, int n, float* x) {
+  k_embed_rows<<<n, 256, 0, s>>>(Ep, H, tokens_dev, x);
+  return hipGetLastError();
+}
+
+}  // namespace nnc

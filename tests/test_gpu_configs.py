@@ -3,7 +3,8 @@
 config 0: one Qwen3-0.6B-shaped layer, fp32, 16-token prompt + 16 decode steps,
           hidden states compared row by row, infinity-norm relative error <= 1e-4.
 config 1: full Qwen3-0.6B-shaped model, bf16 weights and KV cache, fp32 accumulation,
-          128-token prompt + 128 greedy steps: max abs logit error <= 3e-2 at the prompt's
+          128-token prompt (large-block matrix-core path, two bf16 pieces per GEMM input)
+          + 128 greedy steps: max abs logit error <= 3e-2 at the prompt's
           last position and at every decode step (teacher-forced on the oracle's tokens),
           greedy tokens equal at every step, and the free-running on-device greedy loop
           (the launch configuration bench.py times) reproduces the oracle's tokens.
@@ -54,6 +55,8 @@ def test_config1_qwen3_0p6b_bf16_prompt128_decode128(nnc):
     fl = oracle_flags(shape)
     toks = synth.tokens(T, shape.vocab)
 
+    # prompt pass: 128 tokens run on the large-block path with two bf16 pieces per GEMM input
+    # (fp32-grade), so the oracle runs unrounded activations
     lo, first = o.prefill(0, toks, fl)
     lg, ng = g.prefill(0, toks)
     err = np.abs(lg.double().cpu().numpy() - lo).max()
