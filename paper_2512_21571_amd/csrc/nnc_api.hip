@@ -97,7 +97,7 @@ struct nnc_model {
   unsigned mk_tag = 1;  // next unused exchange tag
   void* mk_layers = nullptr;
   unsigned* mk_error = nullptr;
-  void *mk_xq = nullptr, *mk_xatt = nullptr, *mk_xop = nullptr, *mk_xact = nullptr, *mk_xdp = nullptr,
+  void *mk_xq = nullptr, *mk_xatt = nullptr, *mk_xo = nullptr, *mk_xop = nullptr, *mk_xact = nullptr, *mk_xdp = nullptr,
        *mk_xamv = nullptr, *mk_xami = nullptr;
   unsigned long long* mk_trace = nullptr;
   int mk_trace_step = -1;
@@ -464,7 +464,7 @@ nnc_status persistent_steps(nnc_model* m, uint32_t slot, int32_t token, uint32_t
   MkBuffers b{};
   b.layers = m->mk_layers; b.embed = m->embed; b.lm_head = m->lm_head; b.g_final = m->g_final; b.rope = m->rope;
   b.error = m->mk_error;
-  b.xq = m->mk_xq; b.xatt = m->mk_xatt; b.xop = m->mk_xop; b.xact = m->mk_xact; b.xdp = m->mk_xdp;
+  b.xq = m->mk_xq; b.xatt = m->mk_xatt; b.xo = m->mk_xo; b.xop = m->mk_xop; b.xact = m->mk_xact; b.xdp = m->mk_xdp;
   b.xamv = m->mk_xamv; b.xami = m->mk_xami;
   b.logits = logits_out; b.token_log = m->token_log;
   b.trace = m->mk_trace_step >= 0 ? m->mk_trace : nullptr;
@@ -673,6 +673,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
       m->mk_error = static_cast<unsigned*>(err);
       TRY_OR_BAIL(zeroed(m->mk_xq, (Dq + 2 * Dkv) * 8));
       TRY_OR_BAIL(zeroed(m->mk_xatt, (size_t)c.n_q_heads * m->max_chunks * 132 * 8));
+      TRY_OR_BAIL(zeroed(m->mk_xo, Dq * 8));
       TRY_OR_BAIL(zeroed(m->mk_xop, 4 * H * 8));
       TRY_OR_BAIL(zeroed(m->mk_xact, F * 8));
       TRY_OR_BAIL(zeroed(m->mk_xdp, 4 * H * 8));

@@ -51,6 +51,7 @@ constexpr int MK_WAVES = MK_THREADS / 64;
 constexpr unsigned MK_SPIN_MAX = 1u << 20;
 constexpr int MK_PF = 8;      // prefetched 16-byte weight loads per lane and 16-row tile (32 KiB per workgroup)
 constexpr int MK_MAX_KS = 4;  // k slices of a narrow projection
+constexpr int MK_DIRECT_MERGE_MAX = 4;  // attention chunks up to which every output-projection unit merges by itself
 
 // ---- memory-side accesses ----------------------------------------------------
 __device__ __forceinline__ unsigned ld_u32(const unsigned* p) {
@@ -135,6 +136,7 @@ struct MkArgs {
   u64* xq;    // [Dq + 2 Dkv] raw q | k | v
   u64* xatt;  // [nq][max_chunks][132] attention partials: 128 sums, max, sum
   int max_chunks;
+  u64* xo;    // [Dq] merged attention output (used when the context spans many chunks)
   u64* xop;   // [ks_o][H]
   u64* xact;  // [F]
   u64* xdp;   // [ks_d][H]
@@ -284,53 +286,57 @@ __device__ __forceinline__ float tile_total(const Smem& sm, int rt, int row) {
 template <int NP>
 __device__ __forceinline__ void add_exchanged(const MkArgs& a, Smem& sm, float2 (&x)[NP], int H, const u64* buf, int ks,
                                               unsigned tag) {
-  unsigned spins = 0;
+  constexpr int JB = NP < 4 ? NP : 4;  // pairs per thread whose words are in flight together
   const int tid = opaque(threadIdx.x);
-  for (;;) {
-    u64 w[NP][MK_MAX_KS][2];
 #pragma unroll
-    for (int j = 0; j < NP; ++j) {
-      const int k = 2 * (tid + MK_THREADS * j);
-      if (k < H) {
+  for (int j0 = 0; j0 < NP; j0 += JB) {
+    unsigned spins = 0;
+    for (;;) {
+      u64 w[JB][MK_MAX_KS][2];
 #pragma unroll
-        for (int p = 0; p < MK_MAX_KS; ++p)
-          if (p < ks) {
-            w[j][p][0] = ld_t(buf + (size_t)p * H + k);
-            w[j][p][1] = ld_t(buf + (size_t)p * H + k + 1);
-          }
-      }
-    }
-    bool ok = true;
-#pragma unroll
-    for (int j = 0; j < NP; ++j) {
-      const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
-      if (k < H) {
-#pragma unroll
-        for (int p = 0; p < MK_MAX_KS; ++p)
-          if (p < ks) ok = ok && t_ok(w[j][p][0], tag) && t_ok(w[j][p][1], tag);
-      }
-    }
-    if (ok) {
-#pragma unroll
-      for (int j = 0; j < NP; ++j) {
-        const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
+      for (int j = 0; j < JB; ++j) {
+        const int k = 2 * (tid + MK_THREADS * (j0 + j));
         if (k < H) {
-          float2 add = make_float2(t_val(w[j][0][0]), t_val(w[j][0][1]));
 #pragma unroll
-          for (int p = 1; p < MK_MAX_KS; ++p)
+          for (int p = 0; p < MK_MAX_KS; ++p)
             if (p < ks) {
-              add.x += t_val(w[j][p][0]);
-              add.y += t_val(w[j][p][1]);
+              w[j][p][0] = ld_t(buf + (size_t)p * H + k);
+              w[j][p][1] = ld_t(buf + (size_t)p * H + k + 1);
             }
-          x[j].x += add.x;
-          x[j].y += add.y;
         }
       }
-      return;
-    }
-    if (spin_over(a, spins)) {
-      give_up(a, sm);
-      return;
+      bool ok = true;
+#pragma unroll
+      for (int j = 0; j < JB; ++j) {
+        const int k = 2 * ((int)threadIdx.x + MK_THREADS * (j0 + j));
+        if (k < H) {
+#pragma unroll
+          for (int p = 0; p < MK_MAX_KS; ++p)
+            if (p < ks) ok = ok && t_ok(w[j][p][0], tag) && t_ok(w[j][p][1], tag);
+        }
+      }
+      if (ok) {
+#pragma unroll
+        for (int j = 0; j < JB; ++j) {
+          const int k = 2 * ((int)threadIdx.x + MK_THREADS * (j0 + j));
+          if (k < H) {
+            float2 add = make_float2(t_val(w[j][0][0]), t_val(w[j][0][1]));
+#pragma unroll
+            for (int p = 1; p < MK_MAX_KS; ++p)
+              if (p < ks) {
+                add.x += t_val(w[j][p][0]);
+                add.y += t_val(w[j][p][1]);
+              }
+            x[j0 + j].x += add.x;
+            x[j0 + j].y += add.y;
+          }
+        }
+        break;
+      }
+      if (spin_over(a, spins)) {
+        give_up(a, sm);
+        return;
+      }
     }
   }
 }
@@ -412,7 +418,6 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
   const int qkv_tiles = Nqkv / 16, o_tiles = H / 16, gu_pairs = F / 16, v_tiles = V / 16;
   const int kts_o = (KTQ + a.ks_o - 1) / a.ks_o, kts_d = (KTF + a.ks_d - 1) / a.ks_d;
   const int o_units = o_tiles * a.ks_o, d_units = o_tiles * a.ks_d;
-  const int att_units = nkv * a.max_chunks;
   const unsigned tags_per_step = 5u * (unsigned)a.n_layers + 1u;
 
   // optional stage trace: thread 0 stamps the 100 MHz wall clock at stage boundaries
@@ -474,10 +479,10 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
       stamp(step);  // 2: q | k | v published
 
       // ============ stage 2: QK-norm + RoPE + KV append + attention partials ============
-      for (int u = wg_att; u < att_units; u += nwg) {
-        const int chunk = u % a.max_chunks, kvh = u / a.max_chunks;
+      const int nch = (int)(pos / ATT_CHUNK) + 1;  // chunks that hold positions 0 .. pos
+      for (int u = wg_att; u < nkv * nch; u += nwg) {
+        const int chunk = u % nch, kvh = u / nch;
         const uint32_t j0 = (uint32_t)chunk * ATT_CHUNK;
-        if (j0 > pos) continue;  // uniform per workgroup
         const bool owns_new = pos - j0 < ATT_CHUNK;
         const size_t cbase = ((size_t)a.slot * nkv + kvh) * a.max_seq * 128;
         const int c16 = lane & 15, jj = lane >> 4;
@@ -651,82 +656,197 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
         pf_issue<1>(pf5, L.wd, (size_t)td, KTF, sd * kts_d, min(KTF, (sd + 1) * kts_d));
       }
       // ============ stage 3: merge attention chunks + output projection ============
-      const int nch = (int)(pos / ATT_CHUNK) + 1;
-      for (int u = wg_o; u < o_units; u += nwg) {
-        const int t = u / a.ks_o, s = u % a.ks_o;
-        const int kt0 = s * kts_o, kt1 = min(KTQ, (s + 1) * kts_o);
-        wg_sync();
-        // two (k, k+1) pairs per thread at a time, four chunk records each, all in flight together
-        for (int kb = kt0 * 32 + 2 * tid; kb < kt1 * 32; kb += 4 * MK_THREADS) {
-          float M[2], n0[2], n1[2], den[2];
-#pragma unroll
-          for (int r = 0; r < 2; ++r) {
-            M[r] = -INFINITY;
-            n0[r] = n1[r] = den[r] = 0.f;
-          }
-          for (int c0 = 0; c0 < nch; c0 += 4) {
-            u64 wm[2][4], wl[2][4], wa[2][4], wb[2][4];
+      // Few chunks: every output-projection unit merges the chunk records of its k range itself
+      // (no extra exchange).  Many chunks: that repeated merge would dominate, so one workgroup
+      // per query head merges its records once and publishes the head's output, at the cost of
+      // one more exchange.
+      const bool merged = nch > MK_DIRECT_MERGE_MAX;
+      if (merged) {
+        for (int h = nwg - 1 - wg_att; h < nq; h += nwg) {
+          wg_sync();
+          // wave w takes chunks w, w + 4, ...; lane l the sums of dimensions l and l + 64
+          const u64* rec0 = a.xatt + (size_t)h * a.max_chunks * 132;
+          float M = -INFINITY, n0 = 0.f, n1 = 0.f, den = 0.f;
+          for (int c0 = wave; c0 < nch; c0 += 4 * MK_WAVES) {
+            u64 wm[4], wl[4], wa[4], wb[4];
             unsigned spins = 0;
             for (;;) {
               bool ok = true;
 #pragma unroll
-              for (int r = 0; r < 2; ++r) {
-                const int k = kb + 2 * MK_THREADS * r;
-                if (k < kt1 * 32) {
-                  const u64* rec0 = a.xatt + (size_t)(k >> 7) * a.max_chunks * 132;
-#pragma unroll
-                  for (int q = 0; q < 4; ++q) {
-                    const u64* rec = rec0 + (size_t)min(c0 + q, nch - 1) * 132;
-                    wm[r][q] = ld_t(rec + 128);
-                    wl[r][q] = ld_t(rec + 129);
-                    wa[r][q] = ld_t(rec + (k & 127));
-                    wb[r][q] = ld_t(rec + (k & 127) + 1);
-                  }
-                }
+              for (int q = 0; q < 4; ++q) {
+                const u64* rec = rec0 + (size_t)min(c0 + MK_WAVES * q, nch - 1) * 132;
+                wm[q] = ld_t(rec + 128);
+                wl[q] = ld_t(rec + 129);
+                wa[q] = ld_t(rec + lane);
+                wb[q] = ld_t(rec + lane + 64);
               }
 #pragma unroll
-              for (int r = 0; r < 2; ++r)
-                if (kb + 2 * MK_THREADS * r < kt1 * 32) {
-#pragma unroll
-                  for (int q = 0; q < 4; ++q)
-                    ok = ok && t_ok(wm[r][q], t_att) && t_ok(wl[r][q], t_att) && t_ok(wa[r][q], t_att) &&
-                         t_ok(wb[r][q], t_att);
-                }
+              for (int q = 0; q < 4; ++q)
+                ok = ok && t_ok(wm[q], t_att) && t_ok(wl[q], t_att) && t_ok(wa[q], t_att) && t_ok(wb[q], t_att);
               if (ok) break;
               if (spin_over(a, spins)) {
                 give_up(a, sm);
                 break;
               }
             }
-            // online merge of the chunk records
+            float Mn = M;
 #pragma unroll
-            for (int r = 0; r < 2; ++r)
-              if (kb + 2 * MK_THREADS * r < kt1 * 32) {
-                float Mn = M[r];
+            for (int q = 0; q < 4; ++q)
+              if (c0 + MK_WAVES * q < nch) Mn = fmaxf(Mn, t_val(wm[q]));
+            const float sc = expf(M - Mn);  // 0 on the first group (M = -inf)
+            n0 *= sc;
+            n1 *= sc;
+            den *= sc;
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                  if (c0 + q < nch) Mn = fmaxf(Mn, t_val(wm[r][q]));
-                const float sc = expf(M[r] - Mn);  // 0 on the first group (M = -inf)
-                n0[r] *= sc;
-                n1[r] *= sc;
-                den[r] *= sc;
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                  if (c0 + q < nch) {
-                    const float f = expf(t_val(wm[r][q]) - Mn);
-                    n0[r] += f * t_val(wa[r][q]);
-                    n1[r] += f * t_val(wb[r][q]);
-                    den[r] += f * t_val(wl[r][q]);
-                  }
-                M[r] = Mn;
+            for (int q = 0; q < 4; ++q)
+              if (c0 + MK_WAVES * q < nch) {
+                const float f = expf(t_val(wm[q]) - Mn);
+                n0 += f * t_val(wa[q]);
+                n1 += f * t_val(wb[q]);
+                den += f * t_val(wl[q]);
               }
+            M = Mn;
           }
+          sm.ared[wave][0][lane] = n0;
+          sm.ared[wave][0][lane + 64] = n1;
+          if (lane == 0) {
+            sm.att_m[wave] = M;
+            sm.att_l[wave] = den;
+          }
+          wg_sync();
+          if (sm.abort) return;
+          if (tid < 128) {
+            float Mt = sm.att_m[0];
 #pragma unroll
-          for (int r = 0; r < 2; ++r) {
-            const int k = kb + 2 * MK_THREADS * r;
-            if (k < kt1 * 32) put_pair(opnd, k - kt0 * 32, make_float2(n0[r] / den[r], n1[r] / den[r]));
+            for (int w = 1; w < MK_WAVES; ++w) Mt = fmaxf(Mt, sm.att_m[w]);
+            float num = 0.f, dn = 0.f;
+#pragma unroll
+            for (int w = 0; w < MK_WAVES; ++w) {
+              const float f = expf(sm.att_m[w] - Mt);  // waves without a chunk: exp(-inf) = 0
+              num += f * sm.ared[w][0][tid];
+              dn += f * sm.att_l[w];
+            }
+            st_t(a.xo + (size_t)h * 128 + tid, num / dn, t_att);
           }
         }
+      }
+      // The operand of a unit is its k slice of the attention output; a workgroup's units
+      // usually share the slice (workgroups % slices == 0), which is then loaded once.
+      int s_loaded = -1;
+      for (int u = wg_o; u < o_units; u += nwg) {
+        const int t = u / a.ks_o, s = u % a.ks_o;
+        const int kt0 = s * kts_o, kt1 = min(KTQ, (s + 1) * kts_o);
+        wg_sync();
+        if (s == s_loaded) {
+          // operand already in LDS
+        } else if (merged) {
+          // four (k, k+1) pairs of the merged output per thread at a time, loaded together
+          for (int kb = kt0 * 32 + 2 * tid; kb < kt1 * 32; kb += 8 * MK_THREADS) {
+            unsigned spins = 0;
+            for (;;) {
+              u64 w[4][2];
+              bool ok = true;
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                const int k = kb + 2 * MK_THREADS * j;
+                if (k < kt1 * 32) {
+                  w[j][0] = ld_t(a.xo + k);
+                  w[j][1] = ld_t(a.xo + k + 1);
+                }
+              }
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                const int k = kb + 2 * MK_THREADS * j;
+                if (k < kt1 * 32) ok = ok && t_ok(w[j][0], t_att) && t_ok(w[j][1], t_att);
+              }
+              if (ok) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                  const int k = kb + 2 * MK_THREADS * j;
+                  if (k < kt1 * 32) put_pair(opnd, k - kt0 * 32, make_float2(t_val(w[j][0]), t_val(w[j][1])));
+                }
+                break;
+              }
+              if (spin_over(a, spins)) {
+                give_up(a, sm);
+                break;
+              }
+            }
+          }
+        } else {
+          // two (k, k+1) pairs per thread at a time, four chunk records each, all in flight together
+          for (int kb = kt0 * 32 + 2 * tid; kb < kt1 * 32; kb += 4 * MK_THREADS) {
+            float M[2], n0[2], n1[2], den[2];
+  #pragma unroll
+            for (int r = 0; r < 2; ++r) {
+              M[r] = -INFINITY;
+              n0[r] = n1[r] = den[r] = 0.f;
+            }
+            for (int c0 = 0; c0 < nch; c0 += 4) {
+              u64 wm[2][4], wl[2][4], wa[2][4], wb[2][4];
+              unsigned spins = 0;
+              for (;;) {
+                bool ok = true;
+  #pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                  const int k = kb + 2 * MK_THREADS * r;
+                  if (k < kt1 * 32) {
+                    const u64* rec0 = a.xatt + (size_t)(k >> 7) * a.max_chunks * 132;
+  #pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                      const u64* rec = rec0 + (size_t)min(c0 + q, nch - 1) * 132;
+                      wm[r][q] = ld_t(rec + 128);
+                      wl[r][q] = ld_t(rec + 129);
+                      wa[r][q] = ld_t(rec + (k & 127));
+                      wb[r][q] = ld_t(rec + (k & 127) + 1);
+                    }
+                  }
+                }
+  #pragma unroll
+                for (int r = 0; r < 2; ++r)
+                  if (kb + 2 * MK_THREADS * r < kt1 * 32) {
+  #pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                      ok = ok && t_ok(wm[r][q], t_att) && t_ok(wl[r][q], t_att) && t_ok(wa[r][q], t_att) &&
+                           t_ok(wb[r][q], t_att);
+                  }
+                if (ok) break;
+                if (spin_over(a, spins)) {
+                  give_up(a, sm);
+                  break;
+                }
+              }
+              // online merge of the chunk records
+  #pragma unroll
+              for (int r = 0; r < 2; ++r)
+                if (kb + 2 * MK_THREADS * r < kt1 * 32) {
+                  float Mn = M[r];
+  #pragma unroll
+                  for (int q = 0; q < 4; ++q)
+                    if (c0 + q < nch) Mn = fmaxf(Mn, t_val(wm[r][q]));
+                  const float sc = expf(M[r] - Mn);  // 0 on the first group (M = -inf)
+                  n0[r] *= sc;
+                  n1[r] *= sc;
+                  den[r] *= sc;
+  #pragma unroll
+                  for (int q = 0; q < 4; ++q)
+                    if (c0 + q < nch) {
+                      const float f = expf(t_val(wm[r][q]) - Mn);
+                      n0[r] += f * t_val(wa[r][q]);
+                      n1[r] += f * t_val(wb[r][q]);
+                      den[r] += f * t_val(wl[r][q]);
+                    }
+                  M[r] = Mn;
+                }
+            }
+  #pragma unroll
+            for (int r = 0; r < 2; ++r) {
+              const int k = kb + 2 * MK_THREADS * r;
+              if (k < kt1 * 32) put_pair(opnd, k - kt0 * 32, make_float2(n0[r] / den[r], n1[r] / den[r]));
+            }
+          }
+        }
+        s_loaded = s;
         wg_sync();
         if (sm.abort) return;
         if (u == wg_o)
@@ -764,12 +884,13 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
       if (wg < qkv_tiles && (li + 1 < a.n_layers || step + 1 < a.n_steps))
         pf_issue<1>(pf1, a.layers[li + 1 < a.n_layers ? li + 1 : 0].wqkv, (size_t)wg, KTH, 0, KTH);
       // ============ stage 5: down projection (k slices) ============
+      s_loaded = -1;
       for (int u = wg_d; u < d_units; u += nwg) {
         const int t = u / a.ks_d, s = u % a.ks_d;
         const int kt0 = s * kts_d, kt1 = min(KTF, (s + 1) * kts_d);
         wg_sync();
         // four (k, k+1) pairs per thread at a time, loaded together
-        for (int kb = kt0 * 32 + 2 * tid; kb < kt1 * 32; kb += 8 * MK_THREADS) {
+        for (int kb = kt0 * 32 + 2 * tid; s != s_loaded && kb < kt1 * 32; kb += 8 * MK_THREADS) {
           unsigned spins = 0;
           for (;;) {
             u64 w[4][2];
@@ -801,6 +922,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
             }
           }
         }
+        s_loaded = s;
         wg_sync();
         if (sm.abort) return;
         if (u == wg_d)
@@ -998,6 +1120,7 @@ hipError_t launch_decode_resident(hipStream_t s, const MkPlan& p, const MkBuffer
   a.ks_o = p.ks_o; a.ks_d = p.ks_d;
   a.off_att = p.off_att % p.nwg; a.off_o = p.off_o % p.nwg; a.off_d = p.off_d % p.nwg;
   a.xq = static_cast<u64*>(bf.xq); a.xatt = static_cast<u64*>(bf.xatt); a.max_chunks = p.max_chunks;
+  a.xo = static_cast<u64*>(bf.xo);
   a.xop = static_cast<u64*>(bf.xop); a.xact = static_cast<u64*>(bf.xact); a.xdp = static_cast<u64*>(bf.xdp);
   a.xamv = static_cast<u64*>(bf.xamv); a.xami = static_cast<u64*>(bf.xami);
   a.logits = bf.logits; a.token_log = bf.token_log;

@@ -157,7 +157,7 @@ struct MkBuffers {
   const float2* rope;
   unsigned* error;  // single word, zero-initialised once
   // exchange buffers of 64-bit (value, tag) words, zero-initialised once
-  void *xq, *xatt, *xop, *xact, *xdp, *xamv, *xami;
+  void *xq, *xatt, *xo, *xop, *xact, *xdp, *xamv, *xami;
   float* logits;       // [n_steps][V] or NULL
   int32_t* token_log;  // [n_steps]
   unsigned long long* trace;  // [nwg][trace_points] or NULL
