@@ -90,3 +90,144 @@ def test_config1_qwen3_0p6b_bf16_prompt128_decode128(nnc):
     got, _ = g.decode_greedy([0], [first], S)
     got = got.cpu().numpy()[:, 0]
     assert np.array_equal(got, np.array(want_tokens))
+
+
+def _check_step(lg_row, lo, label, stats):
+    """One position: max abs logit error <= 3e-2; the greedy tokens agree unless the oracle's
+    top-2 margin is within 4x the measured error of that position (a tie within error)."""
+    got = lg_row.double().cpu().numpy()
+    assert np.isfinite(got).all(), label
+    e = float(np.abs(got - lo).max())
+    mg = top2_margin(lo)
+    stats["err"] = max(stats["err"], e)
+    stats["margin"] = min(stats["margin"], mg)
+    assert e <= 3e-2, (label, e)
+    if int(np.argmax(got)) != int(np.argmax(lo)):
+        assert mg < 4 * e, (label, mg, e)
+        stats["ties"].append(label)
+
+
+def test_config2_qwen3_1p7b_bf16_prompt512_decode(nnc):
+    print("case: config 2 (1.7B-shaped, bf16, prompt 512, decode)", flush=True)
+    shape = synth.SHAPES["qwen3-1.7b"]
+    T, S, S_ORACLE = 512, 256, 48
+    blob = synth.make_blob(shape)
+    g = nnc.Model(shape, blob, 1, T + S)
+    o = oracle.from_shape(shape, blob, 1, T + S)
+    fl = oracle_flags(shape)
+    toks = synth.tokens(T, shape.vocab)
+    stats = dict(err=0.0, margin=np.inf, ties=[])
+    lo, first = o.prefill(0, toks, fl)                      # 512 tokens: two bf16 pieces per GEMM input
+    lg, ng = g.prefill(0, toks)
+    _check_step(lg, lo, "prompt", stats)
+    print(f"  prompt: max abs err {stats['err']:.3e}, margin {stats['margin']:.3e}", flush=True)
+    # the first S_ORACLE decode steps against the oracle, teacher-forced on the oracle's tokens
+    want, t = [], first
+    for step in range(S_ORACLE):
+        lo, nxt = o.step_token(0, t, fl)
+        lg, _ = g.decode_step([0], [t])
+        _check_step(lg[0], lo, f"step {step}", stats)
+        want.append(nxt)
+        t = nxt
+    print(f"  {S_ORACLE} steps: max abs err {stats['err']:.3e}, min margin {stats['margin']:.3e}, "
+          f"ties within error {stats['ties']}", flush=True)
+    assert not stats["ties"]
+    # the whole 256-step on-device greedy loop (the timed configuration): its first S_ORACLE
+    # tokens are the oracle's, and a second run reproduces all 256 bit for bit
+    g.kv_reset(0)
+    g.prefill(0, toks, want_logits=False)
+    a, _ = g.decode_greedy([0], [first], S)
+    g.kv_reset(0)
+    g.prefill(0, toks, want_logits=False)
+    b, _ = g.decode_greedy([0], [first], S)
+    a, b = a.cpu().numpy()[:, 0], b.cpu().numpy()[:, 0]
+    assert np.array_equal(a[:S_ORACLE], np.array(want))
+    assert np.array_equal(a, b)
+
+
+def _sampled_depth(nnc, base, n_layers, long_ctx, batch, steps, label):
+    """Configs 3 and 4 at their real layer shape, vocabulary and context, with the depth cut to
+    what the fp64 oracle finishes in about a minute: slot 0 holds the full context (filled by the
+    large-block prompt path, single-bf16 GEMM inputs mirrored by the oracle), the other slots
+    short ragged contexts; then batched decode steps, every slot compared with the oracle."""
+    import dataclasses
+    shape = dataclasses.replace(synth.SHAPES[base], name=f"{base}-{n_layers}layers", n_layers=n_layers)
+    blob = synth.make_blob(shape)
+    g = nnc.Model(shape, blob, batch, long_ctx + steps + 8)
+    o = oracle.from_shape(shape, blob, batch, long_ctx + steps + 8)
+    fl = oracle_flags(shape)
+    stats = dict(err=0.0, margin=np.inf, ties=[])
+    lens = [long_ctx] + [24 + 37 * i for i in range(1, batch)]
+    t = []
+    for b, n in enumerate(lens):
+        toks = synth.tokens(n, shape.vocab, stream=b)
+        lg, _ = g.prefill(b, toks)
+        lo, nxt = o.prefill(b, toks, oracle_flags(shape, mirrored_prefill=n > 512))
+        _check_step(lg, lo, f"{label} prompt slot {b}", stats)
+        t.append(nxt)
+    print(f"  {label}: prompts max abs err {stats['err']:.3e}", flush=True)
+    slots = list(range(batch))
+    for step in range(steps):
+        lg, _ = g.decode_step(slots, t)
+        nxt = []
+        for b in slots:
+            lo, nb = o.step_token(b, t[b], fl)
+            _check_step(lg[b], lo, f"{label} step {step} slot {b}", stats)
+            nxt.append(nb)
+        t = nxt
+    # batch 1 on the long slot: the resident kernel with its merge stage
+    for step in range(steps):
+        lg, _ = g.decode_step([0], [t[0]])
+        lo, t[0] = o.step_token(0, t[0], fl)
+        _check_step(lg[0], lo, f"{label} b1 step {step}", stats)
+    print(f"  {label}: max abs err {stats['err']:.3e}, min margin {stats['margin']:.3e}, ties {stats['ties']}", flush=True)
+
+
+def test_config3_qwen3_4b_shape_sampled_depth(nnc):
+    print("case: config 3 layer shape (4B), 2 layers, context 2048, batch 8 and 1", flush=True)
+    _sampled_depth(nnc, "qwen3-4b", 2, 2048, 8, 3, "cfg3")
+
+
+def test_config4_qwen3_8b_shape_sampled_depth(nnc):
+    print("case: config 4 layer shape (8B), 1 layer, context 4096, batch 16 and 1", flush=True)
+    _sampled_depth(nnc, "qwen3-8b", 1, 4096, 16, 2, "cfg4")
+
+
+@pytest.mark.parametrize("name,batch,ctx", [("qwen3-4b", 8, 2048), ("qwen3-8b", 16, 4096)])
+def test_full_depth_batch_invariance(nnc, name, batch, ctx):
+    """Configs 3 and 4 at full depth (no oracle can follow): the same sequence gives the same
+    logits whether it is decoded alone or as one column of a full batch, and a replay of the
+    greedy loop is bit-identical."""
+    print(f"case: full-depth {name} batch {batch} context {ctx}", flush=True)
+    shape = synth.SHAPES[name]
+    blob = synth.make_blob(shape)
+    g = nnc.Model(shape, blob, batch, ctx + 24)
+    del blob
+    toks = synth.tokens(ctx, shape.vocab, stream=5)
+    _, first = g.prefill(0, toks)
+    first = int(first.item())
+    short = [16 + 9 * b for b in range(1, batch)]
+    firsts = [first]
+    for b, n in enumerate(short, start=1):
+        _, nx = g.prefill(b, synth.tokens(n, shape.vocab, stream=50 + b))
+        firsts.append(int(nx.item()))
+    slots = list(range(batch))
+    lg_b, _ = g.decode_step(slots, firsts)            # slot 0 as a column of the batch
+    row_b = lg_b[0].double().cpu().numpy()
+    assert np.isfinite(lg_b.cpu().numpy()).all()
+    # rewind slot 0 and decode it alone
+    g.kv_reset(0)
+    g.prefill(0, toks, want_logits=False)
+    lg_1, _ = g.decode_step([0], [first])
+    row_1 = lg_1[0].double().cpu().numpy()
+    err = np.abs(row_b - row_1).max()
+    print(f"  batch vs alone: max abs logit difference {err:.3e}, |logit| max {np.abs(row_1).max():.2f}", flush=True)
+    assert err <= 3e-3
+    # greedy loop replay on slot 0
+    g.kv_reset(0)
+    g.prefill(0, toks, want_logits=False)
+    a, _ = g.decode_greedy([0], [first], 8)
+    g.kv_reset(0)
+    g.prefill(0, toks, want_logits=False)
+    b, _ = g.decode_greedy([0], [first], 8)
+    assert np.array_equal(a.cpu().numpy(), b.cpu().numpy())
