@@ -7,8 +7,13 @@ fp32 accumulation, batch 1): reset the KV slot, run the 128-token prompt, then 1
 greedy decode steps with the token fed back on the device.  The paper's metric is
 tokens/s over the decoding stage (Section 5, experimental setup); `value` is that,
 summed over the K timed steps, with weights and prompt already resident in HBM.
+--workload selects the larger configurations (batched requests fill every slot's
+context with prompt passes, then decode all slots together).
 
-Prints ONE JSON line (see the design doc for the meaning of `roofline` and `cpu_baseline`).
+Prints ONE JSON line.  `roofline`: algorithmic bytes of the decode launches (every weight
+element and every cached K/V element once per step) over their duration, against the
+published HBM peak, plus the HBM traffic measured with counters where a summary for the
+workload is committed.  `cpu_baseline`: the fp64 CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
 
@@ -22,19 +27,23 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
 WORKLOADS = {
-    # name: (shape key, prompt tokens, decode steps)
-    "qwen3-0.6b-bf16-b1-p128-d128": ("qwen3-0.6b", 128, 128),
-    "qwen3-1.7b-bf16-b1-p512-d256": ("qwen3-1.7b", 512, 256),
+    # name: (shape key, batch, context tokens filled by the prompt pass per slot, decode steps)
+    "qwen3-0.6b-bf16-b1-p128-d128": ("qwen3-0.6b", 1, 128, 128),
+    "qwen3-1.7b-bf16-b1-p512-d256": ("qwen3-1.7b", 1, 512, 256),
+    "qwen3-4b-bf16-b1-c2048-d128": ("qwen3-4b", 1, 2048, 128),
+    "qwen3-4b-bf16-b8-c2048-d128": ("qwen3-4b", 8, 2048, 128),
+    "qwen3-8b-bf16-b16-c4096-d128": ("qwen3-8b", 16, 4096, 128),
 }
 
 
-def algorithmic_bytes_per_decode_step(shape, ctx_mean: float) -> float:
-    """Every weight element once per step, every cached K/V element once per step."""
+def algorithmic_bytes_per_decode_step(shape, ctx_mean: float, batch: int = 1) -> float:
+    """Every weight element once per step, every cached K/V element of every sequence once per step."""
     w = 2 if shape.dtype == 1 else 4
     per_layer = (shape.dq + 2 * shape.dkv) * shape.hidden + shape.hidden * shape.dq + 3 * shape.ffn * shape.hidden
     weights = w * (shape.n_layers * per_layer + shape.vocab * shape.hidden)
-    kv = shape.n_layers * 2 * shape.dkv * w * ctx_mean
+    kv = shape.n_layers * 2 * shape.dkv * w * ctx_mean * batch
     return float(weights + kv)
 
 
@@ -42,15 +51,17 @@ def counter_traffic(workload: str, decode_steps: int):
     """HBM bytes per launch of the resident kernel as measured with rocprofv3 counters
     (FETCH_SIZE + WRITE_SIZE, scaled by a known copy); read from the committed summary of
     that measurement, which is valid for the same workload only.  None if there is none."""
-    path = os.path.join(ROOT, "profiles", "k_decode_resident__qwen3-0.6b-b1-p128-d128__hbm_traffic.txt")
+    pdir = os.path.join(ROOT, "profiles")
     try:
-        for line in open(path):
+        names = sorted(n for n in os.listdir(pdir) if n.endswith("__hbm_traffic.txt"))
+    except OSError:
+        return None
+    for name in names:
+        for line in open(os.path.join(pdir, name)):
             if line.startswith("traffic_bytes_per_launch="):
                 kv = dict(f.split("=") for f in line.split())
                 if kv.get("workload") == workload and int(kv.get("decode_steps", -1)) == decode_steps:
                     return int(kv["traffic_bytes_per_launch"])
-    except OSError:
-        pass
     return None
 
 
@@ -73,24 +84,26 @@ def main() -> int:
     import synth
     from paper_2512_21571_amd import binding as nnc
 
-    shape_key, T, S = WORKLOADS[args.workload]
+    shape_key, B, T, S = WORKLOADS[args.workload]
     shape = synth.SHAPES[shape_key]
     blob = synth.make_blob(shape)
-    model = nnc.Model(shape, blob, 1, T + S)
-    prompt = synth.tokens(T, shape.vocab)
+    model = nnc.Model(shape, blob, B, T + S)
+    prompts = [synth.tokens(T, shape.vocab, stream=b) for b in range(B)]
+    prompt = prompts[0]
+    slots = list(range(B))
     stream = model.stream
 
     def one_pass(events=None):
-        model.kv_reset(0)
+        model.kv_reset(-1)
         if events:
             events[0].record(stream)
-        _, nxt = model.prefill(0, prompt, want_logits=False)
+        nxt = [model.prefill(b, prompts[b], want_logits=False)[1] for b in slots]
         if events:
             events[1].record(stream)
-        first = int(nxt.item())                    # the one host round trip of a request
+        firsts = [int(t.item()) for t in nxt]       # the one host round trip of a request
         if events:
             events[2].record(stream)
-        toks, _ = model.decode_greedy([0], [first], S)
+        toks, _ = model.decode_greedy(slots, firsts, S)
         if events:
             events[3].record(stream)
         return toks
@@ -107,21 +120,23 @@ def main() -> int:
     wall = time.perf_counter() - t0
     prefill_ms = sum(e[0].elapsed_time(e[1]) for e in evs)
     decode_ms = sum(e[2].elapsed_time(e[3]) for e in evs)
-    decode_tok_s = args.steps * S / (decode_ms * 1e-3)
-    prefill_tok_s = args.steps * T / (prefill_ms * 1e-3)
+    decode_tok_s = args.steps * S * B / (decode_ms * 1e-3)
+    prefill_tok_s = args.steps * T * B / (prefill_ms * 1e-3)
     ctx_mean = T + (S - 1) / 2.0 + 1
-    step_bytes = algorithmic_bytes_per_decode_step(shape, ctx_mean)
-    decode_ms_per_token = decode_ms / (args.steps * S)
+    step_bytes = algorithmic_bytes_per_decode_step(shape, ctx_mean, B)
+    decode_ms_per_token = decode_ms / (args.steps * S)   # per decode step (B tokens)
 
-    # The dominant kernel: the resident decode kernel runs all S steps of a request in one
-    # launch, so the HIP events around nnc_decode_greedy (recorded on the stream the kernel is
-    # launched on) bracket exactly that launch plus one 512-byte copy of the token log.
-    # Algorithmic bytes per launch = S decode steps x bytes per step (weights once per step,
-    # cached K/V rows once per step).
+    # The dominant kernel: at batch 1 the resident decode kernel runs all S steps of a request
+    # in one launch, so the HIP events around nnc_decode_greedy (recorded on the stream the
+    # kernel is launched on) bracket exactly that launch plus one 512-byte copy of the token
+    # log.  Algorithmic bytes per launch = S decode steps x bytes per step (weights once per
+    # step, cached K/V rows once per step).  At batch > 1 the same events bracket S replays of
+    # the captured per-stage graph, reported as one unit.
     launch_ms = decode_ms / args.steps
     launch_bytes = step_bytes * S
     achieved = launch_bytes / (launch_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "k_decode_resident", "achieved": round(achieved, 1),
+    roofline = {"bound": "hbm", "kernel": "k_decode_resident" if B == 1 else "decode step graph (per-stage kernels)",
+                "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": counter_traffic(args.workload, S),
                 "launches": args.steps, "avg_launch_us": round(launch_ms * 1e3, 1),
@@ -133,6 +148,8 @@ def main() -> int:
     model.profile_begin()
     model.prefill(0, prompt, want_logits=False)
     stats = model.profile_end()
+    gemm = [r for r in stats if r["name"] == "gemm_prefill" and r["total_ms"] > 0]
+    prefill_gemm_tflops = gemm[0]["flops"] / (gemm[0]["total_ms"] * 1e-3) / 1e12 if gemm else None
 
     # one plain device-to-device copy of known size (1 GiB read + 1 GiB written), untimed: the
     # reference a counter run (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) scales its readings by
@@ -145,7 +162,7 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        o = oracle.from_shape(shape, blob, 1, T + S)
+        o = oracle.from_shape(shape, blob, 1, 16 + S)
         ctx0 = 16                                    # short prompt so the sample is mostly decode
         _, t = o.prefill(0, prompt[:ctx0], oracle.ROUND_KV)
         n, c0 = 0, time.perf_counter()
@@ -162,13 +179,15 @@ def main() -> int:
         "value": round(decode_tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / args.steps, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload, "batch": 1, "prompt_tokens": T, "decode_steps": S,
+        "config": {"workload": args.workload, "batch": B, "prompt_tokens": T, "decode_steps": S,
                    "weights": "N(0,0.02) seeded, bf16", "kv_cache": "bf16"},
         "decode_ms_per_token": round(decode_ms_per_token, 5),
         "decode_hbm_frac_step": round(step_bytes / (decode_ms_per_token * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
         "decode_algorithmic_bytes_per_step": round(step_bytes),
         "prefill_tokens_per_s": round(prefill_tok_s, 1),
         "prefill_ms": round(prefill_ms / args.steps, 4),
+        "prefill_gemm_tflops": round(prefill_gemm_tflops, 1) if prefill_gemm_tflops else None,
+        "prefill_gemm_mfma_frac": round(prefill_gemm_tflops / MFMA_BF16_PEAK_TFLOPS, 4) if prefill_gemm_tflops else None,
         "roofline": roofline,
         "prefill_kernels": [{"name": r["name"], "launches": r["launches"], "total_ms": round(r["total_ms"], 4)}
                             for r in stats],

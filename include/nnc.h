@@ -165,6 +165,9 @@ typedef enum {
   NNC_OPT_PERSISTENT = 2,   /* 1 (default): batch-1 decode steps of bf16 models run in one
                                resident kernel per call (all steps of nnc_decode_greedy in a
                                single launch); 0: one kernel per stage */
+  NNC_OPT_PREFILL_TILE = 4, /* block tile of the large-block prompt GEMMs: -1 (default) chosen from
+                               the block length; 0: 64 x 128, 1: 256 x 128 (rows x operand
+                               columns); results are bit-identical for both (same k order) */
   NNC_OPT_STAGE_TRACE = 3   /* s + 1: the resident kernel stamps the 100 MHz wall clock at every
                                stage boundary of decode step s of each following launch (read them
                                with nnc_stage_trace); 0 (default): off */

@@ -93,6 +93,7 @@ struct nnc_model {
 
   // resident decode kernel
   bool mk_ok = false;
+  int n_cus = 256;
   int mk_nwg = 0, mk_ks_o = 1, mk_ks_d = 1;
   unsigned mk_tag = 1;  // next unused exchange tag
   void* mk_layers = nullptr;
@@ -104,6 +105,7 @@ struct nnc_model {
 
   bool opt_graph = true;
   bool opt_prefill_exact = false;
+  int opt_prefill_tile = -1;  // forced block tile of the large-block prompt GEMMs, -1 = by size
   bool opt_persistent = true;
   std::map<std::tuple<int, int, int>, hipGraphExec_t> graphs;
 
@@ -512,6 +514,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
   m->c = *cfg;
   m->f32 = cfg->compute_dtype == NNC_F32;
   m->device = device;
+  m->n_cus = prop.multiProcessorCount;
   if (dev) {
     m->stream = static_cast<hipStream_t>(dev->stream);
     if (dev->alloc && dev->free) {
@@ -725,6 +728,10 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
     case NNC_OPT_GRAPH: m->opt_graph = value != 0; return NNC_OK;
     case NNC_OPT_PREFILL_EXACT: m->opt_prefill_exact = value != 0; return NNC_OK;
     case NNC_OPT_PERSISTENT: m->opt_persistent = value != 0; return NNC_OK;
+    case NNC_OPT_PREFILL_TILE:
+      if (value < -1 || value > 1) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic), 0 or 1");
+      m->opt_prefill_tile = value;
+      return NNC_OK;
     case NNC_OPT_STAGE_TRACE:
       if (!m->mk_ok) return fail(NNC_E_STATE, "the resident decode kernel is not available for this model");
       m->mk_trace_step = value - 1;
@@ -746,8 +753,10 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
   // activations as two bf16 pieces (fp32-grade) and use small row tiles for more workgroups.
   // Long prompts are matrix-core bound: one bf16 per activation, 256-row tiles.
   const int pieces = n <= 512 ? 2 : 1;
-  const bool small_tiles = n <= 256;
   const int ct = tt * pieces;  // operand column tiles
+  // Block tile of the GEMMs: 64 x 128 for short prompts (more workgroups), else 256 x 128.
+  const int tile = m->opt_prefill_tile >= 0 ? m->opt_prefill_tile : (n <= 256 ? 0 : 1);
+  auto tile_shape = [&](int) { return tile; };
   const double w = 2.0, T = n;
   HIP_TRY(hipMemcpyAsync(m->pb_tok, tokens, (size_t)n * 4, hipMemcpyHostToDevice, s));
   RUN(FAM_EMBED, T * H * w, 0, launch_embed_rows(s, m->embed, H, m->pb_tok, (int)n, m->pb_x));
@@ -758,7 +767,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       PrefillGemmArgs a{};
       a.Wp = L.wqkv; a.n_tiles = Nqkv / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
       a.out = m->pb_qkv; a.ldo = Nqkv;
-      RUN(FAM_PGEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * T, launch_gemm_prefill(s, EPI_STORE, a, pieces, small_tiles));
+      RUN(FAM_PGEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * T, launch_gemm_prefill(s, EPI_STORE, a, pieces, tile_shape(a.n_tiles)));
     }
     {
       const ColMap cm{nullptr, slot, pos0, 0};
@@ -781,20 +790,20 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       PrefillGemmArgs a{};
       a.Wp = L.wo; a.n_tiles = H / 16; a.KT = Dq / 32; a.Xf = m->pb_fb; a.t_tiles = ct;
       a.out = m->pb_x; a.ldo = H;
-      RUN(FAM_PGEMM, (double)H * Dq * w, 2.0 * H * Dq * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, small_tiles));
+      RUN(FAM_PGEMM, (double)H * Dq * w, 2.0 * H * Dq * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, tile_shape(a.n_tiles)));
     }
     RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, m->pb_x, L.g_post, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
     {
       PrefillGemmArgs a{};
       a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
       a.packed_out = m->pb_fb;
-      RUN(FAM_PGEMM, 2.0 * F * H * w, 4.0 * F * H * T, launch_gemm_prefill(s, EPI_SWIGLU, a, pieces, small_tiles));
+      RUN(FAM_PGEMM, 2.0 * F * H * w, 4.0 * F * H * T, launch_gemm_prefill(s, EPI_SWIGLU, a, pieces, tile_shape(a.n_tiles)));
     }
     {
       PrefillGemmArgs a{};
       a.Wp = L.wd; a.n_tiles = H / 16; a.KT = F / 32; a.Xf = m->pb_fb; a.t_tiles = ct;
       a.out = m->pb_x; a.ldo = H;
-      RUN(FAM_PGEMM, (double)H * F * w, 2.0 * H * F * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, small_tiles));
+      RUN(FAM_PGEMM, (double)H * F * w, 2.0 * H * F * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, tile_shape(a.n_tiles)));
     }
   }
   if (want_head) {

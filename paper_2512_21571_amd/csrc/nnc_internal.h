@@ -119,7 +119,7 @@ struct PrefillGemmArgs {
   long ldo;
   void* packed_out;
 };
-hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a, int pieces, bool small_tiles);
+hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a, int pieces, int shape);
 // RMSNorm of rows 0..n_rows-1 of x ([rows, H] fp32), one bf16 per value, fragment order;
 // rows n_rows .. 16 * t_tiles - 1 of the operand are zero-filled.
 hipError_t launch_rmsnorm_frag(hipStream_t s, const float* x, const float* gain, int H, float eps, int n_rows,

@@ -10,10 +10,14 @@
 // nearest even): that is the precision contract of this path.
 #include "nnc_internal.h"
 
+#include <type_traits>
+#include <utility>
+
 namespace nnc {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -33,21 +37,33 @@ __device__ __forceinline__ void lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a
+// compile-time constant in the body, so register arrays indexed by it stay in registers.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
 }
 
-// Block tile: NT row tiles (16 rows each) x 8 column tiles (16 operand columns each), k step
-// 32.  4 waves in a 2 x 2 arrangement, each NT/2 x 4 accumulator tiles.  NT = 16 (256 rows)
-// for large token counts; NT = 4 (64 rows) gives four times as many workgroups when the
-// prompt is short and the launch would otherwise leave most of the chip idle.
+// Block tile: NT row tiles (16 rows each) x TT column tiles (16 operand columns each), k step
+// 32.  4 waves in a 2 x 2 arrangement, each NT/2 x TT/2 accumulator tiles.
+//   NT = 16, TT = 8  (256 x 128, 128 x 64 per wave): the matrix-core-bound shape; per k step a
+//                    wave reads 12 fragments from LDS for 32 matrix-core instructions.
+//   NT = 4,  TT = 8  (64 x 128): short prompts, where the launch would otherwise leave most of
+//                    the chip idle.
 // PIECES = 1: one bf16 per activation, a column tile is 16 tokens.  PIECES = 2: every
 // activation is carried as two bf16 pieces (value, remainder) in adjacent column tiles, whose
 // products the epilogue adds: fp32-grade activations at twice the matrix-core work, which is
 // free while the GEMM is bound by streaming the weights (short prompts).
-constexpr int PG_TT = 8;  // column tiles per block
 
 }  // namespace
 
@@ -55,89 +71,101 @@ constexpr int PG_TT = 8;  // column tiles per block
 // 16-byte element per lane), so staging is a straight copy: global -> registers -> LDS, and
 // every LDS access is a conflict-free 16-byte access at lane * 16.  Double-buffered in LDS,
 // fed from a register ring several k steps deep; one workgroup barrier per k step.
-template <int EPI, int NT, int PIECES>
+#ifndef PG_RING
+#define PG_RING(NT) ((NT) == 16 ? 4 : 8)
+#endif
+template <int EPI, int NT, int TT, int PIECES>
 __global__ __launch_bounds__(256) void k_gemm_prefill(PrefillGemmArgs a) {
   constexpr int WI = NT / 2;   // row tiles per wave
   constexpr int AL = NT / 4;   // 16-byte A loads per thread and k step
-  __shared__ uint4 As[2][NT][64];
-  __shared__ uint4 Bs[2][PG_TT][64];
+  constexpr int WJ = TT / 2;   // column tiles per wave
+  constexpr int BL = TT / 4;   // 16-byte B loads per thread and k step
+  __shared__ u32x4 As[2][NT][64];
+  __shared__ u32x4 Bs[2][TT][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wn = wave >> 1, wt = wave & 1;
   const int KT = a.KT;
-  const int nt0 = blockIdx.x * NT, tt0 = blockIdx.y * PG_TT;
-  const uint4* __restrict__ W = static_cast<const uint4*>(a.Wp);
-  const uint4* __restrict__ X = static_cast<const uint4*>(a.Xf);
+  const int nt0 = blockIdx.x * NT, tt0 = blockIdx.y * TT;
+  const u32x4* __restrict__ W = static_cast<const u32x4*>(a.Wp);
+  const u32x4* __restrict__ X = static_cast<const u32x4*>(a.Xf);
 
-  f32x4 acc[WI][4];
+  f32x4 acc[WI][WJ];
 #pragma unroll
   for (int i = 0; i < WI; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < WJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // Register ring of D k steps: the loads of step kt + D are issued when step kt starts, so D
   // steps of matrix-core work cover the memory latency even with one workgroup per CU.
-  constexpr int D = NT == 16 ? 4 : 8;
-  uint4 ra[D][AL], rb[D][2];
-  auto gload = [&](int st, int kt) {
+  constexpr int D = PG_RING(NT);  // even; sized to the registers left beside the accumulators
+  u32x4 ra[D][AL], rb[D][BL];  // native vectors: arrays of the HIP uint4 struct end up in scratch memory
+  // Loads are unconditional (tile and k indices clamped to the last valid one) so that the
+  // main loop is free of data-dependent branches and the compiler can wait for exactly the
+  // ring stage it needs; rows / columns past the edge compute garbage that is never stored.
+  auto gload = [&](auto stc, int kt) __attribute__((always_inline)) {
+    constexpr int st = decltype(stc)::value;
+    kt = min(kt, KT - 1);
 #pragma unroll
     for (int j = 0; j < AL; ++j) {
-      const int idx = tid + 256 * j, tile = idx >> 6, ln = idx & 63;
-      ra[st][j] = nt0 + tile < a.n_tiles ? W[((size_t)(nt0 + tile) * KT + kt) * 64 + ln] : uint4{0, 0, 0, 0};
+      const int idx = tid + 256 * j, tile = min(nt0 + (idx >> 6), a.n_tiles - 1), ln = idx & 63;
+      ra[st][j] = W[((size_t)tile * KT + kt) * 64 + ln];
     }
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int idx = tid + 256 * j, tile = idx >> 6, ln = idx & 63;
-      rb[st][j] = tt0 + tile < a.t_tiles ? X[((size_t)(tt0 + tile) * KT + kt) * 64 + ln] : uint4{0, 0, 0, 0};
+    for (int j = 0; j < BL; ++j) {
+      const int idx = tid + 256 * j, tile = min(tt0 + (idx >> 6), a.t_tiles - 1), ln = idx & 63;
+      rb[st][j] = X[((size_t)tile * KT + kt) * 64 + ln];
     }
   };
-  auto sstore = [&](int st, int buf) {
+  auto sstore = [&](auto stc, auto bufc) __attribute__((always_inline)) {
+    constexpr int st = decltype(stc)::value, buf = decltype(bufc)::value;
 #pragma unroll
     for (int j = 0; j < AL; ++j) {
       const int idx = tid + 256 * j;
       As[buf][idx >> 6][idx & 63] = ra[st][j];
     }
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < BL; ++j) {
       const int idx = tid + 256 * j;
       Bs[buf][idx >> 6][idx & 63] = rb[st][j];
     }
   };
+  // One k step: ring stage d holds step kt (already copied to LDS buffer d & 1; D is even).
+  auto step = [&](int kt, auto dc) __attribute__((always_inline)) {
+    constexpr int d = decltype(dc)::value;
+    gload(dc, kt + D);
+    u32x4 af[WI], bf[WJ];
+#pragma unroll
+    for (int i = 0; i < WI; ++i) af[i] = As[d & 1][wn * WI + i][lane];
+#pragma unroll
+    for (int j = 0; j < WJ; ++j) bf[j] = Bs[d & 1][wt * WJ + j][lane];
+#pragma unroll
+    for (int i = 0; i < WI; ++i)
+#pragma unroll
+      for (int j = 0; j < WJ; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[i]),
+                                                            __builtin_bit_cast(bf16x8, bf[j]), acc[i][j], 0, 0, 0);
+    // step kt + 1 into the other buffer (past the end: a clamped copy nobody reads)
+    sstore(std::integral_constant<int, (d + 1) % D>{}, std::integral_constant<int, (d + 1) & 1>{});
+    lds_sync();
+  };
 
-#pragma unroll
-  for (int d = 0; d < D; ++d)
-    if (d < KT) gload(d, d);
-  sstore(0, 0);
+  static_for<D>([&](auto dc) __attribute__((always_inline)) { gload(dc, decltype(dc)::value); });
+  sstore(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
   lds_sync();
-  for (int kt0 = 0; kt0 < KT; kt0 += D) {
-#pragma unroll
-    for (int d = 0; d < D; ++d) {
-      const int kt = kt0 + d;  // ring stage d held step kt (already in LDS); D is even: buffer d & 1
-      if (kt < KT) {
-        if (kt + D < KT) gload(d, kt + D);
-        uint4 af[WI], bf[4];
-#pragma unroll
-        for (int i = 0; i < WI; ++i) af[i] = As[d & 1][wn * WI + i][lane];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) bf[j] = Bs[d & 1][wt * 4 + j][lane];
-#pragma unroll
-        for (int i = 0; i < WI; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8, af[i]), __builtin_bit_cast(bf16x8, bf[j]), acc[i][j], 0, 0, 0);
-        if (kt + 1 < KT) sstore((d + 1) % D, (d + 1) & 1);
-        lds_sync();
-      }
-    }
-  }
+  int kt0 = 0;
+  for (; kt0 + D <= KT; kt0 += D)
+    static_for<D>([&](auto dc) __attribute__((always_inline)) { step(kt0 + decltype(dc)::value, dc); });
+  static_for<D>([&](auto dc) __attribute__((always_inline)) {
+    if (kt0 + decltype(dc)::value < KT) step(kt0 + decltype(dc)::value, dc);
+  });
 
   // accumulator element e of lane l in tile (i, j): row (l / 16) * 4 + e of row tile i,
   // operand column l % 16 of column tile j.  With two pieces, column tiles 2q and 2q+1 are
   // the two pieces of token tile q and their accumulators are added.
   const int c16 = lane & 15, g = lane >> 4;
 #pragma unroll
-  for (int j = 0; j < 4; j += PIECES) {
-    const int ct = tt0 + wt * 4 + j;  // column tile
+  for (int j = 0; j < WJ; j += PIECES) {
+    const int ct = tt0 + wt * WJ + j;  // column tile
     if (ct >= a.t_tiles) continue;
     const int tt = ct / PIECES;        // token tile
     const size_t t = (size_t)tt * 16 + c16;
@@ -195,22 +223,24 @@ __global__ __launch_bounds__(256) void k_gemm_prefill(PrefillGemmArgs a) {
   }
 }
 
-// a.t_tiles counts operand column tiles (token tiles x pieces).
-hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a, int pieces, bool small_tiles) {
-  if (a.n_tiles <= 0 || a.t_tiles <= 0 || a.KT <= 0 || (pieces != 1 && pieces != 2) || a.t_tiles % pieces)
+// a.t_tiles counts operand column tiles (token tiles x pieces).  shape: 0 = 64 x 128 block
+// tiles, 1 = 256 x 128.
+hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a, int pieces, int shape) {
+  if (a.n_tiles <= 0 || a.t_tiles <= 0 || a.KT <= 0 || (pieces != 1 && pieces != 2) || a.t_tiles % pieces ||
+      shape < 0 || shape > 1)
     return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU && a.n_tiles % 4) return hipErrorInvalidValue;
-  const int NT = small_tiles ? 4 : 16;
-  dim3 grid((a.n_tiles + NT - 1) / NT, (a.t_tiles + PG_TT - 1) / PG_TT);
-#define PG_LAUNCH(E)                                                              \
-  do {                                                                            \
-    if (small_tiles) {                                                            \
-      if (pieces == 2) k_gemm_prefill<E, 4, 2><<<grid, 256, 0, s>>>(a);           \
-      else k_gemm_prefill<E, 4, 1><<<grid, 256, 0, s>>>(a);                       \
-    } else {                                                                      \
-      if (pieces == 2) k_gemm_prefill<E, 16, 2><<<grid, 256, 0, s>>>(a);          \
-      else k_gemm_prefill<E, 16, 1><<<grid, 256, 0, s>>>(a);                      \
-    }                                                                             \
+  const int NT = shape == 0 ? 4 : 16, TT = 8;
+  dim3 grid((a.n_tiles + NT - 1) / NT, (a.t_tiles + TT - 1) / TT);
+#define PG_LAUNCH_P(E, P)                                                     \
+  do {                                                                        \
+    if (shape == 0) k_gemm_prefill<E, 4, 8, P><<<grid, 256, 0, s>>>(a);       \
+    else k_gemm_prefill<E, 16, 8, P><<<grid, 256, 0, s>>>(a);                 \
+  } while (0)
+#define PG_LAUNCH(E)                    \
+  do {                                  \
+    if (pieces == 2) PG_LAUNCH_P(E, 2); \
+    else PG_LAUNCH_P(E, 1);             \
   } while (0)
   switch (epi) {
     case EPI_STORE: PG_LAUNCH(EPI_STORE); break;
@@ -219,6 +249,7 @@ hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a,
     default: return hipErrorInvalidValue;
   }
 #undef PG_LAUNCH
+#undef PG_LAUNCH_P
   return hipGetLastError();
 }
 

@@ -144,6 +144,27 @@ def test_large_block_prefill_lengths(nnc, n):
         assert int(ng.item()) == t
 
 
+@pytest.mark.parametrize("tile", [0, 1])
+@pytest.mark.parametrize("n", [47, 300, 530])
+def test_large_block_prefill_every_block_tile(nnc, n, tile):
+    """Each GEMM block tile (64 x 128, 256 x 128) forced on ragged small shapes: the
+    k order of every output element is the same in both, so the logits are bit-identical
+    to the automatic choice, and they match the oracle."""
+    print(f"case: large-block prefill length {n}, forced block tile {tile}", flush=True)
+    shape = SMALL_G4
+    g, o = _pair(nnc, shape, 1, 640, exact_prefill=False)
+    toks = synth.tokens(n, shape.vocab, stream=300 + n)
+    one_piece = n > ONE_PIECE_ABOVE
+    ref, _ = g.prefill(0, toks)
+    g.kv_reset(0)
+    g.set_option(nnc.OPT_PREFILL_TILE, tile)
+    lg, ng = g.prefill(0, toks)
+    assert np.array_equal(lg.cpu().numpy(), ref.cpu().numpy())
+    lo, no = o.prefill(0, toks, oracle_flags(shape, mirrored_prefill=one_piece))
+    _check_logits(shape, lg, lo, BF16_ABS_PROMPT if one_piece else BF16_ABS_TIGHT)
+    assert int(ng.item()) == no
+
+
 def test_multi_block_prefill_long_context(nnc):
     print("case: prompt longer than one 2048-token block", flush=True)
     shape = SMALL_BF16
