@@ -47,9 +47,9 @@ struct ProfRec {
   hipEvent_t e0, e1;
 };
 
-enum Family { FAM_GEMM = 0, FAM_NORM, FAM_QKROPE, FAM_ATTN, FAM_COMBINE, FAM_EMBED, FAM_ARGMAX, FAM_MISC, FAM_PGEMM, FAM_COUNT };
+enum Family { FAM_GEMM = 0, FAM_NORM, FAM_QKROPE, FAM_ATTN, FAM_COMBINE, FAM_EMBED, FAM_ARGMAX, FAM_MISC, FAM_PGEMM, FAM_PATTN, FAM_COUNT };
 const char* const kFamName[FAM_COUNT] = {"gemm_skinny", "rmsnorm_pack", "qknorm_rope_append", "attn_partial",
-                                         "attn_combine", "embed", "argmax", "misc", "gemm_prefill"};
+                                         "attn_combine", "embed", "argmax", "misc", "gemm_prefill", "attn_prefill"};
 
 }  // namespace
 
@@ -90,6 +90,8 @@ struct nnc_model {
   float *pb_x = nullptr, *pb_qkv = nullptr;
   void *pb_fa = nullptr, *pb_fb = nullptr;  // fragment-order bf16 operands: K = H, K = max(Dq, F)
   int32_t* pb_tok = nullptr;
+  void* pb_vt = nullptr;  // transposed V copy of the slot being prefilled
+  uint32_t pb_vt_stride = 0;
 
   // resident decode kernel
   bool mk_ok = false;
@@ -644,6 +646,11 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     ALLOC(m->pb_fa, void*, frag_rows * H * 2);
     ALLOC(m->pb_fb, void*, frag_rows * std::max(Dq, F) * 2);
     ALLOC(m->pb_tok, int32_t*, (size_t)pb * 4);
+    // transposed V copy of one slot: [kv head][128][positions, padded to a multiple of 32];
+    // zero-filled once so that positions never written read as finite values
+    m->pb_vt_stride = (c.max_seq + 31) / 32 * 32;
+    ALLOC(m->pb_vt, void*, (size_t)c.n_kv_heads * 128 * m->pb_vt_stride * 2);
+    TRY_OR_BAIL(hipMemsetAsync(m->pb_vt, 0, (size_t)c.n_kv_heads * 128 * m->pb_vt_stride * 2, s));
   }
 
   // resident decode kernel: per-layer pointer table, exchange buffers
@@ -775,16 +782,16 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
           launch_qknorm_rope_append(s, false, m->pb_qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, (int)n, L.kc,
                                     L.vc, c.max_batch, c.max_seq));
     }
-    for (uint32_t b0 = 0; b0 < n; b0 += MAX_COLS) {
-      const int nb = (int)std::min<uint32_t>(MAX_COLS, n - b0);
-      const ColMap cm{nullptr, slot, pos0 + b0, (int)b0};
+    {
+      // causal attention of the block on the matrix cores, over a transposed copy of the
+      // slot's V rows (positions of earlier blocks included)
       double rows = 0;
-      for (int i = 0; i < nb; ++i) rows += pos0 + b0 + i + 1.0;
-      RUN(FAM_ATTN, rows * 2.0 * Dkv * w, rows * 4.0 * Dq,
-          launch_attn_partial(s, false, m->pb_qkv, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, cm, nb,
-                              chunks_grid(pos0 + b0 + nb - 1), m->partial, m->max_chunks));
-      RUN(FAM_COMBINE, 0, 0,
-          launch_attn_combine(s, false, m->partial, m->max_chunks, nq, cm, nb, m->pb_fb, 0, pieces, true));
+      for (uint32_t i = 0; i < n; ++i) rows += pos0 + i + 1.0;
+      RUN(FAM_MISC, (pos0 + T) * Dkv * 2.0 * w, 0,
+          launch_v_transpose(s, L.vc, slot, nkv, c.max_seq, pos0 + n, m->pb_vt, m->pb_vt_stride));
+      RUN(FAM_PATTN, (pos0 + T) * 2.0 * Dkv * w + T * Dq * 6.0, rows * 4.0 * Dq,
+          launch_attn_prefill(s, m->pb_qkv, nq, nkv, L.kc, m->pb_vt, m->pb_vt_stride, slot, c.max_seq, pos0, (int)n,
+                              pieces, m->pb_fb));
     }
     {
       PrefillGemmArgs a{};

@@ -124,6 +124,10 @@ hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a,
 // rows n_rows .. 16 * t_tiles - 1 of the operand are zero-filled.
 hipError_t launch_rmsnorm_frag(hipStream_t s, const float* x, const float* gain, int H, float eps, int n_rows,
                                int token_tiles, int pieces, void* Xf);
+hipError_t launch_v_transpose(hipStream_t s, const void* vc, uint32_t slot, int nkv, uint32_t max_seq, uint32_t n_pos,
+                              void* vt, uint32_t S);
+hipError_t launch_attn_prefill(hipStream_t s, const float* qkv, int nq, int nkv, const void* kc, const void* vt,
+                               uint32_t S, uint32_t slot, uint32_t max_seq, uint32_t pos0, int n, int pieces, void* Of);
 hipError_t launch_embed_rows(hipStream_t s, const void* Ep, int H, const int32_t* tokens_dev, int n, float* x);
 hipError_t launch_argmax(hipStream_t s, const float* logits, long ld, int V, int ncols,
                          const uint32_t* step_ptr, long step_stride, float* scratch_val,

@@ -319,4 +319,237 @@ hipError_t launch_embed_rows(hipStream_t s, const void* Ep, int H, const int32_t
   return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------
+// causal prompt attention on the matrix cores
+// ---------------------------------------------------------------------------
+// Transposed copy of one slot's cached V rows, positions [0, n_pos): Vt[kv head][d][position]
+// (row stride S, a multiple of 32).  The attention kernel below wants, for a fixed head
+// dimension, eight consecutive positions in one 16-byte load.
+__global__ __launch_bounds__(256) void k_v_transpose(const uint16_t* __restrict__ vc, uint32_t slot, int nkv,
+                                                     uint32_t max_seq, uint32_t n_pos, uint16_t* __restrict__ vt,
+                                                     uint32_t S) {
+  __shared__ uint16_t tile[64][130];  // 64 positions x 128 dims, rows padded to 65 words
+  const int kvh = blockIdx.y, tid = threadIdx.x;
+  const uint32_t p0 = blockIdx.x * 64;
+  const uint16_t* src = vc + (((size_t)slot * nkv + kvh) * max_seq) * 128;
+  for (int q = tid; q < 64 * 16; q += 256) {
+    const uint32_t pr = q >> 4, dc = q & 15, pos = min(p0 + pr, n_pos - 1);
+    const uint4 v = *reinterpret_cast<const uint4*>(src + (size_t)pos * 128 + dc * 8);
+    uint32_t* t = reinterpret_cast<uint32_t*>(&tile[pr][dc * 8]);
+    t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
+  }
+  __syncthreads();
+  for (int q = tid; q < 128 * 8; q += 256) {
+    const int d = q >> 3, seg = q & 7;  // 8 positions p0 + seg * 8 .. + 7 of dimension d
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = tile[seg * 8 + 2 * e][d] | ((uint32_t)tile[seg * 8 + 2 * e + 1][d] << 16);
+    if (p0 + seg * 8 < S)
+      *reinterpret_cast<uint4*>(vt + ((size_t)kvh * 128 + d) * S + p0 + seg * 8) = uint4{w[0], w[1], w[2], w[3]};
+  }
+}
+
+hipError_t launch_v_transpose(hipStream_t s, const void* vc, uint32_t slot, int nkv, uint32_t max_seq, uint32_t n_pos,
+                              void* vt, uint32_t S) {
+  if (n_pos == 0 || S % 32 || n_pos > S) return hipErrorInvalidValue;
+  dim3 grid((n_pos + 63) / 64, nkv);
+  k_v_transpose<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(vc), slot, nkv, max_seq, n_pos,
+                                     static_cast<uint16_t*>(vt), S);
+  return hipGetLastError();
+}
+
+// Scores and weighted sums of 16 prompt tokens x GH query heads (sharing one kv head) per wave,
+// flash style: positions are walked in chunks of 32 with a running maximum and sum per row.
+// Both products run transposed, so that no operand needs a shuffle between them:
+//   S^T = K Q^T   A = 16 cached K rows (their 128 dims in four k steps, straight from the
+//                 cache), B = the wave's 16 query rows; D holds, per lane, one query token
+//                 (column) and 4 + 4 positions of the two 16-row tiles.  The K rows of the two
+//                 tiles are picked so that these are 8 consecutive positions g*8 .. g*8+7.
+//   O^T = V^T P^T A = 16 head dims x 32 positions from the transposed V copy (one 16-byte
+//                 load per lane), B = the lane's own 8 weights: exactly the B-operand layout
+//                 (column = query token, 8 consecutive k).
+// Operands are loaded from global memory (L2) directly into registers: each K / V^T fragment
+// feeds GH heads, which is all the reuse there is, so LDS staging would add nothing.
+// Masked positions get weight exp(-inf) = 0; their K / V^T values are finite (the copy and the
+// cache rows read are initialised memory), so 0 x value = 0.
+// PIECES = 2: queries and weights enter the matrix cores as two bf16 pieces (16 significant
+// bits); PIECES = 1: one bf16 each, and the row sum adds the rounded weights.
+template <int GH, int PIECES>
+__global__ __launch_bounds__(256) void k_attn_prefill(const float* __restrict__ qkv, int nq, int nkv,
+                                                      const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vt,
+                                                      uint32_t S, uint32_t slot, uint32_t max_seq, uint32_t pos0,
+                                                      int n, void* __restrict__ Of) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int c16 = lane & 15, g = lane >> 4;
+  const int G = nq / nkv;
+  const int kvh = blockIdx.y / (G / GH), head0 = kvh * G + (blockIdx.y % (G / GH)) * GH;
+  const int tq = blockIdx.x * 4 + wave;  // token tile of this wave
+  if (tq * 16 >= n) return;
+  const int ld = (nq + 2 * nkv) * 128;
+  const int t = min(tq * 16 + c16, n - 1);  // rows past the prompt repeat the last token (never used)
+  const uint32_t p = pos0 + (uint32_t)t;    // position of this lane's query token
+
+  // query fragments: lane (column c16 = token, g) holds dims ks*32 + g*8 .. +7 of its token
+  u32x4 qf[GH][4][PIECES];
+#pragma unroll
+  for (int h = 0; h < GH; ++h)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const float* src = qkv + (size_t)t * ld + (size_t)(head0 + h) * 128 + ks * 32 + g * 8;
+      const float4 x0 = *reinterpret_cast<const float4*>(src), x1 = *reinterpret_cast<const float4*>(src + 4);
+      float v[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+#pragma unroll
+      for (int pc = 0; pc < PIECES; ++pc) {
+        uint32_t b[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          b[e] = bf16_bits(v[e]);
+          v[e] -= bf16_to_f32(b[e]);
+        }
+        qf[h][ks][pc] = u32x4{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
+      }
+    }
+
+  f32x4 acc[GH][8];
+  float mrun[GH], lsum[GH];
+#pragma unroll
+  for (int h = 0; h < GH; ++h) {
+    mrun[h] = -INFINITY;
+    lsum[h] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) acc[h][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const uint16_t* kbase = kc + (((size_t)slot * nkv + kvh) * max_seq) * 128;
+  const uint16_t* vbase = vt + (size_t)kvh * 128 * S;
+  const uint32_t p_last = pos0 + (uint32_t)min(tq * 16 + 15, n - 1);  // last position any row of the tile sees
+  const int r4 = (c16 >> 2) * 8 + (c16 & 3);  // K row of tile a for A-operand row c16; tile b: + 4
+
+  for (uint32_t kv0 = 0; kv0 <= p_last; kv0 += 32) {
+    u32x4 ka[4], kb[4], vf[8];
+    const uint32_t ra = min(kv0 + r4, max_seq - 1), rb = min(kv0 + r4 + 4, max_seq - 1);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      ka[ks] = *reinterpret_cast<const u32x4*>(kbase + (size_t)ra * 128 + ks * 32 + g * 8);
+      kb[ks] = *reinterpret_cast<const u32x4*>(kbase + (size_t)rb * 128 + ks * 32 + g * 8);
+    }
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+      vf[dt] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(dt * 16 + c16) * S + kv0 + g * 8);
+
+#pragma unroll
+    for (int h = 0; h < GH; ++h) {
+      f32x4 sa = f32x4{0.f, 0.f, 0.f, 0.f}, sb = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int pc = 0; pc < PIECES; ++pc) {
+          sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[ks]),
+                                                       __builtin_bit_cast(bf16x8, qf[h][ks][pc]), sa, 0, 0, 0);
+          sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[ks]),
+                                                       __builtin_bit_cast(bf16x8, qf[h][ks][pc]), sb, 0, 0, 0);
+        }
+      // element i of sa: position kv0 + g*8 + i; of sb: kv0 + g*8 + 4 + i; column = this lane's token
+      float sc[8];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t kv = kv0 + g * 8 + i;
+        const float v = (i < 4 ? sa[i] : sb[i - 4]) * 0.08838834764831845f;
+        sc[i] = kv <= p ? v : -INFINITY;
+        mx = fmaxf(mx, sc[i]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mn = fmaxf(mrun[h], mx);  // finite from the first chunk on: position 0 is visible to every token
+      const float alpha = expf(mrun[h] - mn);
+      mrun[h] = mn;
+      uint32_t pb[PIECES][8];
+      float rs = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float w = expf(sc[i] - mn);
+        if constexpr (PIECES == 1) {
+          pb[0][i] = bf16_bits(w);
+          rs += bf16_to_f32(pb[0][i]);
+        } else {
+          rs += w;
+#pragma unroll
+          for (int pc = 0; pc < PIECES; ++pc) {
+            pb[pc][i] = bf16_bits(w);
+            w -= bf16_to_f32(pb[pc][i]);
+          }
+        }
+      }
+      lsum[h] = lsum[h] * alpha + rs;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[h][dt][e] *= alpha;
+#pragma unroll
+        for (int pc = 0; pc < PIECES; ++pc) {
+          const u32x4 pf = u32x4{pb[pc][0] | (pb[pc][1] << 16), pb[pc][2] | (pb[pc][3] << 16),
+                                 pb[pc][4] | (pb[pc][5] << 16), pb[pc][6] | (pb[pc][7] << 16)};
+          acc[h][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[dt]),
+                                                               __builtin_bit_cast(bf16x8, pf), acc[h][dt], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // acc[h][dt] element e: head dim dt*16 + g*4 + e of this lane's token.  Output goes straight
+  // into the fragment order the output projection reads: operand index k = head * 128 + dim.
+  const int KTQ = nq * 4;
+#pragma unroll
+  for (int h = 0; h < GH; ++h) {
+    float l = lsum[h];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    const float inv = 1.0f / l;
+    if (tq * 16 + c16 < n) {
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        const int k0 = (head0 + h) * 128 + dt * 16 + g * 4;
+        float v[4] = {acc[h][dt][0] * inv, acc[h][dt][1] * inv, acc[h][dt][2] * inv, acc[h][dt][3] * inv};
+#pragma unroll
+        for (int pc = 0; pc < PIECES; ++pc) {
+          uint32_t b[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            b[e] = bf16_bits(v[e]);
+            v[e] -= bf16_to_f32(b[e]);
+          }
+          const size_t el = (((size_t)(tq * PIECES + pc) * KTQ + (k0 >> 5)) * 64 + c16 + 16 * ((k0 & 31) >> 3)) * 8 + (k0 & 7);
+          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(Of) + el) = make_uint2(b[0] | (b[1] << 16), b[2] | (b[3] << 16));
+        }
+      }
+    }
+  }
+}
+
+// qkv: [tokens][(nq + 2 nkv) * 128] fp32 with the query heads already normed and rotated.
+// kc: the layer's K cache; vt: transposed V copy of the slot (row stride S) covering positions
+// 0 .. pos0 + n - 1.  Of: fragment-order bf16 output ([token tile x pieces][nq*4][64][8]).
+hipError_t launch_attn_prefill(hipStream_t s, const float* qkv, int nq, int nkv, const void* kc, const void* vt,
+                               uint32_t S, uint32_t slot, uint32_t max_seq, uint32_t pos0, int n, int pieces, void* Of) {
+  const int G = nq / nkv;
+  if (n <= 0 || G < 1 || nq % nkv || (pieces != 1 && pieces != 2) || S % 32 || pos0 + (uint32_t)n > S)
+    return hipErrorInvalidValue;
+  const int GH = G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1);
+  dim3 grid((n + 63) / 64, nkv * (G / GH));
+  const uint16_t* k = static_cast<const uint16_t*>(kc);
+  const uint16_t* v = static_cast<const uint16_t*>(vt);
+#define AP_LAUNCH(GHV)                                                                                          \
+  do {                                                                                                          \
+    if (pieces == 2) k_attn_prefill<GHV, 2><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, Of); \
+    else k_attn_prefill<GHV, 1><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, Of);           \
+  } while (0)
+  if (GH == 4) AP_LAUNCH(4);
+  else if (GH == 2) AP_LAUNCH(2);
+  else AP_LAUNCH(1);
+#undef AP_LAUNCH
+  return hipGetLastError();
+}
+
 }  // namespace nnc

@@ -24,7 +24,7 @@ def oracle_flags(shape, mirrored_prefill: bool = False) -> int:
     if shape.dtype == synth.BF16:
         f |= oracle.ROUND_KV
         if mirrored_prefill:
-            f |= oracle.ROUND_GEMM_IN
+            f |= oracle.ROUND_GEMM_IN | oracle.ROUND_ATTN_QP
     return f
 
 
