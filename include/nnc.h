@@ -156,12 +156,16 @@ nnc_status nnc_kv_read(nnc_model *m, uint32_t layer, uint32_t slot, uint32_t whi
 /* Runtime switches. */
 typedef enum {
   NNC_OPT_GRAPH = 0,        /* 1 (default): replay decode steps as captured HIP graphs; 0: eager */
-  NNC_OPT_PREFILL_EXACT = 1, /* 0 (default for bf16 models): the prompt pass runs on blocks of up
-                               to 2048 tokens with LDS-staged matrix-core GEMMs.  Blocks of up
-                               to 512 tokens carry every GEMM input as two bf16 pieces (16
-                               significant bits); longer blocks round GEMM inputs to bf16 once
-                               (the LM head of the last position stays fp32-grade).  1: prompt
-                               GEMMs take three bf16 pieces (fp32-grade), in chunks of 21 tokens */
+  NNC_OPT_PREFILL_EXACT = 1, /* precision of the prompt pass of bf16 models.
+                               0 (default): blocks of up to 2048 tokens with LDS-staged
+                               matrix-core GEMMs and matrix-core attention.  Blocks of up to 512
+                               tokens carry every matrix-core input as two bf16 pieces (16
+                               significant bits); longer blocks round those inputs to bf16 once
+                               (the LM head of the last position stays fp32-grade).
+                               2: the same blocks, two pieces at every length (twice the
+                               matrix-core work of long blocks).
+                               1: 21-token chunks through the decode kernels, three bf16 pieces
+                               (fp32-grade) */
   NNC_OPT_PERSISTENT = 2,   /* 1 (default): batch-1 decode steps of bf16 models run in one
                                resident kernel per call (all steps of nnc_decode_greedy in a
                                single launch); 0: one kernel per stage */

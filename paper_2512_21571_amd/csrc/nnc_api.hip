@@ -106,7 +106,7 @@ struct nnc_model {
   int mk_trace_step = -1;
 
   bool opt_graph = true;
-  bool opt_prefill_exact = false;
+  int opt_prefill_exact = 0;  // 0: large blocks, pieces by length; 1: 21-token chunks, three pieces; 2: large blocks, two pieces
   int opt_prefill_tile = -1;  // forced block tile of the large-block prompt GEMMs, -1 = by size
   bool opt_persistent = true;
   std::map<std::tuple<int, int, int>, hipGraphExec_t> graphs;
@@ -524,7 +524,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
       m->use_hooks = true;
     }
   }
-  m->opt_prefill_exact = false;
+  m->opt_prefill_exact = 0;
   const nnc_config& c = m->c;
   const size_t H = m->H(), Dq = m->Dq(), Dkv = m->Dkv(), F = m->F(), V = m->V(), d = c.head_dim;
   const size_t w = m->esz(), bw = c.blob_dtype == NNC_F32 ? 4 : 2;
@@ -641,8 +641,8 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     m->pb_max = pb;
     ALLOC(m->pb_x, float*, (size_t)pb * H * 4);
     ALLOC(m->pb_qkv, float*, (size_t)pb * (Dq + 2 * Dkv) * 4);
-    // prompts of <= 512 tokens carry two bf16 pieces per activation
-    const size_t frag_rows = std::max<size_t>(pb, 2 * std::min<size_t>(pb, 512));
+    // up to two bf16 pieces per activation
+    const size_t frag_rows = 2 * (size_t)pb;
     ALLOC(m->pb_fa, void*, frag_rows * H * 2);
     ALLOC(m->pb_fb, void*, frag_rows * std::max(Dq, F) * 2);
     ALLOC(m->pb_tok, int32_t*, (size_t)pb * 4);
@@ -733,7 +733,10 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
   if (!m) return fail(NNC_E_ARG, "model is NULL");
   switch (opt) {
     case NNC_OPT_GRAPH: m->opt_graph = value != 0; return NNC_OK;
-    case NNC_OPT_PREFILL_EXACT: m->opt_prefill_exact = value != 0; return NNC_OK;
+    case NNC_OPT_PREFILL_EXACT:
+      if (value < 0 || value > 2) return fail(NNC_E_ARG, "prefill precision mode must be 0, 1 or 2");
+      m->opt_prefill_exact = value;
+      return NNC_OK;
     case NNC_OPT_PERSISTENT: m->opt_persistent = value != 0; return NNC_OK;
     case NNC_OPT_PREFILL_TILE:
       if (value < -1 || value > 1) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic), 0 or 1");
@@ -759,7 +762,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
   // Short prompts are bound by streaming the weights, not by the matrix cores: carry the
   // activations as two bf16 pieces (fp32-grade) and use small row tiles for more workgroups.
   // Long prompts are matrix-core bound: one bf16 per activation, 256-row tiles.
-  const int pieces = n <= 512 ? 2 : 1;
+  const int pieces = (n <= 512 || m->opt_prefill_exact == 2) ? 2 : 1;
   const int ct = tt * pieces;  // operand column tiles
   // Block tile of the GEMMs: 64 x 128 for short prompts (more workgroups), else 256 x 128.
   const int tile = m->opt_prefill_tile >= 0 ? m->opt_prefill_tile : (n <= 256 ? 0 : 1);
@@ -838,7 +841,7 @@ static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tok
   if (tokens)
     for (uint32_t i = 0; i < n; ++i)
       if (tokens[i] < 0 || (uint32_t)tokens[i] >= m->c.vocab) return fail(NNC_E_ARG, "token %d out of range", tokens[i]);
-  if (tokens && m->pb_max && !m->opt_prefill_exact) {
+  if (tokens && m->pb_max && m->opt_prefill_exact != 1) {
     const uint32_t len0 = m->len[slot];
     for (uint32_t t0 = 0; t0 < n; t0 += m->pb_max) {
       const uint32_t nb = std::min(m->pb_max, n - t0);

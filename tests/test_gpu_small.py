@@ -165,6 +165,18 @@ def test_large_block_prefill_every_block_tile(nnc, n, tile):
     assert int(ng.item()) == no
 
 
+def test_large_block_prefill_two_pieces_at_any_length(nnc):
+    print("case: large-block prefill, 600 tokens, two pieces forced", flush=True)
+    shape = SMALL_G4
+    g, o = _pair(nnc, shape, 1, 640, exact_prefill=False)
+    g.set_option(nnc.OPT_PREFILL_EXACT, 2)
+    toks = synth.tokens(600, shape.vocab, stream=41)
+    lg, ng = g.prefill(0, toks)
+    lo, no = o.prefill(0, toks, oracle_flags(shape))
+    _check_logits(shape, lg, lo, BF16_ABS_TIGHT)
+    assert int(ng.item()) == no
+
+
 def test_multi_block_prefill_long_context(nnc):
     print("case: prompt longer than one 2048-token block", flush=True)
     shape = SMALL_BF16
