@@ -292,7 +292,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
         launch_attn_partial(s, f32, m->qkv, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, cm, n,
                             p.grid_chunks, m->partial, m->max_chunks));
     RUN(FAM_COMBINE, 0, 0,
-        launch_attn_combine(s, f32, m->partial, m->max_chunks, nq, cm, n, m->Ap, nc, ns, false));
+        launch_attn_combine(s, f32, m->partial, m->max_chunks, nq, cm, n, m->Ap, nc, ns));
     {
       GemmArgs a{};
       a.Wp = L.wo; a.n_tiles = H / 16; a.KT = KTQ; a.kts_per_split = pick_kts(a.n_tiles, KTQ);

@@ -100,7 +100,7 @@ hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, int nq
                                const ColMap& cm, int ncols, int grid_chunks, float* partial,
                                int max_chunks);
 hipError_t launch_attn_combine(hipStream_t s, bool f32, const float* partial, int max_chunks, int nq,
-                               const ColMap& cm, int ncols, void* Op, int NC, int nsplit, bool frag);
+                               const ColMap& cm, int ncols, void* Op, int NC, int nsplit);
 
 // ---- prompt pass on large token blocks (bf16 models): LDS-staged matrix-core GEMM ----
 // Y[t, n] = sum_k X[t, k] W[n, k].  W: packed weights (above).  X: bf16 activations in

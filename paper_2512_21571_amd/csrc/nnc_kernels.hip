@@ -223,7 +223,10 @@ __device__ __forceinline__ void store_packed(void* Xp, int NC, int nsplit, int s
 // residual stream: x += part[0] + part[1] + ... (k slices of that GEMM, fixed order),
 // and the updated x is written back.  part_seq0 is the column of `part` that
 // corresponds to blockIdx.x == 0 (the LM head norms a sub-range of the columns).
-template <bool F32>
+// NV = float4 groups per thread: the whole row (H <= 1024 * NV) lives in registers, every load
+// (row, pending partials, gains) is issued before the first use, and the row is neither
+// re-read nor re-written more than once.
+template <bool F32, int NV>
 __global__ __launch_bounds__(256) void k_rmsnorm_pack(float* __restrict__ x, long ldx,
                                                       const float* __restrict__ part, int nparts,
                                                       long part_stride, const float* __restrict__ gain,
@@ -232,29 +235,71 @@ __global__ __launch_bounds__(256) void k_rmsnorm_pack(float* __restrict__ x, lon
   __shared__ float sm[4];
   const int seq = blockIdx.x;
   float* xr = x + (size_t)seq * ldx;
-  float ss = 0.f;
-  for (int i = threadIdx.x; i < H; i += 256) {
-    float v = xr[i];
-    if (nparts > 0) {
-      float add = part[(size_t)seq * H + i];
-      for (int p = 1; p < nparts; ++p) add += part[(size_t)p * part_stride + (size_t)seq * H + i];
-      v += add;
-      xr[i] = v;
+  float4 v[NV], g[NV], pp[NV][4];
+#pragma unroll
+  for (int q = 0; q < NV; ++q) {
+    const int i = (threadIdx.x + 256 * q) * 4;
+    v[q] = g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < H) {
+      v[q] = *reinterpret_cast<const float4*>(xr + i);
+      g[q] = *reinterpret_cast<const float4*>(gain + i);
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        if (p < nparts) pp[q][p] = *reinterpret_cast<const float4*>(part + (size_t)p * part_stride + (size_t)seq * H + i);
     }
-    ss += v * v;
   }
-  ss = block_sum_256(ss, sm);  // also orders the writes above before the reads below
+  float ss = 0.f;
+#pragma unroll
+  for (int q = 0; q < NV; ++q) {
+    const int i = (threadIdx.x + 256 * q) * 4;
+    if (i < H && nparts > 0) {
+      float4 add = pp[q][0];  // slices are added in a fixed order
+#pragma unroll
+      for (int p = 1; p < 4; ++p)
+        if (p < nparts) add = make_float4(add.x + pp[q][p].x, add.y + pp[q][p].y, add.z + pp[q][p].z, add.w + pp[q][p].w);
+      v[q] = make_float4(v[q].x + add.x, v[q].y + add.y, v[q].z + add.z, v[q].w + add.w);
+      *reinterpret_cast<float4*>(xr + i) = v[q];
+    }
+    ss += v[q].x * v[q].x + v[q].y * v[q].y + v[q].z * v[q].z + v[q].w * v[q].w;
+  }
+  ss = block_sum_256(ss, sm);
   const float r = 1.0f / sqrtf(ss / (float)H + eps);
-  for (int i = threadIdx.x; i < H; i += 256) store_packed<F32>(Xp, NC, nsplit, seq, i, xr[i] * r * gain[i]);
+#pragma unroll
+  for (int q = 0; q < NV; ++q) {
+    const int i = (threadIdx.x + 256 * q) * 4;
+    if (i >= H) continue;
+    const float h[4] = {v[q].x * r * g[q].x, v[q].y * r * g[q].y, v[q].z * r * g[q].z, v[q].w * r * g[q].w};
+    if constexpr (F32) {
+      *reinterpret_cast<float4*>(static_cast<float*>(Xp) + ((size_t)(i >> 2) * NC + seq) * 4) =
+          make_float4(h[0], h[1], h[2], h[3]);
+    } else {
+      // elements i .. i+3 of one 8-element group: 8 bytes per piece
+      uint32_t pc[4][3];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) split_bf16(h[e], nsplit, pc[e]);
+      uint16_t* dst = static_cast<uint16_t*>(Xp) + ((size_t)(i >> 3) * NC + seq * nsplit) * 8 + (i & 7);
+#pragma unroll
+      for (int sp = 0; sp < 3; ++sp)
+        if (sp < nsplit)
+          *reinterpret_cast<uint2*>(dst + sp * 8) = make_uint2(pc[0][sp] | (pc[1][sp] << 16), pc[2][sp] | (pc[3][sp] << 16));
+    }
+  }
 }
 
 hipError_t launch_rmsnorm_pack(hipStream_t s, bool f32, float* x, long ldx, const float* part, int nparts,
                                long part_stride, const float* gain, int H, float eps, int ncols, void* Xp,
                                int NC, int nsplit) {
-  if (f32)
-    k_rmsnorm_pack<true><<<ncols, 256, 0, s>>>(x, ldx, part, nparts, part_stride, gain, H, eps, Xp, NC, nsplit);
-  else
-    k_rmsnorm_pack<false><<<ncols, 256, 0, s>>>(x, ldx, part, nparts, part_stride, gain, H, eps, Xp, NC, nsplit);
+  if (H % 4 || H > 8192 || nparts > 4 || nparts < 0 || ldx % 4) return hipErrorInvalidValue;
+#define RN_LAUNCH(NV)                                                                                              \
+  do {                                                                                                             \
+    if (f32) k_rmsnorm_pack<true, NV><<<ncols, 256, 0, s>>>(x, ldx, part, nparts, part_stride, gain, H, eps, Xp, NC, nsplit); \
+    else k_rmsnorm_pack<false, NV><<<ncols, 256, 0, s>>>(x, ldx, part, nparts, part_stride, gain, H, eps, Xp, NC, nsplit);   \
+  } while (0)
+  if (H <= 1024) RN_LAUNCH(1);
+  else if (H <= 2048) RN_LAUNCH(2);
+  else if (H <= 4096) RN_LAUNCH(4);
+  else RN_LAUNCH(8);
+#undef RN_LAUNCH
   return hipGetLastError();
 }
 
@@ -520,6 +565,39 @@ __device__ __forceinline__ void load_row8(const void* base, size_t elem, float* 
   }
 }
 
+// The same 8-element slice as raw register data (no conversion yet), so that all loads of a
+// chunk can be in flight before the first one is used.
+template <bool F32>
+struct Row8Raw {
+  float4 a, b;  // fp32: 8 floats; bf16: `a` reinterpreted as 8 bf16 values
+};
+template <bool F32>
+__device__ __forceinline__ Row8Raw<F32> load_row8_raw(const void* base, size_t elem) {
+  Row8Raw<F32> r;
+  if constexpr (F32) {
+    r.a = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem);
+    r.b = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem + 4);
+  } else {
+    r.a = *reinterpret_cast<const float4*>(static_cast<const uint16_t*>(base) + elem);
+    r.b = r.a;
+  }
+  return r;
+}
+template <bool F32>
+__device__ __forceinline__ void widen_row8(const Row8Raw<F32>& r, float* v) {
+  if constexpr (F32) {
+    v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w;
+    v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
+  } else {
+    const uint32_t x = __float_as_uint(r.a.x), y = __float_as_uint(r.a.y), z = __float_as_uint(r.a.z),
+                   w = __float_as_uint(r.a.w);
+    v[0] = __uint_as_float(x << 16); v[1] = __uint_as_float(x & 0xffff0000u);
+    v[2] = __uint_as_float(y << 16); v[3] = __uint_as_float(y & 0xffff0000u);
+    v[4] = __uint_as_float(z << 16); v[5] = __uint_as_float(z & 0xffff0000u);
+    v[6] = __uint_as_float(w << 16); v[7] = __uint_as_float(w & 0xffff0000u);
+  }
+}
+
 template <bool F32, int GH>
 __global__ __launch_bounds__(256) void k_attn_partial(
     const float* __restrict__ qkv, int nq, int nkv, const void* __restrict__ kc,
@@ -551,18 +629,24 @@ __global__ __launch_bounds__(256) void k_attn_partial(
   }
   const float scale = 0.08838834764831845f;  // 1 / sqrt(128)
 
+  // all K and V rows of the chunk that this lane group touches, loaded up front (rows past
+  // `pos` re-read row `pos`: valid memory, masked below)
+  Row8Raw<F32> kraw[ATT_CHUNK / 16], vraw[ATT_CHUNK / 16];
+#pragma unroll
+  for (int it = 0; it < ATT_CHUNK / 16; ++it) {
+    const uint32_t j = min(j0 + (uint32_t)(it * 16 + wave * 4 + jj), pos);
+    kraw[it] = load_row8_raw<F32>(kc, base + (size_t)j * 128 + c16 * 8);
+    vraw[it] = load_row8_raw<F32>(vc, base + (size_t)j * 128 + c16 * 8);
+  }
+
   // scores s[h][j] = <q_h, K_j> / sqrt(d); positions beyond `pos` get -inf
+#pragma unroll
   for (int it = 0; it < ATT_CHUNK / 16; ++it) {
     const int jl = it * 16 + wave * 4 + jj;
     const uint32_t j = j0 + jl;
     const bool valid = j <= pos;
     float kv[8];
-    if (valid) {
-      load_row8<F32>(kc, base + (size_t)j * 128 + c16 * 8, kv);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) kv[e] = 0.f;
-    }
+    widen_row8<F32>(kraw[it], kv);
 #pragma unroll
     for (int h = 0; h < GH; ++h) {
       float d = 0.f;
@@ -597,18 +681,16 @@ __global__ __launch_bounds__(256) void k_attn_partial(
   for (int h = 0; h < GH; ++h)
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
+#pragma unroll
   for (int it = 0; it < ATT_CHUNK / 16; ++it) {
     const int jl = it * 16 + wave * 4 + jj;
-    const uint32_t j = j0 + jl;
-    if (j <= pos) {
-      float vv[8];
-      load_row8<F32>(vc, base + (size_t)j * 128 + c16 * 8, vv);
+    float vv[8];
+    widen_row8<F32>(vraw[it], vv);  // masked positions have weight 0 and hold row `pos` (finite)
 #pragma unroll
-      for (int h = 0; h < GH; ++h) {
-        const float w = sc[h][jl];
+    for (int h = 0; h < GH; ++h) {
+      const float w = sc[h][jl];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[h][e] += w * vv[e];
-      }
+      for (int e = 0; e < 8; ++e) acc[h][e] += w * vv[e];
     }
   }
 #pragma unroll
@@ -656,54 +738,53 @@ hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, int nq
 // Merge the chunk partials of one (column, head) and write the attention output
 // as the packed operand of the output projection (k index = head * 128 + i).
 //   M = max_c m_c;  o = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} l_c
-// FRAG = false: split-bf16 (or fp32) columns of the skinny GEMM operand.
-// FRAG = true : one bf16 per value, matrix-core fragment order of the prompt GEMM
-//               ([token / 16][k / 32][64 lanes][8], lane = token % 16 + 16 * ((k % 32) / 8)),
-//               as nsplit (1 or 2) bf16 pieces in adjacent column tiles.
-template <bool F32, bool FRAG>
-__global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ partial, int max_chunks,
+// Output: split-bf16 (or fp32) columns of the skinny GEMM operand.
+template <bool F32>
+__global__ __launch_bounds__(512) void k_attn_combine(const float* __restrict__ partial, int max_chunks,
                                                       int nq, ColMap cm, void* __restrict__ Op, int NC,
                                                       int nsplit) {
-  const int head = blockIdx.x, col = blockIdx.y, i = threadIdx.x;
+  // four groups of 128 threads (one per head dimension) take the chunks round-robin and merge
+  // them online; the four running (max, sum, weighted sum) triples meet in LDS
+  __shared__ float sM[4], sden[4], snum[4][128];
+  const int head = blockIdx.x, col = blockIdx.y, i = threadIdx.x & 127, q = threadIdx.x >> 7;
   const int nchunks = (int)(col_pos(cm, col) / ATT_CHUNK) + 1;
   const float* rec0 = partial + ((size_t)col * nq + head) * max_chunks * 132;
-  float M = -INFINITY;
-  for (int c = 0; c < nchunks; ++c) M = fmaxf(M, rec0[(size_t)c * 132 + 128]);
-  float num = 0.f, den = 0.f;
-  for (int c = 0; c < nchunks; ++c) {
+  float M = -INFINITY, num = 0.f, den = 0.f;
+#pragma unroll 4
+  for (int c = q; c < nchunks; c += 4) {
     const float* rec = rec0 + (size_t)c * 132;
-    const float f = expf(rec[128] - M);
-    num += f * rec[i];
-    den += f * rec[129];
+    const float m = rec[128], l = rec[129], a = rec[i];
+    const float Mn = fmaxf(M, m);
+    const float sc = expf(M - Mn), f = expf(m - Mn);  // sc = 0 on the first chunk (M = -inf)
+    num = num * sc + f * a;
+    den = den * sc + f * l;
+    M = Mn;
   }
-  const int k = head * 128 + i;
-  if constexpr (FRAG) {
-    // nsplit bf16 pieces per value; token tile q occupies column tiles q * nsplit + piece
-    const int t = cm.row0 + col, KT = nq * 4;  // k tiles of the operand: nq * 128 / 32
-    float v = num / den;
-    for (int pc = 0; pc < nsplit; ++pc) {
-      const uint32_t h = bf16_bits(v);
-      v -= bf16_to_f32(h);
-      const size_t e =
-          (((size_t)((t >> 4) * nsplit + pc) * KT + (k >> 5)) * 64 + (t & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
-      static_cast<uint16_t*>(Op)[e] = (uint16_t)h;
-    }
-  } else {
-    store_packed<F32>(Op, NC, nsplit, col, k, num / den);
+  snum[q][i] = num;
+  if (i == 0) {
+    sM[q] = M;
+    sden[q] = den;
   }
+  __syncthreads();
+  if (q != 0) return;
+  const float Mt = fmaxf(fmaxf(sM[0], sM[1]), fmaxf(sM[2], sM[3]));
+  float n = 0.f, d = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const float f = expf(sM[w] - Mt);  // groups without a chunk: exp(-inf) = 0
+    n += f * snum[w][i];
+    d += f * sden[w];
+  }
+  store_packed<F32>(Op, NC, nsplit, col, head * 128 + i, n / d);
 }
 
 hipError_t launch_attn_combine(hipStream_t s, bool f32, const float* partial, int max_chunks, int nq,
-                               const ColMap& cm, int ncols, void* Op, int NC, int nsplit, bool frag) {
+                               const ColMap& cm, int ncols, void* Op, int NC, int nsplit) {
   dim3 grid(nq, ncols);
-  if (frag) {
-    if (f32) return hipErrorInvalidValue;
-    k_attn_combine<false, true><<<grid, 128, 0, s>>>(partial, max_chunks, nq, cm, Op, NC, nsplit);
-  } else if (f32) {
-    k_attn_combine<true, false><<<grid, 128, 0, s>>>(partial, max_chunks, nq, cm, Op, NC, nsplit);
-  } else {
-    k_attn_combine<false, false><<<grid, 128, 0, s>>>(partial, max_chunks, nq, cm, Op, NC, nsplit);
-  }
+  if (f32)
+    k_attn_combine<true><<<grid, 512, 0, s>>>(partial, max_chunks, nq, cm, Op, NC, nsplit);
+  else
+    k_attn_combine<false><<<grid, 512, 0, s>>>(partial, max_chunks, nq, cm, Op, NC, nsplit);
   return hipGetLastError();
 }
 
