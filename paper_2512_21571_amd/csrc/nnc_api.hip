@@ -231,7 +231,7 @@ struct Launch {
 
 // k-slices for the narrow output projections: enough workgroups to cover the chip,
 // but at least 8 k tiles (2 per wave) per workgroup.
-constexpr int MAX_KSPLIT = 16;
+constexpr int MAX_KSPLIT = 8;  // the norm kernel folds at most eight pending partials
 int pick_kts(int n_tiles, int KT) {
   int ksplit = 512 / (n_tiles > 0 ? n_tiles : 1);
   if (ksplit < 1) ksplit = 1;

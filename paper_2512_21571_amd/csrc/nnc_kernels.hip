@@ -235,7 +235,8 @@ __global__ __launch_bounds__(256) void k_rmsnorm_pack(float* __restrict__ x, lon
   __shared__ float sm[4];
   const int seq = blockIdx.x;
   float* xr = x + (size_t)seq * ldx;
-  float4 v[NV], g[NV], pp[NV][4];
+  constexpr int MAXP = 8;  // most k slices a projection is split into
+  float4 v[NV], g[NV], pp[NV][MAXP];
 #pragma unroll
   for (int q = 0; q < NV; ++q) {
     const int i = (threadIdx.x + 256 * q) * 4;
@@ -244,7 +245,7 @@ __global__ __launch_bounds__(256) void k_rmsnorm_pack(float* __restrict__ x, lon
       v[q] = *reinterpret_cast<const float4*>(xr + i);
       g[q] = *reinterpret_cast<const float4*>(gain + i);
 #pragma unroll
-      for (int p = 0; p < 4; ++p)
+      for (int p = 0; p < MAXP; ++p)
         if (p < nparts) pp[q][p] = *reinterpret_cast<const float4*>(part + (size_t)p * part_stride + (size_t)seq * H + i);
     }
   }
@@ -255,7 +256,7 @@ __global__ __launch_bounds__(256) void k_rmsnorm_pack(float* __restrict__ x, lon
     if (i < H && nparts > 0) {
       float4 add = pp[q][0];  // slices are added in a fixed order
 #pragma unroll
-      for (int p = 1; p < 4; ++p)
+      for (int p = 1; p < MAXP; ++p)
         if (p < nparts) add = make_float4(add.x + pp[q][p].x, add.y + pp[q][p].y, add.z + pp[q][p].z, add.w + pp[q][p].w);
       v[q] = make_float4(v[q].x + add.x, v[q].y + add.y, v[q].z + add.z, v[q].w + add.w);
       *reinterpret_cast<float4*>(xr + i) = v[q];
@@ -289,7 +290,7 @@ __global__ __launch_bounds__(256) void k_rmsnorm_pack(float* __restrict__ x, lon
 hipError_t launch_rmsnorm_pack(hipStream_t s, bool f32, float* x, long ldx, const float* part, int nparts,
                                long part_stride, const float* gain, int H, float eps, int ncols, void* Xp,
                                int NC, int nsplit) {
-  if (H % 4 || H > 8192 || nparts > 4 || nparts < 0 || ldx % 4) return hipErrorInvalidValue;
+  if (H % 4 || H > 8192 || nparts > 8 || nparts < 0 || ldx % 4) return hipErrorInvalidValue;
 #define RN_LAUNCH(NV)                                                                                              \
   do {                                                                                                             \
     if (f32) k_rmsnorm_pack<true, NV><<<ncols, 256, 0, s>>>(x, ldx, part, nparts, part_stride, gain, H, eps, Xp, NC, nsplit); \
@@ -348,23 +349,33 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) acc[rt][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  bool colok[NCB];
+  // Two register sets of U k tiles each: the loads of the next group are in flight while the
+  // matrix cores work on the current one.  Loads are unconditional (indices clamped, the weight
+  // fragment zeroed by a select when its k tile lies past the slice), so the loop has no
+  // data-dependent branch and the compiler can wait for exactly the set it needs.  Native
+  // vector types: arrays of the HIP uint4 struct carried across a loop end up in scratch memory.
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4* __restrict__ Wv = reinterpret_cast<const u32x4*>(W);
+  const u32x4* __restrict__ Xv = reinterpret_cast<const u32x4*>(X);
+  int bcol[NCB];
 #pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) colok[cb] = cb * 16 + c16 < a.ncols;
-
-  for (int kt0 = kt_begin + wave; kt0 < kt_end; kt0 += 4 * U) {
-    uint4 av[U][RT], bv[U][NCB];
+  for (int cb = 0; cb < NCB; ++cb) bcol[cb] = min(cb * 16 + c16, a.NC - 1);
+  u32x4 avA[U][RT], bvA[U][NCB], avB[U][RT], bvB[U][NCB];
+  auto load_group = [&](int kt0, u32x4(&av)[U][RT], u32x4(&bv)[U][NCB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int kt = kt0 + 4 * u;
+      const int kt = kt0 + 4 * u, ktc = min(kt, kt_end - 1);
       const bool ok = kt < kt_end;
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
-        av[u][rt] = ok ? W[((tile0 + rt) * KT + kt) * 64 + lane] : uint4{0, 0, 0, 0};
+      for (int rt = 0; rt < RT; ++rt) {
+        const u32x4 t = Wv[((tile0 + rt) * KT + ktc) * 64 + lane];
+        av[u][rt] = ok ? t : u32x4{0u, 0u, 0u, 0u};
+      }
 #pragma unroll
-      for (int cb = 0; cb < NCB; ++cb)
-        bv[u][cb] = (ok && colok[cb]) ? X[((size_t)kt * 4 + g) * a.NC + cb * 16 + c16] : uint4{0, 0, 0, 0};
+      for (int cb = 0; cb < NCB; ++cb) bv[u][cb] = Xv[((size_t)ktc * 4 + g) * a.NC + bcol[cb]];
     }
+  };
+  auto mma_group = [&](const u32x4(&av)[U][RT], const u32x4(&bv)[U][NCB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -385,6 +396,20 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
           }
         }
       }
+    }
+  };
+  if (kt_begin + wave < kt_end) {  // waves without a k tile in this slice keep zero accumulators
+    int kt0 = kt_begin + wave;
+    load_group(kt0, avA, bvA);
+    for (;;) {
+      load_group(kt0 + 4 * U, avB, bvB);
+      mma_group(avA, bvA);
+      kt0 += 4 * U;
+      if (kt0 >= kt_end) break;
+      load_group(kt0 + 4 * U, avA, bvA);
+      mma_group(avB, bvB);
+      kt0 += 4 * U;
+      if (kt0 >= kt_end) break;
     }
   }
 
@@ -410,13 +435,15 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
   };
 
   if constexpr (EPI == EPI_SWIGLU) {
-    static_assert(EPI != EPI_SWIGLU || RT == 2, "SwiGLU needs the (gate, up) tile pair");
-    for (int o = tid; o < 16 * nseq; o += 256) {
-      const int seq = o >> 4, row = o & 15;
-      const float gate = total(0, row, seq);
-      const float up = total(RT - 1, row, seq);
+    static_assert(EPI != EPI_SWIGLU || RT % 2 == 0, "SwiGLU needs (gate, up) tile pairs");
+    for (int o = tid; o < (RT / 2) * 16 * nseq; o += 256) {
+      const int pr = o / (16 * nseq);
+      const int rem = o - pr * 16 * nseq;
+      const int seq = rem >> 4, row = rem & 15;
+      const float gate = total(2 * pr, row, seq);
+      const float up = total(2 * pr + 1, row, seq);
       const float act = gate / (1.0f + expf(-gate)) * up;
-      const int f = blockIdx.x * 16 + row;
+      const int f = (blockIdx.x * (RT / 2) + pr) * 16 + row;
       store_packed<F32>(a.packed_out, a.NC_out, a.nsplit_out, seq, f, act);
     }
   } else {
@@ -458,7 +485,17 @@ static hipError_t gemm_dispatch_ncb(hipStream_t s, const GemmArgs& a) {
 // 1 for the narrow output projections, where more workgroups matter more.  Those
 // also split k across workgroups; each slice stores its own partial result and the
 // consumer (k_rmsnorm_pack / k_fold_residual) adds the slices in a fixed order, so
-// results do not depend on scheduling.
+// results do not depend on scheduling.  With more than 16 operand columns (batched decode)
+// every workgroup re-reads the whole operand from L2, all of them the same lines at about the
+// same time; twice the row tiles per workgroup halve that traffic.
+template <bool F32, int EPI, int RT>
+static hipError_t gemm_dispatch_rt(hipStream_t s, const GemmArgs& a) {
+  const int ncb = (a.ncols + 15) / 16;
+  if (ncb >= 2 && ncb <= 3 && a.n_tiles % (2 * RT) == 0 && a.n_tiles / (2 * RT) >= 128)
+    return gemm_dispatch_ncb<F32, EPI, 2 * RT>(s, a);
+  return gemm_dispatch_ncb<F32, EPI, RT>(s, a);
+}
+
 hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a) {
   if (a.ncols <= 0 || a.ncols > MAX_COLS || a.ncols > a.NC || a.nseq * a.nsplit != a.ncols ||
       a.kts_per_split <= 0 || a.n_tiles <= 0)
@@ -466,11 +503,11 @@ hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a) {
   const bool wide = a.n_tiles >= 1024 && (a.n_tiles % 2 == 0);
   if (epi == EPI_SWIGLU) {
     if (a.n_tiles % 2 || a.kts_per_split < a.KT) return hipErrorInvalidValue;
-    return f32 ? gemm_dispatch_ncb<true, EPI_SWIGLU, 2>(s, a) : gemm_dispatch_ncb<false, EPI_SWIGLU, 2>(s, a);
+    return f32 ? gemm_dispatch_rt<true, EPI_SWIGLU, 2>(s, a) : gemm_dispatch_rt<false, EPI_SWIGLU, 2>(s, a);
   }
   if (epi != EPI_STORE) return hipErrorInvalidValue;
-  if (wide) return f32 ? gemm_dispatch_ncb<true, EPI_STORE, 2>(s, a) : gemm_dispatch_ncb<false, EPI_STORE, 2>(s, a);
-  return f32 ? gemm_dispatch_ncb<true, EPI_STORE, 1>(s, a) : gemm_dispatch_ncb<false, EPI_STORE, 1>(s, a);
+  if (wide) return f32 ? gemm_dispatch_rt<true, EPI_STORE, 2>(s, a) : gemm_dispatch_rt<false, EPI_STORE, 2>(s, a);
+  return f32 ? gemm_dispatch_rt<true, EPI_STORE, 1>(s, a) : gemm_dispatch_rt<false, EPI_STORE, 1>(s, a);
 }
 
 // Which sequence position a column of a pass stands for: decode passes look it up in the
