@@ -35,6 +35,7 @@
 #include <cstring>
 
 #include "nnc_internal.h"
+#include "nnc_lanes.h"
 
 namespace nnc {
 
@@ -94,17 +95,6 @@ __device__ __forceinline__ uint32_t bf16_bits(float f) {
 }
 __device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
-}
-
 }  // namespace
 
 struct MkLayer {
@@ -153,7 +143,7 @@ namespace {
 struct Smem {
   union {
     float red[MK_WAVES][2][256];   // GEMM: per-wave accumulator tiles
-    float ared[MK_WAVES][4][128];  // attention: per-wave value sums
+    float ared[MK_WAVES][4][4][128];  // attention: value sums per wave, row group of 16 lanes and head
   };
   float wsum[MK_WAVES];
   float sc[4][ATT_CHUNK];
@@ -575,10 +565,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
               float d = 0.f;
 #pragma unroll
               for (int e = 0; e < 8; ++e) d += q[h][e] * kv[e];
-              d += __shfl_xor(d, 1, 64);
-              d += __shfl_xor(d, 2, 64);
-              d += __shfl_xor(d, 4, 64);
-              d += __shfl_xor(d, 8, 64);
+              d = row16_sum(d);
               if (c16 == 0) sm.sc[h][jl] = j <= pos ? d * 0.08838834764831845f : -INFINITY;
             }
           }
@@ -624,20 +611,18 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
             }
           }
 #pragma unroll
-          for (int h = 0; h < GH; ++h)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              float v = acc[h][e];
-              v += __shfl_xor(v, 16, 64);
-              v += __shfl_xor(v, 32, 64);
-              if (jj == 0) sm.ared[wave][h][c16 * 8 + e] = v;
-            }
+          for (int h = 0; h < GH; ++h) {
+            float4* dst = reinterpret_cast<float4*>(&sm.ared[wave][jj][h][c16 * 8]);
+            dst[0] = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
+            dst[1] = make_float4(acc[h][4], acc[h][5], acc[h][6], acc[h][7]);
+          }
           wg_sync();
           for (int o = tid; o < GH * 128; o += MK_THREADS) {
             const int h = o >> 7, i = o & 127;
             float v = 0.f;
 #pragma unroll
-            for (int w = 0; w < MK_WAVES; ++w) v += sm.ared[w][h][i];
+            for (int w = 0; w < MK_WAVES; ++w)
+              v += (sm.ared[w][0][h][i] + sm.ared[w][1][h][i]) + (sm.ared[w][2][h][i] + sm.ared[w][3][h][i]);
             u64* rec = a.xatt + ((size_t)(head0 + h) * a.max_chunks + chunk) * 132;
             st_t(rec + i, v, t_att);
             if (i == 0) {
@@ -707,8 +692,8 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
               }
             M = Mn;
           }
-          sm.ared[wave][0][lane] = n0;
-          sm.ared[wave][0][lane + 64] = n1;
+          sm.ared[wave][0][0][lane] = n0;
+          sm.ared[wave][0][0][lane + 64] = n1;
           if (lane == 0) {
             sm.att_m[wave] = M;
             sm.att_l[wave] = den;
@@ -723,7 +708,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
 #pragma unroll
             for (int w = 0; w < MK_WAVES; ++w) {
               const float f = expf(sm.att_m[w] - Mt);  // waves without a chunk: exp(-inf) = 0
-              num += f * sm.ared[w][0][tid];
+              num += f * sm.ared[w][0][0][tid];
               dn += f * sm.att_l[w];
             }
             st_t(a.xo + (size_t)h * 128 + tid, num / dn, t_att);

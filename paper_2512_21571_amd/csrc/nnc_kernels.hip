@@ -7,6 +7,7 @@
 // loads.  Everything else (norms, RoPE, SwiGLU, attention) is the public Qwen3
 // decoder arithmetic in fp32.
 #include "nnc_internal.h"
+#include "nnc_lanes.h"
 
 namespace nnc {
 
@@ -39,18 +40,6 @@ __device__ __forceinline__ void split_bf16(float v, int nsplit, uint32_t* piece)
   }
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
-}
-
-// Sum over a 256-thread block; every thread gets the result.  `sm` holds 4 floats.
 __device__ __forceinline__ float block_sum_256(float v, float* sm) {
   v = wave_sum(v);
   __syncthreads();
@@ -641,7 +630,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(
     const void* __restrict__ vc, uint32_t max_seq, ColMap cm,
     float* __restrict__ partial, int max_chunks) {
   __shared__ float sc[GH][ATT_CHUNK];      // scores, then softmax weights
-  __shared__ float red[4][GH][128];        // per-wave value sums
+  __shared__ float red[4][4][GH][128];     // value sums per wave and per row group of 16 lanes
   __shared__ float sm_m[GH], sm_l[GH];
   const int chunk = blockIdx.x, col = blockIdx.z;
   const int G = nq / nkv;
@@ -689,10 +678,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(
       float d = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) d += q[h][e] * kv[e];
-      d += __shfl_xor(d, 1, 64);
-      d += __shfl_xor(d, 2, 64);
-      d += __shfl_xor(d, 4, 64);
-      d += __shfl_xor(d, 8, 64);
+      d = row16_sum(d);
       if (c16 == 0) sc[h][jl] = valid ? d * scale : -INFINITY;
     }
   }
@@ -731,19 +717,18 @@ __global__ __launch_bounds__(256) void k_attn_partial(
     }
   }
 #pragma unroll
-  for (int h = 0; h < GH; ++h)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float v = acc[h][e];
-      v += __shfl_xor(v, 16, 64);
-      v += __shfl_xor(v, 32, 64);
-      if (jj == 0) red[wave][h][c16 * 8 + e] = v;
-    }
+  for (int h = 0; h < GH; ++h) {
+    float4* dst = reinterpret_cast<float4*>(&red[wave][jj][h][c16 * 8]);
+    dst[0] = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
+    dst[1] = make_float4(acc[h][4], acc[h][5], acc[h][6], acc[h][7]);
+  }
   __syncthreads();
   // partial record per (column, head, chunk): 128 value sums, then max, then sum
   for (int o = tid; o < GH * 128; o += 256) {
     const int h = o >> 7, i = o & 127;
-    const float v = (red[0][h][i] + red[1][h][i]) + (red[2][h][i] + red[3][h][i]);
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) v += (red[w][0][h][i] + red[w][1][h][i]) + (red[w][2][h][i] + red[w][3][h][i]);
     float* rec = partial + (((size_t)col * nq + head0 + h) * max_chunks + chunk) * 132;
     rec[i] = v;
     if (i == 0) {

@@ -9,6 +9,7 @@
 // unpacked in between.  Activations entering a GEMM are rounded to bf16 once (round to
 // nearest even): that is the precision contract of this path.
 #include "nnc_internal.h"
+#include "nnc_lanes.h"
 
 #include <type_traits>
 #include <utility>
@@ -46,12 +47,6 @@ __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int
 template <int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
 }
 
 // Block tile: NT row tiles (16 rows each) x TT column tiles (16 operand columns each), k step
