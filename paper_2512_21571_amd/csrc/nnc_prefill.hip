@@ -67,10 +67,10 @@ __device__ __forceinline__ void static_for(F&& f) {
 // every LDS access is a conflict-free 16-byte access at lane * 16.  Double-buffered in LDS,
 // fed from a register ring several k steps deep; one workgroup barrier per k step.
 #ifndef PG_RING
-#define PG_RING(NT) ((NT) == 16 ? 4 : 8)
+#define PG_RING(NT) ((NT) == 16 ? 2 : 8)
 #endif
 template <int EPI, int NT, int TT, int PIECES>
-__global__ __launch_bounds__(256) void k_gemm_prefill(PrefillGemmArgs a) {
+__global__ __launch_bounds__(256, 2) void k_gemm_prefill(PrefillGemmArgs a) {
   constexpr int WI = NT / 2;   // row tiles per wave
   constexpr int AL = NT / 4;   // 16-byte A loads per thread and k step
   constexpr int WJ = TT / 2;   // column tiles per wave
@@ -94,22 +94,30 @@ __global__ __launch_bounds__(256) void k_gemm_prefill(PrefillGemmArgs a) {
   // steps of matrix-core work cover the memory latency even with one workgroup per CU.
   constexpr int D = PG_RING(NT);  // even; sized to the registers left beside the accumulators
   u32x4 ra[D][AL], rb[D][BL];  // native vectors: arrays of the HIP uint4 struct end up in scratch memory
-  // Loads are unconditional (tile and k indices clamped to the last valid one) so that the
-  // main loop is free of data-dependent branches and the compiler can wait for exactly the
-  // ring stage it needs; rows / columns past the edge compute garbage that is never stored.
+  // Load addresses = wave-uniform base of the k step (scalar registers) + a per-thread 32-bit
+  // byte offset fixed for the whole kernel (tile indices clamped to the last valid one: rows /
+  // columns past the edge compute garbage that is never stored).  The steady-state loop thus
+  // has no vector address arithmetic and no data-dependent branch, and the compiler waits per
+  // ring stage.
+  uint32_t voa[AL], vob[BL];
+#pragma unroll
+  for (int j = 0; j < AL; ++j) {
+    const int idx = tid + 256 * j, tile = min(nt0 + (idx >> 6), a.n_tiles - 1);
+    voa[j] = ((uint32_t)tile * (uint32_t)KT * 64u + (uint32_t)(idx & 63)) * 16u;
+  }
+#pragma unroll
+  for (int j = 0; j < BL; ++j) {
+    const int idx = tid + 256 * j, tile = min(tt0 + (idx >> 6), a.t_tiles - 1);
+    vob[j] = ((uint32_t)tile * (uint32_t)KT * 64u + (uint32_t)(idx & 63)) * 16u;
+  }
   auto gload = [&](auto stc, int kt) __attribute__((always_inline)) {
     constexpr int st = decltype(stc)::value;
-    kt = min(kt, KT - 1);
+    const char* wb = reinterpret_cast<const char*>(W) + (size_t)kt * 1024;
+    const char* xb = reinterpret_cast<const char*>(X) + (size_t)kt * 1024;
 #pragma unroll
-    for (int j = 0; j < AL; ++j) {
-      const int idx = tid + 256 * j, tile = min(nt0 + (idx >> 6), a.n_tiles - 1), ln = idx & 63;
-      ra[st][j] = W[((size_t)tile * KT + kt) * 64 + ln];
-    }
+    for (int j = 0; j < AL; ++j) ra[st][j] = *reinterpret_cast<const u32x4*>(wb + voa[j]);
 #pragma unroll
-    for (int j = 0; j < BL; ++j) {
-      const int idx = tid + 256 * j, tile = min(tt0 + (idx >> 6), a.t_tiles - 1), ln = idx & 63;
-      rb[st][j] = X[((size_t)tile * KT + kt) * 64 + ln];
-    }
+    for (int j = 0; j < BL; ++j) rb[st][j] = *reinterpret_cast<const u32x4*>(xb + vob[j]);
   };
   auto sstore = [&](auto stc, auto bufc) __attribute__((always_inline)) {
     constexpr int st = decltype(stc)::value, buf = decltype(bufc)::value;
@@ -125,9 +133,10 @@ __global__ __launch_bounds__(256) void k_gemm_prefill(PrefillGemmArgs a) {
     }
   };
   // One k step: ring stage d holds step kt (already copied to LDS buffer d & 1; D is even).
-  auto step = [&](int kt, auto dc) __attribute__((always_inline)) {
+  // LOAD: the step D ahead exists and is fetched into the stage that this step frees.
+  auto step = [&](int kt, auto dc, auto loadc) __attribute__((always_inline)) {
     constexpr int d = decltype(dc)::value;
-    gload(dc, kt + D);
+    if constexpr (decltype(loadc)::value) gload(dc, kt + D);
     u32x4 af[WI], bf[WJ];
 #pragma unroll
     for (int i = 0; i < WI; ++i) af[i] = As[d & 1][wn * WI + i][lane];
@@ -139,20 +148,32 @@ __global__ __launch_bounds__(256) void k_gemm_prefill(PrefillGemmArgs a) {
       for (int j = 0; j < WJ; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[i]),
                                                             __builtin_bit_cast(bf16x8, bf[j]), acc[i][j], 0, 0, 0);
-    // step kt + 1 into the other buffer (past the end: a clamped copy nobody reads)
+    // step kt + 1 into the other buffer (past the end: a stale copy nobody reads)
     sstore(std::integral_constant<int, (d + 1) % D>{}, std::integral_constant<int, (d + 1) & 1>{});
     lds_sync();
   };
 
-  static_for<D>([&](auto dc) __attribute__((always_inline)) { gload(dc, decltype(dc)::value); });
+  // prologue: the first min(D, KT) steps into the ring, step 0 into LDS
+  static_for<D>([&](auto dc) __attribute__((always_inline)) {
+    if (decltype(dc)::value < KT) gload(dc, decltype(dc)::value);
+  });
   sstore(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
   lds_sync();
   int kt0 = 0;
-  for (; kt0 + D <= KT; kt0 += D)
-    static_for<D>([&](auto dc) __attribute__((always_inline)) { step(kt0 + decltype(dc)::value, dc); });
-  static_for<D>([&](auto dc) __attribute__((always_inline)) {
-    if (kt0 + decltype(dc)::value < KT) step(kt0 + decltype(dc)::value, dc);
-  });
+  // steady state: whole rounds of D steps whose look-ahead loads all exist
+  for (; kt0 + 2 * D <= KT; kt0 += D)
+    static_for<D>([&](auto dc) __attribute__((always_inline)) {
+      step(kt0 + decltype(dc)::value, dc, std::true_type{});
+    });
+  // the last steps (fewer than 2 D), without look-ahead loads past the end
+  for (; kt0 < KT; kt0 += D)
+    static_for<D>([&](auto dc) __attribute__((always_inline)) {
+      const int kt = kt0 + decltype(dc)::value;
+      if (kt < KT) {
+        if (kt + D < KT) gload(dc, kt + D);
+        step(kt, dc, std::false_type{});
+      }
+    });
 
   // accumulator element e of lane l in tile (i, j): row (l / 16) * 4 + e of row tile i,
   // operand column l % 16 of column tile j.  With two pieces, column tiles 2q and 2q+1 are
