@@ -36,6 +36,38 @@ __device__ __forceinline__ float lane_get(float v, int lane) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
 
+// Sum / maximum over the four lanes that share lane % 16 (one per row of 16 lanes), returned
+// in all four, with the two row-swap instructions of gfx950 (no LDS).  v_permlane16_swap
+// exchanges row 1 of its first register with row 0 of its second, and row 3 with row 2: from
+// two copies of v it leaves rows [0,0,2,2] in the first and [1,1,3,3] in the second.
+// v_permlane32_swap exchanges the upper half of the first with the lower half of the second:
+// rows [0,1,0,1] and [2,3,2,3].  Written as inline assembly with both registers as in/out
+// operands: the compiler's builtin folds the two results into one when its inputs are equal.
+// The leading s_nop covers the wait states the instruction needs after a vector write of its
+// operands.
+__device__ __forceinline__ void row_swap16(float& a, float& b) {
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void row_swap32(float& a, float& b) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float col4_max(float v) {
+  float a = v, b = v;
+  row_swap16(a, b);
+  a = fmaxf(a, b);
+  b = a;
+  row_swap32(a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float col4_sum(float v) {
+  float a = v, b = v;
+  row_swap16(a, b);
+  a = a + b;
+  b = a;
+  row_swap32(a, b);
+  return a + b;
+}
+
 // Sum / maximum over the whole wave, returned in every lane (wave-uniform).
 __device__ __forceinline__ float wave_sum(float v) {
   v = row16_sum(v);

@@ -375,7 +375,8 @@ hipError_t launch_v_transpose(hipStream_t s, const void* vc, uint32_t slot, int 
   return hipGetLastError();
 }
 
-// Scores and weighted sums of 16 prompt tokens x GH query heads (sharing one kv head) per wave,
+// Scores and weighted sums of 16 prompt tokens x GH query heads (sharing one kv head) per wave
+// (= workgroup),
 // flash style: positions are walked in chunks of 32 with a running maximum and sum per row.
 // Both products run transposed, so that no operand needs a shuffle between them:
 //   S^T = K Q^T   A = 16 cached K rows (their 128 dims in four k steps, straight from the
@@ -392,15 +393,17 @@ hipError_t launch_v_transpose(hipStream_t s, const void* vc, uint32_t slot, int 
 // PIECES = 2: queries and weights enter the matrix cores as two bf16 pieces (16 significant
 // bits); PIECES = 1: one bf16 each, and the row sum adds the rounded weights.
 template <int GH, int PIECES>
-__global__ __launch_bounds__(256) void k_attn_prefill(const float* __restrict__ qkv, int nq, int nkv,
+__global__ __launch_bounds__(64) void k_attn_prefill(const float* __restrict__ qkv, int nq, int nkv,
                                                       const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vt,
                                                       uint32_t S, uint32_t slot, uint32_t max_seq, uint32_t pos0,
                                                       int n, void* __restrict__ Of) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int lane = threadIdx.x;
   const int c16 = lane & 15, g = lane >> 4;
   const int G = nq / nkv;
   const int kvh = blockIdx.y / (G / GH), head0 = kvh * G + (blockIdx.y % (G / GH)) * GH;
-  const int tq = blockIdx.x * 4 + wave;  // token tile of this wave
+  // one wave per workgroup; the longest rows (last token tiles) are dispatched first, so the
+  // causal triangle packs onto the CUs without a long tail
+  const int tq = (int)gridDim.x - 1 - (int)blockIdx.x;
   if (tq * 16 >= n) return;
   const int ld = (nq + 2 * nkv) * 128;
   const int t = min(tq * 16 + c16, n - 1);  // rows past the prompt repeat the last token (never used)
@@ -442,18 +445,24 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float* __restrict__ 
   const uint32_t p_last = pos0 + (uint32_t)min(tq * 16 + 15, n - 1);  // last position any row of the tile sees
   const int r4 = (c16 >> 2) * 8 + (c16 & 3);  // K row of tile a for A-operand row c16; tile b: + 4
 
-  for (uint32_t kv0 = 0; kv0 <= p_last; kv0 += 32) {
-    u32x4 ka[4], kb[4], vf[8];
+  // The fragments of the next chunk are loaded into a second register set while this chunk is
+  // being multiplied.
+  u32x4 ka[2][4], kb[2][4], vf[2][8];
+  auto load_chunk = [&](auto stc, uint32_t kv0) __attribute__((always_inline)) {
+    constexpr int st = decltype(stc)::value;
     const uint32_t ra = min(kv0 + r4, max_seq - 1), rb = min(kv0 + r4 + 4, max_seq - 1);
+    const uint32_t kvv = min(kv0, S - 32);  // past the last chunk: any valid chunk (never used)
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      ka[ks] = *reinterpret_cast<const u32x4*>(kbase + (size_t)ra * 128 + ks * 32 + g * 8);
-      kb[ks] = *reinterpret_cast<const u32x4*>(kbase + (size_t)rb * 128 + ks * 32 + g * 8);
+      ka[st][ks] = *reinterpret_cast<const u32x4*>(kbase + (size_t)ra * 128 + ks * 32 + g * 8);
+      kb[st][ks] = *reinterpret_cast<const u32x4*>(kbase + (size_t)rb * 128 + ks * 32 + g * 8);
     }
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
-      vf[dt] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(dt * 16 + c16) * S + kv0 + g * 8);
-
+      vf[st][dt] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(dt * 16 + c16) * S + kvv + g * 8);
+  };
+  auto do_chunk = [&](auto stc, uint32_t kv0) __attribute__((always_inline)) {
+    constexpr int st = decltype(stc)::value;
 #pragma unroll
     for (int h = 0; h < GH; ++h) {
       f32x4 sa = f32x4{0.f, 0.f, 0.f, 0.f}, sb = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -461,9 +470,9 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float* __restrict__ 
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
         for (int pc = 0; pc < PIECES; ++pc) {
-          sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[ks]),
+          sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[st][ks]),
                                                        __builtin_bit_cast(bf16x8, qf[h][ks][pc]), sa, 0, 0, 0);
-          sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[ks]),
+          sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[st][ks]),
                                                        __builtin_bit_cast(bf16x8, qf[h][ks][pc]), sb, 0, 0, 0);
         }
       // element i of sa: position kv0 + g*8 + i; of sb: kv0 + g*8 + 4 + i; column = this lane's token
@@ -472,20 +481,22 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float* __restrict__ 
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const uint32_t kv = kv0 + g * 8 + i;
-        const float v = (i < 4 ? sa[i] : sb[i - 4]) * 0.08838834764831845f;
+        // scores in units of log 2: exp(s / sqrt(128)) = exp2(s * log2(e) / sqrt(128))
+        const float v = (i < 4 ? sa[i] : sb[i - 4]) * 0.12751743082459868f;
         sc[i] = kv <= p ? v : -INFINITY;
         mx = fmaxf(mx, sc[i]);
       }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = col4_max(mx);
       const float mn = fmaxf(mrun[h], mx);  // finite from the first chunk on: position 0 is visible to every token
-      const float alpha = expf(mrun[h] - mn);
+      const float alpha = __builtin_amdgcn_exp2f(mrun[h] - mn);
+      // once the running maxima have settled the rescale is a multiplication by one: skip it
+      const bool rescale = __any(mn != mrun[h]);
       mrun[h] = mn;
       uint32_t pb[PIECES][8];
       float rs = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        float w = expf(sc[i] - mn);
+        float w = __builtin_amdgcn_exp2f(sc[i] - mn);
         if constexpr (PIECES == 1) {
           pb[0][i] = bf16_bits(w);
           rs += bf16_to_f32(pb[0][i]);
@@ -499,19 +510,34 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float* __restrict__ 
         }
       }
       lsum[h] = lsum[h] * alpha + rs;
+      if (rescale) {
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[h][dt][e] *= alpha;
+      }
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[h][dt][e] *= alpha;
 #pragma unroll
         for (int pc = 0; pc < PIECES; ++pc) {
           const u32x4 pf = u32x4{pb[pc][0] | (pb[pc][1] << 16), pb[pc][2] | (pb[pc][3] << 16),
                                  pb[pc][4] | (pb[pc][5] << 16), pb[pc][6] | (pb[pc][7] << 16)};
-          acc[h][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[dt]),
+          acc[h][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[st][dt]),
                                                                __builtin_bit_cast(bf16x8, pf), acc[h][dt], 0, 0, 0);
         }
       }
     }
+    };
+  load_chunk(std::integral_constant<int, 0>{}, 0);
+  for (uint32_t kv0 = 0;;) {
+    load_chunk(std::integral_constant<int, 1>{}, kv0 + 32);
+    do_chunk(std::integral_constant<int, 0>{}, kv0);
+    kv0 += 32;
+    if (kv0 > p_last) break;
+    load_chunk(std::integral_constant<int, 0>{}, kv0 + 32);
+    do_chunk(std::integral_constant<int, 1>{}, kv0);
+    kv0 += 32;
+    if (kv0 > p_last) break;
   }
 
   // acc[h][dt] element e: head dim dt*16 + g*4 + e of this lane's token.  Output goes straight
@@ -520,8 +546,7 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float* __restrict__ 
 #pragma unroll
   for (int h = 0; h < GH; ++h) {
     float l = lsum[h];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
+    l = col4_sum(l);
     const float inv = 1.0f / l;
     if (tq * 16 + c16 < n) {
 #pragma unroll
@@ -553,13 +578,13 @@ hipError_t launch_attn_prefill(hipStream_t s, const float* qkv, int nq, int nkv,
   if (n <= 0 || G < 1 || nq % nkv || (pieces != 1 && pieces != 2) || S % 32 || pos0 + (uint32_t)n > S)
     return hipErrorInvalidValue;
   const int GH = G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1);
-  dim3 grid((n + 63) / 64, nkv * (G / GH));
+  dim3 grid((n + 15) / 16, nkv * (G / GH));
   const uint16_t* k = static_cast<const uint16_t*>(kc);
   const uint16_t* v = static_cast<const uint16_t*>(vt);
 #define AP_LAUNCH(GHV)                                                                                          \
   do {                                                                                                          \
-    if (pieces == 2) k_attn_prefill<GHV, 2><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, Of); \
-    else k_attn_prefill<GHV, 1><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, Of);           \
+    if (pieces == 2) k_attn_prefill<GHV, 2><<<grid, 64, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, Of); \
+    else k_attn_prefill<GHV, 1><<<grid, 64, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, Of);           \
   } while (0)
   if (GH == 4) AP_LAUNCH(4);
   else if (GH == 2) AP_LAUNCH(2);
