@@ -160,8 +160,11 @@ typedef enum {
                                0 (default): blocks of up to 2048 tokens with LDS-staged
                                matrix-core GEMMs and matrix-core attention.  Blocks of up to 512
                                tokens carry every matrix-core input as two bf16 pieces (16
-                               significant bits); longer blocks round those inputs to bf16 once
-                               (the LM head of the last position stays fp32-grade).
+                               significant bits); longer blocks round those inputs to bf16 once.
+                               A call with more than 512 tokens runs its last 128 tokens as a
+                               block of their own (two pieces), so that the logits of the last
+                               position see single-piece noise only through the cache; the LM
+                               head itself is always fp32-grade.
                                2: the same blocks, two pieces at every length (twice the
                                matrix-core work of long blocks).
                                1: 21-token chunks through the decode kernels, three bf16 pieces

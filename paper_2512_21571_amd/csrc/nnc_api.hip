@@ -125,6 +125,7 @@ struct nnc_model {
 
 namespace {
 
+constexpr uint32_t PREFILL_TAIL = 128;     // last tokens of a long prompt that run as a two-piece block
 constexpr uint32_t MAX_DECODE_BATCH = 21;  // 21 sequences x 3 pieces = 63 operand columns
 
 nnc_status check_config(const nnc_config* c) {
@@ -843,12 +844,20 @@ static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tok
       if (tokens[i] < 0 || (uint32_t)tokens[i] >= m->c.vocab) return fail(NNC_E_ARG, "token %d out of range", tokens[i]);
   if (tokens && m->pb_max && m->opt_prefill_exact != 1) {
     const uint32_t len0 = m->len[slot];
-    for (uint32_t t0 = 0; t0 < n; t0 += m->pb_max) {
-      const uint32_t nb = std::min(m->pb_max, n - t0);
+    // Blocks of up to pb_max tokens.  A block of more than 512 tokens rounds its matrix-core
+    // inputs to bf16 once; that noise must not reach the logits directly, so the last
+    // PREFILL_TAIL tokens of a longer prompt (the last of which yields the logits) always form
+    // a block of their own, which then carries two pieces.
+    uint32_t head = n;
+    if (m->opt_prefill_exact == 0 && n > 512) head = n - PREFILL_TAIL;
+    for (uint32_t t0 = 0; t0 < n;) {
+      const uint32_t end = t0 < head ? head : n;
+      const uint32_t nb = std::min(m->pb_max, end - t0);
       const bool last = t0 + nb == n;
       if (nnc_status st = prefill_block(m, slot, tokens + t0, nb, len0 + t0, last && (logits_out || next_out),
                                         logits_out, next_out ? m->next : nullptr))
         return st;
+      t0 += nb;
     }
     if (next_out) HIP_TRY(hipMemcpyAsync(next_out, m->next, 4, hipMemcpyDeviceToDevice, m->stream));
     m->len[slot] = len0 + n;

@@ -36,3 +36,30 @@ def rel_inf(got: np.ndarray, want: np.ndarray) -> float:
 def top2_margin(logits: np.ndarray) -> float:
     part = np.partition(logits, -2)
     return float(part[-1] - part[-2])
+
+
+# The library's documented blocking of a prompt call on the large-block path (include/nnc.h,
+# NNC_OPT_PREFILL_EXACT = 0), restated here for the tests: blocks of up to 2048 tokens; a call
+# of more than 512 tokens runs its last 128 tokens as a block of their own; a block of more
+# than 512 tokens carries one bf16 piece per matrix-core input, else two.
+PREFILL_BLOCK, PREFILL_TAIL, ONE_PIECE_ABOVE = 2048, 128, 512
+
+
+def prefill_blocks(n: int):
+    """[(first token, tokens, pieces)] of a default-mode prompt call of n tokens."""
+    head = n - PREFILL_TAIL if n > ONE_PIECE_ABOVE else n
+    out, t0 = [], 0
+    while t0 < n:
+        end = head if t0 < head else n
+        nb = min(PREFILL_BLOCK, end - t0)
+        out.append((t0, nb, 1 if nb > ONE_PIECE_ABOVE else 2))
+        t0 += nb
+    return out
+
+
+def oracle_prefill_like_library(o, slot, toks, shape):
+    """The oracle's prompt pass with the library's rounding points mirrored block by block."""
+    res = None
+    for t0, nb, pieces in prefill_blocks(len(toks)):
+        res = o.prefill(slot, toks[t0:t0 + nb], oracle_flags(shape, mirrored_prefill=pieces == 1))
+    return res

@@ -16,7 +16,7 @@ import pytest
 
 import oracle
 import synth
-from parity_util import oracle_flags, rel_inf, top2_margin
+from parity_util import oracle_flags, oracle_prefill_like_library, rel_inf, top2_margin
 
 pytestmark = pytest.mark.gpu
 
@@ -148,7 +148,7 @@ def test_config2_qwen3_1p7b_bf16_prompt512_decode(nnc):
 def _sampled_depth(nnc, base, n_layers, long_ctx, batch, steps, label):
     """Configs 3 and 4 at their real layer shape, vocabulary and context, with the depth cut to
     what the fp64 oracle finishes in about a minute: slot 0 holds the full context (filled by the
-    large-block prompt path, single-bf16 GEMM inputs mirrored by the oracle), the other slots
+    large-block prompt path, its single-bf16 blocks mirrored by the oracle), the other slots
     short ragged contexts; then batched decode steps, every slot compared with the oracle."""
     import dataclasses
     shape = dataclasses.replace(synth.SHAPES[base], name=f"{base}-{n_layers}layers", n_layers=n_layers)
@@ -162,7 +162,7 @@ def _sampled_depth(nnc, base, n_layers, long_ctx, batch, steps, label):
     for b, n in enumerate(lens):
         toks = synth.tokens(n, shape.vocab, stream=b)
         lg, _ = g.prefill(b, toks)
-        lo, nxt = o.prefill(b, toks, oracle_flags(shape, mirrored_prefill=n > 512))
+        lo, nxt = oracle_prefill_like_library(o, b, toks, shape)
         _check_step(lg, lo, f"{label} prompt slot {b}", stats)
         t.append(nxt)
     print(f"  {label}: prompts max abs err {stats['err']:.3e}", flush=True)

@@ -11,20 +11,19 @@ import pytest
 
 import oracle
 import synth
-from parity_util import (SMALL_BF16, SMALL_F32, SMALL_G4, SMALL_LAYER_F32, oracle_flags, rel_inf)
+from parity_util import (SMALL_BF16, SMALL_F32, SMALL_G4, SMALL_LAYER_F32, oracle_flags,
+                         oracle_prefill_like_library, prefill_blocks, rel_inf)
 
 pytestmark = pytest.mark.gpu
 
 BF16_ABS = 3e-2
 BF16_ABS_TIGHT = 4e-3
-# Prompts longer than ONE_PIECE_ABOVE tokens run with GEMM inputs rounded to bf16 once; the oracle
-# mirrors those rounding points, but the two sides round values that differ by fp32-vs-fp64
-# noise, and a few percent of the elements then round the other way (one ulp = 0.4 %), which
-# is ~2e-3 relative noise on the logits (here |logit| <= 4).  Shorter prompts carry two bf16
-# pieces per activation (16 significant bits) and are held to the tight bound against the
-# unrounded oracle.
+# Prompt blocks of more than 512 tokens run with matrix-core inputs rounded to bf16 once; the
+# oracle mirrors those rounding points block by block (parity_util.prefill_blocks), but the two
+# sides round values that differ by fp32-vs-fp64 noise, some elements then round the other way
+# (one ulp = 0.4 %) and the difference cascades.  The last 128 tokens of such a prompt, and
+# every shorter prompt, carry two bf16 pieces per activation (16 significant bits).
 BF16_ABS_PROMPT = 2.5e-2
-ONE_PIECE_ABOVE = 512
 F32_REL = 1e-4
 
 
@@ -110,16 +109,16 @@ def test_prefill_lengths_and_kv_rows(nnc, n):
             assert np.mean(got != want) < (0.01 if layer == 0 else 0.15)
 
 
-@pytest.mark.parametrize("n", [1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 150, 256, 257, 300, 512, 513, 600])
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 150, 256, 257, 300, 512, 513, 600, 641, 700, 900])
 def test_large_block_prefill_lengths(nnc, n):
     print(f"case: large-block prefill length {n}", flush=True)
     shape = SMALL_G4
-    g, o = _pair(nnc, shape, 1, 640, exact_prefill=False)
+    g, o = _pair(nnc, shape, 1, 1024, exact_prefill=False)
     toks = synth.tokens(n, shape.vocab, stream=100 + n)
-    one_piece = n > ONE_PIECE_ABOVE
+    one_piece = any(pc == 1 for _, _, pc in prefill_blocks(n))   # n > 640: a single-piece block, then the tail
     tight = BF16_ABS_PROMPT if one_piece else BF16_ABS_TIGHT
     lg, ng = g.prefill(0, toks)
-    lo, no = o.prefill(0, toks, oracle_flags(shape, mirrored_prefill=one_piece))
+    lo, no = oracle_prefill_like_library(o, 0, toks, shape)
     _check_logits(shape, lg, lo, tight)
     assert int(ng.item()) == no
     # the cache must be what the oracle's prompt pass cached: same rows in the same places.
@@ -145,22 +144,22 @@ def test_large_block_prefill_lengths(nnc, n):
 
 
 @pytest.mark.parametrize("tile", [0, 1])
-@pytest.mark.parametrize("n", [47, 300, 530])
+@pytest.mark.parametrize("n", [47, 300, 700])
 def test_large_block_prefill_every_block_tile(nnc, n, tile):
     """Each GEMM block tile (64 x 128, 256 x 128) forced on ragged small shapes: the
     k order of every output element is the same in both, so the logits are bit-identical
     to the automatic choice, and they match the oracle."""
     print(f"case: large-block prefill length {n}, forced block tile {tile}", flush=True)
     shape = SMALL_G4
-    g, o = _pair(nnc, shape, 1, 640, exact_prefill=False)
+    g, o = _pair(nnc, shape, 1, 800, exact_prefill=False)
     toks = synth.tokens(n, shape.vocab, stream=300 + n)
-    one_piece = n > ONE_PIECE_ABOVE
+    one_piece = any(pc == 1 for _, _, pc in prefill_blocks(n))
     ref, _ = g.prefill(0, toks)
     g.kv_reset(0)
     g.set_option(nnc.OPT_PREFILL_TILE, tile)
     lg, ng = g.prefill(0, toks)
     assert np.array_equal(lg.cpu().numpy(), ref.cpu().numpy())
-    lo, no = o.prefill(0, toks, oracle_flags(shape, mirrored_prefill=one_piece))
+    lo, no = oracle_prefill_like_library(o, 0, toks, shape)
     _check_logits(shape, lg, lo, BF16_ABS_PROMPT if one_piece else BF16_ABS_TIGHT)
     assert int(ng.item()) == no
 
@@ -178,18 +177,16 @@ def test_large_block_prefill_two_pieces_at_any_length(nnc):
 
 
 def test_multi_block_prefill_long_context(nnc):
-    print("case: prompt longer than one 2048-token block", flush=True)
+    print("case: prompt of several blocks (2048 + 624 single-piece, 128 two-piece)", flush=True)
     shape = SMALL_BF16
-    g, o = _pair(nnc, shape, 1, 2200, exact_prefill=False)
-    toks = synth.tokens(2100, shape.vocab, stream=77)
+    g, o = _pair(nnc, shape, 1, 2900, exact_prefill=False)
+    toks = synth.tokens(2800, shape.vocab, stream=77)
+    assert [(nb, pc) for _, nb, pc in prefill_blocks(2800)] == [(2048, 1), (624, 1), (128, 2)]
     lg, ng = g.prefill(0, toks)
-    # the library runs 2048 tokens with single-bf16 GEMM inputs, then the 52-token tail with
-    # two pieces; the oracle follows the same split
-    o.prefill(0, toks[:2048], oracle_flags(shape, mirrored_prefill=True))
-    lo, no = o.prefill(0, toks[2048:], oracle_flags(shape))
+    lo, no = oracle_prefill_like_library(o, 0, toks, shape)
     _check_logits(shape, lg, lo, BF16_ABS_PROMPT)
     assert int(ng.item()) == no
-    lg, ng = g.decode_step([0], [no])                       # 33 attention chunks in the resident kernel
+    lg, ng = g.decode_step([0], [no])                       # 44 attention chunks in the resident kernel
     lo, n2 = o.step_token(0, no, oracle_flags(shape))
     _check_logits(shape, lg[0], lo, BF16_ABS_PROMPT)
     assert int(ng.item()) == n2
