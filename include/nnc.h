@@ -161,8 +161,8 @@ typedef enum {
                                matrix-core GEMMs and matrix-core attention.  Blocks of up to 512
                                tokens carry every matrix-core input as two bf16 pieces (16
                                significant bits); longer blocks round those inputs to bf16 once.
-                               A call with more than 512 tokens runs its last 128 tokens as a
-                               block of their own (two pieces), so that the logits of the last
+                               A call with more than 512 tokens runs its last 16 tokens through
+                               the three-piece path of mode 1, so that the logits of the last
                                position see single-piece noise only through the cache; the LM
                                head itself is always fp32-grade.
                                2: the same blocks, two pieces at every length (twice the

@@ -125,7 +125,7 @@ struct nnc_model {
 
 namespace {
 
-constexpr uint32_t PREFILL_TAIL = 128;     // last tokens of a long prompt that run as a two-piece block
+constexpr uint32_t PREFILL_TAIL = 16;      // last tokens of a long prompt that run through the fp32-grade chunk path
 constexpr uint32_t MAX_DECODE_BATCH = 21;  // 21 sequences x 3 pieces = 63 operand columns
 
 nnc_status check_config(const nnc_config* c) {
@@ -842,32 +842,36 @@ static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tok
   if (tokens)
     for (uint32_t i = 0; i < n; ++i)
       if (tokens[i] < 0 || (uint32_t)tokens[i] >= m->c.vocab) return fail(NNC_E_ARG, "token %d out of range", tokens[i]);
+  uint32_t done = 0;  // tokens already processed by the large-block path
   if (tokens && m->pb_max && m->opt_prefill_exact != 1) {
     const uint32_t len0 = m->len[slot];
     // Blocks of up to pb_max tokens.  A block of more than 512 tokens rounds its matrix-core
     // inputs to bf16 once; that noise must not reach the logits directly, so the last
-    // PREFILL_TAIL tokens of a longer prompt (the last of which yields the logits) always form
-    // a block of their own, which then carries two pieces.
+    // PREFILL_TAIL tokens of a longer prompt (the last of which yields the logits) go through
+    // the fp32-grade chunk path below instead: one more pass over the weights, about the cost
+    // of one decode step.
     uint32_t head = n;
     if (m->opt_prefill_exact == 0 && n > 512) head = n - PREFILL_TAIL;
-    for (uint32_t t0 = 0; t0 < n;) {
-      const uint32_t end = t0 < head ? head : n;
-      const uint32_t nb = std::min(m->pb_max, end - t0);
+    for (uint32_t t0 = 0; t0 < head;) {
+      const uint32_t nb = std::min(m->pb_max, head - t0);
       const bool last = t0 + nb == n;
       if (nnc_status st = prefill_block(m, slot, tokens + t0, nb, len0 + t0, last && (logits_out || next_out),
                                         logits_out, next_out ? m->next : nullptr))
         return st;
       t0 += nb;
     }
-    if (next_out) HIP_TRY(hipMemcpyAsync(next_out, m->next, 4, hipMemcpyDeviceToDevice, m->stream));
-    m->len[slot] = len0 + n;
-    return NNC_OK;
+    if (head == n) {
+      if (next_out) HIP_TRY(hipMemcpyAsync(next_out, m->next, 4, hipMemcpyDeviceToDevice, m->stream));
+      m->len[slot] = len0 + n;
+      return NNC_OK;
+    }
+    done = head;
   }
   const int nsplit = m->f32 ? 1 : 3;
   const uint32_t chunk = MAX_COLS / nsplit;
   const size_t H = m->H();
   const uint32_t len0 = m->len[slot];
-  for (uint32_t t0 = 0; t0 < n; t0 += chunk) {
+  for (uint32_t t0 = done; t0 < n; t0 += chunk) {
     const uint32_t nc = std::min(chunk, n - t0);
     uint32_t slots[MAX_COLS], pos[MAX_COLS];
     for (uint32_t i = 0; i < nc; ++i) {

@@ -40,20 +40,21 @@ def top2_margin(logits: np.ndarray) -> float:
 
 # The library's documented blocking of a prompt call on the large-block path (include/nnc.h,
 # NNC_OPT_PREFILL_EXACT = 0), restated here for the tests: blocks of up to 2048 tokens; a call
-# of more than 512 tokens runs its last 128 tokens as a block of their own; a block of more
-# than 512 tokens carries one bf16 piece per matrix-core input, else two.
-PREFILL_BLOCK, PREFILL_TAIL, ONE_PIECE_ABOVE = 2048, 128, 512
+# of more than 512 tokens runs its last 16 tokens through the three-piece (fp32-grade) path; a
+# block of more than 512 tokens carries one bf16 piece per matrix-core input, else two.
+PREFILL_BLOCK, PREFILL_TAIL, ONE_PIECE_ABOVE = 2048, 16, 512
 
 
 def prefill_blocks(n: int):
     """[(first token, tokens, pieces)] of a default-mode prompt call of n tokens."""
     head = n - PREFILL_TAIL if n > ONE_PIECE_ABOVE else n
     out, t0 = [], 0
-    while t0 < n:
-        end = head if t0 < head else n
-        nb = min(PREFILL_BLOCK, end - t0)
+    while t0 < head:
+        nb = min(PREFILL_BLOCK, head - t0)
         out.append((t0, nb, 1 if nb > ONE_PIECE_ABOVE else 2))
         t0 += nb
+    if head < n:
+        out.append((head, n - head, 3))
     return out
 
 

@@ -21,8 +21,8 @@ BF16_ABS_TIGHT = 4e-3
 # Prompt blocks of more than 512 tokens run with matrix-core inputs rounded to bf16 once; the
 # oracle mirrors those rounding points block by block (parity_util.prefill_blocks), but the two
 # sides round values that differ by fp32-vs-fp64 noise, some elements then round the other way
-# (one ulp = 0.4 %) and the difference cascades.  The last 128 tokens of such a prompt, and
-# every shorter prompt, carry two bf16 pieces per activation (16 significant bits).
+# (one ulp = 0.4 %) and the difference cascades.  The last 16 tokens of such a prompt take the
+# fp32-grade path, and every shorter prompt carries two bf16 pieces per activation.
 BF16_ABS_PROMPT = 2.5e-2
 F32_REL = 1e-4
 
@@ -109,13 +109,13 @@ def test_prefill_lengths_and_kv_rows(nnc, n):
             assert np.mean(got != want) < (0.01 if layer == 0 else 0.15)
 
 
-@pytest.mark.parametrize("n", [1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 150, 256, 257, 300, 512, 513, 600, 641, 700, 900])
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 150, 256, 257, 300, 512, 513, 528, 529, 600, 900])
 def test_large_block_prefill_lengths(nnc, n):
     print(f"case: large-block prefill length {n}", flush=True)
     shape = SMALL_G4
     g, o = _pair(nnc, shape, 1, 1024, exact_prefill=False)
     toks = synth.tokens(n, shape.vocab, stream=100 + n)
-    one_piece = any(pc == 1 for _, _, pc in prefill_blocks(n))   # n > 640: a single-piece block, then the tail
+    one_piece = any(pc == 1 for _, _, pc in prefill_blocks(n))   # n > 528: a single-piece block, then the tail
     tight = BF16_ABS_PROMPT if one_piece else BF16_ABS_TIGHT
     lg, ng = g.prefill(0, toks)
     lo, no = oracle_prefill_like_library(o, 0, toks, shape)
@@ -177,11 +177,11 @@ def test_large_block_prefill_two_pieces_at_any_length(nnc):
 
 
 def test_multi_block_prefill_long_context(nnc):
-    print("case: prompt of several blocks (2048 + 624 single-piece, 128 two-piece)", flush=True)
+    print("case: prompt of several blocks (2048 + 736 single-piece, 16 fp32-grade)", flush=True)
     shape = SMALL_BF16
     g, o = _pair(nnc, shape, 1, 2900, exact_prefill=False)
     toks = synth.tokens(2800, shape.vocab, stream=77)
-    assert [(nb, pc) for _, nb, pc in prefill_blocks(2800)] == [(2048, 1), (624, 1), (128, 2)]
+    assert [(nb, pc) for _, nb, pc in prefill_blocks(2800)] == [(2048, 1), (736, 1), (16, 3)]
     lg, ng = g.prefill(0, toks)
     lo, no = oracle_prefill_like_library(o, 0, toks, shape)
     _check_logits(shape, lg, lo, BF16_ABS_PROMPT)
