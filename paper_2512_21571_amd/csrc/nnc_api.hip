@@ -75,6 +75,7 @@ struct nnc_model {
   void* Ap = nullptr;        // packed operand, K = max(Dq, F)
   float* rpart = nullptr;    // [MAX_KSPLIT][MAX_COLS][H] k-slice partials of the O / down projections
   float* partial = nullptr;  // attention partials
+  void* qsplit = nullptr;    // [MAX_COLS][nq][3][128] bf16 pieces of the rotated queries (bf16 models)
   int max_chunks = 0;
   float* logits = nullptr;   // [32][V] when the caller passes no logits buffer
   float* am_val = nullptr;
@@ -288,9 +289,9 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
     }
     RUN(FAM_QKROPE, n * Nqkv * 4.0, 0,
         launch_qknorm_rope_append(s, f32, m->qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, n,
-                                  L.kc, L.vc, c.max_batch, c.max_seq));
+                                  L.kc, L.vc, c.max_batch, c.max_seq, m->qsplit));
     RUN(FAM_ATTN, p.kv_rows * 2.0 * Dkv * w, p.kv_rows * 4.0 * Dq,
-        launch_attn_partial(s, f32, m->qkv, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, cm, n,
+        launch_attn_partial(s, f32, m->qkv, m->qsplit, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, cm, n,
                             p.grid_chunks, m->partial, m->max_chunks));
     RUN(FAM_COMBINE, 0, 0,
         launch_attn_combine(s, f32, m->partial, m->max_chunks, nq, cm, n, m->Ap, nc, ns));
@@ -627,6 +628,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
   ALLOC(m->Ap, void*, (size_t)MAX_COLS * std::max(Dq, F) * w);
   ALLOC(m->rpart, float*, (size_t)MAX_KSPLIT * MAX_COLS * H * 4);
   ALLOC(m->partial, float*, (size_t)MAX_COLS * c.n_q_heads * m->max_chunks * 132 * 4);
+  if (!m->f32) ALLOC(m->qsplit, void*, (size_t)MAX_COLS * c.n_q_heads * 3 * 128 * 2);
   ALLOC(m->next, int32_t*, MAX_COLS * 4);
   m->token_log_steps = c.max_seq;
   ALLOC(m->token_log, int32_t*, (size_t)m->token_log_steps * MAX_DECODE_BATCH * 4);
@@ -784,7 +786,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       const ColMap cm{nullptr, slot, pos0, 0};
       RUN(FAM_QKROPE, T * Nqkv * 4.0, 0,
           launch_qknorm_rope_append(s, false, m->pb_qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, (int)n, L.kc,
-                                    L.vc, c.max_batch, c.max_seq));
+                                    L.vc, c.max_batch, c.max_seq, nullptr));
     }
     {
       // causal attention of the block on the matrix cores, over a transposed copy of the

@@ -516,7 +516,7 @@ template <bool F32>
 __global__ __launch_bounds__(64) void k_qknorm_rope_append(
     float* __restrict__ qkv, int nq, int nkv, const float* __restrict__ gq, const float* __restrict__ gk,
     float eps, const float2* __restrict__ rope, ColMap cm, void* __restrict__ kc,
-    void* __restrict__ vc, uint32_t max_seq) {
+    void* __restrict__ vc, uint32_t max_seq, uint16_t* __restrict__ qsplit) {
   const int col = blockIdx.y, hh = blockIdx.x, lane = threadIdx.x;
   const int ld = (nq + 2 * nkv) * 128;
   float* p = qkv + (size_t)(cm.row0 + col) * ld + (size_t)hh * 128;
@@ -538,6 +538,19 @@ __global__ __launch_bounds__(64) void k_qknorm_rope_append(
   if (hh < nq) {
     p[lane] = a;
     p[lane + 64] = b;
+    if (qsplit) {
+      // the query also as three bf16 pieces [column][head][piece][128]: the matrix-core
+      // attention kernel loads them as operand fragments without converting anything
+      uint32_t pa[3], pb[3];
+      split_bf16(a, 3, pa);
+      split_bf16(b, 3, pb);
+      uint16_t* q = qsplit + ((size_t)col * nq + hh) * 3 * 128;
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc) {
+        q[pc * 128 + lane] = (uint16_t)pa[pc];
+        q[pc * 128 + lane + 64] = (uint16_t)pb[pc];
+      }
+    }
     return;
   }
   const int kvh = is_v ? hh - nq - nkv : hh - nq;
@@ -555,13 +568,14 @@ __global__ __launch_bounds__(64) void k_qknorm_rope_append(
 hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq, int nkv,
                                      const float* gq, const float* gk, float eps,
                                      const float2* rope, const ColMap& cm, int ncols, void* kc,
-                                     void* vc, uint32_t max_batch, uint32_t max_seq) {
+                                     void* vc, uint32_t max_batch, uint32_t max_seq, void* qsplit) {
   (void)max_batch;
   dim3 grid(nq + 2 * nkv, ncols);
+  uint16_t* qs = static_cast<uint16_t*>(qsplit);
   if (f32)
-    k_qknorm_rope_append<true><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq);
+    k_qknorm_rope_append<true><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq, nullptr);
   else
-    k_qknorm_rope_append<false><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq);
+    k_qknorm_rope_append<false><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq, qs);
   return hipGetLastError();
 }
 
@@ -738,12 +752,173 @@ __global__ __launch_bounds__(256) void k_attn_partial(
   }
 }
 
-hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, int nq, int nkv,
+// The same partial on the matrix cores (bf16 cache): one workgroup per (chunk, kv head,
+// column) handles ALL query heads of the kv head as the 16 operand columns (G <= 16).
+//   S^T = K Q^T : A = the wave's 16 cached K rows straight from the cache, B = the query heads
+//                 (three bf16 pieces each: fp32-grade), one 16 x 16 tile of scores per wave.
+//   softmax     : scores meet in LDS, one wave per head (64 positions = 64 lanes).
+//   O^T = V^T P^T : the chunk's V rows are staged in LDS as they are; a lane gathers its
+//                 A fragment (one head dimension, 8 positions) with eight 32-bit LDS reads
+//                 (row stride 66 words: conflict-free), B = the weights in three pieces.
+// Replaces 8 multiply-adds per cached element and head on the vector ALU, which bounded the
+// vector version at about half of the HBM rate.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restrict__ qsplit, int nq, int nkv,
+                                                         const uint16_t* __restrict__ kc,
+                                                         const uint16_t* __restrict__ vc, uint32_t max_seq, ColMap cm,
+                                                         float* __restrict__ partial, int max_chunks) {
+  constexpr int VS = 66;  // row stride of the staged V chunk in 32-bit words (128 bf16 + pad)
+  __shared__ uint32_t Vs[ATT_CHUNK][VS];
+  __shared__ float sc[16][ATT_CHUNK];  // scores, then softmax weights, per head
+  __shared__ float sm_m[16], sm_l[16];
+  const int kvh = blockIdx.y, col = blockIdx.z;
+  const int G = nq / nkv, head0 = kvh * G;
+  const uint32_t pos = col_pos(cm, col), slot = col_slot(cm, col);
+  const int chunk = blockIdx.x;
+  const uint32_t j0 = (uint32_t)chunk * ATT_CHUNK;
+  if (j0 > pos) return;  // chunk lies entirely in the future (uniform for the workgroup)
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int c16 = lane & 15, g = lane >> 4;
+  const size_t base = ((size_t)slot * nkv + kvh) * max_seq * 128;
+
+  // rows past `pos` re-read row `pos`: valid memory, finite values, masked / weight 0 below
+  uint2 vreg[4][2];
+  u32x4_t kf[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t j = min(j0 + (uint32_t)((tid >> 4) + 16 * i), pos);
+    const uint4 v = *reinterpret_cast<const uint4*>(vc + base + (size_t)j * 128 + (tid & 15) * 8);
+    vreg[i][0] = make_uint2(v.x, v.y);
+    vreg[i][1] = make_uint2(v.z, v.w);
+  }
+  {
+    // K fragments: A-operand row c16 = position j0 + wave * 16 + c16, 8 dims per lane and k step
+    const uint32_t jk = min(j0 + (uint32_t)(wave * 16 + c16), pos);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      kf[ks] = *reinterpret_cast<const u32x4_t*>(kc + base + (size_t)jk * 128 + ks * 32 + g * 8);
+  }
+
+  // query fragments: operand column c16 = head head0 + c16 (zero beyond G), three pieces as
+  // written by k_qknorm_rope_append
+  u32x4_t qf[4][3];
+  {
+    const uint16_t* qp = qsplit + ((size_t)col * nq + head0 + min(c16, G - 1)) * 3 * 128 + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc) {
+        const u32x4_t t = *reinterpret_cast<const u32x4_t*>(qp + pc * 128 + ks * 32);
+        qf[ks][pc] = c16 < G ? t : u32x4_t{0u, 0u, 0u, 0u};
+      }
+  }
+
+  {
+    f32x4 sv = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc)
+        sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[ks]),
+                                                     __builtin_bit_cast(bf16x8, qf[ks][pc]), sv, 0, 0, 0);
+    // lane (c16 = head, g): positions wave * 16 + g * 4 + i of the chunk
+    if (c16 < G) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int jl = wave * 16 + g * 4 + i;
+        sc[c16][jl] = j0 + (uint32_t)jl <= pos ? sv[i] * 0.08838834764831845f : -INFINITY;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint2* d = reinterpret_cast<uint2*>(&Vs[(tid >> 4) + 16 * i][(tid & 15) * 4]);
+      d[0] = vreg[i][0];
+      d[1] = vreg[i][1];
+    }
+    __syncthreads();
+
+    // chunk max, weights exp(s - max), chunk sum: one wave per head
+    for (int h = wave; h < G; h += 4) {
+      const float x = sc[h][lane];
+      const float m = wave_max(x);
+      const float w = expf(x - m);  // exp(-inf) = 0 for masked positions; position j0 is always valid
+      sc[h][lane] = w;
+      const float l = wave_sum(w);
+      if (lane == 0) {
+        sm_m[h] = m;
+        sm_l[h] = l;
+      }
+    }
+    __syncthreads();
+
+    // weighted value sums: this wave's two 16-dim tiles, two halves of 32 positions
+    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      float w[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) w[e] = 0.f;
+      if (c16 < G) {
+        const float4 w0 = *reinterpret_cast<const float4*>(&sc[c16][half * 32 + g * 8]);
+        const float4 w1 = *reinterpret_cast<const float4*>(&sc[c16][half * 32 + g * 8 + 4]);
+        w[0] = w0.x; w[1] = w0.y; w[2] = w0.z; w[3] = w0.w;
+        w[4] = w1.x; w[5] = w1.y; w[6] = w1.z; w[7] = w1.w;
+      }
+      u32x4_t pf[3];
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc) {
+        uint32_t b[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          b[e] = bf16_bits(w[e]);
+          w[e] -= bf16_to_f32(b[e]);
+        }
+        pf[pc] = u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
+      }
+#pragma unroll
+      for (int dtl = 0; dtl < 2; ++dtl) {
+        const int dim = (wave * 2 + dtl) * 16 + c16;  // A-operand row c16 = this head dimension
+        uint32_t b[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t two = Vs[half * 32 + g * 8 + e][dim >> 1];
+          b[e] = (dim & 1) ? (two >> 16) : (two & 0xffffu);
+        }
+        const u32x4_t vf = u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc)
+          acc[dtl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
+                                                             __builtin_bit_cast(bf16x8, pf[pc]), acc[dtl], 0, 0, 0);
+      }
+    }
+    // acc[dtl] element i of lane (c16 = head, g): dimension (wave * 2 + dtl) * 16 + g * 4 + i
+    if (c16 < G) {
+      float* rec = partial + (((size_t)col * nq + head0 + c16) * max_chunks + chunk) * 132;
+#pragma unroll
+      for (int dtl = 0; dtl < 2; ++dtl)
+        *reinterpret_cast<float4*>(rec + (wave * 2 + dtl) * 16 + g * 4) =
+            make_float4(acc[dtl][0], acc[dtl][1], acc[dtl][2], acc[dtl][3]);
+    }
+    if (tid < G) {
+      float* rec = partial + (((size_t)col * nq + head0 + tid) * max_chunks + chunk) * 132;
+      rec[128] = sm_m[tid];
+      rec[129] = sm_l[tid];
+    }
+  }
+}
+
+hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, const void* qsplit, int nq, int nkv,
                                const void* kc, const void* vc, uint32_t max_batch, uint32_t max_seq,
                                const ColMap& cm, int ncols, int grid_chunks, float* partial,
                                int max_chunks) {
   (void)max_batch;
   const int G = nq / nkv;
+  if (!f32 && G <= 16 && qsplit && cm.row0 == 0) {
+    dim3 grid(grid_chunks, nkv, ncols);
+    k_attn_partial_mc<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(qsplit), nq, nkv, static_cast<const uint16_t*>(kc),
+                                           static_cast<const uint16_t*>(vc), max_seq, cm, partial, max_chunks);
+    return hipGetLastError();
+  }
   const int GH = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
   dim3 grid(grid_chunks, nkv * (G / GH), ncols);
 #define NNC_ATT(F, H) \

@@ -176,6 +176,30 @@ def test_large_block_prefill_two_pieces_at_any_length(nnc):
     assert int(ng.item()) == no
 
 
+def test_batched_decode_long_contexts(nnc):
+    """16 sequences with 2100-position contexts: many chunks per sequence in the batched
+    attention kernels, ragged last chunks."""
+    print("case: batched decode, 16 x 2100 positions", flush=True)
+    shape = SMALL_BF16
+    B = 16
+    g, o = _pair(nnc, shape, B, 2120, exact_prefill=False)
+    t = []
+    for b in range(B):
+        toks = synth.tokens(2100 - 3 * b, shape.vocab, stream=500 + b)
+        g.prefill(b, toks, want_logits=False)
+        _, nxt = oracle_prefill_like_library(o, b, toks, shape)
+        t.append(nxt)
+    for step in range(2):
+        lg, ng = g.decode_step(list(range(B)), t)
+        nxt = []
+        for b in range(B):
+            lo, nb = o.step_token(b, t[b], oracle_flags(shape))
+            _check_logits(shape, lg[b], lo, BF16_ABS_PROMPT)
+            assert int(ng[b].item()) == nb, (step, b)
+            nxt.append(nb)
+        t = nxt
+
+
 def test_multi_block_prefill_long_context(nnc):
     print("case: prompt of several blocks (2048 + 736 single-piece, 16 fp32-grade)", flush=True)
     shape = SMALL_BF16
