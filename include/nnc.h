@@ -131,6 +131,14 @@ nnc_status nnc_decode_greedy(nnc_model *m, const uint32_t *slots, const int32_t 
 /* Forget the contents of one slot (slot >= 0) or of all slots (slot = -1). */
 nnc_status nnc_kv_reset(nnc_model *m, int32_t slot);
 
+/*
+ * Wait for all work enqueued on the model's stream and report deferred failures: the resident
+ * decode kernel bounds every wait for an exchange word; if one ran out, all its workgroups
+ * exited early, the outputs of that call are invalid and NNC_E_DEVICE is returned here and
+ * by every later prompt / decode call on the model (they check without waiting).
+ */
+nnc_status nnc_synchronize(nnc_model *m);
+
 /* Current length of a slot (host out-param). */
 nnc_status nnc_slot_len(const nnc_model *m, uint32_t slot, uint32_t *len_out);
 
@@ -175,6 +183,9 @@ typedef enum {
   NNC_OPT_PREFILL_TILE = 4, /* block tile of the large-block prompt GEMMs: -1 (default) chosen from
                                the block length; 0: 64 x 128, 1: 256 x 128 (rows x operand
                                columns); results are bit-identical for both (same k order) */
+  NNC_OPT_SPIN_LIMIT = 5,   /* polls after which a wait inside the resident kernel gives up (sets
+                               the failure flag and lets every workgroup exit); 0 (default):
+                               2^20, about a second.  A tiny value makes the give-up path testable */
   NNC_OPT_STAGE_TRACE = 3   /* s + 1: the resident kernel stamps the 100 MHz wall clock at every
                                stage boundary of decode step s of each following launch (read them
                                with nnc_stage_trace); 0 (default): off */

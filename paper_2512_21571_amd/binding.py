@@ -13,12 +13,12 @@ from . import _build
 
 OK, E_ARG, E_CONFIG, E_BLOB, E_NOMEM, E_KV_FULL, E_DEVICE, E_STATE = range(8)
 F32, BF16 = 0, 1
-OPT_GRAPH, OPT_PREFILL_EXACT, OPT_PERSISTENT, OPT_STAGE_TRACE, OPT_PREFILL_TILE = 0, 1, 2, 3, 4
+OPT_GRAPH, OPT_PREFILL_EXACT, OPT_PERSISTENT, OPT_STAGE_TRACE, OPT_PREFILL_TILE, OPT_SPIN_LIMIT = 0, 1, 2, 3, 4, 5
 
 # every symbol include/nnc.h declares
 EXPORTS = [
     "nnc_model_create", "nnc_model_destroy", "nnc_prefill", "nnc_decode_step", "nnc_decode_greedy",
-    "nnc_kv_reset", "nnc_slot_len", "nnc_prefill_hidden", "nnc_decode_step_hidden", "nnc_kv_read",
+    "nnc_kv_reset", "nnc_synchronize", "nnc_slot_len", "nnc_prefill_hidden", "nnc_decode_step_hidden", "nnc_kv_read",
     "nnc_set_option", "nnc_profile_begin", "nnc_profile_end", "nnc_stage_trace", "nnc_blob_bytes",
     "nnc_last_error",
 ]
@@ -73,6 +73,7 @@ def lib():
             "nnc_decode_step": (i32, [vp, vp, vp, u32, vp, vp]),
             "nnc_decode_greedy": (i32, [vp, vp, vp, u32, u32, vp, vp]),
             "nnc_kv_reset": (i32, [vp, i32]),
+            "nnc_synchronize": (i32, [vp]),
             "nnc_slot_len": (i32, [vp, u32, P(u32)]),
             "nnc_prefill_hidden": (i32, [vp, u32, vp, u32, vp]),
             "nnc_decode_step_hidden": (i32, [vp, vp, vp, u32, vp]),
@@ -174,7 +175,8 @@ class Model:
             return self.torch.empty(shape, dtype=dtype, device=self.device)
 
     def synchronize(self):
-        self.stream.synchronize()
+        """Wait for the model's stream; raises NncError if a resident decode launch gave up."""
+        _check(lib().nnc_synchronize(self.h))
 
     def _before(self):
         # inputs may have been produced on the caller's current stream

@@ -101,6 +101,10 @@ struct nnc_model {
   unsigned mk_tag = 1;  // next unused exchange tag
   void* mk_layers = nullptr;
   unsigned* mk_error = nullptr;
+  unsigned* mk_error_host = nullptr;   // pinned copy of the flag, refreshed after every resident launch
+  hipEvent_t mk_error_event = nullptr;  // recorded after that refresh
+  bool mk_error_pending = false, mk_failed = false;
+  unsigned mk_spin_limit = 0;
   void *mk_xq = nullptr, *mk_xatt = nullptr, *mk_xo = nullptr, *mk_xop = nullptr, *mk_xact = nullptr, *mk_xdp = nullptr,
        *mk_xamv = nullptr, *mk_xami = nullptr;
   unsigned long long* mk_trace = nullptr;
@@ -199,6 +203,10 @@ void release_all(nnc_model* m) {
       (void)hipFree(p);
   }
   m->allocs.clear();
+  if (m->mk_error_host) (void)hipHostFree(m->mk_error_host);
+  if (m->mk_error_event) (void)hipEventDestroy(m->mk_error_event);
+  m->mk_error_host = nullptr;
+  m->mk_error_event = nullptr;
 }
 
 // ---- launch bookkeeping ------------------------------------------------------
@@ -476,9 +484,28 @@ nnc_status persistent_steps(nnc_model* m, uint32_t slot, int32_t token, uint32_t
   b.trace = m->mk_trace_step >= 0 ? m->mk_trace : nullptr;
   b.trace_step = m->mk_trace_step;
   b.trace_points = mk_trace_points((int)c.n_layers);
+  p.spin_max = m->mk_spin_limit;
   HIP_TRY(launch_decode_resident(m->stream, p, b));
   m->mk_tag += (unsigned)tags;
+  // the kernel's give-up flag travels to pinned host memory behind the launch; the next call
+  // on this model that finds the copy complete looks at it (resident_failed)
+  HIP_TRY(hipMemcpyAsync(m->mk_error_host, m->mk_error, sizeof(unsigned), hipMemcpyDeviceToHost, m->stream));
+  HIP_TRY(hipEventRecord(m->mk_error_event, m->stream));
+  m->mk_error_pending = true;
   return NNC_OK;
+}
+
+// True once a resident launch has given up on a wait (a lost exchange word): every workgroup
+// of that launch exited early and its outputs are invalid.  The condition is sticky.
+bool resident_failed(nnc_model* m, bool wait) {
+  if (m->mk_error_pending) {
+    hipError_t e = wait ? hipEventSynchronize(m->mk_error_event) : hipEventQuery(m->mk_error_event);
+    if (e == hipSuccess) {
+      m->mk_error_pending = false;
+      if (*m->mk_error_host) m->mk_failed = true;
+    }
+  }
+  return m->mk_failed;
 }
 
 }  // namespace
@@ -684,6 +711,9 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
       void* err = nullptr;
       TRY_OR_BAIL(zeroed(err, 256));
       m->mk_error = static_cast<unsigned*>(err);
+      TRY_OR_BAIL(hipHostMalloc(reinterpret_cast<void**>(&m->mk_error_host), sizeof(unsigned), hipHostMallocDefault));
+      *m->mk_error_host = 0;
+      TRY_OR_BAIL(hipEventCreateWithFlags(&m->mk_error_event, hipEventDisableTiming));
       TRY_OR_BAIL(zeroed(m->mk_xq, (Dq + 2 * Dkv) * 8));
       TRY_OR_BAIL(zeroed(m->mk_xatt, (size_t)c.n_q_heads * m->max_chunks * 132 * 8));
       TRY_OR_BAIL(zeroed(m->mk_xo, Dq * 8));
@@ -725,6 +755,14 @@ nnc_status nnc_kv_reset(nnc_model* m, int32_t slot) {
   return NNC_OK;
 }
 
+nnc_status nnc_synchronize(nnc_model* m) {
+  if (!m) return fail(NNC_E_ARG, "model is NULL");
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  if (resident_failed(m, true))
+    return fail(NNC_E_DEVICE, "a resident decode launch gave up waiting for an exchange word; its outputs are invalid, recreate the model");
+  return NNC_OK;
+}
+
 nnc_status nnc_slot_len(const nnc_model* m, uint32_t slot, uint32_t* len_out) {
   if (!m || !len_out) return fail(NNC_E_ARG, "NULL argument");
   if (slot >= m->c.max_batch) return fail(NNC_E_ARG, "slot %u out of range", slot);
@@ -744,6 +782,10 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
     case NNC_OPT_PREFILL_TILE:
       if (value < -1 || value > 1) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic), 0 or 1");
       m->opt_prefill_tile = value;
+      return NNC_OK;
+    case NNC_OPT_SPIN_LIMIT:
+      if (value < 0) return fail(NNC_E_ARG, "spin limit must be >= 0");
+      m->mk_spin_limit = (unsigned)value;
       return NNC_OK;
     case NNC_OPT_STAGE_TRACE:
       if (!m->mk_ok) return fail(NNC_E_STATE, "the resident decode kernel is not available for this model");
@@ -910,6 +952,8 @@ nnc_status nnc_prefill(nnc_model* m, uint32_t slot, const int32_t* tokens, uint3
                        int32_t* next_out) {
   if (!m || !tokens) return fail(NNC_E_ARG, "NULL argument");
   if (!m->c.has_embed_and_head) return fail(NNC_E_STATE, "model has no embedding; use nnc_prefill_hidden");
+  if (resident_failed(m, false))
+    return fail(NNC_E_DEVICE, "an earlier resident decode launch gave up waiting for an exchange word; recreate the model");
   return prefill_common(m, slot, tokens, nullptr, n, logits_out, next_out, nullptr);
 }
 
@@ -923,6 +967,8 @@ nnc_status nnc_decode_step(nnc_model* m, const uint32_t* slots, const int32_t* t
                            float* logits_out, int32_t* next_out) {
   if (!m || !tokens) return fail(NNC_E_ARG, "NULL argument");
   if (!m->c.has_embed_and_head) return fail(NNC_E_STATE, "model has no embedding; use nnc_decode_step_hidden");
+  if (resident_failed(m, false))
+    return fail(NNC_E_DEVICE, "an earlier resident decode launch gave up waiting for an exchange word; recreate the model");
   if (nnc_status st = check_slots(m, slots, batch, 1)) return st;
   for (uint32_t i = 0; i < batch; ++i)
     if (tokens[i] < 0 || (uint32_t)tokens[i] >= m->c.vocab) return fail(NNC_E_ARG, "token %d out of range", tokens[i]);
@@ -959,6 +1005,8 @@ nnc_status nnc_decode_greedy(nnc_model* m, const uint32_t* slots, const int32_t*
                              uint32_t n_steps, int32_t* tokens_out, float* logits_out) {
   if (!m || !first_tokens || !tokens_out) return fail(NNC_E_ARG, "NULL argument");
   if (!m->c.has_embed_and_head) return fail(NNC_E_STATE, "model has no embedding");
+  if (resident_failed(m, false))
+    return fail(NNC_E_DEVICE, "an earlier resident decode launch gave up waiting for an exchange word; recreate the model");
   if (n_steps == 0) return fail(NNC_E_ARG, "n_steps is 0");
   if (n_steps > m->token_log_steps) return fail(NNC_E_ARG, "n_steps %u exceeds %u", n_steps, m->token_log_steps);
   if (nnc_status st = check_slots(m, slots, batch, n_steps)) return st;

@@ -113,6 +113,7 @@ struct MkArgs {
   const float2* rope;
   uint32_t max_seq;
   unsigned* error;
+  unsigned spin_max;    // polls of one wait before the launch gives up
   int tok0;             // first token
   uint32_t pos0, slot;  // position of the first step, KV slot
   int n_steps;
@@ -163,7 +164,7 @@ __device__ __forceinline__ void give_up(const MkArgs& a, Smem& sm) {
 }
 __device__ __forceinline__ bool spin_over(const MkArgs& a, unsigned& spins) {
   ++spins;
-  return spins > MK_SPIN_MAX || ((spins & 255u) == 0 && ld_u32(a.error) != 0);
+  return spins > a.spin_max || ((spins & 255u) == 0 && ld_u32(a.error) != 0);
 }
 
 // bf16 pieces of the pair (v.x, v.y) = activations k, k+1 (k even, relative to the
@@ -1099,6 +1100,7 @@ hipError_t launch_decode_resident(hipStream_t s, const MkPlan& p, const MkBuffer
   a.rope = bf.rope;
   a.max_seq = p.max_seq;
   a.error = bf.error;
+  a.spin_max = p.spin_max ? p.spin_max : MK_SPIN_MAX;
   a.tok0 = p.tok0; a.pos0 = p.pos0; a.slot = p.slot;
   a.n_steps = p.n_steps;
   a.tag_base = p.tag_base;

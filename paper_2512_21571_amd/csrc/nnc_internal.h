@@ -151,6 +151,7 @@ struct MkPlan {
   unsigned tag_base;    // first exchange tag of this launch (tags must never repeat)
   int ks_o, ks_d;       // k slices of the output / down projections
   int off_att, off_o, off_d;  // first workgroup of the attention / output / down projection units
+  unsigned spin_max;    // polls of one wait before the launch gives up (0 = default)
 };
 
 struct MkBuffers {

@@ -323,3 +323,30 @@ def test_reset_replay_and_error_paths(nnc):
     with pytest.raises(nnc.NncError) as e:
         g.decode_step([0], [1])
     assert e.value.status == nnc.E_KV_FULL
+
+
+def test_resident_kernel_gives_up_cleanly_and_reports_it(nnc):
+    """Failure path of the resident decode kernel, forced from the host: with a spin limit of
+    one poll every wait that is not satisfied at once gives up, all workgroups leave through
+    the same exit (no hang, no fault), and the library reports the failure on synchronize and
+    refuses further decode calls on that model.  A fresh model is unaffected."""
+    print("case: resident kernel give-up path (spin limit 1)", flush=True)
+    shape = SMALL_BF16
+    blob = synth.make_blob(shape, weight_std=0.05)
+    g = nnc.Model(shape, blob, 1, 64)
+    toks = synth.tokens(9, shape.vocab)
+    _, nxt = g.prefill(0, toks)
+    first = int(nxt.item())
+    g.set_option(nnc.OPT_SPIN_LIMIT, 1)
+    g.decode_greedy([0], [first], 4)            # enqueued; the kernel gives up inside
+    with pytest.raises(nnc.NncError) as ei:
+        g.synchronize()
+    assert ei.value.status == nnc.E_DEVICE
+    with pytest.raises(nnc.NncError):
+        g.decode_step([0], [first])
+    g2 = nnc.Model(shape, blob, 1, 64)          # same weights, new model: works
+    _, nxt2 = g2.prefill(0, toks)
+    assert int(nxt2.item()) == first
+    out, _ = g2.decode_greedy([0], [first], 4)
+    g2.synchronize()
+    assert out.shape[0] == 4
