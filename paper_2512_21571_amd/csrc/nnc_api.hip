@@ -360,11 +360,12 @@ int decode_nsplit(const nnc_model* m, uint32_t batch) {
   return m->f32 ? 1 : 3;
 }
 
+// Chunk count of an attention launch, rounded up to a multiple of 8 (the captured decode graphs
+// are keyed by it: a new one every 512 positions, and at most 7 idle workgroups per sequence
+// and kv head instead of up to half of them).
 int chunks_grid(uint32_t max_pos) {
   const int need = (int)(max_pos / ATT_CHUNK) + 1;
-  int g = 1;
-  while (g < need) g <<= 1;
-  return g;
+  return (need + 7) / 8 * 8;
 }
 
 nnc_status check_slots(const nnc_model* m, const uint32_t* slots, uint32_t batch, uint32_t n_steps) {

@@ -769,7 +769,8 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
                                                          float* __restrict__ partial, int max_chunks) {
   constexpr int VS = 66;  // row stride of the staged V chunk in 32-bit words (128 bf16 + pad)
   __shared__ uint32_t Vs[ATT_CHUNK][VS];
-  __shared__ float sc[16][ATT_CHUNK];  // scores, then softmax weights, per head
+  __shared__ float sc[16][ATT_CHUNK];  // scores per head
+  __shared__ __attribute__((aligned(16))) uint16_t pw[3][16][ATT_CHUNK];  // softmax weights as three bf16 pieces
   __shared__ float sm_m[16], sm_l[16];
   const int kvh = blockIdx.y, col = blockIdx.z;
   const int G = nq / nkv, head0 = kvh * G;
@@ -842,7 +843,14 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
       const float x = sc[h][lane];
       const float m = wave_max(x);
       const float w = expf(x - m);  // exp(-inf) = 0 for masked positions; position j0 is always valid
-      sc[h][lane] = w;
+      // the weights go to LDS already split into bf16 pieces (once, not once per consuming wave)
+      float r = w;
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc) {
+        const uint32_t b = bf16_bits(r);
+        pw[pc][h][lane] = (uint16_t)b;
+        r -= bf16_to_f32(b);
+      }
       const float l = wave_sum(w);
       if (lane == 0) {
         sm_m[h] = m;
@@ -855,25 +863,12 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
     f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-      float w[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) w[e] = 0.f;
-      if (c16 < G) {
-        const float4 w0 = *reinterpret_cast<const float4*>(&sc[c16][half * 32 + g * 8]);
-        const float4 w1 = *reinterpret_cast<const float4*>(&sc[c16][half * 32 + g * 8 + 4]);
-        w[0] = w0.x; w[1] = w0.y; w[2] = w0.z; w[3] = w0.w;
-        w[4] = w1.x; w[5] = w1.y; w[6] = w1.z; w[7] = w1.w;
-      }
+      // B operand: lane (c16 = head, g) holds the weights of positions half * 32 + g * 8 .. + 7
       u32x4_t pf[3];
 #pragma unroll
       for (int pc = 0; pc < 3; ++pc) {
-        uint32_t b[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          b[e] = bf16_bits(w[e]);
-          w[e] -= bf16_to_f32(b[e]);
-        }
-        pf[pc] = u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
+        const u32x4_t t = *reinterpret_cast<const u32x4_t*>(&pw[pc][min(c16, G - 1)][half * 32 + g * 8]);
+        pf[pc] = c16 < G ? t : u32x4_t{0u, 0u, 0u, 0u};
       }
 #pragma unroll
       for (int dtl = 0; dtl < 2; ++dtl) {
