@@ -685,7 +685,8 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
   }
 
   // resident decode kernel: per-layer pointer table, exchange buffers
-  if (!m->f32 && c.has_embed_and_head && c.n_layers > 0 && H <= 4096 && (c.n_q_heads / c.n_kv_heads) % 2 == 0) {
+  if (!m->f32 && c.has_embed_and_head && c.n_layers > 0 && H <= 4096 && (c.n_q_heads / c.n_kv_heads) % 2 == 0 &&
+      c.n_q_heads / c.n_kv_heads <= 16) {
     const int qkv_tiles = (int)((Dq + 2 * Dkv) / 16);
     m->mk_nwg = prop.multiProcessorCount < qkv_tiles ? prop.multiProcessorCount : qkv_tiles;
     // k slices of the narrow projections: 32 k tiles per slice (all of it prefetched, 8 loads

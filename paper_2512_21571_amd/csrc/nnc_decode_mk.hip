@@ -41,6 +41,7 @@ namespace nnc {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
 
 namespace {
@@ -141,16 +142,21 @@ struct MkArgs {
 
 namespace {
 
+constexpr int MK_VS = 66;  // row stride of the staged V chunk in 32-bit words (128 bf16 + pad: conflict-free gathers)
+
 struct Smem {
   union {
-    float red[MK_WAVES][2][256];   // GEMM: per-wave accumulator tiles
-    float ared[MK_WAVES][4][4][128];  // attention: value sums per wave, row group of 16 lanes and head
+    float red[MK_WAVES][2][256];          // GEMM: per-wave accumulator tiles
+    uint32_t Vs[ATT_CHUNK][MK_VS];        // attention: the chunk's V rows, two bf16 per word
+    float mrg[MK_WAVES][128];             // merge stage: per-wave weighted sums of one head
   };
   float wsum[MK_WAVES];
-  float sc[4][ATT_CHUNK];
-  float qs[4][128];
-  float knew[128], vnew[128];
-  float att_m[4], att_l[4];
+  float sc[16][ATT_CHUNK];                                          // scores per head
+  __attribute__((aligned(16))) uint16_t qp[3][16][128];            // rotated queries, three bf16 pieces
+  __attribute__((aligned(16))) uint16_t pw[3][16][ATT_CHUNK];      // softmax weights, three bf16 pieces
+  __attribute__((aligned(16))) uint16_t knew[128], vnew[128];      // this step's K and V rows (bf16 bits)
+  float att_m[16], att_l[16];
+  __attribute__((aligned(16))) float outv[16][128];                // value sums of the chunk per head, for publication
   float bestv[MK_WAVES];
   int besti[MK_WAVES];
   int tok;
@@ -470,166 +476,201 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
       stamp(step);  // 2: q | k | v published
 
       // ============ stage 2: QK-norm + RoPE + KV append + attention partials ============
+      // A unit = (kv head, chunk of 64 positions) for all G query heads of the kv head, both
+      // products on the matrix cores with the heads as operand columns:
+      //   S^T = K Q^T   A = this wave's 16 cached K rows straight from the cache, B = the queries
+      //                 (three bf16 pieces from LDS: fp32-grade);
+      //   O^T = V^T P^T A = one head dimension x 8 positions gathered from the V rows staged in
+      //                 LDS, B = the softmax weights (three pieces, split once per head).
+      // The step's own K / V row is not in the cache when the loads are issued: the lane /
+      // LDS row that stands for position `pos` takes it from the role waves instead.
       const int nch = (int)(pos / ATT_CHUNK) + 1;  // chunks that hold positions 0 .. pos
       for (int u = wg_att; u < nkv * nch; u += nwg) {
         const int chunk = u % nch, kvh = u / nch;
         const uint32_t j0 = (uint32_t)chunk * ATT_CHUNK;
         const bool owns_new = pos - j0 < ATT_CHUNK;
         const size_t cbase = ((size_t)a.slot * nkv + kvh) * a.max_seq * 128;
-        const int c16 = lane & 15, jj = lane >> 4;
-        // cached rows of the chunk: ATT_IT K and V rows per lane group, loaded up front
-        constexpr int ATT_IT = ATT_CHUNK / (4 * MK_WAVES);
-        uint4 kreg[ATT_IT], vreg[ATT_IT];
+        const int c16 = lane & 15, g = lane >> 4;
+        const int head0 = kvh * G;
+        // cached rows of the chunk, loaded up front (rows from `pos` on re-read an older row:
+        // valid memory; replaced, zeroed or masked below)
+        const uint32_t jlast = pos > 0 ? pos - 1 : 0;
+        uint2 vreg[4][2];
+        u32x4 kf[4];
 #pragma unroll
-        for (int it = 0; it < ATT_IT; ++it) {
-          const uint32_t j = j0 + it * (4 * MK_WAVES) + wave * 4 + jj;
-          kreg[it] = vreg[it] = uint4{0, 0, 0, 0};
-          if (j < pos) {
-            kreg[it] = *reinterpret_cast<const uint4*>(L.kc + cbase + (size_t)j * 128 + c16 * 8);
-            vreg[it] = *reinterpret_cast<const uint4*>(L.vc + cbase + (size_t)j * 128 + c16 * 8);
+        for (int it = 0; it < 4; ++it) {
+          const uint32_t j = min(j0 + (uint32_t)((tid >> 4) + 16 * it), jlast);
+          const uint4 v = *reinterpret_cast<const uint4*>(L.vc + cbase + (size_t)j * 128 + (tid & 15) * 8);
+          vreg[it][0] = make_uint2(v.x, v.y);
+          vreg[it][1] = make_uint2(v.z, v.w);
+        }
+        const uint32_t jk = j0 + (uint32_t)(wave * 16 + c16);  // this lane's A-operand row
+        {
+          const uint32_t jc = min(jk, jlast);
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks)
+            kf[ks] = *reinterpret_cast<const u32x4*>(L.kc + cbase + (size_t)jc * 128 + ks * 32 + g * 8);
+        }
+        wg_sync();  // LDS of the previous unit / stage is free
+        // roles 0..G-1: q heads; role G: the step's k row; role G+1: its v row
+        for (int role = wave; role < G + 2; role += MK_WAVES) {
+          if (role >= G && !owns_new) continue;
+          const u64* src = role < G ? a.xq + (size_t)(head0 + role) * 128
+                                    : a.xq + Dq + (size_t)(role == G ? 0 : Dkv) + (size_t)kvh * 128;
+          // rotary factors and norm gains first: their loads overlap with the wait for q
+          const float* gsrc = role < G ? L.g_q : L.g_k;
+          const float g0 = gsrc[lane], g1 = gsrc[lane + 64];
+          const float2 cs = a.rope[(size_t)pos * 64 + lane];
+          u64 w0, w1;
+          unsigned spins = 0;
+          for (;;) {
+            w0 = ld_t(src + lane);
+            w1 = ld_t(src + lane + 64);
+            if (t_ok(w0, t_q) && t_ok(w1, t_q)) break;
+            if (spin_over(a, spins)) {
+              give_up(a, sm);
+              break;
+            }
+          }
+          float x0 = t_val(w0), x1 = t_val(w1);
+          if (role <= G) {
+            const float ss = wave_sum(x0 * x0 + x1 * x1);
+            const float r = 1.0f / sqrtf(ss * (1.0f / 128.0f) + a.eps);
+            x0 = x0 * r * g0;
+            x1 = x1 * r * g1;
+            const float r0 = x0 * cs.x - x1 * cs.y, r1 = x1 * cs.x + x0 * cs.y;
+            x0 = r0;
+            x1 = r1;
+          }
+          if (role < G) {
+#pragma unroll
+            for (int pc = 0; pc < 3; ++pc) {
+              const uint32_t b0 = bf16_bits(x0), b1 = bf16_bits(x1);
+              sm.qp[pc][role][lane] = (uint16_t)b0;
+              sm.qp[pc][role][lane + 64] = (uint16_t)b1;
+              x0 -= bf16_to_f32(b0);
+              x1 -= bf16_to_f32(b1);
+            }
+          } else {
+            const uint32_t b0 = bf16_bits(x0), b1 = bf16_bits(x1);
+            uint16_t* dst = (role == G ? L.kc : L.vc) + cbase + (size_t)pos * 128;
+            // memory-side 32-bit stores (two bf16 each): other workgroups read this row next step
+            const uint32_t n0 = __shfl_down(b0, 1, 64), n1 = __shfl_down(b1, 1, 64);
+            if ((lane & 1) == 0) {
+              st_u32(reinterpret_cast<unsigned*>(dst + lane), b0 | (n0 << 16));
+              st_u32(reinterpret_cast<unsigned*>(dst + lane + 64), b1 | (n1 << 16));
+            }
+            uint16_t* keep = role == G ? sm.knew : sm.vnew;
+            keep[lane] = (uint16_t)b0;
+            keep[lane + 64] = (uint16_t)b1;
           }
         }
-        for (int hg = 0; hg < G; hg += GH) {
-          const int head0 = kvh * G + hg;
-          wg_sync();
-          // roles 0..GH-1: q heads; role GH: the step's k row; role GH+1: its v row
-          for (int role = wave; role < GH + 2; role += MK_WAVES) {
-            if (role >= GH && !(owns_new && hg == 0)) continue;
-            const u64* src = role < GH ? a.xq + (size_t)(head0 + role) * 128
-                                       : a.xq + Dq + (size_t)(role == GH ? 0 : Dkv) + (size_t)kvh * 128;
-            // rotary factors and norm gains first: their loads overlap with the wait for q
-            const float* gsrc = role < GH ? L.g_q : L.g_k;
-            const float g0 = gsrc[lane], g1 = gsrc[lane + 64];
-            const float2 cs = a.rope[(size_t)pos * 64 + lane];
-            u64 w0, w1;
-            unsigned spins = 0;
-            for (;;) {
-              w0 = ld_t(src + lane);
-              w1 = ld_t(src + lane + 64);
-              if (t_ok(w0, t_q) && t_ok(w1, t_q)) break;
-              if (spin_over(a, spins)) {
-                give_up(a, sm);
-                break;
-              }
+        wg_sync();
+        if (sm.abort) return;
+        // scores: one 16 x 16 tile per wave (rows = positions, columns = heads)
+        if (jk == pos) {
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) kf[ks] = *reinterpret_cast<const u32x4*>(&sm.knew[ks * 32 + g * 8]);
+        }
+        f32x4 sv = f32x4{0.f, 0.f, 0.f, 0.f};
+        {
+          const int hq = min(c16, G - 1);
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int pc = 0; pc < 3; ++pc) {
+              const u32x4 t = *reinterpret_cast<const u32x4*>(&sm.qp[pc][hq][ks * 32 + g * 8]);
+              const u32x4 qf = c16 < G ? t : u32x4{0u, 0u, 0u, 0u};
+              sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[ks]),
+                                                           __builtin_bit_cast(bf16x8, qf), sv, 0, 0, 0);
             }
-            float x0 = t_val(w0), x1 = t_val(w1);
-            if (role <= GH) {
-              const float ss = wave_sum(x0 * x0 + x1 * x1);
-              const float r = 1.0f / sqrtf(ss * (1.0f / 128.0f) + a.eps);
-              x0 = x0 * r * g0;
-              x1 = x1 * r * g1;
-              const float r0 = x0 * cs.x - x1 * cs.y, r1 = x1 * cs.x + x0 * cs.y;
-              x0 = r0;
-              x1 = r1;
-            }
-            if (role < GH) {
-              sm.qs[role][lane] = x0;
-              sm.qs[role][lane + 64] = x1;
-            } else {
-              const uint32_t b0 = bf16_bits(x0), b1 = bf16_bits(x1);
-              uint16_t* dst = (role == GH ? L.kc : L.vc) + cbase + (size_t)pos * 128;
-              // memory-side 32-bit stores (two bf16 each): other workgroups read this row next step
-              const uint32_t n0 = __shfl_down(b0, 1, 64), n1 = __shfl_down(b1, 1, 64);
-              if ((lane & 1) == 0) {
-                st_u32(reinterpret_cast<unsigned*>(dst + lane), b0 | (n0 << 16));
-                st_u32(reinterpret_cast<unsigned*>(dst + lane + 64), b1 | (n1 << 16));
-              }
-              float* keep = role == GH ? sm.knew : sm.vnew;
-              keep[lane] = bf16_to_f32(b0);
-              keep[lane + 64] = bf16_to_f32(b1);
-            }
+        }
+        // lane (c16 = head, g): positions wave * 16 + g * 4 + i of the chunk
+        if (c16 < G) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int jl = wave * 16 + g * 4 + i;
+            sm.sc[c16][jl] = j0 + (uint32_t)jl <= pos ? sv[i] * 0.08838834764831845f : -INFINITY;
           }
-          wg_sync();
-          if (sm.abort) return;
-          float q[GH][8];
+        }
+        // V rows into LDS; the step's own row from the role wave
 #pragma unroll
-          for (int h = 0; h < GH; ++h)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) q[h][e] = sm.qs[h][c16 * 8 + e];
-          // scores s[h][j] = <q_h, K_j> / sqrt(128)
-#pragma unroll
-          for (int it = 0; it < ATT_IT; ++it) {
-            const int jl = it * (4 * MK_WAVES) + wave * 4 + jj;
-            const uint32_t j = j0 + jl;
-            float kv[8];
-            const uint4 xk = kreg[it];
-            kv[0] = __uint_as_float(xk.x << 16); kv[1] = __uint_as_float(xk.x & 0xffff0000u);
-            kv[2] = __uint_as_float(xk.y << 16); kv[3] = __uint_as_float(xk.y & 0xffff0000u);
-            kv[4] = __uint_as_float(xk.z << 16); kv[5] = __uint_as_float(xk.z & 0xffff0000u);
-            kv[6] = __uint_as_float(xk.w << 16); kv[7] = __uint_as_float(xk.w & 0xffff0000u);
-            if (j == pos) {
-#pragma unroll
-              for (int e = 0; e < 8; ++e) kv[e] = sm.knew[c16 * 8 + e];
-            }
-#pragma unroll
-            for (int h = 0; h < GH; ++h) {
-              float d = 0.f;
-#pragma unroll
-              for (int e = 0; e < 8; ++e) d += q[h][e] * kv[e];
-              d = row16_sum(d);
-              if (c16 == 0) sm.sc[h][jl] = j <= pos ? d * 0.08838834764831845f : -INFINITY;
-            }
+        for (int it = 0; it < 4; ++it) {
+          const int row = (tid >> 4) + 16 * it;
+          uint2* d = reinterpret_cast<uint2*>(&sm.Vs[row][(tid & 15) * 4]);
+          if (j0 + (uint32_t)row == pos) {
+            const uint2* nv = reinterpret_cast<const uint2*>(&sm.vnew[(tid & 15) * 8]);
+            d[0] = nv[0];
+            d[1] = nv[1];
+          } else if (j0 + (uint32_t)row > pos) {
+            d[0] = d[1] = make_uint2(0u, 0u);  // masked rows: weight 0 times a finite value
+          } else {
+            d[0] = vreg[it][0];
+            d[1] = vreg[it][1];
           }
-          wg_sync();
-          for (int h = wave; h < GH; h += MK_WAVES) {
-            const float s = sm.sc[h][lane];
-            const float m = wave_max(s);
-            const float w = expf(s - m);
-            sm.sc[h][lane] = w;
-            const float l = wave_sum(w);
-            if (lane == 0) {
-              sm.att_m[h] = m;
-              sm.att_l[h] = l;
-            }
+        }
+        wg_sync();
+        // chunk max, weights exp(s - max) split into pieces, chunk sum: one wave per head
+        for (int h = wave; h < G; h += MK_WAVES) {
+          const float x = sm.sc[h][lane];
+          const float m = wave_max(x);
+          const float w = expf(x - m);  // exp(-inf) = 0 for masked positions; position j0 is always valid
+          float r = w;
+#pragma unroll
+          for (int pc = 0; pc < 3; ++pc) {
+            const uint32_t b = bf16_bits(r);
+            sm.pw[pc][h][lane] = (uint16_t)b;
+            r -= bf16_to_f32(b);
           }
-          wg_sync();
-          float acc[GH][8];
+          const float l = wave_sum(w);
+          if (lane == 0) {
+            sm.att_m[h] = m;
+            sm.att_l[h] = l;
+          }
+        }
+        wg_sync();
+        // weighted value sums: this wave's two 16-dim tiles, two halves of 32 positions
+        f32x4 acc2[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-          for (int h = 0; h < GH; ++h)
+        for (int half = 0; half < 2; ++half) {
+          u32x4 pf[3];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
-#pragma unroll
-          for (int it = 0; it < ATT_IT; ++it) {
-            const int jl = it * (4 * MK_WAVES) + wave * 4 + jj;
-            const uint32_t j = j0 + jl;
-            float vv[8];
-            const uint4 xv = vreg[it];
-            vv[0] = __uint_as_float(xv.x << 16); vv[1] = __uint_as_float(xv.x & 0xffff0000u);
-            vv[2] = __uint_as_float(xv.y << 16); vv[3] = __uint_as_float(xv.y & 0xffff0000u);
-            vv[4] = __uint_as_float(xv.z << 16); vv[5] = __uint_as_float(xv.z & 0xffff0000u);
-            vv[6] = __uint_as_float(xv.w << 16); vv[7] = __uint_as_float(xv.w & 0xffff0000u);
-            if (j == pos) {
-#pragma unroll
-              for (int e = 0; e < 8; ++e) vv[e] = sm.vnew[c16 * 8 + e];
-            }
-            if (j <= pos) {
-#pragma unroll
-              for (int h = 0; h < GH; ++h) {
-                const float w = sm.sc[h][jl];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[h][e] += w * vv[e];
-              }
-            }
+          for (int pc = 0; pc < 3; ++pc) {
+            const u32x4 t = *reinterpret_cast<const u32x4*>(&sm.pw[pc][min(c16, G - 1)][half * 32 + g * 8]);
+            pf[pc] = c16 < G ? t : u32x4{0u, 0u, 0u, 0u};
           }
 #pragma unroll
-          for (int h = 0; h < GH; ++h) {
-            float4* dst = reinterpret_cast<float4*>(&sm.ared[wave][jj][h][c16 * 8]);
-            dst[0] = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
-            dst[1] = make_float4(acc[h][4], acc[h][5], acc[h][6], acc[h][7]);
-          }
-          wg_sync();
-          for (int o = tid; o < GH * 128; o += MK_THREADS) {
-            const int h = o >> 7, i = o & 127;
-            float v = 0.f;
+          for (int dtl = 0; dtl < 2; ++dtl) {
+            const int dim = (wave * 2 + dtl) * 16 + c16;  // A-operand row c16 = this head dimension
+            uint32_t b[8];
 #pragma unroll
-            for (int w = 0; w < MK_WAVES; ++w)
-              v += (sm.ared[w][0][h][i] + sm.ared[w][1][h][i]) + (sm.ared[w][2][h][i] + sm.ared[w][3][h][i]);
-            u64* rec = a.xatt + ((size_t)(head0 + h) * a.max_chunks + chunk) * 132;
-            st_t(rec + i, v, t_att);
-            if (i == 0) {
-              st_t(rec + 128, sm.att_m[h], t_att);
-              st_t(rec + 129, sm.att_l[h], t_att);
+            for (int e = 0; e < 8; ++e) {
+              const uint32_t two = sm.Vs[half * 32 + g * 8 + e][dim >> 1];
+              b[e] = (dim & 1) ? (two >> 16) : (two & 0xffffu);
             }
+            const u32x4 vf = u32x4{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
+#pragma unroll
+            for (int pc = 0; pc < 3; ++pc)
+              acc2[dtl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
+                                                                  __builtin_bit_cast(bf16x8, pf[pc]), acc2[dtl], 0, 0, 0);
+          }
+        }
+        // acc2[dtl] element i of lane (c16 = head, g): dimension (wave * 2 + dtl) * 16 + g * 4 + i.
+        // Through LDS, so that every thread publishes one word (the consumers are waiting).
+        if (c16 < G) {
+#pragma unroll
+          for (int dtl = 0; dtl < 2; ++dtl)
+            *reinterpret_cast<float4*>(&sm.outv[c16][(wave * 2 + dtl) * 16 + g * 4]) =
+                make_float4(acc2[dtl][0], acc2[dtl][1], acc2[dtl][2], acc2[dtl][3]);
+        }
+        wg_sync();
+        for (int o = tid; o < G * 128; o += MK_THREADS) {
+          const int h = o >> 7, i = o & 127;
+          u64* rec = a.xatt + ((size_t)(head0 + h) * a.max_chunks + chunk) * 132;
+          st_t(rec + i, sm.outv[h][i], t_att);
+          if (i == 0) {
+            st_t(rec + 128, sm.att_m[h], t_att);
+            st_t(rec + 129, sm.att_l[h], t_att);
           }
         }
       }
@@ -693,8 +734,8 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
               }
             M = Mn;
           }
-          sm.ared[wave][0][0][lane] = n0;
-          sm.ared[wave][0][0][lane + 64] = n1;
+          sm.mrg[wave][lane] = n0;
+          sm.mrg[wave][lane + 64] = n1;
           if (lane == 0) {
             sm.att_m[wave] = M;
             sm.att_l[wave] = den;
@@ -709,7 +750,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
 #pragma unroll
             for (int w = 0; w < MK_WAVES; ++w) {
               const float f = expf(sm.att_m[w] - Mt);  // waves without a chunk: exp(-inf) = 0
-              num += f * sm.ared[w][0][0][tid];
+              num += f * sm.mrg[w][tid];
               dn += f * sm.att_l[w];
             }
             st_t(a.xo + (size_t)h * 128 + tid, num / dn, t_att);
@@ -1087,7 +1128,7 @@ size_t mk_opnd_bytes(const MkPlan& p) {
 
 hipError_t launch_decode_resident(hipStream_t s, const MkPlan& p, const MkBuffers& bf) {
   const int G = p.nq / p.nkv;
-  if (p.H > 4096 || p.ks_o > MK_MAX_KS || p.ks_d > MK_MAX_KS || p.ks_o < 1 || p.ks_d < 1 || (G % 2) != 0 ||
+  if (p.H > 4096 || p.ks_o > MK_MAX_KS || p.ks_d > MK_MAX_KS || p.ks_o < 1 || p.ks_d < 1 || (G % 2) != 0 || G > 16 ||
       p.nwg < 1 || p.nwg > (p.nq + 2 * p.nkv) * 8)
     return hipErrorInvalidValue;
   MkArgs a{};
