@@ -811,9 +811,13 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
   // Long prompts are matrix-core bound: one bf16 per activation, 256-row tiles.
   const int pieces = (n <= 512 || m->opt_prefill_exact == 2) ? 2 : 1;
   const int ct = tt * pieces;  // operand column tiles
-  // Block tile of the GEMMs: 64 x 128 for short prompts (more workgroups), else 256 x 128.
-  const int tile = m->opt_prefill_tile >= 0 ? m->opt_prefill_tile : (n <= 256 ? 0 : 1);
-  auto tile_shape = [&](int) { return tile; };
+  // Block tile per GEMM: 256 x 128 when that launch still has a workgroup for every CU,
+  // else 64 x 128 (four times as many workgroups: short prompts, narrow projections).
+  auto tile_shape = [&](int n_tiles) {
+    if (m->opt_prefill_tile >= 0) return m->opt_prefill_tile;
+    const long big = (long)((n_tiles + 15) / 16) * ((ct + 7) / 8);
+    return big >= (long)m->n_cus ? 1 : 0;
+  };
   const double w = 2.0, T = n;
   HIP_TRY(hipMemcpyAsync(m->pb_tok, tokens, (size_t)n * 4, hipMemcpyHostToDevice, s));
   RUN(FAM_EMBED, T * H * w, 0, launch_embed_rows(s, m->embed, H, m->pb_tok, (int)n, m->pb_x));
