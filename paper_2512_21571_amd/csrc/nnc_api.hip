@@ -297,7 +297,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
     }
     RUN(FAM_QKROPE, n * Nqkv * 4.0, 0,
         launch_qknorm_rope_append(s, f32, m->qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, n,
-                                  L.kc, L.vc, c.max_batch, c.max_seq, m->qsplit));
+                                  L.kc, L.vc, c.max_batch, c.max_seq, m->qsplit, nullptr, 0));
     RUN(FAM_ATTN, p.kv_rows * 2.0 * Dkv * w, p.kv_rows * 4.0 * Dq,
         launch_attn_partial(s, f32, m->qkv, m->qsplit, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, cm, n,
                             p.grid_chunks, m->partial, m->max_chunks));
@@ -834,15 +834,18 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       const ColMap cm{nullptr, slot, pos0, 0};
       RUN(FAM_QKROPE, T * Nqkv * 4.0, 0,
           launch_qknorm_rope_append(s, false, m->pb_qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, (int)n, L.kc,
-                                    L.vc, c.max_batch, c.max_seq, nullptr));
+                                    L.vc, c.max_batch, c.max_seq, nullptr, m->pb_vt, m->pb_vt_stride));
     }
     {
       // causal attention of the block on the matrix cores, over a transposed copy of the
       // slot's V rows (positions of earlier blocks included)
       double rows = 0;
       for (uint32_t i = 0; i < n; ++i) rows += pos0 + i + 1.0;
-      RUN(FAM_MISC, (pos0 + T) * Dkv * 2.0 * w, 0,
-          launch_v_transpose(s, L.vc, slot, nkv, c.max_seq, pos0 + n, m->pb_vt, m->pb_vt_stride));
+      // the block's own V rows were written transposed by the append kernel; rows of earlier
+      // blocks come from the cache
+      if (pos0 > 0)
+        RUN(FAM_MISC, pos0 * Dkv * 2.0 * w, 0,
+            launch_v_transpose(s, L.vc, slot, nkv, c.max_seq, pos0, m->pb_vt, m->pb_vt_stride));
       RUN(FAM_PATTN, (pos0 + T) * 2.0 * Dkv * w + T * Dq * 6.0, rows * 4.0 * Dq,
           launch_attn_prefill(s, m->pb_qkv, nq, nkv, L.kc, m->pb_vt, m->pb_vt_stride, slot, c.max_seq, pos0, (int)n,
                               pieces, m->pb_fb));

@@ -94,7 +94,8 @@ hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a);
 hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq, int nkv,
                                      const float* gq, const float* gk, float eps,
                                      const float2* rope, const ColMap& cm, int ncols, void* kc,
-                                     void* vc, uint32_t max_batch, uint32_t max_seq, void* qsplit);
+                                     void* vc, uint32_t max_batch, uint32_t max_seq, void* qsplit, void* vt,
+                                     uint32_t vt_stride);
 hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, const void* qsplit, int nq, int nkv,
                                const void* kc, const void* vc, uint32_t max_batch, uint32_t max_seq,
                                const ColMap& cm, int ncols, int grid_chunks, float* partial,

@@ -516,7 +516,8 @@ template <bool F32>
 __global__ __launch_bounds__(64) void k_qknorm_rope_append(
     float* __restrict__ qkv, int nq, int nkv, const float* __restrict__ gq, const float* __restrict__ gk,
     float eps, const float2* __restrict__ rope, ColMap cm, void* __restrict__ kc,
-    void* __restrict__ vc, uint32_t max_seq, uint16_t* __restrict__ qsplit) {
+    void* __restrict__ vc, uint32_t max_seq, uint16_t* __restrict__ qsplit, uint16_t* __restrict__ vt,
+    uint32_t vt_stride) {
   const int col = blockIdx.y, hh = blockIdx.x, lane = threadIdx.x;
   const int ld = (nq + 2 * nkv) * 128;
   float* p = qkv + (size_t)(cm.row0 + col) * ld + (size_t)hh * 128;
@@ -562,20 +563,29 @@ __global__ __launch_bounds__(64) void k_qknorm_rope_append(
   } else {
     static_cast<uint16_t*>(dst)[row + lane] = (uint16_t)bf16_bits(a);
     static_cast<uint16_t*>(dst)[row + lane + 64] = (uint16_t)bf16_bits(b);
+    if (is_v && vt) {
+      // prompt blocks: also the transposed copy [kv head][dim][position] that the
+      // matrix-core prompt attention reads
+      vt[((size_t)kvh * 128 + lane) * vt_stride + pos] = (uint16_t)bf16_bits(a);
+      vt[((size_t)kvh * 128 + lane + 64) * vt_stride + pos] = (uint16_t)bf16_bits(b);
+    }
   }
 }
 
 hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq, int nkv,
                                      const float* gq, const float* gk, float eps,
                                      const float2* rope, const ColMap& cm, int ncols, void* kc,
-                                     void* vc, uint32_t max_batch, uint32_t max_seq, void* qsplit) {
+                                     void* vc, uint32_t max_batch, uint32_t max_seq, void* qsplit, void* vt,
+                                     uint32_t vt_stride) {
   (void)max_batch;
   dim3 grid(nq + 2 * nkv, ncols);
   uint16_t* qs = static_cast<uint16_t*>(qsplit);
   if (f32)
-    k_qknorm_rope_append<true><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq, nullptr);
+    k_qknorm_rope_append<true><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq, nullptr,
+                                                   nullptr, 0);
   else
-    k_qknorm_rope_append<false><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq, qs);
+    k_qknorm_rope_append<false><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq, qs,
+                                                    static_cast<uint16_t*>(vt), vt_stride);
   return hipGetLastError();
 }
 
