@@ -782,7 +782,7 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
       return NNC_OK;
     case NNC_OPT_PERSISTENT: m->opt_persistent = value != 0; return NNC_OK;
     case NNC_OPT_PREFILL_TILE:
-      if (value < -1 || value > 2) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic), 0, 1 or 2");
+      if (value < -1 || value > 3) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic) or 0 .. 3");
       m->opt_prefill_tile = value;
       return NNC_OK;
     case NNC_OPT_SPIN_LIMIT:
@@ -812,13 +812,15 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
   const int pieces = (n <= 512 || m->opt_prefill_exact == 2) ? 2 : 1;
   const int ct = tt * pieces;  // operand column tiles
   // Block tile per GEMM: 256 x 128 when that launch has two workgroups for every CU, 128 x 128
-  // when it still has one of those, else 64 x 128 (short prompts, narrow projections).
+  // when it still has one of those, else 64 x 128, or 64 x 64 when even those are fewer than the
+  // CUs (short prompts, narrow projections).
   auto tile_shape = [&](int n_tiles) {
     if (m->opt_prefill_tile >= 0) return m->opt_prefill_tile;
     const long cols = (ct + 7) / 8;
     if ((long)((n_tiles + 15) / 16) * cols >= 2L * m->n_cus) return 1;
     if ((long)((n_tiles + 7) / 8) * cols >= (long)m->n_cus) return 2;
-    return 0;
+    if ((long)((n_tiles + 3) / 4) * cols >= (long)m->n_cus) return 0;
+    return 3;
   };
   const double w = 2.0, T = n;
   HIP_TRY(hipMemcpyAsync(m->pb_tok, tokens, (size_t)n * 4, hipMemcpyHostToDevice, s));

@@ -56,6 +56,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 //   NT = 8,  TT = 8  (128 x 128): launches that have fewer than two 256 x 128 workgroups per CU.
 //   NT = 4,  TT = 8  (64 x 128): short prompts, where the launch would otherwise leave most of
 //                    the chip idle.
+//   NT = 4,  TT = 4  (64 x 64): the same, for launches that even so have fewer workgroups than CUs.
 // PIECES = 1: one bf16 per activation, a column tile is 16 tokens.  PIECES = 2: every
 // activation is carried as two bf16 pieces (value, remainder) in adjacent column tiles, whose
 // products the epilogue adds: fp32-grade activations at twice the matrix-core work, which is
@@ -241,19 +242,20 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill(PrefillGemmArgs a) {
 }
 
 // a.t_tiles counts operand column tiles (token tiles x pieces).  shape: 0 = 64 x 128 block
-// tiles, 1 = 256 x 128, 2 = 128 x 128.
+// tiles, 1 = 256 x 128, 2 = 128 x 128, 3 = 64 x 64.
 hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a, int pieces, int shape) {
   if (a.n_tiles <= 0 || a.t_tiles <= 0 || a.KT <= 0 || (pieces != 1 && pieces != 2) || a.t_tiles % pieces ||
-      shape < 0 || shape > 2)
+      shape < 0 || shape > 3)
     return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU && a.n_tiles % 4) return hipErrorInvalidValue;
-  const int NT = shape == 0 ? 4 : shape == 1 ? 16 : 8, TT = 8;
+  const int NT = shape == 1 ? 16 : shape == 2 ? 8 : 4, TT = shape == 3 ? 4 : 8;
   dim3 grid((a.n_tiles + NT - 1) / NT, (a.t_tiles + TT - 1) / TT);
 #define PG_LAUNCH_P(E, P)                                                     \
   do {                                                                        \
     if (shape == 0) k_gemm_prefill<E, 4, 8, P><<<grid, 256, 0, s>>>(a);       \
     else if (shape == 1) k_gemm_prefill<E, 16, 8, P><<<grid, 256, 0, s>>>(a); \
-    else k_gemm_prefill<E, 8, 8, P><<<grid, 256, 0, s>>>(a);                  \
+    else if (shape == 2) k_gemm_prefill<E, 8, 8, P><<<grid, 256, 0, s>>>(a);  \
+    else k_gemm_prefill<E, 4, 4, P><<<grid, 256, 0, s>>>(a);                  \
   } while (0)
 #define PG_LAUNCH(E)                    \
   do {                                  \
