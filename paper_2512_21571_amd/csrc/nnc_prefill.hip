@@ -30,6 +30,16 @@ __device__ __forceinline__ uint32_t bf16_bits(float f) {
 }
 __device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
+// Two floats to two bf16 (round to nearest even) in one word, low half = a: the hardware
+// conversion, bit-identical to bf16_bits for every input that is not a NaN.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_pack2(float a, float b) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
+}
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
 // Workgroup barrier that orders LDS traffic only: the global loads of the register ring stay
 // in flight across it (a plain __syncthreads() would wait for all of them at every k step).
 __device__ __forceinline__ void lds_sync() {
@@ -379,38 +389,44 @@ hipError_t launch_v_transpose(hipStream_t s, const void* vc, uint32_t slot, int 
   return hipGetLastError();
 }
 
-// Scores and weighted sums of 16 prompt tokens x GH query heads (sharing one kv head) per wave
-// (= workgroup),
-// flash style: positions are walked in chunks of 32 with a running maximum and sum per row.
+// Scores and weighted sums of 16 prompt tokens x GH query heads (sharing one kv head) per wave,
+// four waves (64 consecutive tokens) per workgroup, flash style: positions are walked in chunks
+// of 32 with a running maximum and sum per row.
 // Both products run transposed, so that no operand needs a shuffle between them:
-//   S^T = K Q^T   A = 16 cached K rows (their 128 dims in four k steps, straight from the
-//                 cache), B = the wave's 16 query rows; D holds, per lane, one query token
-//                 (column) and 4 + 4 positions of the two 16-row tiles.  The K rows of the two
-//                 tiles are picked so that these are 8 consecutive positions g*8 .. g*8+7.
-//   O^T = V^T P^T A = 16 head dims x 32 positions from the transposed V copy (one 16-byte
-//                 load per lane), B = the lane's own 8 weights: exactly the B-operand layout
-//                 (column = query token, 8 consecutive k).
-// Operands are loaded from global memory (L2) directly into registers: each K / V^T fragment
-// feeds GH heads, which is all the reuse there is, so LDS staging would add nothing.
+//   S^T = K Q^T   A = 16 cached K rows (their 128 dims in four k steps), B = the wave's 16
+//                 query rows; D holds, per lane, one query token (column) and 4 + 4 positions
+//                 of the two 16-row tiles.  The K rows of the two tiles are picked so that
+//                 these are 8 consecutive positions g*8 .. g*8+7.
+//   O^T = V^T P^T A = 16 head dims x 32 positions from the transposed V copy (16 bytes per
+//                 lane), B = the lane's own 8 weights: exactly the B-operand layout (column =
+//                 query token, 8 consecutive k).
+// The 16 fragments of a chunk (8 K, 8 V^T, 1 KiB each) are the same for all four waves: the
+// workgroup copies them once, global -> registers -> LDS, one chunk ahead of the products
+// (double-buffered, one barrier per chunk), and each wave reads them from LDS for its GH heads.
+// A wave keeps only its queries and accumulators in registers, so two workgroups fit on a CU
+// and one wave's softmax arithmetic overlaps another's matrix-core work.
 // Masked positions get weight exp(-inf) = 0; their K / V^T values are finite (the copy and the
 // cache rows read are initialised memory), so 0 x value = 0.
 // PIECES = 2: queries and weights enter the matrix cores as two bf16 pieces (16 significant
 // bits); PIECES = 1: one bf16 each, and the row sum adds the rounded weights.
 template <int GH, int PIECES>
-__global__ __launch_bounds__(64) void k_attn_prefill(const float* __restrict__ qkv, int nq, int nkv,
-                                                      const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vt,
-                                                      uint32_t S, uint32_t slot, uint32_t max_seq, uint32_t pos0,
-                                                      int n, void* __restrict__ Of) {
-  const int lane = threadIdx.x;
+__global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict__ qkv, int nq, int nkv,
+                                                         const uint16_t* __restrict__ kc,
+                                                         const uint16_t* __restrict__ vt, uint32_t S, uint32_t slot,
+                                                         uint32_t max_seq, uint32_t pos0, int n,
+                                                         void* __restrict__ Of) {
+  __shared__ u32x4 Fs[2][16][64];  // fragments 0-3: K tile a, 4-7: K tile b (k steps), 8-15: V^T (dim tiles)
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c16 = lane & 15, g = lane >> 4;
   const int G = nq / nkv;
   const int kvh = blockIdx.y / (G / GH), head0 = kvh * G + (blockIdx.y % (G / GH)) * GH;
-  // one wave per workgroup; the longest rows (last token tiles) are dispatched first, so the
-  // causal triangle packs onto the CUs without a long tail
-  const int tq = (int)gridDim.x - 1 - (int)blockIdx.x;
-  if (tq * 16 >= n) return;
+  // the longest rows (last token tiles) are dispatched first, so the causal triangle packs onto
+  // the CUs without a long tail
+  const int tq4 = (int)gridDim.x - 1 - (int)blockIdx.x;
+  const int tq = tq4 * 4 + wave;
+  const bool active = tq * 16 < n;  // a wave past the prompt only helps with the copies
   const int ld = (nq + 2 * nkv) * 128;
-  const int t = min(tq * 16 + c16, n - 1);  // rows past the prompt repeat the last token (never used)
+  const int t = min(tq * 16 + c16, n - 1);  // rows past the prompt repeat the last token (never stored)
   const uint32_t p = pos0 + (uint32_t)t;    // position of this lane's query token
 
   // query fragments: lane (column c16 = token, g) holds dims ks*32 + g*8 .. +7 of its token
@@ -424,13 +440,14 @@ __global__ __launch_bounds__(64) void k_attn_prefill(const float* __restrict__ q
       float v[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
 #pragma unroll
       for (int pc = 0; pc < PIECES; ++pc) {
-        uint32_t b[8];
+        uint32_t b[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          b[e] = bf16_bits(v[e]);
-          v[e] -= bf16_to_f32(b[e]);
+        for (int e = 0; e < 4; ++e) {
+          b[e] = bf16_pack2(v[2 * e], v[2 * e + 1]);
+          v[2 * e] -= bf16_lo(b[e]);
+          v[2 * e + 1] -= bf16_hi(b[e]);
         }
-        qf[h][ks][pc] = u32x4{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
+        qf[h][ks][pc] = u32x4{b[0], b[1], b[2], b[3]};
       }
     }
 
@@ -446,103 +463,121 @@ __global__ __launch_bounds__(64) void k_attn_prefill(const float* __restrict__ q
 
   const uint16_t* kbase = kc + (((size_t)slot * nkv + kvh) * max_seq) * 128;
   const uint16_t* vbase = vt + (size_t)kvh * 128 * S;
-  const uint32_t p_last = pos0 + (uint32_t)min(tq * 16 + 15, n - 1);  // last position any row of the tile sees
-  const int r4 = (c16 >> 2) * 8 + (c16 & 3);  // K row of tile a for A-operand row c16; tile b: + 4
+  const uint32_t p_first = pos0 + (uint32_t)tq * 16;                  // positions up to here are visible to every row
+  const uint32_t p_last = pos0 + (uint32_t)min(tq * 16 + 15, n - 1);  // last position any row of the wave's tile sees
+  const uint32_t p_last_wg = pos0 + (uint32_t)min(tq4 * 64 + 63, n - 1);
 
-  // The fragments of the next chunk are loaded into a second register set while this chunk is
-  // being multiplied.
-  u32x4 ka[2][4], kb[2][4], vf[2][8];
-  auto load_chunk = [&](auto stc, uint32_t kv0) __attribute__((always_inline)) {
-    constexpr int st = decltype(stc)::value;
+  // copy of a chunk: thread tid moves element (tid & 63) of fragments (tid >> 6) + 4 j
+  u32x4 stage[4];
+  auto gload = [&](uint32_t kv0) __attribute__((always_inline)) {
+    const int r4 = (c16 >> 2) * 8 + (c16 & 3);  // K row of tile a for A-operand row c16; tile b: + 4
     const uint32_t ra = min(kv0 + r4, max_seq - 1), rb = min(kv0 + r4 + 4, max_seq - 1);
     const uint32_t kvv = min(kv0, S - 32);  // past the last chunk: any valid chunk (never used)
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      ka[st][ks] = *reinterpret_cast<const u32x4*>(kbase + (size_t)ra * 128 + ks * 32 + g * 8);
-      kb[st][ks] = *reinterpret_cast<const u32x4*>(kbase + (size_t)rb * 128 + ks * 32 + g * 8);
-    }
-#pragma unroll
-    for (int dt = 0; dt < 8; ++dt)
-      vf[st][dt] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(dt * 16 + c16) * S + kvv + g * 8);
+    // fragments wave (K a, k step = wave), wave + 4 (K b), wave + 8 and wave + 12 (V^T dim tiles)
+    stage[0] = *reinterpret_cast<const u32x4*>(kbase + (size_t)ra * 128 + wave * 32 + g * 8);
+    stage[1] = *reinterpret_cast<const u32x4*>(kbase + (size_t)rb * 128 + wave * 32 + g * 8);
+    stage[2] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(wave * 16 + c16) * S + kvv + g * 8);
+    stage[3] = *reinterpret_cast<const u32x4*>(vbase + (size_t)((wave + 4) * 16 + c16) * S + kvv + g * 8);
   };
-  auto do_chunk = [&](auto stc, uint32_t kv0) __attribute__((always_inline)) {
-    constexpr int st = decltype(stc)::value;
+  auto sstore = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-    for (int h = 0; h < GH; ++h) {
-      f32x4 sa = f32x4{0.f, 0.f, 0.f, 0.f}, sb = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < 4; ++j) Fs[buf][wave + 4 * j][lane] = stage[j];
+  };
+
+  auto do_chunk = [&](int buf, uint32_t kv0) __attribute__((always_inline)) {
+    u32x4 pf[GH][PIECES];
+    {
+      u32x4 ka[4], kb[4];
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-        for (int pc = 0; pc < PIECES; ++pc) {
-          sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[st][ks]),
-                                                       __builtin_bit_cast(bf16x8, qf[h][ks][pc]), sa, 0, 0, 0);
-          sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[st][ks]),
-                                                       __builtin_bit_cast(bf16x8, qf[h][ks][pc]), sb, 0, 0, 0);
-        }
-      // element i of sa: position kv0 + g*8 + i; of sb: kv0 + g*8 + 4 + i; column = this lane's token
-      float sc[8];
-      float mx = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t kv = kv0 + g * 8 + i;
-        // scores in units of log 2: exp(s / sqrt(128)) = exp2(s * log2(e) / sqrt(128))
-        const float v = (i < 4 ? sa[i] : sb[i - 4]) * 0.12751743082459868f;
-        sc[i] = kv <= p ? v : -INFINITY;
-        mx = fmaxf(mx, sc[i]);
+      for (int ks = 0; ks < 4; ++ks) {
+        ka[ks] = Fs[buf][ks][lane];
+        kb[ks] = Fs[buf][4 + ks][lane];
       }
-      mx = col4_max(mx);
-      const float mn = fmaxf(mrun[h], mx);  // finite from the first chunk on: position 0 is visible to every token
-      const float alpha = __builtin_amdgcn_exp2f(mrun[h] - mn);
-      // once the running maxima have settled the rescale is a multiplication by one: skip it
-      const bool rescale = __any(mn != mrun[h]);
-      mrun[h] = mn;
-      uint32_t pb[PIECES][8];
-      float rs = 0.f;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        float w = __builtin_amdgcn_exp2f(sc[i] - mn);
-        if constexpr (PIECES == 1) {
-          pb[0][i] = bf16_bits(w);
-          rs += bf16_to_f32(pb[0][i]);
-        } else {
-          rs += w;
+      for (int h = 0; h < GH; ++h) {
+        f32x4 sa = f32x4{0.f, 0.f, 0.f, 0.f}, sb = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
           for (int pc = 0; pc < PIECES; ++pc) {
-            pb[pc][i] = bf16_bits(w);
-            w -= bf16_to_f32(pb[pc][i]);
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[ks]),
+                                                         __builtin_bit_cast(bf16x8, qf[h][ks][pc]), sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[ks]),
+                                                         __builtin_bit_cast(bf16x8, qf[h][ks][pc]), sb, 0, 0, 0);
+          }
+        // element i of sa: position kv0 + g*8 + i; of sb: kv0 + g*8 + 4 + i; column = this lane's token
+        float sc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sc[i] = i < 4 ? sa[i] : sb[i - 4];
+        if (kv0 + 31 > p_first) {  // the chunk reaches past the tile's first token: mask per lane
+#pragma unroll
+          for (int i = 0; i < 8; ++i) sc[i] = kv0 + g * 8 + i <= p ? sc[i] : -INFINITY;
+        }
+        float mx =
+            fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+        mx = col4_max(mx);
+        // scores in units of log 2: exp(s / sqrt(128)) = exp2(s * log2(e) / sqrt(128))
+        constexpr float kScale = 0.12751743082459868f;
+        const float mn = fmaxf(mrun[h], mx * kScale);  // finite from the first chunk on: position 0 is visible to every token
+        const float alpha = __builtin_amdgcn_exp2f(mrun[h] - mn);
+        // once the running maxima have settled the rescale is a multiplication by one: skip it
+        const bool rescale = __any(mn != mrun[h]);
+        mrun[h] = mn;
+        uint32_t pw[PIECES][4];  // weights as packed bf16 pairs: the B operand of the second product
+        float rs = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) {
+          float w0 = __builtin_amdgcn_exp2f(fmaf(sc[i], kScale, -mn));
+          float w1 = __builtin_amdgcn_exp2f(fmaf(sc[i + 1], kScale, -mn));
+          if constexpr (PIECES == 1) {
+            pw[0][i / 2] = bf16_pack2(w0, w1);
+            rs += bf16_lo(pw[0][i / 2]) + bf16_hi(pw[0][i / 2]);
+          } else {
+            rs += w0 + w1;
+#pragma unroll
+            for (int pc = 0; pc < PIECES; ++pc) {
+              pw[pc][i / 2] = bf16_pack2(w0, w1);
+              w0 -= bf16_lo(pw[pc][i / 2]);
+              w1 -= bf16_hi(pw[pc][i / 2]);
+            }
           }
         }
-      }
-      lsum[h] = lsum[h] * alpha + rs;
-      if (rescale) {
+        lsum[h] = lsum[h] * alpha + rs;
+        if (rescale) {
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
+          for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) acc[h][dt][e] *= alpha;
-      }
-#pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-#pragma unroll
-        for (int pc = 0; pc < PIECES; ++pc) {
-          const u32x4 pf = u32x4{pb[pc][0] | (pb[pc][1] << 16), pb[pc][2] | (pb[pc][3] << 16),
-                                 pb[pc][4] | (pb[pc][5] << 16), pb[pc][6] | (pb[pc][7] << 16)};
-          acc[h][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[st][dt]),
-                                                               __builtin_bit_cast(bf16x8, pf), acc[h][dt], 0, 0, 0);
+            for (int e = 0; e < 4; ++e) acc[h][dt][e] *= alpha;
         }
+#pragma unroll
+        for (int pc = 0; pc < PIECES; ++pc) pf[h][pc] = u32x4{pw[pc][0], pw[pc][1], pw[pc][2], pw[pc][3]};
       }
     }
-    };
-  load_chunk(std::integral_constant<int, 0>{}, 0);
-  for (uint32_t kv0 = 0;;) {
-    load_chunk(std::integral_constant<int, 1>{}, kv0 + 32);
-    do_chunk(std::integral_constant<int, 0>{}, kv0);
-    kv0 += 32;
-    if (kv0 > p_last) break;
-    load_chunk(std::integral_constant<int, 0>{}, kv0 + 32);
-    do_chunk(std::integral_constant<int, 1>{}, kv0);
-    kv0 += 32;
-    if (kv0 > p_last) break;
+    // every V^T fragment is read once and feeds all GH heads
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      const u32x4 vf = Fs[buf][8 + dt][lane];
+#pragma unroll
+      for (int h = 0; h < GH; ++h)
+#pragma unroll
+        for (int pc = 0; pc < PIECES; ++pc)
+          acc[h][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
+                                                               __builtin_bit_cast(bf16x8, pf[h][pc]), acc[h][dt], 0, 0, 0);
+    }
+  };
+
+  gload(0);
+  sstore(0);
+  lds_sync();
+  int buf = 0;
+  for (uint32_t kv0 = 0; kv0 <= p_last_wg; kv0 += 32, buf ^= 1) {
+    const bool more = kv0 + 32 <= p_last_wg;  // uniform over the workgroup
+    if (more) gload(kv0 + 32);
+    if (active && kv0 <= p_last) do_chunk(buf, kv0);
+    if (more) sstore(buf ^ 1);
+    lds_sync();
   }
+  if (!active) return;
 
   // acc[h][dt] element e: head dim dt*16 + g*4 + e of this lane's token.  Output goes straight
   // into the fragment order the output projection reads: operand index k = head * 128 + dim.
@@ -559,14 +594,13 @@ __global__ __launch_bounds__(64) void k_attn_prefill(const float* __restrict__ q
         float v[4] = {acc[h][dt][0] * inv, acc[h][dt][1] * inv, acc[h][dt][2] * inv, acc[h][dt][3] * inv};
 #pragma unroll
         for (int pc = 0; pc < PIECES; ++pc) {
-          uint32_t b[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            b[e] = bf16_bits(v[e]);
-            v[e] -= bf16_to_f32(b[e]);
-          }
+          const uint32_t b0 = bf16_pack2(v[0], v[1]), b1 = bf16_pack2(v[2], v[3]);
+          v[0] -= bf16_lo(b0);
+          v[1] -= bf16_hi(b0);
+          v[2] -= bf16_lo(b1);
+          v[3] -= bf16_hi(b1);
           const size_t el = (((size_t)(tq * PIECES + pc) * KTQ + (k0 >> 5)) * 64 + c16 + 16 * ((k0 & 31) >> 3)) * 8 + (k0 & 7);
-          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(Of) + el) = make_uint2(b[0] | (b[1] << 16), b[2] | (b[3] << 16));
+          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(Of) + el) = make_uint2(b0, b1);
         }
       }
     }
@@ -581,17 +615,16 @@ hipError_t launch_attn_prefill(hipStream_t s, const float* qkv, int nq, int nkv,
   const int G = nq / nkv;
   if (n <= 0 || G < 1 || nq % nkv || (pieces != 1 && pieces != 2) || S % 32 || pos0 + (uint32_t)n > S)
     return hipErrorInvalidValue;
-  const int GH = G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1);
-  dim3 grid((n + 15) / 16, nkv * (G / GH));
+  const int GH = G % 2 == 0 ? 2 : 1;
+  dim3 grid((n + 63) / 64, nkv * (G / GH));
   const uint16_t* k = static_cast<const uint16_t*>(kc);
   const uint16_t* v = static_cast<const uint16_t*>(vt);
 #define AP_LAUNCH(GHV)                                                                                          \
   do {                                                                                                          \
-    if (pieces == 2) k_attn_prefill<GHV, 2><<<grid, 64, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, Of); \
-    else k_attn_prefill<GHV, 1><<<grid, 64, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, Of);           \
+    if (pieces == 2) k_attn_prefill<GHV, 2><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, Of); \
+    else k_attn_prefill<GHV, 1><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, Of);           \
   } while (0)
-  if (GH == 4) AP_LAUNCH(4);
-  else if (GH == 2) AP_LAUNCH(2);
+  if (GH == 2) AP_LAUNCH(2);
   else AP_LAUNCH(1);
 #undef AP_LAUNCH
   return hipGetLastError();
