@@ -852,7 +852,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
             launch_v_transpose(s, L.vc, slot, nkv, c.max_seq, pos0, m->pb_vt, m->pb_vt_stride));
       RUN(FAM_PATTN, (pos0 + T) * 2.0 * Dkv * w + T * Dq * 6.0, rows * 4.0 * Dq,
           launch_attn_prefill(s, m->pb_qkv, nq, nkv, L.kc, m->pb_vt, m->pb_vt_stride, slot, c.max_seq, pos0, (int)n,
-                              pieces, m->pb_fb));
+                              pieces, m->pb_fb, m->n_cus));
     }
     {
       PrefillGemmArgs a{};

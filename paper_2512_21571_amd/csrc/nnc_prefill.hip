@@ -413,16 +413,21 @@ template <int GH, int PIECES>
 __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict__ qkv, int nq, int nkv,
                                                          const uint16_t* __restrict__ kc,
                                                          const uint16_t* __restrict__ vt, uint32_t S, uint32_t slot,
-                                                         uint32_t max_seq, uint32_t pos0, int n,
+                                                         uint32_t max_seq, uint32_t pos0, int n, int paired,
                                                          void* __restrict__ Of) {
   __shared__ u32x4 Fs[2][16][64];  // fragments 0-3: K tile a, 4-7: K tile b (k steps), 8-15: V^T (dim tiles)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c16 = lane & 15, g = lane >> 4;
   const int G = nq / nkv;
   const int kvh = blockIdx.y / (G / GH), head0 = kvh * G + (blockIdx.y % (G / GH)) * GH;
-  // the longest rows (last token tiles) are dispatched first, so the causal triangle packs onto
-  // the CUs without a long tail
-  const int tq4 = (int)gridDim.x - 1 - (int)blockIdx.x;
+  // Rows near the end of the prompt see many more positions than rows near its start.  Unpaired:
+  // one 64-token block per workgroup, the longest dispatched first.  Paired (launches whose
+  // workgroups are all resident at once, so dispatch order cannot balance them): every workgroup
+  // does block NB-1-i and then block i, the same number of chunks for all of them.
+  const int NB = (n + 63) / 64;
+  for (int pass = 0; pass < (paired ? 2 : 1); ++pass) {
+  const int tq4 = pass == 0 ? NB - 1 - (int)blockIdx.x : (int)blockIdx.x;
+  if (pass == 1 && tq4 >= NB - 1 - (int)blockIdx.x) break;  // the middle block of an odd count is done
   const int tq = tq4 * 4 + wave;
   const bool active = tq * 16 < n;  // a wave past the prompt only helps with the copies
   const int ld = (nq + 2 * nkv) * 128;
@@ -577,7 +582,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
     if (more) sstore(buf ^ 1);
     lds_sync();
   }
-  if (!active) return;
+  if (!active) continue;
 
   // acc[h][dt] element e: head dim dt*16 + g*4 + e of this lane's token.  Output goes straight
   // into the fragment order the output projection reads: operand index k = head * 128 + dim.
@@ -605,24 +610,32 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
       }
     }
   }
+  }  // pass
 }
 
 // qkv: [tokens][(nq + 2 nkv) * 128] fp32 with the query heads already normed and rotated.
 // kc: the layer's K cache; vt: transposed V copy of the slot (row stride S) covering positions
 // 0 .. pos0 + n - 1.  Of: fragment-order bf16 output ([token tile x pieces][nq*4][64][8]).
 hipError_t launch_attn_prefill(hipStream_t s, const float* qkv, int nq, int nkv, const void* kc, const void* vt,
-                               uint32_t S, uint32_t slot, uint32_t max_seq, uint32_t pos0, int n, int pieces, void* Of) {
+                               uint32_t S, uint32_t slot, uint32_t max_seq, uint32_t pos0, int n, int pieces, void* Of,
+                               int n_cus) {
   const int G = nq / nkv;
   if (n <= 0 || G < 1 || nq % nkv || (pieces != 1 && pieces != 2) || S % 32 || pos0 + (uint32_t)n > S)
     return hipErrorInvalidValue;
-  const int GH = G % 2 == 0 ? 2 : 1;
-  dim3 grid((n + 63) / 64, nkv * (G / GH));
+  // Two heads per wave halve the LDS reads per product; one head per wave doubles the
+  // workgroups.  Pairing needs two workgroups per CU after halving their number.
+  const int NB = (n + 63) / 64, slots = 2 * n_cus;
+  int GH = 1, paired = 0;
+  if (G % 2 == 0 && (NB + 1) / 2 * nkv * (G / 2) >= slots) GH = 2, paired = 1;
+  else if ((NB + 1) / 2 * nkv * G >= slots) paired = 1;
+  else if (G % 2 == 0 && NB * nkv * (G / 2) >= slots) GH = 2;
+  dim3 grid(paired ? (NB + 1) / 2 : NB, nkv * (G / GH));
   const uint16_t* k = static_cast<const uint16_t*>(kc);
   const uint16_t* v = static_cast<const uint16_t*>(vt);
 #define AP_LAUNCH(GHV)                                                                                          \
   do {                                                                                                          \
-    if (pieces == 2) k_attn_prefill<GHV, 2><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, Of); \
-    else k_attn_prefill<GHV, 1><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, Of);           \
+    if (pieces == 2) k_attn_prefill<GHV, 2><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, paired, Of); \
+    else k_attn_prefill<GHV, 1><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, paired, Of);           \
   } while (0)
   if (GH == 2) AP_LAUNCH(2);
   else AP_LAUNCH(1);
