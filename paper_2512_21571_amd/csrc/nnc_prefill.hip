@@ -408,7 +408,7 @@ hipError_t launch_v_transpose(hipStream_t s, const void* vc, uint32_t slot, int 
 // Masked positions get weight exp(-inf) = 0; their K / V^T values are finite (the copy and the
 // cache rows read are initialised memory), so 0 x value = 0.
 // PIECES = 2: queries and weights enter the matrix cores as two bf16 pieces (16 significant
-// bits); PIECES = 1: one bf16 each, and the row sum adds the rounded weights.
+// bits); PIECES = 1: one bf16 each.  The row sum adds the weights as they are multiplied.
 template <int GH, int PIECES>
 __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict__ qkv, int nq, int nkv,
                                                          const uint16_t* __restrict__ kc,
@@ -456,12 +456,12 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
       }
     }
 
-  f32x4 acc[GH][8];
-  float mrun[GH], lsum[GH];
+  f32x4 acc[GH][8], lacc[GH];  // lacc: the row sums, every element of a lane the sum of its token
+  float mrun[GH];
 #pragma unroll
   for (int h = 0; h < GH; ++h) {
     mrun[h] = -INFINITY;
-    lsum[h] = 0.f;
+    lacc[h] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) acc[h][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
@@ -472,22 +472,45 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
   const uint32_t p_last = pos0 + (uint32_t)min(tq * 16 + 15, n - 1);  // last position any row of the wave's tile sees
   const uint32_t p_last_wg = pos0 + (uint32_t)min(tq4 * 64 + 63, n - 1);
 
-  // copy of a chunk: thread tid moves element (tid & 63) of fragments (tid >> 6) + 4 j
+  // copy of a chunk: thread tid moves element (tid & 63) of fragments (tid >> 6) + 4 j, i.e.
+  // fragments wave (K tile a, k step = wave), wave + 4 (K tile b), wave + 8 and wave + 12
+  // (V^T dim tiles).  Addresses = a base that is uniform over the workgroup + a byte offset per
+  // thread that is fixed for the whole kernel.
+  const int r4 = (c16 >> 2) * 8 + (c16 & 3);  // K row of tile a for A-operand row c16; tile b: + 4
+  const uint32_t ok = (uint32_t)(r4 * 128 + wave * 32 + g * 8) * 2u;
+  const uint32_t ov0 = ((uint32_t)(wave * 16 + c16) * S + (uint32_t)g * 8u) * 2u, ov1 = ov0 + 64u * S * 2u;
   u32x4 stage[4];
-  auto gload = [&](uint32_t kv0) __attribute__((always_inline)) {
-    const int r4 = (c16 >> 2) * 8 + (c16 & 3);  // K row of tile a for A-operand row c16; tile b: + 4
-    const uint32_t ra = min(kv0 + r4, max_seq - 1), rb = min(kv0 + r4 + 4, max_seq - 1);
-    const uint32_t kvv = min(kv0, S - 32);  // past the last chunk: any valid chunk (never used)
-    // fragments wave (K a, k step = wave), wave + 4 (K b), wave + 8 and wave + 12 (V^T dim tiles)
-    stage[0] = *reinterpret_cast<const u32x4*>(kbase + (size_t)ra * 128 + wave * 32 + g * 8);
-    stage[1] = *reinterpret_cast<const u32x4*>(kbase + (size_t)rb * 128 + wave * 32 + g * 8);
-    stage[2] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(wave * 16 + c16) * S + kvv + g * 8);
-    stage[3] = *reinterpret_cast<const u32x4*>(vbase + (size_t)((wave + 4) * 16 + c16) * S + kvv + g * 8);
+  auto gload = [&](uint32_t kv0) __attribute__((always_inline)) {  // kv0 < S, a multiple of 32
+    const char* kb = reinterpret_cast<const char*>(kbase) + (size_t)kv0 * 256;
+    const char* vb = reinterpret_cast<const char*>(vbase) + (size_t)kv0 * 2;
+    if (kv0 + 32 <= max_seq) {
+      stage[0] = *reinterpret_cast<const u32x4*>(kb + ok);
+      stage[1] = *reinterpret_cast<const u32x4*>(kb + ok + 4 * 256);
+    } else {  // the cache ends inside the chunk: repeat its last row (those positions are masked)
+      const uint32_t ra = min(kv0 + r4, max_seq - 1), rb = min(kv0 + r4 + 4, max_seq - 1);
+      stage[0] = *reinterpret_cast<const u32x4*>(kbase + (size_t)ra * 128 + wave * 32 + g * 8);
+      stage[1] = *reinterpret_cast<const u32x4*>(kbase + (size_t)rb * 128 + wave * 32 + g * 8);
+    }
+    stage[2] = *reinterpret_cast<const u32x4*>(vb + ov0);
+    stage[3] = *reinterpret_cast<const u32x4*>(vb + ov1);
   };
   auto sstore = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) Fs[buf][wave + 4 * j][lane] = stage[j];
   };
+
+  // maxima without the NaN-quieting copies that fmaxf brings (no operand here is a NaN)
+  auto max3 = [](float x, float y, float z) __attribute__((always_inline)) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z));
+    return r;
+  };
+  auto max2 = [](float x, float y) __attribute__((always_inline)) {
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+  };
+  const u32x4 ones = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 x 8
 
   auto do_chunk = [&](int buf, uint32_t kv0) __attribute__((always_inline)) {
     u32x4 pf[GH][PIECES];
@@ -518,44 +541,44 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
 #pragma unroll
           for (int i = 0; i < 8; ++i) sc[i] = kv0 + g * 8 + i <= p ? sc[i] : -INFINITY;
         }
-        float mx =
-            fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-        mx = col4_max(mx);
         // scores in units of log 2: exp(s / sqrt(128)) = exp2(s * log2(e) / sqrt(128))
         constexpr float kScale = 0.12751743082459868f;
-        const float mn = fmaxf(mrun[h], mx * kScale);  // finite from the first chunk on: position 0 is visible to every token
-        const float alpha = __builtin_amdgcn_exp2f(mrun[h] - mn);
-        // once the running maxima have settled the rescale is a multiplication by one: skip it
-        const bool rescale = __any(mn != mrun[h]);
-        mrun[h] = mn;
-        uint32_t pw[PIECES][4];  // weights as packed bf16 pairs: the B operand of the second product
-        float rs = 0.f;
+        const float mx = max2(max3(sc[0], sc[1], sc[2]), max3(sc[3], sc[4], max3(sc[5], sc[6], sc[7]))) * kScale;
+        // The running maximum is the same in the four lanes of a token.  It only has to bound the
+        // scores: while no lane exceeds it, nothing is exchanged or rescaled.
+        if (__any(mx > mrun[h])) {
+          const float mn = max2(mrun[h], col4_max(mx));  // finite from the first chunk on: position 0 is visible to every token
+          const float alpha = __builtin_amdgcn_exp2f(mrun[h] - mn);
+          mrun[h] = mn;
 #pragma unroll
-        for (int i = 0; i < 8; i += 2) {
-          float w0 = __builtin_amdgcn_exp2f(fmaf(sc[i], kScale, -mn));
-          float w1 = __builtin_amdgcn_exp2f(fmaf(sc[i + 1], kScale, -mn));
-          if constexpr (PIECES == 1) {
-            pw[0][i / 2] = bf16_pack2(w0, w1);
-            rs += bf16_lo(pw[0][i / 2]) + bf16_hi(pw[0][i / 2]);
-          } else {
-            rs += w0 + w1;
-#pragma unroll
-            for (int pc = 0; pc < PIECES; ++pc) {
-              pw[pc][i / 2] = bf16_pack2(w0, w1);
-              w0 -= bf16_lo(pw[pc][i / 2]);
-              w1 -= bf16_hi(pw[pc][i / 2]);
-            }
-          }
-        }
-        lsum[h] = lsum[h] * alpha + rs;
-        if (rescale) {
+          for (int e = 0; e < 4; ++e) lacc[h][e] *= alpha;
 #pragma unroll
           for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[h][dt][e] *= alpha;
         }
+        const float mn = mrun[h];
+        uint32_t pw[PIECES][4];  // weights as packed bf16 pairs: the B operand of the second product
 #pragma unroll
-        for (int pc = 0; pc < PIECES; ++pc) pf[h][pc] = u32x4{pw[pc][0], pw[pc][1], pw[pc][2], pw[pc][3]};
+        for (int i = 0; i < 8; i += 2) {
+          float w0 = __builtin_amdgcn_exp2f(fmaf(sc[i], kScale, -mn));
+          float w1 = __builtin_amdgcn_exp2f(fmaf(sc[i + 1], kScale, -mn));
+#pragma unroll
+          for (int pc = 0; pc < PIECES; ++pc) {
+            pw[pc][i / 2] = bf16_pack2(w0, w1);
+            if (pc + 1 < PIECES) {
+              w0 -= bf16_lo(pw[pc][i / 2]);
+              w1 -= bf16_hi(pw[pc][i / 2]);
+            }
+          }
+        }
+#pragma unroll
+        for (int pc = 0; pc < PIECES; ++pc) {
+          pf[h][pc] = u32x4{pw[pc][0], pw[pc][1], pw[pc][2], pw[pc][3]};
+          // row sums of the weights as multiplied (all pieces): a product with a tile of ones
+          lacc[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones),
+                                                            __builtin_bit_cast(bf16x8, pf[h][pc]), lacc[h], 0, 0, 0);
+        }
       }
     }
     // every V^T fragment is read once and feeds all GH heads
@@ -589,9 +612,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
   const int KTQ = nq * 4;
 #pragma unroll
   for (int h = 0; h < GH; ++h) {
-    float l = lsum[h];
-    l = col4_sum(l);
-    const float inv = 1.0f / l;
+    const float inv = 1.0f / lacc[h][0];
     if (tq * 16 + c16 < n) {
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt) {
