@@ -514,6 +514,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
 
   auto do_chunk = [&](int buf, uint32_t kv0) __attribute__((always_inline)) {
     u32x4 pf[GH][PIECES];
+    // all 16 fragments are requested up front: the V^T reads complete under the first product
+    // and the softmax arithmetic
+    u32x4 vf[8];
     {
       u32x4 ka[4], kb[4];
 #pragma unroll
@@ -521,6 +524,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
         ka[ks] = Fs[buf][ks][lane];
         kb[ks] = Fs[buf][4 + ks][lane];
       }
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) vf[dt] = Fs[buf][8 + dt][lane];
 #pragma unroll
       for (int h = 0; h < GH; ++h) {
         f32x4 sa = f32x4{0.f, 0.f, 0.f, 0.f}, sb = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -581,15 +586,14 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
         }
       }
     }
-    // every V^T fragment is read once and feeds all GH heads
+    // every V^T fragment feeds all GH heads
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) {
-      const u32x4 vf = Fs[buf][8 + dt][lane];
 #pragma unroll
       for (int h = 0; h < GH; ++h)
 #pragma unroll
         for (int pc = 0; pc < PIECES; ++pc)
-          acc[h][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
+          acc[h][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[dt]),
                                                                __builtin_bit_cast(bf16x8, pf[h][pc]), acc[h][dt], 0, 0, 0);
     }
   };
