@@ -183,6 +183,10 @@ typedef enum {
   NNC_OPT_PREFILL_TILE = 4, /* block tile of the large-block prompt GEMMs: -1 (default) chosen from
                                each launch's size; 0: 64 x 128, 1: 256 x 128, 2: 128 x 128, 3: 64 x 64 (rows x
                                operand columns); results are bit-identical for all (same k order) */
+  NNC_OPT_PREFILL_ATTN = 6, /* launch shape of the large-block prompt attention: -1 (default) chosen
+                               from each launch's size; else bit 0: every workgroup takes a long
+                               and a short 64-token block, bit 1: two query heads per wave; results
+                               are bit-identical for all (a wave's arithmetic per head is the same) */
   NNC_OPT_SPIN_LIMIT = 5,   /* polls after which a wait inside the resident kernel gives up (sets
                                the failure flag and lets every workgroup exit); 0 (default):
                                2^20, about a second.  A tiny value makes the give-up path testable */

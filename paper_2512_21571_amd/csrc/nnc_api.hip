@@ -112,6 +112,7 @@ struct nnc_model {
 
   bool opt_graph = true;
   int opt_prefill_exact = 0;  // 0: large blocks, pieces by length; 1: 21-token chunks, three pieces; 2: large blocks, two pieces
+  int opt_prefill_attn = -1;  // forced launch shape of the prompt attention, -1 = by size
   int opt_prefill_tile = -1;  // forced block tile of the large-block prompt GEMMs, -1 = by size
   bool opt_persistent = true;
   std::map<std::tuple<int, int, int>, hipGraphExec_t> graphs;
@@ -785,6 +786,10 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
       if (value < -1 || value > 3) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic) or 0 .. 3");
       m->opt_prefill_tile = value;
       return NNC_OK;
+    case NNC_OPT_PREFILL_ATTN:
+      if (value < -1 || value > 3) return fail(NNC_E_ARG, "prefill attention shape must be -1 (automatic) or 0 .. 3");
+      m->opt_prefill_attn = value;
+      return NNC_OK;
     case NNC_OPT_SPIN_LIMIT:
       if (value < 0) return fail(NNC_E_ARG, "spin limit must be >= 0");
       m->mk_spin_limit = (unsigned)value;
@@ -852,7 +857,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
             launch_v_transpose(s, L.vc, slot, nkv, c.max_seq, pos0, m->pb_vt, m->pb_vt_stride));
       RUN(FAM_PATTN, (pos0 + T) * 2.0 * Dkv * w + T * Dq * 6.0, rows * 4.0 * Dq,
           launch_attn_prefill(s, m->pb_qkv, nq, nkv, L.kc, m->pb_vt, m->pb_vt_stride, slot, c.max_seq, pos0, (int)n,
-                              pieces, m->pb_fb, m->n_cus));
+                              pieces, m->pb_fb, m->n_cus, m->opt_prefill_attn));
     }
     {
       PrefillGemmArgs a{};

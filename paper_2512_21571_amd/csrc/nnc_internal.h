@@ -129,7 +129,7 @@ hipError_t launch_v_transpose(hipStream_t s, const void* vc, uint32_t slot, int 
                               void* vt, uint32_t S);
 hipError_t launch_attn_prefill(hipStream_t s, const float* qkv, int nq, int nkv, const void* kc, const void* vt,
                                uint32_t S, uint32_t slot, uint32_t max_seq, uint32_t pos0, int n, int pieces, void* Of,
-                               int n_cus);
+                               int n_cus, int shape);
 hipError_t launch_embed_rows(hipStream_t s, const void* Ep, int H, const int32_t* tokens_dev, int n, float* x);
 hipError_t launch_argmax(hipStream_t s, const float* logits, long ld, int V, int ncols,
                          const uint32_t* step_ptr, long step_stride, float* scratch_val,

@@ -643,7 +643,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
 // 0 .. pos0 + n - 1.  Of: fragment-order bf16 output ([token tile x pieces][nq*4][64][8]).
 hipError_t launch_attn_prefill(hipStream_t s, const float* qkv, int nq, int nkv, const void* kc, const void* vt,
                                uint32_t S, uint32_t slot, uint32_t max_seq, uint32_t pos0, int n, int pieces, void* Of,
-                               int n_cus) {
+                               int n_cus, int shape) {
   const int G = nq / nkv;
   if (n <= 0 || G < 1 || nq % nkv || (pieces != 1 && pieces != 2) || S % 32 || pos0 + (uint32_t)n > S)
     return hipErrorInvalidValue;
@@ -654,6 +654,11 @@ hipError_t launch_attn_prefill(hipStream_t s, const float* qkv, int nq, int nkv,
   if (G % 2 == 0 && (NB + 1) / 2 * nkv * (G / 2) >= slots) GH = 2, paired = 1;
   else if ((NB + 1) / 2 * nkv * G >= slots) paired = 1;
   else if (G % 2 == 0 && NB * nkv * (G / 2) >= slots) GH = 2;
+  if (shape >= 0) {  // forced: bit 0 = paired, bit 1 = two heads per wave (where the group size allows)
+    if (shape > 3) return hipErrorInvalidValue;
+    paired = shape & 1;
+    GH = (shape & 2) && G % 2 == 0 ? 2 : 1;
+  }
   dim3 grid(paired ? (NB + 1) / 2 : NB, nkv * (G / GH));
   const uint16_t* k = static_cast<const uint16_t*>(kc);
   const uint16_t* v = static_cast<const uint16_t*>(vt);

@@ -164,6 +164,28 @@ def test_large_block_prefill_every_block_tile(nnc, n, tile):
     assert int(ng.item()) == no
 
 
+@pytest.mark.parametrize("attn", [0, 1, 2, 3])
+@pytest.mark.parametrize("n", [40, 330, 700])
+def test_large_block_prefill_every_attention_shape(nnc, n, attn):
+    """Prompt attention launch shapes (one or two 64-token blocks per workgroup, one or two
+    heads per wave) forced on prompts with an odd and an even number of blocks: a wave's
+    arithmetic per head is the same in all of them, so the logits are bit-identical to the
+    automatic choice, and they match the oracle."""
+    print(f"case: large-block prefill length {n}, forced attention shape {attn}", flush=True)
+    shape = SMALL_G4
+    g, o = _pair(nnc, shape, 1, 800, exact_prefill=False)
+    toks = synth.tokens(n, shape.vocab, stream=500 + n)
+    one_piece = any(pc == 1 for _, _, pc in prefill_blocks(n))
+    ref, _ = g.prefill(0, toks)
+    g.kv_reset(0)
+    g.set_option(nnc.OPT_PREFILL_ATTN, attn)
+    lg, ng = g.prefill(0, toks)
+    assert np.array_equal(lg.cpu().numpy(), ref.cpu().numpy())
+    lo, no = oracle_prefill_like_library(o, 0, toks, shape)
+    _check_logits(shape, lg, lo, BF16_ABS_PROMPT if one_piece else BF16_ABS_TIGHT)
+    assert int(ng.item()) == no
+
+
 def test_large_block_prefill_two_pieces_at_any_length(nnc):
     print("case: large-block prefill, 600 tokens, two pieces forced", flush=True)
     shape = SMALL_G4
@@ -210,6 +232,12 @@ def test_multi_block_prefill_long_context(nnc):
     lo, no = oracle_prefill_like_library(o, 0, toks, shape)
     _check_logits(shape, lg, lo, BF16_ABS_PROMPT)
     assert int(ng.item()) == no
+    for attn in (1, 3):                                     # paired attention blocks on a block that starts mid-context
+        g.kv_reset(0)
+        g.set_option(nnc.OPT_PREFILL_ATTN, attn)
+        l2, _ = g.prefill(0, toks)
+        assert np.array_equal(l2.cpu().numpy(), lg.cpu().numpy())
+    g.set_option(nnc.OPT_PREFILL_ATTN, -1)
     lg, ng = g.decode_step([0], [no])                       # 44 attention chunks in the resident kernel
     lo, n2 = o.step_token(0, no, oracle_flags(shape))
     _check_logits(shape, lg[0], lo, BF16_ABS_PROMPT)
