@@ -15,6 +15,8 @@ HIPCC_FLAGS = [
     # the compiler may not form packed fp32 instructions on its own
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
+    # the direct-to-LDS copies set m0 inside inline assembly and list it as clobbered
+    "-Wno-inline-asm",
 ]
 
 

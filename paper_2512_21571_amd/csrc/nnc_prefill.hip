@@ -74,13 +74,81 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 }  // namespace
 
+// Epilogue of the prompt GEMMs: the accumulators of wave (wn, wt) of the block at (nt0, tt0).
+template <int EPI, int NT, int TT, int PIECES>
+__device__ __forceinline__ void pg_epilogue(const PrefillGemmArgs& a, f32x4 (&acc)[NT / 2][TT / 2], int nt0, int tt0,
+                                            int wn, int wt, int lane) {
+  constexpr int WI = NT / 2, WJ = TT / 2;
+  // accumulator element e of lane l in tile (i, j): row (l / 16) * 4 + e of row tile i,
+  // operand column l % 16 of column tile j.  With two pieces, column tiles 2q and 2q+1 are
+  // the two pieces of token tile q and their accumulators are added.
+  const int c16 = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int j = 0; j < WJ; j += PIECES) {
+    const int ct = tt0 + wt * WJ + j;  // column tile
+    if (ct >= a.t_tiles) continue;
+    const int tt = ct / PIECES;        // token tile
+    const size_t t = (size_t)tt * 16 + c16;
+    f32x4 v[WI];
+#pragma unroll
+    for (int i = 0; i < WI; ++i) {
+      v[i] = acc[i][j];
+      if constexpr (PIECES == 2) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[i][e] += acc[i][j + 1][e];
+      }
+    }
+    if constexpr (EPI == EPI_SWIGLU) {
+      // row tiles come as (gate, up) pairs; feature tile = row tile / 2
+      const int FKT = a.n_tiles / 4;  // k tiles of the next GEMM: features / 32
+#pragma unroll
+      for (int i = 0; i < WI; i += 2) {
+        const int nt = nt0 + wn * WI + i;
+        if (nt >= a.n_tiles) continue;
+        const int f0 = (nt >> 1) * 16 + g * 4;
+        uint32_t h[PIECES][4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float gate = v[i][e], up = v[i + 1][e];
+          float act = gate / (1.0f + expf(-gate)) * up;
+#pragma unroll
+          for (int pc = 0; pc < PIECES; ++pc) {
+            h[pc][e] = bf16_bits(act);
+            act -= bf16_to_f32(h[pc][e]);
+          }
+        }
+        // features f0 .. f0+3 of token t: 8 bytes inside one 16-byte fragment element
+#pragma unroll
+        for (int pc = 0; pc < PIECES; ++pc) {
+          const size_t el =
+              (((size_t)(tt * PIECES + pc) * FKT + (f0 >> 5)) * 64 + c16 + 16 * ((f0 & 31) >> 3)) * 8 + (f0 & 7);
+          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.packed_out) + el) =
+              make_uint2(h[pc][0] | (h[pc][1] << 16), h[pc][2] | (h[pc][3] << 16));
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < WI; ++i) {
+        const int nt = nt0 + wn * WI + i;
+        if (nt >= a.n_tiles) continue;
+        float4* dst = reinterpret_cast<float4*>(a.out + t * a.ldo + (size_t)nt * 16 + g * 4);
+        float4 o = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
+        if constexpr (EPI == EPI_RESID) {
+          const float4 p = *dst;
+          o = make_float4(p.x + o.x, p.y + o.y, p.z + o.z, p.w + o.w);
+        }
+        *dst = o;
+      }
+    }
+  }
+}
+
 // Both operands are already stored in fragment order in memory (1 KiB per 16 x 32 tile, one
 // 16-byte element per lane), so staging is a straight copy: global -> registers -> LDS, and
 // every LDS access is a conflict-free 16-byte access at lane * 16.  Double-buffered in LDS,
-// fed from a register ring several k steps deep; one workgroup barrier per k step.
-#ifndef PG_RING
-#define PG_RING(NT) ((NT) == 16 ? 2 : (NT) == 8 ? 4 : 8)
-#endif
+// fed from a register ring eight k steps deep; one workgroup barrier per k step.  This is the
+// kernel of the small block tiles (64 rows: short prompts, bound by streaming the weights, where
+// the deep ring matters); the large tiles use k_gemm_prefill_dl below.
 template <int EPI, int NT, int TT, int PIECES>
 __global__ __launch_bounds__(256, 2) void k_gemm_prefill(PrefillGemmArgs a) {
   constexpr int WI = NT / 2;   // row tiles per wave
@@ -104,7 +172,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill(PrefillGemmArgs a) {
 
   // Register ring of D k steps: the loads of step kt + D are issued when step kt starts, so D
   // steps of matrix-core work cover the memory latency even with one workgroup per CU.
-  constexpr int D = PG_RING(NT);  // even; sized to the registers left beside the accumulators
+  constexpr int D = 8;  // even
   u32x4 ra[D][AL], rb[D][BL];  // native vectors: arrays of the HIP uint4 struct end up in scratch memory
   // Load addresses = wave-uniform base of the k step (scalar registers) + a per-thread 32-bit
   // byte offset fixed for the whole kernel (tile indices clamped to the last valid one: rows /
@@ -187,68 +255,114 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill(PrefillGemmArgs a) {
       }
     });
 
-  // accumulator element e of lane l in tile (i, j): row (l / 16) * 4 + e of row tile i,
-  // operand column l % 16 of column tile j.  With two pieces, column tiles 2q and 2q+1 are
-  // the two pieces of token tile q and their accumulators are added.
-  const int c16 = lane & 15, g = lane >> 4;
+  pg_epilogue<EPI, NT, TT, PIECES>(a, acc, nt0, tt0, wn, wt, lane);
+}
+
+// The same GEMM with the operands copied global -> LDS directly (16 bytes per lane, a wave's 64
+// lanes land on 1 KiB contiguous: exactly one fragment), without passing through registers.
+// Three LDS stages and two register sets of fragments: when step kt starts, the copies of step
+// kt + 3 are issued into the stage whose fragments step kt already holds in registers, and the
+// fragments of step kt + 1 are read while the matrix cores work on step kt; one barrier per k
+// step.
+template <int EPI, int NT, int TT, int PIECES>
+__global__ __launch_bounds__(256, 2) void k_gemm_prefill_dl(PrefillGemmArgs a) {
+  constexpr int WI = NT / 2, AL = NT / 4, WJ = TT / 2, BL = TT / 4;
+  constexpr int ST = 3;
+  __shared__ u32x4 As[ST][NT][64];
+  __shared__ u32x4 Bs[ST][TT][64];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wn = wave >> 1, wt = wave & 1;
+  const int KT = a.KT;
+  const int nt0 = blockIdx.x * NT, tt0 = blockIdx.y * TT;
+  const char* __restrict__ W = static_cast<const char*>(a.Wp);
+  const char* __restrict__ X = static_cast<const char*>(a.Xf);
+
+  f32x4 acc[WI][WJ];
 #pragma unroll
-  for (int j = 0; j < WJ; j += PIECES) {
-    const int ct = tt0 + wt * WJ + j;  // column tile
-    if (ct >= a.t_tiles) continue;
-    const int tt = ct / PIECES;        // token tile
-    const size_t t = (size_t)tt * 16 + c16;
-    f32x4 v[WI];
+  for (int i = 0; i < WI; ++i)
 #pragma unroll
-    for (int i = 0; i < WI; ++i) {
-      v[i] = acc[i][j];
-      if constexpr (PIECES == 2) {
+    for (int j = 0; j < WJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // wave w copies fragments w, w + 4, ...; per-thread byte offsets are fixed for the kernel
+  // (tile indices clamped to the last valid one: rows / columns past the edge compute garbage
+  // that is never stored)
+  uint32_t voa[AL], vob[BL];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[i][e] += acc[i][j + 1][e];
-      }
-    }
-    if constexpr (EPI == EPI_SWIGLU) {
-      // row tiles come as (gate, up) pairs; feature tile = row tile / 2
-      const int FKT = a.n_tiles / 4;  // k tiles of the next GEMM: features / 32
+  for (int j = 0; j < AL; ++j) voa[j] = ((uint32_t)min(nt0 + wave + 4 * j, a.n_tiles - 1) * (uint32_t)KT * 64u + lane) * 16u;
 #pragma unroll
-      for (int i = 0; i < WI; i += 2) {
-        const int nt = nt0 + wn * WI + i;
-        if (nt >= a.n_tiles) continue;
-        const int f0 = (nt >> 1) * 16 + g * 4;
-        uint32_t h[PIECES][4];
+  for (int j = 0; j < BL; ++j) vob[j] = ((uint32_t)min(tt0 + wave + 4 * j, a.t_tiles - 1) * (uint32_t)KT * 64u + lane) * 16u;
+  // The copy instruction is written as inline assembly: the compiler, when it sees one, makes
+  // every later LDS read wait for all of them (it cannot tell which stage a read touches), which
+  // would undo the look-ahead.  Hidden from it, the waits are the explicit ones below.
+  // m0 = LDS byte address of the fragment (wave-uniform); lane l's 16 bytes land at m0 + 16 l.
+  typedef __attribute__((address_space(3))) void* lptr;
+  auto copy1 = [&](const char* base, uint32_t voff, uint32_t lds_addr) __attribute__((always_inline)) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(base)
+                 : "memory", "m0");
+  };
+  auto issue = [&](int kt, int st) __attribute__((always_inline)) {
+    const size_t ko = (size_t)kt * 1024;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float gate = v[i][e], up = v[i + 1][e];
-          float act = gate / (1.0f + expf(-gate)) * up;
+    for (int j = 0; j < AL; ++j) copy1(W + ko, voa[j], (uint32_t)(size_t)(lptr)&As[st][wave + 4 * j][0]);
 #pragma unroll
-          for (int pc = 0; pc < PIECES; ++pc) {
-            h[pc][e] = bf16_bits(act);
-            act -= bf16_to_f32(h[pc][e]);
-          }
-        }
-        // features f0 .. f0+3 of token t: 8 bytes inside one 16-byte fragment element
+    for (int j = 0; j < BL; ++j) copy1(X + ko, vob[j], (uint32_t)(size_t)(lptr)&Bs[st][wave + 4 * j][0]);
+  };
+  // s_waitcnt vmcnt(n) with the other counters left alone
+  constexpr int L = AL + BL;  // copy instructions per wave and k step
+  auto wait_vm = [](auto nc) __attribute__((always_inline)) {
+    constexpr int n = decltype(nc)::value;
+    __builtin_amdgcn_s_waitcnt((n & 0xf) | (7 << 4) | (15 << 8) | ((n >> 4) << 14));
+  };
+  // Fragments live in two register sets: while the matrix cores work on step kt (set kt & 1),
+  // the fragments of step kt + 1 are read from LDS into the other set.
+  u32x4 af[2][WI], bf[2][WJ];
+  auto read_frags = [&](auto setc, int st) __attribute__((always_inline)) {
+    constexpr int P = decltype(setc)::value;
 #pragma unroll
-        for (int pc = 0; pc < PIECES; ++pc) {
-          const size_t el =
-              (((size_t)(tt * PIECES + pc) * FKT + (f0 >> 5)) * 64 + c16 + 16 * ((f0 & 31) >> 3)) * 8 + (f0 & 7);
-          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.packed_out) + el) =
-              make_uint2(h[pc][0] | (h[pc][1] << 16), h[pc][2] | (h[pc][3] << 16));
-        }
-      }
-    } else {
+    for (int i = 0; i < WI; ++i) af[P][i] = As[st][wn * WI + i][lane];
 #pragma unroll
-      for (int i = 0; i < WI; ++i) {
-        const int nt = nt0 + wn * WI + i;
-        if (nt >= a.n_tiles) continue;
-        float4* dst = reinterpret_cast<float4*>(a.out + t * a.ldo + (size_t)nt * 16 + g * 4);
-        float4 o = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
-        if constexpr (EPI == EPI_RESID) {
-          const float4 p = *dst;
-          o = make_float4(p.x + o.x, p.y + o.y, p.z + o.z, p.w + o.w);
-        }
-        *dst = o;
-      }
+    for (int j = 0; j < WJ; ++j) bf[P][j] = Bs[st][wt * WJ + j][lane];
+  };
+  constexpr std::integral_constant<int, 0> c0{};
+  constexpr std::integral_constant<int, 1> c1{};
+  constexpr std::integral_constant<int, L> cL{};
+  constexpr std::integral_constant<int, 2 * L> c2L{};
+  // Step kt: stage kt % 3 is already in registers and free again, stage (kt + 1) % 3 must have
+  // landed (its copies were issued two steps ago), stage (kt + 2) % 3 is in flight.
+  auto step = [&](auto setc, int kt, int st) __attribute__((always_inline)) {
+    constexpr int P = decltype(setc)::value;
+    if (kt + 2 < KT) wait_vm(cL);  // all but the newest issue
+    else wait_vm(c0);
+    lds_sync();
+    if (kt + 3 < KT) issue(kt + 3, st);
+    if (kt + 1 < KT) read_frags(std::integral_constant<int, 1 - P>{}, st == 2 ? 0 : st + 1);
+#pragma unroll
+    for (int i = 0; i < WI; ++i)
+#pragma unroll
+      for (int j = 0; j < WJ; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[P][i]),
+                                                            __builtin_bit_cast(bf16x8, bf[P][j]), acc[i][j], 0, 0, 0);
+  };
+  issue(0, 0);
+  if (KT > 1) issue(1, 1);
+  if (KT > 2) issue(2, 2);
+  if (KT > 2) wait_vm(c2L);
+  else if (KT > 1) wait_vm(cL);
+  else wait_vm(c0);
+  lds_sync();
+  read_frags(c0, 0);
+  int st = 0;
+  for (int kt = 0; kt < KT; kt += 2) {
+    step(c0, kt, st);
+    st = st == 2 ? 0 : st + 1;
+    if (kt + 1 < KT) {
+      step(c1, kt + 1, st);
+      st = st == 2 ? 0 : st + 1;
     }
   }
+  pg_epilogue<EPI, NT, TT, PIECES>(a, acc, nt0, tt0, wn, wt, lane);
 }
 
 // a.t_tiles counts operand column tiles (token tiles x pieces).  shape: 0 = 64 x 128 block
@@ -260,12 +374,12 @@ hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a,
   if (epi == EPI_SWIGLU && a.n_tiles % 4) return hipErrorInvalidValue;
   const int NT = shape == 1 ? 16 : shape == 2 ? 8 : 4, TT = shape == 3 ? 4 : 8;
   dim3 grid((a.n_tiles + NT - 1) / NT, (a.t_tiles + TT - 1) / TT);
-#define PG_LAUNCH_P(E, P)                                                     \
-  do {                                                                        \
-    if (shape == 0) k_gemm_prefill<E, 4, 8, P><<<grid, 256, 0, s>>>(a);       \
-    else if (shape == 1) k_gemm_prefill<E, 16, 8, P><<<grid, 256, 0, s>>>(a); \
-    else if (shape == 2) k_gemm_prefill<E, 8, 8, P><<<grid, 256, 0, s>>>(a);  \
-    else k_gemm_prefill<E, 4, 4, P><<<grid, 256, 0, s>>>(a);                  \
+#define PG_LAUNCH_P(E, P)                                                          \
+  do {                                                                             \
+    if (shape == 0) k_gemm_prefill<E, 4, 8, P><<<grid, 256, 0, s>>>(a);            \
+    else if (shape == 1) k_gemm_prefill_dl<E, 16, 8, P><<<grid, 256, 0, s>>>(a);   \
+    else if (shape == 2) k_gemm_prefill_dl<E, 8, 8, P><<<grid, 256, 0, s>>>(a);    \
+    else k_gemm_prefill<E, 4, 4, P><<<grid, 256, 0, s>>>(a);                       \
   } while (0)
 #define PG_LAUNCH(E)                    \
   do {                                  \
