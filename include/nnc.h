@@ -181,7 +181,7 @@ typedef enum {
                                resident kernel per call (all steps of nnc_decode_greedy in a
                                single launch); 0: one kernel per stage */
   NNC_OPT_PREFILL_TILE = 4, /* block tile of the large-block prompt GEMMs: -1 (default) chosen from
-                               each launch's size; 0: 64 x 128, 1: 256 x 128, 2: 128 x 128, 3: 64 x 64 (rows x
+                               each launch's size; 0: 64 x 128, 1: 256 x 128, 2: 128 x 128, 3: 64 x 64, 4: 192 x 128 (rows x
                                operand columns); results are bit-identical for all (same k order) */
   NNC_OPT_PREFILL_ATTN = 6, /* launch shape of the large-block prompt attention: -1 (default) chosen
                                from each launch's size; else bit 0: every workgroup takes a long

@@ -783,7 +783,7 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
       return NNC_OK;
     case NNC_OPT_PERSISTENT: m->opt_persistent = value != 0; return NNC_OK;
     case NNC_OPT_PREFILL_TILE:
-      if (value < -1 || value > 3) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic) or 0 .. 3");
+      if (value < -1 || value > 4) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic) or 0 .. 4");
       m->opt_prefill_tile = value;
       return NNC_OK;
     case NNC_OPT_PREFILL_ATTN:
@@ -816,14 +816,24 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
   // Long prompts are matrix-core bound: one bf16 per activation, 256-row tiles.
   const int pieces = (n <= 512 || m->opt_prefill_exact == 2) ? 2 : 1;
   const int ct = tt * pieces;  // operand column tiles
-  // Block tile per GEMM: 256 x 128 when that launch has two workgroups for every CU, 128 x 128
-  // when it still has one of those, else 64 x 128, or 64 x 64 when even those are fewer than the
-  // CUs (short prompts, narrow projections).
+  // Block tile per GEMM.  Two workgroups fit on a CU and a launch runs in rounds of 2 x CUs of
+  // them: of 256 / 192 / 128 x 128 take the shape whose last round is fullest (larger tiles do
+  // a little more per byte of LDS traffic, hence the weights); 64 x 128, or 64 x 64 when even
+  // those are fewer than the CUs, for launches that cannot give every CU a larger tile.
   auto tile_shape = [&](int n_tiles) {
     if (m->opt_prefill_tile >= 0) return m->opt_prefill_tile;
-    const long cols = (ct + 7) / 8;
-    if ((long)((n_tiles + 15) / 16) * cols >= 2L * m->n_cus) return 1;
-    if ((long)((n_tiles + 7) / 8) * cols >= (long)m->n_cus) return 2;
+    const long cols = (ct + 7) / 8, slots = 2L * m->n_cus;
+    const int nts[3] = {16, 12, 8}, codes[3] = {1, 4, 2};
+    const double weight[3] = {1.0, 0.97, 0.93};
+    int best = -1;
+    double best_eff = 0.0;
+    for (int i = 0; i < 3; ++i) {
+      const long wgs = (long)((n_tiles + nts[i] - 1) / nts[i]) * cols;
+      if (wgs < (long)m->n_cus) continue;
+      const double eff = weight[i] * (double)wgs / (double)((wgs + slots - 1) / slots * slots);
+      if (eff > best_eff) best_eff = eff, best = codes[i];
+    }
+    if (best >= 0) return best;
     if ((long)((n_tiles + 3) / 4) * cols >= (long)m->n_cus) return 0;
     return 3;
   };

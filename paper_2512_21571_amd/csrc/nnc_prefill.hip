@@ -63,7 +63,8 @@ __device__ __forceinline__ void static_for(F&& f) {
 // 32.  4 waves in a 2 x 2 arrangement, each NT/2 x TT/2 accumulator tiles.
 //   NT = 16, TT = 8  (256 x 128, 128 x 64 per wave): the matrix-core-bound shape; per k step a
 //                    wave reads 12 fragments from LDS for 32 matrix-core instructions.
-//   NT = 8,  TT = 8  (128 x 128): launches that have fewer than two 256 x 128 workgroups per CU.
+//   NT = 12, TT = 8  (192 x 128) and NT = 8, TT = 8 (128 x 128): launches whose 256 x 128
+//                    workgroups would fill the last round of two per CU badly.
 //   NT = 4,  TT = 8  (64 x 128): short prompts, where the launch would otherwise leave most of
 //                    the chip idle.
 //   NT = 4,  TT = 4  (64 x 64): the same, for launches that even so have fewer workgroups than CUs.
@@ -366,19 +367,20 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill_dl(PrefillGemmArgs a) {
 }
 
 // a.t_tiles counts operand column tiles (token tiles x pieces).  shape: 0 = 64 x 128 block
-// tiles, 1 = 256 x 128, 2 = 128 x 128, 3 = 64 x 64.
+// tiles, 1 = 256 x 128, 2 = 128 x 128, 3 = 64 x 64, 4 = 192 x 128.
 hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a, int pieces, int shape) {
   if (a.n_tiles <= 0 || a.t_tiles <= 0 || a.KT <= 0 || (pieces != 1 && pieces != 2) || a.t_tiles % pieces ||
-      shape < 0 || shape > 3)
+      shape < 0 || shape > 4)
     return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU && a.n_tiles % 4) return hipErrorInvalidValue;
-  const int NT = shape == 1 ? 16 : shape == 2 ? 8 : 4, TT = shape == 3 ? 4 : 8;
+  const int NT = shape == 1 ? 16 : shape == 4 ? 12 : shape == 2 ? 8 : 4, TT = shape == 3 ? 4 : 8;
   dim3 grid((a.n_tiles + NT - 1) / NT, (a.t_tiles + TT - 1) / TT);
 #define PG_LAUNCH_P(E, P)                                                          \
   do {                                                                             \
     if (shape == 0) k_gemm_prefill<E, 4, 8, P><<<grid, 256, 0, s>>>(a);            \
     else if (shape == 1) k_gemm_prefill_dl<E, 16, 8, P><<<grid, 256, 0, s>>>(a);   \
     else if (shape == 2) k_gemm_prefill_dl<E, 8, 8, P><<<grid, 256, 0, s>>>(a);    \
+    else if (shape == 4) k_gemm_prefill_dl<E, 12, 8, P><<<grid, 256, 0, s>>>(a);   \
     else k_gemm_prefill<E, 4, 4, P><<<grid, 256, 0, s>>>(a);                       \
   } while (0)
 #define PG_LAUNCH(E)                    \

@@ -143,7 +143,7 @@ def test_large_block_prefill_lengths(nnc, n):
         assert int(ng.item()) == t
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 @pytest.mark.parametrize("n", [47, 300, 700])
 def test_large_block_prefill_every_block_tile(nnc, n, tile):
     """Each GEMM block tile (64 x 128, 256 x 128) forced on ragged small shapes: the
