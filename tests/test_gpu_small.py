@@ -146,8 +146,8 @@ def test_large_block_prefill_lengths(nnc, n):
 @pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 @pytest.mark.parametrize("n", [47, 300, 700])
 def test_large_block_prefill_every_block_tile(nnc, n, tile):
-    """Each GEMM block tile (64 x 128, 256 x 128) forced on ragged small shapes: the
-    k order of every output element is the same in both, so the logits are bit-identical
+    """Each GEMM block tile (64 x 128, 256 x 128, 128 x 128, 64 x 64, 192 x 128) forced on ragged
+    small shapes: the k order of every output element is the same in all, so the logits are bit-identical
     to the automatic choice, and they match the oracle."""
     print(f"case: large-block prefill length {n}, forced block tile {tile}", flush=True)
     shape = SMALL_G4
@@ -161,6 +161,22 @@ def test_large_block_prefill_every_block_tile(nnc, n, tile):
     assert np.array_equal(lg.cpu().numpy(), ref.cpu().numpy())
     lo, no = oracle_prefill_like_library(o, 0, toks, shape)
     _check_logits(shape, lg, lo, BF16_ABS_PROMPT if one_piece else BF16_ABS_TIGHT)
+    assert int(ng.item()) == no
+
+
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4])
+def test_large_block_prefill_short_k_loops(nnc, tile):
+    """A model so narrow that the GEMM k loops have 2 (QKV, gate|up) and 3 (down) steps:
+    shorter than the register ring and than the three LDS stages of the block-tile kernels."""
+    print(f"case: large-block prefill, hidden 64 / ffn 96, forced block tile {tile}", flush=True)
+    shape = synth.ModelShape("narrow", hidden=64, n_layers=2, n_q_heads=2, n_kv_heads=1, head_dim=128,
+                             ffn=96, vocab=512, dtype=synth.BF16)
+    g, o = _pair(nnc, shape, 1, 256, exact_prefill=False)
+    g.set_option(nnc.OPT_PREFILL_TILE, tile)
+    toks = synth.tokens(200, shape.vocab, stream=9)
+    lg, ng = g.prefill(0, toks)
+    lo, no = oracle_prefill_like_library(o, 0, toks, shape)
+    _check_logits(shape, lg, lo, BF16_ABS_TIGHT)
     assert int(ng.item()) == no
 
 
