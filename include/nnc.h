@@ -181,8 +181,11 @@ typedef enum {
                                resident kernel per call (all steps of nnc_decode_greedy in a
                                single launch); 0: one kernel per stage */
   NNC_OPT_PREFILL_TILE = 4, /* block tile of the large-block prompt GEMMs: -1 (default) chosen from
-                               each launch's size; 0: 64 x 128, 1: 256 x 128, 2: 128 x 128, 3: 64 x 64, 4: 192 x 128 (rows x
-                               operand columns); results are bit-identical for all (same k order) */
+                               each launch's size; 0: 64 x 128, 1: 256 x 128, 2: 128 x 128, 3: 64 x 64,
+                               4: 192 x 128 (rows x operand columns).  Same k order per output
+                               element in all, hence bit-identical results, except that the 64-row
+                               tiles split the k range of a short block's narrow projections over
+                               several workgroups (partial sums added in a fixed order) */
   NNC_OPT_PREFILL_ATTN = 6, /* launch shape of the large-block prompt attention: -1 (default) chosen
                                from each launch's size; else bit 0: every workgroup takes a long
                                and a short 64-token block, bit 1: two query heads per wave; results

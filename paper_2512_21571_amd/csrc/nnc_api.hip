@@ -89,6 +89,7 @@ struct nnc_model {
   // prompt pass on large token blocks
   uint32_t pb_max = 0;         // tokens per block (multiple of 128), 0 if unavailable
   float *pb_x = nullptr, *pb_qkv = nullptr;
+  float* pb_part = nullptr;                 // k-slice partial sums of short blocks' O / down projections
   void *pb_fa = nullptr, *pb_fb = nullptr;  // fragment-order bf16 operands: K = H, K = max(Dq, F)
   int32_t* pb_tok = nullptr;
   void* pb_vt = nullptr;  // transposed V copy of the slot being prefilled
@@ -242,6 +243,10 @@ struct Launch {
 
 // k-slices for the narrow output projections: enough workgroups to cover the chip,
 // but at least 8 k tiles (2 per wave) per workgroup.
+// Prompt blocks of at most PB_SPLIT_TOKENS tokens may split the k range of their narrow
+// projections over up to PB_SPLIT_MAX workgroups per output tile.
+constexpr int PB_SPLIT_MAX = 4;
+constexpr uint32_t PB_SPLIT_TOKENS = 512;
 constexpr int MAX_KSPLIT = 8;  // the norm kernel folds at most eight pending partials
 int pick_kts(int n_tiles, int KT) {
   int ksplit = 512 / (n_tiles > 0 ? n_tiles : 1);
@@ -678,6 +683,8 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     ALLOC(m->pb_fa, void*, frag_rows * H * 2);
     ALLOC(m->pb_fb, void*, frag_rows * std::max(Dq, F) * 2);
     ALLOC(m->pb_tok, int32_t*, (size_t)pb * 4);
+    // k-slice partials of the narrow projections of short blocks (up to PB_SPLIT_MAX - 1 buffers)
+    ALLOC(m->pb_part, float*, (size_t)(PB_SPLIT_MAX - 1) * std::min<size_t>(pb, PB_SPLIT_TOKENS) * H * 4);
     // transposed V copy of one slot: [kv head][128][positions, padded to a multiple of 32];
     // zero-filled once so that positions never written read as finite values
     m->pb_vt_stride = (c.max_seq + 31) / 32 * 32;
@@ -837,12 +844,27 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
     if ((long)((n_tiles + 3) / 4) * cols >= (long)m->n_cus) return 0;
     return 3;
   };
+  // k slices of a residual projection: only with the 64-row tiles, when the launch would leave
+  // most CUs without a workgroup, and with at least 8 k steps per slice
+  const long part_stride = (long)std::min<size_t>(m->pb_max, PB_SPLIT_TOKENS) * H;
+  auto resid_split = [&](PrefillGemmArgs& a, int shape) {
+    if ((shape != 0 && shape != 3) || n > PB_SPLIT_TOKENS) return 0;
+    const long wgs = (long)((a.n_tiles + 3) / 4) * ((ct + (shape == 3 ? 3 : 7)) / (shape == 3 ? 4 : 8));
+    int ks = (int)std::min<long>(PB_SPLIT_MAX, m->n_cus / (wgs > 0 ? wgs : 1));
+    ks = std::min(ks, a.KT / 8);
+    if (ks < 2) return 0;
+    a.kts_per_split = (a.KT + ks - 1) / ks;
+    a.part = m->pb_part;
+    a.part_stride = part_stride;
+    return (a.KT + a.kts_per_split - 1) / a.kts_per_split - 1;  // partial buffers to fold later
+  };
+  int pending = 0;  // partial buffers of the previous projection still to be added to pb_x
   const double w = 2.0, T = n;
   HIP_TRY(hipMemcpyAsync(m->pb_tok, tokens, (size_t)n * 4, hipMemcpyHostToDevice, s));
   RUN(FAM_EMBED, T * H * w, 0, launch_embed_rows(s, m->embed, H, m->pb_tok, (int)n, m->pb_x));
   for (uint32_t li = 0; li < c.n_layers; ++li) {
     const LayerW& L = m->L[li];
-    RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, m->pb_x, L.g_in, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
+    RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, m->pb_x, m->pb_part, pending, part_stride, L.g_in, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
     {
       PrefillGemmArgs a{};
       a.Wp = L.wqkv; a.n_tiles = Nqkv / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
@@ -873,9 +895,11 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       PrefillGemmArgs a{};
       a.Wp = L.wo; a.n_tiles = H / 16; a.KT = Dq / 32; a.Xf = m->pb_fb; a.t_tiles = ct;
       a.out = m->pb_x; a.ldo = H;
-      RUN(FAM_PGEMM, (double)H * Dq * w, 2.0 * H * Dq * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, tile_shape(a.n_tiles)));
+      const int shape = tile_shape(a.n_tiles);
+      pending = resid_split(a, shape);
+      RUN(FAM_PGEMM, (double)H * Dq * w, 2.0 * H * Dq * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, shape));
     }
-    RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, m->pb_x, L.g_post, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
+    RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, m->pb_x, m->pb_part, pending, part_stride, L.g_post, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
     {
       PrefillGemmArgs a{};
       a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
@@ -886,14 +910,16 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       PrefillGemmArgs a{};
       a.Wp = L.wd; a.n_tiles = H / 16; a.KT = F / 32; a.Xf = m->pb_fb; a.t_tiles = ct;
       a.out = m->pb_x; a.ldo = H;
-      RUN(FAM_PGEMM, (double)H * F * w, 2.0 * H * F * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, tile_shape(a.n_tiles)));
+      const int shape = tile_shape(a.n_tiles);
+      pending = resid_split(a, shape);
+      RUN(FAM_PGEMM, (double)H * F * w, 2.0 * H * F * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, shape));
     }
   }
   if (want_head) {
     // logits of the block's last token: fp32-grade (three-piece) GEMV over the LM head
     RUN(FAM_NORM, H * 8.0, 0,
-        launch_rmsnorm_pack(s, false, m->pb_x + (size_t)(n - 1) * H, H, nullptr, 0, 0, m->g_final, H, c.rms_eps, 1,
-                            m->Xp, 3, 3));
+        launch_rmsnorm_pack(s, false, m->pb_x + (size_t)(n - 1) * H, H, m->pb_part + (size_t)(n - 1) * H, pending,
+                            part_stride, m->g_final, H, c.rms_eps, 1, m->Xp, 3, 3));
     GemmArgs a{};
     a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = H / 32; a.kts_per_split = H / 32;
     a.Xp = m->Xp; a.NC = 3; a.ncols = 3; a.nsplit = 3; a.nseq = 1;

@@ -119,12 +119,20 @@ struct PrefillGemmArgs {
   float* out;
   long ldo;
   void* packed_out;
+  // k split (64-row tiles with the residual epilogue only): k tiles per blockIdx.z slice, 0 =
+  // one slice.  Slice 0 adds to `out`; slice s > 0 stores its partial sums at part + (s - 1) *
+  // part_stride (same row stride as out).
+  int kts_per_split = 0;
+  float* part = nullptr;
+  long part_stride = 0;
 };
 hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a, int pieces, int shape);
-// RMSNorm of rows 0..n_rows-1 of x ([rows, H] fp32), one bf16 per value, fragment order;
-// rows n_rows .. 16 * t_tiles - 1 of the operand are zero-filled.
-hipError_t launch_rmsnorm_frag(hipStream_t s, const float* x, const float* gain, int H, float eps, int n_rows,
-                               int token_tiles, int pieces, void* Xf);
+// x[rows, H] += part[0] + ... + part[nparts-1] (written back), then RMSNorm of rows 0..n_rows-1
+// as `pieces` bf16 per value in fragment order; rows n_rows .. 16 * token_tiles - 1 of the
+// operand are zero-filled.
+hipError_t launch_rmsnorm_frag(hipStream_t s, float* x, const float* part, int nparts, long part_stride,
+                               const float* gain, int H, float eps, int n_rows, int token_tiles, int pieces,
+                               void* Xf);
 hipError_t launch_v_transpose(hipStream_t s, const void* vc, uint32_t slot, int nkv, uint32_t max_seq, uint32_t n_pos,
                               void* vt, uint32_t S);
 hipError_t launch_attn_prefill(hipStream_t s, const float* qkv, int nq, int nkv, const void* kc, const void* vt,

@@ -78,7 +78,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 // Epilogue of the prompt GEMMs: the accumulators of wave (wn, wt) of the block at (nt0, tt0).
 template <int EPI, int NT, int TT, int PIECES>
 __device__ __forceinline__ void pg_epilogue(const PrefillGemmArgs& a, f32x4 (&acc)[NT / 2][TT / 2], int nt0, int tt0,
-                                            int wn, int wt, int lane) {
+                                            int wn, int wt, int lane, int kslice = 0) {
   constexpr int WI = NT / 2, WJ = TT / 2;
   // accumulator element e of lane l in tile (i, j): row (l / 16) * 4 + e of row tile i,
   // operand column l % 16 of column tile j.  With two pieces, column tiles 2q and 2q+1 are
@@ -132,11 +132,16 @@ __device__ __forceinline__ void pg_epilogue(const PrefillGemmArgs& a, f32x4 (&ac
       for (int i = 0; i < WI; ++i) {
         const int nt = nt0 + wn * WI + i;
         if (nt >= a.n_tiles) continue;
-        float4* dst = reinterpret_cast<float4*>(a.out + t * a.ldo + (size_t)nt * 16 + g * 4);
+        // k slice 0 owns the output; slice s > 0 stores its partial sums in buffer s - 1, which
+        // the next norm kernel adds in a fixed order
+        float* base = kslice == 0 ? a.out : a.part + (size_t)(kslice - 1) * a.part_stride;
+        float4* dst = reinterpret_cast<float4*>(base + t * a.ldo + (size_t)nt * 16 + g * 4);
         float4 o = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
         if constexpr (EPI == EPI_RESID) {
-          const float4 p = *dst;
-          o = make_float4(p.x + o.x, p.y + o.y, p.z + o.z, p.w + o.w);
+          if (kslice == 0) {
+            const float4 p = *dst;
+            o = make_float4(p.x + o.x, p.y + o.y, p.z + o.z, p.w + o.w);
+          }
         }
         *dst = o;
       }
@@ -160,10 +165,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill(PrefillGemmArgs a) {
   __shared__ u32x4 Bs[2][TT][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wn = wave >> 1, wt = wave & 1;
-  const int KT = a.KT;
+  // blockIdx.z = k slice (narrow launches of short prompts split k for more workgroups)
+  const int kts = a.kts_per_split > 0 ? a.kts_per_split : a.KT;
+  const int kt_first = blockIdx.z * kts;
+  const int KT = min(a.KT, kt_first + kts) - kt_first;  // k steps of this slice
   const int nt0 = blockIdx.x * NT, tt0 = blockIdx.y * TT;
-  const u32x4* __restrict__ W = static_cast<const u32x4*>(a.Wp);
-  const u32x4* __restrict__ X = static_cast<const u32x4*>(a.Xf);
+  const u32x4* __restrict__ W = static_cast<const u32x4*>(a.Wp) + (size_t)kt_first * 64;
+  const u32x4* __restrict__ X = static_cast<const u32x4*>(a.Xf) + (size_t)kt_first * 64;
 
   f32x4 acc[WI][WJ];
 #pragma unroll
@@ -184,12 +192,12 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill(PrefillGemmArgs a) {
 #pragma unroll
   for (int j = 0; j < AL; ++j) {
     const int idx = tid + 256 * j, tile = min(nt0 + (idx >> 6), a.n_tiles - 1);
-    voa[j] = ((uint32_t)tile * (uint32_t)KT * 64u + (uint32_t)(idx & 63)) * 16u;
+    voa[j] = ((uint32_t)tile * (uint32_t)a.KT * 64u + (uint32_t)(idx & 63)) * 16u;
   }
 #pragma unroll
   for (int j = 0; j < BL; ++j) {
     const int idx = tid + 256 * j, tile = min(tt0 + (idx >> 6), a.t_tiles - 1);
-    vob[j] = ((uint32_t)tile * (uint32_t)KT * 64u + (uint32_t)(idx & 63)) * 16u;
+    vob[j] = ((uint32_t)tile * (uint32_t)a.KT * 64u + (uint32_t)(idx & 63)) * 16u;
   }
   auto gload = [&](auto stc, int kt) __attribute__((always_inline)) {
     constexpr int st = decltype(stc)::value;
@@ -256,7 +264,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill(PrefillGemmArgs a) {
       }
     });
 
-  pg_epilogue<EPI, NT, TT, PIECES>(a, acc, nt0, tt0, wn, wt, lane);
+  pg_epilogue<EPI, NT, TT, PIECES>(a, acc, nt0, tt0, wn, wt, lane, (int)blockIdx.z);
 }
 
 // The same GEMM with the operands copied global -> LDS directly (16 bytes per lane, a wave's 64
@@ -374,7 +382,12 @@ hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a,
     return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU && a.n_tiles % 4) return hipErrorInvalidValue;
   const int NT = shape == 1 ? 16 : shape == 4 ? 12 : shape == 2 ? 8 : 4, TT = shape == 3 ? 4 : 8;
-  dim3 grid((a.n_tiles + NT - 1) / NT, (a.t_tiles + TT - 1) / TT);
+  int ksplit = 1;
+  if (a.kts_per_split > 0) {  // only the small tiles, only the residual epilogue, and a place for the partials
+    if ((shape != 0 && shape != 3) || epi != EPI_RESID || !a.part) return hipErrorInvalidValue;
+    ksplit = (a.KT + a.kts_per_split - 1) / a.kts_per_split;
+  }
+  dim3 grid((a.n_tiles + NT - 1) / NT, (a.t_tiles + TT - 1) / TT, ksplit);
 #define PG_LAUNCH_P(E, P)                                                          \
   do {                                                                             \
     if (shape == 0) k_gemm_prefill<E, 4, 8, P><<<grid, 256, 0, s>>>(a);            \
@@ -402,9 +415,12 @@ hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a,
 // One workgroup per token row: h = x / sqrt(mean(x^2) + eps) * g as `pieces` bf16 values
 // (value, remainder), written in fragment order: token tile q occupies column tiles
 // q * pieces + piece.  Rows beyond n_rows are zero-filled so that padded tiles are defined.
-__global__ __launch_bounds__(256) void k_rmsnorm_frag(const float* __restrict__ x, const float* __restrict__ gain,
-                                                      int H, float eps, int n_rows, int pieces,
-                                                      void* __restrict__ Xf) {
+// The pending k-slice partials of the previous projection are added to x first (fixed order,
+// written back: x is the residual stream).
+__global__ __launch_bounds__(256) void k_rmsnorm_frag(float* __restrict__ x, const float* __restrict__ part,
+                                                      int nparts, long part_stride,
+                                                      const float* __restrict__ gain, int H, float eps, int n_rows,
+                                                      int pieces, void* __restrict__ Xf) {
   __shared__ float sm[4];
   const int t = blockIdx.x, KT = H / 32;
   uint4* out = static_cast<uint4*>(Xf) + ((size_t)(t >> 4) * pieces * KT) * 64 + (t & 15);
@@ -415,7 +431,20 @@ __global__ __launch_bounds__(256) void k_rmsnorm_frag(const float* __restrict__ 
         out[pc * piece_stride + (size_t)(kg >> 2) * 64 + 16 * (kg & 3)] = uint4{0, 0, 0, 0};
     return;
   }
-  const float* xr = x + (size_t)t * H;
+  float* xr = x + (size_t)t * H;
+  if (nparts > 0) {
+    const float* pr = part + (size_t)t * H;
+    for (int i = threadIdx.x * 4; i < H; i += 1024) {
+      float4 add = *reinterpret_cast<const float4*>(pr + i);
+      for (int p = 1; p < nparts; ++p) {
+        const float4 q = *reinterpret_cast<const float4*>(pr + (size_t)p * part_stride + i);
+        add = make_float4(add.x + q.x, add.y + q.y, add.z + q.z, add.w + q.w);
+      }
+      const float4 v = *reinterpret_cast<const float4*>(xr + i);
+      *reinterpret_cast<float4*>(xr + i) = make_float4(v.x + add.x, v.y + add.y, v.z + add.z, v.w + add.w);
+    }
+    __syncthreads();  // the folded row is read back below by other threads of the workgroup
+  }
   float ss = 0.f;
   for (int i = threadIdx.x; i < H; i += 256) ss += xr[i] * xr[i];
   ss = wave_sum(ss);
@@ -427,21 +456,23 @@ __global__ __launch_bounds__(256) void k_rmsnorm_frag(const float* __restrict__ 
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = xr[kg * 8 + e] * r * gain[kg * 8 + e];
     for (int pc = 0; pc < pieces; ++pc) {
-      uint32_t h[8];
+      uint32_t h[4];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        h[e] = bf16_bits(v[e]);
-        v[e] -= bf16_to_f32(h[e]);
+      for (int e = 0; e < 4; ++e) {
+        h[e] = bf16_pack2(v[2 * e], v[2 * e + 1]);
+        v[2 * e] -= bf16_lo(h[e]);
+        v[2 * e + 1] -= bf16_hi(h[e]);
       }
-      out[pc * piece_stride + (size_t)(kg >> 2) * 64 + 16 * (kg & 3)] =
-          uint4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+      out[pc * piece_stride + (size_t)(kg >> 2) * 64 + 16 * (kg & 3)] = uint4{h[0], h[1], h[2], h[3]};
     }
   }
 }
 
-hipError_t launch_rmsnorm_frag(hipStream_t s, const float* x, const float* gain, int H, float eps, int n_rows,
-                               int token_tiles, int pieces, void* Xf) {
-  k_rmsnorm_frag<<<token_tiles * 16, 256, 0, s>>>(x, gain, H, eps, n_rows, pieces, Xf);
+hipError_t launch_rmsnorm_frag(hipStream_t s, float* x, const float* part, int nparts, long part_stride,
+                               const float* gain, int H, float eps, int n_rows, int token_tiles, int pieces,
+                               void* Xf) {
+  if (H % 32 || nparts < 0 || (nparts > 0 && !part) || n_rows <= 0) return hipErrorInvalidValue;
+  k_rmsnorm_frag<<<token_tiles * 16, 256, 0, s>>>(x, part, nparts, part_stride, gain, H, eps, n_rows, pieces, Xf);
   return hipGetLastError();
 }
 

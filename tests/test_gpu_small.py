@@ -147,21 +147,34 @@ def test_large_block_prefill_lengths(nnc, n):
 @pytest.mark.parametrize("n", [47, 300, 700])
 def test_large_block_prefill_every_block_tile(nnc, n, tile):
     """Each GEMM block tile (64 x 128, 256 x 128, 128 x 128, 64 x 64, 192 x 128) forced on ragged
-    small shapes: the k order of every output element is the same in all, so the logits are bit-identical
-    to the automatic choice, and they match the oracle."""
+    small shapes.  The k order of every output element is the same in all of them, so the logits
+    are bit-identical to those of the 256 x 128 tile -- except where a 64-row tile splits the k
+    range of the narrow projections of a short block over several workgroups (partial sums added
+    in a fixed order).  All match the oracle."""
     print(f"case: large-block prefill length {n}, forced block tile {tile}", flush=True)
     shape = SMALL_G4
     g, o = _pair(nnc, shape, 1, 800, exact_prefill=False)
     toks = synth.tokens(n, shape.vocab, stream=300 + n)
     one_piece = any(pc == 1 for _, _, pc in prefill_blocks(n))
+    g.set_option(nnc.OPT_PREFILL_TILE, 1)
     ref, _ = g.prefill(0, toks)
     g.kv_reset(0)
     g.set_option(nnc.OPT_PREFILL_TILE, tile)
     lg, ng = g.prefill(0, toks)
-    assert np.array_equal(lg.cpu().numpy(), ref.cpu().numpy())
+    if tile in (1, 2, 4) or n > 512:
+        assert np.array_equal(lg.cpu().numpy(), ref.cpu().numpy())
+    else:
+        # a partial-sum order that differs in the last bit can round a cached bf16 K / V element
+        # the other way, which moves the logits by ~1e-4
+        assert np.abs(lg.cpu().numpy() - ref.cpu().numpy()).max() <= 5e-4
     lo, no = oracle_prefill_like_library(o, 0, toks, shape)
     _check_logits(shape, lg, lo, BF16_ABS_PROMPT if one_piece else BF16_ABS_TIGHT)
     assert int(ng.item()) == no
+    g.set_option(nnc.OPT_PREFILL_TILE, -1)
+    g.kv_reset(0)
+    la, na = g.prefill(0, toks)                      # the automatic choice
+    _check_logits(shape, la, lo, BF16_ABS_PROMPT if one_piece else BF16_ABS_TIGHT)
+    assert int(na.item()) == no
 
 
 @pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4])
