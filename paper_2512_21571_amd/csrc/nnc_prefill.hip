@@ -662,7 +662,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
   auto do_chunk = [&](int buf, uint32_t kv0) __attribute__((always_inline)) {
     u32x4 pf[GH][PIECES];
     // all 16 fragments are requested up front: the V^T reads complete under the first product
-    // and the softmax arithmetic
+    // and the softmax arithmetic (two heads with two pieces each have no registers left for
+    // that: they read each V^T fragment where it is used)
+    constexpr bool kVfUpFront = !(GH == 2 && PIECES == 2);
     u32x4 vf[8];
     {
       u32x4 ka[4], kb[4];
@@ -671,8 +673,10 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
         ka[ks] = Fs[buf][ks][lane];
         kb[ks] = Fs[buf][4 + ks][lane];
       }
+      if constexpr (kVfUpFront) {
 #pragma unroll
-      for (int dt = 0; dt < 8; ++dt) vf[dt] = Fs[buf][8 + dt][lane];
+        for (int dt = 0; dt < 8; ++dt) vf[dt] = Fs[buf][8 + dt][lane];
+      }
 #pragma unroll
       for (int h = 0; h < GH; ++h) {
         f32x4 sa = f32x4{0.f, 0.f, 0.f, 0.f}, sb = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -736,6 +740,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
     // every V^T fragment feeds all GH heads
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) {
+      if constexpr (!kVfUpFront) vf[dt] = Fs[buf][8 + dt][lane];
 #pragma unroll
       for (int h = 0; h < GH; ++h)
 #pragma unroll
