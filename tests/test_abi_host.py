@@ -27,6 +27,19 @@ def test_library_exports_every_declared_symbol(nnc):
         assert getattr(nnc.lib(), name) is not None
 
 
+def test_binding_constants_match_the_header(nnc):
+    """The Python binding restates the option and status codes of the header: same values."""
+    header = open(os.path.join(ROOT, "include", "nnc.h")).read()
+    opts = dict(re.findall(r"\bNNC_(OPT_[A-Z_]+)\s*=\s*(\d+)", header))
+    assert len(opts) >= 7
+    for name, value in opts.items():
+        assert getattr(nnc, name) == int(value), name
+    codes = dict(re.findall(r"\bNNC_(OK|E_[A-Z_]+)\s*=\s*(\d+)", header))
+    assert len(codes) == 8
+    for name, value in codes.items():
+        assert getattr(nnc, name) == int(value), name
+
+
 def test_blob_bytes_matches_generator_for_all_benchmark_shapes(nnc):
     for shape in synth.SHAPES.values():
         cfg = nnc.make_config(shape, 1, 64)
