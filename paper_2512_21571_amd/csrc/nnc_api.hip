@@ -697,10 +697,24 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
       c.n_q_heads / c.n_kv_heads <= 16) {
     const int qkv_tiles = (int)((Dq + 2 * Dkv) / 16);
     m->mk_nwg = prop.multiProcessorCount < qkv_tiles ? prop.multiProcessorCount : qkv_tiles;
-    // k slices of the narrow projections: 32 k tiles per slice (all of it prefetched, 8 loads
-    // per lane), at most 4 slices (a consumer adds at most four partial vectors)
-    m->mk_ks_o = (int)std::min<size_t>(4, (Dq / 32 + 31) / 32);
-    m->mk_ks_d = (int)std::min<size_t>(4, (F / 32 + 31) / 32);
+    // k slices of the narrow projections (units = 16-row tiles x slices, dealt round-robin to the
+    // workgroups): at most 4 (a consumer adds at most four partial vectors), at least 32 k tiles
+    // per slice and a multiple of 4 (the four waves share a slice evenly); among those the count
+    // that leaves the busiest workgroup the fewest bytes, ties going to 2, 3, 4, 1 in that order
+    // (measured: fewer partials to add beat more parallelism, one slice per tile is slowest).
+    auto pick_ks = [&](size_t K) {
+      const int KT = (int)(K / 32), tiles = (int)(H / 16), nwg = m->mk_nwg;
+      int best = 1;
+      double best_m = 1e30;
+      for (int ks : {2, 3, 4, 1}) {
+        if (ks > 1 && (ks > KT / 32 || KT % (4 * ks))) continue;
+        const double mload = (double)((tiles * ks + nwg - 1) / nwg) / ks;
+        if (mload < best_m * 0.999) best_m = mload, best = ks;
+      }
+      return best;
+    };
+    m->mk_ks_o = pick_ks(Dq);
+    m->mk_ks_d = pick_ks(F);
     MkPlan plan{};
     plan.H = (int)H; plan.nq = (int)c.n_q_heads; plan.F = (int)F;
     plan.ks_o = m->mk_ks_o; plan.ks_d = m->mk_ks_d;
