@@ -65,6 +65,40 @@ def counter_traffic(workload: str, decode_steps: int):
     return None
 
 
+def resident_stage_trace(model, nnc, shape, prompt):
+    """Per-stage times of one decode step inside the resident kernel: every workgroup stamps the
+    100 MHz wall clock at its stage boundaries; mean / fastest / slowest workgroup of the
+    per-layer means, in microseconds."""
+    import numpy as np
+    model.kv_reset(0)
+    _, nxt = model.prefill(0, prompt, want_logits=False)
+    first = int(nxt.item())
+    model.decode_greedy([0], [first], 8)
+    model.set_option(nnc.OPT_STAGE_TRACE, 5 + 1)               # trace step 5 of the next launch
+    model.decode_greedy([0], [first], 16)
+    model.synchronize()
+    t = model.stage_trace().astype(np.int64)
+    model.set_option(nnc.OPT_STAGE_TRACE, 0)
+    L = shape.n_layers
+    names = ["wait for x + input norm", "QKV GEMM + publish", "attention", "merge + O projection",
+             "wait for x + post-attention norm", "gate|up GEMM + publish", "down projection", "to next layer"]
+    per = t[:, :8 * L].reshape(-1, L, 8)
+    nxt_start = np.concatenate([per[:, 1:, 0], t[:, 8 * L:8 * L + 1]], axis=1)
+    d = np.diff(np.concatenate([per, nxt_start[:, :, None]], axis=2), axis=2) * 0.01
+    lo = min(2, L - 1)                                          # skip the first layers of the step (cold prefetch)
+    out = {"per_layer": [{"stage": n, "mean": round(float(d[:, lo:, i].mean()), 2),
+                          "fastest_wg": round(float(d[:, lo:, i].mean(axis=1).min()), 2),
+                          "slowest_wg": round(float(d[:, lo:, i].mean(axis=1).max()), 2)}
+                         for i, n in enumerate(names)],
+           "layer_total": round(float(d[:, lo:, :].sum(axis=2).mean()), 2)}
+    fin = np.diff(t[:, 8 * L - 1:], axis=1) * 0.01
+    out["after_last_layer"] = {"wait + final norm": round(float(fin[:, 0].mean()), 2),
+                               "LM head": round(float(fin[:, 1].mean()), 2),
+                               "token exchange": round(float(fin[:, 2].mean()), 2)}
+    out["step_total"] = round(float((t[0, -1] - t[0, 0]) * 0.01), 2)
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +107,8 @@ def main() -> int:
     ap.add_argument("--workload", default="qwen3-0.6b-bf16-b1-p128-d128", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing sample")
+    ap.add_argument("--stage-trace", action="store_true",
+                    help="batch-1 workloads: add the resident decode kernel's per-stage wall-clock times of one step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no cross-GPU sharding or collectives); "
@@ -159,6 +195,10 @@ def main() -> int:
     torch.cuda.synchronize()
     del src, dst
 
+    stage_trace = None
+    if args.stage_trace and B == 1:
+        stage_trace = resident_stage_trace(model, nnc, shape, prompt)
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -193,6 +233,8 @@ def main() -> int:
                             for r in stats],
         "cpu_baseline": cpu,
     }
+    if stage_trace is not None:
+        out["decode_stage_trace_us"] = stage_trace
     print(json.dumps(out))
     return 0
 
