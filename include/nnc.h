@@ -190,6 +190,9 @@ typedef enum {
                                from each launch's size; else bit 0: every workgroup takes a long
                                and a short 64-token block, bit 1: two query heads per wave; results
                                are bit-identical for all (a wave's arithmetic per head is the same) */
+  NNC_OPT_FUSE_QK = 7,      /* 1 (default): per-stage decode passes of bf16 models do QK-norm, RoPE and
+                               the cache append inside the attention kernel (one kernel less per
+                               layer); 0: in a kernel of their own.  Bit-identical results */
   NNC_OPT_SPIN_LIMIT = 5,   /* polls after which a wait inside the resident kernel gives up (sets
                                the failure flag and lets every workgroup exit); 0 (default):
                                2^20, about a second.  A tiny value makes the give-up path testable */

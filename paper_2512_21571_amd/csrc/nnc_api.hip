@@ -113,6 +113,7 @@ struct nnc_model {
 
   bool opt_graph = true;
   int opt_prefill_exact = 0;  // 0: large blocks, pieces by length; 1: 21-token chunks, three pieces; 2: large blocks, two pieces
+  bool opt_fuse_qk = true;    // decode passes: QK-norm / RoPE / append inside the attention kernel
   int opt_prefill_attn = -1;  // forced launch shape of the prompt attention, -1 = by size
   int opt_prefill_tile = -1;  // forced block tile of the large-block prompt GEMMs, -1 = by size
   bool opt_persistent = true;
@@ -271,6 +272,7 @@ struct Pass {
   int32_t* next = nullptr;  // arg-max output (device) or NULL
   int grid_chunks = 1;
   double kv_rows = 0;       // sum over columns of (position + 1): cached rows attention must read
+  bool decode = false;      // every column is a different slot: QK-norm, RoPE and the cache append may run inside the attention kernel
 };
 
 nnc_status run_pass(nnc_model* m, const Pass& p) {
@@ -301,12 +303,15 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.out = m->qkv; a.ldo = Nqkv;
       RUN(FAM_GEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * n, launch_gemm(s, f32, EPI_STORE, a));
     }
-    RUN(FAM_QKROPE, n * Nqkv * 4.0, 0,
-        launch_qknorm_rope_append(s, f32, m->qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, n,
-                                  L.kc, L.vc, c.max_batch, c.max_seq, m->qsplit, nullptr, 0));
+    const bool fuse = p.decode && m->opt_fuse_qk && attn_partial_can_fuse(f32, nq, nkv);
+    const AttnFuseArgs fz{L.g_q, L.g_k, c.rms_eps, m->rope};
+    if (!fuse)
+      RUN(FAM_QKROPE, n * Nqkv * 4.0, 0,
+          launch_qknorm_rope_append(s, f32, m->qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, n,
+                                    L.kc, L.vc, c.max_batch, c.max_seq, m->qsplit, nullptr, 0));
     RUN(FAM_ATTN, p.kv_rows * 2.0 * Dkv * w, p.kv_rows * 4.0 * Dq,
         launch_attn_partial(s, f32, m->qkv, m->qsplit, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, cm, n,
-                            p.grid_chunks, m->partial, m->max_chunks));
+                            p.grid_chunks, m->partial, m->max_chunks, fuse ? &fz : nullptr));
     RUN(FAM_COMBINE, 0, 0,
         launch_attn_combine(s, f32, m->partial, m->max_chunks, nq, cm, n, m->Ap, nc, ns));
     {
@@ -411,6 +416,7 @@ nnc_status set_decode_state(nnc_model* m, const uint32_t* slots, const int32_t* 
 nnc_status greedy_step(nnc_model* m, uint32_t batch, int nsplit, int grid_chunks, bool allow_graph,
                        double kv_rows) {
   Pass p;
+  p.decode = true;
   p.kv_rows = kv_rows;
   p.ncols = (int)batch;
   p.nsplit = nsplit;
@@ -811,6 +817,12 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
       if (value < -1 || value > 3) return fail(NNC_E_ARG, "prefill attention shape must be -1 (automatic) or 0 .. 3");
       m->opt_prefill_attn = value;
       return NNC_OK;
+    case NNC_OPT_FUSE_QK:
+      m->opt_fuse_qk = value != 0;
+      // captured decode graphs contain one or the other set of kernels
+      for (auto& kv : m->graphs) (void)hipGraphExecDestroy(kv.second);
+      m->graphs.clear();
+      return NNC_OK;
     case NNC_OPT_SPIN_LIMIT:
       if (value < 0) return fail(NNC_E_ARG, "spin limit must be >= 0");
       m->mk_spin_limit = (unsigned)value;
@@ -1052,6 +1064,7 @@ nnc_status nnc_decode_step(nnc_model* m, const uint32_t* slots, const int32_t* t
   }
   if (logits_out) {
     Pass p;
+    p.decode = true;
     p.ncols = (int)batch;
     p.nsplit = nsplit;
     p.head_ncols = (int)batch;
@@ -1095,6 +1108,7 @@ nnc_status nnc_decode_greedy(nnc_model* m, const uint32_t* slots, const int32_t*
     const int gc = chunks_grid(max_pos + step);
     if (logits_out) {
       Pass p;
+      p.decode = true;
       p.ncols = (int)batch;
       p.nsplit = nsplit;
       p.head_ncols = (int)batch;
@@ -1123,6 +1137,7 @@ nnc_status nnc_decode_step_hidden(nnc_model* m, const uint32_t* slots, const flo
   if (nnc_status st = set_decode_state(m, slots, nullptr, batch, &max_pos, &kv_rows)) return st;
   HIP_TRY(launch_copy_rows(m->stream, x, m->x, (size_t)batch * m->H()));
   Pass p;
+  p.decode = true;
   p.kv_rows = kv_rows;
   p.ncols = (int)batch;
   p.nsplit = decode_nsplit(m, batch);

@@ -96,10 +96,19 @@ hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq
                                      const float2* rope, const ColMap& cm, int ncols, void* kc,
                                      void* vc, uint32_t max_batch, uint32_t max_seq, void* qsplit, void* vt,
                                      uint32_t vt_stride);
+// Fused QK-norm + RoPE + append inside the batched decode attention (bf16, at most 8 query heads
+// per kv head, every column a different slot): what the kernel needs besides the raw projection.
+struct AttnFuseArgs {
+  const float* gq;
+  const float* gk;
+  float eps;
+  const float2* rope;
+};
+bool attn_partial_can_fuse(bool f32, int nq, int nkv);
 hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, const void* qsplit, int nq, int nkv,
-                               const void* kc, const void* vc, uint32_t max_batch, uint32_t max_seq,
-                               const ColMap& cm, int ncols, int grid_chunks, float* partial,
-                               int max_chunks);
+                               void* kc, void* vc, uint32_t max_batch, uint32_t max_seq, const ColMap& cm,
+                               int ncols, int grid_chunks, float* partial, int max_chunks,
+                               const AttnFuseArgs* fuse);
 hipError_t launch_attn_combine(hipStream_t s, bool f32, const float* partial, int max_chunks, int nq,
                                const ColMap& cm, int ncols, void* Op, int NC, int nsplit);
 

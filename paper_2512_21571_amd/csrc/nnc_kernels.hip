@@ -772,15 +772,32 @@ __global__ __launch_bounds__(256) void k_attn_partial(
 //                 (row stride 66 words: conflict-free), B = the weights in three pieces.
 // Replaces 8 multiply-adds per cached element and head on the vector ALU, which bounded the
 // vector version at about half of the HBM rate.
+// FUSED (decode passes: every column is a different slot, G <= 8): the workgroup also does what
+// k_qknorm_rope_append does for its column and kv head -- QK-norm and RoPE of the G query heads
+// from the raw projection output (every chunk's workgroup repeats that: 128 values per head),
+// and, in the workgroup whose chunk holds the new position, of the new K row, which it appends
+// to the cache together with the V row and patches into its own operands (the row is not in the
+// cache when the loads are issued).  One kernel less per layer.
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-__global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restrict__ qsplit, int nq, int nkv,
-                                                         const uint16_t* __restrict__ kc,
-                                                         const uint16_t* __restrict__ vc, uint32_t max_seq, ColMap cm,
+struct AttnFuse {
+  const float* qkv;   // [columns][(nq + 2 nkv) * 128] raw q | k | v
+  const float* gq;    // QK-norm gains
+  const float* gk;
+  float eps;
+  const float2* rope;
+};
+template <bool FUSED>
+__global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restrict__ qsplit, AttnFuse fz, int nq,
+                                                         int nkv, uint16_t* __restrict__ kc,
+                                                         uint16_t* __restrict__ vc, uint32_t max_seq, ColMap cm,
                                                          float* __restrict__ partial, int max_chunks) {
   constexpr int VS = 66;  // row stride of the staged V chunk in 32-bit words (128 bf16 + pad)
   __shared__ uint32_t Vs[ATT_CHUNK][VS];
   __shared__ float sc[16][ATT_CHUNK];  // scores per head
-  __shared__ __attribute__((aligned(16))) uint16_t pw[3][16][ATT_CHUNK];  // softmax weights as three bf16 pieces
+  // softmax weights as three bf16 pieces; before the scores exist the same bytes hold the query
+  // pieces of the fused variant ([3][8][128]), which every wave has in registers by then
+  __shared__ __attribute__((aligned(16))) uint16_t pw[3][16][ATT_CHUNK];
+  __shared__ __attribute__((aligned(16))) uint16_t knew[128], vnew[128];
   __shared__ float sm_m[16], sm_l[16];
   const int kvh = blockIdx.y, col = blockIdx.z;
   const int G = nq / nkv, head0 = kvh * G;
@@ -792,34 +809,86 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
   const int c16 = lane & 15, g = lane >> 4;
   const size_t base = ((size_t)slot * nkv + kvh) * max_seq * 128;
 
-  // rows past `pos` re-read row `pos`: valid memory, finite values, masked / weight 0 below
+  // rows past the last cached one re-read it: valid memory, finite values, masked / weight 0
+  // below (fused: row `pos` is not cached yet; it is patched in from the role waves)
+  const uint32_t jlast = FUSED ? (pos > 0 ? pos - 1 : 0) : pos;
+  const bool owns_new = pos - j0 < (uint32_t)ATT_CHUNK;
   uint2 vreg[4][2];
   u32x4_t kf[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const uint32_t j = min(j0 + (uint32_t)((tid >> 4) + 16 * i), pos);
+    const uint32_t j = min(j0 + (uint32_t)((tid >> 4) + 16 * i), jlast);
     const uint4 v = *reinterpret_cast<const uint4*>(vc + base + (size_t)j * 128 + (tid & 15) * 8);
     vreg[i][0] = make_uint2(v.x, v.y);
     vreg[i][1] = make_uint2(v.z, v.w);
   }
   {
     // K fragments: A-operand row c16 = position j0 + wave * 16 + c16, 8 dims per lane and k step
-    const uint32_t jk = min(j0 + (uint32_t)(wave * 16 + c16), pos);
+    const uint32_t jk = min(j0 + (uint32_t)(wave * 16 + c16), jlast);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
       kf[ks] = *reinterpret_cast<const u32x4_t*>(kc + base + (size_t)jk * 128 + ks * 32 + g * 8);
+  }
+  uint16_t(*qp)[8][128] = reinterpret_cast<uint16_t(*)[8][128]>(&pw[0][0][0]);
+  if constexpr (FUSED) {
+    // roles 0 .. G-1: query heads; G: the new K row; G + 1: the new V row (same arithmetic, in
+    // the same order, as k_qknorm_rope_append)
+    const int ld = (nq + 2 * nkv) * 128;
+    const float* row = fz.qkv + (size_t)col * ld;
+    for (int role = wave; role < G + 2; role += 4) {
+      if (role >= G && !owns_new) continue;
+      const float* p = role < G ? row + (size_t)(head0 + role) * 128
+                                : row + (size_t)(nq + (role == G ? 0 : nkv) + kvh) * 128;
+      float a = p[lane], b = p[lane + 64];
+      if (role <= G) {
+        const float ss = wave_sum(a * a + b * b);
+        const float r = 1.0f / sqrtf(ss * (1.0f / 128.0f) + fz.eps);
+        const float* gg = role < G ? fz.gq : fz.gk;
+        a = a * r * gg[lane];
+        b = b * r * gg[lane + 64];
+        const float2 cs = fz.rope[(size_t)pos * 64 + lane];
+        const float ra = a * cs.x - b * cs.y;
+        const float rb = b * cs.x + a * cs.y;
+        a = ra;
+        b = rb;
+      }
+      if (role < G) {
+        uint32_t pa[3], pb[3];
+        split_bf16(a, 3, pa);
+        split_bf16(b, 3, pb);
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc) {
+          qp[pc][role][lane] = (uint16_t)pa[pc];
+          qp[pc][role][lane + 64] = (uint16_t)pb[pc];
+        }
+      } else {
+        const uint16_t ha = (uint16_t)bf16_bits(a), hb = (uint16_t)bf16_bits(b);
+        uint16_t* dst = (role == G ? kc : vc) + base + (size_t)pos * 128;
+        dst[lane] = ha;
+        dst[lane + 64] = hb;
+        uint16_t* keep = role == G ? knew : vnew;
+        keep[lane] = ha;
+        keep[lane + 64] = hb;
+      }
+    }
+    __syncthreads();
+    if (j0 + (uint32_t)(wave * 16 + c16) == pos) {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) kf[ks] = *reinterpret_cast<const u32x4_t*>(&knew[ks * 32 + g * 8]);
+    }
   }
 
   // query fragments: operand column c16 = head head0 + c16 (zero beyond G), three pieces as
   // written by k_qknorm_rope_append
   u32x4_t qf[4][3];
   {
-    const uint16_t* qp = qsplit + ((size_t)col * nq + head0 + min(c16, G - 1)) * 3 * 128 + g * 8;
+    const uint16_t* qg = qsplit + ((size_t)col * nq + head0 + min(c16, G - 1)) * 3 * 128 + g * 8;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int pc = 0; pc < 3; ++pc) {
-        const u32x4_t t = *reinterpret_cast<const u32x4_t*>(qp + pc * 128 + ks * 32);
+        const u32x4_t t = FUSED ? *reinterpret_cast<const u32x4_t*>(&qp[pc][min(c16, G - 1)][ks * 32 + g * 8])
+                                : *reinterpret_cast<const u32x4_t*>(qg + pc * 128 + ks * 32);
         qf[ks][pc] = c16 < G ? t : u32x4_t{0u, 0u, 0u, 0u};
       }
   }
@@ -843,10 +912,16 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       uint2* d = reinterpret_cast<uint2*>(&Vs[(tid >> 4) + 16 * i][(tid & 15) * 4]);
-      d[0] = vreg[i][0];
-      d[1] = vreg[i][1];
+      if (FUSED && j0 + (uint32_t)((tid >> 4) + 16 * i) == pos) {
+        const uint2* nv = reinterpret_cast<const uint2*>(&vnew[(tid & 15) * 8]);
+        d[0] = nv[0];
+        d[1] = nv[1];
+      } else {
+        d[0] = vreg[i][0];
+        d[1] = vreg[i][1];
+      }
     }
-    __syncthreads();
+    __syncthreads();  // (fused: every wave holds its query fragments in registers; the LDS behind them becomes pw)
 
     // chunk max, weights exp(s - max), chunk sum: one wave per head
     for (int h = wave; h < G; h += 4) {
@@ -912,16 +987,29 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
   }
 }
 
+bool attn_partial_can_fuse(bool f32, int nq, int nkv) { return !f32 && nq / nkv <= 8; }
+
+// fuse != NULL: raw projection output, gains and rotary table for the fused variant (the caller
+// then does not launch k_qknorm_rope_append; columns must be different slots).
 hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, const void* qsplit, int nq, int nkv,
-                               const void* kc, const void* vc, uint32_t max_batch, uint32_t max_seq,
+                               void* kc, void* vc, uint32_t max_batch, uint32_t max_seq,
                                const ColMap& cm, int ncols, int grid_chunks, float* partial,
-                               int max_chunks) {
+                               int max_chunks, const AttnFuseArgs* fuse) {
   (void)max_batch;
   const int G = nq / nkv;
+  if (fuse) {
+    if (!attn_partial_can_fuse(f32, nq, nkv) || cm.row0 != 0 || !cm.st) return hipErrorInvalidValue;
+    dim3 grid(grid_chunks, nkv, ncols);
+    const AttnFuse fz{qkv, fuse->gq, fuse->gk, fuse->eps, fuse->rope};
+    k_attn_partial_mc<true><<<grid, 256, 0, s>>>(nullptr, fz, nq, nkv, static_cast<uint16_t*>(kc),
+                                                 static_cast<uint16_t*>(vc), max_seq, cm, partial, max_chunks);
+    return hipGetLastError();
+  }
   if (!f32 && G <= 16 && qsplit && cm.row0 == 0) {
     dim3 grid(grid_chunks, nkv, ncols);
-    k_attn_partial_mc<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(qsplit), nq, nkv, static_cast<const uint16_t*>(kc),
-                                           static_cast<const uint16_t*>(vc), max_seq, cm, partial, max_chunks);
+    k_attn_partial_mc<false><<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(qsplit), AttnFuse{}, nq, nkv,
+                                                  static_cast<uint16_t*>(kc), static_cast<uint16_t*>(vc), max_seq, cm,
+                                                  partial, max_chunks);
     return hipGetLastError();
   }
   const int GH = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;

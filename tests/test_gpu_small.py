@@ -215,6 +215,33 @@ def test_large_block_prefill_every_attention_shape(nnc, n, attn):
     assert int(ng.item()) == no
 
 
+@pytest.mark.parametrize("batch", [1, 3, 16])
+def test_fused_qk_norm_rope_append_equals_separate_kernel(nnc, batch):
+    """Per-stage decode passes with QK-norm / RoPE / cache append inside the attention kernel and
+    in a kernel of their own: the same arithmetic in the same order, so the same bits -- over
+    steps that cross a 64-position chunk boundary, ragged contexts, eager and captured."""
+    print(f"case: fused vs separate QK-norm/RoPE/append, B={batch}", flush=True)
+    shape = SMALL_G4
+    runs = []
+    for fused in (0, 1):
+        g, _ = _pair(nnc, shape, batch, 260)
+        g.set_option(nnc.OPT_PERSISTENT, 0)
+        g.set_option(nnc.OPT_FUSE_QK, fused)
+        firsts = []
+        for s in range(batch):
+            _, nx = g.prefill(s, synth.tokens(55 + 9 * s, shape.vocab, stream=40 + s))
+            firsts.append(int(nx.item()))
+        slots = list(range(batch))
+        toks, logits = g.decode_greedy(slots, firsts, 14, want_logits=True)
+        lg, ng = g.decode_step(slots, toks[-1].cpu().numpy().tolist())
+        k = g.kv_read(1, 0, 0, 0, 55 + 15)
+        v = g.kv_read(1, 0, 1, 0, 55 + 15)
+        runs.append((toks.cpu().numpy().copy(), logits.cpu().numpy().copy(), lg.cpu().numpy().copy(),
+                     k.cpu().numpy().copy(), v.cpu().numpy().copy()))
+    for a, b in zip(runs[0], runs[1]):
+        assert np.array_equal(a, b)
+
+
 def test_large_block_prefill_two_pieces_at_any_length(nnc):
     print("case: large-block prefill, 600 tokens, two pieces forced", flush=True)
     shape = SMALL_G4
