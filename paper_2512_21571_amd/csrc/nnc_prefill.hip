@@ -445,25 +445,45 @@ __global__ __launch_bounds__(256) void k_rmsnorm_frag(float* __restrict__ x, con
     }
     __syncthreads();  // the folded row is read back below by other threads of the workgroup
   }
+  // the row stays in registers between the sum of squares and the conversion: groups of 8
+  // consecutive elements (one 16-byte fragment element each), up to four per thread
+  constexpr int MAXG = 4;
+  float v[MAXG][8];
   float ss = 0.f;
-  for (int i = threadIdx.x; i < H; i += 256) ss += xr[i] * xr[i];
+#pragma unroll
+  for (int j = 0; j < MAXG; ++j) {
+    const int kg = threadIdx.x + 256 * j;
+    if (kg < H / 8) {
+      const float4 a0 = *reinterpret_cast<const float4*>(xr + kg * 8), a1 = *reinterpret_cast<const float4*>(xr + kg * 8 + 4);
+      v[j][0] = a0.x; v[j][1] = a0.y; v[j][2] = a0.z; v[j][3] = a0.w;
+      v[j][4] = a1.x; v[j][5] = a1.y; v[j][6] = a1.z; v[j][7] = a1.w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += v[j][e] * v[j][e];
+    }
+  }
   ss = wave_sum(ss);
   if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = ss;
   __syncthreads();
   const float r = 1.0f / sqrtf(((sm[0] + sm[1]) + (sm[2] + sm[3])) / (float)H + eps);
-  for (int kg = threadIdx.x; kg < H / 8; kg += 256) {
-    float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = xr[kg * 8 + e] * r * gain[kg * 8 + e];
-    for (int pc = 0; pc < pieces; ++pc) {
-      uint32_t h[4];
+  for (int j = 0; j < MAXG; ++j) {
+    const int kg = threadIdx.x + 256 * j;
+    if (kg < H / 8) {
+      const float4 g0 = *reinterpret_cast<const float4*>(gain + kg * 8), g1 = *reinterpret_cast<const float4*>(gain + kg * 8 + 4);
+      const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+      float y[8];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        h[e] = bf16_pack2(v[2 * e], v[2 * e + 1]);
-        v[2 * e] -= bf16_lo(h[e]);
-        v[2 * e + 1] -= bf16_hi(h[e]);
+      for (int e = 0; e < 8; ++e) y[e] = v[j][e] * r * gg[e];
+      for (int pc = 0; pc < pieces; ++pc) {
+        uint32_t h[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          h[e] = bf16_pack2(y[2 * e], y[2 * e + 1]);
+          y[2 * e] -= bf16_lo(h[e]);
+          y[2 * e + 1] -= bf16_hi(h[e]);
+        }
+        out[pc * piece_stride + (size_t)(kg >> 2) * 64 + 16 * (kg & 3)] = uint4{h[0], h[1], h[2], h[3]};
       }
-      out[pc * piece_stride + (size_t)(kg >> 2) * 64 + 16 * (kg & 3)] = uint4{h[0], h[1], h[2], h[3]};
     }
   }
 }
@@ -471,7 +491,7 @@ __global__ __launch_bounds__(256) void k_rmsnorm_frag(float* __restrict__ x, con
 hipError_t launch_rmsnorm_frag(hipStream_t s, float* x, const float* part, int nparts, long part_stride,
                                const float* gain, int H, float eps, int n_rows, int token_tiles, int pieces,
                                void* Xf) {
-  if (H % 32 || nparts < 0 || (nparts > 0 && !part) || n_rows <= 0) return hipErrorInvalidValue;
+  if (H % 32 || H > 8192 || nparts < 0 || (nparts > 0 && !part) || n_rows <= 0) return hipErrorInvalidValue;
   k_rmsnorm_frag<<<token_tiles * 16, 256, 0, s>>>(x, part, nparts, part_stride, gain, H, eps, n_rows, pieces, Xf);
   return hipGetLastError();
 }
