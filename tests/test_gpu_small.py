@@ -242,6 +242,47 @@ def test_fused_qk_norm_rope_append_equals_separate_kernel(nnc, batch):
         assert np.array_equal(a, b)
 
 
+def test_random_requests_against_oracle(nnc):
+    """Seeded random requests (shape, batch, ragged prompt lengths across the block and piece
+    boundaries, decode steps, forced kernel shapes, fused / separate kernels, resident / per-stage
+    decode) against the oracle: logits within tolerance, every greedy token equal."""
+    import random
+    rng = random.Random(20251)
+    for case in range(14):
+        shape = rng.choice([SMALL_BF16, SMALL_G4])
+        batch = rng.choice([1, 1, 2, 3, 5])
+        n = rng.choice([rng.randint(1, 70), rng.randint(60, 520), rng.randint(513, 900)])
+        steps = rng.randint(1, 6)
+        tile, attn = rng.choice([-1, -1, 0, 1, 2, 3, 4]), rng.choice([-1, -1, 0, 1, 2, 3])
+        fuse, pers = rng.choice([0, 1]), rng.choice([0, 1])
+        print(f"case: random request {case}: {shape.name} B={batch} n={n} steps={steps} tile={tile} "
+              f"attn={attn} fuse={fuse} resident={pers}", flush=True)
+        g, o = _pair(nnc, shape, batch, n + steps + 8, exact_prefill=False)
+        g.set_option(nnc.OPT_PREFILL_TILE, tile)
+        g.set_option(nnc.OPT_PREFILL_ATTN, attn)
+        g.set_option(nnc.OPT_FUSE_QK, fuse)
+        g.set_option(nnc.OPT_PERSISTENT, pers)
+        fl = oracle_flags(shape)
+        firsts = []
+        for b in range(batch):
+            nb = max(1, n - 7 * b)
+            toks = synth.tokens(nb, shape.vocab, stream=1000 * case + b)
+            lg, ng = g.prefill(b, toks)
+            lo, no = oracle_prefill_like_library(o, b, toks, shape)
+            one_piece = any(pc == 1 for _, _, pc in prefill_blocks(nb))
+            _check_logits(shape, lg, lo, BF16_ABS_PROMPT if one_piece else BF16_ABS_TIGHT)
+            assert int(ng.item()) == no
+            firsts.append(no)
+        toks_g, logits_g = g.decode_greedy(list(range(batch)), firsts, steps, want_logits=True)
+        cur = list(firsts)
+        for s_ in range(steps):
+            for b in range(batch):
+                lo, nx = o.step_token(b, cur[b], fl)
+                _check_logits(shape, logits_g[s_, b], lo, BF16_ABS_PROMPT)
+                assert int(toks_g[s_, b].item()) == nx
+                cur[b] = nx
+
+
 def test_large_block_prefill_two_pieces_at_any_length(nnc):
     print("case: large-block prefill, 600 tokens, two pieces forced", flush=True)
     shape = SMALL_G4
