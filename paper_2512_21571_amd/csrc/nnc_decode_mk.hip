@@ -42,6 +42,12 @@ namespace nnc {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// Weights are read once per step: a streaming (non-temporal) load keeps them from displacing
+// the operands and exchange words that every workgroup re-reads from L2.
+__device__ __forceinline__ uint4 ldw(const uint4* p) {
+  const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return uint4{t.x, t.y, t.z, t.w};
+}
 typedef unsigned long long u64;
 
 namespace {
@@ -204,7 +210,7 @@ __device__ __forceinline__ void pf_issue(Pf<RT>& pf, const uint4* __restrict__ W
   for (int j = 0; j < MK_PF * RT; ++j) {
     const int kt = kt_begin + wave + MK_WAVES * (j / RT);
     const int rt = j % RT;
-    pf.v[j] = kt < kt_end ? W[((tile0 + rt) * KT + kt) * 64 + lane] : uint4{0, 0, 0, 0};
+    pf.v[j] = kt < kt_end ? ldw(&W[((tile0 + rt) * KT + kt) * 64 + lane]) : uint4{0, 0, 0, 0};
   }
 }
 
@@ -251,7 +257,7 @@ __device__ __forceinline__ void gemm_unit(Smem& sm, const uint4* __restrict__ W,
       const int kt = kt0 + MK_WAVES * u;
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
-        av[u][rt] = kt < kt_end ? W[((tile0 + rt) * KT + kt) * 64 + lane] : uint4{0, 0, 0, 0};
+        av[u][rt] = kt < kt_end ? ldw(&W[((tile0 + rt) * KT + kt) * 64 + lane]) : uint4{0, 0, 0, 0};
     }
     consume(kt0, av);
   }
