@@ -476,12 +476,30 @@ static hipError_t gemm_dispatch_ncb(hipStream_t s, const GemmArgs& a) {
 // consumer (k_rmsnorm_pack / k_fold_residual) adds the slices in a fixed order, so
 // results do not depend on scheduling.  With more than 16 operand columns (batched decode)
 // every workgroup re-reads the whole operand from L2, all of them the same lines at about the
-// same time; twice the row tiles per workgroup halve that traffic.
+// same time; twice the row tiles per workgroup halve that traffic, and a launch takes them
+// unless that leaves the last round of workgroups over the CUs clearly emptier (8B gate|up:
+// 768 workgroups of two tile pairs fill three rounds, 384 of four only 1.5; 1.7B QKV: 256
+// workgroups of one tile rather than 128 of two; the LM head has thousands either way).
+static int cu_count() {
+  static const int n = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      v = 256;
+    return v;
+  }();
+  return n;
+}
+
 template <bool F32, int EPI, int RT>
 static hipError_t gemm_dispatch_rt(hipStream_t s, const GemmArgs& a) {
   const int ncb = (a.ncols + 15) / 16;
-  if (ncb >= 2 && ncb <= 3 && a.n_tiles % (2 * RT) == 0 && a.n_tiles / (2 * RT) >= 128)
-    return gemm_dispatch_ncb<F32, EPI, 2 * RT>(s, a);
+  if (ncb >= 2 && ncb <= 3 && a.n_tiles % (2 * RT) == 0) {
+    const int ks = (a.KT + a.kts_per_split - 1) / a.kts_per_split, cus = cu_count();
+    auto fullness = [&](int wgs) { return (double)wgs / ((double)((wgs + cus - 1) / cus) * cus); };
+    if (fullness(a.n_tiles / (2 * RT) * ks) >= fullness(a.n_tiles / RT * ks) - 0.05)
+      return gemm_dispatch_ncb<F32, EPI, 2 * RT>(s, a);
+  }
   return gemm_dispatch_ncb<F32, EPI, RT>(s, a);
 }
 
