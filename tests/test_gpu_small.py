@@ -242,6 +242,35 @@ def test_fused_qk_norm_rope_append_equals_separate_kernel(nnc, batch):
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("shape,fuse", [(SMALL_BF16, 1), (SMALL_G4, 0)], ids=["small-bf16-fused", "small-g4-separate"])
+def test_batched_decode_at_long_contexts(nnc, shape, fuse):
+    """Three slots of one batch at very different lengths (100, 2040 and 4090 cached positions,
+    i.e. 2 to 65 chunks of the decode attention, the two long ones crossing 2048 and 4096 while
+    decoding); logits and greedy tokens are checked against the oracle at every step, prompt
+    included (fp32-grade prompt path, which runs the same attention kernel)."""
+    print(f"case: long-context batched decode {shape.name} fuse={fuse}", flush=True)
+    lens = [2040, 4090, 100]
+    g, o = _pair(nnc, shape, 3, 4120, exact_prefill=True)
+    g.set_option(nnc.OPT_FUSE_QK, fuse)
+    fl = oracle_flags(shape)
+    cur = []
+    for b, n in enumerate(lens):
+        toks = synth.tokens(n, shape.vocab, stream=40 + b)
+        lg, ng = g.prefill(b, toks)
+        lo, no = o.prefill(b, toks, fl)
+        _check_logits(shape, lg, lo)
+        assert int(ng.item()) == no
+        cur.append(no)
+    for step in range(14):                         # slot 0 crosses 2048, slot 1 crosses 4096
+        lg, ng = g.decode_step([0, 1, 2], cur)
+        for b in range(3):
+            lo, no = o.step_token(b, cur[b], fl)
+            _check_logits(shape, lg[b], lo)
+            assert int(ng[b].item()) == no, (step, b)
+            cur[b] = no
+    assert g.slot_len(1) == 4104
+
+
 def test_random_requests_against_oracle(nnc):
     """Seeded random requests (shape, batch, ragged prompt lengths across the block and piece
     boundaries, decode steps, forced kernel shapes, fused / separate kernels, resident / per-stage
