@@ -243,7 +243,7 @@ def test_fused_qk_norm_rope_append_equals_separate_kernel(nnc, batch):
 
 
 @pytest.mark.parametrize("shape,fuse", [(SMALL_BF16, 1), (SMALL_G4, 0)], ids=["small-bf16-fused", "small-g4-separate"])
-def test_batched_decode_at_long_contexts(nnc, shape, fuse):
+def test_batched_decode_mixed_lengths_up_to_4k(nnc, shape, fuse):
     """Three slots of one batch at very different lengths (100, 2040 and 4090 cached positions,
     i.e. 2 to 65 chunks of the decode attention, the two long ones crossing 2048 and 4096 while
     decoding); logits and greedy tokens are checked against the oracle at every step, prompt
