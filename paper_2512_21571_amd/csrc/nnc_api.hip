@@ -272,6 +272,7 @@ struct Pass {
   int32_t* next = nullptr;  // arg-max output (device) or NULL
   int grid_chunks = 1;
   double kv_rows = 0;       // sum over columns of (position + 1): cached rows attention must read
+  bool one_slot = false;    // the columns are consecutive positions of one slot (prompt chunk)
   bool decode = false;      // every column is a different slot: QK-norm, RoPE and the cache append may run inside the attention kernel
 };
 
@@ -311,7 +312,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
                                     L.kc, L.vc, c.max_batch, c.max_seq, m->qsplit, nullptr, 0));
     RUN(FAM_ATTN, p.kv_rows * 2.0 * Dkv * w, p.kv_rows * 4.0 * Dq,
         launch_attn_partial(s, f32, m->qkv, m->qsplit, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, cm, n,
-                            p.grid_chunks, m->partial, m->max_chunks, fuse ? &fz : nullptr));
+                            p.grid_chunks, m->partial, m->max_chunks, fuse ? &fz : nullptr, p.one_slot));
     RUN(FAM_COMBINE, 0, 0,
         launch_attn_combine(s, f32, m->partial, m->max_chunks, nq, cm, n, m->Ap, nc, ns));
     {
@@ -1008,6 +1009,7 @@ static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tok
     p.nsplit = nsplit;
     p.tokens = tokens != nullptr;
     p.grid_chunks = chunks_grid(pos[nc - 1]);
+    p.one_slot = true;
     for (uint32_t i = 0; i < nc; ++i) p.kv_rows += pos[i] + 1.0;
     const bool last = t0 + nc == n;
     if (!tokens)

@@ -108,7 +108,7 @@ bool attn_partial_can_fuse(bool f32, int nq, int nkv);
 hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, const void* qsplit, int nq, int nkv,
                                void* kc, void* vc, uint32_t max_batch, uint32_t max_seq, const ColMap& cm,
                                int ncols, int grid_chunks, float* partial, int max_chunks,
-                               const AttnFuseArgs* fuse);
+                               const AttnFuseArgs* fuse, bool one_slot = false);
 hipError_t launch_attn_combine(hipStream_t s, bool f32, const float* partial, int max_chunks, int nq,
                                const ColMap& cm, int ncols, void* Op, int NC, int nsplit);
 

@@ -1005,6 +1005,138 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
   }
 }
 
+// Prompt chunks (the columns are consecutive positions of one slot): the same arithmetic per
+// (column, head) as k_attn_partial_mc, but one workgroup serves every column from one read of its
+// cache chunk -- the (column, head) pairs are the operand columns, sixteen at a time.
+__global__ __launch_bounds__(256) void k_attn_partial_shared(const uint16_t* __restrict__ qsplit, int nq, int nkv,
+                                                             const uint16_t* __restrict__ kc,
+                                                             const uint16_t* __restrict__ vc, uint32_t max_seq,
+                                                             ColMap cm, int ncols, float* __restrict__ partial,
+                                                             int max_chunks) {
+  constexpr int VS = 66;
+  __shared__ uint32_t Vs[ATT_CHUNK][VS];
+  __shared__ float sc[16][ATT_CHUNK];
+  __shared__ __attribute__((aligned(16))) uint16_t pw[3][16][ATT_CHUNK];
+  __shared__ float sm_m[16], sm_l[16];
+  const int kvh = blockIdx.y, chunk = blockIdx.x;
+  const int G = nq / nkv, head0 = kvh * G;
+  const uint32_t pos0 = col_pos(cm, 0), slot = col_slot(cm, 0);  // column c stands for position pos0 + c
+  const uint32_t pos_last = pos0 + (uint32_t)ncols - 1;  // every column's row is in the cache already
+  const uint32_t j0 = (uint32_t)chunk * ATT_CHUNK;
+  if (j0 > pos_last) return;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int c16 = lane & 15, g = lane >> 4;
+  const size_t base = ((size_t)slot * nkv + kvh) * max_seq * 128;
+  // rows past the last cached one re-read it: valid memory, finite values, masked below
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t j = min(j0 + (uint32_t)((tid >> 4) + 16 * i), pos_last);
+    const uint4 v = *reinterpret_cast<const uint4*>(vc + base + (size_t)j * 128 + (tid & 15) * 8);
+    uint2* d = reinterpret_cast<uint2*>(&Vs[(tid >> 4) + 16 * i][(tid & 15) * 4]);
+    d[0] = make_uint2(v.x, v.y);
+    d[1] = make_uint2(v.z, v.w);
+  }
+  u32x4_t kf[4];
+  {
+    const uint32_t jk = min(j0 + (uint32_t)(wave * 16 + c16), pos_last);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      kf[ks] = *reinterpret_cast<const u32x4_t*>(kc + base + (size_t)jk * 128 + ks * 32 + g * 8);
+  }
+  const int nops = ncols * G;  // operand columns: (column, head of this kv head)
+  for (int op0 = 0; op0 < nops; op0 += 16) {
+    const int op = op0 + c16;
+    const bool valid = op < nops;
+    const int col = valid ? op / G : ncols - 1, hd = valid ? op - col * G : 0;
+    const uint32_t pos = pos0 + (uint32_t)col;
+    u32x4_t qf[4][3];
+    {
+      const uint16_t* qg = qsplit + ((size_t)col * nq + head0 + hd) * 3 * 128 + g * 8;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc) {
+          const u32x4_t t = *reinterpret_cast<const u32x4_t*>(qg + pc * 128 + ks * 32);
+          qf[ks][pc] = valid ? t : u32x4_t{0u, 0u, 0u, 0u};
+        }
+    }
+    f32x4 sv = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc)
+        sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[ks]),
+                                                     __builtin_bit_cast(bf16x8, qf[ks][pc]), sv, 0, 0, 0);
+    // lane (c16 = operand column, g): positions wave * 16 + g * 4 + i of the chunk
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int jl = wave * 16 + g * 4 + i;
+      sc[c16][jl] = valid && j0 + (uint32_t)jl <= pos ? sv[i] * 0.08838834764831845f : -INFINITY;
+    }
+    __syncthreads();  // scores (and, the first time round, the staged V rows) are in LDS
+
+    // chunk max, weights exp(s - max), chunk sum: one wave per operand column; a column whose
+    // position lies before this chunk has no valid score (weights 0, nothing stored)
+    for (int r = wave; r < 16; r += 4) {
+      const float x = sc[r][lane];
+      const float m = wave_max(x);
+      const float w = m == -INFINITY ? 0.f : expf(x - m);
+      float rr = w;
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc) {
+        const uint32_t b = bf16_bits(rr);
+        pw[pc][r][lane] = (uint16_t)b;
+        rr -= bf16_to_f32(b);
+      }
+      const float l = wave_sum(w);
+      if (lane == 0) {
+        sm_m[r] = m;
+        sm_l[r] = l;
+      }
+    }
+    __syncthreads();
+
+    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      u32x4_t pf[3];
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc) pf[pc] = *reinterpret_cast<const u32x4_t*>(&pw[pc][c16][half * 32 + g * 8]);
+#pragma unroll
+      for (int dtl = 0; dtl < 2; ++dtl) {
+        const int dim = (wave * 2 + dtl) * 16 + c16;
+        uint32_t b[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t two = Vs[half * 32 + g * 8 + e][dim >> 1];
+          b[e] = (dim & 1) ? (two >> 16) : (two & 0xffffu);
+        }
+        const u32x4_t vf = u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc)
+          acc[dtl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
+                                                             __builtin_bit_cast(bf16x8, pf[pc]), acc[dtl], 0, 0, 0);
+      }
+    }
+    if (valid && j0 <= pos) {
+      float* rec = partial + (((size_t)col * nq + head0 + hd) * max_chunks + chunk) * 132;
+#pragma unroll
+      for (int dtl = 0; dtl < 2; ++dtl)
+        *reinterpret_cast<float4*>(rec + (wave * 2 + dtl) * 16 + g * 4) =
+            make_float4(acc[dtl][0], acc[dtl][1], acc[dtl][2], acc[dtl][3]);
+    }
+    if (tid < 16 && op0 + tid < nops) {
+      const int c2 = (op0 + tid) / G, h2 = (op0 + tid) - c2 * G;
+      if (j0 <= pos0 + (uint32_t)c2) {
+        float* rec = partial + (((size_t)c2 * nq + head0 + h2) * max_chunks + chunk) * 132;
+        rec[128] = sm_m[tid];
+        rec[129] = sm_l[tid];
+      }
+    }
+    __syncthreads();  // scores, weights and row statistics have been read
+  }
+}
+
 bool attn_partial_can_fuse(bool f32, int nq, int nkv) { return !f32 && nq / nkv <= 8; }
 
 // fuse != NULL: raw projection output, gains and rotary table for the fused variant (the caller
@@ -1012,7 +1144,7 @@ bool attn_partial_can_fuse(bool f32, int nq, int nkv) { return !f32 && nq / nkv 
 hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, const void* qsplit, int nq, int nkv,
                                void* kc, void* vc, uint32_t max_batch, uint32_t max_seq,
                                const ColMap& cm, int ncols, int grid_chunks, float* partial,
-                               int max_chunks, const AttnFuseArgs* fuse) {
+                               int max_chunks, const AttnFuseArgs* fuse, bool one_slot) {
   (void)max_batch;
   const int G = nq / nkv;
   if (fuse) {
@@ -1021,6 +1153,14 @@ hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, const 
     const AttnFuse fz{qkv, fuse->gq, fuse->gk, fuse->eps, fuse->rope};
     k_attn_partial_mc<true><<<grid, 256, 0, s>>>(nullptr, fz, nq, nkv, static_cast<uint16_t*>(kc),
                                                  static_cast<uint16_t*>(vc), max_seq, cm, partial, max_chunks);
+    return hipGetLastError();
+  }
+  if (!f32 && G <= 16 && qsplit && cm.row0 == 0 && one_slot && ncols > 1) {
+    // prompt chunk: consecutive positions of one slot share each read of the cache
+    dim3 grid(grid_chunks, nkv);
+    k_attn_partial_shared<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(qsplit), nq, nkv,
+                                               static_cast<const uint16_t*>(kc), static_cast<const uint16_t*>(vc),
+                                               max_seq, cm, ncols, partial, max_chunks);
     return hipGetLastError();
   }
   if (!f32 && G <= 16 && qsplit && cm.row0 == 0) {
