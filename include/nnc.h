@@ -193,6 +193,12 @@ typedef enum {
   NNC_OPT_FUSE_QK = 7,      /* 1 (default): per-stage decode passes of bf16 models do QK-norm, RoPE and
                                the cache append inside the attention kernel (one kernel less per
                                layer); 0: in a kernel of their own.  Bit-identical results */
+  NNC_OPT_TAIL_OVERLAP = 8, /* 1 (default): the fp32-grade pass over the last tokens of a long prompt is
+                               enqueued on a second stream of the library's own and runs beside the
+                               prompt's last block, each of its layers waiting (event) for that
+                               layer's cache rows; the model's stream waits for it before the call
+                               returns to the caller's later work.  0: it follows the block on the
+                               model's stream.  Bit-identical results */
   NNC_OPT_SPIN_LIMIT = 5,   /* polls after which a wait inside the resident kernel gives up (sets
                                the failure flag and lets every workgroup exit); 0 (default):
                                2^20, about a second.  A tiny value makes the give-up path testable */

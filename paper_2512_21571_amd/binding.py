@@ -16,6 +16,7 @@ F32, BF16 = 0, 1
 OPT_GRAPH, OPT_PREFILL_EXACT, OPT_PERSISTENT, OPT_STAGE_TRACE, OPT_PREFILL_TILE, OPT_SPIN_LIMIT = 0, 1, 2, 3, 4, 5
 OPT_PREFILL_ATTN = 6
 OPT_FUSE_QK = 7
+OPT_TAIL_OVERLAP = 8
 
 # every symbol include/nnc.h declares
 EXPORTS = [

@@ -120,6 +120,13 @@ struct nnc_model {
   std::map<std::tuple<int, int, int>, hipGraphExec_t> graphs;
 
   bool profiling = false;
+  // Long prompts: the fp32-grade tail pass runs on a second stream, one layer behind the last
+  // block (whose layers record layer_done after their cache append); created on first use.
+  bool opt_tail_overlap = true;
+  hipStream_t tail_stream = nullptr;
+  std::vector<hipEvent_t> layer_done;   // one per layer, + [n_layers]: fork point, + [n_layers + 1]: join
+  bool record_layers = false;           // prefill_block records layer_done[li]
+  bool wait_layers = false;             // run_pass makes its stream wait for layer_done[li] before layer li
   std::vector<ProfRec> prof;
 
   uint32_t H() const { return c.hidden; }
@@ -192,6 +199,13 @@ void* dev_alloc(nnc_model* m, size_t bytes) {
 }
 
 void release_all(nnc_model* m) {
+  if (m->tail_stream) {
+    (void)hipStreamSynchronize(m->tail_stream);
+    (void)hipStreamDestroy(m->tail_stream);
+    m->tail_stream = nullptr;
+  }
+  for (hipEvent_t e : m->layer_done) (void)hipEventDestroy(e);
+  m->layer_done.clear();
   for (auto& kv : m->graphs) (void)hipGraphExecDestroy(kv.second);
   m->graphs.clear();
   for (auto& r : m->prof) {
@@ -295,6 +309,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
   const long pstride = (long)n * H;
   for (uint32_t li = 0; li < c.n_layers; ++li) {
     const LayerW& L = m->L[li];
+    if (m->wait_layers) HIP_TRY(hipStreamWaitEvent(s, m->layer_done[li], 0));
     RUN(FAM_NORM, n * H * 8.0, 0,
         launch_rmsnorm_pack(s, f32, m->x, H, m->rpart, pending, pstride, L.g_in, H, c.rms_eps, n, m->Xp, nc, ns));
     {
@@ -814,6 +829,7 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
       if (value < -1 || value > 4) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic) or 0 .. 4");
       m->opt_prefill_tile = value;
       return NNC_OK;
+    case NNC_OPT_TAIL_OVERLAP: m->opt_tail_overlap = value != 0; return NNC_OK;
     case NNC_OPT_PREFILL_ATTN:
       if (value < -1 || value > 3) return fail(NNC_E_ARG, "prefill attention shape must be -1 (automatic) or 0 .. 3");
       m->opt_prefill_attn = value;
@@ -903,6 +919,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       RUN(FAM_QKROPE, T * Nqkv * 4.0, 0,
           launch_qknorm_rope_append(s, false, m->pb_qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, (int)n, L.kc,
                                     L.vc, c.max_batch, c.max_seq, nullptr, m->pb_vt, m->pb_vt_stride));
+      if (m->record_layers) HIP_TRY(hipEventRecord(m->layer_done[li], s));
     }
     {
       // causal attention of the block on the matrix cores, over a transposed copy of the
@@ -958,6 +975,45 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
   return NNC_OK;
 }
 
+// Second stream and per-layer events for the tail of a long prompt; false if they cannot be had
+// (the tail then follows the last block on the model's stream).
+static bool ensure_tail_stream(nnc_model* m) {
+  if (m->tail_stream) return true;
+  hipStream_t st = nullptr;
+  if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return false;
+  std::vector<hipEvent_t> ev(m->c.n_layers + 2, nullptr);
+  for (auto& e : ev)
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+      for (hipEvent_t d : ev)
+        if (d) (void)hipEventDestroy(d);
+      (void)hipStreamDestroy(st);
+      return false;
+    }
+  m->tail_stream = st;
+  m->layer_done = ev;
+  return true;
+}
+
+// While alive, the model's passes are enqueued on the tail stream and wait, layer by layer, for
+// the last block's cache appends.
+struct TailStreamScope {
+  nnc_model* m;
+  hipStream_t main;
+  bool on;
+  TailStreamScope(nnc_model* m_, bool on_) : m(m_), main(m_->stream), on(on_) {
+    if (on) {
+      m->stream = m->tail_stream;
+      m->wait_layers = true;
+    }
+  }
+  ~TailStreamScope() {
+    if (on) {
+      m->stream = main;
+      m->wait_layers = false;
+    }
+  }
+};
+
 static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tokens, const float* x, uint32_t n,
                                  float* logits_out, int32_t* next_out, float* y) {
   if (slot >= m->c.max_batch) return fail(NNC_E_ARG, "slot %u out of range", slot);
@@ -968,6 +1024,7 @@ static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tok
     for (uint32_t i = 0; i < n; ++i)
       if (tokens[i] < 0 || (uint32_t)tokens[i] >= m->c.vocab) return fail(NNC_E_ARG, "token %d out of range", tokens[i]);
   uint32_t done = 0;  // tokens already processed by the large-block path
+  bool overlap = false;
   if (tokens && m->pb_max && m->opt_prefill_exact != 1) {
     const uint32_t len0 = m->len[slot];
     // Blocks of up to pb_max tokens.  A block of more than 512 tokens rounds its matrix-core
@@ -977,12 +1034,22 @@ static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tok
     // of one decode step.
     uint32_t head = n;
     if (m->opt_prefill_exact == 0 && n > 512) head = n - PREFILL_TAIL;
+    // The tail pass streams every weight once more at a few percent of the matrix cores' rate,
+    // the last block is bound by the matrix cores: the two run side by side, the tail's layer l
+    // starting when the block's layer l has appended its K / V rows.
+    overlap = head < n && m->opt_tail_overlap && !m->profiling && ensure_tail_stream(m);
     for (uint32_t t0 = 0; t0 < head;) {
       const uint32_t nb = std::min(m->pb_max, head - t0);
       const bool last = t0 + nb == n;
-      if (nnc_status st = prefill_block(m, slot, tokens + t0, nb, len0 + t0, last && (logits_out || next_out),
-                                        logits_out, next_out ? m->next : nullptr))
-        return st;
+      const bool fork = overlap && t0 + nb == head;
+      if (fork) {
+        HIP_TRY(hipEventRecord(m->layer_done[m->c.n_layers], m->stream));  // everything enqueued so far
+        m->record_layers = true;
+      }
+      const nnc_status st = prefill_block(m, slot, tokens + t0, nb, len0 + t0, last && (logits_out || next_out),
+                                          logits_out, next_out ? m->next : nullptr);
+      m->record_layers = false;
+      if (st) return st;
       t0 += nb;
     }
     if (head == n) {
@@ -996,6 +1063,10 @@ static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tok
   const uint32_t chunk = MAX_COLS / nsplit;
   const size_t H = m->H();
   const uint32_t len0 = m->len[slot];
+  hipStream_t main_stream = m->stream;
+  if (overlap) HIP_TRY(hipStreamWaitEvent(m->tail_stream, m->layer_done[m->c.n_layers], 0));
+  {
+  TailStreamScope scope(m, overlap);
   for (uint32_t t0 = done; t0 < n; t0 += chunk) {
     const uint32_t nc = std::min(chunk, n - t0);
     uint32_t slots[MAX_COLS], pos[MAX_COLS];
@@ -1025,6 +1096,11 @@ static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tok
     if (!tokens) HIP_TRY(launch_copy_rows(m->stream, m->x, y + (size_t)t0 * H, (size_t)nc * H));
     if (last && next_out && tokens)
       HIP_TRY(hipMemcpyAsync(next_out, m->next, 4, hipMemcpyDeviceToDevice, m->stream));
+  }
+  }
+  if (overlap) {  // the model's stream continues after the tail
+    HIP_TRY(hipEventRecord(m->layer_done[m->c.n_layers + 1], m->tail_stream));
+    HIP_TRY(hipStreamWaitEvent(main_stream, m->layer_done[m->c.n_layers + 1], 0));
   }
   m->len[slot] = len0 + n;
   return NNC_OK;

@@ -271,6 +271,39 @@ def test_batched_decode_mixed_lengths_up_to_4k(nnc, shape, fuse):
     assert g.slot_len(1) == 4104
 
 
+def test_prompt_tail_beside_the_last_block_equals_tail_after_it(nnc):
+    """The fp32-grade pass over a long prompt's last tokens runs on the library's second stream
+    beside the last block (default) or after it on the model's stream: same bits, for one block,
+    two blocks, prompts back to back in one model, and the decode steps that follow."""
+    shape = SMALL_G4
+    blob = synth.make_blob(shape, weight_std=0.05, gain_jitter=0.1)
+    out = {}
+    for overlap in (1, 0):
+        print(f"case: prompt tail overlap={overlap}", flush=True)
+        g = nnc.Model(shape, blob, 3, 2300)
+        g.set_option(nnc.OPT_PREFILL_EXACT, 0)
+        g.set_option(nnc.OPT_TAIL_OVERLAP, overlap)
+        res = []
+        firsts = []
+        for b, n in enumerate([700, 2200, 1300]):
+            lg, nx = g.prefill(b, synth.tokens(n, shape.vocab, stream=70 + b))
+            res.append(lg.cpu().numpy().copy())
+            firsts.append(int(nx.item()))
+        toks, logits = g.decode_greedy([0, 1, 2], firsts, 3, want_logits=True)
+        res.append(logits.cpu().numpy().copy())
+        res.append(toks.cpu().numpy().copy())
+        out[overlap] = (res, firsts)
+        del g
+    assert out[1][1] == out[0][1]
+    for a, b in zip(out[1][0], out[0][0]):
+        assert np.array_equal(a, b)
+    # and the default path against the oracle
+    o = oracle.from_shape(shape, blob, 1, 800)
+    lo, no = oracle_prefill_like_library(o, 0, synth.tokens(700, shape.vocab, stream=70), shape)
+    assert np.abs(out[1][0][0].astype(np.float64) - lo).max() <= BF16_ABS_PROMPT
+    assert out[1][1][0] == no
+
+
 def test_random_requests_against_oracle(nnc):
     """Seeded random requests (shape, batch, ragged prompt lengths across the block and piece
     boundaries, decode steps, forced kernel shapes, fused / separate kernels, resident / per-stage
