@@ -15,7 +15,10 @@
  *     the model state are left untouched and nnc_last_error() describes the cause;
  *   - "host" pointers are ordinary CPU memory read during the call only;
  *     "device" pointers are GPU memory owned by the caller, read or written by
- *     work enqueued on the model's stream; calls do not synchronise the stream;
+ *     work enqueued on the model's stream; calls do not synchronise the stream
+ *     (a long prompt's last pass runs on a second stream that the library creates
+ *     and joins back to the model's stream with events before the call returns,
+ *     see NNC_OPT_TAIL_OVERLAP: a caller still orders its work on the one stream);
  *   - a model is bound to the GPU that was current at nnc_model_create and to one
  *     stream; calls on one model must not overlap (not thread-safe);
  *   - positions are implicit: each KV slot remembers its length, nnc_prefill and
