@@ -836,7 +836,7 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const uint32_t j = min(j0 + (uint32_t)((tid >> 4) + 16 * i), jlast);
-    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(vc + base + (size_t)j * 128 + (tid & 15) * 8));
+    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(vc + base + (size_t)j * 128 + (tid & 15) * 8);
     vreg[i][0] = make_uint2(v.x, v.y);
     vreg[i][1] = make_uint2(v.z, v.w);
   }
@@ -845,7 +845,7 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
     const uint32_t jk = min(j0 + (uint32_t)(wave * 16 + c16), jlast);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
-      kf[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(kc + base + (size_t)jk * 128 + ks * 32 + g * 8));
+      kf[ks] = *reinterpret_cast<const u32x4_t*>(kc + base + (size_t)jk * 128 + ks * 32 + g * 8);
   }
   uint16_t(*qp)[8][128] = reinterpret_cast<uint16_t(*)[8][128]>(&pw[0][0][0]);
   if constexpr (FUSED) {
