@@ -337,11 +337,21 @@ def test_random_requests_against_oracle(nnc):
             firsts.append(no)
         toks_g, logits_g = g.decode_greedy(list(range(batch)), firsts, steps, want_logits=True)
         cur = list(firsts)
+        following = True
         for s_ in range(steps):
+            if not following:
+                break
             for b in range(batch):
                 lo, nx = o.step_token(b, cur[b], fl)
                 _check_logits(shape, logits_g[s_, b], lo, BF16_ABS_PROMPT)
-                assert int(toks_g[s_, b].item()) == nx
+                if int(toks_g[s_, b].item()) != nx:
+                    # only a tie within the logit error may flip the greedy token; the on-device
+                    # loop then continues from its own token and the comparison of this case ends
+                    err = np.abs(logits_g[s_, b].double().cpu().numpy() - lo).max()
+                    top = np.sort(lo)[-2:]
+                    assert top[1] - top[0] <= 2 * err, (case, s_, b)
+                    following = False
+                    break
                 cur[b] = nx
 
 
