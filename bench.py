@@ -5,7 +5,7 @@ One "step" = one whole pass of the hot path over one synthetic request of the
 configuration the metric is quoted on (Qwen3-0.6B-shaped, bf16 weights and KV cache,
 fp32 accumulation, batch 1): reset the KV slot, run the 128-token prompt, then 128
 greedy decode steps with the token fed back on the device.  The paper's metric is
-tokens/s over the decoding stage (Section 5, experimental setup); `value` is that,
+tokens/s over the decoding stage (Section 4, experimental setup); `value` is that,
 summed over the K timed steps, with weights and prompt already resident in HBM.
 --workload selects the larger configurations (batched requests fill every slot's
 context with prompt passes, then decode all slots together).

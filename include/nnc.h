@@ -3,7 +3,7 @@
  *
  * The workload is the one the nncase paper compiles and times: the decode stage
  * (and the prompt pass before it) of Qwen3-0.6B / 1.7B at batch 1, tokens/s over
- * the decoding stage (Section 5, experimental setup; Sections 5.1 and 5.2), with
+ * the decoding stage (Section 4, experimental setup; Sections 4.1 and 4.2), with
  * weights laid out once, ahead of time, in the layout the matmul micro-kernel
  * wants (Section 3.1.2 "Auto Vectorize": packed / blocked layouts; Section 3.3.1:
  * constants are pre-split and pinned; Section 3.3.2: MatMul micro-kernels over
@@ -101,7 +101,7 @@ nnc_status nnc_model_create(const nnc_config *cfg, const void *blob, size_t blob
 void nnc_model_destroy(nnc_model *m);
 
 /*
- * Prompt pass (the paper's pre-decode stage, Section 5 setup): run n tokens
+ * Prompt pass (the paper's pre-decode stage, Section 4 setup): run n tokens
  * (host int32, each in [0, vocab)) through the model for one KV slot, appending
  * K/V at positions len..len+n-1.  logits_out: device, vocab floats, logits of the
  * LAST position; may be NULL.  next_out: device int32, greedy arg-max of those

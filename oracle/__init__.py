@@ -16,8 +16,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
-F32, BF16 = 0, 1
-ROUND_KV, ROUND_GEMM_IN, ROUND_ATTN_QP, ROUND_HEAD_IN = 1, 2, 4, 8
+F32, BF16, F16 = 0, 1, 2
+ROUND_KV, ROUND_GEMM_IN, ROUND_ATTN_QP, ROUND_HEAD_IN, ROUND_F16 = 1, 2, 4, 8, 16
 
 
 class OrcConfig(ctypes.Structure):
@@ -45,6 +45,8 @@ def lib():
         sig = {
             "orc_bf16_round": (dbl, [dbl]),
             "orc_bf16_bits": (ctypes.c_uint16, [ctypes.c_float]),
+            "orc_f16_round": (dbl, [dbl]),
+            "orc_f16_bits": (ctypes.c_uint16, [ctypes.c_float]),
             "orc_silu": (dbl, [dbl]),
             "orc_rmsnorm": (None, [vp, vp, u32, dbl, vp]),
             "orc_rope": (None, [vp, u32, u32, dbl, vp]),
@@ -86,6 +88,14 @@ def bf16_bits(f: float) -> int:
     return int(lib().orc_bf16_bits(float(np.float32(f))))
 
 
+def f16_round(v: float) -> float:
+    return lib().orc_f16_round(float(v))
+
+
+def f16_bits(f: float) -> int:
+    return int(lib().orc_f16_bits(float(np.float32(f))))
+
+
 def silu(z: float) -> float:
     return lib().orc_silu(float(z))
 
@@ -116,7 +126,7 @@ def softmax(s):
 
 
 def matvec(w: np.ndarray, x, dtype: int = F32):
-    """w: [rows, cols] float32 (dtype F32) or uint16 bf16 bit patterns (dtype BF16)."""
+    """w: [rows, cols] float32 (dtype F32) or uint16 bit patterns (dtype BF16 / F16)."""
     w = np.ascontiguousarray(w)
     assert w.dtype == (np.float32 if dtype == F32 else np.uint16)
     x, xp = _d(x)
@@ -125,8 +135,8 @@ def matvec(w: np.ndarray, x, dtype: int = F32):
     return y
 
 
-def attend(q, keys, vals, round_p: bool = False):
-    """q [d]; keys, vals [n, d] -> softmax(q K^T / sqrt(d)) V."""
+def attend(q, keys, vals, round_p: int = 0):
+    """q [d]; keys, vals [n, d] -> softmax(q K^T / sqrt(d)) V.  round_p: 0 / 1 (bf16) / 2 (binary16)."""
     q, qp = _d(q)
     keys, kp = _d(keys)
     vals, vp = _d(vals)

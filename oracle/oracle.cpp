@@ -14,9 +14,9 @@
  *
  * Where it comes from: the paper evaluates the decode stage of Qwen3-0.6B
  * (F32/F16) and Qwen3-1.7B (F16) at batch 1, prompt first and then one token at
- * a time, reporting tokens/s (Section 5, experimental setup; Sections 5.1, 5.2),
+ * a time, reporting tokens/s (Section 4, experimental setup; Sections 4.1, 4.2),
  * and it attributes the cost to MatMul micro-kernels over packed weights under a
- * memory-bandwidth wall (Section 3.3.2; Sections 5.1, 5.2).  The paper prints no
+ * memory-bandwidth wall (Section 3.3.2; Sections 4.1, 4.2).  The paper prints no
  * equations for the model itself.  The forward pass below is therefore the
  * public Qwen3 decoder architecture with the hyper-parameters of the benchmark
  * configurations: RMSNorm (eps inside the square root, plain gain), bias-free
@@ -30,10 +30,12 @@
  * comparison with an independent library model at a tiny shape, and the
  * individual functions by closed forms and brute force.
  *
- * Rounding points (flags, default none):
- *   ORC_ROUND_KV      k (after norm and RoPE) and v are rounded to bf16, round to
+ * Rounding points (flags, default none).  The 16-bit format of every rounding
+ * point is bf16, or IEEE binary16 ("F16", the paper's own 16-bit precision,
+ * Section 4, experimental setup) when ORC_ROUND_F16 is also set:
+ *   ORC_ROUND_KV      k (after norm and RoPE) and v are rounded to 16 bits, round to
  *                     nearest even, before they enter the cache, and attention
- *                     uses the rounded values.  This mirrors a bf16 KV cache.
+ *                     uses the rounded values.  This mirrors a 16-bit KV cache.
  *   ORC_ROUND_GEMM_IN the input vector of each matmul (the two normed hidden
  *                     states, the attention output, the SwiGLU activation; the
  *                     LM-head input too when ORC_ROUND_HEAD_IN is also set) is
@@ -66,8 +68,9 @@
 
 extern "C" {
 
-enum { ORC_F32 = 0, ORC_BF16 = 1 };
-enum { ORC_ROUND_KV = 1, ORC_ROUND_GEMM_IN = 2, ORC_ROUND_ATTN_QP = 4, ORC_ROUND_HEAD_IN = 8 };
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2 };
+enum { ORC_ROUND_KV = 1, ORC_ROUND_GEMM_IN = 2, ORC_ROUND_ATTN_QP = 4, ORC_ROUND_HEAD_IN = 8,
+       ORC_ROUND_F16 = 16 };
 
 struct orc_config {
   uint32_t hidden, n_layers, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
@@ -92,6 +95,15 @@ struct Tensor {
     }
     uint16_t h;
     std::memcpy(&h, static_cast<const char *>(p) + 2 * i, 2);
+    if (dtype == ORC_F16) {
+      /* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits */
+      const int e = (h >> 10) & 31, f = h & 1023;
+      double v;
+      if (e == 0) v = std::ldexp((double)f, -24);
+      else if (e == 31) v = f ? std::numeric_limits<double>::quiet_NaN() : std::numeric_limits<double>::infinity();
+      else v = std::ldexp((double)(1024 + f), e - 25);
+      return (h & 0x8000) ? -v : v;
+    }
     uint32_t b = (uint32_t)h << 16;
     float f;
     std::memcpy(&f, &b, 4);
@@ -142,6 +154,34 @@ uint16_t orc_bf16_bits(float f) {
   uint32_t b;
   std::memcpy(&b, &g, 4);
   return (uint16_t)(b >> 16);
+}
+
+/* Nearest IEEE binary16 value (11 significant bits, normal exponents -14..15,
+ * subnormal spacing 2^-24, largest finite 65504) of a double, ties to even,
+ * returned as a double.  Rounds once, directly from fp64. */
+double orc_f16_round(double v) {
+  if (v == 0.0 || !std::isfinite(v)) return v;
+  int e;
+  (void)std::frexp(std::fabs(v), &e);
+  int q = e - 11;
+  if (q < -24) q = -24;
+  double r = std::ldexp(std::nearbyint(std::ldexp(std::fabs(v), -q)), q);
+  if (r >= 65520.0) r = std::numeric_limits<double>::infinity(); /* 65520 = tie above 65504 -> even = inf */
+  return v < 0 ? -r : r;
+}
+
+/* The 16 stored bits of the nearest binary16 of an fp32 value. */
+uint16_t orc_f16_bits(float f) {
+  if (std::isnan(f)) return 0x7e00;
+  const double r = orc_f16_round((double)f);
+  const uint16_t sgn = std::signbit(f) ? 0x8000 : 0;
+  const double a = std::fabs(r);
+  if (a == 0.0) return sgn;
+  if (std::isinf(a)) return sgn | 0x7c00;
+  int e;
+  const double m = std::frexp(a, &e); /* a = m * 2^e, m in [0.5, 1) */
+  if (e < -13) return sgn | (uint16_t)std::ldexp(a, 24); /* subnormal: multiples of 2^-24 */
+  return sgn | (uint16_t)(((e + 14) << 10) | ((int)std::ldexp(m, 11) - 1024));
 }
 
 double orc_silu(double z) { return z / (1.0 + std::exp(-z)); }
@@ -198,7 +238,8 @@ void orc_matvec(const void *w, int dtype, uint32_t rows, uint32_t cols, const do
 /* One query against n cached rows: keys/values are [n, stride] with the head's
  * d elements starting at column 0 of the pointers given.
  * s_j = <q, K_j> / sqrt(d); o = sum_j softmax(s)_j V_j.
- * round_p: round exp(s_j - max) to bf16 before use (see ORC_ROUND_ATTN_QP). */
+ * round_p: round exp(s_j - max) to 16 bits before use (see ORC_ROUND_ATTN_QP):
+ * 0 = no, 1 = bf16, 2 = binary16. */
 void orc_attend(const double *q, const double *keys, const double *vals, uint32_t n, uint32_t d,
                 size_t stride, int round_p, double *out) {
   std::vector<double> s(n);
@@ -213,12 +254,13 @@ void orc_attend(const double *q, const double *keys, const double *vals, uint32_
   if (!round_p) {
     orc_softmax(s.data(), n, w.data());
   } else {
-    /* un-normalised weights rounded to bf16; the denominator sums what was used */
+    /* un-normalised weights rounded to 16 bits; the denominator sums what was used */
     double m = s[0];
     for (uint32_t j = 1; j < n; ++j) m = s[j] > m ? s[j] : m;
     z = 0.0;
     for (uint32_t j = 0; j < n; ++j) {
-      w[j] = orc_bf16_round(std::exp(s[j] - m));
+      const double ex = std::exp(s[j] - m);
+      w[j] = round_p == 2 ? orc_f16_round(ex) : orc_bf16_round(ex);
       z += w[j];
     }
   }
@@ -318,9 +360,9 @@ void gains(const Tensor &t, size_t n, std::vector<double> &g) {
   for (size_t i = 0; i < n; ++i) g[i] = t.at(i);
 }
 
-void maybe_round(std::vector<double> &v, bool on) {
+void maybe_round(std::vector<double> &v, bool on, bool f16) {
   if (on)
-    for (auto &e : v) e = orc_bf16_round(e);
+    for (auto &e : v) e = f16 ? orc_f16_round(e) : orc_bf16_round(e);
 }
 
 /* One decoder layer for the token at position pos of `slot`; x is updated in place. */
@@ -330,13 +372,14 @@ void layer_forward(orc_model *m, uint32_t li, uint32_t slot, uint32_t pos, uint3
   const Layer &L = m->layers[li];
   const uint32_t H = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads,
                  Dq = nq * d, Dkv = nkv * d, F = c.ffn, G = nq / nkv;
-  const bool rin = flags & ORC_ROUND_GEMM_IN, rkv = flags & ORC_ROUND_KV, rqp = flags & ORC_ROUND_ATTN_QP;
+  const bool rin = flags & ORC_ROUND_GEMM_IN, rkv = flags & ORC_ROUND_KV, rqp = flags & ORC_ROUND_ATTN_QP,
+             f16 = flags & ORC_ROUND_F16;
   std::vector<double> g, h(H), q(Dq), k(Dkv), v(Dkv), tmp(d), o(Dq), y(H);
 
   /* input norm, then q, k, v projections */
   gains(L.g_in, H, g);
   orc_rmsnorm(x.data(), g.data(), H, c.rms_eps, h.data());
-  maybe_round(h, rin);
+  maybe_round(h, rin, f16);
   orc_matvec(L.wq.p, L.wq.dtype, Dq, H, h.data(), q.data());
   orc_matvec(L.wk.p, L.wk.dtype, Dkv, H, h.data(), k.data());
   orc_matvec(L.wv.p, L.wv.dtype, Dkv, H, h.data(), v.data());
@@ -352,9 +395,9 @@ void layer_forward(orc_model *m, uint32_t li, uint32_t slot, uint32_t pos, uint3
     orc_rmsnorm(&k[b * d], g.data(), d, c.rms_eps, tmp.data());
     orc_rope(tmp.data(), d, pos, c.rope_theta, &k[b * d]);
   }
-  maybe_round(k, rkv);
-  maybe_round(v, rkv);
-  maybe_round(q, rqp);
+  maybe_round(k, rkv, f16);
+  maybe_round(v, rkv, f16);
+  maybe_round(q, rqp, f16);
 
   /* append to the cache at position pos */
   double *kc = m->kcache.data() + m->kv_index(li, slot, 0);
@@ -366,23 +409,23 @@ void layer_forward(orc_model *m, uint32_t li, uint32_t slot, uint32_t pos, uint3
 #pragma omp parallel for schedule(static)
   for (int64_t a = 0; a < (int64_t)nq; ++a) {
     const uint32_t b = (uint32_t)a / G;
-    orc_attend(&q[a * d], kc + b * d, vc + b * d, pos + 1, d, Dkv, rqp ? 1 : 0, &o[a * d]);
+    orc_attend(&q[a * d], kc + b * d, vc + b * d, pos + 1, d, Dkv, rqp ? (f16 ? 2 : 1) : 0, &o[a * d]);
   }
 
   /* output projection + residual */
-  maybe_round(o, rin);
+  maybe_round(o, rin, f16);
   orc_matvec(L.wo.p, L.wo.dtype, H, Dq, o.data(), y.data());
   for (uint32_t i = 0; i < H; ++i) x[i] += y[i];
 
   /* post-attention norm, SwiGLU feed-forward, residual */
   gains(L.g_post, H, g);
   orc_rmsnorm(x.data(), g.data(), H, c.rms_eps, h.data());
-  maybe_round(h, rin);
+  maybe_round(h, rin, f16);
   std::vector<double> gate(F), up(F), act(F);
   orc_matvec(L.wgate.p, L.wgate.dtype, F, H, h.data(), gate.data());
   orc_matvec(L.wup.p, L.wup.dtype, F, H, h.data(), up.data());
   for (uint32_t i = 0; i < F; ++i) act[i] = orc_silu(gate[i]) * up[i];
-  maybe_round(act, rin);
+  maybe_round(act, rin, f16);
   orc_matvec(L.wdown.p, L.wdown.dtype, H, F, act.data(), y.data());
   for (uint32_t i = 0; i < H; ++i) x[i] += y[i];
 }
@@ -414,7 +457,7 @@ int orc_step_token(orc_model *m, uint32_t slot, int32_t token, uint32_t flags, d
   std::vector<double> g, xn(H), logits;
   gains(m->g_final, H, g);
   orc_rmsnorm(x.data(), g.data(), H, c.rms_eps, xn.data());
-  maybe_round(xn, (flags & ORC_ROUND_GEMM_IN) && (flags & ORC_ROUND_HEAD_IN));
+  maybe_round(xn, (flags & ORC_ROUND_GEMM_IN) && (flags & ORC_ROUND_HEAD_IN), flags & ORC_ROUND_F16);
   double *lp = logits_out;
   if (!lp) {
     logits.resize(V);

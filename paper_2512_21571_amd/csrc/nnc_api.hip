@@ -7,7 +7,7 @@
 // pass whose columns are consecutive positions of one slot (the attention kernel
 // takes each column's own position from device memory, so causal masking needs no
 // special case).  The paper's run loop is the same: prompt first, then one token
-// at a time, timed over the decoding stage (Section 5, experimental setup).
+// at a time, timed over the decoding stage (Section 4, experimental setup).
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>

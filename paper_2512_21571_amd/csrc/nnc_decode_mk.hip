@@ -5,7 +5,7 @@
 // Run as separate kernels, every stage pays a launch-drain-launch bubble of several
 // microseconds, and that is where the time goes.  The paper observes the same on
 // CPUs: fork-join barriers of a threading runtime limit scaling, and a static
-// partition with cheap, deterministic communication wins (Section 5.2,
+// partition with cheap, deterministic communication wins (Section 4.2,
 // architectural discussion).  Here one resident grid (at most one workgroup per
 // compute unit) runs all the decode steps of a call:
 //

@@ -5,7 +5,7 @@ canonical weight-blob layout (a file format) and draws the random numbers that
 fill it.  Tests feed the same blob to the CPU oracle and to the GPU library.
 
 Stands in for the trained Qwen3-0.6B / 1.7B checkpoints and the short prompt of
-the paper's evaluation (Section 5, experimental setup); the 4B / 8B shapes extend
+the paper's evaluation (Section 4, experimental setup); the 4B / 8B shapes extend
 the same family.
 """
 from __future__ import annotations
@@ -24,7 +24,7 @@ _lib = None
 WEIGHT_SEED = 251221571
 INPUT_SEED = 251221572
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -44,10 +44,11 @@ def _load():
         u64, dbl, vp = ctypes.c_uint64, ctypes.c_double, ctypes.c_void_p
         lib.synth_normal_f32.argtypes = [u64, u64, u64, u64, dbl, vp]
         lib.synth_normal_bf16.argtypes = [u64, u64, u64, u64, dbl, vp]
+        lib.synth_normal_f16.argtypes = [u64, u64, u64, u64, dbl, vp]
         lib.synth_uniform_i32.argtypes = [u64, u64, u64, u64, ctypes.c_uint32, vp]
         lib.synth_raw.argtypes = [u64, u64, u64]
         lib.synth_raw.restype = u64
-        for f in (lib.synth_normal_f32, lib.synth_normal_bf16, lib.synth_uniform_i32):
+        for f in (lib.synth_normal_f32, lib.synth_normal_bf16, lib.synth_normal_f16, lib.synth_uniform_i32):
             f.restype = None
         _lib = lib
     return _lib
@@ -163,13 +164,15 @@ def make_blob(s: ModelShape, seed: int = WEIGHT_SEED, weight_std: float = 0.02,
                 g[:] = 1.0
         elif s.dtype == F32:
             lib.synth_normal_f32(seed, tid, 0, n, weight_std, base + off)
+        elif s.dtype == F16:
+            lib.synth_normal_f16(seed, tid, 0, n, weight_std, base + off)
         else:
             lib.synth_normal_bf16(seed, tid, 0, n, weight_std, base + off)
     return blob
 
 
 def blob_tensor(s: ModelShape, blob: np.ndarray, name: str) -> np.ndarray:
-    """View of one tensor inside the blob (uint16 holds bf16 bit patterns)."""
+    """View of one tensor inside the blob (uint16 holds bf16 or binary16 bit patterns)."""
     table, _ = blob_offsets(s)
     off, shape, dt = table[name]
     return np.frombuffer(blob, dtype=dt, count=int(np.prod(shape)), offset=off).reshape(shape)
@@ -178,6 +181,11 @@ def blob_tensor(s: ModelShape, blob: np.ndarray, name: str) -> np.ndarray:
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     """Widen stored bf16 bit patterns to fp32 (exact; a format conversion)."""
     return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def f16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Widen stored binary16 bit patterns to fp32 (exact; a format conversion)."""
+    return bits.view(np.float16).astype(np.float32)
 
 
 def tokens(n: int, vocab: int, stream: int = 0, seed: int = INPUT_SEED) -> np.ndarray:

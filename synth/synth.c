@@ -14,7 +14,7 @@
  *   normal = sqrt(-2 ln u1) * cos(2 pi u2)      (Box-Muller, fp64)
  *
  * The workload these stand in for is the Qwen3 checkpoints and prompts of the
- * paper's evaluation (Section 5, experimental setup), which are not available
+ * paper's evaluation (Section 4, experimental setup), which are not available
  * here; shapes follow the public Qwen3 sizes.
  */
 #include <math.h>
@@ -48,6 +48,23 @@ static inline uint16_t store_bf16(float f) {
   return (uint16_t)(b >> 16);
 }
 
+/* fp32 -> IEEE binary16 storage format, round to nearest, ties to even, for finite
+ * inputs below the binary16 overflow threshold (weights are ~N(0, 0.02^2)). */
+static inline uint16_t store_f16(float f) {
+  uint32_t b;
+  memcpy(&b, &f, 4);
+  const uint16_t sgn = (uint16_t)((b >> 16) & 0x8000u);
+  const uint32_t a = b & 0x7fffffffu;
+  if (a >= 0x477ff000u) return sgn | 0x7c00u;          /* >= 65520: rounds to infinity */
+  if (a < 0x38800000u) {                               /* below 2^-14: multiples of 2^-24 */
+    float av;
+    memcpy(&av, &a, 4);
+    return sgn | (uint16_t)lrintf(av * 16777216.0f);   /* exact scaling, nearest-even rounding */
+  }
+  uint32_t r = a + 0xfffu + ((a >> 13) & 1u);           /* drop 13 fraction bits, nearest even */
+  return sgn | (uint16_t)((r - 0x38000000u) >> 13);
+}
+
 void synth_normal_f32(uint64_t seed, uint64_t tensor, uint64_t first, uint64_t n,
                       double scale, float *out) {
 #pragma omp parallel for schedule(static)
@@ -60,6 +77,13 @@ void synth_normal_bf16(uint64_t seed, uint64_t tensor, uint64_t first, uint64_t 
 #pragma omp parallel for schedule(static)
   for (int64_t i = 0; i < (int64_t)n; ++i)
     out[i] = store_bf16((float)(scale * std_normal(draw(seed, tensor, first + (uint64_t)i))));
+}
+
+void synth_normal_f16(uint64_t seed, uint64_t tensor, uint64_t first, uint64_t n,
+                      double scale, uint16_t *out) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < (int64_t)n; ++i)
+    out[i] = store_f16((float)(scale * std_normal(draw(seed, tensor, first + (uint64_t)i))));
 }
 
 /* Uniform integers in [0, bound): floor(u * bound) with u the high 32 bits / 2^32. */

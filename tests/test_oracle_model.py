@@ -211,25 +211,196 @@ def test_conventions_against_library_qwen3_in_fp64(tiny_shape):
     assert np.abs(want).max() > 0.1                       # the comparison is not vacuous
 
 
-def test_round_kv_flag_stores_bf16_values_of_the_exact_rows(tiny_shape):
+# ---- rounding points (flags) -------------------------------------------------------
+#
+# Every rounding flag is pinned by making ONE rounded vector observable through selector
+# weights (rows of the identity) on a one-layer hidden-state model, and comparing with a value
+# built from the closed-form RMSNorm, a numpy matrix product and the separately pinned scalar
+# rounding function.  Each probe also shows that the plausible mistakes (rounding dropped,
+# rounding at the neighbouring point instead) would give a different value.
+
+FORMATS = [("bf16", 0), ("f16", oracle.ROUND_F16)]
+
+
+def _rnd(fmt_flag):
+    f = oracle.f16_round if fmt_flag else oracle.bf16_round
+    return lambda a: np.array([f(float(v)) for v in np.ravel(a)]).reshape(np.shape(a))
+
+
+def _layer_model(tiny_shape, **zero):
+    s = tiny_shape.scaled(has_embed_and_head=False, tied_lm_head=False, vocab=0, n_layers=1)
+    blob = synth.make_blob(s, weight_std=0.3, gain_jitter=0.1)
+    return s, blob
+
+
+def _selector(w, col0=0):
+    """w[i, col0 + i] = 1, everything else 0: y = W x copies x[col0 : col0 + rows]."""
+    w[...] = 0.0
+    for i in range(w.shape[0]):
+        if col0 + i < w.shape[1]:
+            w[i, col0 + i] = 1.0
+
+
+def _norm(x, g, eps):
+    return x / math.sqrt(np.mean(x * x) + eps) * g
+
+
+@pytest.mark.parametrize("fmt,ff", FORMATS)
+def test_round_kv_flag_stores_rounded_values_of_the_exact_rows(tiny_shape, fmt, ff):
     blob = synth.make_blob(tiny_shape, weight_std=0.2)
     toks = synth.tokens(3, tiny_shape.vocab)
-    exact, rnd = _mk(tiny_shape, blob), _mk(tiny_shape, blob)
+    rnd = _rnd(ff)
+    exact, rounded = _mk(tiny_shape, blob), _mk(tiny_shape, blob)
     exact.step_token(0, toks[0], want_logits=False)
-    rnd.step_token(0, toks[0], flags=oracle.ROUND_KV, want_logits=False)
+    rounded.step_token(0, toks[0], flags=oracle.ROUND_KV | ff, want_logits=False)
     for which in (0, 1):
         e = exact.kv_rows(0, 0, which)[0]            # layer 0, position 0 depends on no cache
-        r = rnd.kv_rows(0, 0, which)[0]
-        assert np.array_equal(r, [oracle.bf16_round(v) for v in e])
+        r = rounded.kv_rows(0, 0, which)[0]
+        assert np.array_equal(r, rnd(e))
         assert np.any(r != e)
 
 
-def test_round_gemm_in_flag_is_a_small_perturbation(tiny_shape):
-    blob = synth.make_blob(tiny_shape, weight_std=0.2)
-    toks = synth.tokens(6, tiny_shape.vocab)
-    a, _ = _mk(tiny_shape, blob).prefill(0, toks)
-    b, _ = _mk(tiny_shape, blob).prefill(0, toks, flags=oracle.ROUND_GEMM_IN | oracle.ROUND_HEAD_IN)
-    c, _ = _mk(tiny_shape, blob).prefill(0, toks, flags=oracle.ROUND_GEMM_IN)
-    err = np.abs(a - b).max() / np.abs(a).max()
-    assert 1e-5 < err < 3e-2
-    assert not np.array_equal(b, c)
+@pytest.mark.parametrize("fmt,ff", FORMATS)
+def test_round_gemm_in_rounds_the_normed_input_of_the_qkv_projections(tiny_shape, fmt, ff):
+    # Wv = rows of the identity: the cached V row IS the projection's input vector
+    s, blob = _layer_model(tiny_shape)
+    _selector(synth.blob_tensor(s, blob, "l0.wv"))
+    g_in = synth.blob_tensor(s, blob, "l0.g_in").astype(np.float64)
+    x = synth.activations(1, s.hidden)[0].astype(np.float64)
+    h = _norm(x, g_in, s.rms_eps)
+    m = _mk(s, blob)
+    m.step_hidden(0, x, flags=oracle.ROUND_GEMM_IN | ff)
+    m.step_hidden(1, x, flags=0)
+    want = _rnd(ff)(h[:s.dkv])
+    assert np.array_equal(m.kv_rows(0, 0, 1)[0], want)
+    assert np.allclose(m.kv_rows(0, 1, 1)[0], h[:s.dkv], rtol=1e-14) and np.any(want != h[:s.dkv])
+
+
+@pytest.mark.parametrize("fmt,ff", FORMATS)
+def test_round_gemm_in_rounds_the_attention_output_before_the_o_projection(tiny_shape, fmt, ff):
+    # position 0: o_a = v_{a // G}; Wo copies head a into the residual; Wdown = 0
+    s, blob = _layer_model(tiny_shape)
+    _set(s, blob, "l0.wdown", 0.0)
+    d, G = s.head_dim, s.n_q_heads // s.n_kv_heads
+    rnd = _rnd(ff)
+    wv = synth.blob_tensor(s, blob, "l0.wv").astype(np.float64)
+    g_in = synth.blob_tensor(s, blob, "l0.g_in").astype(np.float64)
+    x = synth.activations(1, s.hidden)[0].astype(np.float64)
+    v = wv @ rnd(_norm(x, g_in, s.rms_eps))           # the projection input is rounded too
+    a = 3
+    _selector(synth.blob_tensor(s, blob, "l0.wo")[:d], col0=a * d)
+    synth.blob_tensor(s, blob, "l0.wo")[d:] = 0.0
+    m = _mk(s, blob)
+    y = m.step_hidden(0, x, flags=oracle.ROUND_GEMM_IN | ff)
+    vb = v[(a // G) * d:(a // G + 1) * d]
+    want = rnd(vb)
+    # the residual add happens in fp64: y - x loses the bits below ulp(x)
+    assert np.allclose(y[:d] - x[:d], want, rtol=0, atol=1e-14)
+    assert np.abs(want - vb).max() > 1e-6             # an unrounded o would be off by far more than 1e-14
+
+
+@pytest.mark.parametrize("fmt,ff", FORMATS)
+def test_round_gemm_in_rounds_the_swiglu_product_once_after_multiplying(tiny_shape, fmt, ff):
+    # Wo = 0 (attention adds nothing), Wdown copies act[0:H] into the residual
+    s, blob = _layer_model(tiny_shape)
+    _set(s, blob, "l0.wo", 0.0)
+    _selector(synth.blob_tensor(s, blob, "l0.wdown"))
+    rnd = _rnd(ff)
+    H = s.hidden
+    wg = synth.blob_tensor(s, blob, "l0.wgate").astype(np.float64)
+    wu = synth.blob_tensor(s, blob, "l0.wup").astype(np.float64)
+    g_post = synth.blob_tensor(s, blob, "l0.g_post").astype(np.float64)
+    x = synth.activations(1, H, stream=2)[0].astype(np.float64)
+    h2 = _norm(x, g_post, s.rms_eps)
+    silu = lambda z: z / (1.0 + np.exp(-z))
+    gate, up = wg @ rnd(h2), wu @ rnd(h2)
+    want = rnd(silu(gate) * up)[:H]
+    m = _mk(s, blob)
+    y = m.step_hidden(0, x, flags=oracle.ROUND_GEMM_IN | ff)
+    assert np.allclose(y - x, want, rtol=0, atol=1e-14)
+    # the mistakes this must catch are visible at this tolerance:
+    before = (rnd(silu(gate)) * rnd(up))[:H]                              # rounded before the product
+    unrounded_h2 = rnd(silu(wg @ h2) * (wu @ h2))[:H]                     # second norm's rounding dropped
+    no_act = (silu(gate) * up)[:H]                                        # act rounding dropped
+    for wrong in (before, unrounded_h2, no_act):
+        assert np.abs(wrong - want).max() > 1e-6
+
+
+@pytest.mark.parametrize("fmt,ff", FORMATS)
+def test_round_attn_qp_rounds_the_rotated_query_and_the_unnormalised_weights(tiny_shape, fmt, ff):
+    # two cached positions; K / V rows are read back from the cache (no ORC_ROUND_KV: exact),
+    # the rotated query is rebuilt from the pinned building blocks, the head's output is made
+    # visible by a selector Wo with Wdown = 0
+    s, blob = _layer_model(tiny_shape)
+    _set(s, blob, "l0.wdown", 0.0)
+    d, G, H = s.head_dim, s.n_q_heads // s.n_kv_heads, s.hidden
+    rnd = _rnd(ff)
+    a = 2
+    b = a // G
+    wo = synth.blob_tensor(s, blob, "l0.wo")
+    _selector(wo[:d], col0=a * d)
+    wo[d:] = 0.0
+    wq = synth.blob_tensor(s, blob, "l0.wq").astype(np.float64)
+    g_in = synth.blob_tensor(s, blob, "l0.g_in").astype(np.float64)
+    synth.blob_tensor(s, blob, "l0.g_q")[...] *= 3.0    # wider scores: the query's rounding moves the weights
+    g_q = synth.blob_tensor(s, blob, "l0.g_q").astype(np.float64)
+    xs = 4.0 * synth.activations(2, H, stream=4).astype(np.float64)
+    m = _mk(s, blob)
+    fl = oracle.ROUND_ATTN_QP | ff
+    y0 = m.step_hidden(0, xs[0], flags=fl)
+    # the second input does not depend on the first output here (hidden-state model)
+    y1 = m.step_hidden(0, xs[1], flags=fl)
+    K = m.kv_rows(0, 0, 0)[:, b * d:(b + 1) * d]
+    V = m.kv_rows(0, 0, 1)[:, b * d:(b + 1) * d]
+    q = (wq @ _norm(xs[1], g_in, s.rms_eps))[a * d:(a + 1) * d]
+    qt = oracle.rope(oracle.rmsnorm(q, g_q, s.rms_eps), 1, s.rope_theta)
+
+    def attn(qv, round_w):
+        sc = np.array([qv @ K[0], qv @ K[1]]) / math.sqrt(d)
+        w = np.exp(sc - sc.max())
+        if round_w:
+            w = rnd(w)
+        return (w[0] * V[0] + w[1] * V[1]) / (w[0] + w[1])
+
+    want = attn(rnd(qt), True)
+    assert np.allclose(y1[:d] - xs[1][:d], want, rtol=0, atol=1e-13)
+    for wrong in (attn(qt, True), attn(rnd(qt), False), attn(qt, False)):
+        assert np.abs(wrong - want).max() > 1e-7      # a million times the tolerance above
+    # the query must not be rounded in the cache-facing path of K: rows are exact
+    exact = _mk(s, blob)
+    exact.step_hidden(0, xs[0])
+    assert np.array_equal(exact.kv_rows(0, 0, 0)[0], m.kv_rows(0, 0, 0)[0])
+    assert np.isfinite(y0).all()
+
+
+@pytest.mark.parametrize("fmt,ff", FORMATS)
+def test_round_head_in_needs_both_flags_and_rounds_the_final_norm_output(tiny_shape, fmt, ff):
+    s = tiny_shape.scaled(n_layers=0)
+    blob = synth.make_blob(s, weight_std=1.0, gain_jitter=0.2)
+    E = synth.blob_tensor(s, blob, "embed").astype(np.float64)
+    g = synth.blob_tensor(s, blob, "g_final").astype(np.float64)
+    t = 17
+    xn = _norm(E[t], g, s.rms_eps)
+    m = _mk(s, blob)
+    both, _ = m.step_token(0, t, flags=oracle.ROUND_GEMM_IN | oracle.ROUND_HEAD_IN | ff)
+    only_in, _ = m.step_token(0, t, flags=oracle.ROUND_GEMM_IN | ff)
+    only_head, _ = m.step_token(0, t, flags=oracle.ROUND_HEAD_IN | ff)
+    assert np.allclose(both, E @ _rnd(ff)(xn), rtol=1e-13, atol=1e-13)
+    assert np.allclose(only_in, E @ xn, rtol=1e-13, atol=1e-13)
+    assert np.allclose(only_head, E @ xn, rtol=1e-13, atol=1e-13)
+    assert np.abs(both - only_in).max() > 1e-4
+
+
+def test_f16_blob_model_equals_fp32_model_of_the_widened_weights(tiny_shape):
+    # the 16-bit storage formats are only a widening step: a binary16 blob gives exactly the
+    # logits of an fp32 blob that holds the same values
+    sh = tiny_shape.scaled(dtype=synth.F16)
+    bh = synth.make_blob(sh, weight_std=0.2, gain_jitter=0.1)
+    bf = synth.make_blob(tiny_shape, weight_std=0.2, gain_jitter=0.1)
+    for name, _, is_gain in synth.blob_layout(sh):
+        src = synth.blob_tensor(sh, bh, name)
+        synth.blob_tensor(tiny_shape, bf, name)[...] = src if is_gain else synth.f16_bits_to_f32(src)
+    toks = synth.tokens(5, sh.vocab)
+    la, na = _mk(sh, bh).prefill(0, toks)
+    lb, nb = _mk(tiny_shape, bf).prefill(0, toks)
+    assert np.array_equal(la, lb) and na == nb

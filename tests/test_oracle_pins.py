@@ -50,6 +50,52 @@ def test_bf16_error_at_most_half_ulp():
     assert np.all(np.abs(r - x) <= ulp / 2)
 
 
+# ---- binary16 rounding (the paper's "F16") --------------------------------------------
+
+def test_f16_ties_range_and_subnormals():
+    assert oracle.f16_round(1.0) == 1.0
+    assert oracle.f16_round(1.0 + 2 ** -10) == 1.0 + 2 ** -10           # representable
+    assert oracle.f16_round(1.0 + 2 ** -11) == 1.0                       # tie -> even (down)
+    assert oracle.f16_round(1.0 + 3 * 2 ** -11) == 1.0 + 2 ** -9         # tie -> even (up)
+    assert oracle.f16_round(1.0 + 2 ** -11 + 2 ** -40) == 1.0 + 2 ** -10
+    assert oracle.f16_round(-(1.0 + 3 * 2 ** -11)) == -(1.0 + 2 ** -9)
+    assert oracle.f16_round(65504.0) == 65504.0                          # largest finite
+    assert oracle.f16_round(65519.99) == 65504.0
+    assert math.isinf(oracle.f16_round(65520.0))                         # tie -> even = overflow
+    assert oracle.f16_round(2.0 ** -24) == 2.0 ** -24                    # smallest subnormal
+    assert oracle.f16_round(2.0 ** -25) == 0.0                           # tie -> even (zero)
+    assert oracle.f16_round(3 * 2.0 ** -25) == 2.0 ** -23                # tie -> even (up)
+    assert oracle.f16_round(2.0 ** -14 + 2.0 ** -25) == 2.0 ** -14       # spacing 2^-24 at the bottom normal
+
+
+def test_f16_matches_library_conversion_on_random_and_edge_floats():
+    # numpy's float32 -> float16 cast is IEEE round-to-nearest-even: an independent implementation
+    bits = rng.integers(0, 2 ** 32, size=200000, dtype=np.uint64).astype(np.uint32)
+    near = (rng.normal(size=50000) * 0.02).astype(np.float32).view(np.uint32)   # the weights' range
+    tiny = (rng.normal(size=20000) * 1e-6).astype(np.float32).view(np.uint32)   # subnormal results
+    edge = np.array([0x3f801000, 0x3f803000, 0x3f800fff, 0x3f801001, 0x33000000, 0x33800000,
+                     0x33c00000, 0x387fe000, 0x387ff000, 0x477fe000, 0x477fefff, 0x477ff000,
+                     0x7f7fffff, 0x80000000, 0x7f800000, 0xff800000], dtype=np.uint32)
+    f = np.concatenate([bits, near, tiny, edge]).view(np.float32)
+    f = f[~np.isnan(f)]
+    with np.errstate(over="ignore"):
+        want = f.astype(np.float16).view(np.uint16)
+    got = np.array([oracle.f16_bits(v) for v in f], dtype=np.uint16)
+    assert np.array_equal(got, want)
+    back = np.array([oracle.f16_round(float(v)) for v in f[:5000]])
+    with np.errstate(over="ignore"):
+        assert np.array_equal(back, f[:5000].astype(np.float16).astype(np.float64))
+
+
+def test_matvec_f16_storage_is_widened_exactly():
+    wf = np.concatenate([rng.normal(size=50) * 0.02, rng.normal(size=4) * 1e-6]).astype(np.float32).reshape(6, 9)
+    wh = wf.astype(np.float16)                                            # includes subnormal entries
+    assert np.any(np.abs(wh) < 2.0 ** -14)
+    x = rng.normal(size=9)
+    want = wh.astype(np.float64) @ x
+    assert np.allclose(oracle.matvec(wh.view(np.uint16), x, oracle.F16), want, rtol=1e-14, atol=0)
+
+
 # ---- matvec ----------------------------------------------------------------------
 
 def test_matvec_against_naive_triple_loop():
@@ -215,7 +261,12 @@ def test_attend_rounded_weights_variant():
     # un-normalised weights (1, 1/3); 1/3 rounds to bf16 0.333984375
     third = oracle.bf16_round(1.0 / 3.0)
     assert third == 0.333984375
-    out = oracle.attend(q, keys, vals, round_p=True)
+    out = oracle.attend(q, keys, vals, round_p=1)
+    assert np.allclose(out[:2], [1 / (1 + third), third / (1 + third)], rtol=1e-14)
+    # binary16: 1/3 rounds to 0.333251953125
+    third = oracle.f16_round(1.0 / 3.0)
+    assert third == 0.333251953125
+    out = oracle.attend(q, keys, vals, round_p=2)
     assert np.allclose(out[:2], [1 / (1 + third), third / (1 + third)], rtol=1e-14)
 
 

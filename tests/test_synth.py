@@ -65,3 +65,22 @@ def test_bf16_blob_is_rounded_fp32_sample(tiny_shape):
     assert g.dtype == np.float32 and np.all(g == 1.0)
     w = synth.bf16_bits_to_f32(bf).astype(np.float64)
     assert abs(w.std() - 0.02) < 2e-3
+
+
+def test_f16_blob_is_rounded_fp32_sample(tiny_shape):
+    sh = tiny_shape.scaled(dtype=synth.F16)
+    h = synth.blob_tensor(sh, synth.make_blob(sh), "l0.wq")
+    f32 = synth.blob_tensor(tiny_shape, synth.make_blob(tiny_shape), "l0.wq")
+    assert np.array_equal(h, f32.astype(np.float16).view(np.uint16))     # numpy's cast: nearest even
+    # small magnitudes (subnormal binary16 results) and the overflow edge go through the same store
+    lib = synth._load()
+    n = 4096
+    for scale in (1e-6, 3e-5, 2e4):
+        a = np.empty(n, np.float32)
+        b = np.empty(n, np.uint16)
+        lib.synth_normal_f32(5, 9, 0, n, scale, a.ctypes.data)
+        lib.synth_normal_f16(5, 9, 0, n, scale, b.ctypes.data)
+        with np.errstate(over="ignore"):
+            assert np.array_equal(b, a.astype(np.float16).view(np.uint16)), scale
+    w = synth.f16_bits_to_f32(h).astype(np.float64)
+    assert abs(w.std() - 0.02) < 2e-3
