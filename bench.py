@@ -1,19 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the decoder hot path on one MI355X.
 
-One "step" = one whole pass of the hot path over one synthetic request of the
-configuration the metric is quoted on (Qwen3-0.6B-shaped, bf16 weights and KV cache,
-fp32 accumulation, batch 1): reset the KV slot, run the 128-token prompt, then 128
-greedy decode steps with the token fed back on the device.  The paper's metric is
-tokens/s over the decoding stage (Section 4, experimental setup); `value` is that,
-summed over the K timed steps, with weights and prompt already resident in HBM.
---workload selects the larger configurations (batched requests fill every slot's
-context with prompt passes, then decode all slots together).
+One "step" = one whole pass of the hot path over one batch of synthetic requests.  The default
+workload is the largest single-GPU configuration (Qwen3-8B-shaped, bf16 weights and KV cache,
+fp32 accumulation, 16 sequences): reset the KV slots, run a 4096-token prompt pass per slot
+(2048-token matrix-core blocks), read the 16 first tokens back, then 128 greedy decode steps of
+all 16 sequences with the tokens fed back on the device.  The paper's metric is tokens/s over
+the decoding stage (Section 4, experimental setup); `value` is that, summed over the K timed
+steps, with weights and prompts already resident in HBM.  --workload selects the other
+configurations (the batch-1 ones decode inside one resident kernel launch per request).
 
-Prints ONE JSON line.  `roofline`: algorithmic bytes of the decode launches (every weight
-element and every cached K/V element once per step) over their duration, against the
-published HBM peak, plus the HBM traffic measured with counters where a summary for the
-workload is committed.  `cpu_baseline`: the fp64 CPU oracle timed on a bounded sample.
+Prints ONE JSON line.  `roofline`: the dominant decode kernel (by summed time), its algorithmic
+bytes per launch (every weight element of its matrix once) over its average launch duration,
+measured with HIP events on the model's stream, against the published HBM peak, plus the HBM
+traffic per launch measured with counters where a summary for the workload is committed.
+`roofline_prefill_gemm`: the same for the prompt GEMM kernel against the bf16 matrix-core peak.
+`cpu_baseline`: the fp64 CPU oracle timed on a bounded sample.  `parity`: a short leg that
+compares logits with the oracle (live for the small models, against the committed full-depth
+expected values of the oracle for the 4B / 8B workloads).
 """
 from __future__ import annotations
 
@@ -47,10 +51,11 @@ def algorithmic_bytes_per_decode_step(shape, ctx_mean: float, batch: int = 1) ->
     return float(weights + kv)
 
 
-def counter_traffic(workload: str, decode_steps: int):
-    """HBM bytes per launch of the resident kernel as measured with rocprofv3 counters
-    (FETCH_SIZE + WRITE_SIZE, scaled by a known copy); read from the committed summary of
-    that measurement, which is valid for the same workload only.  None if there is none."""
+def counter_traffic(workload: str, kernel: str, decode_steps: int):
+    """Mean HBM bytes per launch of `kernel` as measured with rocprofv3 counters (FETCH_SIZE +
+    WRITE_SIZE, each scaled by what it reads for a known copy); taken from the committed summary
+    of that measurement, which is valid for the same workload and kernel only.  None if there
+    is none."""
     pdir = os.path.join(ROOT, "profiles")
     try:
         names = sorted(n for n in os.listdir(pdir) if n.endswith("__hbm_traffic.txt"))
@@ -60,9 +65,17 @@ def counter_traffic(workload: str, decode_steps: int):
         for line in open(os.path.join(pdir, name)):
             if line.startswith("traffic_bytes_per_launch="):
                 kv = dict(f.split("=") for f in line.split())
-                if kv.get("workload") == workload and int(kv.get("decode_steps", -1)) == decode_steps:
+                if (kv.get("workload") == workload and kv.get("kernel", "k_decode_resident") == kernel
+                        and int(kv.get("decode_steps", decode_steps)) == decode_steps):
                     return int(kv["traffic_bytes_per_launch"])
     return None
+
+
+KERNEL_OF_FAMILY = {"gemm_skinny": "k_gemm_skinny", "attn_partial": "k_attn_partial_mc",
+                    "rmsnorm_pack": "k_rmsnorm_pack", "attn_combine": "k_attn_combine",
+                    "gemm_prefill": "k_gemm_prefill_dl", "attn_prefill": "k_attn_prefill"}
+GOLDEN = {"qwen3-4b-bf16-b1-c2048-d128": "cfg3", "qwen3-4b-bf16-b8-c2048-d128": "cfg3",
+          "qwen3-8b-bf16-b16-c4096-d128": "cfg4"}
 
 
 def resident_stage_trace(model, nnc, shape, prompt):
@@ -99,13 +112,56 @@ def resident_stage_trace(model, nnc, shape, prompt):
     return out
 
 
+def percentile(v, q):
+    v = sorted(v)
+    return v[min(len(v) - 1, int(round(q * (len(v) - 1))))]
+
+
+def compare(model, prompt, want):
+    """GPU logits of slot 0's prompt pass and of decode steps teacher-forced on the expected
+    tokens against `want` = [(fp64 logits, greedy token)]: max abs error, agreement, margin."""
+    import numpy as np
+    model.kv_reset(0)
+    lg, _ = model.prefill(0, prompt)
+    got = [lg.double().cpu().numpy()]
+    for i in range(len(want) - 1):
+        lg, _ = model.decode_step([0], [want[i][1]])
+        got.append(lg[0].double().cpu().numpy())
+    err, agree, margin = 0.0, 0, float("inf")
+    for g, (lo, t) in zip(got, want):
+        err = max(err, float(np.abs(g - lo).max()))
+        part = np.partition(lo, -2)
+        margin = min(margin, float(part[-1] - part[-2]))
+        agree += int(int(np.argmax(g)) == t)
+    return {"positions": len(want), "max_abs_err": round(err, 6), "greedy_agreement": round(agree / len(want), 4),
+            "min_margin": round(margin, 6)}
+
+
+def parity_full_depth(model, workload, prompt):
+    """Slot 0 at the workload's full context against the expected values the oracle wrote offline
+    (tests/golden/, full depth; prompt blocks mirrored); None where no such file is committed."""
+    import numpy as np
+    gold = GOLDEN.get(workload)
+    path = os.path.join(ROOT, "tests", "golden", f"{gold}_slot0_mirrored.npz") if gold else None
+    if not path or not os.path.exists(path):
+        return None
+    z = np.load(path)
+    want = [(z["logits"][i].astype(np.float64), int(z["next"][i])) for i in range(len(z["next"]))]
+    out = compare(model, prompt, want)
+    out["reference"] = "full-depth oracle values written offline (prompt rounding points mirrored), full context"
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="qwen3-0.6b-bf16-b1-p128-d128", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="qwen3-8b-bf16-b16-c4096-d128", choices=sorted(WORKLOADS))
+    ap.add_argument("--decode-steps", type=int, default=0,
+                    help="decode steps per request instead of the workload's (short profiler runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-parity", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing sample")
     ap.add_argument("--stage-trace", action="store_true",
                     help="batch-1 workloads: add the resident decode kernel's per-stage wall-clock times of one step")
@@ -120,10 +176,18 @@ def main() -> int:
     import synth
     from paper_2512_21571_amd import binding as nnc
 
+    def note(msg):                                   # progress on stderr; stdout carries the one JSON line
+        print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
     shape_key, B, T, S = WORKLOADS[args.workload]
+    if args.decode_steps > 0:
+        S = args.decode_steps
     shape = synth.SHAPES[shape_key]
+    note(f"workload {args.workload}: generating the weight blob")
     blob = synth.make_blob(shape)
-    model = nnc.Model(shape, blob, B, T + S)
+    note(f"blob {blob.nbytes / 1e9:.2f} GB; creating the model (upload + repack)")
+    model = nnc.Model(shape, blob, B, T + S + 8)       # + the few extra steps of the per-kernel leg
+    note("model ready; warm-up passes")
     prompts = [synth.tokens(T, shape.vocab, stream=b) for b in range(B)]
     prompt = prompts[0]
     slots = list(range(B))
@@ -142,16 +206,17 @@ def main() -> int:
         toks, _ = model.decode_greedy(slots, firsts, S)
         if events:
             events[3].record(stream)
-        return toks
+        return toks, firsts
 
     for _ in range(args.warmup):
         one_pass()
     torch.cuda.synchronize()
+    note(f"timing {args.steps} passes")
 
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for k in range(args.steps):
-        toks = one_pass(evs[k])
+        toks, firsts = one_pass(evs[k])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     prefill_ms = sum(e[0].elapsed_time(e[1]) for e in evs)
@@ -162,30 +227,77 @@ def main() -> int:
     step_bytes = algorithmic_bytes_per_decode_step(shape, ctx_mean, B)
     decode_ms_per_token = decode_ms / (args.steps * S)   # per decode step (B tokens)
 
-    # The dominant kernel: at batch 1 the resident decode kernel runs all S steps of a request
-    # in one launch, so the HIP events around nnc_decode_greedy (recorded on the stream the
-    # kernel is launched on) bracket exactly that launch plus one 512-byte copy of the token
-    # log.  Algorithmic bytes per launch = S decode steps x bytes per step (weights once per
-    # step, cached K/V rows once per step).  At batch > 1 the same events bracket S replays of
-    # the captured per-stage graph, reported as one unit.
-    launch_ms = decode_ms / args.steps
-    launch_bytes = step_bytes * S
-    achieved = launch_bytes / (launch_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "k_decode_resident" if B == 1 else "decode step graph (per-stage kernels)",
-                "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": counter_traffic(args.workload, S),
-                "launches": args.steps, "avg_launch_us": round(launch_ms * 1e3, 1),
-                "bytes_per_launch": round(launch_bytes)}
+    # per-step latency of the single-step entry point (one call per step, events between calls):
+    # p50 / p99 over the S steps that follow the timed passes' prompt state
+    note("timed passes done; per-step latency leg")
+    toks_host = toks.cpu().numpy()
+    model.kv_reset(-1)
+    firsts = [int(model.prefill(b, prompts[b], want_logits=False)[1].item()) for b in slots]
+    lat_ev = [torch.cuda.Event(enable_timing=True) for _ in range(S + 1)]
+    cur = firsts
+    lat_ev[0].record(stream)
+    nxt_dev = None
+    for i in range(S):
+        _, nxt_dev = model.decode_step(slots, cur, want_logits=False)
+        lat_ev[i + 1].record(stream)
+        cur = [int(v) for v in toks_host[i]]         # the tokens the greedy loop produced (same state)
+    torch.cuda.synchronize()
+    lat = [lat_ev[i].elapsed_time(lat_ev[i + 1]) for i in range(S)]
+    step_latency = {"p50": round(percentile(lat, 0.5), 4), "p99": round(percentile(lat, 0.99), 4),
+                    "mean": round(sum(lat) / len(lat), 4), "unit": "ms",
+                    "what": "nnc_decode_step, one call per step, tokens passed from the host"}
 
-    # per-kernel durations of the per-stage path (prompt pass and its kernels): the same request
-    # again with every launch bracketed by HIP events inside the library
+    # The dominant decode kernel.  Batch 1: the resident kernel runs all S steps of a request in
+    # one launch, bracketed by the events around nnc_decode_greedy (recorded on the stream the
+    # kernel is launched on); algorithmic bytes per launch = S x bytes per step.  Batch > 1: a
+    # step is a graph of per-stage kernels; a few more steps run eagerly with every launch
+    # bracketed by HIP events inside the library (same kernels, same arguments), the kernel with
+    # the largest summed time is reported with its own algorithmic bytes (every weight element
+    # of the launched matrix once) and its own mean duration.
+    note("per-kernel event legs")
+    decode_kernels = None
+    if B == 1:
+        launch_ms = decode_ms / args.steps
+        launch_bytes = step_bytes * S
+        achieved = launch_bytes / (launch_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "k_decode_resident", "achieved": round(achieved, 1),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": counter_traffic(args.workload, "k_decode_resident", S),
+                    "launches": args.steps, "avg_launch_us": round(launch_ms * 1e3, 1),
+                    "bytes_per_launch": round(launch_bytes)}
+    else:
+        model.profile_begin()
+        model.decode_greedy(slots, cur, 4)
+        dstats = model.profile_end()
+        decode_kernels = [{"name": KERNEL_OF_FAMILY.get(r["name"], r["name"]), "launches": r["launches"],
+                           "total_ms": round(r["total_ms"], 4),
+                           "algorithmic_GBps": round(r["bytes"] / (r["total_ms"] * 1e-3) / 1e9, 1) if r["total_ms"] > 0 else None}
+                          for r in dstats]
+        dom = max(dstats, key=lambda r: r["total_ms"])
+        kname = KERNEL_OF_FAMILY.get(dom["name"], dom["name"])
+        achieved = dom["bytes"] / (dom["total_ms"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": counter_traffic(args.workload, kname, S),
+                    "launches": dom["launches"], "avg_launch_us": round(dom["total_ms"] * 1e3 / dom["launches"], 2),
+                    "bytes_per_launch": round(dom["bytes"] / dom["launches"])}
+
+    # per-kernel durations of the prompt pass: the same request again with every launch
+    # bracketed by HIP events inside the library
     model.kv_reset(0)
     model.profile_begin()
     model.prefill(0, prompt, want_logits=False)
     stats = model.profile_end()
     gemm = [r for r in stats if r["name"] == "gemm_prefill" and r["total_ms"] > 0]
     prefill_gemm_tflops = gemm[0]["flops"] / (gemm[0]["total_ms"] * 1e-3) / 1e12 if gemm else None
+    roofline_pg = None
+    if gemm:
+        roofline_pg = {"bound": "mfma", "kernel": "k_gemm_prefill_dl", "achieved": round(prefill_gemm_tflops, 1),
+                       "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                       "frac": round(prefill_gemm_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                       "launches": gemm[0]["launches"],
+                       "avg_launch_us": round(gemm[0]["total_ms"] * 1e3 / gemm[0]["launches"], 2),
+                       "flops_per_launch": round(gemm[0]["flops"] / gemm[0]["launches"])}
 
     # one plain device-to-device copy of known size (1 GiB read + 1 GiB written), untimed: the
     # reference a counter run (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) scales its readings by
@@ -199,20 +311,39 @@ def main() -> int:
     if args.stage_trace and B == 1:
         stage_trace = resident_stage_trace(model, nnc, shape, prompt)
 
+    note("parity and oracle legs")
+    parity = None if args.no_parity else parity_full_depth(model, args.workload, prompt)
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
         o = oracle.from_shape(shape, blob, 1, 16 + S)
         ctx0 = 16                                    # short prompt so the sample is mostly decode
-        _, t = o.prefill(0, prompt[:ctx0], oracle.ROUND_KV)
+        lo, t = o.prefill(0, prompt[:ctx0], oracle.ROUND_KV)
+        want = [(lo, t)]
         n, c0 = 0, time.perf_counter()
         while n < S and time.perf_counter() - c0 < args.cpu_seconds:
-            _, t = o.step_token(0, t, oracle.ROUND_KV)
+            lo, t = o.step_token(0, t, oracle.ROUND_KV)
+            want.append((lo, t))
             n += 1
         dt = time.perf_counter() - c0
         cpu = {"value": round(n / dt, 3), "unit": "tokens/s", "cores": oracle.get_threads(), "kind": "oracle",
-               "sample": f"{n} greedy decode steps of the same model after a {ctx0}-token prompt, fp64, "
-                         f"{oracle.get_threads()} OpenMP threads"}
+               "sample": f"{n} greedy decode steps of one sequence of the same model after a {ctx0}-token prompt "
+                         f"(the workload's context is {T}: cached rows add {100.0 * shape.n_layers * 2 * shape.dq * T / (sum_macs(shape)):.0f} % "
+                         f"to the multiply-adds of a step), fp64, {oracle.get_threads()} OpenMP threads"}
+        if not args.no_parity:
+            # the oracle run just timed doubles as a reference: the same short request on the GPU
+            cpu["parity_of_the_sample"] = compare(model, prompt[:ctx0], want)
+        if B == 1 and shape.hidden <= 2048:
+            # the paper's single-thread rows (Section 4.1) have a counterpart: the oracle on one thread
+            threads = oracle.get_threads()
+            oracle.set_threads(1)
+            n1, c1 = 0, time.perf_counter()
+            while n1 < 8 and time.perf_counter() - c1 < args.cpu_seconds / 2:
+                _, t = o.step_token(0, t, oracle.ROUND_KV)
+                n1 += 1
+            cpu["one_thread_tokens_per_s"] = round(n1 / (time.perf_counter() - c1), 3)
+            oracle.set_threads(threads)
 
     out = {
         "metric": "decode tokens/s + achieved HBM GB/s fraction; prefill tokens/s + MFMA util",
@@ -224,19 +355,28 @@ def main() -> int:
         "decode_ms_per_token": round(decode_ms_per_token, 5),
         "decode_hbm_frac_step": round(step_bytes / (decode_ms_per_token * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
         "decode_algorithmic_bytes_per_step": round(step_bytes),
+        "decode_step_latency_ms": step_latency,
         "prefill_tokens_per_s": round(prefill_tok_s, 1),
         "prefill_ms": round(prefill_ms / args.steps, 4),
         "prefill_gemm_tflops": round(prefill_gemm_tflops, 1) if prefill_gemm_tflops else None,
         "prefill_gemm_mfma_frac": round(prefill_gemm_tflops / MFMA_BF16_PEAK_TFLOPS, 4) if prefill_gemm_tflops else None,
         "roofline": roofline,
-        "prefill_kernels": [{"name": r["name"], "launches": r["launches"], "total_ms": round(r["total_ms"], 4)}
-                            for r in stats],
+        "roofline_prefill_gemm": roofline_pg,
+        "decode_kernels": decode_kernels,
+        "prefill_kernels": [{"name": KERNEL_OF_FAMILY.get(r["name"], r["name"]), "launches": r["launches"],
+                             "total_ms": round(r["total_ms"], 4)} for r in stats],
+        "parity": parity,
         "cpu_baseline": cpu,
     }
     if stage_trace is not None:
         out["decode_stage_trace_us"] = stage_trace
     print(json.dumps(out))
     return 0
+
+
+def sum_macs(shape) -> float:
+    per_layer = (shape.dq + 2 * shape.dkv) * shape.hidden + shape.hidden * shape.dq + 3 * shape.ffn * shape.hidden
+    return float(shape.n_layers * per_layer + shape.vocab * shape.hidden)
 
 
 if __name__ == "__main__":

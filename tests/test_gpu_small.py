@@ -307,9 +307,14 @@ def test_prompt_tail_beside_the_last_block_equals_tail_after_it(nnc):
 def test_random_requests_against_oracle(nnc):
     """Seeded random requests (shape, batch, ragged prompt lengths across the block and piece
     boundaries, decode steps, forced kernel shapes, fused / separate kernels, resident / per-stage
-    decode) against the oracle: logits within tolerance, every greedy token equal."""
+    decode) against the oracle: logits within tolerance at every step, every greedy token equal
+    unless the oracle's top-2 margin is within 4x that step's measured error (a tie within error:
+    counted and printed).  A sequence whose on-device greedy loop leaves the oracle's tokens at
+    such a tie is decoded again, teacher-forced on the oracle's tokens, so that every step of
+    every request is compared."""
     import random
     rng = random.Random(20251)
+    ties = []
     for case in range(14):
         shape = rng.choice([SMALL_BF16, SMALL_G4])
         batch = rng.choice([1, 1, 2, 3, 5])
@@ -325,10 +330,11 @@ def test_random_requests_against_oracle(nnc):
         g.set_option(nnc.OPT_FUSE_QK, fuse)
         g.set_option(nnc.OPT_PERSISTENT, pers)
         fl = oracle_flags(shape)
-        firsts = []
+        firsts, prompts = [], []
         for b in range(batch):
             nb = max(1, n - 7 * b)
             toks = synth.tokens(nb, shape.vocab, stream=1000 * case + b)
+            prompts.append(toks)
             lg, ng = g.prefill(b, toks)
             lo, no = oracle_prefill_like_library(o, b, toks, shape)
             one_piece = any(pc == 1 for _, _, pc in prefill_blocks(nb))
@@ -337,22 +343,60 @@ def test_random_requests_against_oracle(nnc):
             firsts.append(no)
         toks_g, logits_g = g.decode_greedy(list(range(batch)), firsts, steps, want_logits=True)
         cur = list(firsts)
-        following = True
+        left = [False] * batch            # the device loop of this sequence has left the oracle's tokens
+        fed, want = [], []                # per step: the oracle's input tokens, its logits
         for s_ in range(steps):
-            if not following:
-                break
+            fed.append(list(cur))
+            want.append([])
             for b in range(batch):
                 lo, nx = o.step_token(b, cur[b], fl)
-                _check_logits(shape, logits_g[s_, b], lo, BF16_ABS_PROMPT)
-                if int(toks_g[s_, b].item()) != nx:
-                    # only a tie within the logit error may flip the greedy token; the on-device
-                    # loop then continues from its own token and the comparison of this case ends
-                    err = np.abs(logits_g[s_, b].double().cpu().numpy() - lo).max()
-                    top = np.sort(lo)[-2:]
-                    assert top[1] - top[0] <= 2 * err, (case, s_, b)
-                    following = False
-                    break
+                want[-1].append(lo)
+                if not left[b]:
+                    _check_logits(shape, logits_g[s_, b], lo, BF16_ABS_PROMPT)
+                    if int(toks_g[s_, b].item()) != nx:
+                        err = np.abs(logits_g[s_, b].double().cpu().numpy() - lo).max()
+                        top = np.sort(lo)[-2:]
+                        assert top[1] - top[0] < 4 * err, (case, s_, b, top[1] - top[0], err)
+                        ties.append((case, s_, b, float(top[1] - top[0]), float(err)))
+                        left[b] = True
                 cur[b] = nx
+        if any(left):
+            g.kv_reset(-1)
+            for b in range(batch):
+                g.prefill(b, prompts[b], want_logits=False)
+            for s_ in range(steps):
+                lg, _ = g.decode_step(list(range(batch)), fed[s_])
+                for b in range(batch):
+                    _check_logits(shape, lg[b], want[s_][b], BF16_ABS_PROMPT)
+    print(f"ties within error (case, step, slot, oracle margin, max abs error): {ties}", flush=True)
+    assert len(ties) <= 1, ties
+
+
+@pytest.mark.parametrize("shape", [SMALL_BF16, SMALL_G4], ids=lambda s: s.name)
+def test_default_long_prompt_against_the_unmirrored_oracle(nnc, shape):
+    """A 2100-token prompt in the default mode (a 2048-token block with matrix-core inputs
+    rounded to bf16 once, then a 36-token block with two pieces, then the fp32-grade 16-token
+    tail) against the oracle with NO mirrored rounding, only the 16-bit cache: the stated bar
+    (3e-2, greedy agreement) must hold against the exact definition too, and the decode steps
+    that follow read that cache."""
+    print(f"case: default-mode 2100-token prompt vs the plain oracle, {shape.name}", flush=True)
+    g, o = _pair(nnc, shape, 1, 2120, exact_prefill=False)
+    toks = synth.tokens(2100, shape.vocab, stream=33)
+    fl = oracle_flags(shape)
+    lg, ng = g.prefill(0, toks)
+    lo, no = o.prefill(0, toks, fl)
+    errs = [float(np.abs(lg.double().cpu().numpy() - lo).max())]
+    assert int(ng.item()) == no or np.sort(lo)[-1] - np.sort(lo)[-2] < 4 * errs[0]
+    t = no
+    for _ in range(6):
+        lg, ng = g.decode_step([0], [t])
+        lo, no = o.step_token(0, t, fl)
+        errs.append(float(np.abs(lg[0].double().cpu().numpy() - lo).max()))
+        assert int(ng.item()) == no or np.sort(lo)[-1] - np.sort(lo)[-2] < 4 * errs[-1]
+        t = no
+    print(f"  max abs logit error vs the plain oracle: prompt {errs[0]:.3e}, decode {max(errs[1:]):.3e}; "
+          f"|logit| max {np.abs(lo).max():.2f}", flush=True)
+    assert max(errs) <= BF16_ABS
 
 
 def test_large_block_prefill_two_pieces_at_any_length(nnc):
