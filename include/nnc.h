@@ -131,6 +131,28 @@ nnc_status nnc_decode_greedy(nnc_model *m, const uint32_t *slots, const int32_t 
                              uint32_t batch, uint32_t n_steps, int32_t *tokens_out,
                              float *logits_out);
 
+/*
+ * nnc_decode_step for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * results bit for bit as nnc_decode_step when that is called with a logits buffer (one kernel
+ * per stage, launched eagerly on the model's stream), but the call allocates nothing: no
+ * device or host memory, no graph, no event.  Its workspace is a fixed array of
+ * NNC_STATIC_SCRATCH_MIB MiB inside the library's code object, one copy per GPU, held from
+ * the first use until the process ends.
+ * Limits: batch <= NNC_STATIC_MAX_BATCH, and the step's workspace (it grows with batch x
+ * hidden / ffn sizes and with batch x query heads x cached positions; without logits_out also
+ * batch x vocab floats) must fit the array: NNC_E_ARG with the byte counts otherwise, state
+ * untouched.  NNC_E_STATE while nnc_profile_begin is active or if the model's GPU is not the
+ * current device.
+ * Every call on one GPU shares that GPU's array, whatever the model or stream: calls that
+ * overlap on one GPU race.  Nothing in the array has to start at zero (every word a kernel
+ * reads was written earlier in the same call), so no call clears it.
+ */
+#define NNC_STATIC_SCRATCH_MIB 24
+#define NNC_STATIC_MAX_BATCH 8
+nnc_status nnc_decode_step_static(nnc_model *m, const uint32_t *slots, const int32_t *tokens,
+                                  uint32_t batch, float *logits_out, int32_t *next_out);
+
 /* Forget the contents of one slot (slot >= 0) or of all slots (slot = -1). */
 nnc_status nnc_kv_reset(nnc_model *m, int32_t slot);
 

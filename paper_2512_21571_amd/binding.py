@@ -20,7 +20,8 @@ OPT_TAIL_OVERLAP = 8
 
 # every symbol include/nnc.h declares
 EXPORTS = [
-    "nnc_model_create", "nnc_model_destroy", "nnc_prefill", "nnc_decode_step", "nnc_decode_greedy",
+    "nnc_model_create", "nnc_model_destroy", "nnc_prefill", "nnc_decode_step", "nnc_decode_step_static",
+    "nnc_decode_greedy",
     "nnc_kv_reset", "nnc_synchronize", "nnc_slot_len", "nnc_prefill_hidden", "nnc_decode_step_hidden", "nnc_kv_read",
     "nnc_set_option", "nnc_profile_begin", "nnc_profile_end", "nnc_stage_trace", "nnc_blob_bytes",
     "nnc_last_error",
@@ -74,6 +75,7 @@ def lib():
             "nnc_model_destroy": (None, [vp]),
             "nnc_prefill": (i32, [vp, u32, vp, u32, vp, vp]),
             "nnc_decode_step": (i32, [vp, vp, vp, u32, vp, vp]),
+            "nnc_decode_step_static": (i32, [vp, vp, vp, u32, vp, vp]),
             "nnc_decode_greedy": (i32, [vp, vp, vp, u32, u32, vp, vp]),
             "nnc_kv_reset": (i32, [vp, i32]),
             "nnc_synchronize": (i32, [vp]),
@@ -211,6 +213,19 @@ class Model:
         try:
             _check(lib().nnc_decode_step(self.h, s.ctypes.data, t.ctypes.data, b,
                                          logits.data_ptr() if want_logits else None, nxt.data_ptr()))
+        finally:
+            self._after()
+        return logits, nxt
+
+    def decode_step_static(self, slots, tokens, logits=None, nxt=None):
+        """nnc_decode_step_static: the caller passes the output tensors (nothing is allocated,
+        here or in the library); either may be None."""
+        s, t = _u32(slots), _i32(tokens)
+        self._before()
+        try:
+            _check(lib().nnc_decode_step_static(self.h, s.ctypes.data, t.ctypes.data, s.size,
+                                                logits.data_ptr() if logits is not None else None,
+                                                nxt.data_ptr() if nxt is not None else None))
         finally:
             self._after()
         return logits, nxt

@@ -1160,6 +1160,112 @@ nnc_status nnc_decode_step(nnc_model* m, const uint32_t* slots, const int32_t* t
   return NNC_OK;
 }
 
+// ---- decode step for callers that cannot allocate -------------------------------
+// The workspace of the pass (column state, residual stream, projection outputs, packed operands,
+// k-slice partials, attention partials, logits, arg-max partials) lives in one file-scope
+// device array instead of buffers obtained at create.  Host code never uses the array's name
+// as an address: the per-device address comes from hipGetSymbolAddress, once per device.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)NNC_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+unsigned char* g_scratch_ptr[MAX_DEVICES] = {};  // this device's copy of `scratch`, by device ordinal
+
+// Workspace pointers of the model while a pass runs out of the static array; restored on exit.
+struct WorkspaceSwap {
+  nnc_model* m;
+  ColState* st; float *x, *qkv, *rpart, *partial, *logits, *am_val; void *Xp, *Ap, *qsplit;
+  int32_t *am_idx, *next; int max_chunks;
+  explicit WorkspaceSwap(nnc_model* m_)
+      : m(m_), st(m_->st), x(m_->x), qkv(m_->qkv), rpart(m_->rpart), partial(m_->partial), logits(m_->logits),
+        am_val(m_->am_val), Xp(m_->Xp), Ap(m_->Ap), qsplit(m_->qsplit), am_idx(m_->am_idx), next(m_->next),
+        max_chunks(m_->max_chunks) {}
+  ~WorkspaceSwap() {
+    m->st = st; m->x = x; m->qkv = qkv; m->rpart = rpart; m->partial = partial; m->logits = logits;
+    m->am_val = am_val; m->Xp = Xp; m->Ap = Ap; m->qsplit = qsplit; m->am_idx = am_idx; m->next = next;
+    m->max_chunks = max_chunks;
+  }
+};
+}  // namespace
+
+nnc_status nnc_decode_step_static(nnc_model* m, const uint32_t* slots, const int32_t* tokens, uint32_t batch,
+                                  float* logits_out, int32_t* next_out) {
+  if (!m || !tokens) return fail(NNC_E_ARG, "NULL argument");
+  if (!m->c.has_embed_and_head) return fail(NNC_E_STATE, "model has no embedding");
+  if (m->profiling) return fail(NNC_E_STATE, "per-kernel profiling creates events; not available here");
+  if (resident_failed(m, false))
+    return fail(NNC_E_DEVICE, "an earlier resident decode launch gave up waiting for an exchange word; recreate the model");
+  if (batch > NNC_STATIC_MAX_BATCH)
+    return fail(NNC_E_ARG, "batch %u exceeds the static workspace limit of %d sequences", batch, NNC_STATIC_MAX_BATCH);
+  if (nnc_status st = check_slots(m, slots, batch, 1)) return st;
+  for (uint32_t i = 0; i < batch; ++i)
+    if (tokens[i] < 0 || (uint32_t)tokens[i] >= m->c.vocab) return fail(NNC_E_ARG, "token %d out of range", tokens[i]);
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev != m->device) return fail(NNC_E_STATE, "the model lives on device %d, the current device is %d", m->device, dev);
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(NNC_E_DEVICE, "device ordinal %d not supported", dev);
+
+  // carve the workspace; sizes follow this call's batch and longest context, not max_seq
+  uint32_t max_pos = 0;
+  for (uint32_t i = 0; i < batch; ++i) max_pos = std::max(max_pos, m->len[slots[i]]);
+  const int nsplit = decode_nsplit(m, batch), grid_chunks = chunks_grid(max_pos);
+  const size_t H = m->H(), Dq = m->Dq(), Dkv = m->Dkv(), F = m->F(), V = m->V(), w = m->esz(), B = batch;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off += (bytes + 255) / 256 * 256;
+    return at;
+  };
+  const size_t o_st = take(sizeof(ColState)), o_x = take(B * H * 4), o_qkv = take(B * (Dq + 2 * Dkv) * 4),
+               o_Xp = take(B * nsplit * H * w), o_Ap = take(B * nsplit * std::max(Dq, F) * w),
+               o_rpart = take((size_t)MAX_KSPLIT * B * H * 4),
+               o_partial = take(B * m->c.n_q_heads * (size_t)grid_chunks * 132 * 4),
+               o_qsplit = take(B * m->c.n_q_heads * 3 * 128 * 2), o_next = take(B * 4), o_amv = take(B * 64 * 4),
+               o_ami = take(B * 64 * 4), o_logits = logits_out ? 0 : take(B * V * 4);
+  if (off > STATIC_SCRATCH_BYTES)
+    return fail(NNC_E_ARG, "this step needs %zu bytes of workspace (batch %u, context %u); the static workspace holds %zu",
+                off, batch, max_pos + 1, STATIC_SCRATCH_BYTES);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(NNC_E_DEVICE, "hipGetSymbolAddress returned NULL");
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+  }
+  unsigned char* base = g_scratch_ptr[dev];
+
+  WorkspaceSwap keep(m);
+  m->st = reinterpret_cast<ColState*>(base + o_st);
+  m->x = reinterpret_cast<float*>(base + o_x);
+  m->qkv = reinterpret_cast<float*>(base + o_qkv);
+  m->Xp = base + o_Xp;
+  m->Ap = base + o_Ap;
+  m->rpart = reinterpret_cast<float*>(base + o_rpart);
+  m->partial = reinterpret_cast<float*>(base + o_partial);
+  m->max_chunks = grid_chunks;  // row stride of the partial records
+  m->qsplit = base + o_qsplit;
+  m->next = reinterpret_cast<int32_t*>(base + o_next);
+  m->am_val = reinterpret_cast<float*>(base + o_amv);
+  m->am_idx = reinterpret_cast<int32_t*>(base + o_ami);
+
+  double kv_rows = 0;
+  if (nnc_status st = set_decode_state(m, slots, tokens, batch, &max_pos, &kv_rows)) return st;
+  Pass p;
+  p.decode = true;
+  p.ncols = (int)batch;
+  p.nsplit = nsplit;
+  p.head_ncols = (int)batch;
+  p.logits = logits_out ? logits_out : reinterpret_cast<float*>(base + o_logits);
+  p.logits_ld = (long)V;
+  p.next = next_out ? m->next : nullptr;
+  p.grid_chunks = grid_chunks;
+  p.kv_rows = kv_rows;
+  if (nnc_status st = run_pass(m, p)) return st;
+  if (next_out) HIP_TRY(hipMemcpyAsync(next_out, m->next, batch * 4, hipMemcpyDeviceToDevice, m->stream));
+  for (uint32_t i = 0; i < batch; ++i) m->len[slots[i]] += 1;
+  return NNC_OK;
+}
+
 nnc_status nnc_decode_greedy(nnc_model* m, const uint32_t* slots, const int32_t* first_tokens, uint32_t batch,
                              uint32_t n_steps, int32_t* tokens_out, float* logits_out) {
   if (!m || !first_tokens || !tokens_out) return fail(NNC_E_ARG, "NULL argument");
