@@ -78,6 +78,24 @@ GOLDEN = {"qwen3-4b-bf16-b1-c2048-d128": "cfg3", "qwen3-4b-bf16-b8-c2048-d128": 
           "qwen3-8b-bf16-b16-c4096-d128": "cfg4"}
 
 
+def by_kernel(stats):
+    """Per-kernel records from the library's per-family ones (the skinny GEMM reports one family
+    per matrix it streams: added up here, kept separately as `parts`)."""
+    out = {}
+    for r in stats:
+        fam = r["name"]
+        k = KERNEL_OF_FAMILY.get(fam.split(".")[0], fam)
+        d = out.setdefault(k, {"name": k, "launches": 0, "total_ms": 0.0, "bytes": 0.0, "flops": 0.0, "parts": {}})
+        for f in ("launches", "total_ms", "bytes", "flops"):
+            d[f] += r[f]
+        if "." in fam and r["total_ms"] > 0:
+            d["parts"][fam.split(".", 1)[1]] = {"launches": r["launches"],
+                                                 "avg_us": round(r["total_ms"] * 1e3 / r["launches"], 2),
+                                                 "GBps": round(r["bytes"] / (r["total_ms"] * 1e-3) / 1e9, 1),
+                                                 "TFLOPs": round(r["flops"] / (r["total_ms"] * 1e-3) / 1e12, 1)}
+    return list(out.values())
+
+
 def resident_stage_trace(model, nnc, shape, prompt):
     """Per-stage times of one decode step inside the resident kernel: every workgroup stamps the
     100 MHz wall clock at its stage boundaries; mean / fastest / slowest workgroup of the
@@ -160,6 +178,9 @@ def main() -> int:
     ap.add_argument("--workload", default="qwen3-8b-bf16-b16-c4096-d128", choices=sorted(WORKLOADS))
     ap.add_argument("--decode-steps", type=int, default=0,
                     help="decode steps per request instead of the workload's (short profiler runs)")
+    ap.add_argument("--prefill-block", type=int, default=0,
+                    help="tokens per block of the prompt pass (NNC_OPT_PREFILL_BLOCK; 0 = the library's default)")
+    ap.add_argument("--prefill-tile", type=int, default=-1, help="force a block tile of the prompt GEMMs (NNC_OPT_PREFILL_TILE)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing sample")
@@ -187,6 +208,10 @@ def main() -> int:
     blob = synth.make_blob(shape)
     note(f"blob {blob.nbytes / 1e9:.2f} GB; creating the model (upload + repack)")
     model = nnc.Model(shape, blob, B, T + S + 8)       # + the few extra steps of the per-kernel leg
+    if args.prefill_block:
+        model.set_option(nnc.OPT_PREFILL_BLOCK, args.prefill_block)
+    if args.prefill_tile >= 0:
+        model.set_option(nnc.OPT_PREFILL_TILE, args.prefill_tile)
     note("model ready; warm-up passes")
     prompts = [synth.tokens(T, shape.vocab, stream=b) for b in range(B)]
     prompt = prompts[0]
@@ -268,13 +293,13 @@ def main() -> int:
     else:
         model.profile_begin()
         model.decode_greedy(slots, cur, 4)
-        dstats = model.profile_end()
-        decode_kernels = [{"name": KERNEL_OF_FAMILY.get(r["name"], r["name"]), "launches": r["launches"],
-                           "total_ms": round(r["total_ms"], 4),
-                           "algorithmic_GBps": round(r["bytes"] / (r["total_ms"] * 1e-3) / 1e9, 1) if r["total_ms"] > 0 else None}
+        dstats = by_kernel(model.profile_end())
+        decode_kernels = [{"name": r["name"], "launches": r["launches"], "total_ms": round(r["total_ms"], 4),
+                           "algorithmic_GBps": round(r["bytes"] / (r["total_ms"] * 1e-3) / 1e9, 1) if r["total_ms"] > 0 else None,
+                           **({"parts": r["parts"]} if r["parts"] else {})}
                           for r in dstats]
         dom = max(dstats, key=lambda r: r["total_ms"])
-        kname = KERNEL_OF_FAMILY.get(dom["name"], dom["name"])
+        kname = dom["name"]
         achieved = dom["bytes"] / (dom["total_ms"] * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1),
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -287,8 +312,8 @@ def main() -> int:
     model.kv_reset(0)
     model.profile_begin()
     model.prefill(0, prompt, want_logits=False)
-    stats = model.profile_end()
-    gemm = [r for r in stats if r["name"] == "gemm_prefill" and r["total_ms"] > 0]
+    stats = by_kernel(model.profile_end())
+    gemm = [r for r in stats if r["name"] == "k_gemm_prefill_dl" and r["total_ms"] > 0]
     prefill_gemm_tflops = gemm[0]["flops"] / (gemm[0]["total_ms"] * 1e-3) / 1e12 if gemm else None
     roofline_pg = None
     if gemm:
@@ -363,8 +388,8 @@ def main() -> int:
         "roofline": roofline,
         "roofline_prefill_gemm": roofline_pg,
         "decode_kernels": decode_kernels,
-        "prefill_kernels": [{"name": KERNEL_OF_FAMILY.get(r["name"], r["name"]), "launches": r["launches"],
-                             "total_ms": round(r["total_ms"], 4)} for r in stats],
+        "prefill_kernels": [{"name": r["name"], "launches": r["launches"], "total_ms": round(r["total_ms"], 4),
+                             **({"parts": r["parts"]} if r["parts"] else {})} for r in stats],
         "parity": parity,
         "cpu_baseline": cpu,
     }

@@ -97,7 +97,7 @@ nnc_status nnc_model_create(const nnc_config *cfg, const void *blob, size_t blob
                             const nnc_device *dev, nnc_model **out);
 
 /* Release everything obtained through nnc_device.alloc.  NULL is allowed.
- * Synchronises the stream first. */
+ * Synchronises the stream first.  (Lifetime management: the paper is silent; defined here.) */
 void nnc_model_destroy(nnc_model *m);
 
 /*
@@ -153,7 +153,10 @@ nnc_status nnc_decode_greedy(nnc_model *m, const uint32_t *slots, const int32_t 
 nnc_status nnc_decode_step_static(nnc_model *m, const uint32_t *slots, const int32_t *tokens,
                                   uint32_t batch, float *logits_out, int32_t *next_out);
 
-/* Forget the contents of one slot (slot >= 0) or of all slots (slot = -1). */
+/* Forget the contents of one slot (slot >= 0) or of all slots (slot = -1): the slot's length
+ * becomes 0, nothing is cleared on the device, no work is enqueued.  The paper is silent on
+ * cache management (its runs are one prompt + one decode loop, Section 4 setup); defined here
+ * so that one model serves request after request. */
 nnc_status nnc_kv_reset(nnc_model *m, int32_t slot);
 
 /*
@@ -164,11 +167,14 @@ nnc_status nnc_kv_reset(nnc_model *m, int32_t slot);
  */
 nnc_status nnc_synchronize(nnc_model *m);
 
-/* Current length of a slot (host out-param). */
+/* Current length of a slot (host out-param).  (Paper silent; bookkeeping of this library.) */
 nnc_status nnc_slot_len(const nnc_model *m, uint32_t slot, uint32_t *len_out);
 
 /*
- * Hidden-state variants for models created with has_embed_and_head = 0.
+ * Hidden-state variants for models created with has_embed_and_head = 0: one decoder layer
+ * (or several) without embedding and LM head, the unit the paper's operator-level
+ * discussion is about (Section 3.1.2, the attention-like MatMul / Exp / MatMul chain) and the shape
+ * of the smallest benchmark configuration.  The paper defines no such call; defined here.
  * x: device [n, hidden] floats in; y: device [n, hidden] floats out (the residual
  * stream after the last layer).  nnc_prefill_hidden treats the n rows as
  * consecutive positions of one slot; nnc_decode_step_hidden treats row i as the
@@ -190,7 +196,7 @@ nnc_status nnc_kv_read(nnc_model *m, uint32_t layer, uint32_t slot, uint32_t whi
 typedef enum {
   NNC_OPT_GRAPH = 0,        /* 1 (default): replay decode steps as captured HIP graphs; 0: eager */
   NNC_OPT_PREFILL_EXACT = 1, /* precision of the prompt pass of bf16 models.
-                               0 (default): blocks of up to 2048 tokens with LDS-staged
+                               0 (default): blocks of up to 4096 tokens with LDS-staged
                                matrix-core GEMMs and matrix-core attention.  Blocks of up to 512
                                tokens carry every matrix-core input as two bf16 pieces (16
                                significant bits); longer blocks round those inputs to bf16 once.
@@ -224,6 +230,11 @@ typedef enum {
                                layer's cache rows; the model's stream waits for it before the call
                                returns to the caller's later work.  0: it follows the block on the
                                model's stream.  Bit-identical results */
+  NNC_OPT_PREFILL_BLOCK = 9, /* tokens per block of the large-block prompt pass: 0 (default) = the largest
+                               (4096, or max_seq rounded up to 128 if that is less); else a multiple of
+                               128.  Longer blocks give the narrow projections enough workgroups for the
+                               largest block tile; the blocking does not change which inputs are rounded
+                               (every block of more than 512 tokens carries one bf16 piece) */
   NNC_OPT_SPIN_LIMIT = 5,   /* polls after which a wait inside the resident kernel gives up (sets
                                the failure flag and lets every workgroup exit); 0 (default):
                                2^20, about a second.  A tiny value makes the give-up path testable */
@@ -240,7 +251,8 @@ nnc_status nnc_set_option(nnc_model *m, nnc_option opt, int32_t value);
  * to `cap` records (host), returning the number written in *n_out.
  */
 typedef struct {
-  char name[48];        /* kernel family, e.g. "gemm_skinny" */
+  char name[48];        /* kernel family, e.g. "attn_partial"; the skinny GEMM reports one record per
+                           matrix it streams: "gemm_skinny.qkv", ".o", ".gate_up", ".down", ".lm_head" */
   uint64_t launches;
   double total_ms;      /* sum of event-to-event times */
   double bytes;         /* algorithmic bytes those launches had to move */
@@ -261,10 +273,12 @@ nnc_status nnc_profile_end(nnc_model *m, nnc_kernel_stat *out, uint32_t cap, uin
 nnc_status nnc_stage_trace(nnc_model *m, uint64_t *out, uint32_t cap, uint32_t *workgroups,
                            uint32_t *points);
 
-/* Bytes of the canonical blob for a config (0 if the config is invalid). */
+/* Bytes of the canonical blob for a config (0 if the config is invalid).  (Paper silent: the blob
+ * is this library's input format, the stand-in for the paper's pre-laid-out constants,
+ * Section 3.3.1.) */
 uint64_t nnc_blob_bytes(const nnc_config *cfg);
 
-/* Message for the most recent failure on this thread (static storage). */
+/* Message for the most recent failure on this thread (static storage).  (Paper silent.) */
 const char *nnc_last_error(void);
 
 #ifdef __cplusplus

@@ -17,6 +17,7 @@ OPT_GRAPH, OPT_PREFILL_EXACT, OPT_PERSISTENT, OPT_STAGE_TRACE, OPT_PREFILL_TILE,
 OPT_PREFILL_ATTN = 6
 OPT_FUSE_QK = 7
 OPT_TAIL_OVERLAP = 8
+OPT_PREFILL_BLOCK = 9
 
 # every symbol include/nnc.h declares
 EXPORTS = [
@@ -310,7 +311,7 @@ class Model:
         _check(lib().nnc_profile_begin(self.h))
 
     def profile_end(self):
-        cap = 16
+        cap = 32
         arr = (NncKernelStat * cap)()
         n = ctypes.c_uint32()
         _check(lib().nnc_profile_end(self.h, arr, cap, ctypes.byref(n)))

@@ -47,9 +47,14 @@ struct ProfRec {
   hipEvent_t e0, e1;
 };
 
-enum Family { FAM_GEMM = 0, FAM_NORM, FAM_QKROPE, FAM_ATTN, FAM_COMBINE, FAM_EMBED, FAM_ARGMAX, FAM_MISC, FAM_PGEMM, FAM_PATTN, FAM_COUNT };
-const char* const kFamName[FAM_COUNT] = {"gemm_skinny", "rmsnorm_pack", "qknorm_rope_append", "attn_partial",
-                                         "attn_combine", "embed", "argmax", "misc", "gemm_prefill", "attn_prefill"};
+// One family per kernel; the skinny GEMM is split by the matrix it streams (same kernel, very
+// different sizes), the reader adds what it wants.
+enum Family { FAM_GEMM = 0, FAM_NORM, FAM_QKROPE, FAM_ATTN, FAM_COMBINE, FAM_EMBED, FAM_ARGMAX, FAM_MISC, FAM_PGEMM, FAM_PATTN,
+              FAM_GEMM_O, FAM_GEMM_GU, FAM_GEMM_D, FAM_GEMM_HEAD, FAM_PGEMM_O, FAM_PGEMM_GU, FAM_PGEMM_D, FAM_COUNT };
+const char* const kFamName[FAM_COUNT] = {"gemm_skinny.qkv", "rmsnorm_pack", "qknorm_rope_append", "attn_partial",
+                                         "attn_combine", "embed", "argmax", "misc", "gemm_prefill.qkv", "attn_prefill",
+                                         "gemm_skinny.o", "gemm_skinny.gate_up", "gemm_skinny.down", "gemm_skinny.lm_head",
+                                         "gemm_prefill.o", "gemm_prefill.gate_up", "gemm_prefill.down"};
 
 }  // namespace
 
@@ -87,7 +92,8 @@ struct nnc_model {
   std::vector<uint32_t> len;
 
   // prompt pass on large token blocks
-  uint32_t pb_max = 0;         // tokens per block (multiple of 128), 0 if unavailable
+  uint32_t pb_max = 0;         // tokens per block the buffers hold (multiple of 128), 0 if unavailable
+  uint32_t opt_prefill_block = 0;  // tokens per block asked for (0: pb_max)
   float *pb_x = nullptr, *pb_qkv = nullptr;
   float* pb_part = nullptr;                 // k-slice partial sums of short blocks' O / down projections
   void *pb_fa = nullptr, *pb_fb = nullptr;  // fragment-order bf16 operands: K = H, K = max(Dq, F)
@@ -336,7 +342,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
       pending = (KTQ + a.kts_per_split - 1) / a.kts_per_split;
-      RUN(FAM_GEMM, (double)H * Dq * w, 2.0 * H * Dq * n, launch_gemm(s, f32, EPI_STORE, a));
+      RUN(FAM_GEMM_O, (double)H * Dq * w, 2.0 * H * Dq * n, launch_gemm(s, f32, EPI_STORE, a));
     }
     RUN(FAM_NORM, n * H * 8.0, 0,
         launch_rmsnorm_pack(s, f32, m->x, H, m->rpart, pending, pstride, L.g_post, H, c.rms_eps, n, m->Xp, nc, ns));
@@ -345,7 +351,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = KTH; a.kts_per_split = KTH;
       a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.packed_out = m->Ap; a.NC_out = nc; a.nsplit_out = ns;
-      RUN(FAM_GEMM, 2.0 * F * H * w, 4.0 * F * H * n, launch_gemm(s, f32, EPI_SWIGLU, a));
+      RUN(FAM_GEMM_GU, 2.0 * F * H * w, 4.0 * F * H * n, launch_gemm(s, f32, EPI_SWIGLU, a));
     }
     {
       GemmArgs a{};
@@ -353,7 +359,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
       pending = (KTF + a.kts_per_split - 1) / a.kts_per_split;
-      RUN(FAM_GEMM, (double)H * F * w, 2.0 * H * F * n, launch_gemm(s, f32, EPI_STORE, a));
+      RUN(FAM_GEMM_D, (double)H * F * w, 2.0 * H * F * n, launch_gemm(s, f32, EPI_STORE, a));
     }
   }
 
@@ -366,7 +372,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
     a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = KTH; a.kts_per_split = KTH;
     a.Xp = m->Xp; a.NC = hc; a.ncols = hc; a.nsplit = ns; a.nseq = hn;
     a.out = p.logits; a.ldo = p.logits_ld; a.step_ptr = p.step_ptr; a.step_stride = p.step_stride;
-    RUN(FAM_GEMM, (double)V * H * w, 2.0 * V * H * hn, launch_gemm(s, f32, EPI_STORE, a));
+    RUN(FAM_GEMM_HEAD, (double)V * H * w, 2.0 * V * H * hn, launch_gemm(s, f32, EPI_STORE, a));
     if (p.next)
       RUN(FAM_ARGMAX, hn * V * 4.0, 0,
           launch_argmax(s, p.logits, p.logits_ld, V, hn, p.step_ptr, p.step_stride, m->am_val, m->am_idx,
@@ -696,7 +702,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
   // prompt pass on large token blocks (bf16 token models)
   if (!m->f32 && c.has_embed_and_head) {
     uint32_t pb = (c.max_seq + 127) / 128 * 128;
-    if (pb > 2048) pb = 2048;
+    if (pb > 4096) pb = 4096;
     m->pb_max = pb;
     ALLOC(m->pb_x, float*, (size_t)pb * H * 4);
     ALLOC(m->pb_qkv, float*, (size_t)pb * (Dq + 2 * Dkv) * 4);
@@ -738,9 +744,13 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     m->mk_ks_o = pick_ks(Dq);
     m->mk_ks_d = pick_ks(F);
     MkPlan plan{};
-    plan.H = (int)H; plan.nq = (int)c.n_q_heads; plan.F = (int)F;
+    plan.H = (int)H; plan.nq = (int)c.n_q_heads; plan.nkv = (int)c.n_kv_heads; plan.F = (int)F;
     plan.ks_o = m->mk_ks_o; plan.ks_d = m->mk_ks_d;
-    if (m->mk_ks_o <= 4 && m->mk_ks_d <= 4 && mk_opnd_bytes(plan) <= 96 * 1024) {
+    // The grid's workgroups wait for each other, so all of them must be resident at once: ask
+    // the runtime how many fit (registers, LDS).  If the grid does not fit, batch-1 decode
+    // falls back to the per-stage kernels; it is not an error.
+    if (m->mk_ks_o <= 4 && m->mk_ks_d <= 4 && mk_opnd_bytes(plan) <= 96 * 1024 &&
+        mk_max_resident_workgroups(plan, m->n_cus) >= m->mk_nwg) {
       const size_t lb = mk_layer_bytes();
       std::vector<char> table(lb * c.n_layers);
       for (uint32_t i = 0; i < c.n_layers; ++i) {
@@ -830,6 +840,10 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
       m->opt_prefill_tile = value;
       return NNC_OK;
     case NNC_OPT_TAIL_OVERLAP: m->opt_tail_overlap = value != 0; return NNC_OK;
+    case NNC_OPT_PREFILL_BLOCK:
+      if (value != 0 && (value < 128 || value % 128)) return fail(NNC_E_ARG, "prefill block must be 0 (largest) or a multiple of 128");
+      m->opt_prefill_block = (uint32_t)value;
+      return NNC_OK;
     case NNC_OPT_PREFILL_ATTN:
       if (value < -1 || value > 3) return fail(NNC_E_ARG, "prefill attention shape must be -1 (automatic) or 0 .. 3");
       m->opt_prefill_attn = value;
@@ -941,14 +955,14 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       a.out = m->pb_x; a.ldo = H;
       const int shape = tile_shape(a.n_tiles);
       pending = resid_split(a, shape);
-      RUN(FAM_PGEMM, (double)H * Dq * w, 2.0 * H * Dq * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, shape));
+      RUN(FAM_PGEMM_O, (double)H * Dq * w, 2.0 * H * Dq * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, shape));
     }
     RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, m->pb_x, m->pb_part, pending, part_stride, L.g_post, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
     {
       PrefillGemmArgs a{};
       a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
       a.packed_out = m->pb_fb;
-      RUN(FAM_PGEMM, 2.0 * F * H * w, 4.0 * F * H * T, launch_gemm_prefill(s, EPI_SWIGLU, a, pieces, tile_shape(a.n_tiles)));
+      RUN(FAM_PGEMM_GU, 2.0 * F * H * w, 4.0 * F * H * T, launch_gemm_prefill(s, EPI_SWIGLU, a, pieces, tile_shape(a.n_tiles)));
     }
     {
       PrefillGemmArgs a{};
@@ -956,7 +970,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       a.out = m->pb_x; a.ldo = H;
       const int shape = tile_shape(a.n_tiles);
       pending = resid_split(a, shape);
-      RUN(FAM_PGEMM, (double)H * F * w, 2.0 * H * F * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, shape));
+      RUN(FAM_PGEMM_D, (double)H * F * w, 2.0 * H * F * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, shape));
     }
   }
   if (want_head) {
@@ -968,7 +982,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
     a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = H / 32; a.kts_per_split = H / 32;
     a.Xp = m->Xp; a.NC = 3; a.ncols = 3; a.nsplit = 3; a.nseq = 1;
     a.out = logits_out ? logits_out : m->logits; a.ldo = V;
-    RUN(FAM_GEMM, (double)V * H * w, 2.0 * V * H, launch_gemm(s, false, EPI_STORE, a));
+    RUN(FAM_GEMM_HEAD, (double)V * H * w, 2.0 * V * H, launch_gemm(s, false, EPI_STORE, a));
     if (next_dev)
       RUN(FAM_ARGMAX, V * 4.0, 0, launch_argmax(s, a.out, V, V, 1, nullptr, 0, m->am_val, m->am_idx, next_dev));
   }
@@ -1027,7 +1041,7 @@ static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tok
   bool overlap = false;
   if (tokens && m->pb_max && m->opt_prefill_exact != 1) {
     const uint32_t len0 = m->len[slot];
-    // Blocks of up to pb_max tokens.  A block of more than 512 tokens rounds its matrix-core
+    // Blocks of up to pb_max tokens (NNC_OPT_PREFILL_BLOCK may ask for less).  A block of more than 512 tokens rounds its matrix-core
     // inputs to bf16 once; that noise must not reach the logits directly, so the last
     // PREFILL_TAIL tokens of a longer prompt (the last of which yields the logits) go through
     // the fp32-grade chunk path below instead: one more pass over the weights, about the cost
@@ -1039,7 +1053,8 @@ static nnc_status prefill_common(nnc_model* m, uint32_t slot, const int32_t* tok
     // starting when the block's layer l has appended its K / V rows.
     overlap = head < n && m->opt_tail_overlap && !m->profiling && ensure_tail_stream(m);
     for (uint32_t t0 = 0; t0 < head;) {
-      const uint32_t nb = std::min(m->pb_max, head - t0);
+      const uint32_t blk = m->opt_prefill_block ? std::min(m->opt_prefill_block, m->pb_max) : m->pb_max;
+      const uint32_t nb = std::min(blk, head - t0);
       const bool last = t0 + nb == n;
       const bool fork = overlap && t0 + nb == head;
       if (fork) {

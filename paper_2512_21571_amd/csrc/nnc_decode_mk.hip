@@ -670,6 +670,13 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
                 make_float4(acc2[dtl][0], acc2[dtl][1], acc2[dtl][2], acc2[dtl][3]);
         }
         wg_sync();
+        // The unit that appended this step's K / V row publishes nothing before those stores are
+        // complete: every wave waits for its own outstanding memory operations (only the role
+        // waves have any: the two row stores, issued microseconds ago), so a reader that has seen
+        // all words of this unit's records -- every wave writes some of them -- and everything
+        // that transitively waits for them is ordered after the row.  Other workgroups read the
+        // row with ordinary loads from the next step on.
+        if (owns_new) __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0), the other counters left alone
         for (int o = tid; o < G * 128; o += MK_THREADS) {
           const int h = o >> 7, i = o & 127;
           u64* rec = a.xatt + ((size_t)(head0 + h) * a.max_chunks + chunk) * 132;
@@ -1130,6 +1137,34 @@ size_t mk_opnd_bytes(const MkPlan& p) {
   if (kts_o > kt) kt = kts_o;
   if (kts_d > kt) kt = kts_d;
   return (size_t)kt * 4 * 4 * 16;
+}
+
+// Workgroups of the resident kernel (for this plan's template instance and LDS size) that the
+// device can hold at once, 0 on error: the grid must fit, since its workgroups wait for each other.
+int mk_max_resident_workgroups(const MkPlan& p, int n_cus) {
+  const int G = p.nkv > 0 ? p.nq / p.nkv : 0;
+  const size_t dyn = mk_opnd_bytes(p);
+  int per_cu = 0;
+  hipError_t e = hipErrorInvalidValue;
+#define MK_OCC(GH, NP)                                                                                        \
+  do {                                                                                                        \
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_resident<GH, NP>),                        \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);                            \
+    if (e == hipSuccess)                                                                                      \
+      e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_decode_resident<GH, NP>, MK_THREADS, dyn);   \
+  } while (0)
+#define MK_OCC_NP(GH)                    \
+  do {                                   \
+    if (p.H <= 1024) MK_OCC(GH, 2);      \
+    else if (p.H <= 2048) MK_OCC(GH, 4); \
+    else MK_OCC(GH, 8);                  \
+  } while (0)
+  if (G % 4 == 0) MK_OCC_NP(4);
+  else MK_OCC_NP(2);
+#undef MK_OCC_NP
+#undef MK_OCC
+  if (e != hipSuccess || per_cu < 1) return 0;
+  return per_cu * n_cus;
 }
 
 hipError_t launch_decode_resident(hipStream_t s, const MkPlan& p, const MkBuffers& bf) {

@@ -199,6 +199,7 @@ size_t mk_layer_bytes();
 void mk_fill_layer(void* dst, const void* wqkv, const void* wo, const void* wgu, const void* wd, const float* g_in,
                    const float* g_q, const float* g_k, const float* g_post, void* kc, void* vc);
 size_t mk_opnd_bytes(const MkPlan& p);
+int mk_max_resident_workgroups(const MkPlan& p, int n_cus);
 hipError_t launch_decode_resident(hipStream_t s, const MkPlan& p, const MkBuffers& b);
 
 }  // namespace nnc

@@ -39,18 +39,19 @@ def top2_margin(logits: np.ndarray) -> float:
 
 
 # The library's documented blocking of a prompt call on the large-block path (include/nnc.h,
-# NNC_OPT_PREFILL_EXACT = 0), restated here for the tests: blocks of up to 2048 tokens; a call
+# NNC_OPT_PREFILL_EXACT = 0), restated here for the tests: blocks of up to 4096 tokens (or what
+# NNC_OPT_PREFILL_BLOCK asks for); a call
 # of more than 512 tokens runs its last 16 tokens through the three-piece (fp32-grade) path; a
 # block of more than 512 tokens carries one bf16 piece per matrix-core input, else two.
-PREFILL_BLOCK, PREFILL_TAIL, ONE_PIECE_ABOVE = 2048, 16, 512
+PREFILL_BLOCK, PREFILL_TAIL, ONE_PIECE_ABOVE = 4096, 16, 512
 
 
-def prefill_blocks(n: int):
+def prefill_blocks(n: int, block: int = PREFILL_BLOCK):
     """[(first token, tokens, pieces)] of a default-mode prompt call of n tokens."""
     head = n - PREFILL_TAIL if n > ONE_PIECE_ABOVE else n
     out, t0 = [], 0
     while t0 < head:
-        nb = min(PREFILL_BLOCK, head - t0)
+        nb = min(block, head - t0)
         out.append((t0, nb, 1 if nb > ONE_PIECE_ABOVE else 2))
         t0 += nb
     if head < n:
@@ -58,9 +59,9 @@ def prefill_blocks(n: int):
     return out
 
 
-def oracle_prefill_like_library(o, slot, toks, shape):
+def oracle_prefill_like_library(o, slot, toks, shape, block: int = PREFILL_BLOCK):
     """The oracle's prompt pass with the library's rounding points mirrored block by block."""
     res = None
-    for t0, nb, pieces in prefill_blocks(len(toks)):
+    for t0, nb, pieces in prefill_blocks(len(toks), block):
         res = o.prefill(slot, toks[t0:t0 + nb], oracle_flags(shape, mirrored_prefill=pieces == 1))
     return res

@@ -374,9 +374,8 @@ def test_random_requests_against_oracle(nnc):
 
 @pytest.mark.parametrize("shape", [SMALL_BF16, SMALL_G4], ids=lambda s: s.name)
 def test_default_long_prompt_against_the_unmirrored_oracle(nnc, shape):
-    """A 2100-token prompt in the default mode (a 2048-token block with matrix-core inputs
-    rounded to bf16 once, then a 36-token block with two pieces, then the fp32-grade 16-token
-    tail) against the oracle with NO mirrored rounding, only the 16-bit cache: the stated bar
+    """A 2100-token prompt in the default mode (a 2084-token block with matrix-core inputs
+    rounded to bf16 once, then the fp32-grade 16-token tail) against the oracle with NO mirrored rounding, only the 16-bit cache: the stated bar
     (3e-2, greedy agreement) must hold against the exact definition too, and the decode steps
     that follow read that cache."""
     print(f"case: default-mode 2100-token prompt vs the plain oracle, {shape.name}", flush=True)
@@ -439,10 +438,11 @@ def test_multi_block_prefill_long_context(nnc):
     print("case: prompt of several blocks (2048 + 736 single-piece, 16 fp32-grade)", flush=True)
     shape = SMALL_BF16
     g, o = _pair(nnc, shape, 1, 2900, exact_prefill=False)
+    g.set_option(nnc.OPT_PREFILL_BLOCK, 2048)
     toks = synth.tokens(2800, shape.vocab, stream=77)
-    assert [(nb, pc) for _, nb, pc in prefill_blocks(2800)] == [(2048, 1), (736, 1), (16, 3)]
+    assert [(nb, pc) for _, nb, pc in prefill_blocks(2800, 2048)] == [(2048, 1), (736, 1), (16, 3)]
     lg, ng = g.prefill(0, toks)
-    lo, no = oracle_prefill_like_library(o, 0, toks, shape)
+    lo, no = oracle_prefill_like_library(o, 0, toks, shape, 2048)
     _check_logits(shape, lg, lo, BF16_ABS_PROMPT)
     assert int(ng.item()) == no
     for attn in (1, 3):                                     # paired attention blocks on a block that starts mid-context
@@ -455,6 +455,25 @@ def test_multi_block_prefill_long_context(nnc):
     lo, n2 = o.step_token(0, no, oracle_flags(shape))
     _check_logits(shape, lg[0], lo, BF16_ABS_PROMPT)
     assert int(ng.item()) == n2
+
+
+def test_default_blocks_of_4096_tokens(nnc):
+    print("case: prompt of 4300 tokens in default blocks (4096 single-piece + 188 two-piece, 16 fp32-grade)", flush=True)
+    shape = SMALL_G4
+    g, o = _pair(nnc, shape, 1, 4320, exact_prefill=False)
+    toks = synth.tokens(4300, shape.vocab, stream=78)
+    assert [(nb, pc) for _, nb, pc in prefill_blocks(4300)] == [(4096, 1), (188, 2), (16, 3)]
+    lg, ng = g.prefill(0, toks)
+    lo, no = oracle_prefill_like_library(o, 0, toks, shape)
+    _check_logits(shape, lg, lo, BF16_ABS_PROMPT)
+    assert int(ng.item()) == no
+    # the blocking changes no rounding point of blocks beyond 512 tokens: 2048-token blocks give
+    # logits within the same distance of the same oracle values
+    g.kv_reset(0)
+    g.set_option(nnc.OPT_PREFILL_BLOCK, 2048)
+    l2, n2 = g.prefill(0, toks)
+    _check_logits(shape, l2, lo, BF16_ABS_PROMPT)
+    assert int(n2.item()) == no
 
 
 @pytest.mark.parametrize("batch", [2, 5, 8, 16])
