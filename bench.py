@@ -35,6 +35,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix cores, published
 WORKLOADS = {
     # name: (shape key, batch, context tokens filled by the prompt pass per slot, decode steps)
     "qwen3-0.6b-bf16-b1-p128-d128": ("qwen3-0.6b", 1, 128, 128),
+    "qwen3-0.6b-f16-b1-p128-d128": ("qwen3-0.6b-f16", 1, 128, 128),
     "qwen3-1.7b-bf16-b1-p512-d256": ("qwen3-1.7b", 1, 512, 256),
     "qwen3-4b-bf16-b1-c2048-d128": ("qwen3-4b", 1, 2048, 128),
     "qwen3-4b-bf16-b8-c2048-d128": ("qwen3-4b", 8, 2048, 128),
@@ -44,7 +45,7 @@ WORKLOADS = {
 
 def algorithmic_bytes_per_decode_step(shape, ctx_mean: float, batch: int = 1) -> float:
     """Every weight element once per step, every cached K/V element of every sequence once per step."""
-    w = 2 if shape.dtype == 1 else 4
+    w = 4 if shape.dtype == 0 else 2
     per_layer = (shape.dq + 2 * shape.dkv) * shape.hidden + shape.hidden * shape.dq + 3 * shape.ffn * shape.hidden
     weights = w * (shape.n_layers * per_layer + shape.vocab * shape.hidden)
     kv = shape.n_layers * 2 * shape.dkv * w * ctx_mean * batch
@@ -342,13 +343,14 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        o = oracle.from_shape(shape, blob, 1, 16 + S)
+        ofl = oracle.ROUND_KV | (oracle.ROUND_F16 if shape.dtype == 2 else 0)   # the 16-bit cache, in the model's format
+        o = oracle.from_shape(shape, blob, 1, 16 + S + 8)    # + the one-thread sample's steps
         ctx0 = 16                                    # short prompt so the sample is mostly decode
-        lo, t = o.prefill(0, prompt[:ctx0], oracle.ROUND_KV)
+        lo, t = o.prefill(0, prompt[:ctx0], ofl)
         want = [(lo, t)]
         n, c0 = 0, time.perf_counter()
         while n < S and time.perf_counter() - c0 < args.cpu_seconds:
-            lo, t = o.step_token(0, t, oracle.ROUND_KV)
+            lo, t = o.step_token(0, t, ofl)
             want.append((lo, t))
             n += 1
         dt = time.perf_counter() - c0
@@ -365,18 +367,19 @@ def main() -> int:
             oracle.set_threads(1)
             n1, c1 = 0, time.perf_counter()
             while n1 < 8 and time.perf_counter() - c1 < args.cpu_seconds / 2:
-                _, t = o.step_token(0, t, oracle.ROUND_KV)
+                _, t = o.step_token(0, t, ofl)
                 n1 += 1
             cpu["one_thread_tokens_per_s"] = round(n1 / (time.perf_counter() - c1), 3)
             oracle.set_threads(threads)
 
+    dname = {0: "f32", 1: "bf16", 2: "f16"}[shape.dtype]
     out = {
         "metric": "decode tokens/s + achieved HBM GB/s fraction; prefill tokens/s + MFMA util",
         "value": round(decode_tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / args.steps, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": dname, "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "prompt_tokens": T, "decode_steps": S,
-                   "weights": "N(0,0.02) seeded, bf16", "kv_cache": "bf16"},
+                   "weights": f"N(0,0.02) seeded, {dname}", "kv_cache": dname},
         "decode_ms_per_token": round(decode_ms_per_token, 5),
         "decode_hbm_frac_step": round(step_bytes / (decode_ms_per_token * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
         "decode_algorithmic_bytes_per_step": round(step_bytes),

@@ -56,7 +56,7 @@ typedef enum {
   NNC_E_STATE = 7    /* call not valid for this model (e.g. token API on a hidden-state model) */
 } nnc_status;
 
-typedef enum { NNC_F32 = 0, NNC_BF16 = 1 } nnc_dtype;
+typedef enum { NNC_F32 = 0, NNC_BF16 = 1, NNC_F16 = 2 /* IEEE binary16, the paper's F16 (Section 4, setup) */ } nnc_dtype;
 
 typedef struct {
   uint32_t struct_bytes; /* = sizeof(nnc_config) */
@@ -66,9 +66,11 @@ typedef struct {
   uint32_t tied_lm_head;       /* 1: LM head is the embedding matrix, blob holds no lm_head */
   uint32_t blob_dtype;         /* nnc_dtype of the matrices in the blob */
   uint32_t compute_dtype;      /* NNC_F32: fp32 weights, fp32 KV cache, fp32 matrix-core math;
-                                  NNC_BF16: bf16 weights and KV cache, fp32 accumulation.
-                                  Must equal blob_dtype, or be NNC_BF16 with an NNC_F32 blob
-                                  (weights are then rounded to nearest even once, at create). */
+                                  NNC_BF16 / NNC_F16: 16-bit weights and KV cache in that format,
+                                  fp32 accumulation (activations enter the matrix cores as 16-bit
+                                  pieces of that format).  Must equal blob_dtype, or be a 16-bit type
+                                  with an NNC_F32 blob (weights are then rounded to nearest even
+                                  once, at create). */
   uint32_t max_batch;          /* number of KV slots */
   uint32_t max_seq;            /* positions per slot */
 } nnc_config;

@@ -12,7 +12,7 @@ import numpy as np
 from . import _build
 
 OK, E_ARG, E_CONFIG, E_BLOB, E_NOMEM, E_KV_FULL, E_DEVICE, E_STATE = range(8)
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 OPT_GRAPH, OPT_PREFILL_EXACT, OPT_PERSISTENT, OPT_STAGE_TRACE, OPT_PREFILL_TILE, OPT_SPIN_LIMIT = 0, 1, 2, 3, 4, 5
 OPT_PREFILL_ATTN = 6
 OPT_FUSE_QK = 7

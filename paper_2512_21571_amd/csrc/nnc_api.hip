@@ -61,6 +61,7 @@ const char* const kFamName[FAM_COUNT] = {"gemm_skinny.qkv", "rmsnorm_pack", "qkn
 struct nnc_model {
   nnc_config c{};
   bool f32 = false;
+  int dt = 1;  // element type of weights and cache: 0 fp32, 1 bf16, 2 binary16 (nnc_dtype)
   int device = 0;
   hipStream_t stream = nullptr;
   nnc_device hooks{};
@@ -160,10 +161,10 @@ nnc_status check_config(const nnc_config* c) {
   if (c->hidden % 32 || c->ffn % 32) return fail(NNC_E_CONFIG, "hidden and ffn must be multiples of 32");
   if (c->has_embed_and_head && (c->vocab == 0 || c->vocab % 16))
     return fail(NNC_E_CONFIG, "vocab must be a positive multiple of 16");
-  if (c->blob_dtype > NNC_BF16 || c->compute_dtype > NNC_BF16)
+  if (c->blob_dtype > NNC_F16 || c->compute_dtype > NNC_F16)
     return fail(NNC_E_CONFIG, "unknown dtype");
-  if (c->compute_dtype == NNC_F32 && c->blob_dtype != NNC_F32)
-    return fail(NNC_E_CONFIG, "fp32 compute needs an fp32 blob");
+  if (c->blob_dtype != NNC_F32 && c->blob_dtype != c->compute_dtype)
+    return fail(NNC_E_CONFIG, "a 16-bit blob must be in the compute dtype (an fp32 blob is rounded once at create)");
   if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return fail(NNC_E_CONFIG, "bad rms_eps / rope_theta");
   if (c->max_batch > 4096 || c->max_seq > (1u << 20)) return fail(NNC_E_CONFIG, "max_batch / max_seq too large");
   if (c->n_layers > 1024) return fail(NNC_E_CONFIG, "too many layers");
@@ -299,7 +300,7 @@ struct Pass {
 nnc_status run_pass(nnc_model* m, const Pass& p) {
   const nnc_config& c = m->c;
   hipStream_t s = m->stream;
-  const bool f32 = m->f32;
+  const int dt = m->dt;  // element type, passed to every launcher
   const int H = m->H(), Dq = m->Dq(), Dkv = m->Dkv(), F = m->F(), V = m->V();
   const int nq = c.n_q_heads, nkv = c.n_kv_heads;
   const int n = p.ncols, ns = p.nsplit, nc = n * ns;
@@ -307,7 +308,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
   const int KTH = H / m->ktile(), KTQ = Dq / m->ktile(), KTF = F / m->ktile();
   const int Nqkv = Dq + 2 * Dkv;
 
-  if (p.tokens) RUN(FAM_EMBED, n * H * w, 0, launch_embed(s, f32, m->embed, H, m->st, n, m->x));
+  if (p.tokens) RUN(FAM_EMBED, n * H * w, 0, launch_embed(s, dt, m->embed, H, m->st, n, m->x));
 
   const ColMap cm{m->st, 0, 0, 0};
   // k-slice partials of the previous projection still to be added to x
@@ -317,41 +318,41 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
     const LayerW& L = m->L[li];
     if (m->wait_layers) HIP_TRY(hipStreamWaitEvent(s, m->layer_done[li], 0));
     RUN(FAM_NORM, n * H * 8.0, 0,
-        launch_rmsnorm_pack(s, f32, m->x, H, m->rpart, pending, pstride, L.g_in, H, c.rms_eps, n, m->Xp, nc, ns));
+        launch_rmsnorm_pack(s, dt, m->x, H, m->rpart, pending, pstride, L.g_in, H, c.rms_eps, n, m->Xp, nc, ns));
     {
       GemmArgs a{};
       a.Wp = L.wqkv; a.n_tiles = Nqkv / 16; a.KT = KTH; a.kts_per_split = KTH;
       a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->qkv; a.ldo = Nqkv;
-      RUN(FAM_GEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * n, launch_gemm(s, f32, EPI_STORE, a));
+      RUN(FAM_GEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * n, launch_gemm(s, dt, EPI_STORE, a));
     }
-    const bool fuse = p.decode && m->opt_fuse_qk && attn_partial_can_fuse(f32, nq, nkv);
+    const bool fuse = p.decode && m->opt_fuse_qk && attn_partial_can_fuse(dt, nq, nkv);
     const AttnFuseArgs fz{L.g_q, L.g_k, c.rms_eps, m->rope};
     if (!fuse)
       RUN(FAM_QKROPE, n * Nqkv * 4.0, 0,
-          launch_qknorm_rope_append(s, f32, m->qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, n,
+          launch_qknorm_rope_append(s, dt, m->qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, n,
                                     L.kc, L.vc, c.max_batch, c.max_seq, m->qsplit, nullptr, 0));
     RUN(FAM_ATTN, p.kv_rows * 2.0 * Dkv * w, p.kv_rows * 4.0 * Dq,
-        launch_attn_partial(s, f32, m->qkv, m->qsplit, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, cm, n,
+        launch_attn_partial(s, dt, m->qkv, m->qsplit, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, cm, n,
                             p.grid_chunks, m->partial, m->max_chunks, fuse ? &fz : nullptr, p.one_slot));
     RUN(FAM_COMBINE, 0, 0,
-        launch_attn_combine(s, f32, m->partial, m->max_chunks, nq, cm, n, m->Ap, nc, ns));
+        launch_attn_combine(s, dt, m->partial, m->max_chunks, nq, cm, n, m->Ap, nc, ns));
     {
       GemmArgs a{};
       a.Wp = L.wo; a.n_tiles = H / 16; a.KT = KTQ; a.kts_per_split = pick_kts(a.n_tiles, KTQ);
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
       pending = (KTQ + a.kts_per_split - 1) / a.kts_per_split;
-      RUN(FAM_GEMM_O, (double)H * Dq * w, 2.0 * H * Dq * n, launch_gemm(s, f32, EPI_STORE, a));
+      RUN(FAM_GEMM_O, (double)H * Dq * w, 2.0 * H * Dq * n, launch_gemm(s, dt, EPI_STORE, a));
     }
     RUN(FAM_NORM, n * H * 8.0, 0,
-        launch_rmsnorm_pack(s, f32, m->x, H, m->rpart, pending, pstride, L.g_post, H, c.rms_eps, n, m->Xp, nc, ns));
+        launch_rmsnorm_pack(s, dt, m->x, H, m->rpart, pending, pstride, L.g_post, H, c.rms_eps, n, m->Xp, nc, ns));
     {
       GemmArgs a{};
       a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = KTH; a.kts_per_split = KTH;
       a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.packed_out = m->Ap; a.NC_out = nc; a.nsplit_out = ns;
-      RUN(FAM_GEMM_GU, 2.0 * F * H * w, 4.0 * F * H * n, launch_gemm(s, f32, EPI_SWIGLU, a));
+      RUN(FAM_GEMM_GU, 2.0 * F * H * w, 4.0 * F * H * n, launch_gemm(s, dt, EPI_SWIGLU, a));
     }
     {
       GemmArgs a{};
@@ -359,20 +360,20 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
       pending = (KTF + a.kts_per_split - 1) / a.kts_per_split;
-      RUN(FAM_GEMM_D, (double)H * F * w, 2.0 * H * F * n, launch_gemm(s, f32, EPI_STORE, a));
+      RUN(FAM_GEMM_D, (double)H * F * w, 2.0 * H * F * n, launch_gemm(s, dt, EPI_STORE, a));
     }
   }
 
   if (c.has_embed_and_head && p.head_ncols > 0) {
     const int hn = p.head_ncols, hc = hn * ns;
     RUN(FAM_NORM, hn * H * 8.0, 0,
-        launch_rmsnorm_pack(s, f32, m->x + (size_t)p.head_col0 * H, H, m->rpart + (size_t)p.head_col0 * H, pending,
+        launch_rmsnorm_pack(s, dt, m->x + (size_t)p.head_col0 * H, H, m->rpart + (size_t)p.head_col0 * H, pending,
                             pstride, m->g_final, H, c.rms_eps, hn, m->Xp, hc, ns));
     GemmArgs a{};
     a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = KTH; a.kts_per_split = KTH;
     a.Xp = m->Xp; a.NC = hc; a.ncols = hc; a.nsplit = ns; a.nseq = hn;
     a.out = p.logits; a.ldo = p.logits_ld; a.step_ptr = p.step_ptr; a.step_stride = p.step_stride;
-    RUN(FAM_GEMM_HEAD, (double)V * H * w, 2.0 * V * H * hn, launch_gemm(s, f32, EPI_STORE, a));
+    RUN(FAM_GEMM_HEAD, (double)V * H * w, 2.0 * V * H * hn, launch_gemm(s, dt, EPI_STORE, a));
     if (p.next)
       RUN(FAM_ARGMAX, hn * V * 4.0, 0,
           launch_argmax(s, p.logits, p.logits_ld, V, hn, p.step_ptr, p.step_stride, m->am_val, m->am_idx,
@@ -495,6 +496,7 @@ nnc_status persistent_steps(nnc_model* m, uint32_t slot, int32_t token, uint32_t
   p.n_steps = (int)n_steps;
   p.tag_base = m->mk_tag;
   p.ks_o = m->mk_ks_o; p.ks_d = m->mk_ks_d;
+  p.f16 = m->dt == NNC_F16;
   {
     // gate/up pairs and attention units start at workgroup 0 (attention workgroups then have
     // nothing to prefetch before they wait for q); output-projection units end at the last
@@ -579,6 +581,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
   if (!m) return fail(NNC_E_NOMEM, "host allocation failed");
   m->c = *cfg;
   m->f32 = cfg->compute_dtype == NNC_F32;
+  m->dt = (int)cfg->compute_dtype;
   m->device = device;
   m->n_cus = prop.multiProcessorCount;
   if (dev) {
@@ -630,7 +633,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     hipError_t e = hipMemcpyAsync(stage, bp, rows * K * bw, hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return e;
     bp += rows * K * bw;
-    return launch_repack(s, src_f32, m->f32, stage, dst, (int)rows, (int)K, tile_stride, tile_offset);
+    return launch_repack(s, src_f32, m->dt, stage, dst, (int)rows, (int)K, tile_stride, tile_offset);
   };
 
   if (c.has_embed_and_head) {
@@ -746,6 +749,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     MkPlan plan{};
     plan.H = (int)H; plan.nq = (int)c.n_q_heads; plan.nkv = (int)c.n_kv_heads; plan.F = (int)F;
     plan.ks_o = m->mk_ks_o; plan.ks_d = m->mk_ks_d;
+    plan.f16 = m->dt == NNC_F16;
     // The grid's workgroups wait for each other, so all of them must be resident at once: ask
     // the runtime how many fit (registers, LDS).  If the grid does not fit, batch-1 decode
     // falls back to the per-stage kernels; it is not an error.
@@ -874,6 +878,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
   hipStream_t s = m->stream;
   const int H = m->H(), Dq = m->Dq(), Dkv = m->Dkv(), F = m->F(), V = m->V();
   const int nq = c.n_q_heads, nkv = c.n_kv_heads, Nqkv = Dq + 2 * Dkv;
+  const bool f16 = m->dt == NNC_F16;
   const int tt = (int)((n + 15) / 16);  // token tiles; rows up to 16 * tt exist in every buffer
   // Short prompts are bound by streaming the weights, not by the matrix cores: carry the
   // activations as two bf16 pieces (fp32-grade) and use small row tiles for more workgroups.
@@ -918,20 +923,20 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
   int pending = 0;  // partial buffers of the previous projection still to be added to pb_x
   const double w = 2.0, T = n;
   HIP_TRY(hipMemcpyAsync(m->pb_tok, tokens, (size_t)n * 4, hipMemcpyHostToDevice, s));
-  RUN(FAM_EMBED, T * H * w, 0, launch_embed_rows(s, m->embed, H, m->pb_tok, (int)n, m->pb_x));
+  RUN(FAM_EMBED, T * H * w, 0, launch_embed_rows(s, f16, m->embed, H, m->pb_tok, (int)n, m->pb_x));
   for (uint32_t li = 0; li < c.n_layers; ++li) {
     const LayerW& L = m->L[li];
-    RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, m->pb_x, m->pb_part, pending, part_stride, L.g_in, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
+    RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, f16, m->pb_x, m->pb_part, pending, part_stride, L.g_in, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
     {
       PrefillGemmArgs a{};
       a.Wp = L.wqkv; a.n_tiles = Nqkv / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
       a.out = m->pb_qkv; a.ldo = Nqkv;
-      RUN(FAM_PGEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * T, launch_gemm_prefill(s, EPI_STORE, a, pieces, tile_shape(a.n_tiles)));
+      RUN(FAM_PGEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * T, launch_gemm_prefill(s, f16, EPI_STORE, a, pieces, tile_shape(a.n_tiles)));
     }
     {
       const ColMap cm{nullptr, slot, pos0, 0};
       RUN(FAM_QKROPE, T * Nqkv * 4.0, 0,
-          launch_qknorm_rope_append(s, false, m->pb_qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, (int)n, L.kc,
+          launch_qknorm_rope_append(s, m->dt, m->pb_qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, (int)n, L.kc,
                                     L.vc, c.max_batch, c.max_seq, nullptr, m->pb_vt, m->pb_vt_stride));
       if (m->record_layers) HIP_TRY(hipEventRecord(m->layer_done[li], s));
     }
@@ -946,7 +951,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
         RUN(FAM_MISC, pos0 * Dkv * 2.0 * w, 0,
             launch_v_transpose(s, L.vc, slot, nkv, c.max_seq, pos0, m->pb_vt, m->pb_vt_stride));
       RUN(FAM_PATTN, (pos0 + T) * 2.0 * Dkv * w + T * Dq * 6.0, rows * 4.0 * Dq,
-          launch_attn_prefill(s, m->pb_qkv, nq, nkv, L.kc, m->pb_vt, m->pb_vt_stride, slot, c.max_seq, pos0, (int)n,
+          launch_attn_prefill(s, f16, m->pb_qkv, nq, nkv, L.kc, m->pb_vt, m->pb_vt_stride, slot, c.max_seq, pos0, (int)n,
                               pieces, m->pb_fb, m->n_cus, m->opt_prefill_attn));
     }
     {
@@ -955,14 +960,14 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       a.out = m->pb_x; a.ldo = H;
       const int shape = tile_shape(a.n_tiles);
       pending = resid_split(a, shape);
-      RUN(FAM_PGEMM_O, (double)H * Dq * w, 2.0 * H * Dq * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, shape));
+      RUN(FAM_PGEMM_O, (double)H * Dq * w, 2.0 * H * Dq * T, launch_gemm_prefill(s, f16, EPI_RESID, a, pieces, shape));
     }
-    RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, m->pb_x, m->pb_part, pending, part_stride, L.g_post, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
+    RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, f16, m->pb_x, m->pb_part, pending, part_stride, L.g_post, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
     {
       PrefillGemmArgs a{};
       a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
       a.packed_out = m->pb_fb;
-      RUN(FAM_PGEMM_GU, 2.0 * F * H * w, 4.0 * F * H * T, launch_gemm_prefill(s, EPI_SWIGLU, a, pieces, tile_shape(a.n_tiles)));
+      RUN(FAM_PGEMM_GU, 2.0 * F * H * w, 4.0 * F * H * T, launch_gemm_prefill(s, f16, EPI_SWIGLU, a, pieces, tile_shape(a.n_tiles)));
     }
     {
       PrefillGemmArgs a{};
@@ -970,19 +975,19 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       a.out = m->pb_x; a.ldo = H;
       const int shape = tile_shape(a.n_tiles);
       pending = resid_split(a, shape);
-      RUN(FAM_PGEMM_D, (double)H * F * w, 2.0 * H * F * T, launch_gemm_prefill(s, EPI_RESID, a, pieces, shape));
+      RUN(FAM_PGEMM_D, (double)H * F * w, 2.0 * H * F * T, launch_gemm_prefill(s, f16, EPI_RESID, a, pieces, shape));
     }
   }
   if (want_head) {
     // logits of the block's last token: fp32-grade (three-piece) GEMV over the LM head
     RUN(FAM_NORM, H * 8.0, 0,
-        launch_rmsnorm_pack(s, false, m->pb_x + (size_t)(n - 1) * H, H, m->pb_part + (size_t)(n - 1) * H, pending,
+        launch_rmsnorm_pack(s, m->dt, m->pb_x + (size_t)(n - 1) * H, H, m->pb_part + (size_t)(n - 1) * H, pending,
                             part_stride, m->g_final, H, c.rms_eps, 1, m->Xp, 3, 3));
     GemmArgs a{};
     a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = H / 32; a.kts_per_split = H / 32;
     a.Xp = m->Xp; a.NC = 3; a.ncols = 3; a.nsplit = 3; a.nseq = 1;
     a.out = logits_out ? logits_out : m->logits; a.ldo = V;
-    RUN(FAM_GEMM_HEAD, (double)V * H * w, 2.0 * V * H, launch_gemm(s, false, EPI_STORE, a));
+    RUN(FAM_GEMM_HEAD, (double)V * H * w, 2.0 * V * H, launch_gemm(s, m->dt, EPI_STORE, a));
     if (next_dev)
       RUN(FAM_ARGMAX, V * 4.0, 0, launch_argmax(s, a.out, V, V, 1, nullptr, 0, m->am_val, m->am_idx, next_dev));
   }
@@ -1356,7 +1361,7 @@ nnc_status nnc_kv_read(nnc_model* m, uint32_t layer, uint32_t slot, uint32_t whi
     return fail(NNC_E_ARG, "kv_read range out of bounds");
   const size_t slot_elems = (size_t)m->c.n_kv_heads * m->c.max_seq * 128;
   const char* base = static_cast<const char*>(which ? m->L[layer].vc : m->L[layer].kc) + slot * slot_elems * m->esz();
-  HIP_TRY(launch_kv_read(m->stream, m->f32, base, m->c.max_seq, (int)m->c.n_kv_heads, pos0, n, out));
+  HIP_TRY(launch_kv_read(m->stream, m->dt, base, m->c.max_seq, (int)m->c.n_kv_heads, pos0, n, out));
   return NNC_OK;
 }
 

@@ -34,6 +34,7 @@
 // step are immutable during a launch and use ordinary loads.
 #include <cstring>
 
+#include "nnc_half.h"
 #include "nnc_internal.h"
 #include "nnc_lanes.h"
 
@@ -93,14 +94,6 @@ __device__ __forceinline__ void wg_sync() {
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
-
-__device__ __forceinline__ uint32_t bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
-}
-__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 }  // namespace
 
@@ -182,15 +175,16 @@ __device__ __forceinline__ bool spin_over(const MkArgs& a, unsigned& spins) {
 // bf16 pieces of the pair (v.x, v.y) = activations k, k+1 (k even, relative to the
 // operand's first k) into the packed LDS operand: 4 columns of 16 bytes per 8 k
 // (three pieces and one unused column).
+template <class HF>
 __device__ __forceinline__ void put_pair(uint4* opnd, int k, float2 v) {
   float rx = v.x, ry = v.y;
   uint32_t* base = reinterpret_cast<uint32_t*>(opnd + (size_t)(k >> 3) * 4) + ((k & 7) >> 1);
 #pragma unroll
   for (int s = 0; s < 3; ++s) {
-    const uint32_t bx = bf16_bits(rx), by = bf16_bits(ry);
+    const uint32_t bx = HF::bits(rx), by = HF::bits(ry);
     base[s * 4] = bx | (by << 16);
-    rx -= bf16_to_f32(bx);
-    ry -= bf16_to_f32(by);
+    rx -= HF::widen(bx);
+    ry -= HF::widen(by);
   }
 }
 
@@ -217,7 +211,7 @@ __device__ __forceinline__ void pf_issue(Pf<RT>& pf, const uint4* __restrict__ W
 // One GEMM unit: RT adjacent 16-row tiles x k tiles [kt_begin, kt_end), the
 // waves taking k tiles round-robin; the operand in LDS starts at k tile opnd_kt0.
 // Every wave leaves its partial tile in red[wave][rt]; the caller synchronises.
-template <int RT, bool USE_PF>
+template <int RT, bool USE_PF, class HF>
 __device__ __forceinline__ void gemm_unit(Smem& sm, const uint4* __restrict__ W, size_t tile0, int KT, int kt_begin,
                                           int kt_end, const Pf<RT>& pf, const uint4* opnd, int opnd_kt0) {
   const int tid = opaque(threadIdx.x);
@@ -236,8 +230,7 @@ __device__ __forceinline__ void gemm_unit(Smem& sm, const uint4* __restrict__ W,
       if (kt < kt_end && colok) bv = opnd[((size_t)(kt - opnd_kt0) * 4 + g) * 4 + c16];
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
-        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av[u][rt]),
-                                                          __builtin_bit_cast(bf16x8, bv), acc[rt], 0, 0, 0);
+        acc[rt] = HF::mfma(__builtin_bit_cast(u32x4, av[u][rt]), __builtin_bit_cast(u32x4, bv), acc[rt]);
     }
   };
   int kt0 = kt_begin + wave;
@@ -345,7 +338,7 @@ __device__ __forceinline__ void add_exchanged(const MkArgs& a, Smem& sm, float2 
 }
 
 // Row r of the packed embedding matrix, pairs owned by this thread.
-template <int NP>
+template <int NP, class HF>
 __device__ __forceinline__ void gather_embed(float2 (&x)[NP], int H, const uint4* embed, int r) {
   const int KTH = H / 32;
 #pragma unroll
@@ -355,7 +348,7 @@ __device__ __forceinline__ void gather_embed(float2 (&x)[NP], int H, const uint4
     if (k < H) {
       const size_t e = (((size_t)(r >> 4) * KTH + (k >> 5)) * 64 + (r & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
       const uint32_t two = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint16_t*>(embed) + e);
-      x[j] = make_float2(bf16_to_f32(two & 0xffffu), bf16_to_f32(two >> 16));
+      x[j] = make_float2(HF::lo(two), HF::hi(two));
     }
   }
 }
@@ -375,34 +368,49 @@ __device__ __forceinline__ void load_gain(float2 (&gg)[NP], int H, const float* 
   }
 }
 
-template <int NP>
-__device__ __forceinline__ void norm_pack(Smem& sm, uint4* opnd, int H, const float2 (&x)[NP],
-                                          const float2 (&gg)[NP]) {
-  float ss = 0.f;
-#pragma unroll
-  for (int j = 0; j < NP; ++j) ss += x[j].x * x[j].x + x[j].y * x[j].y;  // unowned pairs are zero
-  ss = wave_sum(ss);
-  if ((threadIdx.x & 63) == 0) sm.wsum[threadIdx.x >> 6] = ss;
-#pragma unroll
-  for (int j = 0; j < NP; ++j) {
-    const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
-    if (k < H) put_pair(opnd, k, make_float2(x[j].x * gg[j].x, x[j].y * gg[j].y));
-  }
-}
-
-// 1 / sqrt(mean(x^2) + eps) of the row last passed to norm_pack (after the workgroup barrier).
-__device__ __forceinline__ float rms_scale(const Smem& sm, int H, float eps) {
+// 1 / sqrt(mean(x^2) + eps) from the per-wave sums of squares (after a workgroup barrier).
+__device__ __forceinline__ float rms_from_sums(const Smem& sm, int H, float eps) {
   float t = 0.f;
 #pragma unroll
   for (int w = 0; w < MK_WAVES; ++w) t += sm.wsum[w];
   return 1.0f / sqrtf(t / (float)H + eps);
 }
 
+// A format with a narrow exponent range (binary16) cannot split an un-normalised row of small
+// magnitude into pieces without losing bits, so there the row is normalised first (one more
+// workgroup barrier) and the epilogues multiply by one.
+template <int NP, class HF>
+__device__ __forceinline__ void norm_pack(Smem& sm, uint4* opnd, int H, float eps, const float2 (&x)[NP],
+                                          const float2 (&gg)[NP]) {
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < NP; ++j) ss += x[j].x * x[j].x + x[j].y * x[j].y;  // unowned pairs are zero
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) sm.wsum[threadIdx.x >> 6] = ss;
+  float r = 1.0f;
+  if constexpr (HF::kNarrowRange) {
+    wg_sync();
+    r = rms_from_sums(sm, H, eps);
+  }
+#pragma unroll
+  for (int j = 0; j < NP; ++j) {
+    const int k = 2 * ((int)threadIdx.x + MK_THREADS * j);
+    if (k < H) put_pair<HF>(opnd, k, make_float2(x[j].x * gg[j].x * r, x[j].y * gg[j].y * r));
+  }
+}
+
+// What the GEMM epilogues after norm_pack multiply their outputs by (after the workgroup barrier).
+template <class HF>
+__device__ __forceinline__ float rms_scale(const Smem& sm, int H, float eps) {
+  if constexpr (HF::kNarrowRange) return 1.0f;
+  else return rms_from_sums(sm, H, eps);
+}
+
 }  // namespace
 
 // GH = query heads sharing one kv head that a workgroup handles together (divides nq/nkv).
 // NP = (k, k+1) pairs of a hidden-state row per thread: hidden <= 2 * MK_THREADS * NP.
-template <int GH, int NP>
+template <int GH, int NP, class HF>
 __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
   extern __shared__ uint4 opnd[];  // packed activation operand of the current GEMM stage
   __shared__ Smem sm;
@@ -458,20 +466,20 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
       float2 gg[NP];
       load_gain<NP>(gg, H, L.g_in);
       if (li == 0)
-        gather_embed<NP>(x, H, a.embed, tok);
+        gather_embed<NP, HF>(x, H, a.embed, tok);
       else
         add_exchanged<NP>(a, sm, x, H, a.xdp, a.ks_d, t_dp - 5u);
-      norm_pack<NP>(sm, opnd, H, x, gg);
+      norm_pack<NP, HF>(sm, opnd, H, a.eps, x, gg);
       wg_sync();
       if (sm.abort) return;
       stamp(step);  // 1: operand ready
       for (int t = wg; t < qkv_tiles; t += nwg) {
         if (t == wg)
-          gemm_unit<1, true>(sm, L.wqkv, (size_t)t, KTH, 0, KTH, pf1, opnd, 0);
+          gemm_unit<1, true, HF>(sm, L.wqkv, (size_t)t, KTH, 0, KTH, pf1, opnd, 0);
         else
-          gemm_unit<1, false>(sm, L.wqkv, (size_t)t, KTH, 0, KTH, pf1, opnd, 0);
+          gemm_unit<1, false, HF>(sm, L.wqkv, (size_t)t, KTH, 0, KTH, pf1, opnd, 0);
         wg_sync();
-        if (tid < 16) st_t(a.xq + t * 16 + tid, tile_total(sm, 0, tid) * rms_scale(sm, H, a.eps), t_q);
+        if (tid < 16) st_t(a.xq + t * 16 + tid, tile_total(sm, 0, tid) * rms_scale<HF>(sm, H, a.eps), t_q);
         wg_sync();
       }
       // prefetch point A (a long wait follows: attention has to run first): output projection
@@ -551,14 +559,14 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
           if (role < G) {
 #pragma unroll
             for (int pc = 0; pc < 3; ++pc) {
-              const uint32_t b0 = bf16_bits(x0), b1 = bf16_bits(x1);
+              const uint32_t b0 = HF::bits(x0), b1 = HF::bits(x1);
               sm.qp[pc][role][lane] = (uint16_t)b0;
               sm.qp[pc][role][lane + 64] = (uint16_t)b1;
-              x0 -= bf16_to_f32(b0);
-              x1 -= bf16_to_f32(b1);
+              x0 -= HF::widen(b0);
+              x1 -= HF::widen(b1);
             }
           } else {
-            const uint32_t b0 = bf16_bits(x0), b1 = bf16_bits(x1);
+            const uint32_t b0 = HF::bits(x0), b1 = HF::bits(x1);
             uint16_t* dst = (role == G ? L.kc : L.vc) + cbase + (size_t)pos * 128;
             // memory-side 32-bit stores (two bf16 each): other workgroups read this row next step
             const uint32_t n0 = __shfl_down(b0, 1, 64), n1 = __shfl_down(b1, 1, 64);
@@ -587,8 +595,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
             for (int pc = 0; pc < 3; ++pc) {
               const u32x4 t = *reinterpret_cast<const u32x4*>(&sm.qp[pc][hq][ks * 32 + g * 8]);
               const u32x4 qf = c16 < G ? t : u32x4{0u, 0u, 0u, 0u};
-              sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[ks]),
-                                                           __builtin_bit_cast(bf16x8, qf), sv, 0, 0, 0);
+              sv = HF::mfma(kf[ks], qf, sv);
             }
         }
         // lane (c16 = head, g): positions wave * 16 + g * 4 + i of the chunk
@@ -624,9 +631,9 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
           float r = w;
 #pragma unroll
           for (int pc = 0; pc < 3; ++pc) {
-            const uint32_t b = bf16_bits(r);
+            const uint32_t b = HF::bits(r);
             sm.pw[pc][h][lane] = (uint16_t)b;
-            r -= bf16_to_f32(b);
+            r -= HF::widen(b);
           }
           const float l = wave_sum(w);
           if (lane == 0) {
@@ -657,8 +664,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
             const u32x4 vf = u32x4{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
 #pragma unroll
             for (int pc = 0; pc < 3; ++pc)
-              acc2[dtl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
-                                                                  __builtin_bit_cast(bf16x8, pf[pc]), acc2[dtl], 0, 0, 0);
+              acc2[dtl] = HF::mfma(vf, pf[pc], acc2[dtl]);
           }
         }
         // acc2[dtl] element i of lane (c16 = head, g): dimension (wave * 2 + dtl) * 16 + g * 4 + i.
@@ -803,7 +809,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                   const int k = kb + 2 * MK_THREADS * j;
-                  if (k < kt1 * 32) put_pair(opnd, k - kt0 * 32, make_float2(t_val(w[j][0]), t_val(w[j][1])));
+                  if (k < kt1 * 32) put_pair<HF>(opnd, k - kt0 * 32, make_float2(t_val(w[j][0]), t_val(w[j][1])));
                 }
                 break;
               }
@@ -882,7 +888,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
   #pragma unroll
             for (int r = 0; r < 2; ++r) {
               const int k = kb + 2 * MK_THREADS * r;
-              if (k < kt1 * 32) put_pair(opnd, k - kt0 * 32, make_float2(n0[r] / den[r], n1[r] / den[r]));
+              if (k < kt1 * 32) put_pair<HF>(opnd, k - kt0 * 32, make_float2(n0[r] / den[r], n1[r] / den[r]));
             }
           }
         }
@@ -890,9 +896,9 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
         wg_sync();
         if (sm.abort) return;
         if (u == wg_o)
-          gemm_unit<1, true>(sm, L.wo, (size_t)t, KTQ, kt0, kt1, pf3, opnd, kt0);
+          gemm_unit<1, true, HF>(sm, L.wo, (size_t)t, KTQ, kt0, kt1, pf3, opnd, kt0);
         else
-          gemm_unit<1, false>(sm, L.wo, (size_t)t, KTQ, kt0, kt1, pf3, opnd, kt0);
+          gemm_unit<1, false, HF>(sm, L.wo, (size_t)t, KTQ, kt0, kt1, pf3, opnd, kt0);
         wg_sync();
         if (tid < 16) st_t(a.xop + (size_t)s * H + t * 16 + tid, tile_total(sm, 0, tid), t_op);
       }
@@ -901,18 +907,18 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
       // ============ stage 4: residual update + post-attention norm + gate/up + SwiGLU ============
       load_gain<NP>(gg, H, L.g_post);
       add_exchanged<NP>(a, sm, x, H, a.xop, a.ks_o, t_op);
-      norm_pack<NP>(sm, opnd, H, x, gg);
+      norm_pack<NP, HF>(sm, opnd, H, a.eps, x, gg);
       wg_sync();
       if (sm.abort) return;
       stamp(step);  // 5: operand ready
       for (int pr = wg; pr < gu_pairs; pr += nwg) {
         if (pr == wg)
-          gemm_unit<2, true>(sm, L.wgu, (size_t)pr * 2, KTH, 0, KTH, pf4, opnd, 0);
+          gemm_unit<2, true, HF>(sm, L.wgu, (size_t)pr * 2, KTH, 0, KTH, pf4, opnd, 0);
         else
-          gemm_unit<2, false>(sm, L.wgu, (size_t)pr * 2, KTH, 0, KTH, pf4, opnd, 0);
+          gemm_unit<2, false, HF>(sm, L.wgu, (size_t)pr * 2, KTH, 0, KTH, pf4, opnd, 0);
         wg_sync();
         if (tid < 16) {
-          const float r = rms_scale(sm, H, a.eps);
+          const float r = rms_scale<HF>(sm, H, a.eps);
           const float gate = tile_total(sm, 0, tid) * r, up = tile_total(sm, 1, tid) * r;
           st_t(a.xact + pr * 16 + tid, gate / (1.0f + expf(-gate)) * up, t_act);
         }
@@ -952,7 +958,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
 #pragma unroll
               for (int j = 0; j < 4; ++j) {
                 const int k = kb + 2 * MK_THREADS * j;
-                if (k < kt1 * 32) put_pair(opnd, k - kt0 * 32, make_float2(t_val(w[j][0]), t_val(w[j][1])));
+                if (k < kt1 * 32) put_pair<HF>(opnd, k - kt0 * 32, make_float2(t_val(w[j][0]), t_val(w[j][1])));
               }
               break;
             }
@@ -966,9 +972,9 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
         wg_sync();
         if (sm.abort) return;
         if (u == wg_d)
-          gemm_unit<1, true>(sm, L.wd, (size_t)t, KTF, kt0, kt1, pf5, opnd, kt0);
+          gemm_unit<1, true, HF>(sm, L.wd, (size_t)t, KTF, kt0, kt1, pf5, opnd, kt0);
         else
-          gemm_unit<1, false>(sm, L.wd, (size_t)t, KTF, kt0, kt1, pf5, opnd, kt0);
+          gemm_unit<1, false, HF>(sm, L.wd, (size_t)t, KTF, kt0, kt1, pf5, opnd, kt0);
         wg_sync();
         if (tid < 16) st_t(a.xdp + (size_t)s * H + t * 16 + tid, tile_total(sm, 0, tid), t_dp);
       }
@@ -981,7 +987,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
       float2 gg[NP];
       load_gain<NP>(gg, H, a.g_final);
       add_exchanged<NP>(a, sm, x, H, a.xdp, a.ks_d, t_am - 1u);
-      norm_pack<NP>(sm, opnd, H, x, gg);
+      norm_pack<NP, HF>(sm, opnd, H, a.eps, x, gg);
     }
     wg_sync();
     if (sm.abort) return;
@@ -993,7 +999,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
       const bool colok = c16 < 3;
       float best = -INFINITY;
       int besti = 0x7fffffff;
-      const float rms = rms_scale(sm, H, a.eps);
+      const float rms = rms_scale<HF>(sm, H, a.eps);
       float* lg = a.logits ? a.logits + (size_t)step * V : nullptr;
       for (int t = wg * MK_WAVES + wave; t < v_tiles; t += nwg * MK_WAVES) {
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -1006,8 +1012,7 @@ __global__ __launch_bounds__(MK_THREADS, 1) void k_decode_resident(MkArgs a) {
           for (int u = 0; u < 16; ++u) {
             uint4 bv = uint4{0, 0, 0, 0};
             if (kt0 + u < KTH && colok) bv = opnd[((size_t)(kt0 + u) * 4 + g) * 4 + c16];
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av[u]),
-                                                          __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
+            acc = HF::mfma(__builtin_bit_cast(u32x4, av[u]), __builtin_bit_cast(u32x4, bv), acc);
           }
         }
         // add the three pieces: columns 0, 1, 2 sit in adjacent lanes
@@ -1148,10 +1153,17 @@ int mk_max_resident_workgroups(const MkPlan& p, int n_cus) {
   hipError_t e = hipErrorInvalidValue;
 #define MK_OCC(GH, NP)                                                                                        \
   do {                                                                                                        \
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_resident<GH, NP>),                        \
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);                            \
-    if (e == hipSuccess)                                                                                      \
-      e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_decode_resident<GH, NP>, MK_THREADS, dyn);   \
+    if (p.f16) {                                                                                              \
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_resident<GH, NP, Fp16>),                \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);                          \
+      if (e == hipSuccess)                                                                                    \
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_decode_resident<GH, NP, Fp16>, MK_THREADS, dyn); \
+    } else {                                                                                                  \
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_resident<GH, NP, Bf16>),                \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);                          \
+      if (e == hipSuccess)                                                                                    \
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_decode_resident<GH, NP, Bf16>, MK_THREADS, dyn); \
+    }                                                                                                         \
   } while (0)
 #define MK_OCC_NP(GH)                    \
   do {                                   \
@@ -1198,10 +1210,17 @@ hipError_t launch_decode_resident(hipStream_t s, const MkPlan& p, const MkBuffer
   hipError_t e;
 #define MK_LAUNCH(GH, NP)                                                                                     \
   do {                                                                                                        \
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_resident<GH, NP>),                        \
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);                            \
-    if (e != hipSuccess) return e;                                                                            \
-    k_decode_resident<GH, NP><<<p.nwg, MK_THREADS, dyn, s>>>(a);                                              \
+    if (p.f16) {                                                                                              \
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_resident<GH, NP, Fp16>),                \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);                          \
+      if (e != hipSuccess) return e;                                                                          \
+      k_decode_resident<GH, NP, Fp16><<<p.nwg, MK_THREADS, dyn, s>>>(a);                                      \
+    } else {                                                                                                  \
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_resident<GH, NP, Bf16>),                \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);                          \
+      if (e != hipSuccess) return e;                                                                          \
+      k_decode_resident<GH, NP, Bf16><<<p.nwg, MK_THREADS, dyn, s>>>(a);                                      \
+    }                                                                                                         \
   } while (0)
 #define MK_LAUNCH_NP(GH)                    \
   do {                                      \

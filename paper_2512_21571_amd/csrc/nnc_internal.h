@@ -8,6 +8,9 @@
 
 namespace nnc {
 
+// `dt` arguments of the launchers: the model's element type, 0 = fp32, 1 = bf16, 2 = binary16
+// (enum Dtype in nnc_half.h, same values as nnc_dtype in the public header).
+
 // Activation columns one pass may carry: decode batch, or a prompt chunk.
 constexpr int MAX_COLS = 64;
 // Cached positions one attention workgroup covers.
@@ -79,19 +82,19 @@ struct GemmArgs {
 struct KernelCtx;  // profiling hook, defined in nnc_api.hip
 
 // All launchers enqueue on `s` and return the launch error code.
-hipError_t launch_repack(hipStream_t s, bool src_f32, bool dst_f32, const void* src, void* dst,
+hipError_t launch_repack(hipStream_t s, bool src_f32, int dst_dt, const void* src, void* dst,
                          int rows, int K, int tile_stride, int tile_offset);
 hipError_t launch_set_state(hipStream_t s, ColState* st, int ncols, const int32_t* tok,
                             const uint32_t* slot, const uint32_t* pos, uint32_t step);
-hipError_t launch_embed(hipStream_t s, bool f32, const void* Ep, int H, const ColState* st,
+hipError_t launch_embed(hipStream_t s, int dt, const void* Ep, int H, const ColState* st,
                         int ncols, float* x);
-hipError_t launch_rmsnorm_pack(hipStream_t s, bool f32, float* x, long ldx, const float* part, int nparts,
+hipError_t launch_rmsnorm_pack(hipStream_t s, int dt, float* x, long ldx, const float* part, int nparts,
                                long part_stride, const float* gain, int H, float eps, int ncols, void* Xp,
                                int NC, int nsplit);
 hipError_t launch_fold_residual(hipStream_t s, float* x, const float* part, int nparts, long part_stride,
                                 size_t n);
-hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a);
-hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq, int nkv,
+hipError_t launch_gemm(hipStream_t s, int dt, int epi, const GemmArgs& a);
+hipError_t launch_qknorm_rope_append(hipStream_t s, int dt, float* qkv, int nq, int nkv,
                                      const float* gq, const float* gk, float eps,
                                      const float2* rope, const ColMap& cm, int ncols, void* kc,
                                      void* vc, uint32_t max_batch, uint32_t max_seq, void* qsplit, void* vt,
@@ -104,12 +107,12 @@ struct AttnFuseArgs {
   float eps;
   const float2* rope;
 };
-bool attn_partial_can_fuse(bool f32, int nq, int nkv);
-hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, const void* qsplit, int nq, int nkv,
+bool attn_partial_can_fuse(int dt, int nq, int nkv);
+hipError_t launch_attn_partial(hipStream_t s, int dt, const float* qkv, const void* qsplit, int nq, int nkv,
                                void* kc, void* vc, uint32_t max_batch, uint32_t max_seq, const ColMap& cm,
                                int ncols, int grid_chunks, float* partial, int max_chunks,
                                const AttnFuseArgs* fuse, bool one_slot = false);
-hipError_t launch_attn_combine(hipStream_t s, bool f32, const float* partial, int max_chunks, int nq,
+hipError_t launch_attn_combine(hipStream_t s, int dt, const float* partial, int max_chunks, int nq,
                                const ColMap& cm, int ncols, void* Op, int NC, int nsplit);
 
 // ---- prompt pass on large token blocks (bf16 models): LDS-staged matrix-core GEMM ----
@@ -135,25 +138,25 @@ struct PrefillGemmArgs {
   float* part = nullptr;
   long part_stride = 0;
 };
-hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a, int pieces, int shape);
+hipError_t launch_gemm_prefill(hipStream_t s, bool f16, int epi, const PrefillGemmArgs& a, int pieces, int shape);
 // x[rows, H] += part[0] + ... + part[nparts-1] (written back), then RMSNorm of rows 0..n_rows-1
 // as `pieces` bf16 per value in fragment order; rows n_rows .. 16 * token_tiles - 1 of the
 // operand are zero-filled.
-hipError_t launch_rmsnorm_frag(hipStream_t s, float* x, const float* part, int nparts, long part_stride,
+hipError_t launch_rmsnorm_frag(hipStream_t s, bool f16, float* x, const float* part, int nparts, long part_stride,
                                const float* gain, int H, float eps, int n_rows, int token_tiles, int pieces,
                                void* Xf);
 hipError_t launch_v_transpose(hipStream_t s, const void* vc, uint32_t slot, int nkv, uint32_t max_seq, uint32_t n_pos,
                               void* vt, uint32_t S);
-hipError_t launch_attn_prefill(hipStream_t s, const float* qkv, int nq, int nkv, const void* kc, const void* vt,
+hipError_t launch_attn_prefill(hipStream_t s, bool f16, const float* qkv, int nq, int nkv, const void* kc, const void* vt,
                                uint32_t S, uint32_t slot, uint32_t max_seq, uint32_t pos0, int n, int pieces, void* Of,
                                int n_cus, int shape);
-hipError_t launch_embed_rows(hipStream_t s, const void* Ep, int H, const int32_t* tokens_dev, int n, float* x);
+hipError_t launch_embed_rows(hipStream_t s, bool f16, const void* Ep, int H, const int32_t* tokens_dev, int n, float* x);
 hipError_t launch_argmax(hipStream_t s, const float* logits, long ld, int V, int ncols,
                          const uint32_t* step_ptr, long step_stride, float* scratch_val,
                          int32_t* scratch_idx, int32_t* next);
 hipError_t launch_finish_step(hipStream_t s, ColState* st, int ncols, const int32_t* next,
                               int32_t* token_log);
-hipError_t launch_kv_read(hipStream_t s, bool f32, const void* cache, uint32_t max_seq, int nkv,
+hipError_t launch_kv_read(hipStream_t s, int dt, const void* cache, uint32_t max_seq, int nkv,
                           uint32_t pos0, uint32_t n, float* out);
 hipError_t launch_copy_rows(hipStream_t s, const float* src, float* dst, size_t n);
 
@@ -171,6 +174,7 @@ struct MkPlan {
   int ks_o, ks_d;       // k slices of the output / down projections
   int off_att, off_o, off_d;  // first workgroup of the attention / output / down projection units
   unsigned spin_max;    // polls of one wait before the launch gives up (0 = default)
+  bool f16;             // binary16 model (else bf16)
 };
 
 struct MkBuffers {

@@ -6,6 +6,7 @@
 // once in matrix-core fragment order and every lane streams them with 16-byte
 // loads.  Everything else (norms, RoPE, SwiGLU, attention) is the public Qwen3
 // decoder arithmetic in fp32.
+#include "nnc_half.h"
 #include "nnc_internal.h"
 #include "nnc_lanes.h"
 
@@ -18,27 +19,24 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // small device helpers
 // ---------------------------------------------------------------------------
 
-// fp32 -> bf16 bit pattern, round to nearest, ties to even; NaN stays NaN.
-__device__ __forceinline__ uint32_t bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
-}
-__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
-
-// Split v into up to three bf16 pieces whose sum is v to fp32 accuracy.
-__device__ __forceinline__ void split_bf16(float v, int nsplit, uint32_t* piece) {
-  float r = v;
-#pragma unroll
-  for (int s = 0; s < 3; ++s) {
-    if (s < nsplit) {
-      const uint32_t b = bf16_bits(r);
-      piece[s] = b;
-      r -= bf16_to_f32(b);
-    }
-  }
-}
+// Launch one instance of a kernel template for the model's element type: inside the statement
+// F32 is a constant expression and HF names the 16-bit format (unused by fp32 instances).
+#define NNC_FOR_DTYPE(dt, ...)              \
+  do {                                      \
+    if ((dt) == DT_F32) {                   \
+      constexpr bool F32 = true;            \
+      using HF = Bf16;                      \
+      __VA_ARGS__;                          \
+    } else if ((dt) == DT_BF16) {           \
+      constexpr bool F32 = false;           \
+      using HF = Bf16;                      \
+      __VA_ARGS__;                          \
+    } else {                                \
+      constexpr bool F32 = false;           \
+      using HF = Fp16;                      \
+      __VA_ARGS__;                          \
+    }                                       \
+  } while (0)
 
 __device__ __forceinline__ float block_sum_256(float v, float* sm) {
   v = wave_sum(v);
@@ -55,7 +53,7 @@ __device__ __forceinline__ float block_sum_256(float v, float* sm) {
 // nt * tile_stride + tile_offset, which expresses both "append below" (stride 1,
 // offset = first tile of the sub-matrix in a fused matrix) and "interleave with a
 // sibling matrix in 16-row tiles" (stride 2, offset 0 or 1).
-template <bool SRC_F32, bool DST_F32>
+template <bool SRC_F32, bool DST_F32, class HF>
 __global__ __launch_bounds__(256) void k_repack(const void* __restrict__ src, void* __restrict__ dst,
                                                 int rows, int K, int tile_stride, int tile_offset) {
   constexpr int VEC = DST_F32 ? 4 : 8;
@@ -72,7 +70,7 @@ __global__ __launch_bounds__(256) void k_repack(const void* __restrict__ src, vo
   const size_t k0 = (size_t)kt * KTILE + (lane >> 4) * VEC;
   const size_t dvec = ((size_t)(nt * tile_stride + tile_offset) * KT + kt) * 64 + lane;
   if constexpr (DST_F32) {
-    static_assert(SRC_F32 || !DST_F32, "bf16 blobs are never widened");
+    static_assert(SRC_F32 || !DST_F32, "16-bit blobs are never widened");
     const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(src) + r * K + k0);
     reinterpret_cast<float4*>(dst)[dvec] = x;
   } else if constexpr (SRC_F32) {
@@ -80,10 +78,10 @@ __global__ __launch_bounds__(256) void k_repack(const void* __restrict__ src, vo
     const float4 a = *reinterpret_cast<const float4*>(p);
     const float4 b = *reinterpret_cast<const float4*>(p + 4);
     uint4 o;
-    o.x = bf16_bits(a.x) | (bf16_bits(a.y) << 16);
-    o.y = bf16_bits(a.z) | (bf16_bits(a.w) << 16);
-    o.z = bf16_bits(b.x) | (bf16_bits(b.y) << 16);
-    o.w = bf16_bits(b.z) | (bf16_bits(b.w) << 16);
+    o.x = HF::bits(a.x) | (HF::bits(a.y) << 16);
+    o.y = HF::bits(a.z) | (HF::bits(a.w) << 16);
+    o.z = HF::bits(b.x) | (HF::bits(b.y) << 16);
+    o.w = HF::bits(b.z) | (HF::bits(b.w) << 16);
     reinterpret_cast<uint4*>(dst)[dvec] = o;
   } else {
     reinterpret_cast<uint4*>(dst)[dvec] =
@@ -91,17 +89,20 @@ __global__ __launch_bounds__(256) void k_repack(const void* __restrict__ src, vo
   }
 }
 
-hipError_t launch_repack(hipStream_t s, bool src_f32, bool dst_f32, const void* src, void* dst,
+// src_f32: the blob holds fp32; dst_dt: the model's element type (a 16-bit blob is already in it).
+hipError_t launch_repack(hipStream_t s, bool src_f32, int dst_dt, const void* src, void* dst,
                          int rows, int K, int tile_stride, int tile_offset) {
-  const int ktile = dst_f32 ? 16 : 32;
+  const int ktile = dst_dt == DT_F32 ? 16 : 32;
   const size_t total = (size_t)(rows / 16) * (K / ktile) * 64;
   const unsigned grid = (unsigned)((total + 255) / 256);
-  if (dst_f32)
-    k_repack<true, true><<<grid, 256, 0, s>>>(src, dst, rows, K, tile_stride, tile_offset);
+  if (dst_dt == DT_F32)
+    k_repack<true, true, Bf16><<<grid, 256, 0, s>>>(src, dst, rows, K, tile_stride, tile_offset);
+  else if (src_f32 && dst_dt == DT_BF16)
+    k_repack<true, false, Bf16><<<grid, 256, 0, s>>>(src, dst, rows, K, tile_stride, tile_offset);
   else if (src_f32)
-    k_repack<true, false><<<grid, 256, 0, s>>>(src, dst, rows, K, tile_stride, tile_offset);
+    k_repack<true, false, Fp16><<<grid, 256, 0, s>>>(src, dst, rows, K, tile_stride, tile_offset);
   else
-    k_repack<false, false><<<grid, 256, 0, s>>>(src, dst, rows, K, tile_stride, tile_offset);
+    k_repack<false, false, Bf16><<<grid, 256, 0, s>>>(src, dst, rows, K, tile_stride, tile_offset);
   return hipGetLastError();
 }
 
@@ -159,7 +160,7 @@ hipError_t launch_finish_step(hipStream_t s, ColState* st, int ncols, const int3
 // ---------------------------------------------------------------------------
 // embedding gather from the packed matrix: x[col][k] = E[tok[col]][k]
 // ---------------------------------------------------------------------------
-template <bool F32>
+template <bool F32, class HF>
 __global__ __launch_bounds__(256) void k_embed(const void* __restrict__ Ep, int H,
                                                const ColState* __restrict__ st, float* __restrict__ x) {
   constexpr int VEC = F32 ? 4 : 8;
@@ -176,17 +177,14 @@ __global__ __launch_bounds__(256) void k_embed(const void* __restrict__ Ep, int 
     if constexpr (F32)
       v = static_cast<const float*>(Ep)[e];
     else
-      v = bf16_to_f32(static_cast<const uint16_t*>(Ep)[e]);
+      v = HF::widen(static_cast<const uint16_t*>(Ep)[e]);
     x[(size_t)col * H + k] = v;
   }
 }
 
-hipError_t launch_embed(hipStream_t s, bool f32, const void* Ep, int H, const ColState* st,
+hipError_t launch_embed(hipStream_t s, int dt, const void* Ep, int H, const ColState* st,
                         int ncols, float* x) {
-  if (f32)
-    k_embed<true><<<ncols, 256, 0, s>>>(Ep, H, st, x);
-  else
-    k_embed<false><<<ncols, 256, 0, s>>>(Ep, H, st, x);
+  NNC_FOR_DTYPE(dt, k_embed<F32, HF><<<ncols, 256, 0, s>>>(Ep, H, st, x));
   return hipGetLastError();
 }
 
@@ -194,13 +192,13 @@ hipError_t launch_embed(hipStream_t s, bool f32, const void* Ep, int H, const Co
 // RMSNorm of one column, written as a packed (split) GEMM operand
 //   h_i = x_i / sqrt(mean_j x_j^2 + eps) * g_i
 // ---------------------------------------------------------------------------
-template <bool F32>
+template <bool F32, class HF>
 __device__ __forceinline__ void store_packed(void* Xp, int NC, int nsplit, int seq, int k, float v) {
   if constexpr (F32) {
     static_cast<float*>(Xp)[((size_t)(k >> 2) * NC + seq) * 4 + (k & 3)] = v;
   } else {
     uint32_t piece[3];
-    split_bf16(v, nsplit, piece);
+    split_pieces<HF>(v, nsplit, piece);
     uint16_t* p = static_cast<uint16_t*>(Xp) + ((size_t)(k >> 3) * NC + seq * nsplit) * 8 + (k & 7);
 #pragma unroll
     for (int s = 0; s < 3; ++s)
@@ -215,7 +213,7 @@ __device__ __forceinline__ void store_packed(void* Xp, int NC, int nsplit, int s
 // NV = float4 groups per thread: the whole row (H <= 1024 * NV) lives in registers, every load
 // (row, pending partials, gains) is issued before the first use, and the row is neither
 // re-read nor re-written more than once.
-template <bool F32, int NV>
+template <bool F32, int NV, class HF>
 __global__ __launch_bounds__(256) void k_rmsnorm_pack(float* __restrict__ x, long ldx,
                                                       const float* __restrict__ part, int nparts,
                                                       long part_stride, const float* __restrict__ gain,
@@ -266,7 +264,7 @@ __global__ __launch_bounds__(256) void k_rmsnorm_pack(float* __restrict__ x, lon
       // elements i .. i+3 of one 8-element group: 8 bytes per piece
       uint32_t pc[4][3];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) split_bf16(h[e], nsplit, pc[e]);
+      for (int e = 0; e < 4; ++e) split_pieces<HF>(h[e], nsplit, pc[e]);
       uint16_t* dst = static_cast<uint16_t*>(Xp) + ((size_t)(i >> 3) * NC + seq * nsplit) * 8 + (i & 7);
 #pragma unroll
       for (int sp = 0; sp < 3; ++sp)
@@ -276,15 +274,12 @@ __global__ __launch_bounds__(256) void k_rmsnorm_pack(float* __restrict__ x, lon
   }
 }
 
-hipError_t launch_rmsnorm_pack(hipStream_t s, bool f32, float* x, long ldx, const float* part, int nparts,
+hipError_t launch_rmsnorm_pack(hipStream_t s, int dt, float* x, long ldx, const float* part, int nparts,
                                long part_stride, const float* gain, int H, float eps, int ncols, void* Xp,
                                int NC, int nsplit) {
   if (H % 4 || H > 8192 || nparts > 8 || nparts < 0 || ldx % 4) return hipErrorInvalidValue;
-#define RN_LAUNCH(NV)                                                                                              \
-  do {                                                                                                             \
-    if (f32) k_rmsnorm_pack<true, NV><<<ncols, 256, 0, s>>>(x, ldx, part, nparts, part_stride, gain, H, eps, Xp, NC, nsplit); \
-    else k_rmsnorm_pack<false, NV><<<ncols, 256, 0, s>>>(x, ldx, part, nparts, part_stride, gain, H, eps, Xp, NC, nsplit);   \
-  } while (0)
+#define RN_LAUNCH(NV) \
+  NNC_FOR_DTYPE(dt, k_rmsnorm_pack<F32, NV, HF><<<ncols, 256, 0, s>>>(x, ldx, part, nparts, part_stride, gain, H, eps, Xp, NC, nsplit))
   if (H <= 1024) RN_LAUNCH(1);
   else if (H <= 2048) RN_LAUNCH(2);
   else if (H <= 4096) RN_LAUNCH(4);
@@ -320,7 +315,7 @@ hipError_t launch_fold_residual(hipStream_t s, float* x, const float* part, int 
 // issues RT x NCB matrix-core instructions (x4 k-steps for fp32).  Partial
 // accumulators of the four waves meet in LDS; the epilogue adds the bf16 pieces
 // of each activation column and stores / accumulates / applies SwiGLU.
-template <bool F32, int NCB, int RT, int EPI, int U>
+template <bool F32, int NCB, int RT, int EPI, int U, class HF>
 __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
   __shared__ float red[4][RT][NCB][256];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -379,9 +374,7 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
             acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, acc[rt][cb], 0, 0, 0);
             acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, acc[rt][cb], 0, 0, 0);
           } else {
-            acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8, av[u][rt]), __builtin_bit_cast(bf16x8, bv[u][cb]),
-                acc[rt][cb], 0, 0, 0);
+            acc[rt][cb] = HF::mfma(av[u][rt], bv[u][cb], acc[rt][cb]);
           }
         }
       }
@@ -433,7 +426,7 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
       const float up = total(2 * pr + 1, row, seq);
       const float act = gate / (1.0f + expf(-gate)) * up;
       const int f = (blockIdx.x * (RT / 2) + pr) * 16 + row;
-      store_packed<F32>(a.packed_out, a.NC_out, a.nsplit_out, seq, f, act);
+      store_packed<F32, HF>(a.packed_out, a.NC_out, a.nsplit_out, seq, f, act);
     }
   } else {
     float* out = a.out;
@@ -449,23 +442,23 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
   }
 }
 
-template <bool F32, int NCB, int RT, int EPI>
+template <bool F32, int NCB, int RT, int EPI, class HF>
 static hipError_t gemm_dispatch(hipStream_t s, const GemmArgs& a) {
   const int ksplit = (a.KT + a.kts_per_split - 1) / a.kts_per_split;
   dim3 grid(a.n_tiles / RT, ksplit);
   constexpr int U = (RT * NCB <= 2) ? 4 : 2;
-  k_gemm_skinny<F32, NCB, RT, EPI, U><<<grid, 256, 0, s>>>(a);
+  k_gemm_skinny<F32, NCB, RT, EPI, U, HF><<<grid, 256, 0, s>>>(a);
   return hipGetLastError();
 }
 
-template <bool F32, int EPI, int RT>
+template <bool F32, int EPI, int RT, class HF>
 static hipError_t gemm_dispatch_ncb(hipStream_t s, const GemmArgs& a) {
   const int ncb = (a.ncols + 15) / 16;
   switch (ncb) {
-    case 1: return gemm_dispatch<F32, 1, RT, EPI>(s, a);
-    case 2: return gemm_dispatch<F32, 2, RT, EPI>(s, a);
-    case 3: return gemm_dispatch<F32, 3, RT, EPI>(s, a);
-    case 4: return gemm_dispatch<F32, 4, RT, EPI>(s, a);
+    case 1: return gemm_dispatch<F32, 1, RT, EPI, HF>(s, a);
+    case 2: return gemm_dispatch<F32, 2, RT, EPI, HF>(s, a);
+    case 3: return gemm_dispatch<F32, 3, RT, EPI, HF>(s, a);
+    case 4: return gemm_dispatch<F32, 4, RT, EPI, HF>(s, a);
     default: return hipErrorInvalidValue;
   }
 }
@@ -491,30 +484,30 @@ static int cu_count() {
   return n;
 }
 
-template <bool F32, int EPI, int RT>
+template <bool F32, int EPI, int RT, class HF>
 static hipError_t gemm_dispatch_rt(hipStream_t s, const GemmArgs& a) {
   const int ncb = (a.ncols + 15) / 16;
   if (ncb >= 2 && ncb <= 3 && a.n_tiles % (2 * RT) == 0) {
     const int ks = (a.KT + a.kts_per_split - 1) / a.kts_per_split, cus = cu_count();
     auto fullness = [&](int wgs) { return (double)wgs / ((double)((wgs + cus - 1) / cus) * cus); };
     if (fullness(a.n_tiles / (2 * RT) * ks) >= fullness(a.n_tiles / RT * ks) - 0.05)
-      return gemm_dispatch_ncb<F32, EPI, 2 * RT>(s, a);
+      return gemm_dispatch_ncb<F32, EPI, 2 * RT, HF>(s, a);
   }
-  return gemm_dispatch_ncb<F32, EPI, RT>(s, a);
+  return gemm_dispatch_ncb<F32, EPI, RT, HF>(s, a);
 }
 
-hipError_t launch_gemm(hipStream_t s, bool f32, int epi, const GemmArgs& a) {
+hipError_t launch_gemm(hipStream_t s, int dt, int epi, const GemmArgs& a) {
   if (a.ncols <= 0 || a.ncols > MAX_COLS || a.ncols > a.NC || a.nseq * a.nsplit != a.ncols ||
       a.kts_per_split <= 0 || a.n_tiles <= 0)
     return hipErrorInvalidValue;
   const bool wide = a.n_tiles >= 1024 && (a.n_tiles % 2 == 0);
   if (epi == EPI_SWIGLU) {
     if (a.n_tiles % 2 || a.kts_per_split < a.KT) return hipErrorInvalidValue;
-    return f32 ? gemm_dispatch_rt<true, EPI_SWIGLU, 2>(s, a) : gemm_dispatch_rt<false, EPI_SWIGLU, 2>(s, a);
+    NNC_FOR_DTYPE(dt, return gemm_dispatch_rt<F32, EPI_SWIGLU, 2, HF>(s, a));
   }
   if (epi != EPI_STORE) return hipErrorInvalidValue;
-  if (wide) return f32 ? gemm_dispatch_rt<true, EPI_STORE, 2>(s, a) : gemm_dispatch_rt<false, EPI_STORE, 2>(s, a);
-  return f32 ? gemm_dispatch_rt<true, EPI_STORE, 1>(s, a) : gemm_dispatch_rt<false, EPI_STORE, 1>(s, a);
+  if (wide) NNC_FOR_DTYPE(dt, return gemm_dispatch_rt<F32, EPI_STORE, 2, HF>(s, a));
+  NNC_FOR_DTYPE(dt, return gemm_dispatch_rt<F32, EPI_STORE, 1, HF>(s, a));
 }
 
 // Which sequence position a column of a pass stands for: decode passes look it up in the
@@ -530,7 +523,7 @@ __device__ __forceinline__ uint32_t col_slot(const ColMap& cm, int col) { return
 // rotated and written back in place (fp32); k heads are normed, rotated and
 // stored in the cache; v heads are stored as they are.
 // Cache layout: [slot][kv head][position][128], one such array per layer.
-template <bool F32>
+template <bool F32, class HF>
 __global__ __launch_bounds__(64) void k_qknorm_rope_append(
     float* __restrict__ qkv, int nq, int nkv, const float* __restrict__ gq, const float* __restrict__ gk,
     float eps, const float2* __restrict__ rope, ColMap cm, void* __restrict__ kc,
@@ -561,8 +554,8 @@ __global__ __launch_bounds__(64) void k_qknorm_rope_append(
       // the query also as three bf16 pieces [column][head][piece][128]: the matrix-core
       // attention kernel loads them as operand fragments without converting anything
       uint32_t pa[3], pb[3];
-      split_bf16(a, 3, pa);
-      split_bf16(b, 3, pb);
+      split_pieces<HF>(a, 3, pa);
+      split_pieces<HF>(b, 3, pb);
       uint16_t* q = qsplit + ((size_t)col * nq + hh) * 3 * 128;
 #pragma unroll
       for (int pc = 0; pc < 3; ++pc) {
@@ -579,18 +572,18 @@ __global__ __launch_bounds__(64) void k_qknorm_rope_append(
     static_cast<float*>(dst)[row + lane] = a;
     static_cast<float*>(dst)[row + lane + 64] = b;
   } else {
-    static_cast<uint16_t*>(dst)[row + lane] = (uint16_t)bf16_bits(a);
-    static_cast<uint16_t*>(dst)[row + lane + 64] = (uint16_t)bf16_bits(b);
+    static_cast<uint16_t*>(dst)[row + lane] = (uint16_t)HF::bits(a);
+    static_cast<uint16_t*>(dst)[row + lane + 64] = (uint16_t)HF::bits(b);
     if (is_v && vt) {
       // prompt blocks: also the transposed copy [kv head][dim][position] that the
       // matrix-core prompt attention reads
-      vt[((size_t)kvh * 128 + lane) * vt_stride + pos] = (uint16_t)bf16_bits(a);
-      vt[((size_t)kvh * 128 + lane + 64) * vt_stride + pos] = (uint16_t)bf16_bits(b);
+      vt[((size_t)kvh * 128 + lane) * vt_stride + pos] = (uint16_t)HF::bits(a);
+      vt[((size_t)kvh * 128 + lane + 64) * vt_stride + pos] = (uint16_t)HF::bits(b);
     }
   }
 }
 
-hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq, int nkv,
+hipError_t launch_qknorm_rope_append(hipStream_t s, int dt, float* qkv, int nq, int nkv,
                                      const float* gq, const float* gk, float eps,
                                      const float2* rope, const ColMap& cm, int ncols, void* kc,
                                      void* vc, uint32_t max_batch, uint32_t max_seq, void* qsplit, void* vt,
@@ -598,12 +591,13 @@ hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq
   (void)max_batch;
   dim3 grid(nq + 2 * nkv, ncols);
   uint16_t* qs = static_cast<uint16_t*>(qsplit);
-  if (f32)
-    k_qknorm_rope_append<true><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq, nullptr,
-                                                   nullptr, 0);
-  else
-    k_qknorm_rope_append<false><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq, qs,
-                                                    static_cast<uint16_t*>(vt), vt_stride);
+  if (dt == DT_F32) {
+    qs = nullptr;
+    vt = nullptr;
+    vt_stride = 0;
+  }
+  NNC_FOR_DTYPE(dt, k_qknorm_rope_append<F32, HF><<<grid, 64, 0, s>>>(qkv, nq, nkv, gq, gk, eps, rope, cm, kc, vc, max_seq,
+                                                                       qs, static_cast<uint16_t*>(vt), vt_stride));
   return hipGetLastError();
 }
 
@@ -617,7 +611,7 @@ hipError_t launch_qknorm_rope_append(hipStream_t s, bool f32, float* qkv, int nq
 // own max / sum / weighted value sum (un-normalised) are written as a partial
 // that k_attn_combine merges with the other chunks (online-softmax rescaling).
 // 16 lanes cover one cached row (8 elements each), a wave covers 4 rows per step.
-template <bool F32>
+template <bool F32, class HF>
 __device__ __forceinline__ void load_row8(const void* base, size_t elem, float* v) {
   if constexpr (F32) {
     const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem);
@@ -626,10 +620,10 @@ __device__ __forceinline__ void load_row8(const void* base, size_t elem, float* 
     v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
   } else {
     const uint4 x = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(base) + elem);
-    v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xffff0000u);
-    v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
-    v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xffff0000u);
-    v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xffff0000u);
+    v[0] = HF::lo(x.x); v[1] = HF::hi(x.x);
+    v[2] = HF::lo(x.y); v[3] = HF::hi(x.y);
+    v[4] = HF::lo(x.z); v[5] = HF::hi(x.z);
+    v[6] = HF::lo(x.w); v[7] = HF::hi(x.w);
   }
 }
 
@@ -637,7 +631,7 @@ __device__ __forceinline__ void load_row8(const void* base, size_t elem, float* 
 // chunk can be in flight before the first one is used.
 template <bool F32>
 struct Row8Raw {
-  float4 a, b;  // fp32: 8 floats; bf16: `a` reinterpreted as 8 bf16 values
+  float4 a, b;  // fp32: 8 floats; 16-bit formats: `a` reinterpreted as 8 stored values
 };
 template <bool F32>
 __device__ __forceinline__ Row8Raw<F32> load_row8_raw(const void* base, size_t elem) {
@@ -651,7 +645,7 @@ __device__ __forceinline__ Row8Raw<F32> load_row8_raw(const void* base, size_t e
   }
   return r;
 }
-template <bool F32>
+template <bool F32, class HF>
 __device__ __forceinline__ void widen_row8(const Row8Raw<F32>& r, float* v) {
   if constexpr (F32) {
     v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w;
@@ -659,14 +653,14 @@ __device__ __forceinline__ void widen_row8(const Row8Raw<F32>& r, float* v) {
   } else {
     const uint32_t x = __float_as_uint(r.a.x), y = __float_as_uint(r.a.y), z = __float_as_uint(r.a.z),
                    w = __float_as_uint(r.a.w);
-    v[0] = __uint_as_float(x << 16); v[1] = __uint_as_float(x & 0xffff0000u);
-    v[2] = __uint_as_float(y << 16); v[3] = __uint_as_float(y & 0xffff0000u);
-    v[4] = __uint_as_float(z << 16); v[5] = __uint_as_float(z & 0xffff0000u);
-    v[6] = __uint_as_float(w << 16); v[7] = __uint_as_float(w & 0xffff0000u);
+    v[0] = HF::lo(x); v[1] = HF::hi(x);
+    v[2] = HF::lo(y); v[3] = HF::hi(y);
+    v[4] = HF::lo(z); v[5] = HF::hi(z);
+    v[6] = HF::lo(w); v[7] = HF::hi(w);
   }
 }
 
-template <bool F32, int GH>
+template <bool F32, int GH, class HF>
 __global__ __launch_bounds__(256) void k_attn_partial(
     const float* __restrict__ qkv, int nq, int nkv, const void* __restrict__ kc,
     const void* __restrict__ vc, uint32_t max_seq, ColMap cm,
@@ -714,7 +708,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(
     const uint32_t j = j0 + jl;
     const bool valid = j <= pos;
     float kv[8];
-    widen_row8<F32>(kraw[it], kv);
+    widen_row8<F32, HF>(kraw[it], kv);
 #pragma unroll
     for (int h = 0; h < GH; ++h) {
       float d = 0.f;
@@ -750,7 +744,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(
   for (int it = 0; it < ATT_CHUNK / 16; ++it) {
     const int jl = it * 16 + wave * 4 + jj;
     float vv[8];
-    widen_row8<F32>(vraw[it], vv);  // masked positions have weight 0 and hold row `pos` (finite)
+    widen_row8<F32, HF>(vraw[it], vv);  // masked positions have weight 0 and hold row `pos` (finite)
 #pragma unroll
     for (int h = 0; h < GH; ++h) {
       const float w = sc[h][jl];
@@ -804,7 +798,7 @@ struct AttnFuse {
   float eps;
   const float2* rope;
 };
-template <bool FUSED>
+template <bool FUSED, class HF>
 __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restrict__ qsplit, AttnFuse fz, int nq,
                                                          int nkv, uint16_t* __restrict__ kc,
                                                          uint16_t* __restrict__ vc, uint32_t max_seq, ColMap cm,
@@ -872,15 +866,15 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
       }
       if (role < G) {
         uint32_t pa[3], pb[3];
-        split_bf16(a, 3, pa);
-        split_bf16(b, 3, pb);
+        split_pieces<HF>(a, 3, pa);
+        split_pieces<HF>(b, 3, pb);
 #pragma unroll
         for (int pc = 0; pc < 3; ++pc) {
           qp[pc][role][lane] = (uint16_t)pa[pc];
           qp[pc][role][lane + 64] = (uint16_t)pb[pc];
         }
       } else {
-        const uint16_t ha = (uint16_t)bf16_bits(a), hb = (uint16_t)bf16_bits(b);
+        const uint16_t ha = (uint16_t)HF::bits(a), hb = (uint16_t)HF::bits(b);
         uint16_t* dst = (role == G ? kc : vc) + base + (size_t)pos * 128;
         dst[lane] = ha;
         dst[lane + 64] = hb;
@@ -917,8 +911,7 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int pc = 0; pc < 3; ++pc)
-        sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[ks]),
-                                                     __builtin_bit_cast(bf16x8, qf[ks][pc]), sv, 0, 0, 0);
+        sv = HF::mfma(kf[ks], qf[ks][pc], sv);
     // lane (c16 = head, g): positions wave * 16 + g * 4 + i of the chunk
     if (c16 < G) {
 #pragma unroll
@@ -950,9 +943,9 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
       float r = w;
 #pragma unroll
       for (int pc = 0; pc < 3; ++pc) {
-        const uint32_t b = bf16_bits(r);
+        const uint32_t b = HF::bits(r);
         pw[pc][h][lane] = (uint16_t)b;
-        r -= bf16_to_f32(b);
+        r -= HF::widen(b);
       }
       const float l = wave_sum(w);
       if (lane == 0) {
@@ -985,8 +978,7 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
         const u32x4_t vf = u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
 #pragma unroll
         for (int pc = 0; pc < 3; ++pc)
-          acc[dtl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
-                                                             __builtin_bit_cast(bf16x8, pf[pc]), acc[dtl], 0, 0, 0);
+          acc[dtl] = HF::mfma(vf, pf[pc], acc[dtl]);
       }
     }
     // acc[dtl] element i of lane (c16 = head, g): dimension (wave * 2 + dtl) * 16 + g * 4 + i
@@ -1008,6 +1000,7 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
 // Prompt chunks (the columns are consecutive positions of one slot): the same arithmetic per
 // (column, head) as k_attn_partial_mc, but one workgroup serves every column from one read of its
 // cache chunk -- the (column, head) pairs are the operand columns, sixteen at a time.
+template <class HF>
 __global__ __launch_bounds__(256) void k_attn_partial_shared(const uint16_t* __restrict__ qsplit, int nq, int nkv,
                                                              const uint16_t* __restrict__ kc,
                                                              const uint16_t* __restrict__ vc, uint32_t max_seq,
@@ -1065,8 +1058,7 @@ __global__ __launch_bounds__(256) void k_attn_partial_shared(const uint16_t* __r
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int pc = 0; pc < 3; ++pc)
-        sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[ks]),
-                                                     __builtin_bit_cast(bf16x8, qf[ks][pc]), sv, 0, 0, 0);
+        sv = HF::mfma(kf[ks], qf[ks][pc], sv);
     // lane (c16 = operand column, g): positions wave * 16 + g * 4 + i of the chunk
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -1084,9 +1076,9 @@ __global__ __launch_bounds__(256) void k_attn_partial_shared(const uint16_t* __r
       float rr = w;
 #pragma unroll
       for (int pc = 0; pc < 3; ++pc) {
-        const uint32_t b = bf16_bits(rr);
+        const uint32_t b = HF::bits(rr);
         pw[pc][r][lane] = (uint16_t)b;
-        rr -= bf16_to_f32(b);
+        rr -= HF::widen(b);
       }
       const float l = wave_sum(w);
       if (lane == 0) {
@@ -1114,8 +1106,7 @@ __global__ __launch_bounds__(256) void k_attn_partial_shared(const uint16_t* __r
         const u32x4_t vf = u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
 #pragma unroll
         for (int pc = 0; pc < 3; ++pc)
-          acc[dtl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
-                                                             __builtin_bit_cast(bf16x8, pf[pc]), acc[dtl], 0, 0, 0);
+          acc[dtl] = HF::mfma(vf, pf[pc], acc[dtl]);
       }
     }
     if (valid && j0 <= pos) {
@@ -1137,48 +1128,59 @@ __global__ __launch_bounds__(256) void k_attn_partial_shared(const uint16_t* __r
   }
 }
 
-bool attn_partial_can_fuse(bool f32, int nq, int nkv) { return !f32 && nq / nkv <= 8; }
+bool attn_partial_can_fuse(int dt, int nq, int nkv) { return dt != DT_F32 && nq / nkv <= 8; }
 
 // fuse != NULL: raw projection output, gains and rotary table for the fused variant (the caller
 // then does not launch k_qknorm_rope_append; columns must be different slots).
-hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, const void* qsplit, int nq, int nkv,
+hipError_t launch_attn_partial(hipStream_t s, int dt, const float* qkv, const void* qsplit, int nq, int nkv,
                                void* kc, void* vc, uint32_t max_batch, uint32_t max_seq,
                                const ColMap& cm, int ncols, int grid_chunks, float* partial,
                                int max_chunks, const AttnFuseArgs* fuse, bool one_slot) {
   (void)max_batch;
   const int G = nq / nkv;
+  const bool f32 = dt == DT_F32, f16 = dt == DT_F16;
   if (fuse) {
-    if (!attn_partial_can_fuse(f32, nq, nkv) || cm.row0 != 0 || !cm.st) return hipErrorInvalidValue;
+    if (!attn_partial_can_fuse(dt, nq, nkv) || cm.row0 != 0 || !cm.st) return hipErrorInvalidValue;
     dim3 grid(grid_chunks, nkv, ncols);
     const AttnFuse fz{qkv, fuse->gq, fuse->gk, fuse->eps, fuse->rope};
-    k_attn_partial_mc<true><<<grid, 256, 0, s>>>(nullptr, fz, nq, nkv, static_cast<uint16_t*>(kc),
-                                                 static_cast<uint16_t*>(vc), max_seq, cm, partial, max_chunks);
+    if (f16)
+      k_attn_partial_mc<true, Fp16><<<grid, 256, 0, s>>>(nullptr, fz, nq, nkv, static_cast<uint16_t*>(kc),
+                                                         static_cast<uint16_t*>(vc), max_seq, cm, partial, max_chunks);
+    else
+      k_attn_partial_mc<true, Bf16><<<grid, 256, 0, s>>>(nullptr, fz, nq, nkv, static_cast<uint16_t*>(kc),
+                                                         static_cast<uint16_t*>(vc), max_seq, cm, partial, max_chunks);
     return hipGetLastError();
   }
   if (!f32 && G <= 16 && qsplit && cm.row0 == 0 && one_slot && ncols > 1) {
     // prompt chunk: consecutive positions of one slot share each read of the cache
     dim3 grid(grid_chunks, nkv);
-    k_attn_partial_shared<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(qsplit), nq, nkv,
-                                               static_cast<const uint16_t*>(kc), static_cast<const uint16_t*>(vc),
-                                               max_seq, cm, ncols, partial, max_chunks);
+    if (f16)
+      k_attn_partial_shared<Fp16><<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(qsplit), nq, nkv,
+                                                       static_cast<const uint16_t*>(kc), static_cast<const uint16_t*>(vc),
+                                                       max_seq, cm, ncols, partial, max_chunks);
+    else
+      k_attn_partial_shared<Bf16><<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(qsplit), nq, nkv,
+                                                       static_cast<const uint16_t*>(kc), static_cast<const uint16_t*>(vc),
+                                                       max_seq, cm, ncols, partial, max_chunks);
     return hipGetLastError();
   }
   if (!f32 && G <= 16 && qsplit && cm.row0 == 0) {
     dim3 grid(grid_chunks, nkv, ncols);
-    k_attn_partial_mc<false><<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(qsplit), AttnFuse{}, nq, nkv,
-                                                  static_cast<uint16_t*>(kc), static_cast<uint16_t*>(vc), max_seq, cm,
-                                                  partial, max_chunks);
+    if (f16)
+      k_attn_partial_mc<false, Fp16><<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(qsplit), AttnFuse{}, nq, nkv,
+                                                          static_cast<uint16_t*>(kc), static_cast<uint16_t*>(vc), max_seq,
+                                                          cm, partial, max_chunks);
+    else
+      k_attn_partial_mc<false, Bf16><<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(qsplit), AttnFuse{}, nq, nkv,
+                                                          static_cast<uint16_t*>(kc), static_cast<uint16_t*>(vc), max_seq,
+                                                          cm, partial, max_chunks);
     return hipGetLastError();
   }
   const int GH = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
   dim3 grid(grid_chunks, nkv * (G / GH), ncols);
-#define NNC_ATT(F, H) \
-  k_attn_partial<F, H><<<grid, 256, 0, s>>>(qkv, nq, nkv, kc, vc, max_seq, cm, partial, max_chunks)
-  if (f32) {
-    if (GH == 4) NNC_ATT(true, 4); else if (GH == 2) NNC_ATT(true, 2); else NNC_ATT(true, 1);
-  } else {
-    if (GH == 4) NNC_ATT(false, 4); else if (GH == 2) NNC_ATT(false, 2); else NNC_ATT(false, 1);
-  }
+#define NNC_ATT(H) \
+  NNC_FOR_DTYPE(dt, k_attn_partial<F32, H, HF><<<grid, 256, 0, s>>>(qkv, nq, nkv, kc, vc, max_seq, cm, partial, max_chunks))
+  if (GH == 4) NNC_ATT(4); else if (GH == 2) NNC_ATT(2); else NNC_ATT(1);
 #undef NNC_ATT
   return hipGetLastError();
 }
@@ -1187,7 +1189,7 @@ hipError_t launch_attn_partial(hipStream_t s, bool f32, const float* qkv, const 
 // as the packed operand of the output projection (k index = head * 128 + i).
 //   M = max_c m_c;  o = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} l_c
 // Output: split-bf16 (or fp32) columns of the skinny GEMM operand.
-template <bool F32>
+template <bool F32, class HF>
 __global__ __launch_bounds__(512) void k_attn_combine(const float* __restrict__ partial, int max_chunks,
                                                       int nq, ColMap cm, void* __restrict__ Op, int NC,
                                                       int nsplit) {
@@ -1223,16 +1225,13 @@ __global__ __launch_bounds__(512) void k_attn_combine(const float* __restrict__ 
     n += f * snum[w][i];
     d += f * sden[w];
   }
-  store_packed<F32>(Op, NC, nsplit, col, head * 128 + i, n / d);
+  store_packed<F32, HF>(Op, NC, nsplit, col, head * 128 + i, n / d);
 }
 
-hipError_t launch_attn_combine(hipStream_t s, bool f32, const float* partial, int max_chunks, int nq,
+hipError_t launch_attn_combine(hipStream_t s, int dt, const float* partial, int max_chunks, int nq,
                                const ColMap& cm, int ncols, void* Op, int NC, int nsplit) {
   dim3 grid(nq, ncols);
-  if (f32)
-    k_attn_combine<true><<<grid, 512, 0, s>>>(partial, max_chunks, nq, cm, Op, NC, nsplit);
-  else
-    k_attn_combine<false><<<grid, 512, 0, s>>>(partial, max_chunks, nq, cm, Op, NC, nsplit);
+  NNC_FOR_DTYPE(dt, k_attn_combine<F32, HF><<<grid, 512, 0, s>>>(partial, max_chunks, nq, cm, Op, NC, nsplit));
   return hipGetLastError();
 }
 
@@ -1312,7 +1311,7 @@ hipError_t launch_argmax(hipStream_t s, const float* logits, long ld, int V, int
 // inspection / plumbing
 // ---------------------------------------------------------------------------
 // cache [kv head][position][128] of one slot and layer -> out [n][nkv*128] fp32
-template <bool F32>
+template <bool F32, class HF>
 __global__ __launch_bounds__(128) void k_kv_read(const void* __restrict__ cache, uint32_t max_seq, int nkv,
                                                  uint32_t pos0, float* __restrict__ out) {
   const int kvh = blockIdx.x, t = blockIdx.y, i = threadIdx.x;
@@ -1321,17 +1320,14 @@ __global__ __launch_bounds__(128) void k_kv_read(const void* __restrict__ cache,
   if constexpr (F32)
     v = static_cast<const float*>(cache)[e];
   else
-    v = bf16_to_f32(static_cast<const uint16_t*>(cache)[e]);
+    v = HF::widen(static_cast<const uint16_t*>(cache)[e]);
   out[((size_t)t * nkv + kvh) * 128 + i] = v;
 }
 
-hipError_t launch_kv_read(hipStream_t s, bool f32, const void* cache, uint32_t max_seq, int nkv,
+hipError_t launch_kv_read(hipStream_t s, int dt, const void* cache, uint32_t max_seq, int nkv,
                           uint32_t pos0, uint32_t n, float* out) {
   dim3 grid(nkv, n);
-  if (f32)
-    k_kv_read<true><<<grid, 128, 0, s>>>(cache, max_seq, nkv, pos0, out);
-  else
-    k_kv_read<false><<<grid, 128, 0, s>>>(cache, max_seq, nkv, pos0, out);
+  NNC_FOR_DTYPE(dt, k_kv_read<F32, HF><<<grid, 128, 0, s>>>(cache, max_seq, nkv, pos0, out));
   return hipGetLastError();
 }
 

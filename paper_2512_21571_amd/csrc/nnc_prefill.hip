@@ -8,6 +8,7 @@
 // write bf16 values directly in the fragment order the next GEMM loads, and nothing is
 // unpacked in between.  Activations entering a GEMM are rounded to bf16 once (round to
 // nearest even): that is the precision contract of this path.
+#include "nnc_half.h"
 #include "nnc_internal.h"
 #include "nnc_lanes.h"
 
@@ -21,24 +22,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
-
-__device__ __forceinline__ uint32_t bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
-}
-__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
-
-// Two floats to two bf16 (round to nearest even) in one word, low half = a: the hardware
-// conversion, bit-identical to bf16_bits for every input that is not a NaN.
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t bf16_pack2(float a, float b) {
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
-}
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 // Workgroup barrier that orders LDS traffic only: the global loads of the register ring stay
 // in flight across it (a plain __syncthreads() would wait for all of them at every k step).
@@ -76,7 +59,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 }  // namespace
 
 // Epilogue of the prompt GEMMs: the accumulators of wave (wn, wt) of the block at (nt0, tt0).
-template <int EPI, int NT, int TT, int PIECES>
+template <int EPI, int NT, int TT, int PIECES, class HF>
 __device__ __forceinline__ void pg_epilogue(const PrefillGemmArgs& a, f32x4 (&acc)[NT / 2][TT / 2], int nt0, int tt0,
                                             int wn, int wt, int lane, int kslice = 0) {
   constexpr int WI = NT / 2, WJ = TT / 2;
@@ -114,8 +97,8 @@ __device__ __forceinline__ void pg_epilogue(const PrefillGemmArgs& a, f32x4 (&ac
           float act = gate / (1.0f + expf(-gate)) * up;
 #pragma unroll
           for (int pc = 0; pc < PIECES; ++pc) {
-            h[pc][e] = bf16_bits(act);
-            act -= bf16_to_f32(h[pc][e]);
+            h[pc][e] = HF::bits(act);
+            act -= HF::widen(h[pc][e]);
           }
         }
         // features f0 .. f0+3 of token t: 8 bytes inside one 16-byte fragment element
@@ -155,7 +138,7 @@ __device__ __forceinline__ void pg_epilogue(const PrefillGemmArgs& a, f32x4 (&ac
 // fed from a register ring eight k steps deep; one workgroup barrier per k step.  This is the
 // kernel of the small block tiles (64 rows: short prompts, bound by streaming the weights, where
 // the deep ring matters); the large tiles use k_gemm_prefill_dl below.
-template <int EPI, int NT, int TT, int PIECES>
+template <int EPI, int NT, int TT, int PIECES, class HF>
 __global__ __launch_bounds__(256, 2) void k_gemm_prefill(PrefillGemmArgs a) {
   constexpr int WI = NT / 2;   // row tiles per wave
   constexpr int AL = NT / 4;   // 16-byte A loads per thread and k step
@@ -235,8 +218,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill(PrefillGemmArgs a) {
     for (int i = 0; i < WI; ++i)
 #pragma unroll
       for (int j = 0; j < WJ; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[i]),
-                                                            __builtin_bit_cast(bf16x8, bf[j]), acc[i][j], 0, 0, 0);
+        acc[i][j] = HF::mfma(af[i], bf[j], acc[i][j]);
     // step kt + 1 into the other buffer (past the end: a stale copy nobody reads)
     sstore(std::integral_constant<int, (d + 1) % D>{}, std::integral_constant<int, (d + 1) & 1>{});
     lds_sync();
@@ -264,7 +246,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill(PrefillGemmArgs a) {
       }
     });
 
-  pg_epilogue<EPI, NT, TT, PIECES>(a, acc, nt0, tt0, wn, wt, lane, (int)blockIdx.z);
+  pg_epilogue<EPI, NT, TT, PIECES, HF>(a, acc, nt0, tt0, wn, wt, lane, (int)blockIdx.z);
 }
 
 // The same GEMM with the operands copied global -> LDS directly (16 bytes per lane, a wave's 64
@@ -273,7 +255,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill(PrefillGemmArgs a) {
 // kt + 3 are issued into the stage whose fragments step kt already holds in registers, and the
 // fragments of step kt + 1 are read while the matrix cores work on step kt; one barrier per k
 // step.
-template <int EPI, int NT, int TT, int PIECES>
+template <int EPI, int NT, int TT, int PIECES, class HF>
 __global__ __launch_bounds__(256, 2) void k_gemm_prefill_dl(PrefillGemmArgs a) {
   constexpr int WI = NT / 2, AL = NT / 4, WJ = TT / 2, BL = TT / 4;
   constexpr int ST = 3;
@@ -351,8 +333,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill_dl(PrefillGemmArgs a) {
     for (int i = 0; i < WI; ++i)
 #pragma unroll
       for (int j = 0; j < WJ; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[P][i]),
-                                                            __builtin_bit_cast(bf16x8, bf[P][j]), acc[i][j], 0, 0, 0);
+        acc[i][j] = HF::mfma(af[P][i], bf[P][j], acc[i][j]);
   };
   issue(0, 0);
   if (KT > 1) issue(1, 1);
@@ -371,12 +352,12 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill_dl(PrefillGemmArgs a) {
       st = st == 2 ? 0 : st + 1;
     }
   }
-  pg_epilogue<EPI, NT, TT, PIECES>(a, acc, nt0, tt0, wn, wt, lane);
+  pg_epilogue<EPI, NT, TT, PIECES, HF>(a, acc, nt0, tt0, wn, wt, lane);
 }
 
 // a.t_tiles counts operand column tiles (token tiles x pieces).  shape: 0 = 64 x 128 block
 // tiles, 1 = 256 x 128, 2 = 128 x 128, 3 = 64 x 64, 4 = 192 x 128.
-hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a, int pieces, int shape) {
+hipError_t launch_gemm_prefill(hipStream_t s, bool f16, int epi, const PrefillGemmArgs& a, int pieces, int shape) {
   if (a.n_tiles <= 0 || a.t_tiles <= 0 || a.KT <= 0 || (pieces != 1 && pieces != 2) || a.t_tiles % pieces ||
       shape < 0 || shape > 4)
     return hipErrorInvalidValue;
@@ -388,13 +369,18 @@ hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a,
     ksplit = (a.KT + a.kts_per_split - 1) / a.kts_per_split;
   }
   dim3 grid((a.n_tiles + NT - 1) / NT, (a.t_tiles + TT - 1) / TT, ksplit);
-#define PG_LAUNCH_P(E, P)                                                          \
-  do {                                                                             \
-    if (shape == 0) k_gemm_prefill<E, 4, 8, P><<<grid, 256, 0, s>>>(a);            \
-    else if (shape == 1) k_gemm_prefill_dl<E, 16, 8, P><<<grid, 256, 0, s>>>(a);   \
-    else if (shape == 2) k_gemm_prefill_dl<E, 8, 8, P><<<grid, 256, 0, s>>>(a);    \
-    else if (shape == 4) k_gemm_prefill_dl<E, 12, 8, P><<<grid, 256, 0, s>>>(a);   \
-    else k_gemm_prefill<E, 4, 4, P><<<grid, 256, 0, s>>>(a);                       \
+#define PG_LAUNCH_H(E, P, HF)                                                          \
+  do {                                                                                 \
+    if (shape == 0) k_gemm_prefill<E, 4, 8, P, HF><<<grid, 256, 0, s>>>(a);            \
+    else if (shape == 1) k_gemm_prefill_dl<E, 16, 8, P, HF><<<grid, 256, 0, s>>>(a);   \
+    else if (shape == 2) k_gemm_prefill_dl<E, 8, 8, P, HF><<<grid, 256, 0, s>>>(a);    \
+    else if (shape == 4) k_gemm_prefill_dl<E, 12, 8, P, HF><<<grid, 256, 0, s>>>(a);   \
+    else k_gemm_prefill<E, 4, 4, P, HF><<<grid, 256, 0, s>>>(a);                       \
+  } while (0)
+#define PG_LAUNCH_P(E, P)              \
+  do {                                 \
+    if (f16) PG_LAUNCH_H(E, P, Fp16);  \
+    else PG_LAUNCH_H(E, P, Bf16);      \
   } while (0)
 #define PG_LAUNCH(E)                    \
   do {                                  \
@@ -409,6 +395,7 @@ hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a,
   }
 #undef PG_LAUNCH
 #undef PG_LAUNCH_P
+#undef PG_LAUNCH_H
   return hipGetLastError();
 }
 
@@ -417,6 +404,7 @@ hipError_t launch_gemm_prefill(hipStream_t s, int epi, const PrefillGemmArgs& a,
 // q * pieces + piece.  Rows beyond n_rows are zero-filled so that padded tiles are defined.
 // The pending k-slice partials of the previous projection are added to x first (fixed order,
 // written back: x is the residual stream).
+template <class HF>
 __global__ __launch_bounds__(256) void k_rmsnorm_frag(float* __restrict__ x, const float* __restrict__ part,
                                                       int nparts, long part_stride,
                                                       const float* __restrict__ gain, int H, float eps, int n_rows,
@@ -478,9 +466,9 @@ __global__ __launch_bounds__(256) void k_rmsnorm_frag(float* __restrict__ x, con
         uint32_t h[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          h[e] = bf16_pack2(y[2 * e], y[2 * e + 1]);
-          y[2 * e] -= bf16_lo(h[e]);
-          y[2 * e + 1] -= bf16_hi(h[e]);
+          h[e] = HF::pack2(y[2 * e], y[2 * e + 1]);
+          y[2 * e] -= HF::lo(h[e]);
+          y[2 * e + 1] -= HF::hi(h[e]);
         }
         out[pc * piece_stride + (size_t)(kg >> 2) * 64 + 16 * (kg & 3)] = uint4{h[0], h[1], h[2], h[3]};
       }
@@ -488,15 +476,19 @@ __global__ __launch_bounds__(256) void k_rmsnorm_frag(float* __restrict__ x, con
   }
 }
 
-hipError_t launch_rmsnorm_frag(hipStream_t s, float* x, const float* part, int nparts, long part_stride,
+hipError_t launch_rmsnorm_frag(hipStream_t s, bool f16, float* x, const float* part, int nparts, long part_stride,
                                const float* gain, int H, float eps, int n_rows, int token_tiles, int pieces,
                                void* Xf) {
   if (H % 32 || H > 8192 || nparts < 0 || (nparts > 0 && !part) || n_rows <= 0) return hipErrorInvalidValue;
-  k_rmsnorm_frag<<<token_tiles * 16, 256, 0, s>>>(x, part, nparts, part_stride, gain, H, eps, n_rows, pieces, Xf);
+  if (f16)
+    k_rmsnorm_frag<Fp16><<<token_tiles * 16, 256, 0, s>>>(x, part, nparts, part_stride, gain, H, eps, n_rows, pieces, Xf);
+  else
+    k_rmsnorm_frag<Bf16><<<token_tiles * 16, 256, 0, s>>>(x, part, nparts, part_stride, gain, H, eps, n_rows, pieces, Xf);
   return hipGetLastError();
 }
 
-// x[t][k] = E[tokens[t]][k] from the packed bf16 embedding matrix.
+// x[t][k] = E[tokens[t]][k] from the packed 16-bit embedding matrix.
+template <class HF>
 __global__ __launch_bounds__(256) void k_embed_rows(const void* __restrict__ Ep, int H,
                                                     const int32_t* __restrict__ tokens, float* __restrict__ x) {
   const int t = blockIdx.x, r = tokens[t], KT = H / 32;
@@ -504,15 +496,14 @@ __global__ __launch_bounds__(256) void k_embed_rows(const void* __restrict__ Ep,
   for (int kg = threadIdx.x; kg < H / 8; kg += 256) {
     const uint4 v = row[(size_t)(kg >> 2) * 64 + 16 * (kg & 3)];
     float* dst = x + (size_t)t * H + kg * 8;
-    *reinterpret_cast<float4*>(dst) = make_float4(bf16_to_f32(v.x & 0xffffu), bf16_to_f32(v.x >> 16),
-                                                  bf16_to_f32(v.y & 0xffffu), bf16_to_f32(v.y >> 16));
-    *reinterpret_cast<float4*>(dst + 4) = make_float4(bf16_to_f32(v.z & 0xffffu), bf16_to_f32(v.z >> 16),
-                                                      bf16_to_f32(v.w & 0xffffu), bf16_to_f32(v.w >> 16));
+    *reinterpret_cast<float4*>(dst) = make_float4(HF::lo(v.x), HF::hi(v.x), HF::lo(v.y), HF::hi(v.y));
+    *reinterpret_cast<float4*>(dst + 4) = make_float4(HF::lo(v.z), HF::hi(v.z), HF::lo(v.w), HF::hi(v.w));
   }
 }
 
-hipError_t launch_embed_rows(hipStream_t s, const void* Ep, int H, const int32_t* tokens_dev, int n, float* x) {
-  k_embed_rows<<<n, 256, 0, s>>>(Ep, H, tokens_dev, x);
+hipError_t launch_embed_rows(hipStream_t s, bool f16, const void* Ep, int H, const int32_t* tokens_dev, int n, float* x) {
+  if (f16) k_embed_rows<Fp16><<<n, 256, 0, s>>>(Ep, H, tokens_dev, x);
+  else k_embed_rows<Bf16><<<n, 256, 0, s>>>(Ep, H, tokens_dev, x);
   return hipGetLastError();
 }
 
@@ -576,7 +567,7 @@ hipError_t launch_v_transpose(hipStream_t s, const void* vc, uint32_t slot, int 
 // cache rows read are initialised memory), so 0 x value = 0.
 // PIECES = 2: queries and weights enter the matrix cores as two bf16 pieces (16 significant
 // bits); PIECES = 1: one bf16 each.  The row sum adds the weights as they are multiplied.
-template <int GH, int PIECES>
+template <int GH, int PIECES, class HF>
 __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict__ qkv, int nq, int nkv,
                                                          const uint16_t* __restrict__ kc,
                                                          const uint16_t* __restrict__ vt, uint32_t S, uint32_t slot,
@@ -615,9 +606,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
         uint32_t b[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          b[e] = bf16_pack2(v[2 * e], v[2 * e + 1]);
-          v[2 * e] -= bf16_lo(b[e]);
-          v[2 * e + 1] -= bf16_hi(b[e]);
+          b[e] = HF::pack2(v[2 * e], v[2 * e + 1]);
+          v[2 * e] -= HF::lo(b[e]);
+          v[2 * e + 1] -= HF::hi(b[e]);
         }
         qf[h][ks][pc] = u32x4{b[0], b[1], b[2], b[3]};
       }
@@ -677,7 +668,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
     asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
     return r;
   };
-  const u32x4 ones = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 x 8
+  const u32x4 ones = u32x4{HF::kOnes2, HF::kOnes2, HF::kOnes2, HF::kOnes2};  // 1.0 x 8
 
   auto do_chunk = [&](int buf, uint32_t kv0) __attribute__((always_inline)) {
     u32x4 pf[GH][PIECES];
@@ -704,10 +695,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
         for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
           for (int pc = 0; pc < PIECES; ++pc) {
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[ks]),
-                                                         __builtin_bit_cast(bf16x8, qf[h][ks][pc]), sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[ks]),
-                                                         __builtin_bit_cast(bf16x8, qf[h][ks][pc]), sb, 0, 0, 0);
+            sa = HF::mfma(ka[ks], qf[h][ks][pc], sa);
+            sb = HF::mfma(kb[ks], qf[h][ks][pc], sb);
           }
         // element i of sa: position kv0 + g*8 + i; of sb: kv0 + g*8 + 4 + i; column = this lane's token
         float sc[8];
@@ -741,10 +730,10 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
           float w1 = __builtin_amdgcn_exp2f(fmaf(sc[i + 1], kScale, -mn));
 #pragma unroll
           for (int pc = 0; pc < PIECES; ++pc) {
-            pw[pc][i / 2] = bf16_pack2(w0, w1);
+            pw[pc][i / 2] = HF::pack2(w0, w1);
             if (pc + 1 < PIECES) {
-              w0 -= bf16_lo(pw[pc][i / 2]);
-              w1 -= bf16_hi(pw[pc][i / 2]);
+              w0 -= HF::lo(pw[pc][i / 2]);
+              w1 -= HF::hi(pw[pc][i / 2]);
             }
           }
         }
@@ -752,8 +741,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
         for (int pc = 0; pc < PIECES; ++pc) {
           pf[h][pc] = u32x4{pw[pc][0], pw[pc][1], pw[pc][2], pw[pc][3]};
           // row sums of the weights as multiplied (all pieces): a product with a tile of ones
-          lacc[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones),
-                                                            __builtin_bit_cast(bf16x8, pf[h][pc]), lacc[h], 0, 0, 0);
+          lacc[h] = HF::mfma(ones, pf[h][pc], lacc[h]);
         }
       }
     }
@@ -765,8 +753,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
       for (int h = 0; h < GH; ++h)
 #pragma unroll
         for (int pc = 0; pc < PIECES; ++pc)
-          acc[h][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[dt]),
-                                                               __builtin_bit_cast(bf16x8, pf[h][pc]), acc[h][dt], 0, 0, 0);
+          acc[h][dt] = HF::mfma(vf[dt], pf[h][pc], acc[h][dt]);
     }
   };
 
@@ -796,11 +783,11 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
         float v[4] = {acc[h][dt][0] * inv, acc[h][dt][1] * inv, acc[h][dt][2] * inv, acc[h][dt][3] * inv};
 #pragma unroll
         for (int pc = 0; pc < PIECES; ++pc) {
-          const uint32_t b0 = bf16_pack2(v[0], v[1]), b1 = bf16_pack2(v[2], v[3]);
-          v[0] -= bf16_lo(b0);
-          v[1] -= bf16_hi(b0);
-          v[2] -= bf16_lo(b1);
-          v[3] -= bf16_hi(b1);
+          const uint32_t b0 = HF::pack2(v[0], v[1]), b1 = HF::pack2(v[2], v[3]);
+          v[0] -= HF::lo(b0);
+          v[1] -= HF::hi(b0);
+          v[2] -= HF::lo(b1);
+          v[3] -= HF::hi(b1);
           const size_t el = (((size_t)(tq * PIECES + pc) * KTQ + (k0 >> 5)) * 64 + c16 + 16 * ((k0 & 31) >> 3)) * 8 + (k0 & 7);
           *reinterpret_cast<uint2*>(static_cast<uint16_t*>(Of) + el) = make_uint2(b0, b1);
         }
@@ -813,7 +800,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float* __restrict
 // qkv: [tokens][(nq + 2 nkv) * 128] fp32 with the query heads already normed and rotated.
 // kc: the layer's K cache; vt: transposed V copy of the slot (row stride S) covering positions
 // 0 .. pos0 + n - 1.  Of: fragment-order bf16 output ([token tile x pieces][nq*4][64][8]).
-hipError_t launch_attn_prefill(hipStream_t s, const float* qkv, int nq, int nkv, const void* kc, const void* vt,
+hipError_t launch_attn_prefill(hipStream_t s, bool f16, const float* qkv, int nq, int nkv, const void* kc, const void* vt,
                                uint32_t S, uint32_t slot, uint32_t max_seq, uint32_t pos0, int n, int pieces, void* Of,
                                int n_cus, int shape) {
   const int G = nq / nkv;
@@ -834,14 +821,20 @@ hipError_t launch_attn_prefill(hipStream_t s, const float* qkv, int nq, int nkv,
   dim3 grid(paired ? (NB + 1) / 2 : NB, nkv * (G / GH));
   const uint16_t* k = static_cast<const uint16_t*>(kc);
   const uint16_t* v = static_cast<const uint16_t*>(vt);
-#define AP_LAUNCH(GHV)                                                                                          \
-  do {                                                                                                          \
-    if (pieces == 2) k_attn_prefill<GHV, 2><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, paired, Of); \
-    else k_attn_prefill<GHV, 1><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, paired, Of);           \
+#define AP_LAUNCH_H(GHV, HF)                                                                                        \
+  do {                                                                                                              \
+    if (pieces == 2) k_attn_prefill<GHV, 2, HF><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, paired, Of); \
+    else k_attn_prefill<GHV, 1, HF><<<grid, 256, 0, s>>>(qkv, nq, nkv, k, v, S, slot, max_seq, pos0, n, paired, Of);           \
+  } while (0)
+#define AP_LAUNCH(GHV)                \
+  do {                                \
+    if (f16) AP_LAUNCH_H(GHV, Fp16);  \
+    else AP_LAUNCH_H(GHV, Bf16);      \
   } while (0)
   if (GH == 2) AP_LAUNCH(2);
   else AP_LAUNCH(1);
 #undef AP_LAUNCH
+#undef AP_LAUNCH_H
   return hipGetLastError();
 }
 

@@ -89,6 +89,8 @@ SHAPES = {
     "layer-0.6b-f32": ModelShape("layer-0.6b-f32", 1024, 1, 16, 8, 128, 3072, 0,
                                  has_embed_and_head=False, tied_lm_head=False, dtype=F32),
     "qwen3-0.6b": ModelShape("qwen3-0.6b", 1024, 28, 16, 8, 128, 3072, V_QWEN3),
+    # the paper's own 16-bit precision (IEEE binary16) at its smallest model
+    "qwen3-0.6b-f16": ModelShape("qwen3-0.6b-f16", 1024, 28, 16, 8, 128, 3072, V_QWEN3, dtype=F16),
     "qwen3-1.7b": ModelShape("qwen3-1.7b", 2048, 28, 16, 8, 128, 6144, V_QWEN3),
     "qwen3-4b": ModelShape("qwen3-4b", 2560, 36, 32, 8, 128, 9728, V_QWEN3),
     "qwen3-8b": ModelShape("qwen3-8b", 4096, 36, 32, 8, 128, 12288, V_QWEN3, tied_lm_head=False),

@@ -12,6 +12,10 @@ SMALL_BF16 = synth.ModelShape("small-bf16", hidden=256, n_layers=2, n_q_heads=4,
                               head_dim=128, ffn=512, vocab=1024, dtype=synth.BF16)
 SMALL_G4 = synth.ModelShape("small-g4", hidden=320, n_layers=2, n_q_heads=8, n_kv_heads=2,
                             head_dim=128, ffn=608, vocab=2064, dtype=synth.BF16, tied_lm_head=False)
+SMALL_F16 = synth.ModelShape("small-f16", hidden=256, n_layers=2, n_q_heads=4, n_kv_heads=2,
+                             head_dim=128, ffn=512, vocab=1024, dtype=synth.F16)
+SMALL_G4_F16 = synth.ModelShape("small-g4-f16", hidden=320, n_layers=2, n_q_heads=8, n_kv_heads=2,
+                                head_dim=128, ffn=608, vocab=2064, dtype=synth.F16, tied_lm_head=False)
 SMALL_F32 = synth.ModelShape("small-f32", hidden=256, n_layers=2, n_q_heads=4, n_kv_heads=2,
                              head_dim=128, ffn=512, vocab=1024, dtype=synth.F32)
 SMALL_LAYER_F32 = synth.ModelShape("small-layer-f32", hidden=256, n_layers=1, n_q_heads=4, n_kv_heads=2,
@@ -21,10 +25,12 @@ SMALL_LAYER_F32 = synth.ModelShape("small-layer-f32", hidden=256, n_layers=1, n_
 
 def oracle_flags(shape, mirrored_prefill: bool = False) -> int:
     f = 0
-    if shape.dtype == synth.BF16:
+    if shape.dtype != synth.F32:
         f |= oracle.ROUND_KV
         if mirrored_prefill:
             f |= oracle.ROUND_GEMM_IN | oracle.ROUND_ATTN_QP
+        if shape.dtype == synth.F16:
+            f |= oracle.ROUND_F16          # every rounding point in binary16 instead of bf16
     return f
 
 

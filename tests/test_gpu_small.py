@@ -39,7 +39,7 @@ def _pair(nnc, shape, max_batch, max_seq, weight_std=0.05, jitter=0.1, exact_pre
     activations in 21-token chunks (True) or the large-block matrix-core GEMMs (False)."""
     blob = synth.make_blob(shape, weight_std=weight_std, gain_jitter=jitter)
     g = nnc.Model(shape, blob, max_batch, max_seq)
-    if shape.dtype == synth.BF16 and shape.has_embed_and_head:
+    if shape.dtype != synth.F32 and shape.has_embed_and_head:
         g.set_option(nnc.OPT_PREFILL_EXACT, int(exact_prefill))
     return g, oracle.from_shape(shape, blob, max_batch, max_seq)
 
