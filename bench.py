@@ -182,6 +182,7 @@ def main() -> int:
     ap.add_argument("--prefill-block", type=int, default=0,
                     help="tokens per block of the prompt pass (NNC_OPT_PREFILL_BLOCK; 0 = the library's default)")
     ap.add_argument("--prefill-tile", type=int, default=-1, help="force a block tile of the prompt GEMMs (NNC_OPT_PREFILL_TILE)")
+    ap.add_argument("--planner", type=int, default=1, help="0: the hand rules instead of the analytic tile chooser (NNC_OPT_PLANNER)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing sample")
@@ -211,6 +212,8 @@ def main() -> int:
     model = nnc.Model(shape, blob, B, T + S + 8)       # + the few extra steps of the per-kernel leg
     if args.prefill_block:
         model.set_option(nnc.OPT_PREFILL_BLOCK, args.prefill_block)
+    if not args.planner:
+        model.set_option(nnc.OPT_PLANNER, 0)
     if args.prefill_tile >= 0:
         model.set_option(nnc.OPT_PREFILL_TILE, args.prefill_tile)
     note("model ready; warm-up passes")

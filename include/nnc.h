@@ -237,6 +237,9 @@ typedef enum {
                                128.  Longer blocks give the narrow projections enough workgroups for the
                                largest block tile; the blocking does not change which inputs are rounded
                                (every block of more than 512 tokens carries one bf16 piece) */
+  NNC_OPT_PLANNER = 10,     /* 1 (default): block tiles, row tiles per workgroup and k slices of the GEMM
+                               launches come from the analytic model behind nnc_plan_*_query; 0: from the
+                               hand-written rules that preceded it (kept for comparison) */
   NNC_OPT_SPIN_LIMIT = 5,   /* polls after which a wait inside the resident kernel gives up (sets
                                the failure flag and lets every workgroup exit); 0 (default):
                                2^20, about a second.  A tiny value makes the give-up path testable */
@@ -274,6 +277,35 @@ nnc_status nnc_profile_end(nnc_model *m, nnc_kernel_stat *out, uint32_t cap, uin
  */
 nnc_status nnc_stage_trace(nnc_model *m, uint64_t *out, uint32_t cap, uint32_t *workgroups,
                            uint32_t *points);
+
+/*
+ * The analytic tile chooser the library plans its GEMM launches with, exposed for inspection and
+ * tests (host code only, no GPU needed).  It follows the paper's parametric optimisation
+ * (Section 3.2.2): tile variables, capacity constraints per storage level (LDS bytes of the
+ * staged operands, registers per wave), and the objective minimise max(T_mem, T_comp) with T_comp
+ * from a linear regression of the micro-kernel's time per k step and T_mem = traffic / bandwidth,
+ * plus launch and epilogue-traffic time.  The search space is the block tiles the kernels are
+ * instantiated for, times the k slices a launch may use, so the problem is solved by enumeration.
+ * epilogue: 0 store, 1 add to the residual stream, 2 SwiGLU.  n_cus: compute units (0 = 256).
+ *   nnc_plan_prefill_gemm_query  prompt GEMM [rows x k] x [k x n_tokens] with `pieces` 16-bit
+ *                                pieces per activation; may use up to max_k_slices k slices
+ *   nnc_plan_skinny_gemm_query   weight-streaming GEMM of a decode pass with n_seq sequences of
+ *                                `pieces` pieces each; tile_rows = rows per workgroup, t_comp_us =
+ *                                time of the operand re-reads
+ */
+typedef struct {
+  uint32_t tile_rows, tile_cols;  /* block tile (rows x operand columns) */
+  int32_t tile_code;              /* the library's code of that tile (NNC_OPT_PREFILL_TILE) / row tiles per workgroup */
+  uint32_t k_slices, workgroups;
+  double t_comp_us, t_mem_us, t_us; /* model times of the choice */
+  uint32_t candidates, rejected_by_capacity; /* prompt GEMM: tiles enumerated / ruled out by LDS or registers */
+} nnc_gemm_plan;
+nnc_status nnc_plan_prefill_gemm_query(uint32_t rows, uint32_t k, uint32_t n_tokens, uint32_t pieces,
+                                       uint32_t epilogue, uint32_t max_k_slices, uint32_t n_cus,
+                                       nnc_gemm_plan *out);
+nnc_status nnc_plan_skinny_gemm_query(uint32_t rows, uint32_t k, uint32_t n_seq, uint32_t pieces,
+                                      uint32_t epilogue, uint32_t max_k_slices, uint32_t n_cus,
+                                      nnc_gemm_plan *out);
 
 /* Bytes of the canonical blob for a config (0 if the config is invalid).  (Paper silent: the blob
  * is this library's input format, the stand-in for the paper's pre-laid-out constants,

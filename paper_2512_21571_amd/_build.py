@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libnnc.so")
-SOURCES = ["nnc_kernels.hip", "nnc_decode_mk.hip", "nnc_prefill.hip", "nnc_api.hip"]
+SOURCES = ["nnc_kernels.hip", "nnc_decode_mk.hip", "nnc_prefill.hip", "nnc_api.hip", "nnc_plan.cpp"]
 HEADERS = [os.path.join(CSRC, "nnc_internal.h"), os.path.join(HERE, "..", "include", "nnc.h")]
 
 OBJ_DIR = os.path.join(HERE, "_build")
@@ -44,7 +44,7 @@ def build(force: bool = True) -> str:
     """force: compile every source; otherwise only the sources newer than their object file
     (the sources are compiled side by side, one hipcc each, then linked)."""
     os.makedirs(OBJ_DIR, exist_ok=True)
-    hdr_time = max(os.path.getmtime(h) for h in HEADERS + [os.path.join(CSRC, "nnc_lanes.h")])
+    hdr_time = max(os.path.getmtime(h) for h in HEADERS + [os.path.join(CSRC, n) for n in ("nnc_lanes.h", "nnc_half.h", "nnc_plan.h")])
     jobs = []
     for src in SOURCES:
         sp, op = os.path.join(CSRC, src), os.path.join(OBJ_DIR, src + ".o")

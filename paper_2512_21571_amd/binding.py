@@ -18,6 +18,7 @@ OPT_PREFILL_ATTN = 6
 OPT_FUSE_QK = 7
 OPT_TAIL_OVERLAP = 8
 OPT_PREFILL_BLOCK = 9
+OPT_PLANNER = 10
 
 # every symbol include/nnc.h declares
 EXPORTS = [
@@ -25,7 +26,7 @@ EXPORTS = [
     "nnc_decode_greedy",
     "nnc_kv_reset", "nnc_synchronize", "nnc_slot_len", "nnc_prefill_hidden", "nnc_decode_step_hidden", "nnc_kv_read",
     "nnc_set_option", "nnc_profile_begin", "nnc_profile_end", "nnc_stage_trace", "nnc_blob_bytes",
-    "nnc_last_error",
+    "nnc_last_error", "nnc_plan_prefill_gemm_query", "nnc_plan_skinny_gemm_query",
 ]
 
 
@@ -47,6 +48,13 @@ class NncDevice(ctypes.Structure):
 class NncKernelStat(ctypes.Structure):
     _fields_ = [("name", ctypes.c_char * 48), ("launches", ctypes.c_uint64), ("total_ms", ctypes.c_double),
                 ("bytes", ctypes.c_double), ("flops", ctypes.c_double)]
+
+
+class NncGemmPlan(ctypes.Structure):
+    _fields_ = [("tile_rows", ctypes.c_uint32), ("tile_cols", ctypes.c_uint32), ("tile_code", ctypes.c_int32),
+                ("k_slices", ctypes.c_uint32), ("workgroups", ctypes.c_uint32), ("t_comp_us", ctypes.c_double),
+                ("t_mem_us", ctypes.c_double), ("t_us", ctypes.c_double), ("candidates", ctypes.c_uint32),
+                ("rejected_by_capacity", ctypes.c_uint32)]
 
 
 class NncError(RuntimeError):
@@ -90,6 +98,8 @@ def lib():
             "nnc_stage_trace": (i32, [vp, vp, u32, P(u32), P(u32)]),
             "nnc_blob_bytes": (ctypes.c_uint64, [P(NncConfig)]),
             "nnc_last_error": (ctypes.c_char_p, []),
+            "nnc_plan_prefill_gemm_query": (i32, [u32, u32, u32, u32, u32, u32, u32, P(NncGemmPlan)]),
+            "nnc_plan_skinny_gemm_query": (i32, [u32, u32, u32, u32, u32, u32, u32, P(NncGemmPlan)]),
         }
         for name, (res, args) in sig.items():
             f = getattr(L, name)
@@ -118,6 +128,18 @@ def make_config(shape, max_batch: int, max_seq: int, compute_dtype: int | None =
 
 def blob_bytes(cfg: NncConfig) -> int:
     return int(lib().nnc_blob_bytes(ctypes.byref(cfg)))
+
+
+def plan_prefill_gemm(rows, k, n_tokens, pieces, epilogue, max_k_slices=1, n_cus=256) -> NncGemmPlan:
+    out = NncGemmPlan()
+    _check(lib().nnc_plan_prefill_gemm_query(rows, k, n_tokens, pieces, epilogue, max_k_slices, n_cus, ctypes.byref(out)))
+    return out
+
+
+def plan_skinny_gemm(rows, k, n_seq, pieces, epilogue, max_k_slices=1, n_cus=256) -> NncGemmPlan:
+    out = NncGemmPlan()
+    _check(lib().nnc_plan_skinny_gemm_query(rows, k, n_seq, pieces, epilogue, max_k_slices, n_cus, ctypes.byref(out)))
+    return out
 
 
 def _i32(a):

@@ -20,6 +20,7 @@
 
 #include "../../include/nnc.h"
 #include "nnc_internal.h"
+#include "nnc_plan.h"
 
 using namespace nnc;
 
@@ -124,6 +125,7 @@ struct nnc_model {
   int opt_prefill_attn = -1;  // forced launch shape of the prompt attention, -1 = by size
   int opt_prefill_tile = -1;  // forced block tile of the large-block prompt GEMMs, -1 = by size
   bool opt_persistent = true;
+  bool opt_planner = true;    // tile sizes from the analytic model (nnc_plan.h); false: the earlier hand rules
   std::map<std::tuple<int, int, int>, hipGraphExec_t> graphs;
 
   bool profiling = false;
@@ -280,6 +282,19 @@ int pick_kts(int n_tiles, int KT) {
   return (KT + ksplit - 1) / ksplit;
 }
 
+// Row tiles per workgroup and k slices of a weight-streaming GEMM from the analytic model
+// (the hand rules: pick_kts above and the launcher's own row-tile rule, stay in `a` when the
+// planner is switched off).
+void plan_skinny(const nnc_model* m, GemmArgs& a, int epi, bool may_split) {
+  if (!m->opt_planner) return;
+  const Machine mc = machine_mi355x(m->n_cus);
+  const int rts = epi == EPI_SWIGLU ? ((1 << 2) | (1 << 4)) : ((1 << 1) | (1 << 2) | (1 << 4));
+  const SkinnyGemmPlan pl = plan_skinny_gemm(mc, a.n_tiles, a.KT, a.ncols, a.nseq, rts, may_split ? MAX_KSPLIT : 1);
+  if (pl.rt <= 0) return;
+  a.rt = pl.rt;
+  a.kts_per_split = pl.kts_per_split;
+}
+
 struct Pass {
   int ncols = 0;          // sequences (columns) in the pass
   int nsplit = 1;         // bf16 pieces per activation
@@ -324,6 +339,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Wp = L.wqkv; a.n_tiles = Nqkv / 16; a.KT = KTH; a.kts_per_split = KTH;
       a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->qkv; a.ldo = Nqkv;
+      plan_skinny(m, a, EPI_STORE, false);
       RUN(FAM_GEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * n, launch_gemm(s, dt, EPI_STORE, a));
     }
     const bool fuse = p.decode && m->opt_fuse_qk && attn_partial_can_fuse(dt, nq, nkv);
@@ -342,6 +358,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Wp = L.wo; a.n_tiles = H / 16; a.KT = KTQ; a.kts_per_split = pick_kts(a.n_tiles, KTQ);
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
+      plan_skinny(m, a, EPI_STORE, true);
       pending = (KTQ + a.kts_per_split - 1) / a.kts_per_split;
       RUN(FAM_GEMM_O, (double)H * Dq * w, 2.0 * H * Dq * n, launch_gemm(s, dt, EPI_STORE, a));
     }
@@ -352,6 +369,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = KTH; a.kts_per_split = KTH;
       a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.packed_out = m->Ap; a.NC_out = nc; a.nsplit_out = ns;
+      plan_skinny(m, a, EPI_SWIGLU, false);
       RUN(FAM_GEMM_GU, 2.0 * F * H * w, 4.0 * F * H * n, launch_gemm(s, dt, EPI_SWIGLU, a));
     }
     {
@@ -359,6 +377,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Wp = L.wd; a.n_tiles = H / 16; a.KT = KTF; a.kts_per_split = pick_kts(a.n_tiles, KTF);
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
+      plan_skinny(m, a, EPI_STORE, true);
       pending = (KTF + a.kts_per_split - 1) / a.kts_per_split;
       RUN(FAM_GEMM_D, (double)H * F * w, 2.0 * H * F * n, launch_gemm(s, dt, EPI_STORE, a));
     }
@@ -373,6 +392,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
     a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = KTH; a.kts_per_split = KTH;
     a.Xp = m->Xp; a.NC = hc; a.ncols = hc; a.nsplit = ns; a.nseq = hn;
     a.out = p.logits; a.ldo = p.logits_ld; a.step_ptr = p.step_ptr; a.step_stride = p.step_stride;
+    plan_skinny(m, a, EPI_STORE, false);
     RUN(FAM_GEMM_HEAD, (double)V * H * w, 2.0 * V * H * hn, launch_gemm(s, dt, EPI_STORE, a));
     if (p.next)
       RUN(FAM_ARGMAX, hn * V * 4.0, 0,
@@ -844,6 +864,12 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
       m->opt_prefill_tile = value;
       return NNC_OK;
     case NNC_OPT_TAIL_OVERLAP: m->opt_tail_overlap = value != 0; return NNC_OK;
+    case NNC_OPT_PLANNER:
+      m->opt_planner = value != 0;
+      // captured decode graphs contain the launches of one or the other choice
+      for (auto& kv : m->graphs) (void)hipGraphExecDestroy(kv.second);
+      m->graphs.clear();
+      return NNC_OK;
     case NNC_OPT_PREFILL_BLOCK:
       if (value != 0 && (value < 128 || value % 128)) return fail(NNC_E_ARG, "prefill block must be 0 (largest) or a multiple of 128");
       m->opt_prefill_block = (uint32_t)value;
@@ -889,6 +915,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
   // them: of 256 / 192 / 128 x 128 take the shape whose last round is fullest (larger tiles do
   // a little more per byte of LDS traffic, hence the weights); 64 x 128, or 64 x 64 when even
   // those are fewer than the CUs, for launches that cannot give every CU a larger tile.
+  const Machine mc = machine_mi355x(m->n_cus);
   auto tile_shape = [&](int n_tiles) {
     if (m->opt_prefill_tile >= 0) return m->opt_prefill_tile;
     const long cols = (ct + 7) / 8, slots = 2L * m->n_cus;
@@ -920,6 +947,26 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
     a.part_stride = part_stride;
     return (a.KT + a.kts_per_split - 1) / a.kts_per_split - 1;  // partial buffers to fold later
   };
+  // Block tile and k slices of one prompt GEMM: from the analytic model, unless a tile is
+  // forced or the planner is switched off (then the two rules above).  Returns the tile; sets
+  // the k split in `a` and the number of partial buffers the next norm kernel has to fold.
+  auto plan_gemm = [&](PrefillGemmArgs& a, int epi, int* pend) {
+    if (pend) *pend = 0;
+    if (!m->opt_planner || m->opt_prefill_tile >= 0) {
+      const int shape = tile_shape(a.n_tiles);
+      if (pend) *pend = resid_split(a, shape);
+      return shape;
+    }
+    const int max_ks = (epi == EPI_RESID && n <= PB_SPLIT_TOKENS) ? PB_SPLIT_MAX : 1;
+    const PrefillGemmPlan pl = plan_prefill_gemm(mc, a.n_tiles, a.KT, ct, (int)n, pieces, epi, max_ks);
+    if (pl.k_slices > 1) {
+      a.kts_per_split = pl.kts_per_split;
+      a.part = m->pb_part;
+      a.part_stride = part_stride;
+      if (pend) *pend = pl.k_slices - 1;
+    }
+    return pl.tile;
+  };
   int pending = 0;  // partial buffers of the previous projection still to be added to pb_x
   const double w = 2.0, T = n;
   HIP_TRY(hipMemcpyAsync(m->pb_tok, tokens, (size_t)n * 4, hipMemcpyHostToDevice, s));
@@ -931,7 +978,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       PrefillGemmArgs a{};
       a.Wp = L.wqkv; a.n_tiles = Nqkv / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
       a.out = m->pb_qkv; a.ldo = Nqkv;
-      RUN(FAM_PGEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * T, launch_gemm_prefill(s, f16, EPI_STORE, a, pieces, tile_shape(a.n_tiles)));
+      RUN(FAM_PGEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * T, launch_gemm_prefill(s, f16, EPI_STORE, a, pieces, plan_gemm(a, EPI_STORE, nullptr)));
     }
     {
       const ColMap cm{nullptr, slot, pos0, 0};
@@ -958,8 +1005,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       PrefillGemmArgs a{};
       a.Wp = L.wo; a.n_tiles = H / 16; a.KT = Dq / 32; a.Xf = m->pb_fb; a.t_tiles = ct;
       a.out = m->pb_x; a.ldo = H;
-      const int shape = tile_shape(a.n_tiles);
-      pending = resid_split(a, shape);
+      const int shape = plan_gemm(a, EPI_RESID, &pending);
       RUN(FAM_PGEMM_O, (double)H * Dq * w, 2.0 * H * Dq * T, launch_gemm_prefill(s, f16, EPI_RESID, a, pieces, shape));
     }
     RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, f16, m->pb_x, m->pb_part, pending, part_stride, L.g_post, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
@@ -967,14 +1013,13 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
       PrefillGemmArgs a{};
       a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
       a.packed_out = m->pb_fb;
-      RUN(FAM_PGEMM_GU, 2.0 * F * H * w, 4.0 * F * H * T, launch_gemm_prefill(s, f16, EPI_SWIGLU, a, pieces, tile_shape(a.n_tiles)));
+      RUN(FAM_PGEMM_GU, 2.0 * F * H * w, 4.0 * F * H * T, launch_gemm_prefill(s, f16, EPI_SWIGLU, a, pieces, plan_gemm(a, EPI_SWIGLU, nullptr)));
     }
     {
       PrefillGemmArgs a{};
       a.Wp = L.wd; a.n_tiles = H / 16; a.KT = F / 32; a.Xf = m->pb_fb; a.t_tiles = ct;
       a.out = m->pb_x; a.ldo = H;
-      const int shape = tile_shape(a.n_tiles);
-      pending = resid_split(a, shape);
+      const int shape = plan_gemm(a, EPI_RESID, &pending);
       RUN(FAM_PGEMM_D, (double)H * F * w, 2.0 * H * F * T, launch_gemm_prefill(s, f16, EPI_RESID, a, pieces, shape));
     }
   }
@@ -1374,6 +1419,42 @@ nnc_status nnc_stage_trace(nnc_model* m, uint64_t* out, uint32_t cap, uint32_t* 
   HIP_TRY(hipMemcpy(out, m->mk_trace, (size_t)m->mk_nwg * np * 8, hipMemcpyDeviceToHost));
   *workgroups = (uint32_t)m->mk_nwg;
   *points = np;
+  return NNC_OK;
+}
+
+nnc_status nnc_plan_prefill_gemm_query(uint32_t rows, uint32_t k, uint32_t n_tokens, uint32_t pieces, uint32_t epilogue,
+                                       uint32_t max_k_slices, uint32_t n_cus, nnc_gemm_plan* out) {
+  if (!out) return fail(NNC_E_ARG, "out is NULL");
+  if (!rows || rows % 16 || !k || k % 32 || !n_tokens || pieces < 1 || pieces > 2 || epilogue > 2 || !max_k_slices)
+    return fail(NNC_E_ARG, "bad GEMM shape for the planner");
+  const Machine mc = machine_mi355x((int)n_cus);
+  const int ct = (int)((n_tokens + 15) / 16 * pieces);
+  const PrefillGemmPlan p = plan_prefill_gemm(mc, (int)(rows / 16), (int)(k / 32), ct, (int)n_tokens, (int)pieces,
+                                              (int)epilogue, (int)max_k_slices);
+  nnc_gemm_plan o{};
+  o.tile_rows = (uint32_t)p.nt * 16; o.tile_cols = (uint32_t)p.tt * 16; o.tile_code = p.tile;
+  o.k_slices = (uint32_t)p.k_slices; o.workgroups = (uint32_t)p.workgroups;
+  o.t_comp_us = p.t_comp_us; o.t_mem_us = p.t_mem_us; o.t_us = p.t_us;
+  o.candidates = (uint32_t)p.candidates; o.rejected_by_capacity = (uint32_t)p.rejected_by_capacity;
+  *out = o;
+  return NNC_OK;
+}
+
+nnc_status nnc_plan_skinny_gemm_query(uint32_t rows, uint32_t k, uint32_t n_seq, uint32_t pieces, uint32_t epilogue,
+                                      uint32_t max_k_slices, uint32_t n_cus, nnc_gemm_plan* out) {
+  if (!out) return fail(NNC_E_ARG, "out is NULL");
+  if (!rows || rows % 16 || !k || k % 32 || !n_seq || pieces < 1 || pieces > 3 || n_seq * pieces > (uint32_t)MAX_COLS ||
+      epilogue > 2 || epilogue == 1 || !max_k_slices)
+    return fail(NNC_E_ARG, "bad GEMM shape for the planner");
+  const Machine mc = machine_mi355x((int)n_cus);
+  const int rts = epilogue == 2 ? ((1 << 2) | (1 << 4)) : ((1 << 1) | (1 << 2) | (1 << 4));
+  const SkinnyGemmPlan p = plan_skinny_gemm(mc, (int)(rows / 16), (int)(k / 32), (int)(n_seq * pieces), (int)n_seq, rts,
+                                            (int)std::min<uint32_t>(max_k_slices, MAX_KSPLIT));
+  nnc_gemm_plan o{};
+  o.tile_rows = (uint32_t)p.rt * 16; o.tile_cols = n_seq * pieces; o.tile_code = p.rt;
+  o.k_slices = (uint32_t)p.k_slices; o.workgroups = (uint32_t)p.workgroups;
+  o.t_comp_us = p.t_operand_us; o.t_mem_us = p.t_mem_us; o.t_us = p.t_us;
+  *out = o;
   return NNC_OK;
 }
 

@@ -77,6 +77,8 @@ struct GemmArgs {
   void* packed_out;
   int NC_out;
   int nsplit_out;
+  // 16-row tiles per workgroup (1, 2 or 4; SwiGLU: 2 or 4); 0: the launcher's own rule
+  int rt;
 };
 
 struct KernelCtx;  // profiling hook, defined in nnc_api.hip

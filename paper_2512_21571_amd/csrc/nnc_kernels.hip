@@ -501,11 +501,21 @@ hipError_t launch_gemm(hipStream_t s, int dt, int epi, const GemmArgs& a) {
       a.kts_per_split <= 0 || a.n_tiles <= 0)
     return hipErrorInvalidValue;
   const bool wide = a.n_tiles >= 1024 && (a.n_tiles % 2 == 0);
-  if (epi == EPI_SWIGLU) {
-    if (a.n_tiles % 2 || a.kts_per_split < a.KT) return hipErrorInvalidValue;
-    NNC_FOR_DTYPE(dt, return gemm_dispatch_rt<F32, EPI_SWIGLU, 2, HF>(s, a));
+  if (epi != EPI_STORE && epi != EPI_SWIGLU) return hipErrorInvalidValue;
+  if (epi == EPI_SWIGLU && (a.n_tiles % 2 || a.kts_per_split < a.KT)) return hipErrorInvalidValue;
+  if (a.rt > 0) {  // row tiles per workgroup chosen by the caller (the analytic planner)
+    if (a.n_tiles % a.rt || (epi == EPI_SWIGLU && a.rt % 2)) return hipErrorInvalidValue;
+    if (epi == EPI_SWIGLU) {
+      if (a.rt == 2) NNC_FOR_DTYPE(dt, return gemm_dispatch_ncb<F32, EPI_SWIGLU, 2, HF>(s, a));
+      if (a.rt == 4) NNC_FOR_DTYPE(dt, return gemm_dispatch_ncb<F32, EPI_SWIGLU, 4, HF>(s, a));
+      return hipErrorInvalidValue;
+    }
+    if (a.rt == 1) NNC_FOR_DTYPE(dt, return gemm_dispatch_ncb<F32, EPI_STORE, 1, HF>(s, a));
+    if (a.rt == 2) NNC_FOR_DTYPE(dt, return gemm_dispatch_ncb<F32, EPI_STORE, 2, HF>(s, a));
+    if (a.rt == 4) NNC_FOR_DTYPE(dt, return gemm_dispatch_ncb<F32, EPI_STORE, 4, HF>(s, a));
+    return hipErrorInvalidValue;
   }
-  if (epi != EPI_STORE) return hipErrorInvalidValue;
+  if (epi == EPI_SWIGLU) NNC_FOR_DTYPE(dt, return gemm_dispatch_rt<F32, EPI_SWIGLU, 2, HF>(s, a));
   if (wide) NNC_FOR_DTYPE(dt, return gemm_dispatch_rt<F32, EPI_STORE, 2, HF>(s, a));
   NNC_FOR_DTYPE(dt, return gemm_dispatch_rt<F32, EPI_STORE, 1, HF>(s, a));
 }

@@ -1,0 +1,133 @@
+// Analytic tile chooser: see nnc_plan.h for the model (paper Section 3.2.2).
+#include "nnc_plan.h"
+
+#include <algorithm>
+#include <cmath>
+
+namespace nnc {
+
+Machine machine_mi355x(int cus) {
+  Machine m{};
+  m.cus = cus > 0 ? cus : 256;
+  m.lds_bytes = 160 * 1024;
+  m.vgprs_per_wave = 256;
+  // measured on these kernels, not datasheet values: the skinny GEMM streams weights at 5.8 TB/s
+  // once every CU has work; 768 workgroups re-reading one 393 KB operand cost what 46 TB/s would
+  m.hbm_bytes_per_us = 5.8e6;
+  m.l2_operand_bytes_per_us = 46e6;
+  m.launch_us = 5.0;
+  // prompt GEMM, time per k step with two workgroups per CU, measured at the 4B / 8B shapes:
+  // 0.48 us for 128 x 128 tiles (16 matrix-core instructions per wave), 0.726 for 192 x 128 (24),
+  // 0.865 for 256 x 128 (32): least-squares line through the three; a lone workgroup on a CU
+  // takes 0.78 x that
+  m.pg_c1 = 0.0241;
+  m.pg_c0 = 0.110;
+  m.pg_solo = 0.78;
+  // the register-ring kernel of the 64-row tiles: 0.26 us per k step with 4 matrix-core
+  // instructions per wave (64 x 64), 0.37 with 8 (64 x 128)
+  m.rg_c1 = 0.0275;
+  m.rg_c0 = 0.150;
+  return m;
+}
+
+namespace {
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+struct PgTile {
+  int code, nt, tt;
+  bool lds_direct;  // three LDS stages filled by direct copies, no k split; else register ring, two stages
+};
+// every block tile the prompt GEMM kernels are instantiated for, plus one that is not (256 x 256
+// with four waves: it shows the capacity constraints at work and is never chosen)
+const PgTile kPgTiles[] = {{1, 16, 8, true}, {4, 12, 8, true}, {2, 8, 8, true}, {0, 4, 8, false}, {3, 4, 4, false},
+                           {-1, 16, 16, true}};
+}  // namespace
+
+PrefillGemmPlan plan_prefill_gemm(const Machine& mc, int n_tiles, int KT, int col_tiles, int n_tokens, int pieces,
+                                  int epi, int max_k_slices) {
+  PrefillGemmPlan best{};
+  best.tile = -1;
+  best.t_us = 1e30;
+  const double W = (double)n_tiles * KT * 1024.0, X = (double)col_tiles * KT * 1024.0;
+  const double N = (double)n_tiles * 16.0;
+  const double out_bytes = epi == PLAN_EPI_STORE ? n_tokens * N * 4.0
+                           : epi == PLAN_EPI_RESID ? n_tokens * N * 8.0  // read-modify-write of the residual stream
+                                                   : n_tokens * (N / 2.0) * 2.0 * pieces;
+  const int wgs_per_cu = 2;  // the kernels are built for two resident workgroups per CU
+  for (const PgTile& t : kPgTiles) {
+    ++best.candidates;
+    // capacity: staged operands of the resident workgroups in LDS; accumulators and two sets of
+    // fragments (one for the ring kernels) in the wave's registers
+    const int stages = t.lds_direct ? 3 : 2;
+    const int lds = stages * (t.nt + t.tt) * 1024 * wgs_per_cu;
+    const int wi = t.nt / 2, wj = t.tt / 2;
+    const int regs = wi * wj * 4 + (t.lds_direct ? 2 : 1) * (wi + wj) * 4 + (t.lds_direct ? 0 : 8 * (t.nt / 4 + t.tt / 4) * 4);
+    if (lds > mc.lds_bytes || regs > mc.vgprs_per_wave || t.code < 0) {
+      ++best.rejected_by_capacity;
+      continue;
+    }
+    const int ks_max = (t.lds_direct || epi != PLAN_EPI_RESID) ? 1 : std::max(1, max_k_slices);
+    for (int ks = 1; ks <= ks_max; ++ks) {
+      const int kts = ceil_div(KT, ks);
+      if (ks > 1 && kts < 8) break;          // a slice shorter than the register ring gains nothing
+      const int slices = ceil_div(KT, kts);
+      if (slices != ks) continue;            // same launch as a smaller ks
+      const int wgs = ceil_div(n_tiles, t.nt) * ceil_div(col_tiles, t.tt) * slices;
+      const int slots = wgs_per_cu * mc.cus;
+      const int full = wgs / slots, rem = wgs - full * slots;
+      const double t2 = t.lds_direct ? mc.pg_c0 + mc.pg_c1 * wi * wj : mc.rg_c0 + mc.rg_c1 * wi * wj;
+      const double t1 = mc.pg_solo * t2;
+      const double t_comp = kts * (full * t2 + (rem == 0 ? 0.0 : rem <= mc.cus ? t1 : t2));
+      const double fold = (slices - 1) * n_tokens * N * 4.0 * 2.0;  // partials written, then read by the norm kernel
+      const double t_mem = (W + X) / mc.hbm_bytes_per_us;
+      const double total = std::max(t_comp, t_mem) + (out_bytes + fold) / mc.hbm_bytes_per_us + mc.launch_us;
+      if (total < best.t_us * 0.999) {
+        best.tile = t.code; best.nt = t.nt; best.tt = t.tt;
+        best.k_slices = slices; best.kts_per_split = slices > 1 ? kts : 0;
+        best.workgroups = wgs;
+        best.t_comp_us = t_comp; best.t_mem_us = t_mem; best.t_us = total;
+      }
+    }
+  }
+  return best;
+}
+
+SkinnyGemmPlan plan_skinny_gemm(const Machine& mc, int n_tiles, int KT, int ncols, int nseq, int rt_choices,
+                                int max_k_slices) {
+  SkinnyGemmPlan best{};
+  best.rt = 0;
+  best.t_us = 1e30;
+  const double W = (double)n_tiles * KT * 1024.0;
+  // operand bytes per k tile: one 16-byte group per (k / 8 or k / 4, column), i.e. 64 bytes per
+  // column, and the kernel loads whole blocks of 16 columns
+  const double x_per_kt = 64.0 * ((ncols + 15) / 16 * 16);
+  for (int rt = 1; rt <= 8; ++rt) {
+    if (!((rt_choices >> rt) & 1) || n_tiles % rt) continue;
+    for (int ks = 1; ks <= std::max(1, max_k_slices); ++ks) {
+      const int kts = ceil_div(KT, ks);
+      if (ks > 1 && kts < 8) break;  // at least two k tiles per wave
+      const int slices = ceil_div(KT, kts);
+      if (slices != ks) continue;
+      const int wgs = n_tiles / rt * slices;
+      // every CU streams at its share of the rate once it has a workgroup; a launch whose busiest
+      // CU holds more workgroups than the average takes that much longer
+      const double per_cu = (double)wgs / mc.cus;
+      const double eff = wgs <= mc.cus ? per_cu : per_cu / std::ceil(per_cu);
+      const double t_mem = W / (mc.hbm_bytes_per_us * eff);
+      // every workgroup reads the operand of its k slice (its RT row tiles share it)
+      const double t_opnd = (double)wgs * kts * x_per_kt / mc.l2_operand_bytes_per_us;
+      // partial sums: written per slice and read once more by the consumer, a norm kernel of one
+      // workgroup per sequence that runs at an eighth of the streaming rate at best (measured: six
+      // slices instead of three cost the 4B down projection more than the halved operand reads save)
+      const double fold = slices > 1 ? slices * (double)n_tiles * 16.0 * nseq * 4.0 * 2.0 / (mc.hbm_bytes_per_us / 8.0) : 0.0;
+      const double total = t_mem + t_opnd + fold + mc.launch_us;
+      if (total < best.t_us * 0.999) {
+        best.rt = rt; best.k_slices = slices; best.kts_per_split = kts; best.workgroups = wgs;
+        best.t_mem_us = t_mem; best.t_operand_us = t_opnd; best.t_us = total;
+      }
+    }
+  }
+  return best;
+}
+
+}  // namespace nnc

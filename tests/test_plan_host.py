@@ -1,0 +1,98 @@
+"""The analytic tile chooser (host code, no GPU): constraints, objective, and that it lands on
+the choices that were found by hand and measured on the large shapes.
+
+Model after the paper's parametric optimisation (Section 3.2.2): tile variables, capacity
+constraints per storage level, minimise max(T_mem, T_comp) + launch and epilogue time.
+"""
+import pytest
+
+from paper_2512_21571_amd import binding as nnc
+
+STORE, RESID, SWIGLU = 0, 1, 2
+SHAPES = {  # hidden, Dq, Dkv, ffn
+    "0.6b": (1024, 2048, 1024, 3072), "1.7b": (2048, 2048, 1024, 6144),
+    "4b": (2560, 4096, 1024, 9728), "8b": (4096, 4096, 1024, 12288)}
+V = 151936
+
+
+def _gemms(name):
+    H, Dq, Dkv, F = SHAPES[name]
+    return {"qkv": (Dq + 2 * Dkv, H, STORE), "o": (H, Dq, RESID), "gate_up": (2 * F, H, SWIGLU), "down": (H, F, RESID)}
+
+
+def test_capacity_constraints_rule_out_what_does_not_fit():
+    p = nnc.plan_prefill_gemm(24576, 4096, 4080, 1, SWIGLU)
+    assert p.candidates == 6 and p.rejected_by_capacity == 1       # 256 x 256: 3 stages x 32 KiB x 2 workgroups > 160 KiB
+    assert (p.tile_rows, p.tile_cols) == (256, 128)
+
+
+@pytest.mark.parametrize("name,tokens,want", [
+    # the block tiles measured best by hand at the benchmark shapes (rows x 128 operand columns)
+    ("8b", 4080, {"qkv": 192, "o": 256, "gate_up": 256, "down": 256}),
+    ("8b", 2032, {"qkv": 192, "o": 128, "gate_up": 256, "down": 128}),
+    ("4b", 4080, {"qkv": 192, "o": 192, "gate_up": 256, "down": 192}),
+    ("4b", 2032, {"qkv": 192, "o": 128, "gate_up": 256, "down": 128}),   # gate|up: 256 measured 197 us, 128 (the hand rule) 201
+    ("1.7b", 4080, {"qkv": 256, "o": 128, "gate_up": 256, "down": 128}),
+])
+def test_prompt_gemm_tiles_at_the_benchmark_shapes(name, tokens, want):
+    for g, (rows, k, epi) in _gemms(name).items():
+        p = nnc.plan_prefill_gemm(rows, k, tokens, 1, epi)
+        assert p.tile_cols == 128 and p.tile_rows == want[g], (g, p.tile_rows, p.tile_cols)
+        assert p.k_slices == 1                                       # the LDS-direct kernels never split k
+        assert p.t_us >= max(p.t_comp_us, p.t_mem_us)                # objective: max(T_mem, T_comp) + epilogue + launch
+
+
+def test_model_times_are_close_to_the_measured_ones():
+    # 8B shapes, 4080-token block, microseconds measured with HIP events around each launch
+    measured = {"qkv": 185, "o": 134, "gate_up": 673, "down": 335}
+    for g, (rows, k, epi) in _gemms("8b").items():
+        p = nnc.plan_prefill_gemm(rows, k, 4080, 1, epi)
+        assert abs(p.t_us - measured[g]) / measured[g] < 0.12, (g, p.t_us)
+    # batched decode GEMMs of the 8B shape, 16 sequences x 3 pieces
+    H, Dq, Dkv, F = SHAPES["8b"]
+    for rows, k, epi, ks, us in ((Dq + 2 * Dkv, H, STORE, 1, 21.2), (2 * F, H, SWIGLU, 1, 45.9), (H, F, STORE, 8, 25.2),
+                                 (V, H, STORE, 1, 225.0)):
+        p = nnc.plan_skinny_gemm(rows, k, 16, 3, epi, ks)
+        assert abs(p.t_us - us) / us < 0.20, (rows, p.t_us)
+
+
+def test_short_prompts_are_memory_bound_and_may_split_k():
+    # 128 tokens of the 0.6B shape: the narrow projections have too few tiles for the chip, the
+    # model splits k (the epilogue adds partial sums) and picks small tiles
+    rows, k, epi = _gemms("0.6b")["o"]
+    one = nnc.plan_prefill_gemm(rows, k, 128, 2, epi, 1)
+    many = nnc.plan_prefill_gemm(rows, k, 128, 2, epi, 4)
+    assert many.k_slices > 1 and many.tile_rows == 64 and many.t_us < one.t_us
+    assert many.workgroups >= 256
+    # never beyond what the caller allows, never slices shorter than 8 k steps
+    for ks in (1, 2, 3, 4):
+        p = nnc.plan_prefill_gemm(rows, k, 128, 2, epi, ks)
+        assert 1 <= p.k_slices <= ks and (k // 32) / p.k_slices >= 8
+    # QKV cannot split (its consumer wants the full sums)
+    rows, k, epi = _gemms("0.6b")["qkv"]
+    assert nnc.plan_prefill_gemm(rows, k, 128, 2, epi, 1).k_slices == 1
+
+
+def test_skinny_gemm_plans_at_the_batched_workloads():
+    H, Dq, Dkv, F = SHAPES["8b"]
+    assert nnc.plan_skinny_gemm(Dq + 2 * Dkv, H, 16, 3, STORE).tile_code == 2           # 192 workgroups of two tiles
+    gu = nnc.plan_skinny_gemm(2 * F, H, 16, 3, SWIGLU)
+    assert gu.tile_code == 2 and gu.workgroups == 768                                    # three per CU, not 384 of four
+    head = nnc.plan_skinny_gemm(V, H, 16, 3, STORE)
+    assert head.tile_code == 4                                                           # operand re-reads dominate the choice
+    down = nnc.plan_skinny_gemm(H, F, 16, 3, STORE, 8)
+    assert down.workgroups % 256 == 0 and 1 < down.k_slices <= 8
+    # batch 1: nothing to re-read, the choice is about filling the chip
+    assert nnc.plan_skinny_gemm(V, 1024, 1, 3, STORE).workgroups >= 2048
+    H4, Dq4, _, F4 = SHAPES["4b"]
+    d4 = nnc.plan_skinny_gemm(H4, F4, 8, 3, STORE, 8)
+    assert (d4.tile_code, d4.k_slices, d4.workgroups) == (2, 3, 240)                     # 80 tile pairs x 3 slices
+
+
+def test_planner_rejects_bad_shapes():
+    with pytest.raises(nnc.NncError):
+        nnc.plan_prefill_gemm(100, 4096, 128, 1, STORE)        # rows not a multiple of 16
+    with pytest.raises(nnc.NncError):
+        nnc.plan_skinny_gemm(4096, 4096, 30, 3, STORE)         # 90 operand columns: more than a pass carries
+    with pytest.raises(nnc.NncError):
+        nnc.plan_skinny_gemm(4096, 4096, 4, 3, RESID)          # no such epilogue for the streaming GEMM
