@@ -77,7 +77,7 @@ struct nnc_model {
 
   ColState* st = nullptr;
   float* x = nullptr;        // [MAX_COLS][H] residual stream
-  float* qkv = nullptr;      // [MAX_COLS][Dq + 2 Dkv]
+  float* qkv = nullptr;      // [MAX_QKV_SLICES][MAX_COLS][Dq + 2 Dkv] (k-slice partial sums in fused decode passes)
   void* Xp = nullptr;        // packed operand, K = H
   void* Ap = nullptr;        // packed operand, K = max(Dq, F)
   float* rpart = nullptr;    // [MAX_KSPLIT][MAX_COLS][H] k-slice partials of the O / down projections
@@ -285,11 +285,15 @@ int pick_kts(int n_tiles, int KT) {
 // Row tiles per workgroup and k slices of a weight-streaming GEMM from the analytic model
 // (the hand rules: pick_kts above and the launcher's own row-tile rule, stay in `a` when the
 // planner is switched off).
-void plan_skinny(const nnc_model* m, GemmArgs& a, int epi, bool may_split) {
+constexpr int MAX_QKV_SLICES = 4;  // k slices of the QKV projection that the fused attention kernel adds up
+int skinny_rt_choices(int dt, int epi) {
+  if (dt == (int)NNC_F32) return epi == EPI_SWIGLU ? ((1 << 2) | (1 << 4)) : ((1 << 1) | (1 << 2) | (1 << 4));
+  return epi == EPI_SWIGLU ? ((1 << 2) | (1 << 4) | (1 << 6) | (1 << 8)) : ((1 << 1) | (1 << 2) | (1 << 3) | (1 << 4) | (1 << 6));
+}
+void plan_skinny(const nnc_model* m, GemmArgs& a, int epi, int max_slices) {
   if (!m->opt_planner) return;
   const Machine mc = machine_mi355x(m->n_cus);
-  const int rts = epi == EPI_SWIGLU ? ((1 << 2) | (1 << 4)) : ((1 << 1) | (1 << 2) | (1 << 4));
-  const SkinnyGemmPlan pl = plan_skinny_gemm(mc, a.n_tiles, a.KT, a.ncols, a.nseq, rts, may_split ? MAX_KSPLIT : 1);
+  const SkinnyGemmPlan pl = plan_skinny_gemm(mc, a.n_tiles, a.KT, a.ncols, a.nseq, skinny_rt_choices(m->dt, epi), max_slices);
   if (pl.rt <= 0) return;
   a.rt = pl.rt;
   a.kts_per_split = pl.kts_per_split;
@@ -334,16 +338,19 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
     if (m->wait_layers) HIP_TRY(hipStreamWaitEvent(s, m->layer_done[li], 0));
     RUN(FAM_NORM, n * H * 8.0, 0,
         launch_rmsnorm_pack(s, dt, m->x, H, m->rpart, pending, pstride, L.g_in, H, c.rms_eps, n, m->Xp, nc, ns));
+    const bool fuse = p.decode && m->opt_fuse_qk && attn_partial_can_fuse(dt, nq, nkv);
+    int qkv_slices = 1;
     {
       GemmArgs a{};
       a.Wp = L.wqkv; a.n_tiles = Nqkv / 16; a.KT = KTH; a.kts_per_split = KTH;
       a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
-      a.out = m->qkv; a.ldo = Nqkv;
-      plan_skinny(m, a, EPI_STORE, false);
+      a.out = m->qkv; a.ldo = Nqkv; a.split_stride = (long)n * Nqkv;
+      // the fused attention kernel adds k-slice partial sums itself; every other consumer wants full sums
+      plan_skinny(m, a, EPI_STORE, fuse ? MAX_QKV_SLICES : 1);
+      qkv_slices = (KTH + a.kts_per_split - 1) / a.kts_per_split;
       RUN(FAM_GEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * n, launch_gemm(s, dt, EPI_STORE, a));
     }
-    const bool fuse = p.decode && m->opt_fuse_qk && attn_partial_can_fuse(dt, nq, nkv);
-    const AttnFuseArgs fz{L.g_q, L.g_k, c.rms_eps, m->rope};
+    const AttnFuseArgs fz{L.g_q, L.g_k, c.rms_eps, m->rope, qkv_slices, (long)n * Nqkv};
     if (!fuse)
       RUN(FAM_QKROPE, n * Nqkv * 4.0, 0,
           launch_qknorm_rope_append(s, dt, m->qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, n,
@@ -358,7 +365,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Wp = L.wo; a.n_tiles = H / 16; a.KT = KTQ; a.kts_per_split = pick_kts(a.n_tiles, KTQ);
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
-      plan_skinny(m, a, EPI_STORE, true);
+      plan_skinny(m, a, EPI_STORE, MAX_KSPLIT);
       pending = (KTQ + a.kts_per_split - 1) / a.kts_per_split;
       RUN(FAM_GEMM_O, (double)H * Dq * w, 2.0 * H * Dq * n, launch_gemm(s, dt, EPI_STORE, a));
     }
@@ -369,7 +376,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = KTH; a.kts_per_split = KTH;
       a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.packed_out = m->Ap; a.NC_out = nc; a.nsplit_out = ns;
-      plan_skinny(m, a, EPI_SWIGLU, false);
+      plan_skinny(m, a, EPI_SWIGLU, 1);
       RUN(FAM_GEMM_GU, 2.0 * F * H * w, 4.0 * F * H * n, launch_gemm(s, dt, EPI_SWIGLU, a));
     }
     {
@@ -377,7 +384,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Wp = L.wd; a.n_tiles = H / 16; a.KT = KTF; a.kts_per_split = pick_kts(a.n_tiles, KTF);
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
-      plan_skinny(m, a, EPI_STORE, true);
+      plan_skinny(m, a, EPI_STORE, MAX_KSPLIT);
       pending = (KTF + a.kts_per_split - 1) / a.kts_per_split;
       RUN(FAM_GEMM_D, (double)H * F * w, 2.0 * H * F * n, launch_gemm(s, dt, EPI_STORE, a));
     }
@@ -392,7 +399,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
     a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = KTH; a.kts_per_split = KTH;
     a.Xp = m->Xp; a.NC = hc; a.ncols = hc; a.nsplit = ns; a.nseq = hn;
     a.out = p.logits; a.ldo = p.logits_ld; a.step_ptr = p.step_ptr; a.step_stride = p.step_stride;
-    plan_skinny(m, a, EPI_STORE, false);
+    plan_skinny(m, a, EPI_STORE, 1);
     RUN(FAM_GEMM_HEAD, (double)V * H * w, 2.0 * V * H * hn, launch_gemm(s, dt, EPI_STORE, a));
     if (p.next)
       RUN(FAM_ARGMAX, hn * V * 4.0, 0,
@@ -708,7 +715,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
   m->max_chunks = chunks_grid(c.max_seq - 1);
   ALLOC(m->st, ColState*, sizeof(ColState));
   ALLOC(m->x, float*, (size_t)MAX_COLS * H * 4);
-  ALLOC(m->qkv, float*, (size_t)MAX_COLS * (Dq + 2 * Dkv) * 4);
+  ALLOC(m->qkv, float*, (size_t)MAX_QKV_SLICES * MAX_COLS * (Dq + 2 * Dkv) * 4);
   ALLOC(m->Xp, void*, (size_t)MAX_COLS * H * w);
   ALLOC(m->Ap, void*, (size_t)MAX_COLS * std::max(Dq, F) * w);
   ALLOC(m->rpart, float*, (size_t)MAX_KSPLIT * MAX_COLS * H * 4);
@@ -1282,7 +1289,7 @@ nnc_status nnc_decode_step_static(nnc_model* m, const uint32_t* slots, const int
     off += (bytes + 255) / 256 * 256;
     return at;
   };
-  const size_t o_st = take(sizeof(ColState)), o_x = take(B * H * 4), o_qkv = take(B * (Dq + 2 * Dkv) * 4),
+  const size_t o_st = take(sizeof(ColState)), o_x = take(B * H * 4), o_qkv = take((size_t)MAX_QKV_SLICES * B * (Dq + 2 * Dkv) * 4),
                o_Xp = take(B * nsplit * H * w), o_Ap = take(B * nsplit * std::max(Dq, F) * w),
                o_rpart = take((size_t)MAX_KSPLIT * B * H * 4),
                o_partial = take(B * m->c.n_q_heads * (size_t)grid_chunks * 132 * 4),
@@ -1447,8 +1454,8 @@ nnc_status nnc_plan_skinny_gemm_query(uint32_t rows, uint32_t k, uint32_t n_seq,
       epilogue > 2 || epilogue == 1 || !max_k_slices)
     return fail(NNC_E_ARG, "bad GEMM shape for the planner");
   const Machine mc = machine_mi355x((int)n_cus);
-  const int rts = epilogue == 2 ? ((1 << 2) | (1 << 4)) : ((1 << 1) | (1 << 2) | (1 << 4));
-  const SkinnyGemmPlan p = plan_skinny_gemm(mc, (int)(rows / 16), (int)(k / 32), (int)(n_seq * pieces), (int)n_seq, rts,
+  const SkinnyGemmPlan p = plan_skinny_gemm(mc, (int)(rows / 16), (int)(k / 32), (int)(n_seq * pieces), (int)n_seq,
+                                            skinny_rt_choices((int)NNC_BF16, (int)epilogue),
                                             (int)std::min<uint32_t>(max_k_slices, MAX_KSPLIT));
   nnc_gemm_plan o{};
   o.tile_rows = (uint32_t)p.rt * 16; o.tile_cols = n_seq * pieces; o.tile_code = p.rt;

@@ -77,7 +77,8 @@ struct GemmArgs {
   void* packed_out;
   int NC_out;
   int nsplit_out;
-  // 16-row tiles per workgroup (1, 2 or 4; SwiGLU: 2 or 4); 0: the launcher's own rule
+  // 16-row tiles per workgroup (1, 2, 3, 4 or 6; SwiGLU: 2, 4, 6 or 8; fp32 models: 1, 2 or 4);
+  // 0: the launcher's own rule
   int rt;
 };
 
@@ -108,6 +109,10 @@ struct AttnFuseArgs {
   const float* gk;
   float eps;
   const float2* rope;
+  // the raw projection arrives as qkv_slices partial sums (k slices of the QKV GEMM),
+  // qkv_slice_stride floats apart; the kernel adds them in slice order (0 or 1: one array)
+  int qkv_slices;
+  long qkv_slice_stride;
 };
 bool attn_partial_can_fuse(int dt, int nq, int nkv);
 hipError_t launch_attn_partial(hipStream_t s, int dt, const float* qkv, const void* qsplit, int nq, int nkv,

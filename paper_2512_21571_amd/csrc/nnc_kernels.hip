@@ -21,6 +21,16 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Launch one instance of a kernel template for the model's element type: inside the statement
 // F32 is a constant expression and HF names the 16-bit format (unused by fp32 instances).
+#define NNC_FOR_HALF(dt, ...)   \
+  do {                          \
+    if ((dt) == DT_F16) {       \
+      using HF = Fp16;          \
+      __VA_ARGS__;              \
+    } else {                    \
+      using HF = Bf16;          \
+      __VA_ARGS__;              \
+    }                           \
+  } while (0)
 #define NNC_FOR_DTYPE(dt, ...)              \
   do {                                      \
     if ((dt) == DT_F32) {                   \
@@ -317,8 +327,11 @@ hipError_t launch_fold_residual(hipStream_t s, float* x, const float* part, int 
 // of each activation column and stores / accumulates / applies SwiGLU.
 template <bool F32, int NCB, int RT, int EPI, int U, class HF>
 __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
-  __shared__ float red[4][RT][NCB][256];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  constexpr int RC = RT % 2 == 0 ? 2 : 1;  // row tiles per round of the cross-wave reduction
+  __shared__ float red[4][RC][NCB][256];
+  // the wave index as a scalar: every k-tile address below is then a scalar base plus a
+  // per-lane offset that does not change in the loop
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int c16 = lane & 15, g = lane >> 4;
   const int KT = a.KT;
   const int kt_begin = blockIdx.y * a.kts_per_split;
@@ -334,110 +347,127 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
     for (int cb = 0; cb < NCB; ++cb) acc[rt][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // Two register sets of U k tiles each: the loads of the next group are in flight while the
-  // matrix cores work on the current one.  Loads are unconditional (indices clamped, the weight
-  // fragment zeroed by a select when its k tile lies past the slice), so the loop has no
-  // data-dependent branch and the compiler can wait for exactly the set it needs.  Native
-  // vector types: arrays of the HIP uint4 struct carried across a loop end up in scratch memory.
+  // matrix cores work on the current one.  The pipelined loop runs over this wave's full groups
+  // of U k tiles; its loads are unconditional (a group index past the end is clamped to the
+  // wave's last k tile: a repeated read that is never multiplied), so the loop has no
+  // data-dependent branch and no select on loaded data, and the compiler waits for exactly the
+  // set it needs.  The k tiles left over (fewer than U) follow one at a time.  Native vector
+  // types: arrays of the HIP uint4 struct carried across a loop end up in scratch memory.
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   const u32x4* __restrict__ Wv = reinterpret_cast<const u32x4*>(W);
   const u32x4* __restrict__ Xv = reinterpret_cast<const u32x4*>(X);
-  int bcol[NCB];
+  int xoff[NCB];  // operand fragment of this lane within a k tile's 4 x NC groups of 16 bytes
 #pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) bcol[cb] = min(cb * 16 + c16, a.NC - 1);
+  for (int cb = 0; cb < NCB; ++cb) xoff[cb] = g * a.NC + min(cb * 16 + c16, a.NC - 1);
+  // this wave's k tiles: first, first + 4, ... (n_mine of them)
+  const int first = kt_begin + wave;
+  const int n_mine = first < kt_end ? (kt_end - first + 3) >> 2 : 0;
+  const int last_kt = first + 4 * (n_mine - 1);
   u32x4 avA[U][RT], bvA[U][NCB], avB[U][RT], bvB[U][NCB];
-  auto load_group = [&](int kt0, u32x4(&av)[U][RT], u32x4(&bv)[U][NCB]) __attribute__((always_inline)) {
+  auto load_tile = [&](int kt, u32x4(&av)[RT], u32x4(&bv)[NCB]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int kt = kt0 + 4 * u, ktc = min(kt, kt_end - 1);
-      const bool ok = kt < kt_end;
+    for (int rt = 0; rt < RT; ++rt) av[rt] = __builtin_nontemporal_load(&(Wv + ((tile0 + rt) * KT + kt) * 64)[lane]);
+    const u32x4* xk = Xv + (size_t)kt * 4 * a.NC;
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        const u32x4 t = __builtin_nontemporal_load(&Wv[((tile0 + rt) * KT + ktc) * 64 + lane]);
-        av[u][rt] = ok ? t : u32x4{0u, 0u, 0u, 0u};
-      }
-#pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) bv[u][cb] = Xv[((size_t)ktc * 4 + g) * a.NC + bcol[cb]];
-    }
+    for (int cb = 0; cb < NCB; ++cb) bv[cb] = xk[xoff[cb]];
   };
-  auto mma_group = [&](const u32x4(&av)[U][RT], const u32x4(&bv)[U][NCB]) __attribute__((always_inline)) {
+  auto load_group = [&](int t0, u32x4(&av)[U][RT], u32x4(&bv)[U][NCB]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+    for (int u = 0; u < U; ++u) load_tile(min(first + 4 * (t0 + u), last_kt), av[u], bv[u]);
+  };
+  auto mma_tile = [&](const u32x4(&av)[RT], const u32x4(&bv)[NCB]) __attribute__((always_inline)) {
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
+    for (int rt = 0; rt < RT; ++rt) {
 #pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) {
-          if constexpr (F32) {
-            const float4 af = __builtin_bit_cast(float4, av[u][rt]);
-            const float4 bf = __builtin_bit_cast(float4, bv[u][cb]);
-            acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, acc[rt][cb], 0, 0, 0);
-            acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, acc[rt][cb], 0, 0, 0);
-            acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, acc[rt][cb], 0, 0, 0);
-            acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, acc[rt][cb], 0, 0, 0);
-          } else {
-            acc[rt][cb] = HF::mfma(av[u][rt], bv[u][cb], acc[rt][cb]);
-          }
+      for (int cb = 0; cb < NCB; ++cb) {
+        if constexpr (F32) {
+          const float4 af = __builtin_bit_cast(float4, av[rt]);
+          const float4 bf = __builtin_bit_cast(float4, bv[cb]);
+          acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.x, bf.x, acc[rt][cb], 0, 0, 0);
+          acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.y, bf.y, acc[rt][cb], 0, 0, 0);
+          acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.z, bf.z, acc[rt][cb], 0, 0, 0);
+          acc[rt][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(af.w, bf.w, acc[rt][cb], 0, 0, 0);
+        } else {
+          acc[rt][cb] = HF::mfma(av[rt], bv[cb], acc[rt][cb]);
         }
       }
     }
   };
-  if (kt_begin + wave < kt_end) {  // waves without a k tile in this slice keep zero accumulators
-    int kt0 = kt_begin + wave;
-    load_group(kt0, avA, bvA);
-    for (;;) {
-      load_group(kt0 + 4 * U, avB, bvB);
+  auto mma_group = [&](const u32x4(&av)[U][RT], const u32x4(&bv)[U][NCB]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) mma_tile(av[u], bv[u]);
+  };
+  const int n_groups = n_mine / U;
+  if (n_groups > 0) {
+    load_group(0, avA, bvA);
+    // The scheduling barriers keep the order written here: the next set's loads are issued before
+    // the matrix-core work on the current set starts.  Without them the scheduler sinks each set's
+    // loads below the preceding products (shorter live ranges), so that nothing is in flight
+    // while a set is consumed and every pass of the loop pays one full memory latency.
+    for (int gi = 0;;) {
+      load_group((gi + 1) * U, avB, bvB);
+      __builtin_amdgcn_sched_barrier(0);
       mma_group(avA, bvA);
-      kt0 += 4 * U;
-      if (kt0 >= kt_end) break;
-      load_group(kt0 + 4 * U, avA, bvA);
+      __builtin_amdgcn_sched_barrier(0);
+      if (++gi >= n_groups) break;
+      load_group((gi + 1) * U, avA, bvA);
+      __builtin_amdgcn_sched_barrier(0);
       mma_group(avB, bvB);
-      kt0 += 4 * U;
-      if (kt0 >= kt_end) break;
+      __builtin_amdgcn_sched_barrier(0);
+      if (++gi >= n_groups) break;
     }
   }
+  for (int t = n_groups * U; t < n_mine; ++t) {
+    load_tile(first + 4 * t, avA[0], bvA[0]);
+    mma_tile(avA[0], bvA[0]);
+  }
 
-  // accumulator element i of a lane is output row (lane/16)*4 + i, operand column lane%16
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) red[wave][rt][cb][i * 64 + lane] = acc[rt][cb][i];
-  __syncthreads();
-
+  // accumulator element i of a lane is output row (lane/16)*4 + i, operand column lane%16.
+  // The four waves' partial tiles meet in LDS, RC row tiles at a time (one SwiGLU pair), so the
+  // buffer does not grow with RT.
   const int nsplit = a.nsplit, nseq = a.nseq;
-  auto total = [&](int rt, int row, int seq) {
-    float v = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-      const int col = seq * nsplit + s;
-      const int idx = (row & 3) * 64 + (row >> 2) * 16 + (col & 15);
-      const int cb = col >> 4;
-      v += (red[0][rt][cb][idx] + red[1][rt][cb][idx]) + (red[2][rt][cb][idx] + red[3][rt][cb][idx]);
-    }
-    return v;
-  };
-
-  if constexpr (EPI == EPI_SWIGLU) {
-    static_assert(EPI != EPI_SWIGLU || RT % 2 == 0, "SwiGLU needs (gate, up) tile pairs");
-    for (int o = tid; o < (RT / 2) * 16 * nseq; o += 256) {
-      const int pr = o / (16 * nseq);
-      const int rem = o - pr * 16 * nseq;
-      const int seq = rem >> 4, row = rem & 15;
-      const float gate = total(2 * pr, row, seq);
-      const float up = total(2 * pr + 1, row, seq);
-      const float act = gate / (1.0f + expf(-gate)) * up;
-      const int f = (blockIdx.x * (RT / 2) + pr) * 16 + row;
-      store_packed<F32, HF>(a.packed_out, a.NC_out, a.nsplit_out, seq, f, act);
-    }
-  } else {
-    float* out = a.out;
+  float* out = a.out;
+  if constexpr (EPI != EPI_SWIGLU)
     if (a.step_ptr) out += (size_t)(*a.step_ptr) * a.step_stride;
-    for (int o = tid; o < RT * 16 * nseq; o += 256) {
-      const int rt = o / (16 * nseq);
-      const int rem = o - rt * 16 * nseq;
-      const int seq = rem >> 4, row = rem & 15;
-      // each k slice stores its own partial sums: slice s goes to out + s * split_stride
-      out[(size_t)blockIdx.y * a.split_stride + (size_t)seq * a.ldo + (tile0 + rt) * 16 + row] =
-          total(rt, row, seq);
+#pragma unroll
+  for (int ch = 0; ch < RT / RC; ++ch) {
+    if (ch) __syncthreads();
+#pragma unroll
+    for (int r = 0; r < RC; ++r)
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) red[wave][r][cb][i * 64 + lane] = acc[ch * RC + r][cb][i];
+    __syncthreads();
+    auto total = [&](int r, int row, int seq) {
+      float v = 0.f;
+      for (int s = 0; s < nsplit; ++s) {
+        const int col = seq * nsplit + s;
+        const int idx = (row & 3) * 64 + (row >> 2) * 16 + (col & 15);
+        const int cb = col >> 4;
+        v += (red[0][r][cb][idx] + red[1][r][cb][idx]) + (red[2][r][cb][idx] + red[3][r][cb][idx]);
+      }
+      return v;
+    };
+    if constexpr (EPI == EPI_SWIGLU) {
+      static_assert(EPI != EPI_SWIGLU || RT % 2 == 0, "SwiGLU needs (gate, up) tile pairs");
+      for (int o = tid; o < 16 * nseq; o += 256) {
+        const int seq = o >> 4, row = o & 15;
+        const float gate = total(0, row, seq);
+        const float up = total(1, row, seq);
+        const float act = gate / (1.0f + expf(-gate)) * up;
+        const int f = (blockIdx.x * (RT / 2) + ch) * 16 + row;
+        store_packed<F32, HF>(a.packed_out, a.NC_out, a.nsplit_out, seq, f, act);
+      }
+    } else {
+      for (int o = tid; o < RC * 16 * nseq; o += 256) {
+        const int r = o / (16 * nseq);
+        const int rem = o - r * 16 * nseq;
+        const int seq = rem >> 4, row = rem & 15;
+        // each k slice stores its own partial sums: slice s goes to out + s * split_stride
+        out[(size_t)blockIdx.y * a.split_stride + (size_t)seq * a.ldo + (tile0 + ch * RC + r) * 16 + row] =
+            total(r, row, seq);
+      }
     }
   }
 }
@@ -508,11 +538,17 @@ hipError_t launch_gemm(hipStream_t s, int dt, int epi, const GemmArgs& a) {
     if (epi == EPI_SWIGLU) {
       if (a.rt == 2) NNC_FOR_DTYPE(dt, return gemm_dispatch_ncb<F32, EPI_SWIGLU, 2, HF>(s, a));
       if (a.rt == 4) NNC_FOR_DTYPE(dt, return gemm_dispatch_ncb<F32, EPI_SWIGLU, 4, HF>(s, a));
+      if (dt == DT_F32) return hipErrorInvalidValue;
+      if (a.rt == 6) NNC_FOR_HALF(dt, return gemm_dispatch_ncb<false, EPI_SWIGLU, 6, HF>(s, a));
+      if (a.rt == 8) NNC_FOR_HALF(dt, return gemm_dispatch_ncb<false, EPI_SWIGLU, 8, HF>(s, a));
       return hipErrorInvalidValue;
     }
     if (a.rt == 1) NNC_FOR_DTYPE(dt, return gemm_dispatch_ncb<F32, EPI_STORE, 1, HF>(s, a));
     if (a.rt == 2) NNC_FOR_DTYPE(dt, return gemm_dispatch_ncb<F32, EPI_STORE, 2, HF>(s, a));
     if (a.rt == 4) NNC_FOR_DTYPE(dt, return gemm_dispatch_ncb<F32, EPI_STORE, 4, HF>(s, a));
+    if (dt == DT_F32) return hipErrorInvalidValue;
+    if (a.rt == 3) NNC_FOR_HALF(dt, return gemm_dispatch_ncb<false, EPI_STORE, 3, HF>(s, a));
+    if (a.rt == 6) NNC_FOR_HALF(dt, return gemm_dispatch_ncb<false, EPI_STORE, 6, HF>(s, a));
     return hipErrorInvalidValue;
   }
   if (epi == EPI_SWIGLU) NNC_FOR_DTYPE(dt, return gemm_dispatch_rt<F32, EPI_SWIGLU, 2, HF>(s, a));
@@ -524,6 +560,21 @@ hipError_t launch_gemm(hipStream_t s, int dt, int epi, const GemmArgs& a) {
 // device-resident column state; prompt blocks are `ncols` consecutive positions of one slot.
 __device__ __forceinline__ uint32_t col_pos(const ColMap& cm, int col) { return cm.st ? cm.st->pos[col] : cm.pos0 + col; }
 __device__ __forceinline__ uint32_t col_slot(const ColMap& cm, int col) { return cm.st ? cm.st->slot[col] : cm.slot; }
+
+// QK-norm and rotary embedding of one head held as (a, b) = elements (lane, lane + 64) of a wave:
+// the one definition both the separate kernel and the fused attention kernel use.  Every
+// multiply-add is written out (fused or explicitly not), so the two kernels round alike whatever
+// the compiler would contract on its own.
+__device__ __forceinline__ void qk_norm_rope(float& a, float& b, float eps, float ga, float gb, float2 cs) {
+  const float ss = wave_sum(__builtin_fmaf(a, a, __fmul_rn(b, b)));
+  const float r = 1.0f / sqrtf(__builtin_fmaf(ss, 1.0f / 128.0f, eps));
+  a = __fmul_rn(__fmul_rn(a, r), ga);
+  b = __fmul_rn(__fmul_rn(b, r), gb);
+  const float ra = __builtin_fmaf(a, cs.x, -__fmul_rn(b, cs.y));
+  const float rb = __builtin_fmaf(b, cs.x, __fmul_rn(a, cs.y));
+  a = ra;
+  b = rb;
+}
 
 // ---------------------------------------------------------------------------
 // per-head QK RMSNorm + rotary embedding + KV append (head_dim 128)
@@ -546,16 +597,8 @@ __global__ __launch_bounds__(64) void k_qknorm_rope_append(
   float a = p[lane], b = p[lane + 64];
   const bool is_v = hh >= nq + nkv;
   if (!is_v) {
-    const float ss = wave_sum(a * a + b * b);
-    const float r = 1.0f / sqrtf(ss * (1.0f / 128.0f) + eps);
     const float* gg = hh < nq ? gq : gk;
-    a = a * r * gg[lane];
-    b = b * r * gg[lane + 64];
-    const float2 cs = rope[(size_t)pos * 64 + lane];
-    const float ra = a * cs.x - b * cs.y;
-    const float rb = b * cs.x + a * cs.y;
-    a = ra;
-    b = rb;
+    qk_norm_rope(a, b, eps, gg[lane], gg[lane + 64], rope[(size_t)pos * 64 + lane]);
   }
   if (hh < nq) {
     p[lane] = a;
@@ -802,11 +845,13 @@ __global__ __launch_bounds__(256) void k_attn_partial(
 // cache when the loads are issued).  One kernel less per layer.
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 struct AttnFuse {
-  const float* qkv;   // [columns][(nq + 2 nkv) * 128] raw q | k | v
+  const float* qkv;   // [slices][columns][(nq + 2 nkv) * 128] raw q | k | v, as k-slice partial sums
   const float* gq;    // QK-norm gains
   const float* gk;
   float eps;
   const float2* rope;
+  int slices;         // partial sums to add, in slice order (>= 1)
+  long slice_stride;  // floats between them
 };
 template <bool FUSED, class HF>
 __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restrict__ qsplit, AttnFuse fz, int nq,
@@ -862,17 +907,13 @@ __global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restr
       const float* p = role < G ? row + (size_t)(head0 + role) * 128
                                 : row + (size_t)(nq + (role == G ? 0 : nkv) + kvh) * 128;
       float a = p[lane], b = p[lane + 64];
+      for (int sl = 1; sl < fz.slices; ++sl) {
+        a += p[(size_t)sl * fz.slice_stride + lane];
+        b += p[(size_t)sl * fz.slice_stride + lane + 64];
+      }
       if (role <= G) {
-        const float ss = wave_sum(a * a + b * b);
-        const float r = 1.0f / sqrtf(ss * (1.0f / 128.0f) + fz.eps);
         const float* gg = role < G ? fz.gq : fz.gk;
-        a = a * r * gg[lane];
-        b = b * r * gg[lane + 64];
-        const float2 cs = fz.rope[(size_t)pos * 64 + lane];
-        const float ra = a * cs.x - b * cs.y;
-        const float rb = b * cs.x + a * cs.y;
-        a = ra;
-        b = rb;
+        qk_norm_rope(a, b, fz.eps, gg[lane], gg[lane + 64], fz.rope[(size_t)pos * 64 + lane]);
       }
       if (role < G) {
         uint32_t pa[3], pb[3];
@@ -1152,7 +1193,8 @@ hipError_t launch_attn_partial(hipStream_t s, int dt, const float* qkv, const vo
   if (fuse) {
     if (!attn_partial_can_fuse(dt, nq, nkv) || cm.row0 != 0 || !cm.st) return hipErrorInvalidValue;
     dim3 grid(grid_chunks, nkv, ncols);
-    const AttnFuse fz{qkv, fuse->gq, fuse->gk, fuse->eps, fuse->rope};
+    const AttnFuse fz{qkv, fuse->gq, fuse->gk, fuse->eps, fuse->rope, fuse->qkv_slices > 1 ? fuse->qkv_slices : 1,
+                      fuse->qkv_slice_stride};
     if (f16)
       k_attn_partial_mc<true, Fp16><<<grid, 256, 0, s>>>(nullptr, fz, nq, nkv, static_cast<uint16_t*>(kc),
                                                          static_cast<uint16_t*>(vc), max_seq, cm, partial, max_chunks);

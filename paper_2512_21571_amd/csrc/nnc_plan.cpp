@@ -11,11 +11,16 @@ Machine machine_mi355x(int cus) {
   m.cus = cus > 0 ? cus : 256;
   m.lds_bytes = 160 * 1024;
   m.vgprs_per_wave = 256;
-  // measured on these kernels, not datasheet values: the skinny GEMM streams weights at 5.8 TB/s
-  // once every CU has work; 768 workgroups re-reading one 393 KB operand cost what 46 TB/s would
+  // measured on these kernels, not datasheet values: inside a pass the GEMMs stream at 5.8 TB/s
+  // once every CU has work
   m.hbm_bytes_per_us = 5.8e6;
-  m.l2_operand_bytes_per_us = 46e6;
   m.launch_us = 5.0;
+  // the weight-streaming GEMM alone, launches back to back, 200 (rows, k, batch, row tiles,
+  // k slices) combinations of the five model shapes: least-squares / best-pick fit
+  m.stream_bytes_per_us = 6.4e6;
+  m.cu_bytes_per_us = 58e3;
+  m.skinny_launch_us = 2.5;
+  m.skinny_round_us = 0.6;
   // prompt GEMM, time per k step with two workgroups per CU, measured at the 4B / 8B shapes:
   // 0.48 us for 128 x 128 tiles (16 matrix-core instructions per wave), 0.726 for 192 x 128 (24),
   // 0.865 for 256 x 128 (32): least-squares line through the three; a lone workgroup on a CU
@@ -109,21 +114,29 @@ SkinnyGemmPlan plan_skinny_gemm(const Machine& mc, int n_tiles, int KT, int ncol
       const int slices = ceil_div(KT, kts);
       if (slices != ks) continue;
       const int wgs = n_tiles / rt * slices;
-      // every CU streams at its share of the rate once it has a workgroup; a launch whose busiest
-      // CU holds more workgroups than the average takes that much longer
-      const double per_cu = (double)wgs / mc.cus;
-      const double eff = wgs <= mc.cus ? per_cu : per_cu / std::ceil(per_cu);
-      const double t_mem = W / (mc.hbm_bytes_per_us * eff);
-      // every workgroup reads the operand of its k slice (its RT row tiles share it)
-      const double t_opnd = (double)wgs * kts * x_per_kt / mc.l2_operand_bytes_per_us;
+      // T_mem, level 1: what the busiest CU pulls through its vector memory path.  A workgroup
+      // reads its rt x kts weight tiles once, and the operand of its k slice once for all its
+      // row tiles; the operand comes from L2, but it crosses the same per-CU path as the
+      // weights, and with 48 operand columns a workgroup of one row tile moves three operand
+      // bytes per weight byte.  Measured: a CU sustains 58 GB/s on this access pattern whether
+      // one workgroup or three share it.
+      const int per_cu = ceil_div(wgs, mc.cus);
+      const double wg_bytes = (double)rt * kts * 1024.0 + kts * x_per_kt;
+      const double t_cu = per_cu * wg_bytes / mc.cu_bytes_per_us;
+      // T_mem, level 2: the weights from HBM; fewer workgroups than CUs cannot draw the full rate
+      const double cover = std::min(1.0, (double)wgs / mc.cus);
+      const double t_hbm = W / (mc.stream_bytes_per_us * std::sqrt(cover));
+      // epilogue: the four waves' partial tiles meet in LDS two row tiles at a time (one at a
+      // time for an odd count), one round after the other, for every workgroup a CU runs
+      const int rounds = rt % 2 == 0 ? rt / 2 : rt;
+      const double t_epi = mc.skinny_round_us * rounds * per_cu;
       // partial sums: written per slice and read once more by the consumer, a norm kernel of one
-      // workgroup per sequence that runs at an eighth of the streaming rate at best (measured: six
-      // slices instead of three cost the 4B down projection more than the halved operand reads save)
+      // workgroup per sequence that runs at an eighth of the streaming rate at best
       const double fold = slices > 1 ? slices * (double)n_tiles * 16.0 * nseq * 4.0 * 2.0 / (mc.hbm_bytes_per_us / 8.0) : 0.0;
-      const double total = t_mem + t_opnd + fold + mc.launch_us;
+      const double total = std::max(t_cu, t_hbm) + t_epi + fold + mc.skinny_launch_us;
       if (total < best.t_us * 0.999) {
         best.rt = rt; best.k_slices = slices; best.kts_per_split = kts; best.workgroups = wgs;
-        best.t_mem_us = t_mem; best.t_operand_us = t_opnd; best.t_us = total;
+        best.t_mem_us = t_hbm; best.t_operand_us = t_cu; best.t_us = total;
       }
     }
   }

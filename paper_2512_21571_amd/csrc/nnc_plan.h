@@ -26,8 +26,11 @@ struct Machine {
   int lds_bytes;          // LDS per CU
   int vgprs_per_wave;     // with two waves per SIMD
   double hbm_bytes_per_us;       // streaming rate these kernels reach
-  double l2_operand_bytes_per_us;  // rate at which many workgroups re-read one operand from L2
   double launch_us;       // start-to-end time of a kernel with nothing to do
+  // the weight-streaming GEMM of decode passes: streaming rate of the whole chip, bytes a CU moves
+  // through its vector memory path (weights + operand), launch-to-launch overhead, one round of
+  // the cross-wave reduction in the epilogue
+  double stream_bytes_per_us, cu_bytes_per_us, skinny_launch_us, skinny_round_us;
   // micro-kernel regression of the LDS-staged prompt GEMM, per k step of 32 with two workgroups per
   // CU: c0 + c1 * (matrix-core instructions per wave and k step) microseconds; one workgroup
   // alone on a CU takes `solo` times that
@@ -57,7 +60,9 @@ struct SkinnyGemmPlan {
   int k_slices;
   int kts_per_split;
   int workgroups;
-  double t_mem_us, t_operand_us, t_us;
+  double t_mem_us;      // weights from HBM
+  double t_operand_us;  // weights + operand through the busiest CU's vector memory path
+  double t_us;
 };
 // Weight-streaming GEMM of decode passes: n_tiles x KT tiles of 1 KiB, ncols operand columns
 // (sequences x pieces) of elem_bytes each, nseq sequences.  rt_choices: bit r set = the kernel is

@@ -50,8 +50,9 @@ def test_model_times_are_close_to_the_measured_ones():
         assert abs(p.t_us - measured[g]) / measured[g] < 0.12, (g, p.t_us)
     # batched decode GEMMs of the 8B shape, 16 sequences x 3 pieces
     H, Dq, Dkv, F = SHAPES["8b"]
-    for rows, k, epi, ks, us in ((Dq + 2 * Dkv, H, STORE, 1, 21.2), (2 * F, H, SWIGLU, 1, 45.9), (H, F, STORE, 8, 25.2),
-                                 (V, H, STORE, 1, 225.0)):
+    # launches back to back of the kernel alone, 16 sequences x 3 pieces, at the model's pick
+    for rows, k, epi, ks, us in ((Dq + 2 * Dkv, H, STORE, 1, 15.3), (Dq + 2 * Dkv, H, STORE, 4, 12.6), (H, Dq, STORE, 8, 9.9),
+                                 (2 * F, H, SWIGLU, 1, 36.4), (H, F, STORE, 8, 21.7), (V, H, STORE, 1, 226.6)):
         p = nnc.plan_skinny_gemm(rows, k, 16, 3, epi, ks)
         assert abs(p.t_us - us) / us < 0.20, (rows, p.t_us)
 
@@ -75,11 +76,18 @@ def test_short_prompts_are_memory_bound_and_may_split_k():
 
 def test_skinny_gemm_plans_at_the_batched_workloads():
     H, Dq, Dkv, F = SHAPES["8b"]
-    assert nnc.plan_skinny_gemm(Dq + 2 * Dkv, H, 16, 3, STORE).tile_code == 2           # 192 workgroups of two tiles
+    # what a CU pulls through its vector memory path (weights + the operand of every workgroup it
+    # runs) decides: one workgroup per CU with as many row tiles as that allows
+    qkv = nnc.plan_skinny_gemm(Dq + 2 * Dkv, H, 16, 3, STORE)
+    assert (qkv.tile_code, qkv.k_slices, qkv.workgroups) == (2, 1, 192)                 # no k split: 384 tiles as 192 x 2
+    qkv = nnc.plan_skinny_gemm(Dq + 2 * Dkv, H, 16, 3, STORE, 4)
+    assert (qkv.tile_code, qkv.k_slices, qkv.workgroups) == (3, 2, 256)                 # the consumer adds two k halves
     gu = nnc.plan_skinny_gemm(2 * F, H, 16, 3, SWIGLU)
-    assert gu.tile_code == 2 and gu.workgroups == 768                                    # three per CU, not 384 of four
+    assert (gu.tile_code, gu.workgroups) == (6, 256)                                     # three (gate, up) pairs per CU
+    o = nnc.plan_skinny_gemm(H, Dq, 16, 3, STORE, 8)
+    assert (o.tile_code, o.k_slices, o.workgroups) == (2, 2, 256)
     head = nnc.plan_skinny_gemm(V, H, 16, 3, STORE)
-    assert head.tile_code == 4                                                           # operand re-reads dominate the choice
+    assert head.tile_code == 4                                                           # 9496 tiles: 1, 2 or 4 divide
     down = nnc.plan_skinny_gemm(H, F, 16, 3, STORE, 8)
     assert down.workgroups % 256 == 0 and 1 < down.k_slices <= 8
     # batch 1: nothing to re-read, the choice is about filling the chip
@@ -87,6 +95,8 @@ def test_skinny_gemm_plans_at_the_batched_workloads():
     H4, Dq4, _, F4 = SHAPES["4b"]
     d4 = nnc.plan_skinny_gemm(H4, F4, 8, 3, STORE, 8)
     assert (d4.tile_code, d4.k_slices, d4.workgroups) == (2, 3, 240)                     # 80 tile pairs x 3 slices
+    g4 = nnc.plan_skinny_gemm(2 * F4, H4, 8, 3, SWIGLU)
+    assert (g4.tile_code, g4.workgroups) == (2, 608)                                     # 152 workgroups of 8 tiles would leave 104 CUs idle
 
 
 def test_planner_rejects_bad_shapes():
