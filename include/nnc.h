@@ -240,6 +240,13 @@ typedef enum {
   NNC_OPT_PLANNER = 10,     /* 1 (default): block tiles, row tiles per workgroup and k slices of the GEMM
                                launches come from the analytic model behind nnc_plan_*_query; 0: from the
                                hand-written rules that preceded it (kept for comparison) */
+  NNC_OPT_FUSE_NORM = 11,   /* 1: in per-stage decode passes the RMSNorm after an output / down
+                               projection runs in the tail of that GEMM launch (its last workgroups to
+                               finish wait for the others, one per sequence, and norm the rows): two
+                               kernels less per layer, same arithmetic, bit-identical results; the wait
+                               is bounded by NNC_OPT_SPIN_LIMIT.  0 (default): in a kernel of its own --
+                               the hand-over inside the launch (store acknowledgement, counter, reads
+                               past the caches) takes as long as the kernel boundary it replaces */
   NNC_OPT_SPIN_LIMIT = 5,   /* polls after which a wait inside the resident kernel gives up (sets
                                the failure flag and lets every workgroup exit); 0 (default):
                                2^20, about a second.  A tiny value makes the give-up path testable */

@@ -19,6 +19,7 @@ OPT_FUSE_QK = 7
 OPT_TAIL_OVERLAP = 8
 OPT_PREFILL_BLOCK = 9
 OPT_PLANNER = 10
+OPT_FUSE_NORM = 11
 
 # every symbol include/nnc.h declares
 EXPORTS = [

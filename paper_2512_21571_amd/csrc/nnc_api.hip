@@ -125,6 +125,8 @@ struct nnc_model {
   int opt_prefill_attn = -1;  // forced launch shape of the prompt attention, -1 = by size
   int opt_prefill_tile = -1;  // forced block tile of the large-block prompt GEMMs, -1 = by size
   bool opt_persistent = true;
+  bool opt_fuse_norm = false;  // decode passes: the norm after an O / down projection runs in that GEMM's tail (measured: no faster)
+  uint32_t* tail_counters = nullptr;  // one per GEMM launch with a norm tail in a pass (2 per layer), zeroed per pass
   bool opt_planner = true;    // tile sizes from the analytic model (nnc_plan.h); false: the earlier hand rules
   std::map<std::tuple<int, int, int>, hipGraphExec_t> graphs;
 
@@ -333,11 +335,27 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
   // k-slice partials of the previous projection still to be added to x
   int pending = 0;
   const long pstride = (long)n * H;
+  // Decode passes run the norm that follows an O / down projection in that GEMM's tail
+  // (NormTail): two kernels less per layer.  The head's norm stays a kernel when the head takes
+  // a sub-range of the columns.
+  const bool fuse_norm = p.decode && m->opt_fuse_norm && m->tail_counters && m->mk_error && H % 4 == 0 && H <= 8192;
+  bool normed = false;  // Xp already holds the normed input of the next GEMM
+  int tails = 0;
+  auto norm_tail = [&](GemmArgs& a, const float* gain) {
+    a.tail.counter = m->tail_counters + tails++;
+    a.tail.x = m->x; a.tail.ldx = H; a.tail.gain = gain; a.tail.H = H; a.tail.eps = c.rms_eps;
+    a.tail.Xp = m->Xp; a.tail.NC = nc; a.tail.nsplit = ns;
+    a.tail.spin_limit = m->mk_spin_limit ? m->mk_spin_limit : (1u << 20);
+    a.tail.error = m->mk_error;
+  };
+  if (fuse_norm) HIP_TRY(launch_zero_words(s, m->tail_counters, 2 * (int)c.n_layers));
   for (uint32_t li = 0; li < c.n_layers; ++li) {
     const LayerW& L = m->L[li];
     if (m->wait_layers) HIP_TRY(hipStreamWaitEvent(s, m->layer_done[li], 0));
-    RUN(FAM_NORM, n * H * 8.0, 0,
-        launch_rmsnorm_pack(s, dt, m->x, H, m->rpart, pending, pstride, L.g_in, H, c.rms_eps, n, m->Xp, nc, ns));
+    if (!normed)
+      RUN(FAM_NORM, n * H * 8.0, 0,
+          launch_rmsnorm_pack(s, dt, m->x, H, m->rpart, pending, pstride, L.g_in, H, c.rms_eps, n, m->Xp, nc, ns));
+    normed = false;
     const bool fuse = p.decode && m->opt_fuse_qk && attn_partial_can_fuse(dt, nq, nkv);
     int qkv_slices = 1;
     {
@@ -367,10 +385,12 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
       plan_skinny(m, a, EPI_STORE, MAX_KSPLIT);
       pending = (KTQ + a.kts_per_split - 1) / a.kts_per_split;
+      if (fuse_norm) norm_tail(a, L.g_post);
       RUN(FAM_GEMM_O, (double)H * Dq * w, 2.0 * H * Dq * n, launch_gemm(s, dt, EPI_STORE, a));
     }
-    RUN(FAM_NORM, n * H * 8.0, 0,
-        launch_rmsnorm_pack(s, dt, m->x, H, m->rpart, pending, pstride, L.g_post, H, c.rms_eps, n, m->Xp, nc, ns));
+    if (!fuse_norm)
+      RUN(FAM_NORM, n * H * 8.0, 0,
+          launch_rmsnorm_pack(s, dt, m->x, H, m->rpart, pending, pstride, L.g_post, H, c.rms_eps, n, m->Xp, nc, ns));
     {
       GemmArgs a{};
       a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = KTH; a.kts_per_split = KTH;
@@ -386,15 +406,25 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
       plan_skinny(m, a, EPI_STORE, MAX_KSPLIT);
       pending = (KTF + a.kts_per_split - 1) / a.kts_per_split;
+      // the norm this output feeds: the next layer's input norm, or the final norm when the head
+      // wants every column
+      const bool last = li + 1 == c.n_layers;
+      const bool head_all = c.has_embed_and_head && p.head_ncols == n && p.head_col0 == 0;
+      if (fuse_norm && (!last || head_all)) {
+        norm_tail(a, last ? m->g_final : m->L[li + 1].g_in);
+        normed = true;
+      }
       RUN(FAM_GEMM_D, (double)H * F * w, 2.0 * H * F * n, launch_gemm(s, dt, EPI_STORE, a));
+      if (normed) pending = 0;
     }
   }
 
   if (c.has_embed_and_head && p.head_ncols > 0) {
     const int hn = p.head_ncols, hc = hn * ns;
-    RUN(FAM_NORM, hn * H * 8.0, 0,
-        launch_rmsnorm_pack(s, dt, m->x + (size_t)p.head_col0 * H, H, m->rpart + (size_t)p.head_col0 * H, pending,
-                            pstride, m->g_final, H, c.rms_eps, hn, m->Xp, hc, ns));
+    if (!normed)
+      RUN(FAM_NORM, hn * H * 8.0, 0,
+          launch_rmsnorm_pack(s, dt, m->x + (size_t)p.head_col0 * H, H, m->rpart + (size_t)p.head_col0 * H, pending,
+                              pstride, m->g_final, H, c.rms_eps, hn, m->Xp, hc, ns));
     GemmArgs a{};
     a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = KTH; a.kts_per_split = KTH;
     a.Xp = m->Xp; a.NC = hc; a.ncols = hc; a.nsplit = ns; a.nseq = hn;
@@ -512,6 +542,17 @@ bool use_persistent(const nnc_model* m, uint32_t batch) {
 
 // n_steps greedy decode steps of one sequence in one resident kernel, starting from
 // `token` at the slot's current length.  Tokens land in token_log [n_steps].
+// The give-up flag of the kernels that wait for other workgroups (the resident decode kernel, the
+// norm tails of decode GEMMs) travels to pinned host memory behind the launches; the next call on
+// this model that finds the copy complete looks at it (resident_failed).
+nnc_status fetch_wait_flag(nnc_model* m) {
+  if (!m->mk_error) return NNC_OK;
+  HIP_TRY(hipMemcpyAsync(m->mk_error_host, m->mk_error, sizeof(unsigned), hipMemcpyDeviceToHost, m->stream));
+  HIP_TRY(hipEventRecord(m->mk_error_event, m->stream));
+  m->mk_error_pending = true;
+  return NNC_OK;
+}
+
 nnc_status persistent_steps(nnc_model* m, uint32_t slot, int32_t token, uint32_t n_steps, float* logits_out) {
   const nnc_config& c = m->c;
   MkPlan p{};
@@ -553,10 +594,7 @@ nnc_status persistent_steps(nnc_model* m, uint32_t slot, int32_t token, uint32_t
   m->mk_tag += (unsigned)tags;
   // the kernel's give-up flag travels to pinned host memory behind the launch; the next call
   // on this model that finds the copy complete looks at it (resident_failed)
-  HIP_TRY(hipMemcpyAsync(m->mk_error_host, m->mk_error, sizeof(unsigned), hipMemcpyDeviceToHost, m->stream));
-  HIP_TRY(hipEventRecord(m->mk_error_event, m->stream));
-  m->mk_error_pending = true;
-  return NNC_OK;
+  return fetch_wait_flag(m);
 }
 
 // True once a resident launch has given up on a wait (a lost exchange word): every workgroup
@@ -687,6 +725,11 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     const size_t kv_bytes = (size_t)c.max_batch * c.n_kv_heads * c.max_seq * d * w;
     ALLOC(L.kc, void*, kv_bytes);
     ALLOC(L.vc, void*, kv_bytes);
+    // The attention kernels load rows past the last cached position of a chunk (clamped to a valid
+    // row) and give them weight zero; a slot's first rows are read that way before they are
+    // written, so they must hold finite values from the start.
+    TRY_OR_BAIL(hipMemsetAsync(L.kc, 0, kv_bytes, s));
+    TRY_OR_BAIL(hipMemsetAsync(L.vc, 0, kv_bytes, s));
   }
   if (c.has_embed_and_head) {
     TRY_OR_BAIL(upload_gain(m->g_final, H));
@@ -750,6 +793,22 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     TRY_OR_BAIL(hipMemsetAsync(m->pb_vt, 0, (size_t)c.n_kv_heads * 128 * m->pb_vt_stride * 2, s));
   }
 
+  // give-up flag of the kernels whose workgroups wait for each other, and the arrival counters of
+  // the norm tails (two GEMM launches per layer)
+  {
+    void* err = dev_alloc(m, 256);
+    if (!err) TRY_OR_BAIL(hipErrorOutOfMemory);
+    TRY_OR_BAIL(hipMemsetAsync(err, 0, 256, s));
+    m->mk_error = static_cast<unsigned*>(err);
+    TRY_OR_BAIL(hipHostMalloc(reinterpret_cast<void**>(&m->mk_error_host), sizeof(unsigned), hipHostMallocDefault));
+    *m->mk_error_host = 0;
+    TRY_OR_BAIL(hipEventCreateWithFlags(&m->mk_error_event, hipEventDisableTiming));
+    void* cnt = dev_alloc(m, (2 * (size_t)c.n_layers + 2) * 4);
+    if (!cnt) TRY_OR_BAIL(hipErrorOutOfMemory);
+    TRY_OR_BAIL(hipMemsetAsync(cnt, 0, (2 * (size_t)c.n_layers + 2) * 4, s));
+    m->tail_counters = static_cast<uint32_t*>(cnt);
+  }
+
   // resident decode kernel: per-layer pointer table, exchange buffers
   if (!m->f32 && c.has_embed_and_head && c.n_layers > 0 && H <= 4096 && (c.n_q_heads / c.n_kv_heads) % 2 == 0 &&
       c.n_q_heads / c.n_kv_heads <= 16) {
@@ -795,12 +854,6 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
         if (!ptr) return hipErrorOutOfMemory;
         return hipMemsetAsync(ptr, 0, bytes, s);
       };
-      void* err = nullptr;
-      TRY_OR_BAIL(zeroed(err, 256));
-      m->mk_error = static_cast<unsigned*>(err);
-      TRY_OR_BAIL(hipHostMalloc(reinterpret_cast<void**>(&m->mk_error_host), sizeof(unsigned), hipHostMallocDefault));
-      *m->mk_error_host = 0;
-      TRY_OR_BAIL(hipEventCreateWithFlags(&m->mk_error_event, hipEventDisableTiming));
       TRY_OR_BAIL(zeroed(m->mk_xq, (Dq + 2 * Dkv) * 8));
       TRY_OR_BAIL(zeroed(m->mk_xatt, (size_t)c.n_q_heads * m->max_chunks * 132 * 8));
       TRY_OR_BAIL(zeroed(m->mk_xo, Dq * 8));
@@ -888,6 +941,11 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
     case NNC_OPT_FUSE_QK:
       m->opt_fuse_qk = value != 0;
       // captured decode graphs contain one or the other set of kernels
+      for (auto& kv : m->graphs) (void)hipGraphExecDestroy(kv.second);
+      m->graphs.clear();
+      return NNC_OK;
+    case NNC_OPT_FUSE_NORM:
+      m->opt_fuse_norm = value != 0;
       for (auto& kv : m->graphs) (void)hipGraphExecDestroy(kv.second);
       m->graphs.clear();
       return NNC_OK;
@@ -1183,7 +1241,7 @@ nnc_status nnc_prefill(nnc_model* m, uint32_t slot, const int32_t* tokens, uint3
   if (!m || !tokens) return fail(NNC_E_ARG, "NULL argument");
   if (!m->c.has_embed_and_head) return fail(NNC_E_STATE, "model has no embedding; use nnc_prefill_hidden");
   if (resident_failed(m, false))
-    return fail(NNC_E_DEVICE, "an earlier resident decode launch gave up waiting for an exchange word; recreate the model");
+    return fail(NNC_E_DEVICE, "an earlier decode launch gave up waiting for its other workgroups; recreate the model");
   return prefill_common(m, slot, tokens, nullptr, n, logits_out, next_out, nullptr);
 }
 
@@ -1198,7 +1256,7 @@ nnc_status nnc_decode_step(nnc_model* m, const uint32_t* slots, const int32_t* t
   if (!m || !tokens) return fail(NNC_E_ARG, "NULL argument");
   if (!m->c.has_embed_and_head) return fail(NNC_E_STATE, "model has no embedding; use nnc_decode_step_hidden");
   if (resident_failed(m, false))
-    return fail(NNC_E_DEVICE, "an earlier resident decode launch gave up waiting for an exchange word; recreate the model");
+    return fail(NNC_E_DEVICE, "an earlier decode launch gave up waiting for its other workgroups; recreate the model");
   if (nnc_status st = check_slots(m, slots, batch, 1)) return st;
   for (uint32_t i = 0; i < batch; ++i)
     if (tokens[i] < 0 || (uint32_t)tokens[i] >= m->c.vocab) return fail(NNC_E_ARG, "token %d out of range", tokens[i]);
@@ -1229,7 +1287,7 @@ nnc_status nnc_decode_step(nnc_model* m, const uint32_t* slots, const int32_t* t
   }
   if (next_out) HIP_TRY(hipMemcpyAsync(next_out, m->next, batch * 4, hipMemcpyDeviceToDevice, m->stream));
   for (uint32_t i = 0; i < batch; ++i) m->len[slots[i]] += 1;
-  return NNC_OK;
+  return fetch_wait_flag(m);
 }
 
 // ---- decode step for callers that cannot allocate -------------------------------
@@ -1267,7 +1325,7 @@ nnc_status nnc_decode_step_static(nnc_model* m, const uint32_t* slots, const int
   if (!m->c.has_embed_and_head) return fail(NNC_E_STATE, "model has no embedding");
   if (m->profiling) return fail(NNC_E_STATE, "per-kernel profiling creates events; not available here");
   if (resident_failed(m, false))
-    return fail(NNC_E_DEVICE, "an earlier resident decode launch gave up waiting for an exchange word; recreate the model");
+    return fail(NNC_E_DEVICE, "an earlier decode launch gave up waiting for its other workgroups; recreate the model");
   if (batch > NNC_STATIC_MAX_BATCH)
     return fail(NNC_E_ARG, "batch %u exceeds the static workspace limit of %d sequences", batch, NNC_STATIC_MAX_BATCH);
   if (nnc_status st = check_slots(m, slots, batch, 1)) return st;
@@ -1335,7 +1393,7 @@ nnc_status nnc_decode_step_static(nnc_model* m, const uint32_t* slots, const int
   if (nnc_status st = run_pass(m, p)) return st;
   if (next_out) HIP_TRY(hipMemcpyAsync(next_out, m->next, batch * 4, hipMemcpyDeviceToDevice, m->stream));
   for (uint32_t i = 0; i < batch; ++i) m->len[slots[i]] += 1;
-  return NNC_OK;
+  return fetch_wait_flag(m);
 }
 
 nnc_status nnc_decode_greedy(nnc_model* m, const uint32_t* slots, const int32_t* first_tokens, uint32_t batch,
@@ -1343,7 +1401,7 @@ nnc_status nnc_decode_greedy(nnc_model* m, const uint32_t* slots, const int32_t*
   if (!m || !first_tokens || !tokens_out) return fail(NNC_E_ARG, "NULL argument");
   if (!m->c.has_embed_and_head) return fail(NNC_E_STATE, "model has no embedding");
   if (resident_failed(m, false))
-    return fail(NNC_E_DEVICE, "an earlier resident decode launch gave up waiting for an exchange word; recreate the model");
+    return fail(NNC_E_DEVICE, "an earlier decode launch gave up waiting for its other workgroups; recreate the model");
   if (n_steps == 0) return fail(NNC_E_ARG, "n_steps is 0");
   if (n_steps > m->token_log_steps) return fail(NNC_E_ARG, "n_steps %u exceeds %u", n_steps, m->token_log_steps);
   if (nnc_status st = check_slots(m, slots, batch, n_steps)) return st;
@@ -1381,7 +1439,7 @@ nnc_status nnc_decode_greedy(nnc_model* m, const uint32_t* slots, const int32_t*
   }
   HIP_TRY(hipMemcpyAsync(tokens_out, m->token_log, (size_t)n_steps * batch * 4, hipMemcpyDeviceToDevice, m->stream));
   for (uint32_t i = 0; i < batch; ++i) m->len[slots[i]] += n_steps;
-  return NNC_OK;
+  return fetch_wait_flag(m);
 }
 
 nnc_status nnc_decode_step_hidden(nnc_model* m, const uint32_t* slots, const float* x, uint32_t batch, float* y) {
@@ -1402,7 +1460,7 @@ nnc_status nnc_decode_step_hidden(nnc_model* m, const uint32_t* slots, const flo
   if (nnc_status st = run_pass(m, p)) return st;
   HIP_TRY(launch_copy_rows(m->stream, m->x, y, (size_t)batch * m->H()));
   for (uint32_t i = 0; i < batch; ++i) m->len[slots[i]] += 1;
-  return NNC_OK;
+  return fetch_wait_flag(m);
 }
 
 nnc_status nnc_kv_read(nnc_model* m, uint32_t layer, uint32_t slot, uint32_t which, uint32_t pos0, uint32_t n,

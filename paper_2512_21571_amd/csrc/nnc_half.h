@@ -70,6 +70,9 @@ struct Fp16 {
 // remainder, rounded remainder of that).
 template <class HF>
 __device__ __forceinline__ void split_pieces(float v, int nsplit, uint32_t* piece) {
+  // the remainders are those of v as rounded to fp32: without this the compiler may fuse the
+  // subtraction with the product that made v, in one caller and not in another
+#pragma clang fp contract(off)
   float r = v;
 #pragma unroll
   for (int s = 0; s < 3; ++s) {

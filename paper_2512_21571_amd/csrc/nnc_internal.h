@@ -53,6 +53,25 @@ struct ColMap {
 // remainder, ...); the pieces' products are summed in the epilogue, which keeps
 // activations at fp32 accuracy while the weights stream through the bf16 matrix
 // cores untouched.
+// The RMSNorm that follows an output / down projection, run in the tail of that GEMM launch
+// instead of a kernel of its own: every workgroup stores its partial tile through to memory and
+// counts itself done; the last workgroups to finish (one per sequence) wait until all have, then
+// each adds the k-slice partials of its sequence to the residual stream (fixed slice order),
+// norms the row and writes the packed operand of the next GEMM: what k_rmsnorm_pack computes,
+// with the same arithmetic.  counter == NULL: no tail.
+struct NormTail {
+  uint32_t* counter;   // zero before the launch
+  float* x;            // residual stream [sequence][ldx]
+  long ldx;
+  const float* gain;
+  int H;
+  float eps;
+  void* Xp;            // packed operand out
+  int NC, nsplit;
+  unsigned spin_limit; // polls of the counter before a waiting workgroup gives up
+  unsigned* error;     // set to 1 when one does (the pass's results are then invalid)
+};
+
 struct GemmArgs {
   const void* Wp;
   int n_tiles;        // output rows / 16
@@ -80,6 +99,7 @@ struct GemmArgs {
   // 16-row tiles per workgroup (1, 2, 3, 4 or 6; SwiGLU: 2, 4, 6 or 8; fp32 models: 1, 2 or 4);
   // 0: the launcher's own rule
   int rt;
+  NormTail tail;  // EPI_STORE with out = [k slice][sequence][ldo = tail.H] only
 };
 
 struct KernelCtx;  // profiling hook, defined in nnc_api.hip
@@ -94,6 +114,8 @@ hipError_t launch_embed(hipStream_t s, int dt, const void* Ep, int H, const ColS
 hipError_t launch_rmsnorm_pack(hipStream_t s, int dt, float* x, long ldx, const float* part, int nparts,
                                long part_stride, const float* gain, int H, float eps, int ncols, void* Xp,
                                int NC, int nsplit);
+// n 32-bit words = 0 (a fill kernel: safe under graph capture)
+hipError_t launch_zero_words(hipStream_t s, uint32_t* p, int n);
 hipError_t launch_fold_residual(hipStream_t s, float* x, const float* part, int nparts, long part_stride,
                                 size_t n);
 hipError_t launch_gemm(hipStream_t s, int dt, int epi, const GemmArgs& a);

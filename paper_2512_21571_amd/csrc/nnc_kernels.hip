@@ -216,6 +216,46 @@ __device__ __forceinline__ void store_packed(void* Xp, int NC, int nsplit, int s
   }
 }
 
+// The three places of the row norm where a compiler may or may not contract a multiply and an
+// add, written out, so that the norm kernel and the norm in a GEMM's tail round alike.
+__device__ __forceinline__ float sumsq4(float ss, float4 v) {
+  ss = __builtin_fmaf(v.x, v.x, ss);
+  ss = __builtin_fmaf(v.y, v.y, ss);
+  ss = __builtin_fmaf(v.z, v.z, ss);
+  return __builtin_fmaf(v.w, v.w, ss);
+}
+// (#pragma clang fp contract(off): the products and sums of the function carry no permission to
+// be fused, here or after inlining; the compiler's own choice depends on the surrounding code.)
+__device__ __forceinline__ float rms_rinv(float ss, int H, float eps) {
+#pragma clang fp contract(off)
+  return 1.0f / sqrtf(ss / (float)H + eps);
+}
+__device__ __forceinline__ float norm_elem(float v, float r, float g) {
+#pragma clang fp contract(off)
+  const float vr = v * r;
+  return vr * g;
+}
+
+// norm_elem of four consecutive elements i .. i+3 of a row -> the packed operand layout
+template <bool F32, class HF>
+__device__ __forceinline__ void store_normed4(void* Xp, int NC, int nsplit, int seq, int i, float4 v, float r, float4 g) {
+  const float h[4] = {norm_elem(v.x, r, g.x), norm_elem(v.y, r, g.y), norm_elem(v.z, r, g.z), norm_elem(v.w, r, g.w)};
+  if constexpr (F32) {
+    *reinterpret_cast<float4*>(static_cast<float*>(Xp) + ((size_t)(i >> 2) * NC + seq) * 4) =
+        make_float4(h[0], h[1], h[2], h[3]);
+  } else {
+    // elements i .. i+3 of one 8-element group: 8 bytes per piece
+    uint32_t pc[4][3];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) split_pieces<HF>(h[e], nsplit, pc[e]);
+    uint16_t* dst = static_cast<uint16_t*>(Xp) + ((size_t)(i >> 3) * NC + seq * nsplit) * 8 + (i & 7);
+#pragma unroll
+    for (int sp = 0; sp < 3; ++sp)
+      if (sp < nsplit)
+        *reinterpret_cast<uint2*>(dst + sp * 8) = make_uint2(pc[0][sp] | (pc[1][sp] << 16), pc[2][sp] | (pc[3][sp] << 16));
+  }
+}
+
 // Before the norm, the pending output of the previous projection is added to the
 // residual stream: x += part[0] + part[1] + ... (k slices of that GEMM, fixed order),
 // and the updated x is written back.  part_seq0 is the column of `part` that
@@ -258,29 +298,15 @@ __global__ __launch_bounds__(256) void k_rmsnorm_pack(float* __restrict__ x, lon
       v[q] = make_float4(v[q].x + add.x, v[q].y + add.y, v[q].z + add.z, v[q].w + add.w);
       *reinterpret_cast<float4*>(xr + i) = v[q];
     }
-    ss += v[q].x * v[q].x + v[q].y * v[q].y + v[q].z * v[q].z + v[q].w * v[q].w;
+    ss = sumsq4(ss, v[q]);
   }
   ss = block_sum_256(ss, sm);
-  const float r = 1.0f / sqrtf(ss / (float)H + eps);
+  const float r = rms_rinv(ss, H, eps);
 #pragma unroll
   for (int q = 0; q < NV; ++q) {
     const int i = (threadIdx.x + 256 * q) * 4;
     if (i >= H) continue;
-    const float h[4] = {v[q].x * r * g[q].x, v[q].y * r * g[q].y, v[q].z * r * g[q].z, v[q].w * r * g[q].w};
-    if constexpr (F32) {
-      *reinterpret_cast<float4*>(static_cast<float*>(Xp) + ((size_t)(i >> 2) * NC + seq) * 4) =
-          make_float4(h[0], h[1], h[2], h[3]);
-    } else {
-      // elements i .. i+3 of one 8-element group: 8 bytes per piece
-      uint32_t pc[4][3];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) split_pieces<HF>(h[e], nsplit, pc[e]);
-      uint16_t* dst = static_cast<uint16_t*>(Xp) + ((size_t)(i >> 3) * NC + seq * nsplit) * 8 + (i & 7);
-#pragma unroll
-      for (int sp = 0; sp < 3; ++sp)
-        if (sp < nsplit)
-          *reinterpret_cast<uint2*>(dst + sp * 8) = make_uint2(pc[0][sp] | (pc[1][sp] << 16), pc[2][sp] | (pc[3][sp] << 16));
-    }
+    store_normed4<F32, HF>(Xp, NC, nsplit, seq, i, v[q], r, g[q]);
   }
 }
 
@@ -295,6 +321,15 @@ hipError_t launch_rmsnorm_pack(hipStream_t s, int dt, float* x, long ldx, const 
   else if (H <= 4096) RN_LAUNCH(4);
   else RN_LAUNCH(8);
 #undef RN_LAUNCH
+  return hipGetLastError();
+}
+
+__global__ void k_zero_words(uint32_t* p, int n) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0u;
+}
+hipError_t launch_zero_words(hipStream_t s, uint32_t* p, int n) {
+  if (n <= 0) return hipSuccess;
+  k_zero_words<<<1, 256, 0, s>>>(p, n);
   return hipGetLastError();
 }
 
@@ -313,6 +348,82 @@ hipError_t launch_fold_residual(hipStream_t s, float* x, const float* part, int 
   const unsigned grid = (unsigned)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
   k_fold_residual<<<grid ? grid : 1, 256, 0, s>>>(x, part, nparts, part_stride, n);
   return hipGetLastError();
+}
+
+// A float written by another workgroup of the running launch with a write-through store: read
+// past this CU's L1 and this XCD's L2, which may hold the line from before that store.
+__device__ __forceinline__ float load_coherent(const float* p) {
+  return __uint_as_float(__hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ void store_through(float* p, float v) {
+  __hip_atomic_store(reinterpret_cast<uint32_t*>(p), __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Tail of a GEMM launch whose output feeds an RMSNorm (NormTail).  Called by every thread of
+// every workgroup after its last partial-tile store.  sm: 8 words of LDS nobody else uses now.
+template <bool F32, class HF>
+__device__ __forceinline__ void gemm_norm_tail(const NormTail& t, const float* part, long part_stride, int nparts,
+                                               int nseq, float* sm) {
+  // this thread's stores have reached memory; after the barrier, the whole workgroup's have
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+  __syncthreads();
+  const unsigned total = gridDim.x * gridDim.y;
+  const unsigned takers = total < (unsigned)nseq ? total : (unsigned)nseq;  // the last `takers` workgroups run the norm
+  int* si = reinterpret_cast<int*>(sm);
+  if (threadIdx.x == 0) {
+    const unsigned done_before = __hip_atomic_fetch_add(t.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int role = -1;
+    if (done_before + takers >= total) {
+      role = (int)(done_before - (total - takers));
+      // at most takers - 1 workgroups are still running: the others among the takers
+      unsigned polls = 0;
+      while (__hip_atomic_load(t.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < total) {
+        if (++polls > t.spin_limit) {
+          __hip_atomic_store(t.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          role = -1;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(4);
+      }
+    }
+    si[4] = role;
+  }
+  __syncthreads();
+  const int role = si[4];
+  if (role < 0) return;
+  const int H = t.H;
+  for (int seq = role; seq < nseq; seq += (int)takers) {
+    float* xr = t.x + (size_t)seq * t.ldx;
+    float4 v[8], g[8];
+    float ss = 0.f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int i = (threadIdx.x + 256 * q) * 4;
+      v[q] = g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i < H) {
+        v[q] = *reinterpret_cast<const float4*>(xr + i);
+        g[q] = *reinterpret_cast<const float4*>(t.gain + i);
+        const float* pp = part + (size_t)seq * H + i;
+        float4 add = make_float4(load_coherent(pp), load_coherent(pp + 1), load_coherent(pp + 2), load_coherent(pp + 3));
+        for (int p = 1; p < nparts; ++p) {  // slices are added in a fixed order
+          const float* q4 = pp + (size_t)p * part_stride;
+          add = make_float4(add.x + load_coherent(q4), add.y + load_coherent(q4 + 1), add.z + load_coherent(q4 + 2),
+                            add.w + load_coherent(q4 + 3));
+        }
+        v[q] = make_float4(v[q].x + add.x, v[q].y + add.y, v[q].z + add.z, v[q].w + add.w);
+        *reinterpret_cast<float4*>(xr + i) = v[q];
+      }
+      ss = sumsq4(ss, v[q]);
+    }
+    ss = block_sum_256(ss, sm);
+    const float r = rms_rinv(ss, H, t.eps);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int i = (threadIdx.x + 256 * q) * 4;
+      if (i < H) store_normed4<F32, HF>(t.Xp, t.NC, t.nsplit, seq, i, v[q], r, g[q]);
+    }
+    __syncthreads();  // sm is reused by the next sequence's block sum
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -356,9 +467,19 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   const u32x4* __restrict__ Wv = reinterpret_cast<const u32x4*>(W);
   const u32x4* __restrict__ Xv = reinterpret_cast<const u32x4*>(X);
-  int xoff[NCB];  // operand fragment of this lane within a k tile's 4 x NC groups of 16 bytes
+  // Loads go through buffer descriptors: a scalar descriptor, a per-lane byte offset that never
+  // changes (lane * 16 for the weights, the lane's operand fragment within a k tile for the
+  // operand) and a scalar offset per k tile.  No vector register is written to form an address
+  // inside the loop.  (With 64-bit vector addresses the compiler recycled registers of earlier
+  // load results for them and waited for every outstanding load before it issued the next set.)
+  const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<u32x4*>(Wv + tile0 * KT * 64), 0, RT * KT * 1024, 0x00020000);
+  const __amdgpu_buffer_rsrc_t xres =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4*>(Xv), 0, KT * 64 * a.NC, 0x00020000);
+  const uint32_t wvoff = (uint32_t)lane * 16u;
+  uint32_t xvoff[NCB];  // operand fragment of this lane within a k tile's 4 x NC groups of 16 bytes
 #pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) xoff[cb] = g * a.NC + min(cb * 16 + c16, a.NC - 1);
+  for (int cb = 0; cb < NCB; ++cb) xvoff[cb] = (uint32_t)(g * a.NC + min(cb * 16 + c16, a.NC - 1)) * 16u;
   // this wave's k tiles: first, first + 4, ... (n_mine of them)
   const int first = kt_begin + wave;
   const int n_mine = first < kt_end ? (kt_end - first + 3) >> 2 : 0;
@@ -366,10 +487,10 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
   u32x4 avA[U][RT], bvA[U][NCB], avB[U][RT], bvB[U][NCB];
   auto load_tile = [&](int kt, u32x4(&av)[RT], u32x4(&bv)[NCB]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) av[rt] = __builtin_nontemporal_load(&(Wv + ((tile0 + rt) * KT + kt) * 64)[lane]);
-    const u32x4* xk = Xv + (size_t)kt * 4 * a.NC;
+    for (int rt = 0; rt < RT; ++rt)  // aux 2: non-temporal, each weight byte is used once per pass
+      av[rt] = __builtin_amdgcn_raw_buffer_load_b128(wres, wvoff, (rt * KT + kt) * 1024, 2);
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) bv[cb] = xk[xoff[cb]];
+    for (int cb = 0; cb < NCB; ++cb) bv[cb] = __builtin_amdgcn_raw_buffer_load_b128(xres, xvoff[cb], kt * 64 * a.NC, 0);
   };
   auto load_group = [&](int t0, u32x4(&av)[U][RT], u32x4(&bv)[U][NCB]) __attribute__((always_inline)) {
 #pragma unroll
@@ -465,9 +586,16 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
         const int rem = o - r * 16 * nseq;
         const int seq = rem >> 4, row = rem & 15;
         // each k slice stores its own partial sums: slice s goes to out + s * split_stride
-        out[(size_t)blockIdx.y * a.split_stride + (size_t)seq * a.ldo + (tile0 + ch * RC + r) * 16 + row] =
-            total(r, row, seq);
+        float* dst = out + (size_t)blockIdx.y * a.split_stride + (size_t)seq * a.ldo + (tile0 + ch * RC + r) * 16 + row;
+        if (a.tail.counter) store_through(dst, total(r, row, seq));
+        else *dst = total(r, row, seq);
       }
+    }
+  }
+  if constexpr (EPI == EPI_STORE) {
+    if (a.tail.counter) {
+      __syncthreads();  // every wave is done with the reduction buffer
+      gemm_norm_tail<F32, HF>(a.tail, out, a.split_stride, (int)gridDim.y, nseq, &red[0][0][0][0]);
     }
   }
 }
@@ -533,6 +661,9 @@ hipError_t launch_gemm(hipStream_t s, int dt, int epi, const GemmArgs& a) {
   const bool wide = a.n_tiles >= 1024 && (a.n_tiles % 2 == 0);
   if (epi != EPI_STORE && epi != EPI_SWIGLU) return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU && (a.n_tiles % 2 || a.kts_per_split < a.KT)) return hipErrorInvalidValue;
+  if (a.tail.counter && (epi != EPI_STORE || a.step_ptr || a.ldo != a.tail.H || a.tail.H != a.n_tiles * 16 ||
+                         a.tail.H % 4 || a.tail.H > 8192 || !a.tail.error || (a.KT + a.kts_per_split - 1) / a.kts_per_split > 8))
+    return hipErrorInvalidValue;
   if (a.rt > 0) {  // row tiles per workgroup chosen by the caller (the analytic planner)
     if (a.n_tiles % a.rt || (epi == EPI_SWIGLU && a.rt % 2)) return hipErrorInvalidValue;
     if (epi == EPI_SWIGLU) {
@@ -563,15 +694,19 @@ __device__ __forceinline__ uint32_t col_slot(const ColMap& cm, int col) { return
 
 // QK-norm and rotary embedding of one head held as (a, b) = elements (lane, lane + 64) of a wave:
 // the one definition both the separate kernel and the fused attention kernel use.  Every
-// multiply-add is written out (fused or explicitly not), so the two kernels round alike whatever
-// the compiler would contract on its own.
+// multiply-add is written out (fused by builtin, or left unfused under contract(off)), so the two
+// kernels round alike whatever the compiler would contract on its own.
 __device__ __forceinline__ void qk_norm_rope(float& a, float& b, float eps, float ga, float gb, float2 cs) {
-  const float ss = wave_sum(__builtin_fmaf(a, a, __fmul_rn(b, b)));
+#pragma clang fp contract(off)
+  const float bb = b * b;
+  const float ss = wave_sum(__builtin_fmaf(a, a, bb));
   const float r = 1.0f / sqrtf(__builtin_fmaf(ss, 1.0f / 128.0f, eps));
-  a = __fmul_rn(__fmul_rn(a, r), ga);
-  b = __fmul_rn(__fmul_rn(b, r), gb);
-  const float ra = __builtin_fmaf(a, cs.x, -__fmul_rn(b, cs.y));
-  const float rb = __builtin_fmaf(b, cs.x, __fmul_rn(a, cs.y));
+  const float ar = a * r, br = b * r;
+  a = ar * ga;
+  b = br * gb;
+  const float bsn = b * cs.y, asn = a * cs.y;
+  const float ra = __builtin_fmaf(a, cs.x, -bsn);
+  const float rb = __builtin_fmaf(b, cs.x, asn);
   a = ra;
   b = rb;
 }

@@ -596,6 +596,55 @@ def test_reset_replay_and_error_paths(nnc):
     assert e.value.status == nnc.E_KV_FULL
 
 
+@pytest.mark.parametrize("shape", [SMALL_BF16, SMALL_G4, SMALL_F32], ids=lambda s: s.name)
+@pytest.mark.parametrize("batch", [1, 3, 16])
+def test_norm_in_the_gemm_tail_equals_the_norm_kernel(nnc, shape, batch):
+    """Per-stage decode passes with the RMSNorm after the output / down projections run in the
+    tail of those GEMM launches, and in a kernel of its own: the same arithmetic in the same
+    order, so the same bits (logits, tokens, cache rows), eager and captured, over ragged contexts."""
+    print(f"case: norm in the GEMM tail vs norm kernel, {shape.name}, B={batch}", flush=True)
+    runs = []
+    for fused in (0, 1):
+        g, _ = _pair(nnc, shape, batch, 200)
+        g.set_option(nnc.OPT_PERSISTENT, 0)
+        g.set_option(nnc.OPT_FUSE_NORM, fused)
+        firsts = []
+        for s_ in range(batch):
+            _, nx = g.prefill(s_, synth.tokens(40 + 7 * s_, shape.vocab, stream=70 + s_))
+            firsts.append(int(nx.item()))
+        slots = list(range(batch))
+        toks, logits = g.decode_greedy(slots, firsts, 6, want_logits=True)   # eager passes (logits wanted)
+        toks2, _ = g.decode_greedy(slots, toks[-1].cpu().numpy().tolist(), 6)  # captured graph
+        lg, ng = g.decode_step(slots, toks2[-1].cpu().numpy().tolist())
+        g.synchronize()
+        k = g.kv_read(shape.n_layers - 1, 0, 0, 0, 40 + 13)
+        runs.append((toks.cpu().numpy().copy(), logits.cpu().numpy().copy(), toks2.cpu().numpy().copy(),
+                     lg.cpu().numpy().copy(), ng.cpu().numpy().copy(), k.cpu().numpy().copy()))
+    for a, b in zip(runs[0], runs[1]):
+        assert np.array_equal(a, b)
+
+
+def test_norm_tail_gives_up_cleanly_and_reports_it(nnc):
+    """Failure path of the norm tail, forced from the host: with a spin limit of one poll a
+    workgroup that finds the others not finished yet gives up instead of waiting; the launch ends
+    normally, and the library reports the failure on synchronize and refuses further decode calls."""
+    print("case: norm tail give-up path (spin limit 1)", flush=True)
+    shape = SMALL_BF16
+    blob = synth.make_blob(shape, weight_std=0.05)
+    g = nnc.Model(shape, blob, 16, 64)
+    firsts = []
+    for s_ in range(16):
+        _, nx = g.prefill(s_, synth.tokens(9, shape.vocab, stream=s_))
+        firsts.append(int(nx.item()))
+    g.set_option(nnc.OPT_SPIN_LIMIT, 1)
+    g.decode_greedy(list(range(16)), firsts, 8)
+    with pytest.raises(nnc.NncError) as ei:
+        g.synchronize()
+    assert ei.value.status == nnc.E_DEVICE
+    with pytest.raises(nnc.NncError):
+        g.decode_step(list(range(16)), firsts)
+
+
 def test_resident_kernel_gives_up_cleanly_and_reports_it(nnc):
     """Failure path of the resident decode kernel, forced from the host: with a spin limit of
     one poll every wait that is not satisfied at once gives up, all workgroups leave through
