@@ -989,13 +989,14 @@ struct AttnFuse {
   long slice_stride;  // floats between them
 };
 template <bool FUSED, class HF>
-__global__ __launch_bounds__(256) void k_attn_partial_mc(const uint16_t* __restrict__ qsplit, AttnFuse fz, int nq,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FUSED ? 6 : 5, FUSED ? 6 : 5))) void k_attn_partial_mc(const uint16_t* __restrict__ qsplit, AttnFuse fz, int nq,
                                                          int nkv, uint16_t* __restrict__ kc,
                                                          uint16_t* __restrict__ vc, uint32_t max_seq, ColMap cm,
                                                          float* __restrict__ partial, int max_chunks) {
   constexpr int VS = 66;  // row stride of the staged V chunk in 32-bit words (128 bf16 + pad)
   __shared__ uint32_t Vs[ATT_CHUNK][VS];
-  __shared__ float sc[16][ATT_CHUNK];  // scores per head
+  constexpr int HMAX = FUSED ? 8 : 16;  // query heads per kv head the variant serves
+  __shared__ float sc[HMAX][ATT_CHUNK];  // scores per head
   // softmax weights as three bf16 pieces; before the scores exist the same bytes hold the query
   // pieces of the fused variant ([3][8][128]), which every wave has in registers by then
   __shared__ __attribute__((aligned(16))) uint16_t pw[3][16][ATT_CHUNK];
