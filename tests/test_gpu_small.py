@@ -636,6 +636,7 @@ def test_norm_tail_gives_up_cleanly_and_reports_it(nnc):
     for s_ in range(16):
         _, nx = g.prefill(s_, synth.tokens(9, shape.vocab, stream=s_))
         firsts.append(int(nx.item()))
+    g.set_option(nnc.OPT_FUSE_NORM, 1)
     g.set_option(nnc.OPT_SPIN_LIMIT, 1)
     g.decode_greedy(list(range(16)), firsts, 8)
     with pytest.raises(nnc.NncError) as ei:
