@@ -288,14 +288,18 @@ int pick_kts(int n_tiles, int KT) {
 // (the hand rules: pick_kts above and the launcher's own row-tile rule, stay in `a` when the
 // planner is switched off).
 constexpr int MAX_QKV_SLICES = 4;  // k slices of the QKV projection that the fused attention kernel adds up
-int skinny_rt_choices(int dt, int epi) {
-  if (dt == (int)NNC_F32) return epi == EPI_SWIGLU ? ((1 << 2) | (1 << 4)) : ((1 << 1) | (1 << 2) | (1 << 4));
+// wide: launches that may run alone on the chip (decode passes).  The chunk pass behind a long
+// prompt runs beside the prompt's last block on a second stream; workgroups of 6 or 8 row tiles
+// (240 registers per wave) do not fit next to that block's GEMM workgroups and cost the prompt 5 %.
+int skinny_rt_choices(int dt, int epi, bool wide = true) {
+  if (dt == (int)NNC_F32 || !wide) return epi == EPI_SWIGLU ? ((1 << 2) | (1 << 4)) : ((1 << 1) | (1 << 2) | (1 << 4));
   return epi == EPI_SWIGLU ? ((1 << 2) | (1 << 4) | (1 << 6) | (1 << 8)) : ((1 << 1) | (1 << 2) | (1 << 3) | (1 << 4) | (1 << 6));
 }
-void plan_skinny(const nnc_model* m, GemmArgs& a, int epi, int max_slices) {
+void plan_skinny(const nnc_model* m, GemmArgs& a, int epi, int max_slices, bool wide) {
   if (!m->opt_planner) return;
   const Machine mc = machine_mi355x(m->n_cus);
-  const SkinnyGemmPlan pl = plan_skinny_gemm(mc, a.n_tiles, a.KT, a.ncols, a.nseq, skinny_rt_choices(m->dt, epi), max_slices);
+  const SkinnyGemmPlan pl =
+      plan_skinny_gemm(mc, a.n_tiles, a.KT, a.ncols, a.nseq, skinny_rt_choices(m->dt, epi, wide), max_slices);
   if (pl.rt <= 0) return;
   a.rt = pl.rt;
   a.kts_per_split = pl.kts_per_split;
@@ -364,7 +368,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->qkv; a.ldo = Nqkv; a.split_stride = (long)n * Nqkv;
       // the fused attention kernel adds k-slice partial sums itself; every other consumer wants full sums
-      plan_skinny(m, a, EPI_STORE, fuse ? MAX_QKV_SLICES : 1);
+      plan_skinny(m, a, EPI_STORE, fuse ? MAX_QKV_SLICES : 1, p.decode);
       qkv_slices = (KTH + a.kts_per_split - 1) / a.kts_per_split;
       RUN(FAM_GEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * n, launch_gemm(s, dt, EPI_STORE, a));
     }
@@ -383,7 +387,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Wp = L.wo; a.n_tiles = H / 16; a.KT = KTQ; a.kts_per_split = pick_kts(a.n_tiles, KTQ);
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
-      plan_skinny(m, a, EPI_STORE, MAX_KSPLIT);
+      plan_skinny(m, a, EPI_STORE, MAX_KSPLIT, p.decode);
       pending = (KTQ + a.kts_per_split - 1) / a.kts_per_split;
       if (fuse_norm) norm_tail(a, L.g_post);
       RUN(FAM_GEMM_O, (double)H * Dq * w, 2.0 * H * Dq * n, launch_gemm(s, dt, EPI_STORE, a));
@@ -396,7 +400,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = KTH; a.kts_per_split = KTH;
       a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.packed_out = m->Ap; a.NC_out = nc; a.nsplit_out = ns;
-      plan_skinny(m, a, EPI_SWIGLU, 1);
+      plan_skinny(m, a, EPI_SWIGLU, 1, p.decode);
       RUN(FAM_GEMM_GU, 2.0 * F * H * w, 4.0 * F * H * n, launch_gemm(s, dt, EPI_SWIGLU, a));
     }
     {
@@ -404,7 +408,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Wp = L.wd; a.n_tiles = H / 16; a.KT = KTF; a.kts_per_split = pick_kts(a.n_tiles, KTF);
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
-      plan_skinny(m, a, EPI_STORE, MAX_KSPLIT);
+      plan_skinny(m, a, EPI_STORE, MAX_KSPLIT, p.decode);
       pending = (KTF + a.kts_per_split - 1) / a.kts_per_split;
       // the norm this output feeds: the next layer's input norm, or the final norm when the head
       // wants every column
@@ -429,7 +433,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
     a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = KTH; a.kts_per_split = KTH;
     a.Xp = m->Xp; a.NC = hc; a.ncols = hc; a.nsplit = ns; a.nseq = hn;
     a.out = p.logits; a.ldo = p.logits_ld; a.step_ptr = p.step_ptr; a.step_stride = p.step_stride;
-    plan_skinny(m, a, EPI_STORE, 1);
+    plan_skinny(m, a, EPI_STORE, 1, p.decode);
     RUN(FAM_GEMM_HEAD, (double)V * H * w, 2.0 * V * H * hn, launch_gemm(s, dt, EPI_STORE, a));
     if (p.next)
       RUN(FAM_ARGMAX, hn * V * 4.0, 0,
