@@ -511,6 +511,29 @@ def test_batched_decode_equals_independent_sequences(nnc, batch):
             nxt[s] = n_o
 
 
+@pytest.mark.parametrize("persistent", [1, 0], ids=["resident", "per-stage"])
+@pytest.mark.parametrize("batch", [1, 3])
+def test_decode_from_empty_slots(nnc, batch, persistent):
+    """No prompt at all: the first decode step runs at position 0 on an empty cache (the attention
+    kernels then read only rows that were never written, with weight zero: the cache is
+    zero-filled at create so that these are finite), the following ones on what the steps appended."""
+    print(f"case: decode from empty slots, B={batch}, persistent={persistent}", flush=True)
+    shape = SMALL_G4
+    g, o = _pair(nnc, shape, batch, 80)
+    g.set_option(nnc.OPT_PERSISTENT, persistent)
+    fl = oracle_flags(shape)
+    t = [int(v) for v in synth.tokens(batch, shape.vocab, stream=9)]
+    for step in range(70):                     # crosses the first 64-position chunk boundary
+        lg, ng = g.decode_step(list(range(batch)), t)
+        nxt = []
+        for b in range(batch):
+            lo, nb = o.step_token(b, t[b], fl)
+            _check_logits(shape, lg[b], lo)
+            assert int(ng[b].item()) == nb, (step, b)
+            nxt.append(nb)
+        t = nxt
+
+
 def test_hidden_state_layer_fp32(nnc):
     print("case: hidden-state layer fp32", flush=True)
     shape = SMALL_LAYER_F32
