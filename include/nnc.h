@@ -297,8 +297,11 @@ nnc_status nnc_stage_trace(nnc_model *m, uint64_t *out, uint32_t cap, uint32_t *
  *   nnc_plan_prefill_gemm_query  prompt GEMM [rows x k] x [k x n_tokens] with `pieces` 16-bit
  *                                pieces per activation; may use up to max_k_slices k slices
  *   nnc_plan_skinny_gemm_query   weight-streaming GEMM of a decode pass with n_seq sequences of
- *                                `pieces` pieces each; tile_rows = rows per workgroup, t_comp_us =
- *                                time of the operand re-reads
+ *                                `pieces` pieces each; T_mem has two levels here: t_mem_us = the
+ *                                weights from HBM, t_comp_us = what the busiest compute unit moves
+ *                                through its vector memory path (its workgroups' weight tiles and
+ *                                operand reads); tile_rows = rows per workgroup (16 x 1, 2, 3, 4, 6
+ *                                or 8 row tiles); max_k_slices = partial sums the consumer can add
  */
 typedef struct {
   uint32_t tile_rows, tile_cols;  /* block tile (rows x operand columns) */
