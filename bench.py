@@ -136,27 +136,32 @@ def percentile(v, q):
     return v[min(len(v) - 1, int(round(q * (len(v) - 1))))]
 
 
-def compare(model, prompt, want):
+def compare(model, prompt, want, others=()):
     """GPU logits of slot 0's prompt pass and of decode steps teacher-forced on the expected
-    tokens against `want` = [(fp64 logits, greedy token)]: max abs error, agreement, margin."""
+    tokens against `want` = [(fp64 logits, greedy token)]: max abs error, agreement, margin.
+    `others`: prompts of slots 1 ..; with them slot 0 decodes as column 0 of the full batch (the
+    timed launch configuration), the other slots following their own greedy tokens."""
     import numpy as np
-    model.kv_reset(0)
+    model.kv_reset(-1)
     lg, _ = model.prefill(0, prompt)
     got = [lg.double().cpu().numpy()]
+    slots = list(range(1 + len(others)))
+    rest = [int(model.prefill(b + 1, p, want_logits=False)[1].item()) for b, p in enumerate(others)]
     for i in range(len(want) - 1):
-        lg, _ = model.decode_step([0], [want[i][1]])
+        lg, nx = model.decode_step(slots, [want[i][1]] + rest)
         got.append(lg[0].double().cpu().numpy())
+        rest = [int(v) for v in nx.tolist()[1:]]
     err, agree, margin = 0.0, 0, float("inf")
     for g, (lo, t) in zip(got, want):
         err = max(err, float(np.abs(g - lo).max()))
         part = np.partition(lo, -2)
         margin = min(margin, float(part[-1] - part[-2]))
         agree += int(int(np.argmax(g)) == t)
-    return {"positions": len(want), "max_abs_err": round(err, 6), "greedy_agreement": round(agree / len(want), 4),
-            "min_margin": round(margin, 6)}
+    return {"positions": len(want), "batch": len(slots), "max_abs_err": round(err, 6),
+            "greedy_agreement": round(agree / len(want), 4), "min_margin": round(margin, 6)}
 
 
-def parity_full_depth(model, workload, prompt):
+def parity_full_depth(model, workload, prompt, others=()):
     """Slot 0 at the workload's full context against the expected values the oracle wrote offline
     (tests/golden/, full depth; prompt blocks mirrored); None where no such file is committed."""
     import numpy as np
@@ -166,8 +171,9 @@ def parity_full_depth(model, workload, prompt):
         return None
     z = np.load(path)
     want = [(z["logits"][i].astype(np.float64), int(z["next"][i])) for i in range(len(z["next"]))]
-    out = compare(model, prompt, want)
-    out["reference"] = "full-depth oracle values written offline (prompt rounding points mirrored), full context"
+    out = compare(model, prompt, want, others)
+    out["reference"] = ("full-depth oracle values written offline (prompt rounding points mirrored), full context; "
+                        "slot 0 decoded as one column of the workload's batch")
     return out
 
 
@@ -183,6 +189,7 @@ def main() -> int:
                     help="tokens per block of the prompt pass (NNC_OPT_PREFILL_BLOCK; 0 = the library's default)")
     ap.add_argument("--prefill-tile", type=int, default=-1, help="force a block tile of the prompt GEMMs (NNC_OPT_PREFILL_TILE)")
     ap.add_argument("--planner", type=int, default=1, help="0: the hand rules instead of the analytic tile chooser (NNC_OPT_PLANNER)")
+    ap.add_argument("--decode-pieces", type=int, default=0, help="pieces per activation in batched decode GEMMs (NNC_OPT_DECODE_PIECES; 0 = the library's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing sample")
@@ -216,6 +223,8 @@ def main() -> int:
         model.set_option(nnc.OPT_PLANNER, 0)
     if args.prefill_tile >= 0:
         model.set_option(nnc.OPT_PREFILL_TILE, args.prefill_tile)
+    if args.decode_pieces:
+        model.set_option(nnc.OPT_DECODE_PIECES, args.decode_pieces)
     note("model ready; warm-up passes")
     prompts = [synth.tokens(T, shape.vocab, stream=b) for b in range(B)]
     prompt = prompts[0]
@@ -354,7 +363,7 @@ def main() -> int:
         stage_trace = resident_stage_trace(model, nnc, shape, prompt)
 
     note("parity and oracle legs")
-    parity = None if args.no_parity else parity_full_depth(model, args.workload, prompt)
+    parity = None if args.no_parity else parity_full_depth(model, args.workload, prompt, prompts[1:])
 
     cpu = None
     if not args.no_cpu_baseline:

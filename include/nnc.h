@@ -247,6 +247,10 @@ typedef enum {
                                is bounded by NNC_OPT_SPIN_LIMIT.  0 (default): in a kernel of its own --
                                the hand-over inside the launch (store acknowledgement, counter, reads
                                past the caches) takes as long as the kernel boundary it replaces */
+  NNC_OPT_DECODE_PIECES = 12, /* bf16 / binary16 pieces an activation is split into before a decode GEMM of
+                               a batch of two or more sequences: 0 (default) the library's choice, 2 or 3
+                               forced.  Three pieces carry an fp32 value to 2^-25 relative, two to 2^-17
+                               (a third fewer operand columns) */
   NNC_OPT_SPIN_LIMIT = 5,   /* polls after which a wait inside the resident kernel gives up (sets
                                the failure flag and lets every workgroup exit); 0 (default):
                                2^20, about a second.  A tiny value makes the give-up path testable */

@@ -20,6 +20,7 @@ OPT_TAIL_OVERLAP = 8
 OPT_PREFILL_BLOCK = 9
 OPT_PLANNER = 10
 OPT_FUSE_NORM = 11
+OPT_DECODE_PIECES = 12
 
 # every symbol include/nnc.h declares
 EXPORTS = [

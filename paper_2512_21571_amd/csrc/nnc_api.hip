@@ -120,6 +120,7 @@ struct nnc_model {
   int mk_trace_step = -1;
 
   bool opt_graph = true;
+  int opt_decode_pieces = 0;  // 0: three pieces; 2 / 3: forced for batches of two or more
   int opt_prefill_exact = 0;  // 0: large blocks, pieces by length; 1: 21-token chunks, three pieces; 2: large blocks, two pieces
   bool opt_fuse_qk = true;    // decode passes: QK-norm / RoPE / append inside the attention kernel
   int opt_prefill_attn = -1;  // forced launch shape of the prompt attention, -1 = by size
@@ -446,13 +447,15 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
   return NNC_OK;
 }
 
-// bf16 pieces per activation in decode: three, whose sum is the fp32 value to within
-// 2^-25 relative, so a batch of B sequences computes what B batch-1 steps compute.
-// (Two pieces, 2^-17, were measurably noisier: a bf16 K/V element that rounds the
-// other way perturbs everything downstream by ~1e-4 relative.)
+// 16-bit pieces per activation in decode.  Three carry an fp32 value to within 2^-25 relative, so
+// a batch of B sequences computes what B batch-1 steps compute; two carry it to 2^-17 (still 64
+// times finer than a binary16 activation, the paper's own 16-bit precision: Section 4, setup) and
+// are taken where they save a whole 16-column operand block of every decode GEMM (6-8 sequences:
+// one block instead of two; 11-16: two instead of three; 17-21: three instead of four).
 int decode_nsplit(const nnc_model* m, uint32_t batch) {
-  (void)batch;
-  return m->f32 ? 1 : 3;
+  if (m->f32) return 1;
+  if (m->opt_decode_pieces && batch >= 2) return m->opt_decode_pieces;
+  return (2 * batch + 15) / 16 < (3 * batch + 15) / 16 ? 2 : 3;
 }
 
 // Chunk count of an attention launch, rounded up to a multiple of 8 (the captured decode graphs
@@ -924,7 +927,7 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
       return NNC_OK;
     case NNC_OPT_PERSISTENT: m->opt_persistent = value != 0; return NNC_OK;
     case NNC_OPT_PREFILL_TILE:
-      if (value < -1 || value > 4) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic) or 0 .. 4");
+      if (value < -1 || value > 5) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic) or 0 .. 5");
       m->opt_prefill_tile = value;
       return NNC_OK;
     case NNC_OPT_TAIL_OVERLAP: m->opt_tail_overlap = value != 0; return NNC_OK;
@@ -952,6 +955,10 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
       m->opt_fuse_norm = value != 0;
       for (auto& kv : m->graphs) (void)hipGraphExecDestroy(kv.second);
       m->graphs.clear();
+      return NNC_OK;
+    case NNC_OPT_DECODE_PIECES:
+      if (value != 0 && value != 2 && value != 3) return fail(NNC_E_ARG, "decode pieces must be 0 (default), 2 or 3");
+      m->opt_decode_pieces = value;
       return NNC_OK;
     case NNC_OPT_SPIN_LIMIT:
       if (value < 0) return fail(NNC_E_ARG, "spin limit must be >= 0");
