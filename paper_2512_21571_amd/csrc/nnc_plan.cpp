@@ -28,6 +28,9 @@ Machine machine_mi355x(int cus) {
   m.pg_c1 = 0.0241;
   m.pg_c0 = 0.110;
   m.pg_solo = 0.78;
+  // the 256 x 256 tile, one workgroup per CU: 0.83 us per k step (64 matrix-core instructions per
+  // wave), measured on the 8B gate|up and down projections at 4080 tokens
+  m.pg_big = 0.83;
   // the register-ring kernel of the 64-row tiles: 0.26 us per k step with 4 matrix-core
   // instructions per wave (64 x 64), 0.37 with 8 (64 x 128)
   m.rg_c1 = 0.0275;
@@ -41,11 +44,12 @@ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 struct PgTile {
   int code, nt, tt;
   bool lds_direct;  // three LDS stages filled by direct copies, no k split; else register ring, two stages
+  int wgs_per_cu;   // resident workgroups per CU the kernel is built for
 };
 // every block tile the prompt GEMM kernels are instantiated for, plus one that is not (256 x 256
-// with four waves: it shows the capacity constraints at work and is never chosen)
-const PgTile kPgTiles[] = {{1, 16, 8, true}, {4, 12, 8, true}, {2, 8, 8, true}, {0, 4, 8, false}, {3, 4, 4, false},
-                           {-1, 16, 16, true}};
+// with two workgroups per CU: it shows the capacity constraints at work and is never chosen)
+const PgTile kPgTiles[] = {{1, 16, 8, true, 2}, {4, 12, 8, true, 2}, {2, 8, 8, true, 2}, {0, 4, 8, false, 2},
+                           {3, 4, 4, false, 2}, {5, 16, 16, true, 1}, {-1, 16, 16, true, 2}};
 }  // namespace
 
 PrefillGemmPlan plan_prefill_gemm(const Machine& mc, int n_tiles, int KT, int col_tiles, int n_tokens, int pieces,
@@ -58,8 +62,8 @@ PrefillGemmPlan plan_prefill_gemm(const Machine& mc, int n_tiles, int KT, int co
   const double out_bytes = epi == PLAN_EPI_STORE ? n_tokens * N * 4.0
                            : epi == PLAN_EPI_RESID ? n_tokens * N * 8.0  // read-modify-write of the residual stream
                                                    : n_tokens * (N / 2.0) * 2.0 * pieces;
-  const int wgs_per_cu = 2;  // the kernels are built for two resident workgroups per CU
   for (const PgTile& t : kPgTiles) {
+    const int wgs_per_cu = t.wgs_per_cu;
     ++best.candidates;
     // capacity: staged operands of the resident workgroups in LDS; accumulators and two sets of
     // fragments (one for the ring kernels) in the wave's registers
@@ -67,7 +71,8 @@ PrefillGemmPlan plan_prefill_gemm(const Machine& mc, int n_tiles, int KT, int co
     const int lds = stages * (t.nt + t.tt) * 1024 * wgs_per_cu;
     const int wi = t.nt / 2, wj = t.tt / 2;
     const int regs = wi * wj * 4 + (t.lds_direct ? 2 : 1) * (wi + wj) * 4 + (t.lds_direct ? 0 : 8 * (t.nt / 4 + t.tt / 4) * 4);
-    if (lds > mc.lds_bytes || regs > mc.vgprs_per_wave || t.code < 0) {
+    // (a wave alone on its SIMD has the accumulation registers on top of the ordinary ones)
+    if (lds > mc.lds_bytes || regs > mc.vgprs_per_wave * (wgs_per_cu == 1 ? 2 : 1) || t.code < 0) {
       ++best.rejected_by_capacity;
       continue;
     }
@@ -80,9 +85,12 @@ PrefillGemmPlan plan_prefill_gemm(const Machine& mc, int n_tiles, int KT, int co
       const int wgs = ceil_div(n_tiles, t.nt) * ceil_div(col_tiles, t.tt) * slices;
       const int slots = wgs_per_cu * mc.cus;
       const int full = wgs / slots, rem = wgs - full * slots;
-      const double t2 = t.lds_direct ? mc.pg_c0 + mc.pg_c1 * wi * wj : mc.rg_c0 + mc.rg_c1 * wi * wj;
+      const double t2 = wgs_per_cu == 1 ? mc.pg_big
+                        : t.lds_direct  ? mc.pg_c0 + mc.pg_c1 * wi * wj
+                                        : mc.rg_c0 + mc.rg_c1 * wi * wj;
       const double t1 = mc.pg_solo * t2;
-      const double t_comp = kts * (full * t2 + (rem == 0 ? 0.0 : rem <= mc.cus ? t1 : t2));
+      const double t_comp = wgs_per_cu == 1 ? kts * t2 * (full + (rem ? 1 : 0))
+                                            : kts * (full * t2 + (rem == 0 ? 0.0 : rem <= mc.cus ? t1 : t2));
       const double fold = (slices - 1) * n_tokens * N * 4.0 * 2.0;  // partials written, then read by the norm kernel
       const double t_mem = (W + X) / mc.hbm_bytes_per_us;
       const double total = std::max(t_comp, t_mem) + (out_bytes + fold) / mc.hbm_bytes_per_us + mc.launch_us;

@@ -58,21 +58,75 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 }  // namespace
 
+// Epilogue of the prompt GEMMs for one token tile: v[i] = the accumulators (pieces already added)
+// of the wave's row tiles nt_first + i for column tile `ct` (token tile ct / PIECES).
+// accumulator element e of lane l: row (l / 16) * 4 + e of the row tile, operand column l % 16.
+template <int EPI, int WI, int PIECES, class HF>
+__device__ __forceinline__ void pg_epilogue_col(const PrefillGemmArgs& a, const f32x4 (&v)[WI], int nt_first, int ct,
+                                                int lane, int kslice) {
+  const int c16 = lane & 15, g = lane >> 4;
+  const int tt = ct / PIECES;        // token tile
+  const size_t t = (size_t)tt * 16 + c16;
+  if constexpr (EPI == EPI_SWIGLU) {
+    // row tiles come as (gate, up) pairs; feature tile = row tile / 2
+    const int FKT = a.n_tiles / 4;  // k tiles of the next GEMM: features / 32
+#pragma unroll
+    for (int i = 0; i < WI; i += 2) {
+      const int nt = nt_first + i;
+      if (nt >= a.n_tiles) continue;
+      const int f0 = (nt >> 1) * 16 + g * 4;
+      uint32_t h[PIECES][4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float gate = v[i][e], up = v[i + 1][e];
+        float act = gate / (1.0f + expf(-gate)) * up;
+#pragma unroll
+        for (int pc = 0; pc < PIECES; ++pc) {
+          h[pc][e] = HF::bits(act);
+          act -= HF::widen(h[pc][e]);
+        }
+      }
+      // features f0 .. f0+3 of token t: 8 bytes inside one 16-byte fragment element
+#pragma unroll
+      for (int pc = 0; pc < PIECES; ++pc) {
+        const size_t el =
+            (((size_t)(tt * PIECES + pc) * FKT + (f0 >> 5)) * 64 + c16 + 16 * ((f0 & 31) >> 3)) * 8 + (f0 & 7);
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.packed_out) + el) =
+            make_uint2(h[pc][0] | (h[pc][1] << 16), h[pc][2] | (h[pc][3] << 16));
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < WI; ++i) {
+      const int nt = nt_first + i;
+      if (nt >= a.n_tiles) continue;
+      // k slice 0 owns the output; slice s > 0 stores its partial sums in buffer s - 1, which
+      // the next norm kernel adds in a fixed order
+      float* base = kslice == 0 ? a.out : a.part + (size_t)(kslice - 1) * a.part_stride;
+      float4* dst = reinterpret_cast<float4*>(base + t * a.ldo + (size_t)nt * 16 + g * 4);
+      float4 o = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
+      if constexpr (EPI == EPI_RESID) {
+        if (kslice == 0) {
+          const float4 p = *dst;
+          o = make_float4(p.x + o.x, p.y + o.y, p.z + o.z, p.w + o.w);
+        }
+      }
+      *dst = o;
+    }
+  }
+}
+
 // Epilogue of the prompt GEMMs: the accumulators of wave (wn, wt) of the block at (nt0, tt0).
+// With two pieces, column tiles 2q and 2q+1 are the two pieces of token tile q and their
+// accumulators are added.
 template <int EPI, int NT, int TT, int PIECES, class HF>
 __device__ __forceinline__ void pg_epilogue(const PrefillGemmArgs& a, f32x4 (&acc)[NT / 2][TT / 2], int nt0, int tt0,
                                             int wn, int wt, int lane, int kslice = 0) {
   constexpr int WI = NT / 2, WJ = TT / 2;
-  // accumulator element e of lane l in tile (i, j): row (l / 16) * 4 + e of row tile i,
-  // operand column l % 16 of column tile j.  With two pieces, column tiles 2q and 2q+1 are
-  // the two pieces of token tile q and their accumulators are added.
-  const int c16 = lane & 15, g = lane >> 4;
 #pragma unroll
   for (int j = 0; j < WJ; j += PIECES) {
     const int ct = tt0 + wt * WJ + j;  // column tile
     if (ct >= a.t_tiles) continue;
-    const int tt = ct / PIECES;        // token tile
-    const size_t t = (size_t)tt * 16 + c16;
     f32x4 v[WI];
 #pragma unroll
     for (int i = 0; i < WI; ++i) {
@@ -82,53 +136,7 @@ __device__ __forceinline__ void pg_epilogue(const PrefillGemmArgs& a, f32x4 (&ac
         for (int e = 0; e < 4; ++e) v[i][e] += acc[i][j + 1][e];
       }
     }
-    if constexpr (EPI == EPI_SWIGLU) {
-      // row tiles come as (gate, up) pairs; feature tile = row tile / 2
-      const int FKT = a.n_tiles / 4;  // k tiles of the next GEMM: features / 32
-#pragma unroll
-      for (int i = 0; i < WI; i += 2) {
-        const int nt = nt0 + wn * WI + i;
-        if (nt >= a.n_tiles) continue;
-        const int f0 = (nt >> 1) * 16 + g * 4;
-        uint32_t h[PIECES][4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float gate = v[i][e], up = v[i + 1][e];
-          float act = gate / (1.0f + expf(-gate)) * up;
-#pragma unroll
-          for (int pc = 0; pc < PIECES; ++pc) {
-            h[pc][e] = HF::bits(act);
-            act -= HF::widen(h[pc][e]);
-          }
-        }
-        // features f0 .. f0+3 of token t: 8 bytes inside one 16-byte fragment element
-#pragma unroll
-        for (int pc = 0; pc < PIECES; ++pc) {
-          const size_t el =
-              (((size_t)(tt * PIECES + pc) * FKT + (f0 >> 5)) * 64 + c16 + 16 * ((f0 & 31) >> 3)) * 8 + (f0 & 7);
-          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.packed_out) + el) =
-              make_uint2(h[pc][0] | (h[pc][1] << 16), h[pc][2] | (h[pc][3] << 16));
-        }
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < WI; ++i) {
-        const int nt = nt0 + wn * WI + i;
-        if (nt >= a.n_tiles) continue;
-        // k slice 0 owns the output; slice s > 0 stores its partial sums in buffer s - 1, which
-        // the next norm kernel adds in a fixed order
-        float* base = kslice == 0 ? a.out : a.part + (size_t)(kslice - 1) * a.part_stride;
-        float4* dst = reinterpret_cast<float4*>(base + t * a.ldo + (size_t)nt * 16 + g * 4);
-        float4 o = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
-        if constexpr (EPI == EPI_RESID) {
-          if (kslice == 0) {
-            const float4 p = *dst;
-            o = make_float4(p.x + o.x, p.y + o.y, p.z + o.z, p.w + o.w);
-          }
-        }
-        *dst = o;
-      }
-    }
+    pg_epilogue_col<EPI, WI, PIECES, HF>(a, v, nt0 + wn * WI, ct, lane, kslice);
   }
 }
 
@@ -355,14 +363,211 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill_dl(PrefillGemmArgs a) {
   pg_epilogue<EPI, NT, TT, PIECES, HF>(a, acc, nt0, tt0, wn, wt, lane);
 }
 
+// 256 x 256 block tile, one workgroup per CU, 128 x 128 per wave: per k step a wave reads 16
+// fragments from LDS for 64 matrix-core instructions (0.25 KiB per instruction against 0.375 for
+// the 128 x 64 wave tile above), which is what the large-tile kernel above is bound by.  The
+// 64 accumulator tiles fill the wave's 256 accumulation registers; the compiler, asked to keep
+// them there, shuffles them through the ordinary registers every k step, so the kernel names
+// them itself: tile (i, j) lives in a[(8 i + j) * 4 .. + 3] and the matrix-core instructions,
+// the zeroing and the read-out are inline assembly with those names.  Being opaque to the
+// compiler they get no automatic wait states: the ones the hardware needs between a write of an
+// accumulation register and a product that reads it, and between the last product and the first
+// read of its result, are put in by hand (s_nop).  The copies and fragment reads of the next
+// steps are spread between the groups of eight products (one wave per SIMD: nothing else hides
+// their issue slots); compiler barriers keep that order.
+template <class HF, int N>
+__device__ __forceinline__ void big_mfma(u32x4 a, u32x4 b) {
+  if constexpr (HF::kDtype == DT_F16)
+    asm volatile("v_mfma_f32_16x16x32_f16 a[%2:%3], %0, %1, a[%2:%3]" : : "v"(a), "v"(b), "n"(N), "n"(N + 3));
+  else
+    asm volatile("v_mfma_f32_16x16x32_bf16 a[%2:%3], %0, %1, a[%2:%3]" : : "v"(a), "v"(b), "n"(N), "n"(N + 3));
+}
+template <int N>
+__device__ __forceinline__ f32x4 big_acc_read() {
+  f32x4 v;
+  asm volatile("v_accvgpr_read_b32 %0, a[%4]\n\tv_accvgpr_read_b32 %1, a[%5]\n\t"
+               "v_accvgpr_read_b32 %2, a[%6]\n\tv_accvgpr_read_b32 %3, a[%7]"
+               : "=v"(v[0]), "=v"(v[1]), "=v"(v[2]), "=v"(v[3])
+               : "n"(N), "n"(N + 1), "n"(N + 2), "n"(N + 3));
+  return v;
+}
+template <int N>
+__device__ __forceinline__ void big_acc_zero() {
+  asm volatile("v_accvgpr_write_b32 a[%0], 0\n\tv_accvgpr_write_b32 a[%1], 0\n\t"
+               "v_accvgpr_write_b32 a[%2], 0\n\tv_accvgpr_write_b32 a[%3], 0"
+               :
+               : "n"(N), "n"(N + 1), "n"(N + 2), "n"(N + 3));
+}
+
+template <int EPI, int PIECES, class HF>
+__global__ __launch_bounds__(256, 1) void k_gemm_prefill_big(PrefillGemmArgs a) {
+  constexpr int NT = 16, TT = 16, WI = 8, WJ = 8, AL = 4, BL = 4;
+  // Three LDS stages (a fourth changed nothing: the copies are bound by throughput, not latency);
+  // the fragment reads of the next step sit in the first RG = 4 groups, so that none is still
+  // outstanding when the step ends at the barrier (+2 % over two reads in each of the 8 groups).
+  constexpr int ST = 3, RG = 4;
+  __shared__ u32x4 As[ST][NT][64];
+  __shared__ u32x4 Bs[ST][TT][64];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wn = wave >> 1, wt = wave & 1;
+  const int KT = a.KT;
+  // Block order.  The workgroups resident together (one per CU, 256 at a time in launch order)
+  // should share operands: panels of 16 row blocks x all column blocks, and inside a panel groups of
+  // 16 x 16 blocks.  The hardware deals consecutive workgroups to the 8 XCDs in turn, so within a
+  // group XCD x takes a patch of 4 row blocks x 8 column blocks: its L2 then serves 12 operand
+  // streams to its 32 workgroups instead of 18.
+  int bx, by;
+  {
+    const int gx = gridDim.x, gy = gridDim.y;
+    const int w = blockIdx.x + gx * blockIdx.y;
+    const int p = w / (16 * gy), within = w - p * 16 * gy;
+    const int rows = min(16, gx - p * 16);
+    if (rows == 16 && gy % 16 == 0) {
+      const int grp = within / 256, wi = within - grp * 256;
+      const int xcd = wi & 7, l = wi >> 3;
+      bx = p * 16 + (xcd >> 1) * 4 + (l & 3);
+      by = grp * 16 + (xcd & 1) * 8 + (l >> 2);
+    } else {
+      bx = p * 16 + within % rows;
+      by = within / rows;
+    }
+  }
+  const int nt0 = bx * NT, tt0 = by * TT;
+  const char* __restrict__ W = static_cast<const char*>(a.Wp);
+  const char* __restrict__ X = static_cast<const char*>(a.Xf);
+
+  // every accumulation register is this kernel's: tell the compiler once (it then allocates all
+  // 256 to the wave and keeps its own values out of them)
+  asm volatile("" ::: "a0", "a255");
+  static_for<WI * WJ>([&](auto n) __attribute__((always_inline)) { big_acc_zero<decltype(n)::value * 4>(); });
+
+  uint32_t voa[AL], vob[BL];
+#pragma unroll
+  for (int j = 0; j < AL; ++j) voa[j] = ((uint32_t)min(nt0 + wave + 4 * j, a.n_tiles - 1) * (uint32_t)KT * 64u + lane) * 16u;
+#pragma unroll
+  for (int j = 0; j < BL; ++j) vob[j] = ((uint32_t)min(tt0 + wave + 4 * j, a.t_tiles - 1) * (uint32_t)KT * 64u + lane) * 16u;
+  typedef __attribute__((address_space(3))) void* lptr;
+  auto copy1 = [&](const char* base, uint32_t voff, uint32_t lds_addr) __attribute__((always_inline)) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(base)
+                 : "memory", "m0");
+  };
+  // copy number c (0 .. 7) of k step kt into stage st: four weight fragments, four operand fragments
+  auto issue1 = [&](auto cc, int kt, int st) __attribute__((always_inline)) {
+    constexpr int c = decltype(cc)::value;
+    const size_t ko = (size_t)kt * 1024;
+    if constexpr (c < AL) copy1(W + ko, voa[c], (uint32_t)(size_t)(lptr)&As[st][wave + 4 * c][0]);
+    else copy1(X + ko, vob[c - AL], (uint32_t)(size_t)(lptr)&Bs[st][wave + 4 * (c - AL)][0]);
+  };
+  auto issue = [&](int kt, int st) __attribute__((always_inline)) {
+    static_for<AL + BL>([&](auto cc) __attribute__((always_inline)) { issue1(cc, kt, st); });
+  };
+  constexpr int L = AL + BL;
+  auto wait_vm = [](auto nc) __attribute__((always_inline)) {
+    constexpr int n = decltype(nc)::value;
+    __builtin_amdgcn_s_waitcnt((n & 0xf) | (7 << 4) | (15 << 8) | ((n >> 4) << 14));
+  };
+  // wait until at most r whole steps of copies (r <= ST - 2) are still in flight
+  auto wait_steps = [&](int r) __attribute__((always_inline)) {
+    if (r >= 2 && ST >= 4) wait_vm(std::integral_constant<int, 2 * L>{});
+    else if (r >= 1) wait_vm(std::integral_constant<int, L>{});
+    else wait_vm(std::integral_constant<int, 0>{});
+  };
+  u32x4 af[2][WI], bf[2][WJ];
+  constexpr std::integral_constant<int, 0> c0{};
+  constexpr std::integral_constant<int, 1> c1{};
+  // Step kt (fragments in register set P): stage kt % ST is in registers and free, stage
+  // (kt + 1) % ST must have landed, the stages after it are in flight.  Group g = copy g of step
+  // kt + ST (MORE), fragments of step kt + 1 into the other set (NEXT; spread over the first RG
+  // groups), then the eight products of row tile g.
+  auto step = [&](auto setc, auto morec, auto nextc, int kt, int st) __attribute__((always_inline)) {
+    constexpr int P = decltype(setc)::value;
+    constexpr bool MORE = decltype(morec)::value, NEXT = decltype(nextc)::value;
+    if constexpr (MORE) wait_vm(std::integral_constant<int, (ST - 2) * L>{});
+    else wait_steps(min(KT - kt - 2, ST - 2));
+    lds_sync();
+    const int nx = st == ST - 1 ? 0 : st + 1;
+    static_for<WI>([&](auto gc) __attribute__((always_inline)) {
+      constexpr int g = decltype(gc)::value;
+      if constexpr (MORE) issue1(gc, kt + ST, st);
+      if constexpr (NEXT && g < RG) {
+        constexpr int per = WI / RG;
+#pragma unroll
+        for (int q = g * per; q < (g + 1) * per; ++q) {
+          af[1 - P][q] = As[nx][wn * WI + q][lane];
+          bf[1 - P][q] = Bs[nx][wt * WJ + q][lane];
+        }
+      }
+      asm volatile("" ::: "memory");
+      static_for<WJ>([&](auto jc) __attribute__((always_inline)) {
+        big_mfma<HF, (g * WJ + decltype(jc)::value) * 4>(af[P][g], bf[P][decltype(jc)::value]);
+      });
+      asm volatile("" ::: "memory");
+    });
+  };
+#pragma unroll
+  for (int q = 0; q < ST; ++q)
+    if (q < KT) issue(q, q);
+  wait_steps(min(KT, ST) - 1);
+  lds_sync();
+#pragma unroll
+  for (int i = 0; i < WI; ++i) af[0][i] = As[0][wn * WI + i][lane];
+#pragma unroll
+  for (int j = 0; j < WJ; ++j) bf[0][j] = Bs[0][wt * WJ + j][lane];
+  asm volatile("s_nop 7" ::: "memory");  // zeroed accumulation registers -> first products
+  constexpr std::true_type yes{};
+  constexpr std::false_type no{};
+  int st = 0, kt = 0;
+  auto next_stage = [&]() __attribute__((always_inline)) { st = st == ST - 1 ? 0 : st + 1; };
+  // steady state: pairs of steps that both copy ST steps ahead
+  for (; kt + 1 + ST < KT; kt += 2) {
+    step(c0, yes, yes, kt, st);
+    next_stage();
+    step(c1, yes, yes, kt + 1, st);
+    next_stage();
+  }
+  // the last steps: kt is even here
+  for (; kt < KT; kt += 2) {
+    if (kt + ST < KT) step(c0, yes, yes, kt, st);
+    else if (kt + 1 < KT) step(c0, no, yes, kt, st);
+    else step(c0, no, no, kt, st);
+    next_stage();
+    if (kt + 1 < KT) {
+      if (kt + 1 + ST < KT) step(c1, yes, yes, kt + 1, st);
+      else if (kt + 2 < KT) step(c1, no, yes, kt + 1, st);
+      else step(c1, no, no, kt + 1, st);
+      next_stage();
+    }
+  }
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // last products -> read-out
+  static_for<WJ / PIECES>([&](auto qc) __attribute__((always_inline)) {
+    constexpr int j = decltype(qc)::value * PIECES;
+    const int ct = tt0 + wt * WJ + j;
+    f32x4 v[WI];
+    static_for<WI>([&](auto ic) __attribute__((always_inline)) {
+      constexpr int i = decltype(ic)::value;
+      v[i] = big_acc_read<(i * WJ + j) * 4>();
+      if constexpr (PIECES == 2) {
+        const f32x4 w = big_acc_read<(i * WJ + j + 1) * 4>();
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[i][e] += w[e];
+      }
+    });
+    if (ct < a.t_tiles) pg_epilogue_col<EPI, WI, PIECES, HF>(a, v, nt0 + wn * WI, ct, lane, 0);
+  });
+}
+
 // a.t_tiles counts operand column tiles (token tiles x pieces).  shape: 0 = 64 x 128 block
-// tiles, 1 = 256 x 128, 2 = 128 x 128, 3 = 64 x 64, 4 = 192 x 128.
+// tiles, 1 = 256 x 128, 2 = 128 x 128, 3 = 64 x 64, 4 = 192 x 128, 5 = 256 x 256 (one workgroup
+// per CU, 128 x 128 per wave: 16 fragments from LDS per 64 matrix-core instructions).
 hipError_t launch_gemm_prefill(hipStream_t s, bool f16, int epi, const PrefillGemmArgs& a, int pieces, int shape) {
   if (a.n_tiles <= 0 || a.t_tiles <= 0 || a.KT <= 0 || (pieces != 1 && pieces != 2) || a.t_tiles % pieces ||
-      shape < 0 || shape > 4)
+      shape < 0 || shape > 5)
     return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU && a.n_tiles % 4) return hipErrorInvalidValue;
-  const int NT = shape == 1 ? 16 : shape == 4 ? 12 : shape == 2 ? 8 : 4, TT = shape == 3 ? 4 : 8;
+  const int NT = (shape == 1 || shape == 5) ? 16 : shape == 4 ? 12 : shape == 2 ? 8 : 4,
+            TT = shape == 3 ? 4 : shape == 5 ? 16 : 8;
   int ksplit = 1;
   if (a.kts_per_split > 0) {  // only the small tiles, only the residual epilogue, and a place for the partials
     if ((shape != 0 && shape != 3) || epi != EPI_RESID || !a.part) return hipErrorInvalidValue;
@@ -375,6 +580,7 @@ hipError_t launch_gemm_prefill(hipStream_t s, bool f16, int epi, const PrefillGe
     else if (shape == 1) k_gemm_prefill_dl<E, 16, 8, P, HF><<<grid, 256, 0, s>>>(a);   \
     else if (shape == 2) k_gemm_prefill_dl<E, 8, 8, P, HF><<<grid, 256, 0, s>>>(a);    \
     else if (shape == 4) k_gemm_prefill_dl<E, 12, 8, P, HF><<<grid, 256, 0, s>>>(a);   \
+    else if (shape == 5) k_gemm_prefill_big<E, P, HF><<<grid, 256, 0, s>>>(a);         \
     else k_gemm_prefill<E, 4, 4, P, HF><<<grid, 256, 0, s>>>(a);                       \
   } while (0)
 #define PG_LAUNCH_P(E, P)              \
