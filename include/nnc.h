@@ -215,7 +215,7 @@ typedef enum {
                                single launch); 0: one kernel per stage */
   NNC_OPT_PREFILL_TILE = 4, /* block tile of the large-block prompt GEMMs: -1 (default) chosen from
                                each launch's size; 0: 64 x 128, 1: 256 x 128, 2: 128 x 128, 3: 64 x 64,
-                               4: 192 x 128, 5: 256 x 256 (rows x operand columns).  Same k order per output
+                               4: 192 x 128, 5: 256 x 256, 6: 192 x 256 (rows x operand columns).  Same k order per output
                                element in all, hence bit-identical results, except that the 64-row
                                tiles split the k range of a short block's narrow projections over
                                several workgroups (partial sums added in a fixed order) */

@@ -927,7 +927,7 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
       return NNC_OK;
     case NNC_OPT_PERSISTENT: m->opt_persistent = value != 0; return NNC_OK;
     case NNC_OPT_PREFILL_TILE:
-      if (value < -1 || value > 5) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic) or 0 .. 5");
+      if (value < -1 || value > 6) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic) or 0 .. 6");
       m->opt_prefill_tile = value;
       return NNC_OK;
     case NNC_OPT_TAIL_OVERLAP: m->opt_tail_overlap = value != 0; return NNC_OK;

@@ -28,9 +28,10 @@ Machine machine_mi355x(int cus) {
   m.pg_c1 = 0.0241;
   m.pg_c0 = 0.110;
   m.pg_solo = 0.78;
-  // the 256 x 256 tile, one workgroup per CU: 0.83 us per k step (64 matrix-core instructions per
+  // the 256 x 256 tile, one workgroup per CU: 0.77 us per k step (64 matrix-core instructions per
   // wave), measured on the 8B gate|up and down projections at 4080 tokens
-  m.pg_big = 0.83;
+  m.pg_big = 0.77;
+  m.pg_big12 = 0.62;  // the 192 x 256 tile (48 per wave): the 8B QKV projection
   // the register-ring kernel of the 64-row tiles: 0.26 us per k step with 4 matrix-core
   // instructions per wave (64 x 64), 0.37 with 8 (64 x 128)
   m.rg_c1 = 0.0275;
@@ -49,7 +50,7 @@ struct PgTile {
 // every block tile the prompt GEMM kernels are instantiated for, plus one that is not (256 x 256
 // with two workgroups per CU: it shows the capacity constraints at work and is never chosen)
 const PgTile kPgTiles[] = {{1, 16, 8, true, 2}, {4, 12, 8, true, 2}, {2, 8, 8, true, 2}, {0, 4, 8, false, 2},
-                           {3, 4, 4, false, 2}, {5, 16, 16, true, 1}, {-1, 16, 16, true, 2}};
+                           {3, 4, 4, false, 2}, {5, 16, 16, true, 1}, {6, 12, 16, true, 1}, {-1, 16, 16, true, 2}};
 }  // namespace
 
 PrefillGemmPlan plan_prefill_gemm(const Machine& mc, int n_tiles, int KT, int col_tiles, int n_tokens, int pieces,
@@ -85,7 +86,7 @@ PrefillGemmPlan plan_prefill_gemm(const Machine& mc, int n_tiles, int KT, int co
       const int wgs = ceil_div(n_tiles, t.nt) * ceil_div(col_tiles, t.tt) * slices;
       const int slots = wgs_per_cu * mc.cus;
       const int full = wgs / slots, rem = wgs - full * slots;
-      const double t2 = wgs_per_cu == 1 ? mc.pg_big
+      const double t2 = wgs_per_cu == 1 ? (t.nt == 16 ? mc.pg_big : mc.pg_big12)
                         : t.lds_direct  ? mc.pg_c0 + mc.pg_c1 * wi * wj
                                         : mc.rg_c0 + mc.rg_c1 * wi * wj;
       const double t1 = mc.pg_solo * t2;

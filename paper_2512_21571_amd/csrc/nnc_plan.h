@@ -35,7 +35,7 @@ struct Machine {
   // CU: c0 + c1 * (matrix-core instructions per wave and k step) microseconds; one workgroup
   // alone on a CU takes `solo` times that
   double pg_c0, pg_c1, pg_solo;
-  double pg_big;  // microseconds per k step of the 256 x 256 tile (one workgroup per CU)
+  double pg_big, pg_big12;  // microseconds per k step of the 256 x 256 / 192 x 256 tile (one workgroup per CU)
   double rg_c0, rg_c1;  // the same regression for the register-ring kernel of the 64-row tiles
 };
 Machine machine_mi355x(int cus);
@@ -43,7 +43,7 @@ Machine machine_mi355x(int cus);
 enum { PLAN_EPI_STORE = 0, PLAN_EPI_RESID = 1, PLAN_EPI_SWIGLU = 2 };
 
 struct PrefillGemmPlan {
-  int tile;            // launch_gemm_prefill shape code (0: 64x128, 1: 256x128, 2: 128x128, 3: 64x64, 4: 192x128, 5: 256x256)
+  int tile;            // launch_gemm_prefill shape code (0: 64x128, 1: 256x128, 2: 128x128, 3: 64x64, 4: 192x128, 5: 256x256, 6: 192x256)
   int nt, tt;          // block tile in 16-row / 16-column tiles
   int k_slices;        // workgroups that share one output tile's k range
   int kts_per_split;   // k tiles per slice (0: one slice)

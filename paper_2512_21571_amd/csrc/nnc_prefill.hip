@@ -269,7 +269,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill_dl(PrefillGemmArgs a) {
   constexpr int ST = 3;
   __shared__ u32x4 As[ST][NT][64];
   __shared__ u32x4 Bs[ST][TT][64];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  // (the wave index as a scalar: the LDS addresses of the copies below are then scalar arithmetic
+  // instead of a vector op + lane read in front of every copy)
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int wn = wave >> 1, wt = wave & 1;
   const int KT = a.KT;
   const int nt0 = blockIdx.x * NT, tt0 = blockIdx.y * TT;
@@ -373,7 +375,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill_dl(PrefillGemmArgs a) {
 // compiler they get no automatic wait states: the ones the hardware needs between a write of an
 // accumulation register and a product that reads it, and between the last product and the first
 // read of its result, are put in by hand (s_nop).  The copies and fragment reads of the next
-// steps are spread between the groups of eight products (one wave per SIMD: nothing else hides
+// steps are placed one at a time behind single products (one wave per SIMD: nothing else hides
 // their issue slots); compiler barriers keep that order.
 template <class HF, int N>
 __device__ __forceinline__ void big_mfma(u32x4 a, u32x4 b) {
@@ -399,16 +401,18 @@ __device__ __forceinline__ void big_acc_zero() {
                : "n"(N), "n"(N + 1), "n"(N + 2), "n"(N + 3));
 }
 
-template <int EPI, int PIECES, class HF>
+template <int EPI, int PIECES, class HF, int NT>
 __global__ __launch_bounds__(256, 1) void k_gemm_prefill_big(PrefillGemmArgs a) {
-  constexpr int NT = 16, TT = 16, WI = 8, WJ = 8, AL = 4, BL = 4;
-  // Three LDS stages (a fourth changed nothing: the copies are bound by throughput, not latency);
-  // the fragment reads of the next step sit in the first RG = 4 groups, so that none is still
-  // outstanding when the step ends at the barrier (+2 % over two reads in each of the 8 groups).
-  constexpr int ST = 3, RG = 4;
+  // NT = 16: 256 x 256; NT = 12: 192 x 256 (96 x 128 per wave), for launches whose 256-row blocks
+  // would leave the last round of one workgroup per CU half empty
+  constexpr int TT = 16, WI = NT / 2, WJ = 8, AL = NT / 4, BL = 4;
+  // Three LDS stages (a fourth changed nothing: the copies are not bound by latency).
+  constexpr int ST = 3;
   __shared__ u32x4 As[ST][NT][64];
   __shared__ u32x4 Bs[ST][TT][64];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  // (the wave index as a scalar: the LDS addresses of the copies below are then scalar arithmetic
+  // instead of a vector op + lane read in front of every copy)
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int wn = wave >> 1, wt = wave & 1;
   const int KT = a.KT;
   // Block order.  The workgroups resident together (one per CU, 256 at a time in launch order)
@@ -479,8 +483,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_prefill_big(PrefillGemmArgs a) 
   constexpr std::integral_constant<int, 1> c1{};
   // Step kt (fragments in register set P): stage kt % ST is in registers and free, stage
   // (kt + 1) % ST must have landed, the stages after it are in flight.  Group g = copy g of step
-  // kt + ST (MORE), fragments of step kt + 1 into the other set (NEXT; spread over the first RG
-  // groups), then the eight products of row tile g.
+  // kt + ST (MORE), fragments of step kt + 1 into the other set (NEXT), interleaved with the 64 products.
   auto step = [&](auto setc, auto morec, auto nextc, int kt, int st) __attribute__((always_inline)) {
     constexpr int P = decltype(setc)::value;
     constexpr bool MORE = decltype(morec)::value, NEXT = decltype(nextc)::value;
@@ -488,21 +491,22 @@ __global__ __launch_bounds__(256, 1) void k_gemm_prefill_big(PrefillGemmArgs a) 
     else wait_steps(min(KT - kt - 2, ST - 2));
     lds_sync();
     const int nx = st == ST - 1 ? 0 : st + 1;
-    static_for<WI>([&](auto gc) __attribute__((always_inline)) {
-      constexpr int g = decltype(gc)::value;
-      if constexpr (MORE) issue1(gc, kt + ST, st);
-      if constexpr (NEXT && g < RG) {
-        constexpr int per = WI / RG;
-#pragma unroll
-        for (int q = g * per; q < (g + 1) * per; ++q) {
-          af[1 - P][q] = As[nx][wn * WI + q][lane];
-          bf[1 - P][q] = Bs[nx][wt * WJ + q][lane];
-        }
+    // One wave per SIMD: the wave's issue pointer is never more than one product ahead of the
+    // matrix core, so everything else has to fit into the 16 cycles a product runs, one
+    // instruction (or one copy: scalar add, m0, copy) at a time.  Fragment reads of step kt + 1
+    // behind the even products of the first half (none is outstanding at the barrier that ends the
+    // step), the copies of step kt + ST behind every fourth product of the second half.
+    static_for<WI * WJ>([&](auto mc) __attribute__((always_inline)) {
+      constexpr int m = decltype(mc)::value, g = m / WJ, j = m % WJ;
+      big_mfma<HF, m * 4>(af[P][g], bf[P][j]);
+      if constexpr (NEXT && m % 2 == 0 && m < 2 * (WI + WJ)) {
+        constexpr int q = m / 2;
+        if constexpr (q < WI) af[1 - P][q] = As[nx][wn * WI + q][lane];
+        else bf[1 - P][q - WI] = Bs[nx][wt * WJ + q - WI][lane];
       }
-      asm volatile("" ::: "memory");
-      static_for<WJ>([&](auto jc) __attribute__((always_inline)) {
-        big_mfma<HF, (g * WJ + decltype(jc)::value) * 4>(af[P][g], bf[P][decltype(jc)::value]);
-      });
+      constexpr int M0 = WI * WJ / 2 + 1, SP = (WI * WJ - M0) / L;  // first copy slot, spacing
+      if constexpr (MORE && m >= M0 && (m - M0) % SP == 0 && (m - M0) / SP < L)
+        issue1(std::integral_constant<int, (m - M0) / SP>{}, kt + ST, st);
       asm volatile("" ::: "memory");
     });
   };
@@ -560,14 +564,15 @@ __global__ __launch_bounds__(256, 1) void k_gemm_prefill_big(PrefillGemmArgs a) 
 
 // a.t_tiles counts operand column tiles (token tiles x pieces).  shape: 0 = 64 x 128 block
 // tiles, 1 = 256 x 128, 2 = 128 x 128, 3 = 64 x 64, 4 = 192 x 128, 5 = 256 x 256 (one workgroup
-// per CU, 128 x 128 per wave: 16 fragments from LDS per 64 matrix-core instructions).
+// per CU, 128 x 128 per wave: 16 fragments from LDS per 64 matrix-core instructions), 6 = 192 x 256
+// (the same kernel with 96 x 128 per wave).
 hipError_t launch_gemm_prefill(hipStream_t s, bool f16, int epi, const PrefillGemmArgs& a, int pieces, int shape) {
   if (a.n_tiles <= 0 || a.t_tiles <= 0 || a.KT <= 0 || (pieces != 1 && pieces != 2) || a.t_tiles % pieces ||
-      shape < 0 || shape > 5)
+      shape < 0 || shape > 6)
     return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU && a.n_tiles % 4) return hipErrorInvalidValue;
-  const int NT = (shape == 1 || shape == 5) ? 16 : shape == 4 ? 12 : shape == 2 ? 8 : 4,
-            TT = shape == 3 ? 4 : shape == 5 ? 16 : 8;
+  const int NT = (shape == 1 || shape == 5) ? 16 : (shape == 4 || shape == 6) ? 12 : shape == 2 ? 8 : 4,
+            TT = shape == 3 ? 4 : shape >= 5 ? 16 : 8;
   int ksplit = 1;
   if (a.kts_per_split > 0) {  // only the small tiles, only the residual epilogue, and a place for the partials
     if ((shape != 0 && shape != 3) || epi != EPI_RESID || !a.part) return hipErrorInvalidValue;
@@ -580,7 +585,8 @@ hipError_t launch_gemm_prefill(hipStream_t s, bool f16, int epi, const PrefillGe
     else if (shape == 1) k_gemm_prefill_dl<E, 16, 8, P, HF><<<grid, 256, 0, s>>>(a);   \
     else if (shape == 2) k_gemm_prefill_dl<E, 8, 8, P, HF><<<grid, 256, 0, s>>>(a);    \
     else if (shape == 4) k_gemm_prefill_dl<E, 12, 8, P, HF><<<grid, 256, 0, s>>>(a);   \
-    else if (shape == 5) k_gemm_prefill_big<E, P, HF><<<grid, 256, 0, s>>>(a);         \
+    else if (shape == 5) k_gemm_prefill_big<E, P, HF, 16><<<grid, 256, 0, s>>>(a);     \
+    else if (shape == 6) k_gemm_prefill_big<E, P, HF, 12><<<grid, 256, 0, s>>>(a);     \
     else k_gemm_prefill<E, 4, 4, P, HF><<<grid, 256, 0, s>>>(a);                       \
   } while (0)
 #define PG_LAUNCH_P(E, P)              \

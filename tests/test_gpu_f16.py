@@ -94,17 +94,18 @@ def test_f16_large_block_prompts(nnc, n):
     assert int(ng.item()) == n2
 
 
-def test_f16_block_tile_256x256_equals_256x128(nnc):
-    """The 256 x 256 block tile of the prompt GEMMs (accumulators named in inline assembly, its own
-    binary16 instruction string) gives the bits of the 256 x 128 tile."""
-    print("case: binary16 large-block prompt, forced 256 x 256 block tile", flush=True)
+@pytest.mark.parametrize("tile", [5, 6])
+def test_f16_block_tile_256x256_equals_256x128(nnc, tile):
+    """The 256 x 256 / 192 x 256 block tiles of the prompt GEMMs (accumulators named in inline
+    assembly, its own binary16 instruction string) give the bits of the 256 x 128 tile."""
+    print(f"case: binary16 large-block prompt, forced block tile {tile}", flush=True)
     shape = SMALL_G4_F16
     g, _ = _pair(nnc, shape, 1, 720, False)
     toks = synth.tokens(700, shape.vocab, stream=77)
     g.set_option(nnc.OPT_PREFILL_TILE, 1)
     ref, _ = g.prefill(0, toks)
     g.kv_reset(0)
-    g.set_option(nnc.OPT_PREFILL_TILE, 5)
+    g.set_option(nnc.OPT_PREFILL_TILE, tile)
     lg, _ = g.prefill(0, toks)
     assert np.array_equal(lg.cpu().numpy(), ref.cpu().numpy())
 
