@@ -348,7 +348,8 @@ def main() -> int:
     if gemm:
         roofline_pg = {"bound": "mfma", "kernel": PG_KERNELS, "achieved": round(prefill_gemm_tflops, 1),
                        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                       "frac": round(prefill_gemm_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                       "frac": round(prefill_gemm_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                       "traffic": counter_traffic(args.workload, PG_KERNELS, S),
                        "launches": gemm[0]["launches"],
                        "avg_launch_us": round(gemm[0]["total_ms"] * 1e3 / gemm[0]["launches"], 2),
                        "flops_per_launch": round(gemm[0]["flops"] / gemm[0]["launches"])}
