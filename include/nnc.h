@@ -32,6 +32,10 @@
  *   g_final [H]                                   if has_embed_and_head
  *   lm_head [V,H]                                 if has_embed_and_head && !tied_lm_head
  * with Dq = n_q_heads*head_dim, Dkv = n_kv_heads*head_dim.
+ * blob_dtype NNC_W8 (weight-only 8 bits; the paper has no low-bit format: this extends its
+ * 16-bit runs of Section 4 towards the memory wall it names in Sections 4.1 and 4.2): every
+ * matrix of a layer is [out, in] signed bytes q followed by [out] fp32 scales s, the weight being
+ * s[row] * q[row][col]; embed and lm_head are bf16; hidden and ffn are multiples of 64.
  */
 #ifndef NNC_H_
 #define NNC_H_
@@ -56,7 +60,12 @@ typedef enum {
   NNC_E_STATE = 7    /* call not valid for this model (e.g. token API on a hidden-state model) */
 } nnc_status;
 
-typedef enum { NNC_F32 = 0, NNC_BF16 = 1, NNC_F16 = 2 /* IEEE binary16, the paper's F16 (Section 4, setup) */ } nnc_dtype;
+typedef enum {
+  NNC_F32 = 0,
+  NNC_BF16 = 1,
+  NNC_F16 = 2, /* IEEE binary16, the paper's F16 (Section 4, setup) */
+  NNC_W8 = 3   /* blob_dtype only: bytes with one scale per output row in the layers, bf16 elsewhere */
+} nnc_dtype;
 
 typedef struct {
   uint32_t struct_bytes; /* = sizeof(nnc_config) */
@@ -70,7 +79,13 @@ typedef struct {
                                   fp32 accumulation (activations enter the matrix cores as 16-bit
                                   pieces of that format).  Must equal blob_dtype, or be a 16-bit type
                                   with an NNC_F32 blob (weights are then rounded to nearest even
-                                  once, at create). */
+                                  once, at create).  An NNC_W8 blob computes in NNC_BF16: the decode
+                                  GEMMs stream the bytes, widen them to bf16 exactly in registers and
+                                  multiply the row sums by the scales; bf16 KV cache, embedding and
+                                  LM head.  Such a model runs its prompts in chunks of 21 tokens through
+                                  the same GEMMs and batch-1 decode through the per-stage kernels (the
+                                  large-block prompt kernels and the resident decode kernel take 16-bit
+                                  weights only). */
   uint32_t max_batch;          /* number of KV slots */
   uint32_t max_seq;            /* positions per slot */
 } nnc_config;

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
 F32, BF16, F16 = 0, 1, 2
+W8 = 3   # blob format only: see from_shape
 ROUND_KV, ROUND_GEMM_IN, ROUND_ATTN_QP, ROUND_HEAD_IN, ROUND_F16 = 1, 2, 4, 8, 16
 
 
@@ -227,8 +228,61 @@ class OracleModel:
         return np.frombuffer(buf, dtype=np.float64).reshape(n, dkv).copy()
 
 
+def _widen_w8_blob(shape, blob: np.ndarray) -> np.ndarray:
+    """Weight-only 8-bit blob -> the fp32 blob of the same model.
+
+    The format (canonical order as for the other dtypes): a matrix of a layer is rows x cols signed
+    bytes q followed by rows fp32 scales s; embedding / LM head are bf16; gains fp32.  The model's
+    weight is w[r, c] = s[r] * q[r, c] -- this line is the oracle's statement of what the 8-bit
+    format means.  The scales carry 8 significant bits and |q| <= 127, so the product is exact in
+    fp32 and the fp64 forward pass below sees exactly the weights the format defines.
+    """
+    H, d = shape.hidden, shape.head_dim
+    Dq, Dkv, F, V = shape.n_q_heads * d, shape.n_kv_heads * d, shape.ffn, shape.vocab
+    src = np.ascontiguousarray(blob).view(np.uint8)
+    parts, off = [], 0
+
+    def take(n, dt):
+        nonlocal off
+        a = np.frombuffer(src, dtype=dt, count=n, offset=off)
+        off += n * np.dtype(dt).itemsize
+        return a
+
+    def bf16(n):
+        return (take(n, np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+    def w8(rows, cols):
+        q = take(rows * cols, np.int8).reshape(rows, cols)
+        s = take(rows, np.float32)
+        w = q.astype(np.float64) * s.astype(np.float64)[:, None]
+        w32 = w.astype(np.float32)
+        assert np.array_equal(w32.astype(np.float64), w), "scale * byte is not exact in fp32"
+        return w32.reshape(-1)
+
+    if shape.has_embed_and_head:
+        parts.append(bf16(V * H))
+    for _ in range(shape.n_layers):
+        parts += [take(H, np.float32), w8(Dq, H), w8(Dkv, H), w8(Dkv, H), take(d, np.float32), take(d, np.float32),
+                  w8(H, Dq), take(H, np.float32), w8(F, H), w8(F, H), w8(H, F)]
+    if shape.has_embed_and_head:
+        parts.append(take(H, np.float32))
+        if not shape.tied_lm_head:
+            parts.append(bf16(V * H))
+    assert off == src.size, "8-bit blob size does not match the shape"
+    return np.concatenate(parts).view(np.uint8)
+
+
 def from_shape(shape, blob: np.ndarray, max_batch: int, max_seq: int) -> OracleModel:
-    """Build from an object with the shape field names used throughout (hidden, n_layers, ...)."""
+    """Build from an object with the shape field names used throughout (hidden, n_layers, ...).
+    A weight-only 8-bit blob (dtype W8) is widened to fp32 first (exactly: _widen_w8_blob)."""
+    if shape.dtype == W8:
+        blob = _widen_w8_blob(shape, blob)
+        return OracleModel(hidden=shape.hidden, n_layers=shape.n_layers, n_q_heads=shape.n_q_heads,
+                           n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
+                           vocab=shape.vocab, has_embed_and_head=shape.has_embed_and_head,
+                           tied_lm_head=shape.tied_lm_head, blob_dtype=F32,
+                           max_batch=max_batch, max_seq=max_seq, rms_eps=shape.rms_eps,
+                           rope_theta=shape.rope_theta, blob=blob)
     return OracleModel(hidden=shape.hidden, n_layers=shape.n_layers, n_q_heads=shape.n_q_heads,
                        n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
                        vocab=shape.vocab, has_embed_and_head=shape.has_embed_and_head,

@@ -13,6 +13,7 @@ from . import _build
 
 OK, E_ARG, E_CONFIG, E_BLOB, E_NOMEM, E_KV_FULL, E_DEVICE, E_STATE = range(8)
 F32, BF16, F16 = 0, 1, 2
+W8 = 3   # blob dtype only (weight-only 8 bits); computes in BF16
 OPT_GRAPH, OPT_PREFILL_EXACT, OPT_PERSISTENT, OPT_STAGE_TRACE, OPT_PREFILL_TILE, OPT_SPIN_LIMIT = 0, 1, 2, 3, 4, 5
 OPT_PREFILL_ATTN = 6
 OPT_FUSE_QK = 7
@@ -124,7 +125,7 @@ def make_config(shape, max_batch: int, max_seq: int, compute_dtype: int | None =
     return NncConfig(ctypes.sizeof(NncConfig), shape.hidden, shape.n_layers, shape.n_q_heads,
                      shape.n_kv_heads, shape.head_dim, shape.ffn, shape.vocab, shape.rms_eps,
                      shape.rope_theta, int(shape.has_embed_and_head), int(shape.tied_lm_head),
-                     shape.dtype, shape.dtype if compute_dtype is None else compute_dtype,
+                     shape.dtype, (BF16 if shape.dtype == W8 else shape.dtype) if compute_dtype is None else compute_dtype,
                      max_batch, max_seq)
 
 

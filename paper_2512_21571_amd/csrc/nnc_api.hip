@@ -39,6 +39,8 @@ nnc_status fail(nnc_status st, const char* fmt, ...) {
 struct LayerW {
   float *g_in = nullptr, *g_q = nullptr, *g_k = nullptr, *g_post = nullptr;
   void *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wd = nullptr;
+  // weight-only 8-bit models: per-row scales in packed row order (else NULL)
+  float *sqkv = nullptr, *so = nullptr, *sgu = nullptr, *sd = nullptr;
   void *kc = nullptr, *vc = nullptr;
 };
 
@@ -148,6 +150,10 @@ struct nnc_model {
   uint32_t V() const { return c.vocab; }
   size_t esz() const { return f32 ? 4 : 2; }
   int ktile() const { return f32 ? 16 : 32; }
+  bool w8 = false;  // the layers' matrices are signed bytes with per-row scales (blob_dtype NNC_W8)
+  // bytes per weight and k per weight tile of the layers' matrices (embedding / LM head: esz, ktile)
+  size_t wsz() const { return w8 ? 1 : esz(); }
+  int wktile() const { return w8 ? 64 : ktile(); }
 };
 
 namespace {
@@ -166,9 +172,12 @@ nnc_status check_config(const nnc_config* c) {
   if (c->hidden % 32 || c->ffn % 32) return fail(NNC_E_CONFIG, "hidden and ffn must be multiples of 32");
   if (c->has_embed_and_head && (c->vocab == 0 || c->vocab % 16))
     return fail(NNC_E_CONFIG, "vocab must be a positive multiple of 16");
-  if (c->blob_dtype > NNC_F16 || c->compute_dtype > NNC_F16)
+  if (c->blob_dtype > NNC_W8 || c->compute_dtype > NNC_F16)
     return fail(NNC_E_CONFIG, "unknown dtype");
-  if (c->blob_dtype != NNC_F32 && c->blob_dtype != c->compute_dtype)
+  if (c->blob_dtype == NNC_W8) {
+    if (c->compute_dtype != NNC_BF16) return fail(NNC_E_CONFIG, "a weight-only 8-bit blob computes in bf16");
+    if (c->hidden % 64 || c->ffn % 64) return fail(NNC_E_CONFIG, "8-bit weights need hidden and ffn to be multiples of 64");
+  } else if (c->blob_dtype != NNC_F32 && c->blob_dtype != c->compute_dtype)
     return fail(NNC_E_CONFIG, "a 16-bit blob must be in the compute dtype (an fp32 blob is rounded once at create)");
   if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return fail(NNC_E_CONFIG, "bad rms_eps / rope_theta");
   if (c->max_batch > 4096 || c->max_seq > (1u << 20)) return fail(NNC_E_CONFIG, "max_batch / max_seq too large");
@@ -181,6 +190,9 @@ uint64_t blob_bytes_of(const nnc_config* c) {
                  Dkv = (uint64_t)c->n_kv_heads * d, F = c->ffn, V = c->vocab;
   const uint64_t w = c->blob_dtype == NNC_F32 ? 4 : 2;
   uint64_t total = (uint64_t)c->n_layers * (w * (Dq * H + 2 * Dkv * H + H * Dq + 3 * F * H) + 4 * (2 * H + 2 * d));
+  if (c->blob_dtype == NNC_W8)  // bytes + one fp32 scale per output row (embedding / LM head stay 16-bit)
+    total = (uint64_t)c->n_layers * ((Dq * H + 2 * Dkv * H + H * Dq + 3 * F * H) + 4 * (Dq + 2 * Dkv + H + 2 * F + H) +
+                                     4 * (2 * H + 2 * d));
   if (c->has_embed_and_head) {
     total += w * V * H + 4 * H;
     if (!c->tied_lm_head) total += w * V * H;
@@ -299,8 +311,10 @@ int skinny_rt_choices(int dt, int epi, bool wide = true) {
 void plan_skinny(const nnc_model* m, GemmArgs& a, int epi, int max_slices, bool wide) {
   if (!m->opt_planner) return;
   const Machine mc = machine_mi355x(m->n_cus);
-  const SkinnyGemmPlan pl =
-      plan_skinny_gemm(mc, a.n_tiles, a.KT, a.ncols, a.nseq, skinny_rt_choices(m->dt, epi, wide), max_slices);
+  // byte weights: a weight tile meets two operand k tiles, and the kernel has the fp32 models' row tile counts
+  const bool w8 = a.wscale != nullptr;
+  const SkinnyGemmPlan pl = plan_skinny_gemm(mc, a.n_tiles, a.KT, w8 ? 2 * a.ncols : a.ncols, a.nseq,
+                                             skinny_rt_choices(w8 ? (int)NNC_F32 : m->dt, epi, wide), max_slices);
   if (pl.rt <= 0) return;
   a.rt = pl.rt;
   a.kts_per_split = pl.kts_per_split;
@@ -330,11 +344,11 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
   const int H = m->H(), Dq = m->Dq(), Dkv = m->Dkv(), F = m->F(), V = m->V();
   const int nq = c.n_q_heads, nkv = c.n_kv_heads;
   const int n = p.ncols, ns = p.nsplit, nc = n * ns;
-  const double w = (double)m->esz();
-  const int KTH = H / m->ktile(), KTQ = Dq / m->ktile(), KTF = F / m->ktile();
+  const double w = (double)m->wsz(), hw = (double)m->esz();  // bytes per weight: layers, embedding / LM head
+  const int KTH = H / m->wktile(), KTQ = Dq / m->wktile(), KTF = F / m->wktile();
   const int Nqkv = Dq + 2 * Dkv;
 
-  if (p.tokens) RUN(FAM_EMBED, n * H * w, 0, launch_embed(s, dt, m->embed, H, m->st, n, m->x));
+  if (p.tokens) RUN(FAM_EMBED, n * H * hw, 0, launch_embed(s, dt, m->embed, H, m->st, n, m->x));
 
   const ColMap cm{m->st, 0, 0, 0};
   // k-slice partials of the previous projection still to be added to x
@@ -365,7 +379,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
     int qkv_slices = 1;
     {
       GemmArgs a{};
-      a.Wp = L.wqkv; a.n_tiles = Nqkv / 16; a.KT = KTH; a.kts_per_split = KTH;
+      a.Wp = L.wqkv; a.wscale = L.sqkv; a.n_tiles = Nqkv / 16; a.KT = KTH; a.kts_per_split = KTH;
       a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->qkv; a.ldo = Nqkv; a.split_stride = (long)n * Nqkv;
       // the fused attention kernel adds k-slice partial sums itself; every other consumer wants full sums
@@ -378,14 +392,14 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       RUN(FAM_QKROPE, n * Nqkv * 4.0, 0,
           launch_qknorm_rope_append(s, dt, m->qkv, nq, nkv, L.g_q, L.g_k, c.rms_eps, m->rope, cm, n,
                                     L.kc, L.vc, c.max_batch, c.max_seq, m->qsplit, nullptr, 0));
-    RUN(FAM_ATTN, p.kv_rows * 2.0 * Dkv * w, p.kv_rows * 4.0 * Dq,
+    RUN(FAM_ATTN, p.kv_rows * 2.0 * Dkv * hw, p.kv_rows * 4.0 * Dq,
         launch_attn_partial(s, dt, m->qkv, m->qsplit, nq, nkv, L.kc, L.vc, c.max_batch, c.max_seq, cm, n,
                             p.grid_chunks, m->partial, m->max_chunks, fuse ? &fz : nullptr, p.one_slot));
     RUN(FAM_COMBINE, 0, 0,
         launch_attn_combine(s, dt, m->partial, m->max_chunks, nq, cm, n, m->Ap, nc, ns));
     {
       GemmArgs a{};
-      a.Wp = L.wo; a.n_tiles = H / 16; a.KT = KTQ; a.kts_per_split = pick_kts(a.n_tiles, KTQ);
+      a.Wp = L.wo; a.wscale = L.so; a.n_tiles = H / 16; a.KT = KTQ; a.kts_per_split = pick_kts(a.n_tiles, KTQ);
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
       plan_skinny(m, a, EPI_STORE, MAX_KSPLIT, p.decode);
@@ -398,7 +412,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
           launch_rmsnorm_pack(s, dt, m->x, H, m->rpart, pending, pstride, L.g_post, H, c.rms_eps, n, m->Xp, nc, ns));
     {
       GemmArgs a{};
-      a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = KTH; a.kts_per_split = KTH;
+      a.Wp = L.wgu; a.wscale = L.sgu; a.n_tiles = 2 * F / 16; a.KT = KTH; a.kts_per_split = KTH;
       a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.packed_out = m->Ap; a.NC_out = nc; a.nsplit_out = ns;
       plan_skinny(m, a, EPI_SWIGLU, 1, p.decode);
@@ -406,7 +420,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
     }
     {
       GemmArgs a{};
-      a.Wp = L.wd; a.n_tiles = H / 16; a.KT = KTF; a.kts_per_split = pick_kts(a.n_tiles, KTF);
+      a.Wp = L.wd; a.wscale = L.sd; a.n_tiles = H / 16; a.KT = KTF; a.kts_per_split = pick_kts(a.n_tiles, KTF);
       a.Xp = m->Ap; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->rpart; a.ldo = H; a.split_stride = pstride;
       plan_skinny(m, a, EPI_STORE, MAX_KSPLIT, p.decode);
@@ -431,11 +445,12 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
           launch_rmsnorm_pack(s, dt, m->x + (size_t)p.head_col0 * H, H, m->rpart + (size_t)p.head_col0 * H, pending,
                               pstride, m->g_final, H, c.rms_eps, hn, m->Xp, hc, ns));
     GemmArgs a{};
-    a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = KTH; a.kts_per_split = KTH;
+    const int KTV = H / m->ktile();  // the LM head is in the model's 16-bit format also when the layers are bytes
+    a.Wp = m->lm_head; a.n_tiles = V / 16; a.KT = KTV; a.kts_per_split = KTV;
     a.Xp = m->Xp; a.NC = hc; a.ncols = hc; a.nsplit = ns; a.nseq = hn;
     a.out = p.logits; a.ldo = p.logits_ld; a.step_ptr = p.step_ptr; a.step_stride = p.step_stride;
     plan_skinny(m, a, EPI_STORE, 1, p.decode);
-    RUN(FAM_GEMM_HEAD, (double)V * H * w, 2.0 * V * H * hn, launch_gemm(s, dt, EPI_STORE, a));
+    RUN(FAM_GEMM_HEAD, (double)V * H * hw, 2.0 * V * H * hn, launch_gemm(s, dt, EPI_STORE, a));
     if (p.next)
       RUN(FAM_ARGMAX, hn * V * 4.0, 0,
           launch_argmax(s, p.logits, p.logits_ld, V, hn, p.step_ptr, p.step_stride, m->am_val, m->am_idx,
@@ -654,6 +669,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
   m->c = *cfg;
   m->f32 = cfg->compute_dtype == NNC_F32;
   m->dt = (int)cfg->compute_dtype;
+  m->w8 = cfg->blob_dtype == NNC_W8;
   m->device = device;
   m->n_cus = prop.multiProcessorCount;
   if (dev) {
@@ -666,7 +682,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
   m->opt_prefill_exact = 0;
   const nnc_config& c = m->c;
   const size_t H = m->H(), Dq = m->Dq(), Dkv = m->Dkv(), F = m->F(), V = m->V(), d = c.head_dim;
-  const size_t w = m->esz(), bw = c.blob_dtype == NNC_F32 ? 4 : 2;
+  const size_t w = m->esz(), bw = c.blob_dtype == NNC_F32 ? 4 : 2, lw = m->wsz();
   const bool src_f32 = c.blob_dtype == NNC_F32;
   hipStream_t s = m->stream;
 
@@ -708,6 +724,34 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     return launch_repack(s, src_f32, m->dt, stage, dst, (int)rows, (int)K, tile_stride, tile_offset);
   };
 
+  // A matrix of a layer.  Byte-weight blobs: rows x K signed bytes, then rows fp32 scales, which go
+  // into `scales` (host, packed row order: tile nt of the sub-matrix becomes tile
+  // nt * tile_stride + tile_offset) and are uploaded once per fused matrix.
+  std::vector<float> scales;
+  auto upload_layer_matrix = [&](void* dst, size_t rows, size_t K, int tile_stride, int tile_offset) -> hipError_t {
+    if (!m->w8) return upload_matrix(dst, rows, K, tile_stride, tile_offset);
+    hipError_t e = hipMemcpyAsync(stage, bp, rows * K, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return e;
+    bp += rows * K;
+    for (size_t nt = 0; nt < rows / 16; ++nt) {
+      const size_t dt_ = (nt * tile_stride + tile_offset) * 16;
+      if (scales.size() < dt_ + 16) scales.resize(dt_ + 16, 0.f);
+      memcpy(&scales[dt_], bp + nt * 64, 64);
+    }
+    bp += rows * 4;
+    return launch_repack_w8(s, stage, dst, (int)rows, (int)K, tile_stride, tile_offset);
+  };
+  auto upload_scales = [&](float*& dst) -> hipError_t {
+    if (!m->w8) return hipSuccess;
+    dst = static_cast<float*>(dev_alloc(m, scales.size() * 4));
+    if (!dst) return hipErrorOutOfMemory;
+    // synchronous: `scales` is reused for the next matrix
+    hipError_t e = hipMemcpyAsync(dst, scales.data(), scales.size() * 4, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    scales.clear();
+    return e;
+  };
+
   if (c.has_embed_and_head) {
     ALLOC(m->embed, void*, V * H * w);
     TRY_OR_BAIL(upload_matrix(m->embed, V, H, 1, 0));
@@ -715,20 +759,24 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
   m->L.resize(c.n_layers);
   for (auto& L : m->L) {
     TRY_OR_BAIL(upload_gain(L.g_in, H));
-    ALLOC(L.wqkv, void*, (Dq + 2 * Dkv) * H * w);
-    TRY_OR_BAIL(upload_matrix(L.wqkv, Dq, H, 1, 0));
-    TRY_OR_BAIL(upload_matrix(L.wqkv, Dkv, H, 1, (int)(Dq / 16)));
-    TRY_OR_BAIL(upload_matrix(L.wqkv, Dkv, H, 1, (int)((Dq + Dkv) / 16)));
+    ALLOC(L.wqkv, void*, (Dq + 2 * Dkv) * H * lw);
+    TRY_OR_BAIL(upload_layer_matrix(L.wqkv, Dq, H, 1, 0));
+    TRY_OR_BAIL(upload_layer_matrix(L.wqkv, Dkv, H, 1, (int)(Dq / 16)));
+    TRY_OR_BAIL(upload_layer_matrix(L.wqkv, Dkv, H, 1, (int)((Dq + Dkv) / 16)));
+    TRY_OR_BAIL(upload_scales(L.sqkv));
     TRY_OR_BAIL(upload_gain(L.g_q, d));
     TRY_OR_BAIL(upload_gain(L.g_k, d));
-    ALLOC(L.wo, void*, H * Dq * w);
-    TRY_OR_BAIL(upload_matrix(L.wo, H, Dq, 1, 0));
+    ALLOC(L.wo, void*, H * Dq * lw);
+    TRY_OR_BAIL(upload_layer_matrix(L.wo, H, Dq, 1, 0));
+    TRY_OR_BAIL(upload_scales(L.so));
     TRY_OR_BAIL(upload_gain(L.g_post, H));
-    ALLOC(L.wgu, void*, 2 * F * H * w);
-    TRY_OR_BAIL(upload_matrix(L.wgu, F, H, 2, 0));
-    TRY_OR_BAIL(upload_matrix(L.wgu, F, H, 2, 1));
-    ALLOC(L.wd, void*, H * F * w);
-    TRY_OR_BAIL(upload_matrix(L.wd, H, F, 1, 0));
+    ALLOC(L.wgu, void*, 2 * F * H * lw);
+    TRY_OR_BAIL(upload_layer_matrix(L.wgu, F, H, 2, 0));
+    TRY_OR_BAIL(upload_layer_matrix(L.wgu, F, H, 2, 1));
+    TRY_OR_BAIL(upload_scales(L.sgu));
+    ALLOC(L.wd, void*, H * F * lw);
+    TRY_OR_BAIL(upload_layer_matrix(L.wd, H, F, 1, 0));
+    TRY_OR_BAIL(upload_scales(L.sd));
     const size_t kv_bytes = (size_t)c.max_batch * c.n_kv_heads * c.max_seq * d * w;
     ALLOC(L.kc, void*, kv_bytes);
     ALLOC(L.vc, void*, kv_bytes);
@@ -779,8 +827,9 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     ALLOC(m->am_val, float*, MAX_COLS * 64 * 4);
     ALLOC(m->am_idx, int32_t*, MAX_COLS * 64 * 4);
   }
-  // prompt pass on large token blocks (bf16 token models)
-  if (!m->f32 && c.has_embed_and_head) {
+  // prompt pass on large token blocks (16-bit token models; byte-weight models run their prompts
+  // through the chunk path, whose GEMM widens the bytes)
+  if (!m->f32 && !m->w8 && c.has_embed_and_head) {
     uint32_t pb = (c.max_seq + 127) / 128 * 128;
     if (pb > 4096) pb = 4096;
     m->pb_max = pb;
@@ -816,8 +865,8 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     m->tail_counters = static_cast<uint32_t*>(cnt);
   }
 
-  // resident decode kernel: per-layer pointer table, exchange buffers
-  if (!m->f32 && c.has_embed_and_head && c.n_layers > 0 && H <= 4096 && (c.n_q_heads / c.n_kv_heads) % 2 == 0 &&
+  // resident decode kernel: per-layer pointer table, exchange buffers (16-bit weights only)
+  if (!m->f32 && !m->w8 && c.has_embed_and_head && c.n_layers > 0 && H <= 4096 && (c.n_q_heads / c.n_kv_heads) % 2 == 0 &&
       c.n_q_heads / c.n_kv_heads <= 16) {
     const int qkv_tiles = (int)((Dq + 2 * Dkv) / 16);
     m->mk_nwg = prop.multiProcessorCount < qkv_tiles ? prop.multiProcessorCount : qkv_tiles;

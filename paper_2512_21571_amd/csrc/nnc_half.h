@@ -16,6 +16,7 @@ enum Dtype { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
 
 struct Bf16 {
   static constexpr int kDtype = DT_BF16;
+  static constexpr bool kW8 = false;  // the weights of a GEMM are in this format too
   // A small value keeps fewer and fewer significant bits below the smallest normal number;
   // bf16 has the exponent range of fp32, so operands need no scaling before they are split.
   static constexpr bool kNarrowRange = false;
@@ -44,6 +45,7 @@ struct Bf16 {
 
 struct Fp16 {
   static constexpr int kDtype = DT_F16;
+  static constexpr bool kW8 = false;
   // binary16 normals end at 2^-14: an operand vector of small magnitude (an embedding row is
   // ~0.02) must be brought to unit scale before it is split into pieces.
   static constexpr bool kNarrowRange = true;
@@ -63,6 +65,21 @@ struct Fp16 {
   static __device__ __forceinline__ float hi(uint32_t w) { return widen(w >> 16); }
   static __device__ __forceinline__ f32x4_t mfma(u32x4_v a, u32x4_v b, f32x4_t c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(vec8, a), __builtin_bit_cast(vec8, b), c, 0, 0, 0);
+  }
+};
+
+// bf16 activations and matrix-core products, weights stored as signed bytes with one fp32 scale
+// per output row (weight-only 8-bit): a byte is widened to bf16 exactly (|q| <= 127 needs 7 bits)
+// right before the product, the scale multiplies the row's sum in the epilogue.
+struct Bf16W8 : Bf16 {
+  static constexpr bool kW8 = true;
+  // 8 signed bytes (two words) -> 8 bf16 in operand order
+  static __device__ __forceinline__ u32x4_v widen8(uint32_t lo, uint32_t hi) {
+    auto two = [](uint32_t w, int sh) __attribute__((always_inline)) {
+      const float a = (float)(int)(int8_t)(w >> sh), b = (float)(int)(int8_t)(w >> (sh + 8));
+      return pack2(a, b);
+    };
+    return u32x4_v{two(lo, 0), two(lo, 16), two(hi, 0), two(hi, 16)};
   }
 };
 

@@ -74,6 +74,11 @@ struct NormTail {
 
 struct GemmArgs {
   const void* Wp;
+  // weight-only 8-bit matrices: one fp32 scale per output row, in the row order of the packed
+  // tiles; NULL for matrices in the model's element type.  A k tile is then 16 rows x 64 k (1 KiB
+  // of bytes, the lane's 8 values of k sub-tile 0 then its 8 of sub-tile 1) and KT, kts_per_split
+  // count those; the operand has two of its 32-wide k tiles per weight tile.
+  const float* wscale;
   int n_tiles;        // output rows / 16
   int KT;             // k tiles in the matrix
   int kts_per_split;  // k tiles per blockIdx.y slice
@@ -107,6 +112,9 @@ struct KernelCtx;  // profiling hook, defined in nnc_api.hip
 // All launchers enqueue on `s` and return the launch error code.
 hipError_t launch_repack(hipStream_t s, bool src_f32, int dst_dt, const void* src, void* dst,
                          int rows, int K, int tile_stride, int tile_offset);
+// row-major signed bytes [rows, K] -> byte tiles of 16 rows x 64 k (K a multiple of 64)
+hipError_t launch_repack_w8(hipStream_t s, const void* src, void* dst, int rows, int K, int tile_stride,
+                            int tile_offset);
 hipError_t launch_set_state(hipStream_t s, ColState* st, int ncols, const int32_t* tok,
                             const uint32_t* slot, const uint32_t* pos, uint32_t step);
 hipError_t launch_embed(hipStream_t s, int dt, const void* Ep, int H, const ColState* st,

@@ -116,6 +116,33 @@ hipError_t launch_repack(hipStream_t s, bool src_f32, int dst_dt, const void* sr
   return hipGetLastError();
 }
 
+// Weight-only 8-bit matrices: a tile is 16 rows x 64 k; lane (row c16, group g) holds the 8 bytes
+// k = 64 kt + 8 g .. + 7 and then the 8 bytes k = 64 kt + 32 + 8 g .. + 7, i.e. its share of the
+// two 32-wide matrix-core k tiles the byte tile covers.
+__global__ __launch_bounds__(256) void k_repack_w8(const int8_t* __restrict__ src, uint4* __restrict__ dst, int rows,
+                                                   int K, int tile_stride, int tile_offset) {
+  const int KT = K / 64;
+  const size_t total = (size_t)(rows / 16) * KT * 64;
+  const size_t v = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (v >= total) return;
+  const int lane = (int)(v & 63);
+  const size_t t = v >> 6;
+  const int kt = (int)(t % KT);
+  const int nt = (int)(t / KT);
+  const int8_t* p = src + ((size_t)nt * 16 + (lane & 15)) * K + (size_t)kt * 64 + (lane >> 4) * 8;
+  const uint2 a = *reinterpret_cast<const uint2*>(p), b = *reinterpret_cast<const uint2*>(p + 32);
+  dst[((size_t)(nt * tile_stride + tile_offset) * KT + kt) * 64 + lane] = make_uint4(a.x, a.y, b.x, b.y);
+}
+
+hipError_t launch_repack_w8(hipStream_t s, const void* src, void* dst, int rows, int K, int tile_stride,
+                            int tile_offset) {
+  if (rows % 16 || K % 64) return hipErrorInvalidValue;
+  const size_t total = (size_t)(rows / 16) * (K / 64) * 64;
+  k_repack_w8<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(static_cast<const int8_t*>(src), static_cast<uint4*>(dst),
+                                                              rows, K, tile_stride, tile_offset);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // column state
 // ---------------------------------------------------------------------------
@@ -438,6 +465,8 @@ __device__ __forceinline__ void gemm_norm_tail(const NormTail& t, const float* p
 // of each activation column and stores / accumulates / applies SwiGLU.
 template <bool F32, int NCB, int RT, int EPI, int U, class HF>
 __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
+  constexpr bool W8 = !F32 && HF::kW8;  // byte weights: two operand k tiles per weight tile
+  constexpr int XT = W8 ? 2 : 1;
   constexpr int RC = RT % 2 == 0 ? 2 : 1;  // row tiles per round of the cross-wave reduction
   __shared__ float red[4][RC][NCB][256];
   // the wave index as a scalar: every k-tile address below is then a scalar base plus a
@@ -475,7 +504,7 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
   const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<u32x4*>(Wv + tile0 * KT * 64), 0, RT * KT * 1024, 0x00020000);
   const __amdgpu_buffer_rsrc_t xres =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4*>(Xv), 0, KT * 64 * a.NC, 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4*>(Xv), 0, KT * XT * 64 * a.NC, 0x00020000);
   const uint32_t wvoff = (uint32_t)lane * 16u;
   uint32_t xvoff[NCB];  // operand fragment of this lane within a k tile's 4 x NC groups of 16 bytes
 #pragma unroll
@@ -484,21 +513,33 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
   const int first = kt_begin + wave;
   const int n_mine = first < kt_end ? (kt_end - first + 3) >> 2 : 0;
   const int last_kt = first + 4 * (n_mine - 1);
-  u32x4 avA[U][RT], bvA[U][NCB], avB[U][RT], bvB[U][NCB];
-  auto load_tile = [&](int kt, u32x4(&av)[RT], u32x4(&bv)[NCB]) __attribute__((always_inline)) {
+  u32x4 avA[U][RT], bvA[U][XT * NCB], avB[U][RT], bvB[U][XT * NCB];
+  auto load_tile = [&](int kt, u32x4(&av)[RT], u32x4(&bv)[XT * NCB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)  // aux 2: non-temporal, each weight byte is used once per pass
       av[rt] = __builtin_amdgcn_raw_buffer_load_b128(wres, wvoff, (rt * KT + kt) * 1024, 2);
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) bv[cb] = __builtin_amdgcn_raw_buffer_load_b128(xres, xvoff[cb], kt * 64 * a.NC, 0);
+    for (int x = 0; x < XT; ++x)
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb)
+        bv[x * NCB + cb] = __builtin_amdgcn_raw_buffer_load_b128(xres, xvoff[cb], (kt * XT + x) * 64 * a.NC, 0);
   };
-  auto load_group = [&](int t0, u32x4(&av)[U][RT], u32x4(&bv)[U][NCB]) __attribute__((always_inline)) {
+  auto load_group = [&](int t0, u32x4(&av)[U][RT], u32x4(&bv)[U][XT * NCB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < U; ++u) load_tile(min(first + 4 * (t0 + u), last_kt), av[u], bv[u]);
   };
-  auto mma_tile = [&](const u32x4(&av)[RT], const u32x4(&bv)[NCB]) __attribute__((always_inline)) {
+  auto mma_tile = [&](const u32x4(&av)[RT], const u32x4(&bv)[XT * NCB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
+      if constexpr (W8) {
+        const u32x4 a0 = HF::widen8(av[rt][0], av[rt][1]), a1 = HF::widen8(av[rt][2], av[rt][3]);
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+          acc[rt][cb] = HF::mfma(a0, bv[cb], acc[rt][cb]);
+          acc[rt][cb] = HF::mfma(a1, bv[NCB + cb], acc[rt][cb]);
+        }
+        continue;
+      }
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) {
         if constexpr (F32) {
@@ -514,7 +555,7 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
       }
     }
   };
-  auto mma_group = [&](const u32x4(&av)[U][RT], const u32x4(&bv)[U][NCB]) __attribute__((always_inline)) {
+  auto mma_group = [&](const u32x4(&av)[U][RT], const u32x4(&bv)[U][XT * NCB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < U; ++u) mma_tile(av[u], bv[u]);
   };
@@ -574,8 +615,13 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
       static_assert(EPI != EPI_SWIGLU || RT % 2 == 0, "SwiGLU needs (gate, up) tile pairs");
       for (int o = tid; o < 16 * nseq; o += 256) {
         const int seq = o >> 4, row = o & 15;
-        const float gate = total(0, row, seq);
-        const float up = total(1, row, seq);
+        float gate = total(0, row, seq);
+        float up = total(1, row, seq);
+        if constexpr (W8) {
+          const float* sc = a.wscale + ((size_t)blockIdx.x * RT + ch * 2) * 16 + row;
+          gate *= sc[0];
+          up *= sc[16];
+        }
         const float act = gate / (1.0f + expf(-gate)) * up;
         const int f = (blockIdx.x * (RT / 2) + ch) * 16 + row;
         store_packed<F32, HF>(a.packed_out, a.NC_out, a.nsplit_out, seq, f, act);
@@ -587,8 +633,10 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a) {
         const int seq = rem >> 4, row = rem & 15;
         // each k slice stores its own partial sums: slice s goes to out + s * split_stride
         float* dst = out + (size_t)blockIdx.y * a.split_stride + (size_t)seq * a.ldo + (tile0 + ch * RC + r) * 16 + row;
-        if (a.tail.counter) store_through(dst, total(r, row, seq));
-        else *dst = total(r, row, seq);
+        float y = total(r, row, seq);
+        if constexpr (W8) y *= a.wscale[(tile0 + ch * RC + r) * 16 + row];
+        if (a.tail.counter) store_through(dst, y);
+        else *dst = y;
       }
     }
   }
@@ -664,6 +712,20 @@ hipError_t launch_gemm(hipStream_t s, int dt, int epi, const GemmArgs& a) {
   if (a.tail.counter && (epi != EPI_STORE || a.step_ptr || a.ldo != a.tail.H || a.tail.H != a.n_tiles * 16 ||
                          a.tail.H % 4 || a.tail.H > 8192 || !a.tail.error || (a.KT + a.kts_per_split - 1) / a.kts_per_split > 8))
     return hipErrorInvalidValue;
+  if (a.wscale) {  // byte weights, bf16 activations: row tiles 1, 2, 4 (SwiGLU: 2, 4)
+    if (dt != DT_BF16 || a.tail.counter) return hipErrorInvalidValue;
+    const int rt = a.rt > 0 ? a.rt : (epi == EPI_SWIGLU || wide ? 2 : 1);
+    if (a.n_tiles % rt) return hipErrorInvalidValue;
+    if (epi == EPI_SWIGLU) {
+      if (rt == 2) return gemm_dispatch_ncb<false, EPI_SWIGLU, 2, Bf16W8>(s, a);
+      if (rt == 4) return gemm_dispatch_ncb<false, EPI_SWIGLU, 4, Bf16W8>(s, a);
+      return hipErrorInvalidValue;
+    }
+    if (rt == 1) return gemm_dispatch_ncb<false, EPI_STORE, 1, Bf16W8>(s, a);
+    if (rt == 2) return gemm_dispatch_ncb<false, EPI_STORE, 2, Bf16W8>(s, a);
+    if (rt == 4) return gemm_dispatch_ncb<false, EPI_STORE, 4, Bf16W8>(s, a);
+    return hipErrorInvalidValue;
+  }
   if (a.rt > 0) {  // row tiles per workgroup chosen by the caller (the analytic planner)
     if (a.n_tiles % a.rt || (epi == EPI_SWIGLU && a.rt % 2)) return hipErrorInvalidValue;
     if (epi == EPI_SWIGLU) {

@@ -25,6 +25,9 @@ WEIGHT_SEED = 251221571
 INPUT_SEED = 251221572
 
 F32, BF16, F16 = 0, 1, 2
+# weight-only 8-bit: the matrices of the layers as signed bytes with one fp32 scale per output row,
+# embedding / LM head in bf16; activations and KV cache as for BF16
+W8 = 3
 
 
 def build(force: bool = False) -> str:
@@ -46,6 +49,8 @@ def _load():
         lib.synth_normal_bf16.argtypes = [u64, u64, u64, u64, dbl, vp]
         lib.synth_normal_f16.argtypes = [u64, u64, u64, u64, dbl, vp]
         lib.synth_uniform_i32.argtypes = [u64, u64, u64, u64, ctypes.c_uint32, vp]
+        lib.synth_normal_w8.argtypes = [u64, u64, u64, u64, dbl, vp, vp]
+        lib.synth_normal_w8.restype = None
         lib.synth_raw.argtypes = [u64, u64, u64]
         lib.synth_raw.restype = u64
         for f in (lib.synth_normal_f32, lib.synth_normal_bf16, lib.synth_normal_f16, lib.synth_uniform_i32):
@@ -102,6 +107,8 @@ def blob_layout(s: ModelShape):
 
     Matrices are row-major [out, in] in the blob dtype; gains are always fp32.
     The ordinal of an entry is its tensor id for the generator.
+    W8 blobs: a matrix of a layer is rows x cols signed bytes followed by rows fp32 scales (the
+    weight is scale[row] * byte); embedding and LM head are bf16.
     """
     out = []
     if s.has_embed_and_head:
@@ -128,6 +135,10 @@ def blob_layout(s: ModelShape):
     return out
 
 
+def _layer_matrix(name: str) -> bool:
+    return name[0] == "l" and name[1].isdigit()
+
+
 def blob_offsets(s: ModelShape):
     """name -> (byte offset, shape, numpy dtype) and the total byte count."""
     esz = 4 if s.dtype == F32 else 2
@@ -137,6 +148,10 @@ def blob_offsets(s: ModelShape):
         if is_gain:
             table[name] = (off, shape, np.float32)
             off += 4 * n
+        elif s.dtype == W8 and _layer_matrix(name):
+            table[name] = (off, shape, np.int8)
+            table[name + ".scale"] = (off + n, (shape[0],), np.float32)
+            off += n + 4 * shape[0]
         else:
             table[name] = (off, shape, np.float32 if s.dtype == F32 else np.uint16)
             off += esz * n
@@ -164,6 +179,8 @@ def make_blob(s: ModelShape, seed: int = WEIGHT_SEED, weight_std: float = 0.02,
                 g += 1.0
             else:
                 g[:] = 1.0
+        elif s.dtype == W8 and _layer_matrix(name):
+            lib.synth_normal_w8(seed, tid, shape[0], shape[1], weight_std, base + off, base + off + n)
         elif s.dtype == F32:
             lib.synth_normal_f32(seed, tid, 0, n, weight_std, base + off)
         elif s.dtype == F16:

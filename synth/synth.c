@@ -86,6 +86,39 @@ void synth_normal_f16(uint64_t seed, uint64_t tensor, uint64_t first, uint64_t n
     out[i] = store_f16((float)(scale * std_normal(draw(seed, tensor, first + (uint64_t)i))));
 }
 
+/* Weight-only 8-bit storage of a [rows, cols] matrix drawn as N(0, scale^2): per output row one
+ * scale s (a bf16-representable fp32: the row's largest magnitude / 127 rounded up to 8 significant
+ * bits, 1.0 for an all-zero row) and cols signed bytes q = nearest integer of w / s (ties to even),
+ * so that the stored weight is exactly s * q with |q| <= 127.  A storage format of the inputs, like
+ * the 16-bit ones above; the forward pass that uses s * q is not here. */
+void synth_normal_w8(uint64_t seed, uint64_t tensor, uint64_t rows, uint64_t cols, double scale,
+                     int8_t *q, float *row_scale) {
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < (int64_t)rows; ++r) {
+    double amax = 0.0;
+    for (uint64_t c = 0; c < cols; ++c) {
+      const double w = scale * std_normal(draw(seed, tensor, (uint64_t)r * cols + c));
+      if (fabs(w) > amax) amax = fabs(w);
+    }
+    float s = 1.0f;
+    if (amax > 0.0) {
+      uint32_t b;
+      s = (float)(amax / 127.0);
+      memcpy(&b, &s, 4);
+      b = (b + 0xffffu) & 0xffff0000u;   /* up to the next bf16-representable value */
+      memcpy(&s, &b, 4);
+    }
+    row_scale[r] = s;
+    for (uint64_t c = 0; c < cols; ++c) {
+      const double w = scale * std_normal(draw(seed, tensor, (uint64_t)r * cols + c));
+      double v = nearbyint(w / (double)s);
+      if (v > 127.0) v = 127.0;
+      if (v < -127.0) v = -127.0;
+      q[(uint64_t)r * cols + c] = (int8_t)v;
+    }
+  }
+}
+
 /* Uniform integers in [0, bound): floor(u * bound) with u the high 32 bits / 2^32. */
 void synth_uniform_i32(uint64_t seed, uint64_t tensor, uint64_t first, uint64_t n,
                        uint32_t bound, int32_t *out) {

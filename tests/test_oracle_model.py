@@ -160,14 +160,19 @@ def test_gqa_equals_mha_with_repeated_kv_heads(tiny_shape):
     assert np.allclose(la, lb, rtol=1e-12, atol=1e-14)
 
 
-def test_conventions_against_library_qwen3_in_fp64(tiny_shape):
+@pytest.mark.parametrize("fmt", ["f32", "w8"])
+def test_conventions_against_library_qwen3_in_fp64(tiny_shape, fmt):
+    """fmt w8: the same cross-check on a weight-only 8-bit blob.  The library model gets
+    scale[row] * byte taken from the blob through the generator's offset table (not through the
+    oracle's own parser), so a misplaced scale, a scale applied per column, or matrices read in
+    the wrong order in the oracle's widening would show as a disagreement."""
     torch = pytest.importorskip("torch")
     tr = pytest.importorskip("transformers")
     try:
         from transformers import Qwen3Config, Qwen3ForCausalLM
     except Exception as e:  # pragma: no cover
         pytest.skip(f"library Qwen3 class unavailable: {e}")
-    s = tiny_shape
+    s = tiny_shape if fmt == "f32" else tiny_shape.scaled(dtype=synth.W8)
     blob = synth.make_blob(s, weight_std=0.25, gain_jitter=0.2)
     cfg = Qwen3Config(vocab_size=s.vocab, hidden_size=s.hidden, intermediate_size=s.ffn,
                       num_hidden_layers=s.n_layers, num_attention_heads=s.n_q_heads,
@@ -178,7 +183,13 @@ def test_conventions_against_library_qwen3_in_fp64(tiny_shape):
     if getattr(cfg, "rope_parameters", None) is not None:
         cfg.rope_parameters = {"rope_type": "default", "rope_theta": s.rope_theta}
     model = Qwen3ForCausalLM(cfg).to(torch.float64).eval()
-    get = lambda n: torch.from_numpy(synth.blob_tensor(s, blob, n).astype(np.float64))
+    def get(n):
+        t = synth.blob_tensor(s, blob, n)
+        if t.dtype == np.int8:
+            return torch.from_numpy(t.astype(np.float64) * synth.blob_tensor(s, blob, n + ".scale").astype(np.float64)[:, None])
+        if t.dtype == np.uint16:
+            return torch.from_numpy(synth.bf16_bits_to_f32(t).astype(np.float64))
+        return torch.from_numpy(t.astype(np.float64))
     sd = {"model.embed_tokens.weight": get("embed"), "model.norm.weight": get("g_final"),
           "lm_head.weight": get("embed")}
     names = {"g_in": "input_layernorm.weight", "wq": "self_attn.q_proj.weight",

@@ -84,3 +84,28 @@ def test_f16_blob_is_rounded_fp32_sample(tiny_shape):
             assert np.array_equal(b, a.astype(np.float16).view(np.uint16)), scale
     w = synth.f16_bits_to_f32(h).astype(np.float64)
     assert abs(w.std() - 0.02) < 2e-3
+
+
+def test_w8_blob_is_a_rowwise_quantised_sample(tiny_shape):
+    """Weight-only 8-bit blobs: bytes + one scale per output row, next to the fp32 draw of the same
+    (seed, tensor, index): scales have 8 significant bits, every row uses the full byte range, the
+    stored weight is within half a step of the draw, embedding and gains are as in a bf16 blob."""
+    s8 = tiny_shape.scaled(dtype=synth.W8)
+    blob = synth.make_blob(s8)
+    table, total = synth.blob_offsets(s8)
+    assert blob.nbytes == total
+    f32 = synth.make_blob(tiny_shape)
+    for name in ("l0.wq", "l1.wdown", "l0.wgate"):
+        q = synth.blob_tensor(s8, blob, name)
+        sc = synth.blob_tensor(s8, blob, name + ".scale")
+        w = synth.blob_tensor(tiny_shape, f32, name).astype(np.float64)
+        assert q.dtype == np.int8 and sc.dtype == np.float32 and sc.shape == (q.shape[0],)
+        assert np.all(sc.view(np.uint32) & 0xffff == 0) and np.all(sc > 0)        # bf16-representable
+        assert np.abs(q.astype(np.int32)).max() <= 127
+        assert np.all(np.abs(q.astype(np.int32)).max(axis=1) >= 126)            # scale = row maximum / 127, rounded up
+        assert np.all(sc.astype(np.float64) * 127 >= np.abs(w).max(axis=1) - 1e-9)
+        err = np.abs(q.astype(np.float64) * sc.astype(np.float64)[:, None] - w)
+        assert np.all(err <= 0.5 * sc.astype(np.float64)[:, None] + 1e-8)        # nearest step (the fp32 draw is rounded)
+    sb = tiny_shape.scaled(dtype=synth.BF16)
+    assert np.array_equal(synth.blob_tensor(s8, blob, "embed"), synth.blob_tensor(sb, synth.make_blob(sb), "embed"))
+    assert np.all(synth.blob_tensor(s8, blob, "l1.g_post") == 1.0)
