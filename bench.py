@@ -40,14 +40,21 @@ WORKLOADS = {
     "qwen3-4b-bf16-b1-c2048-d128": ("qwen3-4b", 1, 2048, 128),
     "qwen3-4b-bf16-b8-c2048-d128": ("qwen3-4b", 8, 2048, 128),
     "qwen3-8b-bf16-b16-c4096-d128": ("qwen3-8b", 16, 4096, 128),
+    # weight-only 8-bit layers (bytes + one scale per output row), bf16 activations / cache / LM head;
+    # prompts run in 21-token chunks through the decode GEMMs, so the context is kept short
+    "qwen3-8b-w8-b16-c512-d128": ("qwen3-8b-w8", 16, 512, 128),
+    "qwen3-8b-w8-b16-c4096-d128": ("qwen3-8b-w8", 16, 4096, 128),
+    "qwen3-8b-bf16-b16-c512-d128": ("qwen3-8b", 16, 512, 128),
 }
 
 
 def algorithmic_bytes_per_decode_step(shape, ctx_mean: float, batch: int = 1) -> float:
     """Every weight element once per step, every cached K/V element of every sequence once per step."""
     w = 4 if shape.dtype == 0 else 2
+    lw = 1 if shape.dtype == 3 else w                       # weight-only 8-bit layers (their scales: 4 bytes per row)
     per_layer = (shape.dq + 2 * shape.dkv) * shape.hidden + shape.hidden * shape.dq + 3 * shape.ffn * shape.hidden
-    weights = w * (shape.n_layers * per_layer + shape.vocab * shape.hidden)
+    scales = 4 * (shape.dq + 2 * shape.dkv + 2 * shape.hidden + 2 * shape.ffn) if shape.dtype == 3 else 0
+    weights = shape.n_layers * (lw * per_layer + scales) + w * shape.vocab * shape.hidden
     kv = shape.n_layers * 2 * shape.dkv * w * ctx_mean * batch
     return float(weights + kv)
 
@@ -401,14 +408,15 @@ def main() -> int:
             cpu["one_thread_tokens_per_s"] = round(n1 / (time.perf_counter() - c1), 3)
             oracle.set_threads(threads)
 
-    dname = {0: "f32", 1: "bf16", 2: "f16"}[shape.dtype]
+    dname = {0: "f32", 1: "bf16", 2: "f16", 3: "bf16"}[shape.dtype]   # byte weights compute in bf16
     out = {
         "metric": "decode tokens/s + achieved HBM GB/s fraction; prefill tokens/s + MFMA util",
         "value": round(decode_tok_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / args.steps, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dname, "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "prompt_tokens": T, "decode_steps": S,
-                   "weights": f"N(0,0.02) seeded, {dname}", "kv_cache": dname},
+                   "weights": "N(0,0.02) seeded, " + ("8-bit with per-row scales (layers), bf16 (embedding, LM head)"
+                                                      if shape.dtype == 3 else dname), "kv_cache": dname},
         "decode_ms_per_token": round(decode_ms_per_token, 5),
         "decode_hbm_frac_step": round(step_bytes / (decode_ms_per_token * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
         "decode_algorithmic_bytes_per_step": round(step_bytes),

@@ -311,10 +311,10 @@ int skinny_rt_choices(int dt, int epi, bool wide = true) {
 void plan_skinny(const nnc_model* m, GemmArgs& a, int epi, int max_slices, bool wide) {
   if (!m->opt_planner) return;
   const Machine mc = machine_mi355x(m->n_cus);
-  // byte weights: a weight tile meets two operand k tiles, and the kernel has the fp32 models' row tile counts
+  // byte weights: a weight tile meets two operand k tiles
   const bool w8 = a.wscale != nullptr;
   const SkinnyGemmPlan pl = plan_skinny_gemm(mc, a.n_tiles, a.KT, w8 ? 2 * a.ncols : a.ncols, a.nseq,
-                                             skinny_rt_choices(w8 ? (int)NNC_F32 : m->dt, epi, wide), max_slices);
+                                             skinny_rt_choices(m->dt, epi, wide), max_slices);
   if (pl.rt <= 0) return;
   a.rt = pl.rt;
   a.kts_per_split = pl.kts_per_split;

@@ -712,18 +712,22 @@ hipError_t launch_gemm(hipStream_t s, int dt, int epi, const GemmArgs& a) {
   if (a.tail.counter && (epi != EPI_STORE || a.step_ptr || a.ldo != a.tail.H || a.tail.H != a.n_tiles * 16 ||
                          a.tail.H % 4 || a.tail.H > 8192 || !a.tail.error || (a.KT + a.kts_per_split - 1) / a.kts_per_split > 8))
     return hipErrorInvalidValue;
-  if (a.wscale) {  // byte weights, bf16 activations: row tiles 1, 2, 4 (SwiGLU: 2, 4)
+  if (a.wscale) {  // byte weights, bf16 activations
     if (dt != DT_BF16 || a.tail.counter) return hipErrorInvalidValue;
     const int rt = a.rt > 0 ? a.rt : (epi == EPI_SWIGLU || wide ? 2 : 1);
     if (a.n_tiles % rt) return hipErrorInvalidValue;
     if (epi == EPI_SWIGLU) {
       if (rt == 2) return gemm_dispatch_ncb<false, EPI_SWIGLU, 2, Bf16W8>(s, a);
       if (rt == 4) return gemm_dispatch_ncb<false, EPI_SWIGLU, 4, Bf16W8>(s, a);
+      if (rt == 6) return gemm_dispatch_ncb<false, EPI_SWIGLU, 6, Bf16W8>(s, a);
+      if (rt == 8) return gemm_dispatch_ncb<false, EPI_SWIGLU, 8, Bf16W8>(s, a);
       return hipErrorInvalidValue;
     }
     if (rt == 1) return gemm_dispatch_ncb<false, EPI_STORE, 1, Bf16W8>(s, a);
     if (rt == 2) return gemm_dispatch_ncb<false, EPI_STORE, 2, Bf16W8>(s, a);
+    if (rt == 3) return gemm_dispatch_ncb<false, EPI_STORE, 3, Bf16W8>(s, a);
     if (rt == 4) return gemm_dispatch_ncb<false, EPI_STORE, 4, Bf16W8>(s, a);
+    if (rt == 6) return gemm_dispatch_ncb<false, EPI_STORE, 6, Bf16W8>(s, a);
     return hipErrorInvalidValue;
   }
   if (a.rt > 0) {  // row tiles per workgroup chosen by the caller (the analytic planner)

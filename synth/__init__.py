@@ -99,6 +99,8 @@ SHAPES = {
     "qwen3-1.7b": ModelShape("qwen3-1.7b", 2048, 28, 16, 8, 128, 6144, V_QWEN3),
     "qwen3-4b": ModelShape("qwen3-4b", 2560, 36, 32, 8, 128, 9728, V_QWEN3),
     "qwen3-8b": ModelShape("qwen3-8b", 4096, 36, 32, 8, 128, 12288, V_QWEN3, tied_lm_head=False),
+    # weight-only 8-bit layers (not a format of the paper: a step beyond its 16-bit runs)
+    "qwen3-8b-w8": ModelShape("qwen3-8b-w8", 4096, 36, 32, 8, 128, 12288, V_QWEN3, tied_lm_head=False, dtype=W8),
 }
 
 

@@ -129,3 +129,13 @@ def test_w8_planner_off_and_error_paths(nnc):
                            vocab=64, dtype=synth.W8)
     with pytest.raises(nnc.NncError):                                 # hidden is not a multiple of 64
         nnc.Model(bad, synth.make_blob(bad), 1, 16)
+
+
+def test_w8_8b_layer_shape_batch16(nnc):
+    """The 8B layer shape, vocabulary and batch at a depth the fp64 oracle follows (1 layer): slot 0
+    with a 600-token context, the other 15 slots short ragged ones; every slot's prompt pass and
+    two batched decode steps against the oracle, then batch-1 steps on the long slot.  The real tile
+    counts, k slices and row tiles per workgroup of the byte-weight GEMMs are the ones launched."""
+    from test_gpu_configs import _sampled_depth
+    print("case: 8-bit weights, 8B layer shape, 1 layer, context 600, batch 16 and 1", flush=True)
+    _sampled_depth(nnc, "qwen3-8b-w8", 1, 600, 16, 2, "w8-8b")
