@@ -40,8 +40,7 @@ WORKLOADS = {
     "qwen3-4b-bf16-b1-c2048-d128": ("qwen3-4b", 1, 2048, 128),
     "qwen3-4b-bf16-b8-c2048-d128": ("qwen3-4b", 8, 2048, 128),
     "qwen3-8b-bf16-b16-c4096-d128": ("qwen3-8b", 16, 4096, 128),
-    # weight-only 8-bit layers (bytes + one scale per output row), bf16 activations / cache / LM head;
-    # prompts run in 21-token chunks through the decode GEMMs, so the context is kept short
+    # weight-only 8-bit layers (bytes + one scale per output row), bf16 activations / cache / LM head
     "qwen3-8b-w8-b16-c512-d128": ("qwen3-8b-w8", 16, 512, 128),
     "qwen3-8b-w8-b16-c4096-d128": ("qwen3-8b-w8", 16, 4096, 128),
     "qwen3-8b-bf16-b16-c512-d128": ("qwen3-8b", 16, 512, 128),

@@ -82,10 +82,10 @@ typedef struct {
                                   once, at create).  An NNC_W8 blob computes in NNC_BF16: the decode
                                   GEMMs stream the bytes, widen them to bf16 exactly in registers and
                                   multiply the row sums by the scales; bf16 KV cache, embedding and
-                                  LM head.  Such a model runs its prompts in chunks of 21 tokens through
-                                  the same GEMMs and batch-1 decode through the per-stage kernels (the
-                                  large-block prompt kernels and the resident decode kernel take 16-bit
-                                  weights only). */
+                                  LM head.  Prompt blocks widen each matrix (exactly) into a scratch
+                                  matrix of bf16 tiles first and scale the rows in the GEMM's epilogue;
+                                  batch-1 decode runs through the per-stage kernels (the resident decode
+                                  kernel takes 16-bit weights only). */
   uint32_t max_batch;          /* number of KV slots */
   uint32_t max_seq;            /* positions per slot */
 } nnc_config;

@@ -101,6 +101,7 @@ struct nnc_model {
   float *pb_x = nullptr, *pb_qkv = nullptr;
   float* pb_part = nullptr;                 // k-slice partial sums of short blocks' O / down projections
   void *pb_fa = nullptr, *pb_fb = nullptr;  // fragment-order bf16 operands: K = H, K = max(Dq, F)
+  void* pb_w = nullptr;  // byte-weight models: the matrix of the next prompt GEMM, widened to bf16 tiles
   int32_t* pb_tok = nullptr;
   void* pb_vt = nullptr;  // transposed V copy of the slot being prefilled
   uint32_t pb_vt_stride = 0;
@@ -827,9 +828,9 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     ALLOC(m->am_val, float*, MAX_COLS * 64 * 4);
     ALLOC(m->am_idx, int32_t*, MAX_COLS * 64 * 4);
   }
-  // prompt pass on large token blocks (16-bit token models; byte-weight models run their prompts
-  // through the chunk path, whose GEMM widens the bytes)
-  if (!m->f32 && !m->w8 && c.has_embed_and_head) {
+  // prompt pass on large token blocks (16-bit token models; byte-weight models widen the matrix
+  // of each GEMM into a scratch buffer first)
+  if (!m->f32 && c.has_embed_and_head) {
     uint32_t pb = (c.max_seq + 127) / 128 * 128;
     if (pb > 4096) pb = 4096;
     m->pb_max = pb;
@@ -840,6 +841,7 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     ALLOC(m->pb_fa, void*, frag_rows * H * 2);
     ALLOC(m->pb_fb, void*, frag_rows * std::max(Dq, F) * 2);
     ALLOC(m->pb_tok, int32_t*, (size_t)pb * 4);
+    if (m->w8) ALLOC(m->pb_w, void*, std::max(std::max(Dq + 2 * Dkv, 2 * F) * H, H * std::max(Dq, F)) * 2);
     // k-slice partials of the narrow projections of short blocks (up to PB_SPLIT_MAX - 1 buffers)
     ALLOC(m->pb_part, float*, (size_t)(PB_SPLIT_MAX - 1) * std::min<size_t>(pb, PB_SPLIT_TOKENS) * H * 4);
     // transposed V copy of one slot: [kv head][128][positions, padded to a multiple of 32];
@@ -1094,6 +1096,17 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
   };
   int pending = 0;  // partial buffers of the previous projection still to be added to pb_x
   const double w = 2.0, T = n;
+  // byte-weight models: the GEMM's matrix is widened to bf16 tiles in a scratch buffer (exact), and
+  // the GEMM's epilogue applies the row scales
+  auto weights_of = [&](PrefillGemmArgs& a, const void* Wp, const float* scale, int rows, int K) -> nnc_status {
+    a.Wp = Wp;
+    if (m->w8) {
+      RUN(FAM_MISC, (double)rows * K * 3.0, 0, launch_widen_w8(s, Wp, m->pb_w, rows / 16, K / 64));
+      a.Wp = m->pb_w;
+      a.wscale = scale;
+    }
+    return NNC_OK;
+  };
   HIP_TRY(hipMemcpyAsync(m->pb_tok, tokens, (size_t)n * 4, hipMemcpyHostToDevice, s));
   RUN(FAM_EMBED, T * H * w, 0, launch_embed_rows(s, f16, m->embed, H, m->pb_tok, (int)n, m->pb_x));
   for (uint32_t li = 0; li < c.n_layers; ++li) {
@@ -1101,7 +1114,8 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
     RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, f16, m->pb_x, m->pb_part, pending, part_stride, L.g_in, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
     {
       PrefillGemmArgs a{};
-      a.Wp = L.wqkv; a.n_tiles = Nqkv / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
+      if (nnc_status st_ = weights_of(a, L.wqkv, L.sqkv, Nqkv, H)) return st_;
+      a.n_tiles = Nqkv / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
       a.out = m->pb_qkv; a.ldo = Nqkv;
       RUN(FAM_PGEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * T, launch_gemm_prefill(s, f16, EPI_STORE, a, pieces, plan_gemm(a, EPI_STORE, nullptr)));
     }
@@ -1128,7 +1142,8 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
     }
     {
       PrefillGemmArgs a{};
-      a.Wp = L.wo; a.n_tiles = H / 16; a.KT = Dq / 32; a.Xf = m->pb_fb; a.t_tiles = ct;
+      if (nnc_status st_ = weights_of(a, L.wo, L.so, H, Dq)) return st_;
+      a.n_tiles = H / 16; a.KT = Dq / 32; a.Xf = m->pb_fb; a.t_tiles = ct;
       a.out = m->pb_x; a.ldo = H;
       const int shape = plan_gemm(a, EPI_RESID, &pending);
       RUN(FAM_PGEMM_O, (double)H * Dq * w, 2.0 * H * Dq * T, launch_gemm_prefill(s, f16, EPI_RESID, a, pieces, shape));
@@ -1136,13 +1151,15 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
     RUN(FAM_NORM, T * H * 6.0, 0, launch_rmsnorm_frag(s, f16, m->pb_x, m->pb_part, pending, part_stride, L.g_post, H, c.rms_eps, (int)n, tt, pieces, m->pb_fa));
     {
       PrefillGemmArgs a{};
-      a.Wp = L.wgu; a.n_tiles = 2 * F / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
+      if (nnc_status st_ = weights_of(a, L.wgu, L.sgu, 2 * F, H)) return st_;
+      a.n_tiles = 2 * F / 16; a.KT = H / 32; a.Xf = m->pb_fa; a.t_tiles = ct;
       a.packed_out = m->pb_fb;
       RUN(FAM_PGEMM_GU, 2.0 * F * H * w, 4.0 * F * H * T, launch_gemm_prefill(s, f16, EPI_SWIGLU, a, pieces, plan_gemm(a, EPI_SWIGLU, nullptr)));
     }
     {
       PrefillGemmArgs a{};
-      a.Wp = L.wd; a.n_tiles = H / 16; a.KT = F / 32; a.Xf = m->pb_fb; a.t_tiles = ct;
+      if (nnc_status st_ = weights_of(a, L.wd, L.sd, H, F)) return st_;
+      a.n_tiles = H / 16; a.KT = F / 32; a.Xf = m->pb_fb; a.t_tiles = ct;
       a.out = m->pb_x; a.ldo = H;
       const int shape = plan_gemm(a, EPI_RESID, &pending);
       RUN(FAM_PGEMM_D, (double)H * F * w, 2.0 * H * F * T, launch_gemm_prefill(s, f16, EPI_RESID, a, pieces, shape));

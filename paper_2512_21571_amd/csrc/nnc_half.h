@@ -55,6 +55,11 @@ struct Fp16 {
   typedef float fvec2 __attribute__((ext_vector_type(2)));
   // the hardware conversion rounds to nearest even, keeps subnormals, overflows to infinity
   static __device__ __forceinline__ uint32_t bits(float f) {
+    // What is converted is the value as rounded to fp32.  Left visible, a product that made f is
+    // folded into the conversion (v_fma_mixlo_f16: one rounding of the exact product instead of
+    // two) for some elements of an unrolled loop and not for others, differently in every
+    // instantiation, and kernels that promise the same bits stop agreeing.
+    asm("" : "+v"(f));
     return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
   }
   static __device__ __forceinline__ float widen(uint32_t b) {

@@ -162,6 +162,9 @@ hipError_t launch_attn_combine(hipStream_t s, int dt, const float* partial, int 
 // written as bf16 in fragment order (k = f, k tiles = n_tiles / 2 / 2) into packed_out.
 struct PrefillGemmArgs {
   const void* Wp;
+  // weight-only 8-bit layers: Wp holds the bytes widened to 16 bits (launch_widen_w8) and the
+  // epilogue multiplies every output row by its scale (packed row order); NULL otherwise
+  const float* wscale = nullptr;
   int n_tiles, KT;
   const void* Xf;
   int t_tiles;
@@ -176,6 +179,9 @@ struct PrefillGemmArgs {
   long part_stride = 0;
 };
 hipError_t launch_gemm_prefill(hipStream_t s, bool f16, int epi, const PrefillGemmArgs& a, int pieces, int shape);
+// packed byte tiles (n_tiles x KT8 of 16 rows x 64 k) -> bf16 tiles of 16 rows x 32 k in the same tile order
+// (exact: |byte| <= 127), the operand the block-tile prompt GEMMs copy into LDS
+hipError_t launch_widen_w8(hipStream_t s, const void* src, void* dst, int n_tiles, int KT8);
 // x[rows, H] += part[0] + ... + part[nparts-1] (written back), then RMSNorm of rows 0..n_rows-1
 // as `pieces` bf16 per value in fragment order; rows n_rows .. 16 * token_tiles - 1 of the
 // operand are zero-filled.

@@ -62,8 +62,12 @@ __device__ __forceinline__ void static_for(F&& f) {
 // of the wave's row tiles nt_first + i for column tile `ct` (token tile ct / PIECES).
 // accumulator element e of lane l: row (l / 16) * 4 + e of the row tile, operand column l % 16.
 template <int EPI, int WI, int PIECES, class HF>
-__device__ __forceinline__ void pg_epilogue_col(const PrefillGemmArgs& a, const f32x4 (&v)[WI], int nt_first, int ct,
-                                                int lane, int kslice) {
+__device__ __forceinline__ void pg_epilogue_col_impl(const PrefillGemmArgs& a, const f32x4 (&v)[WI], int nt_first, int ct,
+                                                     int lane, int kslice) {
+  // Every product and sum below is rounded on its own: the block tiles promise the same bits, and
+  // left free the compiler contracts e.g. the last product inside expf with the "1 +" that follows
+  // in one tile's instantiation and not in another's.
+#pragma clang fp contract(off)
   const int c16 = lane & 15, g = lane >> 4;
   const int tt = ct / PIECES;        // token tile
   const size_t t = (size_t)tt * 16 + c16;
@@ -113,6 +117,28 @@ __device__ __forceinline__ void pg_epilogue_col(const PrefillGemmArgs& a, const 
       }
       *dst = o;
     }
+  }
+}
+
+template <int EPI, int WI, int PIECES, class HF>
+__device__ __forceinline__ void pg_epilogue_col(const PrefillGemmArgs& a, const f32x4 (&v)[WI], int nt_first, int ct,
+                                                int lane, int kslice) {
+  if (a.wscale) {
+    // byte weights: the sums are over the bytes; the row's scale makes them the products.  The
+    // product is rounded on its own: left free, the compiler fuses it with the residual add in
+    // one instantiation and not in another, and the block tiles stop giving the same bits.
+#pragma clang fp contract(off)
+    const int g = lane >> 4;
+    f32x4 sv[WI];
+#pragma unroll
+    for (int i = 0; i < WI; ++i) {
+      const int nt = min(nt_first + i, a.n_tiles - 1);
+      const float4 sc = *reinterpret_cast<const float4*>(a.wscale + (size_t)nt * 16 + g * 4);
+      sv[i] = f32x4{v[i][0] * sc.x, v[i][1] * sc.y, v[i][2] * sc.z, v[i][3] * sc.w};
+    }
+    pg_epilogue_col_impl<EPI, WI, PIECES, HF>(a, sv, nt_first, ct, lane, kslice);
+  } else {
+    pg_epilogue_col_impl<EPI, WI, PIECES, HF>(a, v, nt_first, ct, lane, kslice);
   }
 }
 
@@ -560,6 +586,27 @@ __global__ __launch_bounds__(256, 1) void k_gemm_prefill_big(PrefillGemmArgs a) 
     });
     if (ct < a.t_tiles) pg_epilogue_col<EPI, WI, PIECES, HF>(a, v, nt0 + wn * WI, ct, lane, 0);
   });
+}
+
+__global__ __launch_bounds__(256) void k_widen_w8(const uint4* __restrict__ src, u32x4* __restrict__ dst, int KT8,
+                                                  size_t total) {
+  const size_t v = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (v >= total) return;
+  const int lane = (int)(v & 63);
+  const size_t t = v >> 6;  // byte tile: nt * KT8 + kt8
+  const size_t nt = t / KT8, kt8 = t - nt * KT8;
+  const uint4 b = src[v];
+  u32x4* o = dst + ((nt * KT8 + kt8) * 2) * 64 + lane;
+  o[0] = Bf16W8::widen8(b.x, b.y);
+  o[64] = Bf16W8::widen8(b.z, b.w);
+}
+
+hipError_t launch_widen_w8(hipStream_t s, const void* src, void* dst, int n_tiles, int KT8) {
+  if (n_tiles <= 0 || KT8 <= 0) return hipErrorInvalidValue;
+  const size_t total = (size_t)n_tiles * KT8 * 64;
+  k_widen_w8<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(static_cast<const uint4*>(src), static_cast<u32x4*>(dst),
+                                                             KT8, total);
+  return hipGetLastError();
 }
 
 // a.t_tiles counts operand column tiles (token tiles x pieces).  shape: 0 = 64 x 128 block

@@ -66,10 +66,7 @@ def prefill_blocks(n: int, block: int = PREFILL_BLOCK):
 
 
 def oracle_prefill_like_library(o, slot, toks, shape, block: int = PREFILL_BLOCK):
-    """The oracle's prompt pass with the library's rounding points mirrored block by block.
-    (Weight-only 8-bit models run every prompt through the three-piece chunk path: nothing to mirror.)"""
-    if shape.dtype == synth.W8:
-        return o.prefill(slot, toks, oracle_flags(shape))
+    """The oracle's prompt pass with the library's rounding points mirrored block by block."""
     res = None
     for t0, nb, pieces in prefill_blocks(len(toks), block):
         res = o.prefill(slot, toks[t0:t0 + nb], oracle_flags(shape, mirrored_prefill=pieces == 1))

@@ -12,7 +12,7 @@ import pytest
 
 import oracle
 import synth
-from parity_util import oracle_flags
+from parity_util import oracle_flags, oracle_prefill_like_library, prefill_blocks
 
 pytestmark = pytest.mark.gpu
 
@@ -45,7 +45,8 @@ def _check(got, want, tight=W8_ABS_TIGHT):
 
 @pytest.mark.parametrize("shape", [SMALL_W8, SMALL_G4_W8], ids=lambda s: s.name)
 def test_w8_prefill_then_decode_matches_oracle(nnc, shape):
-    """Prompt (chunks of 21 tokens through the byte-weight GEMM) and batch-1 decode (per-stage kernels)."""
+    """Prompt (one two-piece block: the bytes widened into the scratch matrix of the block-tile GEMMs,
+    scales in their epilogue) and batch-1 decode (per-stage kernels, byte-weight GEMM)."""
     print(f"case: 8-bit weights, prefill + decode, {shape.name}", flush=True)
     g, o = _pair(nnc, shape, 2, 160)
     fl = oracle_flags(shape)
@@ -68,7 +69,45 @@ def test_w8_prefill_then_decode_matches_oracle(nnc, shape):
         got = g.kv_read(1, 0, which, 0, n).double().cpu().numpy()
         want = o.kv_rows(1, 0, which)
         ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 2.0 ** -126))) - 7)
-        assert np.all(np.abs(got - want) <= ulp * 1.001 + 5e-4)
+        # layer 1 also sees the effect of upstream one-ulp cache differences on its inputs (same
+        # allowance as the bf16 test of the cache rows)
+        assert np.all(np.abs(got - want) <= ulp * 1.001 + 3e-3)
+        assert np.mean(got != want) < 0.15
+
+
+@pytest.mark.parametrize("mode", ["blocks", "chunks"])
+@pytest.mark.parametrize("n", [300, 700])
+def test_w8_long_prompts(nnc, n, mode):
+    """Large-block prompt pass of a byte-weight model (two-piece block; single-piece block + the
+    fp32-grade tail, mirrored by the oracle), every block tile; and the 21-token chunk path."""
+    print(f"case: 8-bit weights, prompt of {n} tokens, {mode}", flush=True)
+    shape = SMALL_G4_W8
+    g, o = _pair(nnc, shape, 1, n + 16)
+    toks = synth.tokens(n, shape.vocab, stream=n)
+    if mode == "chunks":
+        g.set_option(nnc.OPT_PREFILL_EXACT, 1)
+        lg, ng = g.prefill(0, toks)
+        lo, no = o.prefill(0, toks, oracle_flags(shape))
+        _check(lg, lo)
+        assert int(ng.item()) == no
+        return
+    one_piece = any(pc == 1 for _, _, pc in prefill_blocks(n))
+    lo, no = oracle_prefill_like_library(o, 0, toks, shape)
+    ref = None
+    for tile in (-1, 1, 0, 2, 3, 4, 5, 6):
+        g.kv_reset(0)
+        g.set_option(nnc.OPT_PREFILL_TILE, tile)
+        lg, ng = g.prefill(0, toks)
+        _check(lg, lo, 1e-2 if one_piece else W8_ABS_TIGHT)
+        assert int(ng.item()) == no
+        if tile in (1, 2, 4, 5, 6):                    # same k order per output element: same bits
+            ref = lg if ref is None else ref
+            assert np.array_equal(lg.cpu().numpy(), ref.cpu().numpy()), tile
+    g.set_option(nnc.OPT_PREFILL_TILE, -1)
+    lg, ng = g.decode_step([0], [no])
+    lo, n2 = o.step_token(0, no, oracle_flags(shape))
+    _check(lg[0], lo, 1e-2 if one_piece else W8_ABS_TIGHT)
+    assert int(ng.item()) == n2
 
 
 @pytest.mark.parametrize("batch", [2, 5, 8, 16])
