@@ -74,6 +74,13 @@ def test_create_rejects_bad_arguments_before_any_device_work(nnc):
         assert nnc.blob_bytes(bad) == 0
     f32_from_bf16 = nnc.make_config(shape, 1, 64, compute_dtype=nnc.F32)
     assert _create(nnc, f32_from_bf16, blob) == nnc.E_CONFIG
+    # weight-only 8-bit blobs compute in bf16 only and need hidden / ffn in multiples of 64
+    w8 = synth.ModelShape("w8", hidden=128, n_layers=1, n_q_heads=2, n_kv_heads=1, head_dim=128, ffn=192,
+                          vocab=64, dtype=synth.W8)
+    assert nnc.blob_bytes(nnc.make_config(w8, 1, 64)) == synth.blob_offsets(w8)[1]
+    assert nnc.blob_bytes(nnc.make_config(w8, 1, 64, compute_dtype=nnc.F16)) == 0
+    assert nnc.blob_bytes(nnc.make_config(w8.scaled(hidden=96), 1, 64)) == 0
+    assert nnc.blob_bytes(nnc.make_config(w8.scaled(ffn=160), 1, 64)) == 0
 
 
 def test_null_model_arguments(nnc):
