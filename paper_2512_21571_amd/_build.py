@@ -19,6 +19,9 @@ HIPCC_FLAGS = [
     "-Wall", "-Wno-unused-command-line-argument",
     # the direct-to-LDS copies set m0 inside inline assembly and list it as clobbered
     "-Wno-inline-asm",
+    # k_gemm_prefill_big keeps its accumulators in accumulation registers it names itself in inline
+    # assembly: the compiler must never park values of its own there (it would, as a cheaper spill)
+    "-mllvm", "-amdgpu-spill-vgpr-to-agpr=0",
 ]
 
 

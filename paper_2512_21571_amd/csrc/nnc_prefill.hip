@@ -466,8 +466,10 @@ __global__ __launch_bounds__(256, 1) void k_gemm_prefill_big(PrefillGemmArgs a) 
   const char* __restrict__ W = static_cast<const char*>(a.Wp);
   const char* __restrict__ X = static_cast<const char*>(a.Xf);
 
-  // every accumulation register is this kernel's: tell the compiler once (it then allocates all
-  // 256 to the wave and keeps its own values out of them)
+  // every accumulation register is this kernel's: naming the first and the last as clobbered makes
+  // the compiler allocate all 256 to the wave.  It has no reason to touch them itself (the kernel
+  // needs about 150 ordinary registers), and the library is built with the compiler's
+  // "spill ordinary registers into accumulation registers" option off, so it never does.
   asm volatile("" ::: "a0", "a255");
   static_for<WI * WJ>([&](auto n) __attribute__((always_inline)) { big_acc_zero<decltype(n)::value * 4>(); });
 
