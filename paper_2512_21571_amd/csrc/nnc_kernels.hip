@@ -1062,10 +1062,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FUSED ? 6 :
   constexpr int VS = 66;  // row stride of the staged V chunk in 32-bit words (128 bf16 + pad)
   __shared__ uint32_t Vs[ATT_CHUNK][VS];
   constexpr int HMAX = FUSED ? 8 : 16;  // query heads per kv head the variant serves
-  __shared__ float sc[HMAX][ATT_CHUNK];  // scores per head
+  // scores per head; one word of padding per row: the four lanes that write one position of four
+  // heads then hit four banks instead of one
+  __shared__ float sc[HMAX][ATT_CHUNK + 1];
   // softmax weights as three bf16 pieces; before the scores exist the same bytes hold the query
   // pieces of the fused variant ([3][8][128]), which every wave has in registers by then
-  __shared__ __attribute__((aligned(16))) uint16_t pw[3][16][ATT_CHUNK];
+  // (fused: 8 heads at a row stride of 96 elements = 48 words, so that the 16-byte reads of four
+  // heads' rows fall on disjoint banks; the query pieces that share the bytes are [3][8][128] with
+  // the 16-byte chunks of a row rotated by the head, for the same reason)
+  constexpr int PWS = FUSED ? 96 : ATT_CHUNK;
+  __shared__ __attribute__((aligned(16))) uint16_t pwbuf[3 * 16 * ATT_CHUNK];  // = 3 * 8 * 128
+  static_assert(3 * HMAX * PWS <= 3 * 16 * ATT_CHUNK, "the weights fit the shared bytes");
+  uint16_t(*pw)[HMAX][PWS] = reinterpret_cast<uint16_t(*)[HMAX][PWS]>(&pwbuf[0]);
   __shared__ __attribute__((aligned(16))) uint16_t knew[128], vnew[128];
   __shared__ float sm_m[16], sm_l[16];
   const int kvh = blockIdx.y, col = blockIdx.z;
@@ -1098,7 +1106,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FUSED ? 6 :
     for (int ks = 0; ks < 4; ++ks)
       kf[ks] = *reinterpret_cast<const u32x4_t*>(kc + base + (size_t)jk * 128 + ks * 32 + g * 8);
   }
-  uint16_t(*qp)[8][128] = reinterpret_cast<uint16_t(*)[8][128]>(&pw[0][0][0]);
+  uint16_t(*qp)[8][128] = reinterpret_cast<uint16_t(*)[8][128]>(&pwbuf[0]);
+  // element e of head row r sits in 16-byte chunk (e / 8) ^ (4 * (r & 3)) of the row
+  auto qsw = [](int r, int e) __attribute__((always_inline)) { return (((e >> 3) ^ ((r & 3) << 2)) << 3) | (e & 7); };
   if constexpr (FUSED) {
     // roles 0 .. G-1: query heads; G: the new K row; G + 1: the new V row (same arithmetic, in
     // the same order, as k_qknorm_rope_append)
@@ -1123,8 +1133,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FUSED ? 6 :
         split_pieces<HF>(b, 3, pb);
 #pragma unroll
         for (int pc = 0; pc < 3; ++pc) {
-          qp[pc][role][lane] = (uint16_t)pa[pc];
-          qp[pc][role][lane + 64] = (uint16_t)pb[pc];
+          qp[pc][role][qsw(role, lane)] = (uint16_t)pa[pc];
+          qp[pc][role][qsw(role, lane + 64)] = (uint16_t)pb[pc];
         }
       } else {
         const uint16_t ha = (uint16_t)HF::bits(a), hb = (uint16_t)HF::bits(b);
@@ -1143,8 +1153,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FUSED ? 6 :
     }
   }
 
-  // query fragments: operand column c16 = head head0 + c16 (zero beyond G), three pieces as
-  // written by k_qknorm_rope_append
+  // query fragments: operand column c16 = head head0 + c16, three pieces as written by
+  // k_qknorm_rope_append
   u32x4_t qf[4][3];
   {
     const uint16_t* qg = qsplit + ((size_t)col * nq + head0 + min(c16, G - 1)) * 3 * 128 + g * 8;
@@ -1152,9 +1162,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FUSED ? 6 :
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int pc = 0; pc < 3; ++pc) {
-        const u32x4_t t = FUSED ? *reinterpret_cast<const u32x4_t*>(&qp[pc][min(c16, G - 1)][ks * 32 + g * 8])
+        const u32x4_t t = FUSED ? *reinterpret_cast<const u32x4_t*>(&qp[pc][min(c16, G - 1)][qsw(min(c16, G - 1), ks * 32 + g * 8)])
                                 : *reinterpret_cast<const u32x4_t*>(qg + pc * 128 + ks * 32);
-        qf[ks][pc] = c16 < G ? t : u32x4_t{0u, 0u, 0u, 0u};
+        qf[ks][pc] = t;  // columns beyond G repeat head G - 1: their results are never stored
       }
   }
 
@@ -1217,18 +1227,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FUSED ? 6 :
 #pragma unroll
       for (int pc = 0; pc < 3; ++pc) {
         const u32x4_t t = *reinterpret_cast<const u32x4_t*>(&pw[pc][min(c16, G - 1)][half * 32 + g * 8]);
-        pf[pc] = c16 < G ? t : u32x4_t{0u, 0u, 0u, 0u};
+        pf[pc] = t;
       }
 #pragma unroll
       for (int dtl = 0; dtl < 2; ++dtl) {
         const int dim = (wave * 2 + dtl) * 16 + c16;  // A-operand row c16 = this head dimension
-        uint32_t b[8];
+        // the lane's dimension is the low or the high half of a staged word: one byte permute
+        // takes that half of two positions' words at once
+        const uint32_t sel = (dim & 1) ? 0x07060302u : 0x05040100u;
+        uint32_t two[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const uint32_t two = Vs[half * 32 + g * 8 + e][dim >> 1];
-          b[e] = (dim & 1) ? (two >> 16) : (two & 0xffffu);
-        }
-        const u32x4_t vf = u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
+        for (int e = 0; e < 8; ++e) two[e] = Vs[half * 32 + g * 8 + e][dim >> 1];
+        const u32x4_t vf = u32x4_t{__builtin_amdgcn_perm(two[1], two[0], sel), __builtin_amdgcn_perm(two[3], two[2], sel),
+                                   __builtin_amdgcn_perm(two[5], two[4], sel), __builtin_amdgcn_perm(two[7], two[6], sel)};
 #pragma unroll
         for (int pc = 0; pc < 3; ++pc)
           acc[dtl] = HF::mfma(vf, pf[pc], acc[dtl]);
@@ -1350,13 +1361,14 @@ __global__ __launch_bounds__(256) void k_attn_partial_shared(const uint16_t* __r
 #pragma unroll
       for (int dtl = 0; dtl < 2; ++dtl) {
         const int dim = (wave * 2 + dtl) * 16 + c16;
-        uint32_t b[8];
+        // the lane's dimension is the low or the high half of a staged word: one byte permute
+        // takes that half of two positions' words at once
+        const uint32_t sel = (dim & 1) ? 0x07060302u : 0x05040100u;
+        uint32_t two[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const uint32_t two = Vs[half * 32 + g * 8 + e][dim >> 1];
-          b[e] = (dim & 1) ? (two >> 16) : (two & 0xffffu);
-        }
-        const u32x4_t vf = u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
+        for (int e = 0; e < 8; ++e) two[e] = Vs[half * 32 + g * 8 + e][dim >> 1];
+        const u32x4_t vf = u32x4_t{__builtin_amdgcn_perm(two[1], two[0], sel), __builtin_amdgcn_perm(two[3], two[2], sel),
+                                   __builtin_amdgcn_perm(two[5], two[4], sel), __builtin_amdgcn_perm(two[7], two[6], sel)};
 #pragma unroll
         for (int pc = 0; pc < 3; ++pc)
           acc[dtl] = HF::mfma(vf, pf[pc], acc[dtl]);
