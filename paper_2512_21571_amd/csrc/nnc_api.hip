@@ -309,13 +309,13 @@ int skinny_rt_choices(int dt, int epi, bool wide = true) {
   if (dt == (int)NNC_F32 || !wide) return epi == EPI_SWIGLU ? ((1 << 2) | (1 << 4)) : ((1 << 1) | (1 << 2) | (1 << 4));
   return epi == EPI_SWIGLU ? ((1 << 2) | (1 << 4) | (1 << 6) | (1 << 8)) : ((1 << 1) | (1 << 2) | (1 << 3) | (1 << 4) | (1 << 6));
 }
-void plan_skinny(const nnc_model* m, GemmArgs& a, int epi, int max_slices, bool wide, bool free_fold = false) {
+void plan_skinny(const nnc_model* m, GemmArgs& a, int epi, int max_slices, bool wide) {
   if (!m->opt_planner) return;
   const Machine mc = machine_mi355x(m->n_cus);
   // byte weights: a weight tile meets two operand k tiles
   const bool w8 = a.wscale != nullptr;
   const SkinnyGemmPlan pl = plan_skinny_gemm(mc, a.n_tiles, a.KT, w8 ? 2 * a.ncols : a.ncols, a.nseq,
-                                             skinny_rt_choices(m->dt, epi, wide), max_slices, free_fold);
+                                             skinny_rt_choices(m->dt, epi, wide), max_slices);
   if (pl.rt <= 0) return;
   a.rt = pl.rt;
   a.kts_per_split = pl.kts_per_split;
@@ -384,7 +384,7 @@ nnc_status run_pass(nnc_model* m, const Pass& p) {
       a.Xp = m->Xp; a.NC = nc; a.ncols = nc; a.nsplit = ns; a.nseq = n;
       a.out = m->qkv; a.ldo = Nqkv; a.split_stride = (long)n * Nqkv;
       // the fused attention kernel adds k-slice partial sums itself; every other consumer wants full sums
-      plan_skinny(m, a, EPI_STORE, fuse ? MAX_QKV_SLICES : 1, p.decode, /*free_fold=*/fuse);
+      plan_skinny(m, a, EPI_STORE, fuse ? MAX_QKV_SLICES : 1, p.decode);
       qkv_slices = (KTH + a.kts_per_split - 1) / a.kts_per_split;
       RUN(FAM_GEMM, (double)Nqkv * H * w, 2.0 * Nqkv * H * n, launch_gemm(s, dt, EPI_STORE, a));
     }

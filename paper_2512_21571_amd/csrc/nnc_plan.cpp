@@ -107,7 +107,7 @@ PrefillGemmPlan plan_prefill_gemm(const Machine& mc, int n_tiles, int KT, int co
 }
 
 SkinnyGemmPlan plan_skinny_gemm(const Machine& mc, int n_tiles, int KT, int ncols, int nseq, int rt_choices,
-                                int max_k_slices, bool free_fold) {
+                                int max_k_slices) {
   SkinnyGemmPlan best{};
   best.rt = 0;
   best.t_us = 1e30;
@@ -141,9 +141,7 @@ SkinnyGemmPlan plan_skinny_gemm(const Machine& mc, int n_tiles, int KT, int ncol
       const double t_epi = mc.skinny_round_us * rounds * per_cu;
       // partial sums: written per slice and read once more by the consumer, a norm kernel of one
       // workgroup per sequence that runs at an eighth of the streaming rate at best
-      const double fold = slices > 1 && !free_fold
-                              ? slices * (double)n_tiles * 16.0 * nseq * 4.0 * 2.0 / (mc.hbm_bytes_per_us / 8.0)
-                              : 0.0;
+      const double fold = slices > 1 ? slices * (double)n_tiles * 16.0 * nseq * 4.0 * 2.0 / (mc.hbm_bytes_per_us / 8.0) : 0.0;
       const double total = std::max(t_cu, t_hbm) + t_epi + fold + mc.skinny_launch_us;
       if (total < best.t_us * 0.999) {
         best.rt = rt; best.k_slices = slices; best.kts_per_split = kts; best.workgroups = wgs;

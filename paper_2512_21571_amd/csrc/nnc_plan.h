@@ -68,9 +68,7 @@ struct SkinnyGemmPlan {
 // Weight-streaming GEMM of decode passes: n_tiles x KT tiles of 1 KiB, ncols operand columns
 // (sequences x pieces) of elem_bytes each, nseq sequences.  rt_choices: bit r set = the kernel is
 // instantiated for r row tiles per workgroup.  max_k_slices: 1 if the consumer cannot add partials.
-// free_fold: the consumer adds the k-slice partials while it reads them anyway (the fused attention
-// kernel behind the QKV projection); otherwise a norm kernel folds them in a pass of its own.
 SkinnyGemmPlan plan_skinny_gemm(const Machine& mc, int n_tiles, int KT, int ncols, int nseq, int rt_choices,
-                                int max_k_slices, bool free_fold = false);
+                                int max_k_slices);
 
 }  // namespace nnc
