@@ -231,9 +231,13 @@ typedef enum {
   NNC_OPT_PREFILL_TILE = 4, /* block tile of the large-block prompt GEMMs: -1 (default) chosen from
                                each launch's size; 0: 64 x 128, 1: 256 x 128, 2: 128 x 128, 3: 64 x 64,
                                4: 192 x 128, 5: 256 x 256, 6: 192 x 256 (rows x operand columns).  Same k order per output
-                               element in all, hence bit-identical results, except that the 64-row
-                               tiles split the k range of a short block's narrow projections over
-                               several workgroups (partial sums added in a fixed order) */
+                               element in all, hence bit-identical results, except where the k range of
+                               a narrow (residual) projection is split over several workgroups (partial
+                               sums added in a fixed order): with a forced tile only the 64-row tiles do
+                               that by themselves, for short blocks; see NNC_OPT_PREFILL_KSLICES */
+  NNC_OPT_PREFILL_KSLICES = 13, /* with a forced NNC_OPT_PREFILL_TILE: k slices (1 .. 4) of the output and
+                               down projections of a large prompt block, 0 (default): by the rule above.
+                               Without a forced tile the tile model picks tile and slices together */
   NNC_OPT_PREFILL_ATTN = 6, /* launch shape of the large-block prompt attention: -1 (default) chosen
                                from each launch's size; else bit 0: every workgroup takes a long
                                and a short 64-token block, bit 1: two query heads per wave; results

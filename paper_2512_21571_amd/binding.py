@@ -22,6 +22,7 @@ OPT_PREFILL_BLOCK = 9
 OPT_PLANNER = 10
 OPT_FUSE_NORM = 11
 OPT_DECODE_PIECES = 12
+OPT_PREFILL_KSLICES = 13
 
 # every symbol include/nnc.h declares
 EXPORTS = [

@@ -128,6 +128,7 @@ struct nnc_model {
   bool opt_fuse_qk = true;    // decode passes: QK-norm / RoPE / append inside the attention kernel
   int opt_prefill_attn = -1;  // forced launch shape of the prompt attention, -1 = by size
   int opt_prefill_tile = -1;  // forced block tile of the large-block prompt GEMMs, -1 = by size
+  int opt_prefill_kslices = 0;  // with a forced tile: forced k slices of the residual projections, 0 = by rule
   bool opt_persistent = true;
   bool opt_fuse_norm = false;  // decode passes: the norm after an O / down projection runs in that GEMM's tail (measured: no faster)
   uint32_t* tail_counters = nullptr;  // one per GEMM launch with a norm tail in a pass (2 per layer), zeroed per pass
@@ -283,8 +284,9 @@ struct Launch {
 
 // k-slices for the narrow output projections: enough workgroups to cover the chip,
 // but at least 8 k tiles (2 per wave) per workgroup.
-// Prompt blocks of at most PB_SPLIT_TOKENS tokens may split the k range of their narrow
-// projections over up to PB_SPLIT_MAX workgroups per output tile.
+// Prompt blocks may split the k range of their narrow (residual) projections over up to
+// PB_SPLIT_MAX workgroups per output tile: any block when the tile model picks the launch, blocks of
+// at most PB_SPLIT_TOKENS tokens on the 64-row tiles under the fixed rules.
 constexpr int PB_SPLIT_MAX = 4;
 constexpr uint32_t PB_SPLIT_TOKENS = 512;
 constexpr int MAX_KSPLIT = 8;  // the norm kernel folds at most eight pending partials
@@ -842,8 +844,8 @@ nnc_status nnc_model_create(const nnc_config* cfg, const void* blob, size_t blob
     ALLOC(m->pb_fb, void*, frag_rows * std::max(Dq, F) * 2);
     ALLOC(m->pb_tok, int32_t*, (size_t)pb * 4);
     if (m->w8) ALLOC(m->pb_w, void*, std::max(std::max(Dq + 2 * Dkv, 2 * F) * H, H * std::max(Dq, F)) * 2);
-    // k-slice partials of the narrow projections of short blocks (up to PB_SPLIT_MAX - 1 buffers)
-    ALLOC(m->pb_part, float*, (size_t)(PB_SPLIT_MAX - 1) * std::min<size_t>(pb, PB_SPLIT_TOKENS) * H * 4);
+    // k-slice partials of the narrow projections (up to PB_SPLIT_MAX - 1 buffers of a whole block)
+    ALLOC(m->pb_part, float*, (size_t)(PB_SPLIT_MAX - 1) * pb * H * 4);
     // transposed V copy of one slot: [kv head][128][positions, padded to a multiple of 32];
     // zero-filled once so that positions never written read as finite values
     m->pb_vt_stride = (c.max_seq + 31) / 32 * 32;
@@ -981,6 +983,10 @@ nnc_status nnc_set_option(nnc_model* m, nnc_option opt, int32_t value) {
       if (value < -1 || value > 6) return fail(NNC_E_ARG, "prefill tile must be -1 (automatic) or 0 .. 6");
       m->opt_prefill_tile = value;
       return NNC_OK;
+    case NNC_OPT_PREFILL_KSLICES:
+      if (value < 0 || value > PB_SPLIT_MAX) return fail(NNC_E_ARG, "prefill k slices must be 0 (by rule) or 1 .. %d", PB_SPLIT_MAX);
+      m->opt_prefill_kslices = value;
+      return NNC_OK;
     case NNC_OPT_TAIL_OVERLAP: m->opt_tail_overlap = value != 0; return NNC_OK;
     case NNC_OPT_PLANNER:
       m->opt_planner = value != 0;
@@ -1062,7 +1068,7 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
   };
   // k slices of a residual projection: only with the 64-row tiles, when the launch would leave
   // most CUs without a workgroup, and with at least 8 k steps per slice
-  const long part_stride = (long)std::min<size_t>(m->pb_max, PB_SPLIT_TOKENS) * H;
+  const long part_stride = (long)m->pb_max * H;
   auto resid_split = [&](PrefillGemmArgs& a, int shape) {
     if ((shape != 0 && shape != 3) || n > PB_SPLIT_TOKENS) return 0;
     const long wgs = (long)((a.n_tiles + 3) / 4) * ((ct + (shape == 3 ? 3 : 7)) / (shape == 3 ? 4 : 8));
@@ -1081,10 +1087,21 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
     if (pend) *pend = 0;
     if (!m->opt_planner || m->opt_prefill_tile >= 0) {
       const int shape = tile_shape(a.n_tiles);
+      if (m->opt_prefill_kslices > 0 && m->opt_prefill_tile >= 0) {
+        // forced slice count of the residual projections (every tile's kernel takes one)
+        const int ks = std::min(m->opt_prefill_kslices, a.KT);
+        if (epi == EPI_RESID && ks > 1) {
+          a.kts_per_split = (a.KT + ks - 1) / ks;
+          a.part = m->pb_part;
+          a.part_stride = part_stride;
+          if (pend) *pend = (a.KT + a.kts_per_split - 1) / a.kts_per_split - 1;
+        }
+        return shape;
+      }
       if (pend) *pend = resid_split(a, shape);
       return shape;
     }
-    const int max_ks = (epi == EPI_RESID && n <= PB_SPLIT_TOKENS) ? PB_SPLIT_MAX : 1;
+    const int max_ks = epi == EPI_RESID ? PB_SPLIT_MAX : 1;
     const PrefillGemmPlan pl = plan_prefill_gemm(mc, a.n_tiles, a.KT, ct, (int)n, pieces, epi, max_ks);
     if (pl.k_slices > 1) {
       a.kts_per_split = pl.kts_per_split;

@@ -15,6 +15,11 @@ Machine machine_mi355x(int cus) {
   // once every CU has work
   m.hbm_bytes_per_us = 5.8e6;
   m.launch_us = 5.0;
+  // whole prompt passes with and without k slices on the large tiles (0.6B .. 8B layer shapes, 768 ..
+  // 4096 tokens): slices pay (4 - 9 %) while the partials are a few tens of MB and cost 2 - 3 % once
+  // they are not; the second rate is the one at which the model stops choosing the losing launches
+  m.fold_cached_bytes = 48e6;
+  m.fold_bytes_per_us = 2.0e6;
   // the weight-streaming GEMM alone, launches back to back, 200 (rows, k, batch, row tiles,
   // k slices) combinations of the five model shapes: least-squares / best-pick fit
   m.stream_bytes_per_us = 6.4e6;
@@ -44,7 +49,7 @@ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct PgTile {
   int code, nt, tt;
-  bool lds_direct;  // three LDS stages filled by direct copies, no k split; else register ring, two stages
+  bool lds_direct;  // three LDS stages filled by direct copies; else register ring, two stages
   int wgs_per_cu;   // resident workgroups per CU the kernel is built for
 };
 // every block tile the prompt GEMM kernels are instantiated for, plus one that is not (256 x 256
@@ -77,10 +82,13 @@ PrefillGemmPlan plan_prefill_gemm(const Machine& mc, int n_tiles, int KT, int co
       ++best.rejected_by_capacity;
       continue;
     }
-    const int ks_max = (t.lds_direct || epi != PLAN_EPI_RESID) ? 1 : std::max(1, max_k_slices);
+    const int ks_max = epi != PLAN_EPI_RESID ? 1 : std::max(1, max_k_slices);
+    // a slice shorter than the register ring (or, for the tiles with three LDS stages in flight,
+    // than a few times their pipeline) gains nothing
+    const int kts_min = !t.lds_direct ? 8 : wgs_per_cu == 1 ? 32 : 16;
     for (int ks = 1; ks <= ks_max; ++ks) {
       const int kts = ceil_div(KT, ks);
-      if (ks > 1 && kts < 8) break;          // a slice shorter than the register ring gains nothing
+      if (ks > 1 && kts < kts_min) break;
       const int slices = ceil_div(KT, kts);
       if (slices != ks) continue;            // same launch as a smaller ks
       const int wgs = ceil_div(n_tiles, t.nt) * ceil_div(col_tiles, t.tt) * slices;
@@ -94,7 +102,8 @@ PrefillGemmPlan plan_prefill_gemm(const Machine& mc, int n_tiles, int KT, int co
                                             : kts * (full * t2 + (rem == 0 ? 0.0 : rem <= mc.cus ? t1 : t2));
       const double fold = (slices - 1) * n_tokens * N * 4.0 * 2.0;  // partials written, then read by the norm kernel
       const double t_mem = (W + X) / mc.hbm_bytes_per_us;
-      const double total = std::max(t_comp, t_mem) + (out_bytes + fold) / mc.hbm_bytes_per_us + mc.launch_us;
+      const double t_fold = fold / (fold <= mc.fold_cached_bytes ? mc.hbm_bytes_per_us : mc.fold_bytes_per_us);
+      const double total = std::max(t_comp, t_mem) + out_bytes / mc.hbm_bytes_per_us + t_fold + mc.launch_us;
       if (total < best.t_us * 0.999) {
         best.tile = t.code; best.nt = t.nt; best.tt = t.tt;
         best.k_slices = slices; best.kts_per_split = slices > 1 ? kts : 0;

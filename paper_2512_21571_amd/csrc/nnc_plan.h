@@ -27,6 +27,9 @@ struct Machine {
   int vgprs_per_wave;     // with two waves per SIMD
   double hbm_bytes_per_us;       // streaming rate these kernels reach
   double launch_us;       // start-to-end time of a kernel with nothing to do
+  // k-slice partials of a prompt GEMM (written by its epilogue, read back by the next norm kernel):
+  // at the streaming rate while all of them stay in the caches, at fold_bytes_per_us beyond that
+  double fold_cached_bytes, fold_bytes_per_us;
   // the weight-streaming GEMM of decode passes: streaming rate of the whole chip, bytes a CU moves
   // through its vector memory path (weights + operand), launch-to-launch overhead, one round of
   // the cross-wave reduction in the epilogue

@@ -299,10 +299,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill_dl(PrefillGemmArgs a) {
   // instead of a vector op + lane read in front of every copy)
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int wn = wave >> 1, wt = wave & 1;
-  const int KT = a.KT;
+  // blockIdx.z = k slice (residual projections whose tiles alone would leave CUs idle)
+  const int kts = a.kts_per_split > 0 ? a.kts_per_split : a.KT;
+  const int kt_first = blockIdx.z * kts;
+  const int KT = min(a.KT, kt_first + kts) - kt_first;  // k steps of this slice
   const int nt0 = blockIdx.x * NT, tt0 = blockIdx.y * TT;
-  const char* __restrict__ W = static_cast<const char*>(a.Wp);
-  const char* __restrict__ X = static_cast<const char*>(a.Xf);
+  const char* __restrict__ W = static_cast<const char*>(a.Wp) + (size_t)kt_first * 1024;
+  const char* __restrict__ X = static_cast<const char*>(a.Xf) + (size_t)kt_first * 1024;
 
   f32x4 acc[WI][WJ];
 #pragma unroll
@@ -315,9 +318,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill_dl(PrefillGemmArgs a) {
   // that is never stored)
   uint32_t voa[AL], vob[BL];
 #pragma unroll
-  for (int j = 0; j < AL; ++j) voa[j] = ((uint32_t)min(nt0 + wave + 4 * j, a.n_tiles - 1) * (uint32_t)KT * 64u + lane) * 16u;
+  for (int j = 0; j < AL; ++j) voa[j] = ((uint32_t)min(nt0 + wave + 4 * j, a.n_tiles - 1) * (uint32_t)a.KT * 64u + lane) * 16u;
 #pragma unroll
-  for (int j = 0; j < BL; ++j) vob[j] = ((uint32_t)min(tt0 + wave + 4 * j, a.t_tiles - 1) * (uint32_t)KT * 64u + lane) * 16u;
+  for (int j = 0; j < BL; ++j) vob[j] = ((uint32_t)min(tt0 + wave + 4 * j, a.t_tiles - 1) * (uint32_t)a.KT * 64u + lane) * 16u;
   // The copy instruction is written as inline assembly: the compiler, when it sees one, makes
   // every later LDS read wait for all of them (it cannot tell which stage a read touches), which
   // would undo the look-ahead.  Hidden from it, the waits are the explicit ones below.
@@ -388,7 +391,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_prefill_dl(PrefillGemmArgs a) {
       st = st == 2 ? 0 : st + 1;
     }
   }
-  pg_epilogue<EPI, NT, TT, PIECES, HF>(a, acc, nt0, tt0, wn, wt, lane);
+  pg_epilogue<EPI, NT, TT, PIECES, HF>(a, acc, nt0, tt0, wn, wt, lane, (int)blockIdx.z);
 }
 
 // 256 x 256 block tile, one workgroup per CU, 128 x 128 per wave: per k step a wave reads 16
@@ -440,7 +443,10 @@ __global__ __launch_bounds__(256, 1) void k_gemm_prefill_big(PrefillGemmArgs a) 
   // instead of a vector op + lane read in front of every copy)
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int wn = wave >> 1, wt = wave & 1;
-  const int KT = a.KT;
+  // blockIdx.z = k slice (residual projections whose tiles alone would leave CUs idle)
+  const int kts = a.kts_per_split > 0 ? a.kts_per_split : a.KT;
+  const int kt_first = blockIdx.z * kts;
+  const int KT = min(a.KT, kt_first + kts) - kt_first;  // k steps of this slice
   // Block order.  The workgroups resident together (one per CU, 256 at a time in launch order)
   // should share operands: panels of 16 row blocks x all column blocks, and inside a panel groups of
   // 16 x 16 blocks.  The hardware deals consecutive workgroups to the 8 XCDs in turn, so within a
@@ -463,8 +469,8 @@ __global__ __launch_bounds__(256, 1) void k_gemm_prefill_big(PrefillGemmArgs a) 
     }
   }
   const int nt0 = bx * NT, tt0 = by * TT;
-  const char* __restrict__ W = static_cast<const char*>(a.Wp);
-  const char* __restrict__ X = static_cast<const char*>(a.Xf);
+  const char* __restrict__ W = static_cast<const char*>(a.Wp) + (size_t)kt_first * 1024;
+  const char* __restrict__ X = static_cast<const char*>(a.Xf) + (size_t)kt_first * 1024;
 
   // every accumulation register is this kernel's: naming the first and the last as clobbered makes
   // the compiler allocate all 256 to the wave.  It has no reason to touch them itself (the kernel
@@ -475,9 +481,9 @@ __global__ __launch_bounds__(256, 1) void k_gemm_prefill_big(PrefillGemmArgs a) 
 
   uint32_t voa[AL], vob[BL];
 #pragma unroll
-  for (int j = 0; j < AL; ++j) voa[j] = ((uint32_t)min(nt0 + wave + 4 * j, a.n_tiles - 1) * (uint32_t)KT * 64u + lane) * 16u;
+  for (int j = 0; j < AL; ++j) voa[j] = ((uint32_t)min(nt0 + wave + 4 * j, a.n_tiles - 1) * (uint32_t)a.KT * 64u + lane) * 16u;
 #pragma unroll
-  for (int j = 0; j < BL; ++j) vob[j] = ((uint32_t)min(tt0 + wave + 4 * j, a.t_tiles - 1) * (uint32_t)KT * 64u + lane) * 16u;
+  for (int j = 0; j < BL; ++j) vob[j] = ((uint32_t)min(tt0 + wave + 4 * j, a.t_tiles - 1) * (uint32_t)a.KT * 64u + lane) * 16u;
   typedef __attribute__((address_space(3))) void* lptr;
   auto copy1 = [&](const char* base, uint32_t voff, uint32_t lds_addr) __attribute__((always_inline)) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
@@ -586,7 +592,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_prefill_big(PrefillGemmArgs a) 
         for (int e = 0; e < 4; ++e) v[i][e] += w[e];
       }
     });
-    if (ct < a.t_tiles) pg_epilogue_col<EPI, WI, PIECES, HF>(a, v, nt0 + wn * WI, ct, lane, 0);
+    if (ct < a.t_tiles) pg_epilogue_col<EPI, WI, PIECES, HF>(a, v, nt0 + wn * WI, ct, lane, (int)blockIdx.z);
   });
 }
 
@@ -623,8 +629,8 @@ hipError_t launch_gemm_prefill(hipStream_t s, bool f16, int epi, const PrefillGe
   const int NT = (shape == 1 || shape == 5) ? 16 : (shape == 4 || shape == 6) ? 12 : shape == 2 ? 8 : 4,
             TT = shape == 3 ? 4 : shape >= 5 ? 16 : 8;
   int ksplit = 1;
-  if (a.kts_per_split > 0) {  // only the small tiles, only the residual epilogue, and a place for the partials
-    if ((shape != 0 && shape != 3) || epi != EPI_RESID || !a.part) return hipErrorInvalidValue;
+  if (a.kts_per_split > 0) {  // only the residual epilogue, and a place for the partials
+    if (epi != EPI_RESID || !a.part) return hipErrorInvalidValue;
     ksplit = (a.KT + a.kts_per_split - 1) / a.kts_per_split;
   }
   dim3 grid((a.n_tiles + NT - 1) / NT, (a.t_tiles + TT - 1) / TT, ksplit);

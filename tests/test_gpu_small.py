@@ -177,6 +177,41 @@ def test_large_block_prefill_every_block_tile(nnc, n, tile):
     assert int(na.item()) == no
 
 
+@pytest.mark.parametrize("ks", [2, 3, 4])
+@pytest.mark.parametrize("tile", [0, 2, 3, 4, 5, 6])
+def test_large_block_prefill_k_slices_on_every_block_tile(nnc, tile, ks):
+    """The k range of the output and down projections split over `ks` workgroups per output tile
+    (what the tile model picks for blocks whose tiles alone would leave most CUs idle): slice 0
+    adds the residual, the others store partial sums that the next norm kernel adds in slice order.
+    Every tile's kernel cuts the same k ranges and keeps the k order inside them, so for one slice
+    count all tiles give the bits of the 256 x 128 tile; against the unsliced launch only the
+    partial-sum order differs.  All match the oracle."""
+    print(f"case: large-block prefill, forced block tile {tile}, {ks} k slices", flush=True)
+    shape, n = SMALL_G4, 700
+    g, o = _pair(nnc, shape, 1, 800, exact_prefill=False)
+    toks = synth.tokens(n, shape.vocab, stream=1000 + n)
+    g.set_option(nnc.OPT_PREFILL_TILE, 1)
+    whole, _ = g.prefill(0, toks)
+    g.kv_reset(0)
+    g.set_option(nnc.OPT_PREFILL_KSLICES, ks)
+    ref, _ = g.prefill(0, toks)
+    g.kv_reset(0)
+    g.set_option(nnc.OPT_PREFILL_TILE, tile)
+    lg, ng = g.prefill(0, toks)
+    assert np.array_equal(lg.cpu().numpy(), ref.cpu().numpy())
+    # (a partial-sum order that differs in the last bit can round a cached bf16 K / V element the
+    # other way, which moves the logits by ~1e-4)
+    d = float(np.abs(lg.cpu().numpy() - whole.cpu().numpy()).max())
+    assert 0.0 < d <= 5e-4, d                       # the slices were really taken, and change nothing else
+    lo, no = oracle_prefill_like_library(o, 0, toks, shape)
+    _check_logits(shape, lg, lo, BF16_ABS_PROMPT)
+    assert int(ng.item()) == no
+    lg2, n2 = g.decode_step([0], [no])              # the cache the sliced block left behind
+    lo2, no2 = o.step_token(0, no, oracle_flags(shape))
+    _check_logits(shape, lg2[0], lo2, BF16_ABS_PROMPT)
+    assert int(n2.item()) == no2
+
+
 @pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6])
 def test_large_block_prefill_short_k_loops(nnc, tile):
     """A model so narrow that the GEMM k loops have 2 (QKV, gate|up) and 3 (down) steps:

@@ -45,7 +45,7 @@ def test_prompt_gemm_tiles_at_the_benchmark_shapes(name, tokens, want):
         p = nnc.plan_prefill_gemm(rows, k, tokens, 1, epi)
         got = (p.tile_rows, p.tile_cols)
         assert got == (want[g] if isinstance(want[g], tuple) else (want[g], 128)), (g, got)
-        assert p.k_slices == 1                                       # the LDS-direct kernels never split k
+        assert p.k_slices == 1                                       # (no slices allowed in this call)
         assert p.t_us >= max(p.t_comp_us, p.t_mem_us)                # objective: max(T_mem, T_comp) + epilogue + launch
 
 
@@ -62,6 +62,28 @@ def test_model_times_are_close_to_the_measured_ones():
                                  (2 * F, H, SWIGLU, 1, 36.4), (H, F, STORE, 8, 21.7), (V, H, STORE, 1, 226.6)):
         p = nnc.plan_skinny_gemm(rows, k, 16, 3, epi, ks)
         assert abs(p.t_us - us) / us < 0.20, (rows, p.t_us)
+
+
+def test_mid_size_blocks_split_k_of_the_residual_projections():
+    """Blocks of 768 .. 2048 tokens give the O / down projections fewer 256- or 128-row tiles than the
+    chip has CUs; the model then splits k on the direct-copy tiles too.  Measured per layer (O + down +
+    the two norm kernels that add the partials, HIP events): 8B shape, 1024 tokens: 224 us unsliced at
+    best, 192 at the pick below; 4B shape, 768 tokens: 181 -> 108; 4B, 2032: 212 -> 201; 8B, 2048:
+    316 -> 290.  From 3072 tokens on the partials no longer stay in the caches and slicing loses."""
+    H8, Dq8, _, F8 = SHAPES["8b"]
+    H4, Dq4, _, F4 = SHAPES["4b"]
+    RESID = 1
+    for rows, k, tokens, tile, ks in ((H8, F8, 1024, (128, 128), 2), (H8, Dq8, 1024, (128, 128), 2),
+                                      (H4, F4, 768, (128, 128), 4), (H4, F4, 2032, (192, 256), 2),
+                                      (H8, F8, 2048, (256, 256), 2)):
+        p = nnc.plan_prefill_gemm(rows, k, tokens, 1, RESID, 4)
+        assert ((p.tile_rows, p.tile_cols), p.k_slices) == (tile, ks), (rows, k, tokens, p.tile_rows, p.tile_cols, p.k_slices)
+        assert p.t_us < nnc.plan_prefill_gemm(rows, k, tokens, 1, RESID, 1).t_us
+        assert (k // 32) / p.k_slices >= 16            # a slice keeps the three LDS stages busy
+    for rows, k in ((H8, F8), (H8, Dq8), (H4, F4), (H4, Dq4)):
+        assert nnc.plan_prefill_gemm(rows, k, 4080, 1, RESID, 4).k_slices == 1
+    # only the residual projections have a consumer that adds partial sums
+    assert nnc.plan_prefill_gemm(2 * F8, H8, 1024, 1, SWIGLU, 4).k_slices == 1
 
 
 def test_short_prompts_are_memory_bound_and_may_split_k():
