@@ -103,6 +103,20 @@ def test_w8_long_prompts(nnc, n, mode):
         if tile in (1, 2, 4, 5, 6):                    # same k order per output element: same bits
             ref = lg if ref is None else ref
             assert np.array_equal(lg.cpu().numpy(), ref.cpu().numpy()), tile
+    # k slices of the residual projections (the row scales then multiply partial sums): the same
+    # bits from the register-ring and the direct-copy kernels, and the oracle's values
+    g.set_option(nnc.OPT_PREFILL_KSLICES, 3)
+    sliced = None
+    for tile in (0, 2, 5, 6):
+        g.kv_reset(0)
+        g.set_option(nnc.OPT_PREFILL_TILE, tile)
+        lg, ng = g.prefill(0, toks)
+        _check(lg, lo, 1e-2 if one_piece else W8_ABS_TIGHT)
+        assert int(ng.item()) == no
+        sliced = lg if sliced is None else sliced
+        assert np.array_equal(lg.cpu().numpy(), sliced.cpu().numpy()), tile
+    assert not np.array_equal(sliced.cpu().numpy(), ref.cpu().numpy())
+    g.set_option(nnc.OPT_PREFILL_KSLICES, 0)
     g.set_option(nnc.OPT_PREFILL_TILE, -1)
     lg, ng = g.decode_step([0], [no])
     lo, n2 = o.step_token(0, no, oracle_flags(shape))
