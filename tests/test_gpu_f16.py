@@ -112,6 +112,27 @@ def test_f16_block_tile_256x256_equals_256x128(nnc, tile):
     assert np.array_equal(lg.cpu().numpy(), ref.cpu().numpy())
 
 
+@pytest.mark.parametrize("tile", [0, 2, 5, 6])
+def test_f16_block_tiles_with_k_slices(nnc, tile):
+    """The residual projections of a block in three k slices: every tile's kernel gives the bits of
+    the 256 x 128 tile for the same slice count, close to the unsliced result."""
+    print(f"case: binary16 large-block prompt, forced block tile {tile}, 3 k slices", flush=True)
+    shape = SMALL_G4_F16
+    g, _ = _pair(nnc, shape, 1, 720, False)
+    toks = synth.tokens(700, shape.vocab, stream=78)
+    g.set_option(nnc.OPT_PREFILL_TILE, 1)
+    whole, _ = g.prefill(0, toks)
+    g.kv_reset(0)
+    g.set_option(nnc.OPT_PREFILL_KSLICES, 3)
+    ref, _ = g.prefill(0, toks)
+    g.kv_reset(0)
+    g.set_option(nnc.OPT_PREFILL_TILE, tile)
+    lg, _ = g.prefill(0, toks)
+    assert np.array_equal(lg.cpu().numpy(), ref.cpu().numpy())
+    d = float(np.abs(lg.cpu().numpy() - whole.cpu().numpy()).max())
+    assert 0.0 < d <= 5e-4, d
+
+
 @pytest.mark.parametrize("batch,fuse", [(5, 1), (16, 0)])
 def test_f16_batched_decode(nnc, batch, fuse):
     print(f"case: binary16 batched decode, {batch} sequences, fused QK-norm {fuse}", flush=True)
