@@ -1066,8 +1066,9 @@ static nnc_status prefill_block(nnc_model* m, uint32_t slot, const int32_t* toke
     if ((long)((n_tiles + 3) / 4) * cols >= (long)m->n_cus) return 0;
     return 3;
   };
-  // k slices of a residual projection: only with the 64-row tiles, when the launch would leave
-  // most CUs without a workgroup, and with at least 8 k steps per slice
+  // k slices of a residual projection under the fixed rules (planner off, or a forced tile without
+  // a forced slice count): only with the 64-row tiles, when the launch would leave most CUs without
+  // a workgroup, and with at least 8 k steps per slice
   const long part_stride = (long)m->pb_max * H;
   auto resid_split = [&](PrefillGemmArgs& a, int shape) {
     if ((shape != 0 && shape != 3) || n > PB_SPLIT_TOKENS) return 0;

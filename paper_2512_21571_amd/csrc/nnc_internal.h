@@ -171,7 +171,7 @@ struct PrefillGemmArgs {
   float* out;
   long ldo;
   void* packed_out;
-  // k split (64-row tiles with the residual epilogue only): k tiles per blockIdx.z slice, 0 =
+  // k split (residual epilogue only, any tile): k tiles per blockIdx.z slice, 0 =
   // one slice.  Slice 0 adds to `out`; slice s > 0 stores its partial sums at part + (s - 1) *
   // part_stride (same row stride as out).
   int kts_per_split = 0;
